@@ -1,0 +1,360 @@
+"""CPU oracle for the Parallel Loop Transformer (PLT) forward / decode path.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, float64 statement of what the
+HIP library must compute.  Only tests, the smoke check and the bench's cpu_baseline leg may
+import it; the product path never does.  It shares no code with the HIP path and imports
+nothing from it.
+
+Every function cites the passage of the paper (arxiv 2510.24824) it follows:
+
+  Eq. (1)   vanilla loop transformer            -> PLTOracle.vanilla_loop_forward
+  Alg. 1    PLT decoding (cross-loop parallel)  -> PLTOracle.clp_prefill / clp_decode_step
+  Alg. 2    PLT training-time forward           -> PLTOracle.seq_forward
+  Alg. 3    non-first-loop attention            -> gated_attention_row / decode_attention
+  Eq. (2)   sigmoid gate merge                  -> gate_merge
+  Sec. 2.2.2  first-loop KV sharing, window of the most recent w entries -> RingKV
+
+Where the paper is silent the following readings are taken (each also listed in the
+design notes of the repository):
+  * block f = pre-norm decoder layer: RMSNorm -> attention -> residual, RMSNorm -> SwiGLU -> residual
+  * rotary position embedding (rotate-half pairing, angle from the absolute position p)
+    on Q and on every cached K; softmax scale 1/sqrt(D) in both branches
+  * the state carried between loops is the residual stream after the last layer (before
+    the final norm); the final norm feeds only the classifier head
+  * the global branch of a non-first loop at position p sees shared keys 0..p inclusive
+  * the window holds positions max(0, p-w+1)..p (w entries including the current one)
+  * the gate logit of head h is <q_h, wg_h> + bg_h on q as produced by f_qkv (before RoPE),
+    one scalar per head; g multiplies the LOCAL branch (Eq. 2)
+  * one weight set serves every loop; query head h reads kv head h // (H_q / H_kv)
+  * argmax ties resolve to the lowest index
+
+Precision: float64 everywhere.  With kv_bf16=True the K and V entries are rounded to
+bfloat16 when they are stored (the device keeps its caches in bfloat16), nothing else is.
+Parity status: every function here is pinned by tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import math
+import numpy as np
+
+__all__ = ["OracleShape", "PLTOracle", "rmsnorm", "rope", "softmax_attend", "gate_merge",
+           "gated_attention_row", "decode_attention", "kv_cache_bytes", "bf16_round"]
+
+
+# ----------------------------------------------------------------------------- helpers
+
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding of float values to bfloat16 (8-bit exponent, 7-bit mantissa)."""
+    f = np.asarray(x, dtype=np.float32)
+    bits = f.view(np.uint32).astype(np.int64)
+    keep_odd = (bits >> 16) & 1
+    bits = ((bits + 0x7FFF + keep_odd) >> 16) << 16
+    return bits.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+class OracleShape:
+    def __init__(self, n_layers, d_model, n_heads, n_kv_heads, head_dim, ffn_hidden, vocab,
+                 n_loops, window, rope_theta=10000.0, norm_eps=1e-5, tie_embeddings=True):
+        self.n_layers, self.d_model = int(n_layers), int(d_model)
+        self.n_heads, self.n_kv_heads, self.head_dim = int(n_heads), int(n_kv_heads), int(head_dim)
+        self.ffn_hidden, self.vocab = int(ffn_hidden), int(vocab)
+        self.n_loops, self.window = int(n_loops), int(window)
+        self.rope_theta, self.norm_eps = float(rope_theta), float(norm_eps)
+        self.tie_embeddings = bool(tie_embeddings)
+        assert self.n_heads % self.n_kv_heads == 0 and self.head_dim % 2 == 0
+
+
+def rmsnorm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """x * gain / sqrt(mean(x^2) + eps) over the last axis (reading: pre-norm RMSNorm)."""
+    x = np.asarray(x, np.float64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(gain, np.float64)
+
+
+def rope(x: np.ndarray, p: int, theta: float) -> np.ndarray:
+    """Rotary embedding of x[..., D] at absolute position p; dim j pairs with j + D/2."""
+    x = np.asarray(x, np.float64)
+    D = x.shape[-1]
+    half = D // 2
+    j = np.arange(half, dtype=np.float64)
+    ang = p * theta ** (-2.0 * j / D)
+    c, s = np.cos(ang), np.sin(ang)
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def softmax_attend(q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
+    """sum_j softmax_j(<q, K[j]> / sqrt(D)) V[j] for one query q[D], K[n,D], V[n,D].
+
+    Alg. 3 lines 2 and 3 each are one call of this (global: all shared entries; local:
+    the window's entries).
+    """
+    q = np.asarray(q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    s = K @ q / math.sqrt(q.shape[-1])
+    s = s - np.max(s)
+    e = np.exp(s)
+    return (e / np.sum(e)) @ V
+
+
+def gate_merge(y_local: np.ndarray, y_global: np.ndarray, z: float) -> np.ndarray:
+    """Eq. (2): g = sigmoid(z);  y = g * y_local + (1 - g) * y_global."""
+    g = 1.0 / (1.0 + math.exp(-float(z)))
+    return g * np.asarray(y_local, np.float64) + (1.0 - g) * np.asarray(y_global, np.float64)
+
+
+def gated_attention_row(q, K_share, V_share, K_loc, V_loc, z) -> np.ndarray:
+    """Alg. 3 lines 2-5 for one query head of a non-first loop."""
+    y_glob = softmax_attend(q, K_share, V_share)
+    y_loc = softmax_attend(q, K_loc, V_loc)
+    return gate_merge(y_loc, y_glob, z)
+
+
+def decode_attention(q, k_share, v_share, k_ring, v_ring, z, n_ctx=None, n_ring=None):
+    """Fused decode attention of one CLP step, all sequences (kernel-only configuration).
+
+    q [B,L,Hq,D]; k_share, v_share [B,Hkv,N,D]; k_ring, v_ring [B,L-1,Hkv,w,D] in slot
+    order; z [B,L-1,Hq] gate logits.  n_ctx (<= N) shared entries and n_ring (<= w) ring
+    slots are valid (default: all).  Row l = 0 is the first loop: global attention only
+    (first loop == plain transformer).  Rows l >= 1: Alg. 3 lines 2-5.  Returns y [B,L,Hq,D].
+    """
+    q = np.asarray(q, np.float64)
+    B, L, Hq, D = q.shape
+    Hkv = k_share.shape[1]
+    G = Hq // Hkv
+    n_ctx = k_share.shape[2] if n_ctx is None else int(n_ctx)
+    y = np.zeros((B, L, Hq, D), np.float64)
+    for b in range(B):
+        for h in range(Hq):
+            kh = h // G
+            Ks = np.asarray(k_share[b, kh, :n_ctx], np.float64)
+            Vs = np.asarray(v_share[b, kh, :n_ctx], np.float64)
+            y[b, 0, h] = softmax_attend(q[b, 0, h], Ks, Vs)
+            for l in range(1, L):
+                nr = k_ring.shape[3] if n_ring is None else int(n_ring)
+                y[b, l, h] = gated_attention_row(q[b, l, h], Ks, Vs,
+                                                 k_ring[b, l - 1, kh, :nr], v_ring[b, l - 1, kh, :nr],
+                                                 z[b, l - 1, h])
+    return y
+
+
+def kv_cache_bytes(shape: OracleShape, n_ctx: int, elem_bytes: int, n_loops: int | None = None,
+                   shared: bool = True) -> int:
+    """Table 1, KV-cache column, as exact entry counts.
+
+    PLT (shared=True): one global cache of n_ctx entries plus (L-1) windows of w entries,
+    per layer, K and V.  Vanilla loop (shared=False): L full caches.
+    """
+    L = shape.n_loops if n_loops is None else n_loops
+    per_entry = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * elem_bytes
+    if shared:
+        return per_entry * (n_ctx + (L - 1) * shape.window)
+    return per_entry * L * n_ctx
+
+
+# ----------------------------------------------------------------------------- KV stores
+
+class FullHistoryKV:
+    """Keeps every K/V ever produced; the window is cut out by position.  Used by Alg. 2."""
+
+    def __init__(self, store):
+        self._store = store
+        self.glob = {}   # (cache_id, layer) -> ([k...], [v...])
+        self.loc = {}    # (loop, layer)     -> ([k...], [v...])
+
+    def put_global(self, cache_id, m, p, k, v):
+        ks, vs = self.glob.setdefault((cache_id, m), ([], []))
+        assert len(ks) == p
+        ks.append(self._store(k)); vs.append(self._store(v))
+
+    def get_global(self, cache_id, m, p):
+        ks, vs = self.glob[(cache_id, m)]
+        return np.stack(ks[:p + 1]), np.stack(vs[:p + 1])
+
+    def put_local(self, l, m, p, k, v, w):
+        ks, vs = self.loc.setdefault((l, m), ([], []))
+        assert len(ks) == p
+        ks.append(self._store(k)); vs.append(self._store(v))
+
+    def get_local(self, l, m, p, w):
+        ks, vs = self.loc[(l, m)]
+        lo = max(0, p - w + 1)
+        return np.stack(ks[lo:p + 1]), np.stack(vs[lo:p + 1])
+
+
+class RingKV:
+    """The decoding-time cache of Sec. 2.2.2: one shared cache plus, for every non-first
+    loop and layer, only the w most recent entries (slot = p mod w).  Used by Alg. 1."""
+
+    def __init__(self, store, shape: OracleShape, max_ctx: int):
+        self._store = store
+        s = shape
+        self.w = s.window
+        self.ks = np.zeros((s.n_layers, max_ctx, s.n_kv_heads, s.head_dim))
+        self.vs = np.zeros_like(self.ks)
+        nl = max(s.n_loops - 1, 0)
+        self.kr = np.zeros((nl, s.n_layers, s.window, s.n_kv_heads, s.head_dim))
+        self.vr = np.zeros_like(self.kr)
+
+    def put_global(self, cache_id, m, p, k, v):
+        assert cache_id == 1
+        self.ks[m, p] = self._store(k); self.vs[m, p] = self._store(v)
+
+    def get_global(self, cache_id, m, p):
+        return self.ks[m, :p + 1], self.vs[m, :p + 1]
+
+    def put_local(self, l, m, p, k, v, w):
+        self.kr[l - 2, m, p % w] = self._store(k); self.vr[l - 2, m, p % w] = self._store(v)
+
+    def get_local(self, l, m, p, w):
+        n = min(p + 1, w)          # slots 0..n-1 are the valid ones, in slot (not time) order
+        return self.kr[l - 2, m, :n], self.vr[l - 2, m, :n]
+
+    def n_bytes(self, n_ctx: int, elem_bytes: int) -> int:
+        per = self.ks.shape[2] * self.ks.shape[3] * elem_bytes
+        return 2 * per * (self.ks.shape[0] * n_ctx + self.kr.shape[0] * self.kr.shape[1] * self.kr.shape[2])
+
+
+# ----------------------------------------------------------------------------- the model
+
+class PLTOracle:
+    """One sequence at a time (sequences of a batch never interact)."""
+
+    def __init__(self, shape: OracleShape, weights: dict, kv_bf16: bool = False):
+        self.s = shape
+        self.w = weights
+        self.kv_bf16 = kv_bf16
+        self._store = bf16_round if kv_bf16 else (lambda a: np.asarray(a, np.float64))
+        self._head = weights["emb"] if shape.tie_embeddings else weights["head"]
+
+    # -- block f: one pass of the whole layer stack for one row at position p in loop l (1-based)
+    def f(self, x, p, l, kv, global_cache_id=1, plain=False):
+        """Transformer stack applied to one hidden row.
+
+        l == 1 (or plain=True): ordinary causal attention; its rotated K and its V are
+        appended to global cache `global_cache_id` (the first loop's cache is the shared one).
+        l >= 2: Alg. 3 -- global attention over the shared cache (0..p inclusive), sliding
+        window attention over this loop's own last w entries, Eq. (2) gate merge.
+        """
+        s = self.s
+        Hq, Hkv, D = s.n_heads, s.n_kv_heads, s.head_dim
+        G = Hq // Hkv
+        x = np.asarray(x, np.float64).copy()
+        first = plain or l == 1
+        for m in range(s.n_layers):
+            W = self.w["layers"][m]
+            a = rmsnorm(x, W["norm1"], s.norm_eps)
+            q = (np.asarray(W["wq"], np.float64) @ a).reshape(Hq, D)          # Alg. 3 l.1
+            k = (np.asarray(W["wk"], np.float64) @ a).reshape(Hkv, D)
+            v = (np.asarray(W["wv"], np.float64) @ a).reshape(Hkv, D)
+            if not first:                                                        # Alg. 3 l.4
+                z = np.sum(q * np.asarray(W["gate_w"], np.float64), axis=-1) + np.asarray(W["gate_b"], np.float64)
+            qr = rope(q, p, s.rope_theta)
+            kr = rope(k, p, s.rope_theta)
+            if first:
+                kv.put_global(global_cache_id, m, p, kr, v)
+            else:
+                kv.put_local(l, m, p, kr, v, s.window)
+            Kg, Vg = kv.get_global(global_cache_id, m, p)                        # [p+1, Hkv, D]
+            y = np.zeros((Hq, D))
+            if first:
+                for h in range(Hq):
+                    y[h] = softmax_attend(qr[h], Kg[:, h // G], Vg[:, h // G])
+            else:
+                Kl, Vl = kv.get_local(l, m, p, s.window)
+                for h in range(Hq):
+                    y[h] = gated_attention_row(qr[h], Kg[:, h // G], Vg[:, h // G],
+                                               Kl[:, h // G], Vl[:, h // G], z[h])  # Alg. 3 l.2-5
+            x = x + np.asarray(W["wo"], np.float64) @ y.reshape(Hq * D)         # Alg. 3 l.6
+            b = rmsnorm(x, W["norm2"], s.norm_eps)
+            gte = np.asarray(W["w_gate"], np.float64) @ b
+            up = np.asarray(W["w_up"], np.float64) @ b
+            x = x + np.asarray(W["w_down"], np.float64) @ (gte / (1.0 + np.exp(-gte)) * up)
+        return x
+
+    def embed(self, t):
+        return np.asarray(self.w["emb"][int(t)], np.float64)
+
+    def logits(self, h):
+        return np.asarray(self._head, np.float64) @ rmsnorm(h, self.w["norm_f"], self.s.norm_eps)
+
+    # -- Alg. 2: loop-serial over the whole sequence
+    def seq_forward(self, tokens):
+        """Returns H [L, n, d] (H[l-1, p] = loop-l state at position p) and logits [n, V]."""
+        s = self.s
+        n = len(tokens)
+        kv = FullHistoryKV(self._store)
+        E = np.stack([self.embed(t) for t in tokens])
+        H = np.zeros((s.n_loops, n, s.d_model))
+        for p in range(n):                                   # Alg. 2 l.2
+            H[0, p] = self.f(E[p], p, 1, kv)
+        for l in range(2, s.n_loops + 1):                    # Alg. 2 l.3-7
+            shifted = np.concatenate([np.zeros((1, s.d_model)), H[l - 2, :-1]], axis=0)
+            Bm = E + shifted
+            for p in range(n):
+                H[l - 1, p] = self.f(Bm[p], p, l, kv)
+        lg = np.stack([self.logits(H[s.n_loops - 1, p]) for p in range(n)])   # Alg. 2 l.8
+        return H, lg
+
+    # -- Alg. 1: prefill, then one displaced micro-batch per new token
+    def clp_prefill(self, tokens, max_ctx):
+        """Alg. 1 l.1-3.  Consumes the prompt position by position with the same micro-batch
+        rule as decoding (which equals Alg. 2 on the prompt); returns (next token id, logits)."""
+        s = self.s
+        self.kv = RingKV(self._store, s, max_ctx)
+        self.carry = np.zeros((max(s.n_loops - 1, 0), s.d_model))   # carry[l-1] = H^l[p-1]
+        self.pos = 0
+        self.trace = []        # per position: H rows [L, d] (for tests)
+        nxt, lg = None, None
+        for t in tokens:
+            nxt, lg = self.clp_decode_step(t)
+        return nxt, lg
+
+    def clp_decode_step(self, t):
+        """Alg. 1 l.5-9 at position p = self.pos: rows B_0 = e, B_l = e + H^l[p-1]; one pass of f
+        per row (rows are independent); carry update; head on the last loop's row."""
+        s = self.s
+        p = self.pos
+        e = self.embed(t)
+        rows = [e] + [e + self.carry[l - 1] for l in range(1, s.n_loops)]   # Alg. 1 l.6
+        out = np.zeros((s.n_loops, s.d_model))
+        # the first-loop row writes K_share/V_share[p] before the other rows read them:
+        for l in range(1, s.n_loops + 1):
+            out[l - 1] = self.f(rows[l - 1], p, l, self.kv)
+        if s.n_loops > 1:
+            self.carry = out[:-1].copy()
+        lg = self.logits(out[-1])
+        self.trace.append(out)
+        self.pos = p + 1
+        return int(np.argmax(lg)), lg
+
+    # -- Eq. (1): vanilla loop transformer, every loop with its own full cache
+    def vanilla_loop_forward(self, tokens):
+        s = self.s
+        n = len(tokens)
+        kv = FullHistoryKV(self._store)
+        H = np.zeros((s.n_loops, n, s.d_model))
+        for p in range(n):
+            h = self.embed(tokens[p])
+            for l in range(1, s.n_loops + 1):
+                h = self.f(h, p, l, kv, global_cache_id=l, plain=True)
+                H[l - 1, p] = h
+        lg = np.stack([self.logits(H[-1, p]) for p in range(n)])
+        return H, lg
+
+    def greedy_generate(self, prompt, n_new, max_ctx=None):
+        """Alg. 1 end to end: returns n_new + 1 ids (the prefill's prediction and one per step),
+        the top-2 logit margin of every prediction, and the logits of every prediction."""
+        max_ctx = max_ctx or (len(prompt) + n_new + 1)
+        nxt, lg = self.clp_prefill(prompt, max_ctx)
+        ids, margins, all_lg = [nxt], [_margin(lg)], [lg]
+        for _ in range(n_new):
+            nxt, lg = self.clp_decode_step(nxt)
+            ids.append(nxt); margins.append(_margin(lg)); all_lg.append(lg)
+        return ids, margins, np.stack(all_lg)
+
+
+def _margin(lg):
+    top = np.sort(lg)[-2:]
+    return float(top[1] - top[0])

