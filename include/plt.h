@@ -1,0 +1,189 @@
+/*
+ * plt.h -- C ABI of the MI355X (gfx950) implementation of the Parallel Loop Transformer's
+ * cross-loop-parallel (CLP) decode path (arxiv 2510.24824).
+ *
+ * Conventions
+ *   - Every function returns 0 (PLT_OK) or a negative plt_status; plt_last_error() gives a
+ *     thread-local message for the last failure.  No C++ exception crosses this boundary.
+ *   - "dev" pointers are HIP device pointers owned by the caller (the library never frees
+ *     them); "host" pointers are ordinary host memory.  The stream handed to plt_init is the
+ *     caller's hipStream_t (NULL = default stream); all work is asynchronous on it except the
+ *     export / import / debug hooks, which synchronise the stream.
+ *   - Matrices are row-major [out_features, in_features] (y = W x).  dtype PLT_F32 keeps
+ *     weights, caches and GEMM inputs in float; PLT_BF16 keeps them in bfloat16 with float
+ *     accumulation, a float residual stream and float softmax statistics.
+ *   - Requirements: head_dim in {64, 128}; n_heads % n_kv_heads == 0; for PLT_BF16 also
+ *     d_model % 64 == 0 and ffn_hidden % 64 == 0.  Anything else -> PLT_EINVAL.
+ *   - One model may serve several plt_kv objects, but calls that share a model or a kv
+ *     object must not overlap in time (they share scratch memory).
+ *
+ * Model statement (sections of the paper in brackets).  Block f is a pre-norm decoder
+ * stack (RMSNorm, attention, residual, RMSNorm, SwiGLU, residual) whose weights are reused
+ * by every loop.  Loop 1 is an ordinary causal transformer pass whose rotated keys and
+ * values form the single shared cache K_share, V_share [Sec. 2.2.2].  Loop l >= 2 at
+ * position p takes e_p + H^(l-1)[p-1] as input [Alg. 2; Sec. 2.2.1] and its attention is
+ * global attention over K_share, V_share[0..p] plus sliding-window attention over its own
+ * last w keys/values, merged per head by g = sigmoid(<q_h, wg_h> + bg_h):
+ * y = g * y_local + (1 - g) * y_global [Alg. 3; Eq. 2].  While decoding, the L loop stages
+ * of one position form one micro-batch of L rows and run as a single pass [Alg. 1].
+ */
+#ifndef PLT_H_
+#define PLT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PLT_OK = 0,
+  PLT_EINVAL = -1,   /* bad argument or unsupported configuration           */
+  PLT_ENOMEM = -2,   /* a caller buffer is too small, or hipMalloc failed    */
+  PLT_ECTXFULL = -3, /* the next position would exceed max_ctx (no state change) */
+  PLT_EHIP = -4,     /* a HIP runtime call failed                            */
+  PLT_ESTATE = -5    /* call order violated (e.g. decode before prefill)     */
+} plt_status;
+
+enum { PLT_F32 = 0, PLT_BF16 = 1 };
+
+/* mode: which schedule / cache organisation the model object runs.                        */
+enum {
+  PLT_MODE_CLP = 0,          /* PLT: Alg. 1 decoding, shared first-loop KV, gated window    */
+  PLT_MODE_VANILLA_LOOP = 2  /* Eq. (1): L serial passes per token, one full cache per loop,
+                                no shift, no gate, no window (the paper's baseline row 2)   */
+};
+
+typedef struct plt_config {
+  int32_t n_layers, d_model, n_heads, n_kv_heads, head_dim, ffn_hidden, vocab;
+  int32_t n_loops;        /* L >= 1; L == 1 is the non-looped transformer                   */
+  int32_t window;         /* w >= 1 (ignored when L == 1 or in vanilla-loop mode)           */
+  int32_t dtype;          /* PLT_F32 or PLT_BF16                                            */
+  int32_t mode;           /* PLT_MODE_*                                                     */
+  int32_t tie_embeddings; /* 1: classifier head = embedding matrix                          */
+  float rope_theta;       /* rotary base (10000)                                            */
+  float norm_eps;         /* RMSNorm epsilon                                                */
+} plt_config;
+
+typedef struct plt_model plt_model; /* opaque */
+typedef struct plt_kv plt_kv;       /* opaque */
+
+/* Tensors of the weight blob, in blob order:
+ *   EMB [vocab, d]; per layer: NORM1 [d], WQKV [(Hq+2Hkv)*D, d] (rows: all Q heads, then all
+ *   K heads, then all V heads), GATE_W [Hq, D], GATE_B [Hq], WO [d, Hq*D], NORM2 [d],
+ *   WGU [2F, d] (rows: W_gate then W_up), WDOWN [d, F]; then NORM_F [d]; then HEAD [vocab, d]
+ *   (absent when tie_embeddings).  Norm gains, gate weight and gate bias are always float;
+ *   the other tensors have the model dtype.  Every tensor starts at a multiple of 256 bytes. */
+enum { PLT_W_EMB = 0, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO,
+       PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD };
+
+/* Total size of the weight blob in bytes (0 if the configuration is invalid). */
+size_t plt_weights_bytes(const plt_config* cfg);
+
+/* Byte offset and element count of one tensor inside the blob.  `layer` is ignored for EMB,
+ * NORM_F and HEAD.  PLT_EINVAL for an invalid configuration / tensor id / layer. */
+int plt_weights_offset(const plt_config* cfg, int32_t layer, int32_t which,
+                       size_t* host_off_out, size_t* host_nelem_out);
+
+/* Creates a model over a weight blob that already lies in device memory (layout above; the
+ * blob must stay alive and unchanged while the model exists).  [Alg. 1 "Require"] */
+int plt_init(const plt_config* cfg, const void* dev_weights, size_t nbytes, void* hip_stream,
+             plt_model** out);
+void plt_free(plt_model* m);
+
+/* Bytes of device memory a KV object for `batch` sequences of up to max_ctx positions needs
+ * (physical: positions are padded to multiples of 32), and the logical size
+ * 2 * layers * Hkv * D * (n_ctx + (L-1) * w) * sizeof(elem) * batch of Table 1 (row 5; row 2
+ * in vanilla-loop mode: 2 * layers * Hkv * D * L * n_ctx). */
+size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx);
+size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_t n_ctx);
+
+/* Binds the cache layout to the caller's device buffer (>= plt_kv_bytes, 256-byte aligned),
+ * clears it, and allocates the per-step activation scratch (the only hipMalloc besides
+ * plt_prefill's temporary workspace).  [Sec. 2.2.2: one shared cache + (L-1) windows] */
+int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* dev_buf, size_t nbytes,
+                 plt_kv** out);
+void plt_kv_free(plt_kv* kv);
+
+/* Prefill [Alg. 1 l.1-3 = Alg. 2 forward]: consumes dev_tokens [batch, n] (int32, row-major),
+ * fills the shared cache for positions 0..n-1, the windows and the carried states, and
+ * writes the greedy next token of every sequence to dev_next [batch] and, if not NULL, the
+ * last position's logits to dev_logits [batch, vocab] (float).  Restarts the kv object. */
+int plt_prefill(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t n,
+                int32_t* dev_next, float* dev_logits);
+
+/* One decode step [Alg. 1 l.5-9]: consumes the newest token of every sequence
+ * (dev_tokens [batch]), runs the L loop stages of this position as one pass, appends to the
+ * caches, updates the carried states and writes the next greedy token (and logits). */
+int plt_decode_step(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t* dev_next,
+                    float* dev_logits);
+
+/* Number of positions consumed so far (prompt + decode steps), or a negative status. */
+int32_t plt_kv_position(const plt_kv* kv);
+
+const char* plt_last_error(void);
+
+/* ---------------------------------------------------------------- test and bench hooks */
+
+/* Sets the position counter without touching cache contents (bench: time steps at a fixed
+ * context; tests: continue after plt_kv_import).  0 <= pos <= max_ctx. */
+int plt_kv_set_position(plt_kv* kv, int32_t pos);
+
+/* Copies one sequence's cache of one layer to / from host memory in a plain layout,
+ * element type = model dtype:
+ *   shared K [Hkv, n, D], shared V [Hkv, n, D], then (CLP mode, L > 1) ring K
+ *   [L-1, Hkv, w, D] and ring V [L-1, Hkv, w, D] in slot order (slot = position mod w).
+ * `cache` selects the loop's cache in vanilla-loop mode (0-based), must be 0 otherwise.
+ * host_nbytes must equal plt_kv_export_bytes(kv, n). */
+size_t plt_kv_export_bytes(const plt_kv* kv, int32_t n);
+int plt_kv_export(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n,
+                  void* host_dst, size_t host_nbytes);
+int plt_kv_import(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n,
+                  const void* host_src, size_t host_nbytes);
+
+/* Carried states H^l[p-1], l = 1..L-1, of every sequence: float [batch, L-1, d]. */
+int plt_get_carry(plt_kv* kv, float* host_dst, size_t host_nbytes);
+int plt_set_carry(plt_kv* kv, const float* host_src, size_t host_nbytes);
+/* Residual-stream rows after the last layer of the most recent decode step: float
+ * [batch, L, d] (row l = loop l+1's output H^(l+1)[p]). */
+int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes);
+
+/* Kernel-only fused decode attention [Alg. 3 l.2-5, Eq. 2; first-loop row: global only].
+ * All pointers are device pointers, element type `dtype`, in the cache's native layout:
+ *   q        [B, L, Hq, D]                       (already rotated)
+ *   k_share  [B, Hkv, n_pad, D]                  n_pad = plt_attn_pad32(n_alloc)
+ *   v_share  [B, Hkv, n_pad/32, D, 32]           blocks of 32 positions, position fastest
+ *   k_ring   [B, L-1, Hkv, w_pad, D]             w_pad = plt_attn_pad32(w)
+ *   v_ring   [B, L-1, Hkv, w_pad/32, D, 32]
+ *   z        [B, L-1, Hq] float gate logits;  y [B, L, Hq, D] output
+ * n_ctx shared entries and n_ring (<= w) ring slots are valid for every sequence.
+ * scratch: device buffer of plt_attn_scratch_bytes(...) bytes (split partials).
+ * n_splits <= 0 lets the library choose.  Rows of loop 0 get the global branch only. */
+int32_t plt_attn_pad32(int32_t n);
+size_t plt_attn_scratch_bytes(int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D);
+int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
+                    int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring,
+                    const void* dev_q, const void* dev_k_share, const void* dev_v_share,
+                    const void* dev_k_ring, const void* dev_v_ring, const float* dev_z,
+                    void* dev_y, void* dev_scratch, size_t scratch_bytes, int32_t n_splits,
+                    void* hip_stream);
+
+/* Device-side layout conversion for the hook above: plain [S, n, D] (S independent streams,
+ * e.g. B*Hkv) -> K layout [S, n_pad, D] (pad rows zeroed) and V layout [S, n_pad/32, D, 32]. */
+int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,
+                    void* dev_dst, void* hip_stream);
+int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,
+                    void* dev_dst, void* hip_stream);
+
+/* Kernel-only dense contraction used by every projection [Alg. 3 l.1 and l.6; FFN; head]:
+ * c [M, N] (float) = a [M, K] * w [N, K]^T with a and w of type `dtype`, float accumulation. */
+int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* dev_a,
+             const void* dev_w, float* dev_c, void* dev_scratch, size_t scratch_bytes,
+             void* hip_stream);
+size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLT_H_ */

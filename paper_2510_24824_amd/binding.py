@@ -1,0 +1,326 @@
+"""Thin ctypes binding of libplt.so: same names as include/plt.h, argument marshalling only.
+
+torch is used for device memory and the current stream; every step of the path runs in the
+library's HIP kernels.  There is no CPU fallback: a missing library raises at load time.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libplt.so")
+
+PLT_F32, PLT_BF16 = 0, 1
+PLT_MODE_CLP, PLT_MODE_VANILLA_LOOP = 0, 2
+(PLT_W_EMB, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO, PLT_W_NORM2, PLT_W_WGU,
+ PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD) = range(11)
+STATUS = {0: "PLT_OK", -1: "PLT_EINVAL", -2: "PLT_ENOMEM", -3: "PLT_ECTXFULL", -4: "PLT_EHIP", -5: "PLT_ESTATE"}
+
+
+class PltError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"{STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+class plt_config(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim",
+                                         "ffn_hidden", "vocab", "n_loops", "window", "dtype", "mode",
+                                         "tie_embeddings")] + [("rope_theta", C.c_float), ("norm_eps", C.c_float)]
+
+
+_P, _I, _Z = C.c_void_p, C.c_int32, C.c_size_t
+_SIGS = {
+    "plt_weights_bytes": (_Z, [C.POINTER(plt_config)]),
+    "plt_weights_offset": (C.c_int, [C.POINTER(plt_config), _I, _I, C.POINTER(_Z), C.POINTER(_Z)]),
+    "plt_init": (C.c_int, [C.POINTER(plt_config), _P, _Z, _P, C.POINTER(_P)]),
+    "plt_free": (None, [_P]),
+    "plt_kv_bytes": (_Z, [_P, _I, _I]),
+    "plt_kv_logical_bytes": (_Z, [_P, _I, _I]),
+    "plt_kv_alloc": (C.c_int, [_P, _I, _I, _P, _Z, C.POINTER(_P)]),
+    "plt_kv_free": (None, [_P]),
+    "plt_prefill": (C.c_int, [_P, _P, _P, _I, _P, _P]),
+    "plt_decode_step": (C.c_int, [_P, _P, _P, _P, _P]),
+    "plt_kv_position": (_I, [_P]),
+    "plt_last_error": (C.c_char_p, []),
+    "plt_kv_set_position": (C.c_int, [_P, _I]),
+    "plt_kv_export_bytes": (_Z, [_P, _I]),
+    "plt_kv_export": (C.c_int, [_P, _I, _I, _I, _I, _P, _Z]),
+    "plt_kv_import": (C.c_int, [_P, _I, _I, _I, _I, _P, _Z]),
+    "plt_get_carry": (C.c_int, [_P, _P, _Z]),
+    "plt_set_carry": (C.c_int, [_P, _P, _Z]),
+    "plt_get_hidden": (C.c_int, [_P, _P, _Z]),
+    "plt_attn_pad32": (_I, [_I]),
+    "plt_attn_scratch_bytes": (_Z, [_I, _I, _I, _I, _I]),
+    "plt_attn_decode": (C.c_int, [_I] * 10 + [_P] * 8 + [_Z, _I, _P]),
+    "plt_attn_pack_k": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
+    "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
+    "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
+    "plt_gemm_scratch_bytes": (_Z, [_I, _I, _I]),
+}
+EXPORTS = tuple(_SIGS)
+
+_lib = None
+
+
+def lib():
+    """Loads libplt.so (built by paper_2510_24824_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not found: build it with __graft_entry__.build() "
+                                    "(python -m paper_2510_24824_amd.build); there is no fallback path")
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(l, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = l
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise PltError(rc, lib().plt_last_error().decode())
+
+
+def make_config(shape, dtype=PLT_BF16, mode=PLT_MODE_CLP, n_loops=None, window=None) -> plt_config:
+    return plt_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
+                      shape.ffn_hidden, shape.vocab, shape.n_loops if n_loops is None else n_loops,
+                      shape.window if window is None else window, dtype, mode,
+                      1 if shape.tie_embeddings else 0, shape.rope_theta, shape.norm_eps)
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def weights_offset(cfg, layer, which):
+    off, n = _Z(), _Z()
+    _check(lib().plt_weights_offset(C.byref(cfg), layer, which, C.byref(off), C.byref(n)))
+    return off.value, n.value
+
+
+def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
+    """Copies a weight dict (float32 arrays, [out, in]) into a device blob in the library's layout."""
+    import torch
+    from . import synth
+    nbytes = lib().plt_weights_bytes(C.byref(cfg))
+    if nbytes == 0:
+        raise PltError(-1, lib().plt_last_error().decode())
+    host = np.zeros(nbytes, np.uint8)
+
+    def put(layer, which, arr, model_dtype):
+        off, n = weights_offset(cfg, layer, which)
+        arr = np.ascontiguousarray(arr, np.float32).reshape(-1)
+        assert arr.size == n, (which, arr.size, n)
+        if model_dtype and cfg.dtype == PLT_BF16:
+            host[off:off + 2 * n] = synth.bf16_bits(arr).view(np.uint8)
+        else:
+            host[off:off + 4 * n] = arr.view(np.uint8)
+
+    put(0, PLT_W_EMB, weights["emb"], True)
+    for m, lw in enumerate(weights["layers"]):
+        put(m, PLT_W_NORM1, lw["norm1"], False)
+        put(m, PLT_W_WQKV, np.concatenate([lw["wq"], lw["wk"], lw["wv"]], axis=0), True)
+        put(m, PLT_W_GATE_W, lw["gate_w"], False)
+        put(m, PLT_W_GATE_B, lw["gate_b"], False)
+        put(m, PLT_W_WO, lw["wo"], True)
+        put(m, PLT_W_NORM2, lw["norm2"], False)
+        put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=0), True)
+        put(m, PLT_W_WDOWN, lw["w_down"], True)
+    put(0, PLT_W_NORM_F, weights["norm_f"], False)
+    if not cfg.tie_embeddings:
+        put(0, PLT_W_HEAD, weights["head"], True)
+    return torch.from_numpy(host).to(device)
+
+
+class Model:
+    """plt_model + its weight blob (kept alive here)."""
+
+    def __init__(self, cfg: plt_config, blob):
+        self.cfg, self.blob = cfg, blob
+        h = _P()
+        _check(lib().plt_init(C.byref(cfg), _ptr(blob), blob.numel(), _stream(), C.byref(h)))
+        self.h = h
+
+    def kv_bytes(self, batch, max_ctx):
+        return lib().plt_kv_bytes(self.h, batch, max_ctx)
+
+    def kv_logical_bytes(self, batch, n_ctx):
+        return lib().plt_kv_logical_bytes(self.h, batch, n_ctx)
+
+    def close(self):
+        if self.h:
+            lib().plt_free(self.h)
+            self.h = None
+
+
+class KV:
+    """plt_kv bound to a torch-owned device buffer."""
+
+    def __init__(self, model: Model, batch: int, max_ctx: int):
+        import torch
+        self.model, self.batch, self.max_ctx = model, batch, max_ctx
+        nbytes = model.kv_bytes(batch, max_ctx)
+        if nbytes == 0:
+            raise PltError(-1, lib().plt_last_error().decode())
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        h = _P()
+        _check(lib().plt_kv_alloc(model.h, batch, max_ctx, _ptr(self.buf), nbytes, C.byref(h)))
+        self.h = h
+        self.next = torch.empty(batch, dtype=torch.int32, device="cuda")
+        self.logits = torch.empty(batch, model.cfg.vocab, dtype=torch.float32, device="cuda")
+
+    def prefill(self, tokens, want_logits=True):
+        """tokens: int32 device tensor [batch, n]; returns (next ids, logits) device tensors."""
+        assert tokens.dtype.is_floating_point is False and tokens.is_cuda and tokens.dim() == 2
+        assert tokens.shape[0] == self.batch
+        tokens = tokens.contiguous()
+        _check(lib().plt_prefill(self.model.h, self.h, _ptr(tokens), tokens.shape[1], _ptr(self.next),
+                                 _ptr(self.logits) if want_logits else None))
+        return self.next, (self.logits if want_logits else None)
+
+    def decode_step(self, tokens, want_logits=True):
+        tokens = tokens.contiguous()
+        assert tokens.numel() == self.batch and tokens.is_cuda
+        _check(lib().plt_decode_step(self.model.h, self.h, _ptr(tokens), _ptr(self.next),
+                                     _ptr(self.logits) if want_logits else None))
+        return self.next, (self.logits if want_logits else None)
+
+    @property
+    def position(self):
+        return lib().plt_kv_position(self.h)
+
+    def set_position(self, pos):
+        _check(lib().plt_kv_set_position(self.h, pos))
+
+    def _np_dtype(self):
+        return np.uint16 if self.model.cfg.dtype == PLT_BF16 else np.float32
+
+    def export(self, seq, layer, n, cache=0):
+        """Returns dict of float32 arrays: k_share, v_share [Hkv,n,D], k_ring, v_ring [L-1,Hkv,w,D]."""
+        from . import synth
+        c = self.model.cfg
+        nbytes = lib().plt_kv_export_bytes(self.h, n)
+        host = np.zeros(nbytes // np.dtype(self._np_dtype()).itemsize, self._np_dtype())
+        _check(lib().plt_kv_export(self.h, seq, layer, cache, n, host.ctypes.data_as(_P), nbytes))
+        vals = synth.bf16_from_bits(host) if c.dtype == PLT_BF16 else host
+        Hkv, D, w = c.n_kv_heads, c.head_dim, max(c.window, 1)
+        nr = c.n_loops - 1 if c.mode == PLT_MODE_CLP else 0
+        a = Hkv * n * D
+        out = {"k_share": vals[:a].reshape(Hkv, n, D), "v_share": vals[a:2 * a].reshape(Hkv, n, D)}
+        r = nr * Hkv * w * D
+        out["k_ring"] = vals[2 * a:2 * a + r].reshape(nr, Hkv, w, D)
+        out["v_ring"] = vals[2 * a + r:2 * a + 2 * r].reshape(nr, Hkv, w, D)
+        return out
+
+    def import_(self, seq, layer, n, k_share, v_share, k_ring=None, v_ring=None, cache=0):
+        from . import synth
+        c = self.model.cfg
+        parts = [k_share, v_share] + ([k_ring, v_ring] if k_ring is not None else [])
+        flat = np.concatenate([np.ascontiguousarray(p, np.float32).reshape(-1) for p in parts])
+        host = synth.bf16_bits(flat) if c.dtype == PLT_BF16 else flat
+        _check(lib().plt_kv_import(self.h, seq, layer, cache, n, host.ctypes.data_as(_P), host.nbytes))
+
+    def get_carry(self):
+        c = self.model.cfg
+        out = np.zeros((self.batch, c.n_loops - 1, c.d_model), np.float32)
+        _check(lib().plt_get_carry(self.h, out.ctypes.data_as(_P), out.nbytes))
+        return out
+
+    def set_carry(self, carry):
+        carry = np.ascontiguousarray(carry, np.float32)
+        _check(lib().plt_set_carry(self.h, carry.ctypes.data_as(_P), carry.nbytes))
+
+    def get_hidden(self):
+        c = self.model.cfg
+        rows = c.n_loops if c.mode == PLT_MODE_CLP else 1
+        out = np.zeros((self.batch, rows, c.d_model), np.float32)
+        _check(lib().plt_get_hidden(self.h, out.ctypes.data_as(_P), out.nbytes))
+        return out
+
+    def close(self):
+        if self.h:
+            lib().plt_kv_free(self.h)
+            self.h = None
+
+
+# ---- kernel-only hooks -------------------------------------------------------------------
+
+def _to_dev(arr, dtype):
+    """float32 numpy (bf16-representable when dtype is bf16) -> device tensor of the storage type."""
+    import torch
+    t = torch.from_numpy(np.ascontiguousarray(arr, np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype == PLT_BF16 else t
+
+
+def attn_pack_k(dtype, src, n):
+    """src: device tensor [S, n, D] -> K layout [S, pad32(n), D]."""
+    import torch
+    S, _, D = src.shape
+    dst = torch.empty(S, lib().plt_attn_pad32(n), D, dtype=src.dtype, device="cuda")
+    _check(lib().plt_attn_pack_k(dtype, S, n, D, _ptr(src.contiguous()), _ptr(dst), _stream()))
+    return dst
+
+
+def attn_pack_v(dtype, src, n):
+    """src: device tensor [S, n, D] -> V layout [S, pad32(n)/32, D, 32]."""
+    import torch
+    S, _, D = src.shape
+    npad = lib().plt_attn_pad32(n)
+    dst = torch.empty(S, npad // 32, D, 32, dtype=src.dtype, device="cuda")
+    _check(lib().plt_attn_pack_v(dtype, S, n, D, _ptr(src.contiguous()), _ptr(dst), _stream()))
+    return dst
+
+
+class AttnDecode:
+    """Device-resident inputs of the kernel-only fused decode attention, in the native layout."""
+
+    def __init__(self, dtype, q, k_share, v_share, k_ring, v_ring, z):
+        import torch
+        self.dtype = dtype
+        B, L, Hq, D = q.shape
+        Hkv, N = k_share.shape[1], k_share.shape[2]
+        w = k_ring.shape[3] if L > 1 else 1
+        self.dims = (B, L, Hq, Hkv, D, N, w)
+        self.q = _to_dev(q, dtype)
+        self.ks = attn_pack_k(dtype, _to_dev(k_share, dtype).reshape(B * Hkv, N, D), N)
+        self.vs = attn_pack_v(dtype, _to_dev(v_share, dtype).reshape(B * Hkv, N, D), N)
+        if L > 1:
+            self.kr = attn_pack_k(dtype, _to_dev(k_ring, dtype).reshape(B * (L - 1) * Hkv, w, D), w)
+            self.vr = attn_pack_v(dtype, _to_dev(v_ring, dtype).reshape(B * (L - 1) * Hkv, w, D), w)
+            self.z = torch.from_numpy(np.ascontiguousarray(z, np.float32)).cuda()
+        else:
+            self.kr = self.vr = self.z = None
+        self.y = torch.empty_like(self.q)
+        nb = lib().plt_attn_scratch_bytes(B, L, Hq, Hkv, D)
+        self.scratch = torch.zeros(nb, dtype=torch.uint8, device="cuda")   # zero once; the library keeps it clean
+
+    def run(self, n_ctx=None, n_ring=None, n_splits=0):
+        B, L, Hq, Hkv, D, N, w = self.dims
+        n_ctx = N if n_ctx is None else n_ctx
+        n_ring = (w if n_ring is None else n_ring) if L > 1 else 0
+        _check(lib().plt_attn_decode(self.dtype, B, L, Hq, Hkv, D, N, n_ctx, w, n_ring, _ptr(self.q), _ptr(self.ks),
+                                     _ptr(self.vs), _ptr(self.kr), _ptr(self.vr), _ptr(self.z), _ptr(self.y),
+                                     _ptr(self.scratch), self.scratch.numel(), n_splits, _stream()))
+        return self.y
+
+
+def gemm(dtype, a, w):
+    """a [M,K], w [N,K] device tensors of the storage type -> float32 [M,N]."""
+    import torch
+    M, K = a.shape
+    N = w.shape[0]
+    c = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    nb = lib().plt_gemm_scratch_bytes(M, N, K)
+    scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    _check(lib().plt_gemm(dtype, M, N, K, _ptr(a.contiguous()), _ptr(w.contiguous()), _ptr(c), _ptr(scratch), nb, _stream()))
+    return c

@@ -1,0 +1,442 @@
+// Fused PLT attention on gfx950 matrix cores, bf16 storage, float statistics.
+//
+// What it computes, for the (up to 16) query rows that share one K/V stream:
+//   first-loop rows : y = Attn(q, K_share, V_share)                                  [Sec. 2.2.1]
+//   other rows      : y = g * SWA(q, own K/V, w) + (1 - g) * Attn(q, K_share, V_share),
+//                     g = sigmoid(z)                                      [Alg. 3 l.2-5, Eq. (2)]
+// Decode: the rows are the L loop stages x G query heads of one (sequence, kv head); K_share /
+// V_share are streamed from HBM exactly once for all of them.  Prefill: the rows are 16
+// consecutive positions of one query head, with per-row causal / window bounds.
+//
+// Tile algebra (one wave, 32 keys at a time, v_mfma_f32_16x16x32_bf16):
+//   S^T[key][row] = K[key][:] . Q[row][:]      A = K rows straight from HBM (16 B per lane),
+//                                              B = Q held in registers
+//   O^T[d][row]  += V^T[d][key] * P^T[key][row]  A = V^T, 16 B per lane thanks to the cache's
+//                                              V layout (blocks of 32 positions, position fastest)
+// With this orientation a lane owns one query row in S^T, P^T and O^T alike, so the online
+// softmax needs no data movement between the two contractions; the row maximum is completed
+// with two wavefront shuffles (lanes r, r+16, r+32, r+48).  The four waves of a workgroup take
+// alternate tiles and merge their (m, l, O) states through LDS; workgroups that split one
+// stream merge through an HBM scratch, the last one to finish (device-scope ticket) writes y.
+#include "plt_internal.h"
+
+namespace plt {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+
+#define NEG_INF (-INFINITY)
+
+__device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ inline uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+
+template <int D>
+struct WaveState {
+  float m;                 // running row maximum (log2 domain), identical in the 4 lanes of a row
+  float l;                 // this lane's share of the row's softmax denominator
+  f32x4 acc[D / 16];       // O^T[d = 16*dt + 4*g + i][row]
+  __device__ void init() {
+    m = NEG_INF; l = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+};
+
+template <int D>
+struct KvTile {
+  uint4 k[2][D / 32];      // two 16-key sub-tiles, D/32 chunks of 8 features each
+  uint4 v[D / 16];         // D/16 groups of 16 features, 8 keys per lane
+};
+
+// kt -> first of the tile's 32 key rows (row stride D); vt -> the tile's V block [D][32]
+template <int D>
+__device__ inline void load_tile(KvTile<D>& t, const bf16_t* __restrict__ kt,
+                                 const bf16_t* __restrict__ vt, int m16, int g) {
+  const int key0 = 8 * (m16 >> 2) + (m16 & 3);   // A-row m16 of sub-tile a <-> key key0 + 4a
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk)
+      t.k[a][kk] = ldg16(kt + (size_t)(key0 + 4 * a) * D + kk * 32 + g * 8);
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16(vt + (dt * 16 + m16) * 32 + g * 8);
+}
+
+// One 32-key step of the online softmax.  valid(j) tells whether key j (0..7 -> tile key 8g+j)
+// may be attended by this lane's row; it is consulted only when need_mask is set.
+template <int D, typename Valid>
+__device__ inline void tile_step(WaveState<D>& st, const KvTile<D>& t, const uint4 (&qf)[D / 32],
+                                 float scale_log2, bool need_mask, Valid valid) {
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[0][kk]), as_bf16x8(qf[kk]), s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[1][kk]), as_bf16x8(qf[kk]), s1, 0, 0, 0);
+  }
+  float sv[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { sv[i] = s0[i] * scale_log2; sv[4 + i] = s1[i] * scale_log2; }
+  if (need_mask) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) if (!valid(j)) sv[j] = NEG_INF;
+  }
+  float mx = sv[0];
+#pragma unroll
+  for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(st.m, mx);
+  const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+  f32x8 p;
+  float ps = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(sv[j] - m_safe); ps += p[j]; }
+  st.l = st.l * alpha + ps;
+  st.m = m_new;
+  const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) {
+    f32x4 a = st.acc[dt];
+    a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
+    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.v[dt]), pb, a, 0, 0, 0);
+  }
+}
+
+// LDS block used to merge the four waves of a workgroup.
+template <int D>
+struct WgMerge {
+  float m[4][16];
+  float l[4][16];
+  float acc[4][16][D + 4];
+};
+
+// After this call thread tid holds, for row tid/16 and features (tid%16)*(D/16) .. +D/16-1, the
+// workgroup-wide unnormalised output o[], the row maximum M and the denominator Lsum.
+template <int D>
+__device__ inline void wg_merge(WgMerge<D>& sm, WaveState<D>& st, int wv, int m16, int g,
+                                float& M, float& Lsum, float (&o)[D / 16]) {
+  float l = st.l;
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  __syncthreads();                       // previous users of sm are done
+  if (g == 0) { sm.m[wv][m16] = st.m; sm.l[wv][m16] = l; }
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sm.acc[wv][m16][dt * 16 + 4 * g + i] = st.acc[dt][i];
+  __syncthreads();
+  const int row = threadIdx.x >> 4, dc = (threadIdx.x & 15) * (D / 16);
+  M = fmaxf(fmaxf(sm.m[0][row], sm.m[1][row]), fmaxf(sm.m[2][row], sm.m[3][row]));
+  Lsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) o[i] = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const float mw = sm.m[w][row];
+    const float f = (mw == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+    Lsum += f * sm.l[w][row];
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) o[i] += f * sm.acc[w][row][dc + i];
+  }
+}
+
+template <int D>
+__device__ inline void store_row(bf16_t* __restrict__ dst, const float (&v)[D / 16]) {
+  // D/16 consecutive bf16 values: 4 (D = 64) or 8 (D = 128)
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) dst[i] = f32_to_bf16(v[i]);
+}
+
+// ------------------------------------------------------------------------------- decode
+
+struct AttnDecArgs {
+  const bf16_t* q; const float* z; bf16_t* y;
+  const bf16_t* k_share; const bf16_t* v_share; const bf16_t* k_ring; const bf16_t* v_ring;
+  const int32_t* pos;          // per-sequence position being consumed, or null
+  int n_ctx_uniform, n_ring_uniform;
+  int n_pad, w_pad, w, n_rings;
+  int L, Hq, Hkv, G, n_rows, n_rt, n_splits, plain;
+  float scale_log2;
+  float* part;                 // [stream][rt][split] records of (16 + 16 + 16*D) floats
+  float* part_loc;             // [stream][rt] records of 16*D floats (normalised local branch)
+  unsigned int* ticket;        // [stream][rt], zero between launches
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
+  __shared__ WgMerge<D> sm;
+  __shared__ unsigned int s_ticket;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int split = blockIdx.x % A.n_splits, rt = blockIdx.x / A.n_splits;
+  const int kvh = blockIdx.y, b = blockIdx.z;
+  const int n_ctx = A.pos ? A.pos[b] + 1 : A.n_ctx_uniform;
+  const int n_ring = A.pos ? (A.pos[b] + 1 < A.w ? A.pos[b] + 1 : A.w) : A.n_ring_uniform;
+  const size_t stream = (size_t)b * A.Hkv + kvh;
+
+  // this lane's query row (B operand: lane (row, g) holds features kk*32 + g*8 .. +7)
+  const int qrow = rt * 16 + m16;
+  const bool qrow_ok = qrow < A.n_rows;
+  const int q_loop = qrow_ok ? qrow / A.G : 0;
+  const int q_head = kvh * A.G + (qrow_ok ? qrow % A.G : 0);
+  uint4 qf[D / 32];
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    qf[kk] = make_uint4(0, 0, 0, 0);
+    if (qrow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.L + q_loop) * A.Hq + q_head) * D + kk * 32 + g * 8);
+  }
+
+  // ---- global branch: this split's share of the shared cache, alternate tiles per wave ----
+  const int n_tiles = (n_ctx + 31) >> 5;
+  const int tps = (n_tiles + A.n_splits - 1) / A.n_splits;
+  const int t_beg = split * tps;
+  const int t_end = (t_beg + tps < n_tiles) ? t_beg + tps : n_tiles;
+  const bf16_t* kbase = A.k_share + stream * (size_t)A.n_pad * D;
+  const bf16_t* vbase = A.v_share + stream * (size_t)A.n_pad * D;
+  WaveState<D> st; st.init();
+  {
+    KvTile<D> cur, nxt;
+    int t = t_beg + wv;
+    if (t < t_end) load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
+    for (; t < t_end; t += 4) {
+      const int tn = t + 4;
+      if (tn < t_end) load_tile<D>(nxt, kbase + (size_t)tn * 32 * D, vbase + (size_t)tn * 32 * D, m16, g);
+      const int kb = t * 32 + 8 * g;
+      tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * 32 > n_ctx, [&](int j) { return kb + j < n_ctx; });
+      if (tn < t_end) cur = nxt;
+    }
+  }
+  float Mg, Lg, og[D / 16];
+  wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
+
+  // ---- local branch (last split only): the rings of loops 2..L, one ring per 32-slot tiles ----
+  const bool do_local = !A.plain && A.n_rings > 0 && split == A.n_splits - 1;
+  float Ml = NEG_INF, Ll = 0.f, ol[D / 16];
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) ol[i] = 0.f;
+  if (do_local) {
+    st.init();
+    const int tpr = A.w_pad >> 5;
+    const int vt_end = A.n_rings * tpr;
+    for (int vt = wv; vt < vt_end; vt += 4) {
+      const int rl = vt / tpr, tr = vt - rl * tpr;
+      if (tr * 32 >= n_ring) continue;
+      const size_t rs = (((size_t)b * A.n_rings + rl) * A.Hkv + kvh) * (size_t)A.w_pad * D;
+      KvTile<D> cur;
+      load_tile<D>(cur, A.k_ring + rs + (size_t)tr * 32 * D, A.v_ring + rs + (size_t)tr * 32 * D, m16, g);
+      const int sb = tr * 32 + 8 * g;
+      const bool mine = qrow_ok && (q_loop == rl + 1);
+      tile_step<D>(st, cur, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); });
+    }
+    wg_merge<D>(sm, st, wv, m16, g, Ml, Ll, ol);
+  }
+
+  // ---- thread (row, feature chunk) view from here on ----
+  const int row = rt * 16 + (tid >> 4), dc = (tid & 15) * (D / 16);
+  const bool row_ok = row < A.n_rows;
+  const int r_loop = row_ok ? row / A.G : 0, r_head = kvh * A.G + (row_ok ? row % A.G : 0);
+  const bool gated = !A.plain && r_loop > 0;
+  const size_t rec = (size_t)(16 + 16 + 16 * D);
+  const size_t slot = stream * A.n_rt + rt;
+
+  if (A.n_splits > 1) {
+    float* pr = A.part + (slot * A.n_splits + split) * rec;
+    if ((tid & 15) == 0) { pr[tid >> 4] = Mg; pr[16 + (tid >> 4)] = Lg; }
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) pr[32 + (tid >> 4) * D + dc + i] = og[i];
+    if (do_local) {
+      float* pl = A.part_loc + slot * (size_t)(16 * D);
+      const float inv = Ll > 0.f ? 1.0f / Ll : 0.f;
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) pl[(tid >> 4) * D + dc + i] = ol[i] * inv;
+    }
+    __threadfence();                                   // publish this workgroup's records
+    __syncthreads();
+    if (tid == 0) s_ticket = atomicAdd(&A.ticket[slot], 1u);
+    __syncthreads();
+    if (s_ticket != (unsigned)(A.n_splits - 1)) return; // not the last one: done
+    __threadfence();                                   // see every other workgroup's records
+    // merge all splits (fixed order -> bit-reproducible regardless of who arrives last)
+    const float* p0 = A.part + slot * A.n_splits * rec;
+    float M = NEG_INF;
+    for (int s = 0; s < A.n_splits; ++s) M = fmaxf(M, *(p0 + s * rec + (tid >> 4)));
+    Lg = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) og[i] = 0.f;
+    for (int s = 0; s < A.n_splits; ++s) {
+      const float* ps = p0 + s * rec;
+      const float ms = *(ps + (tid >> 4));
+      const float f = (ms == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+      Lg += f * *(ps + 16 + (tid >> 4));
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) og[i] += f * *(ps + 32 + (tid >> 4) * D + dc + i);
+    }
+    if (gated) {
+      const float* pl = A.part_loc + slot * (size_t)(16 * D);
+#pragma unroll
+      for (int i = 0; i < D / 16; ++i) ol[i] = *(pl + (tid >> 4) * D + dc + i);
+      Ll = 1.f;
+    }
+    if (tid == 0) A.ticket[slot] = 0u;                 // leave the ticket clean for the next launch
+  }
+
+  if (!row_ok) return;
+  float out[D / 16];
+  const float invg = Lg > 0.f ? 1.0f / Lg : 0.f;
+  if (gated) {
+    const float zz = A.z[((size_t)b * (A.L - 1) + (r_loop - 1)) * A.Hq + r_head];
+    const float gate = 1.0f / (1.0f + __expf(-zz));
+    const float invl = Ll > 0.f ? 1.0f / Ll : 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) out[i] = gate * (ol[i] * invl) + (1.0f - gate) * (og[i] * invg);
+  } else {
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
+  }
+  store_row<D>(A.y + (((size_t)b * A.L + r_loop) * A.Hq + r_head) * D + dc, out);
+}
+
+size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D) {
+  const int G = Hq / Hkv, n_rt = (L * G + 15) / 16;
+  const size_t slots = (size_t)B * Hkv * n_rt;
+  const size_t rec = (size_t)(32 + 16 * D) * sizeof(float);
+  const size_t max_splits = 64;
+  size_t bytes = slots * 256;                       // tickets (one per slot, padded)
+  bytes += slots * max_splits * rec;                // split records
+  bytes += slots * (size_t)(16 * D) * sizeof(float);  // local-branch records
+  return bytes;
+}
+
+int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx) {
+  const int n_rt = (L * G + 15) / 16;
+  const long streams = (long)B * Hkv * n_rt;
+  const int n_tiles = (n_ctx + 31) / 32;
+  // aim for >= 4 workgroups per compute unit, but keep >= 16 tiles (4 per wave) per workgroup
+  int s = (int)((4L * 256 + streams - 1) / streams);
+  int cap = n_tiles / 16; if (cap < 1) cap = 1;
+  if (s > cap) s = cap;
+  if (s > 64) s = 64;
+  if (s < 1) s = 1;
+  return s;
+}
+
+void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
+                             const int32_t* pos, int n_ctx_uniform, int n_ring_uniform, Dims dm,
+                             int plain, void* scratch, int n_splits) {
+  AttnDecArgs A;
+  A.q = q; A.z = z; A.y = y;
+  A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
+  A.k_ring = (const bf16_t*)kv.k_ring; A.v_ring = (const bf16_t*)kv.v_ring;
+  A.pos = pos; A.n_ctx_uniform = n_ctx_uniform; A.n_ring_uniform = n_ring_uniform;
+  A.n_pad = kv.n_pad; A.w_pad = kv.w_pad; A.w = kv.w; A.n_rings = plain ? 0 : kv.n_rings;
+  A.L = dm.L; A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
+  A.n_rows = dm.L * A.G; A.n_rt = (A.n_rows + 15) / 16;
+  A.n_splits = n_splits < 1 ? 1 : (n_splits > 64 ? 64 : n_splits);
+  A.plain = plain;
+  A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
+  const size_t slots = (size_t)dm.B * dm.Hkv * A.n_rt;
+  const size_t rec = (size_t)(32 + 16 * dm.D);
+  char* sp = (char*)scratch;
+  A.ticket = (unsigned int*)sp;
+  A.part = (float*)(sp + slots * 256);
+  A.part_loc = A.part + slots * 64 * rec;
+  dim3 grid(A.n_splits * A.n_rt, dm.Hkv, dm.B);
+  if (dm.D == 64) hipLaunchKernelGGL(k_attn_decode<64>, grid, dim3(256), 0, s, A);
+  else hipLaunchKernelGGL(k_attn_decode<128>, grid, dim3(256), 0, s, A);
+}
+
+// ------------------------------------------------------------------------------- prefill
+// Rows = 16 consecutive positions p0..p0+15 of one query head; keys of the shared cache with
+// j <= p_row; for loops >= 2 also the loop's own keys with p_row - w < j <= p_row, then Eq. (2).
+
+struct AttnPreArgs {
+  const bf16_t* q; const float* z; bf16_t* y;
+  const bf16_t* k_share; const bf16_t* v_share; const bf16_t* k_loc; const bf16_t* v_loc;
+  int n, n_pad, n_pad_loc, w, b0, Hq, Hkv, G, gated;
+  float scale_log2;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void k_attn_prefill(AttnPreArgs A) {
+  __shared__ WgMerge<D> sm;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z, kvh = h / A.G;
+  const int p0 = qt * 16;
+  const int prow = p0 + m16;                       // this lane's query position
+  const bool prow_ok = prow < A.n;
+  uint4 qf[D / 32];
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    qf[kk] = make_uint4(0, 0, 0, 0);
+    if (prow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.n + prow) * A.Hq + h) * D + kk * 32 + g * 8);
+  }
+  const int p_last = (p0 + 15 < A.n ? p0 + 15 : A.n - 1);
+  WaveState<D> st; st.init();
+  {
+    const size_t stream = (size_t)(A.b0 + b) * A.Hkv + kvh;
+    const bf16_t* kbase = A.k_share + stream * (size_t)A.n_pad * D;
+    const bf16_t* vbase = A.v_share + stream * (size_t)A.n_pad * D;
+    const int t_end = (p_last >> 5) + 1;
+    for (int t = wv; t < t_end; t += 4) {
+      KvTile<D> cur;
+      load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
+      const int kb = t * 32 + 8 * g;
+      tile_step<D>(st, cur, qf, A.scale_log2, t * 32 + 31 > p0, [&](int j) { return kb + j <= prow; });
+    }
+  }
+  float Mg, Lg, og[D / 16];
+  wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
+  float Ml = NEG_INF, Ll = 0.f, ol[D / 16];
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) ol[i] = 0.f;
+  if (A.gated) {
+    st.init();
+    const size_t stream = (size_t)b * A.Hkv + kvh;
+    const bf16_t* kbase = A.k_loc + stream * (size_t)A.n_pad_loc * D;
+    const bf16_t* vbase = A.v_loc + stream * (size_t)A.n_pad_loc * D;
+    int j_lo = p0 - A.w + 1; if (j_lo < 0) j_lo = 0;
+    const int t_beg = j_lo >> 5, t_end = (p_last >> 5) + 1;
+    for (int t = t_beg + wv; t < t_end; t += 4) {
+      KvTile<D> cur;
+      load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
+      const int kb = t * 32 + 8 * g;
+      tile_step<D>(st, cur, qf, A.scale_log2, true,
+                   [&](int j) { return (kb + j <= prow) && (kb + j > prow - A.w); });
+    }
+    wg_merge<D>(sm, st, wv, m16, g, Ml, Ll, ol);
+  }
+  const int pr = p0 + (tid >> 4), dc = (tid & 15) * (D / 16);
+  if (pr >= A.n) return;
+  const size_t r = (size_t)b * A.n + pr;
+  float out[D / 16];
+  const float invg = Lg > 0.f ? 1.0f / Lg : 0.f;
+  if (A.gated) {
+    const float zz = A.z[r * A.Hq + h];
+    const float gate = 1.0f / (1.0f + __expf(-zz));
+    const float invl = Ll > 0.f ? 1.0f / Ll : 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) out[i] = gate * (ol[i] * invl) + (1.0f - gate) * (og[i] * invg);
+  } else {
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
+  }
+  store_row<D>(A.y + (r * A.Hq + h) * D + dc, out);
+}
+
+void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
+                              int Bc, int n, int loop, Dims dm, int plain) {
+  AttnPreArgs A;
+  A.q = q; A.z = z; A.y = y;
+  A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
+  A.k_loc = (const bf16_t*)kv.k_loc; A.v_loc = (const bf16_t*)kv.v_loc;
+  A.n = n; A.n_pad = kv.n_pad; A.n_pad_loc = kv.n_pad_loc; A.w = kv.w; A.b0 = kv.b0;
+  A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
+  A.gated = (!plain && loop > 0) ? 1 : 0;
+  A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
+  dim3 grid((n + 15) / 16, dm.Hq, Bc);
+  if (dm.D == 64) hipLaunchKernelGGL(k_attn_prefill<64>, grid, dim3(256), 0, s, A);
+  else hipLaunchKernelGGL(k_attn_prefill<128>, grid, dim3(256), 0, s, A);
+}
+
+}  // namespace plt

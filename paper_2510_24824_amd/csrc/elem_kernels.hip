@@ -1,0 +1,326 @@
+// Element-wise / row-wise kernels of the PLT step: micro-batch build, RMSNorm with residual
+// accumulation, RoPE + gate logit + cache append, SwiGLU, carry update, argmax, layout packs.
+// All are bandwidth-trivial next to attention and the projections; they are written for
+// coalesced access and wave64 reductions, nothing more.
+#include "plt_internal.h"
+
+namespace plt {
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// block-wide sum for blockDim.x == 256 (4 waves)
+__device__ inline float block_sum_256(float v, float* sm /*[4]*/) {
+  v = wave_sum(v);
+  int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sm[w] = v;
+  __syncthreads();
+  return sm[0] + sm[1] + sm[2] + sm[3];
+}
+
+// ---- S0: displaced micro-batch [Alg. 1 l.5-6]; prefill: E + shift(H^(l-1)) [Alg. 2 l.4-5] ----
+template <typename T>
+__global__ void k_embed(const int32_t* __restrict__ tokens, const T* __restrict__ emb,
+                        const float* __restrict__ carry, const float* __restrict__ hprev,
+                        float* __restrict__ x, int d, RowMap rm, int n_loops, int add_prev, int vocab) {
+  int r = blockIdx.x;
+  int b, p, l;
+  row_decode(rm, r, b, p, l);
+  int tok = rm.prefill ? tokens[r] : tokens[b];
+  tok = tok < 0 ? 0 : (tok >= vocab ? vocab - 1 : tok);   // ids outside the vocabulary are clamped
+  const T* e = emb + (size_t)tok * d;
+  const float* add = nullptr;
+  if (add_prev && l > 0) {
+    if (rm.prefill) { if (p > 0) add = hprev + (size_t)(r - 1) * d; }   // right shift by one
+    else add = carry + ((size_t)b * (n_loops - 1) + (l - 1)) * d;        // H^l[p-1]
+  }
+  for (int i = threadIdx.x; i < d; i += blockDim.x) {
+    float v = ld<T>(e + i);
+    if (add) v += add[i];
+    x[(size_t)r * d + i] = v;
+  }
+}
+template <typename T>
+void launch_embed(hipStream_t s, const int32_t* tokens, const T* emb, const float* carry,
+                  const float* hprev, float* x, int R, int d, RowMap rm, int n_loops, int add_prev, int vocab) {
+  hipLaunchKernelGGL(k_embed<T>, dim3(R), dim3(256), 0, s, tokens, emb, carry, hprev, x, d, rm,
+                     n_loops, add_prev, vocab);
+}
+template void launch_embed<float>(hipStream_t, const int32_t*, const float*, const float*, const float*, float*, int, int, RowMap, int, int, int);
+template void launch_embed<bf16_t>(hipStream_t, const int32_t*, const bf16_t*, const float*, const float*, float*, int, int, RowMap, int, int, int);
+
+// ---- residual accumulation of GEMM slabs + RMSNorm (block f's two norms and the final norm) ----
+template <typename T>
+__global__ void k_resid_norm(float* __restrict__ x, int x_row_stride, int x_row_off,
+                             const float* __restrict__ partials, int S, size_t slab,
+                             const float* __restrict__ gain, float eps, T* __restrict__ a_out, int d) {
+  __shared__ float sm[4];
+  int r = blockIdx.x;
+  float* xr = x + ((size_t)r * x_row_stride + x_row_off) * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = xr[i];
+    if (S > 0) {
+      float acc = 0.f;
+      for (int s = 0; s < S; ++s) acc += partials[(size_t)s * slab + (size_t)r * d + i];
+      v += acc;
+      xr[i] = v;
+    }
+    ss += v * v;
+  }
+  if (a_out == nullptr) return;
+  ss = block_sum_256(ss, sm);
+  float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256) st<T>(a_out + (size_t)r * d + i, xr[i] * inv * gain[i]);
+}
+template <typename T>
+void launch_resid_norm(hipStream_t s, float* x, int x_row_stride, int x_row_off,
+                       const float* partials, int S, size_t slab, const float* gain, float eps,
+                       T* a_out, int R, int d) {
+  hipLaunchKernelGGL(k_resid_norm<T>, dim3(R), dim3(256), 0, s, x, x_row_stride, x_row_off, partials,
+                     S, slab, gain, eps, a_out, d);
+}
+template void launch_resid_norm<float>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, float*, int, int);
+template void launch_resid_norm<bf16_t>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, bf16_t*, int, int);
+
+// ---- S3: RoPE, gate logit (Eq. 2, on the un-rotated query), cache append ----
+// grid (Hq + 2*Hkv, R), 64 threads: thread j < D/2 owns the pair (j, j + D/2) of one head vector.
+template <typename T>
+__global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
+                              const float* __restrict__ gate_w, const float* __restrict__ gate_b,
+                              T* __restrict__ q_out, float* __restrict__ z_out, KvView kv, RowMap rm,
+                              Dims dm, float theta, int plain) {
+  const int hs = blockIdx.x, r = blockIdx.y, j = threadIdx.x;
+  const int D = dm.D, half = D / 2, Hq = dm.Hq, Hkv = dm.Hkv;
+  const int ncol = (Hq + 2 * Hkv) * D;
+  int b, p, l;
+  row_decode(rm, r, b, p, l);
+  const bool act = j < half;
+  float lo = 0.f, hi = 0.f;
+  if (act) {
+    const float* src = qkv + (size_t)r * ncol + (size_t)hs * D;
+    for (int s = 0; s < S; ++s) { lo += src[(size_t)s * slab + j]; hi += src[(size_t)s * slab + j + half]; }
+  }
+  float c = 1.f, sn = 0.f;
+  if (act && hs < Hq + Hkv) {
+    double ang = (double)p * pow((double)theta, -2.0 * (double)j / (double)D);
+    c = (float)cos(ang); sn = (float)sin(ang);
+  }
+  if (hs < Hq) {
+    if (!plain && l > 0) {
+      float zp = act ? lo * gate_w[hs * D + j] + hi * gate_w[hs * D + j + half] : 0.f;
+      zp = wave_sum(zp);
+      if (j == 0) {
+        size_t zi = rm.prefill ? (size_t)r * Hq + hs
+                               : ((size_t)b * (dm.L - 1) + (l - 1)) * Hq + hs;
+        z_out[zi] = zp + gate_b[hs];
+      }
+    }
+    if (act) {
+      T* dst = q_out + (size_t)r * Hq * D + (size_t)hs * D;
+      st<T>(dst + j, lo * c - hi * sn);
+      st<T>(dst + j + half, hi * c + lo * sn);
+    }
+    return;
+  }
+  if (!act) return;
+  const bool is_k = hs < Hq + Hkv;
+  const int kh = is_k ? hs - Hq : hs - Hq - Hkv;
+  float v0 = lo, v1 = hi;
+  if (is_k) { v0 = lo * c - hi * sn; v1 = hi * c + lo * sn; }
+  const int bg = kv.b0 + b;
+  if (plain || l == 0) {                       // first loop: the shared cache [Sec. 2.2.2]
+    size_t stream = (size_t)bg * Hkv + kh;
+    if (is_k) {
+      T* dst = (T*)kv.k_share + (stream * kv.n_pad + p) * D;
+      st<T>(dst + j, v0); st<T>(dst + j + half, v1);
+    } else {
+      T* dst = (T*)kv.v_share + stream * (size_t)kv.n_pad * D;
+      st<T>(dst + vblk_index(p, j, D), v0); st<T>(dst + vblk_index(p, j + half, D), v1);
+    }
+    return;
+  }
+  // non-first loop: only the w most recent entries survive (ring slot = p mod w)
+  const int n = rm.rows_per_seq;
+  if (rm.prefill) {
+    size_t stream = (size_t)b * Hkv + kh;
+    if (is_k) {
+      T* dst = (T*)kv.k_loc + (stream * kv.n_pad_loc + p) * D;
+      st<T>(dst + j, v0); st<T>(dst + j + half, v1);
+    } else {
+      T* dst = (T*)kv.v_loc + stream * (size_t)kv.n_pad_loc * D;
+      st<T>(dst + vblk_index(p, j, D), v0); st<T>(dst + vblk_index(p, j + half, D), v1);
+    }
+    if (p < n - kv.w) return;
+  }
+  {
+    const int slot = p % kv.w;
+    size_t stream = ((size_t)bg * kv.n_rings + (l - 1)) * Hkv + kh;
+    if (is_k) {
+      T* dst = (T*)kv.k_ring + (stream * kv.w_pad + slot) * D;
+      st<T>(dst + j, v0); st<T>(dst + j + half, v1);
+    } else {
+      T* dst = (T*)kv.v_ring + stream * (size_t)kv.w_pad * D;
+      st<T>(dst + vblk_index(slot, j, D), v0); st<T>(dst + vblk_index(slot, j + half, D), v1);
+    }
+  }
+}
+template <typename T>
+void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
+                        const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
+                        Dims dm, float theta, int plain) {
+  hipLaunchKernelGGL(k_rope_append<T>, dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
+                     gate_w, gate_b, q_out, z_out, kv, rm, dm, theta, plain);
+}
+template void launch_rope_append<float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, float, int);
+template void launch_rope_append<bf16_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, float, int);
+
+// ---- SwiGLU: act = silu(gate) * up, gate = columns [0,F), up = columns [F,2F) ----
+template <typename T>
+__global__ void k_silu_mul(const float* __restrict__ gu, int S, size_t slab, T* __restrict__ act,
+                           int R, int F) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)R * F) return;
+  int r = (int)(i / F), f = (int)(i - (size_t)r * F);
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float* row = gu + (size_t)s * slab + (size_t)r * 2 * F;
+    g += row[f]; u += row[F + f];
+  }
+  st<T>(act + i, g / (1.0f + expf(-g)) * u);
+}
+template <typename T>
+void launch_silu_mul(hipStream_t s, const float* gu, int S, size_t slab, T* act, int R, int F) {
+  size_t n = (size_t)R * F;
+  hipLaunchKernelGGL(k_silu_mul<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, gu, S, slab,
+                     act, R, F);
+}
+template void launch_silu_mul<float>(hipStream_t, const float*, int, size_t, float*, int, int);
+template void launch_silu_mul<bf16_t>(hipStream_t, const float*, int, size_t, bf16_t*, int, int);
+
+// ---- greedy head: sum slabs, optional logits copy-out, argmax with lowest-index ties ----
+__global__ void k_argmax(const float* __restrict__ lg, int S, size_t slab, float* __restrict__ out,
+                         int32_t* __restrict__ next, int V) {
+  __shared__ float bv[256];
+  __shared__ int bi[256];
+  int b = blockIdx.x;
+  float best = -INFINITY; int idx = 0x7fffffff;
+  for (int i = threadIdx.x; i < V; i += 256) {
+    float v = 0.f;
+    for (int s = 0; s < S; ++s) v += lg[(size_t)s * slab + (size_t)b * V + i];
+    if (out) out[(size_t)b * V + i] = v;
+    if (v > best) { best = v; idx = i; }
+  }
+  bv[threadIdx.x] = best; bi[threadIdx.x] = idx;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) {
+      float v2 = bv[threadIdx.x + o]; int i2 = bi[threadIdx.x + o];
+      if (v2 > bv[threadIdx.x] || (v2 == bv[threadIdx.x] && i2 < bi[threadIdx.x])) {
+        bv[threadIdx.x] = v2; bi[threadIdx.x] = i2;
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) next[b] = bi[0] == 0x7fffffff ? 0 : bi[0];
+}
+void launch_argmax(hipStream_t s, const float* lg, int S, size_t slab, float* logits_out,
+                   int32_t* next, int B, int V) {
+  hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, s, lg, S, slab, logits_out, next, V);
+}
+
+// ---- S7: carried states for the next step: carry[b][l] = H^(l+1)[p], l = 0..L-2 ----
+__global__ void k_carry_update(const float* __restrict__ x, float* __restrict__ carry, int L, int d) {
+  int b = blockIdx.x / (L - 1), l = blockIdx.x % (L - 1);
+  const float* src = x + ((size_t)b * L + l) * d;
+  float* dst = carry + ((size_t)b * (L - 1) + l) * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = src[i];
+}
+void launch_carry_update(hipStream_t s, const float* x, float* carry, int B, int L, int d) {
+  if (L <= 1) return;
+  hipLaunchKernelGGL(k_carry_update, dim3(B * (L - 1)), dim3(256), 0, s, x, carry, L, d);
+}
+// prefill: carry[b0+b][l] = H^(l+1)[n-1] taken from the chunk's activation rows
+__global__ void k_prefill_carry(const float* __restrict__ x, float* __restrict__ carry, int b0, int n,
+                                int L, int l, int d) {
+  int b = blockIdx.x;
+  const float* src = x + ((size_t)b * n + (n - 1)) * d;
+  float* dst = carry + ((size_t)(b0 + b) * (L - 1) + l) * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) dst[i] = src[i];
+}
+void launch_prefill_carry(hipStream_t s, const float* x, float* carry, int b0, int Bc, int n, int L,
+                          int l, int d) {
+  hipLaunchKernelGGL(k_prefill_carry, dim3(Bc), dim3(256), 0, s, x, carry, b0, n, L, l, d);
+}
+
+__global__ void k_pos_set(int32_t* pos, int B, int value, int increment) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < B) pos[i] = increment ? pos[i] + value : value;
+}
+void launch_pos_set(hipStream_t s, int32_t* pos, int B, int value, int increment) {
+  hipLaunchKernelGGL(k_pos_set, dim3((B + 255) / 256), dim3(256), 0, s, pos, B, value, increment);
+}
+
+__global__ void k_copy_f32(const float* __restrict__ a, float* __restrict__ b, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) b[i] = a[i];
+}
+void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n) {
+  unsigned g = (unsigned)((n + 255) / 256); if (g > 65536u) g = 65536u;
+  hipLaunchKernelGGL(k_copy_f32, dim3(g), dim3(256), 0, s, x, hprev, n);
+}
+
+// ---- layout packs: plain [S, n, D] <-> K [S, n_pad, D] / V [S, n_pad/32, D, 32] ----
+template <typename T>
+__global__ void k_pack_k(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D) {
+  int sidx = blockIdx.y;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)n_pad * D) return;
+  int pos = (int)(i / D);
+  T zero; st<T>(&zero, 0.f);
+  dst[(size_t)sidx * n_pad * D + i] = pos < n ? src[(size_t)sidx * n * D + i] : zero;
+}
+template <typename T>
+__global__ void k_pack_v(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D, int unpack) {
+  int sidx = blockIdx.y;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)n_pad * D) return;
+  // i enumerates the blocked layout: [blk][d][32]
+  int blk = (int)(i / ((size_t)D * 32));
+  int rem = (int)(i - (size_t)blk * D * 32);
+  int dd = rem >> 5, pos = blk * 32 + (rem & 31);
+  if (unpack) {
+    if (pos < n) dst[(size_t)sidx * n * D + (size_t)pos * D + dd] = src[(size_t)sidx * n_pad * D + i];
+  } else {
+    T zero; st<T>(&zero, 0.f);
+    dst[(size_t)sidx * n_pad * D + i] = pos < n ? src[(size_t)sidx * n * D + (size_t)pos * D + dd] : zero;
+  }
+}
+template <typename T>
+void launch_pack_k(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D) {
+  size_t per = (size_t)n_pad * D;
+  hipLaunchKernelGGL(k_pack_k<T>, dim3((unsigned)((per + 255) / 256), S), dim3(256), 0, s, src, dst, n, n_pad, D);
+}
+template <typename T>
+void launch_pack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D) {
+  size_t per = (size_t)n_pad * D;
+  hipLaunchKernelGGL(k_pack_v<T>, dim3((unsigned)((per + 255) / 256), S), dim3(256), 0, s, src, dst, n, n_pad, D, 0);
+}
+template <typename T>
+void launch_unpack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D) {
+  size_t per = (size_t)n_pad * D;
+  hipLaunchKernelGGL(k_pack_v<T>, dim3((unsigned)((per + 255) / 256), S), dim3(256), 0, s, src, dst, n, n_pad, D, 1);
+}
+template void launch_pack_k<float>(hipStream_t, const float*, float*, int, int, int, int);
+template void launch_pack_k<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, int, int, int);
+template void launch_pack_v<float>(hipStream_t, const float*, float*, int, int, int, int);
+template void launch_pack_v<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, int, int, int);
+template void launch_unpack_v<float>(hipStream_t, const float*, float*, int, int, int, int);
+template void launch_unpack_v<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, int, int, int);
+
+}  // namespace plt

@@ -1,0 +1,663 @@
+// Host side of libplt.so: the C ABI of include/plt.h, the cache / weight layouts and the
+// CLP token/loop scheduler (which kernels run, in which order, on which rows).
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+#include "plt_internal.h"
+
+using namespace plt;
+
+// ------------------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+static int fail(int code, const char* fmt, ...) {
+  va_list ap; va_start(ap, fmt); vsnprintf(g_err, sizeof(g_err), fmt, ap); va_end(ap);
+  return code;
+}
+#define HIP_TRY(expr)                                                                     \
+  do { hipError_t e_ = (expr);                                                            \
+       if (e_ != hipSuccess) return fail(PLT_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); } while (0)
+
+extern "C" const char* plt_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------------ objects
+struct LayerW {
+  const float* norm1; const void* wqkv; const float* gate_w; const float* gate_b;
+  const void* wo; const float* norm2; const void* wgu; const void* wdown;
+};
+struct plt_model {
+  plt_config cfg;
+  hipStream_t stream;
+  const char* blob;
+  std::vector<LayerW> layers;
+  const void* emb; const float* norm_f; const void* head;
+  int es;   // element size of the model dtype
+};
+struct plt_kv {
+  plt_model* m;
+  int B, max_ctx, n_pad, w_pad, n_caches, n_rings;
+  char* buf;
+  size_t share_elems;  // elements of one layer's K_share (= V_share): B*Hkv*n_pad*D
+  size_t ring_elems;   // elements of one layer's ring K (= ring V): B*(L-1)*Hkv*w_pad*D
+  size_t ring_base;    // byte offset of the ring area
+  int pos; bool started;
+  // per-step activation scratch (device, library-owned)
+  float* x; void* a; float* gout; size_t gout_elems; void* q; float* z; void* y; void* act;
+  float* carry; int32_t* pos_dev; void* attn_scratch; size_t attn_scratch_bytes;
+};
+
+static bool cfg_valid(const plt_config* c, const char** why) {
+  *why = "";
+  if (!c) { *why = "null config"; return false; }
+  if (c->n_layers < 1 || c->d_model < 1 || c->n_heads < 1 || c->n_kv_heads < 1 || c->ffn_hidden < 1 ||
+      c->vocab < 1) { *why = "non-positive dimension"; return false; }
+  if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return false; }
+  if (c->n_heads % c->n_kv_heads) { *why = "n_heads must be a multiple of n_kv_heads"; return false; }
+  if (c->n_loops < 1 || c->n_loops > 16) { *why = "n_loops must be in 1..16"; return false; }
+  if (c->mode != PLT_MODE_CLP && c->mode != PLT_MODE_VANILLA_LOOP) { *why = "unknown mode"; return false; }
+  if (c->mode == PLT_MODE_CLP && c->n_loops > 1 && c->window < 1) { *why = "window must be >= 1"; return false; }
+  if (c->dtype != PLT_F32 && c->dtype != PLT_BF16) { *why = "unknown dtype"; return false; }
+  if (c->dtype == PLT_BF16 && (c->d_model % 64 || c->ffn_hidden % 64)) {
+    *why = "bf16 needs d_model and ffn_hidden to be multiples of 64"; return false;
+  }
+  if (!(c->rope_theta > 0.f) || !(c->norm_eps >= 0.f)) { *why = "bad rope_theta / norm_eps"; return false; }
+  return true;
+}
+
+static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// walks the blob layout; returns total bytes, reports one tensor if asked
+static size_t blob_walk(const plt_config* c, int want_layer, int want_which, size_t* off, size_t* nelem) {
+  const size_t es = c->dtype == PLT_BF16 ? 2 : 4;
+  const size_t d = c->d_model, Hq = c->n_heads, Hkv = c->n_kv_heads, D = c->head_dim, F = c->ffn_hidden,
+               V = c->vocab;
+  size_t cur = 0;
+  auto put = [&](int layer, int which, size_t n, size_t esz) {
+    cur = align256(cur);
+    if (which == want_which && (layer == want_layer || layer < 0)) { if (off) *off = cur; if (nelem) *nelem = n; }
+    cur += n * esz;
+  };
+  put(-1, PLT_W_EMB, V * d, es);
+  for (int m = 0; m < c->n_layers; ++m) {
+    put(m, PLT_W_NORM1, d, 4);
+    put(m, PLT_W_WQKV, (Hq + 2 * Hkv) * D * d, es);
+    put(m, PLT_W_GATE_W, Hq * D, 4);
+    put(m, PLT_W_GATE_B, Hq, 4);
+    put(m, PLT_W_WO, d * Hq * D, es);
+    put(m, PLT_W_NORM2, d, 4);
+    put(m, PLT_W_WGU, 2 * F * d, es);
+    put(m, PLT_W_WDOWN, d * F, es);
+  }
+  put(-1, PLT_W_NORM_F, d, 4);
+  if (!c->tie_embeddings) put(-1, PLT_W_HEAD, V * d, es);
+  return align256(cur);
+}
+
+extern "C" size_t plt_weights_bytes(const plt_config* cfg) {
+  const char* why;
+  if (!cfg_valid(cfg, &why)) { fail(PLT_EINVAL, "plt_weights_bytes: %s", why); return 0; }
+  return blob_walk(cfg, -2, -1, nullptr, nullptr);
+}
+
+extern "C" int plt_weights_offset(const plt_config* cfg, int32_t layer, int32_t which, size_t* off,
+                                  size_t* nelem) {
+  const char* why;
+  if (!cfg_valid(cfg, &why)) return fail(PLT_EINVAL, "plt_weights_offset: %s", why);
+  if (which < PLT_W_EMB || which > PLT_W_HEAD || !off || !nelem) return fail(PLT_EINVAL, "plt_weights_offset: bad tensor id or null output");
+  const bool global = which == PLT_W_EMB || which == PLT_W_NORM_F || which == PLT_W_HEAD;
+  if (which == PLT_W_HEAD && cfg->tie_embeddings) return fail(PLT_EINVAL, "plt_weights_offset: head is tied to the embedding");
+  if (!global && (layer < 0 || layer >= cfg->n_layers)) return fail(PLT_EINVAL, "plt_weights_offset: layer out of range");
+  *off = (size_t)-1;
+  blob_walk(cfg, global ? -1 : layer, which, off, nelem);
+  if (*off == (size_t)-1) return fail(PLT_EINVAL, "plt_weights_offset: tensor not found");
+  return PLT_OK;
+}
+
+extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t nbytes, void* hip_stream,
+                        plt_model** out) {
+  const char* why;
+  if (!out) return fail(PLT_EINVAL, "plt_init: null output pointer");
+  *out = nullptr;
+  if (!cfg_valid(cfg, &why)) return fail(PLT_EINVAL, "plt_init: %s", why);
+  if (!dev_weights) return fail(PLT_EINVAL, "plt_init: null weight blob");
+  const size_t need = blob_walk(cfg, -2, -1, nullptr, nullptr);
+  if (nbytes < need) return fail(PLT_ENOMEM, "plt_init: weight blob has %zu bytes, layout needs %zu", nbytes, need);
+  if (((uintptr_t)dev_weights) & 255) return fail(PLT_EINVAL, "plt_init: weight blob must be 256-byte aligned");
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  plt_model* m = new (std::nothrow) plt_model();
+  if (!m) return fail(PLT_ENOMEM, "plt_init: out of host memory");
+  m->cfg = *cfg; m->stream = (hipStream_t)hip_stream; m->blob = (const char*)dev_weights;
+  m->es = cfg->dtype == PLT_BF16 ? 2 : 4;
+  auto at = [&](int layer, int which) -> const void* {
+    size_t off = 0, n = 0; blob_walk(cfg, layer, which, &off, &n); return m->blob + off;
+  };
+  m->emb = at(-1, PLT_W_EMB);
+  m->norm_f = (const float*)at(-1, PLT_W_NORM_F);
+  m->head = cfg->tie_embeddings ? m->emb : at(-1, PLT_W_HEAD);
+  m->layers.resize(cfg->n_layers);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    LayerW& w = m->layers[l];
+    w.norm1 = (const float*)at(l, PLT_W_NORM1); w.wqkv = at(l, PLT_W_WQKV);
+    w.gate_w = (const float*)at(l, PLT_W_GATE_W); w.gate_b = (const float*)at(l, PLT_W_GATE_B);
+    w.wo = at(l, PLT_W_WO); w.norm2 = (const float*)at(l, PLT_W_NORM2);
+    w.wgu = at(l, PLT_W_WGU); w.wdown = at(l, PLT_W_WDOWN);
+  }
+  *out = m;
+  return PLT_OK;
+}
+
+extern "C" void plt_free(plt_model* m) { delete m; }
+
+// ------------------------------------------------------------------------------ KV layout
+static bool is_clp(const plt_config& c) { return c.mode == PLT_MODE_CLP; }
+static int n_caches_of(const plt_config& c) { return is_clp(c) ? 1 : c.n_loops; }
+static int n_rings_of(const plt_config& c) { return is_clp(c) ? c.n_loops - 1 : 0; }
+
+extern "C" size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx) {
+  if (!m || batch < 1 || max_ctx < 1) { fail(PLT_EINVAL, "plt_kv_bytes: bad argument"); return 0; }
+  const plt_config& c = m->cfg;
+  const size_t share = (size_t)batch * c.n_kv_heads * pad32(max_ctx) * c.head_dim;
+  const size_t ring = (size_t)batch * n_rings_of(c) * c.n_kv_heads * pad32(c.window > 0 ? c.window : 1) * c.head_dim;
+  return align256(2 * share * c.n_layers * n_caches_of(c) * m->es) + align256(2 * ring * c.n_layers * m->es);
+}
+
+extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_t n_ctx) {
+  if (!m || batch < 1 || n_ctx < 0) { fail(PLT_EINVAL, "plt_kv_logical_bytes: bad argument"); return 0; }
+  const plt_config& c = m->cfg;
+  const size_t per = (size_t)2 * c.n_layers * c.n_kv_heads * c.head_dim * m->es * batch;
+  if (is_clp(c)) return per * ((size_t)n_ctx + (size_t)(c.n_loops - 1) * c.window);
+  return per * (size_t)c.n_loops * n_ctx;
+}
+
+static void kv_release(plt_kv* kv) {
+  if (!kv) return;
+  void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch};
+  for (void* p : ptrs) if (p) (void)hipFree(p);
+  delete kv;
+}
+
+extern "C" void plt_kv_free(plt_kv* kv) { kv_release(kv); }
+
+static size_t gemm_out_need(const plt_config& c, int M, int N, int K) {
+  const int S = c.dtype == PLT_BF16 ? gemm_bf16_splits(M, N, K) : 1;
+  return (size_t)S * M * N;
+}
+
+extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* dev_buf, size_t nbytes,
+                            plt_kv** out) {
+  if (!out) return fail(PLT_EINVAL, "plt_kv_alloc: null output pointer");
+  *out = nullptr;
+  if (!m || batch < 1 || max_ctx < 1 || !dev_buf) return fail(PLT_EINVAL, "plt_kv_alloc: bad argument");
+  if (((uintptr_t)dev_buf) & 255) return fail(PLT_EINVAL, "plt_kv_alloc: buffer must be 256-byte aligned");
+  const size_t need = plt_kv_bytes(m, batch, max_ctx);
+  if (nbytes < need) return fail(PLT_ENOMEM, "plt_kv_alloc: buffer has %zu bytes, layout needs %zu", nbytes, need);
+  const plt_config& c = m->cfg;
+  if ((long)batch * c.n_loops > 60000) return fail(PLT_EINVAL, "plt_kv_alloc: batch * n_loops too large");
+  plt_kv* kv = new (std::nothrow) plt_kv();
+  if (!kv) return fail(PLT_ENOMEM, "plt_kv_alloc: out of host memory");
+  kv->m = m; kv->B = batch; kv->max_ctx = max_ctx; kv->n_pad = pad32(max_ctx);
+  kv->w_pad = pad32(c.window > 0 ? c.window : 1);
+  kv->n_caches = n_caches_of(c); kv->n_rings = n_rings_of(c);
+  kv->buf = (char*)dev_buf;
+  kv->share_elems = (size_t)batch * c.n_kv_heads * kv->n_pad * c.head_dim;
+  kv->ring_elems = (size_t)batch * kv->n_rings * c.n_kv_heads * kv->w_pad * c.head_dim;
+  kv->ring_base = align256(2 * kv->share_elems * c.n_layers * kv->n_caches * m->es);
+  kv->pos = 0; kv->started = false;
+  // cleared so that padded / not-yet-written slots hold finite values (masked keys multiply
+  // their value rows by zero weights, which must not meet NaN bit patterns)
+  hipError_t e = hipMemsetAsync(dev_buf, 0, need, m->stream);
+  const int L = c.n_loops, R = is_clp(c) ? batch * L : batch;
+  const int d = c.d_model, Hq = c.n_heads, Hkv = c.n_kv_heads, D = c.head_dim, F = c.ffn_hidden, V = c.vocab;
+  const int Nqkv = (Hq + 2 * Hkv) * D;
+  size_t go = gemm_out_need(c, R, Nqkv, d);
+  size_t t;
+  if ((t = gemm_out_need(c, R, d, Hq * D)) > go) go = t;
+  if ((t = gemm_out_need(c, R, 2 * F, d)) > go) go = t;
+  if ((t = gemm_out_need(c, R, d, F)) > go) go = t;
+  if ((t = gemm_out_need(c, batch, V, d)) > go) go = t;
+  kv->gout_elems = go;
+  kv->attn_scratch_bytes = attn_mfma_scratch_bytes(batch, is_clp(c) ? L : 1, Hq, Hkv, D);
+  auto dmalloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 256); };
+  dmalloc((void**)&kv->x, (size_t)R * d * 4);
+  dmalloc(&kv->a, (size_t)R * d * m->es);
+  dmalloc((void**)&kv->gout, go * 4);
+  dmalloc(&kv->q, (size_t)R * Hq * D * m->es);
+  dmalloc((void**)&kv->z, (size_t)R * Hq * 4);
+  dmalloc(&kv->y, (size_t)R * Hq * D * m->es);
+  dmalloc(&kv->act, (size_t)R * F * m->es);
+  dmalloc((void**)&kv->carry, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4);
+  dmalloc((void**)&kv->pos_dev, (size_t)batch * 4);
+  dmalloc(&kv->attn_scratch, kv->attn_scratch_bytes);
+  if (e == hipSuccess) e = hipMemsetAsync(kv->attn_scratch, 0, kv->attn_scratch_bytes, m->stream);
+  if (e == hipSuccess) e = hipMemsetAsync(kv->carry, 0, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4, m->stream);
+  if (e == hipSuccess) e = hipMemsetAsync(kv->x, 0, (size_t)R * d * 4, m->stream);
+  if (e != hipSuccess) {
+    kv_release(kv);
+    return fail(e == hipErrorOutOfMemory ? PLT_ENOMEM : PLT_EHIP, "plt_kv_alloc: %s", hipGetErrorString(e));
+  }
+  *out = kv;
+  return PLT_OK;
+}
+
+extern "C" int32_t plt_kv_position(const plt_kv* kv) {
+  if (!kv) return fail(PLT_EINVAL, "plt_kv_position: null kv");
+  return kv->pos;
+}
+
+static KvView kv_view(const plt_kv* kv, int layer, int cache) {
+  const plt_model* m = kv->m;
+  const plt_config& c = m->cfg;
+  KvView v;
+  const size_t es = m->es;
+  char* sb = kv->buf + ((size_t)cache * c.n_layers + layer) * 2 * kv->share_elems * es;
+  v.k_share = sb; v.v_share = sb + kv->share_elems * es;
+  if (kv->n_rings > 0) {
+    char* rb = kv->buf + kv->ring_base + (size_t)layer * 2 * kv->ring_elems * es;
+    v.k_ring = rb; v.v_ring = rb + kv->ring_elems * es;
+  } else { v.k_ring = nullptr; v.v_ring = nullptr; }
+  v.k_loc = nullptr; v.v_loc = nullptr;
+  v.n_pad = kv->n_pad; v.w_pad = kv->w_pad; v.n_pad_loc = 0;
+  v.w = c.window > 0 ? c.window : 1; v.n_rings = kv->n_rings; v.b0 = 0;
+  return v;
+}
+
+// ------------------------------------------------------------------------------ scheduler
+struct Work {            // activation buffers one pass of the stack runs on
+  float* x; void* a; float* gout; void* q; float* z; void* y; void* act;
+};
+
+static int run_gemm(const plt_model* m, const void* a, const void* w, float* out, int M, int N, int K) {
+  if (m->cfg.dtype == PLT_BF16) {
+    const int S = gemm_bf16_splits(M, N, K);
+    launch_gemm_bf16(m->stream, (const bf16_t*)a, (const bf16_t*)w, out, M, N, K, S);
+    return S;
+  }
+  launch_gemm_f32(m->stream, (const float*)a, (const float*)w, out, M, N, K);
+  return 1;
+}
+
+template <typename T>
+static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap rm, int cache, bool plain,
+                       KvView loc /*prefill local K/V + b0*/, int Bc, int n_prefill, int attn_L,
+                       const float* next_gain /*norm applied after the last layer, or null*/) {
+  // Runs all layers of block f on the R rows in wk.x (a = RMSNorm(x) is already in wk.a).
+  const plt_config& c = m->cfg;
+  hipStream_t s = m->stream;
+  const int d = c.d_model, Hq = c.n_heads, Hkv = c.n_kv_heads, D = c.head_dim, F = c.ffn_hidden;
+  const int Nqkv = (Hq + 2 * Hkv) * D;
+  Dims dm{rm.prefill ? Bc : kv->B, attn_L, Hq, Hkv, D, d, F, c.vocab};
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerW& w = m->layers[l];
+    KvView v = kv_view(kv, l, cache);
+    v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
+    int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d);                               // Alg. 3 l.1
+    launch_rope_append<T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
+                          dm, c.rope_theta, plain ? 1 : 0);
+    if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
+      if (rm.prefill) {
+        launch_attn_prefill_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, Bc, n_prefill,
+                                 rm.loop_fixed, dm, plain ? 1 : 0);
+      } else {
+        const int G = Hq / Hkv;
+        const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1);
+        launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, kv->pos_dev, 0, 0, dm,
+                                plain ? 1 : 0, kv->attn_scratch, ns);
+      }
+    } else {
+      launch_attn_f32(s, (const float*)wk.q, wk.z, (float*)wk.y, v, rm, R, dm, plain ? 1 : 0);
+    }
+    S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D);                                     // Alg. 3 l.6
+    launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
+    S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d);
+    launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
+    S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F);
+    const float* gain = l + 1 < c.n_layers ? m->layers[l + 1].norm1 : next_gain;
+    launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, gain, c.norm_eps,
+                         gain ? (T*)wk.a : (T*)nullptr, R, d);
+  }
+}
+
+template <typename T>
+static void head_and_argmax(plt_model* m, const Work& wk, int rows, int row_stride, int row_off,
+                            int32_t* dev_next, float* dev_logits) {
+  const plt_config& c = m->cfg;
+  launch_resid_norm<T>(m->stream, wk.x, row_stride, row_off, nullptr, 0, 0, m->norm_f, c.norm_eps, (T*)wk.a,
+                       rows, c.d_model);
+  const int S = run_gemm(m, wk.a, m->head, wk.gout, rows, c.vocab, c.d_model);
+  launch_argmax(m->stream, wk.gout, S, (size_t)rows * c.vocab, dev_logits, dev_next, rows, c.vocab);
+}
+
+template <typename T>
+static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t* dev_next,
+                         float* dev_logits) {
+  const plt_config& c = m->cfg;
+  hipStream_t s = m->stream;
+  const int B = kv->B, L = c.n_loops, d = c.d_model;
+  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act};
+  KvView none{}; none.b0 = 0;
+  if (is_clp(c)) {
+    // Alg. 1 l.5-7: rows B_0 = e, B_l = e + H^l[p-1]; the L rows of a sequence run as one pass
+    const int R = B * L;
+    RowMap rm{0, L, 0, kv->pos_dev};
+    launch_embed<T>(s, dev_tokens, (const T*)m->emb, kv->carry, nullptr, kv->x, R, d, rm, L, 1, c.vocab);
+    launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, R, d);
+    stack_pass<T>(m, kv, wk, R, rm, 0, false, none, 0, 0, L, nullptr);
+    launch_carry_update(s, kv->x, kv->carry, B, L, d);
+    head_and_argmax<T>(m, wk, B, L, L - 1, dev_next, dev_logits);                       // Alg. 1 l.8-9
+  } else {
+    // Eq. (1): L serial passes of B rows, loop l on its own cache l
+    RowMap rm{0, 1, 0, kv->pos_dev};
+    launch_embed<T>(s, dev_tokens, (const T*)m->emb, nullptr, nullptr, kv->x, B, d, rm, 1, 0, c.vocab);
+    launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, B, d);
+    for (int l = 0; l < L; ++l)
+      stack_pass<T>(m, kv, wk, B, rm, l, true, none, 0, 0, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
+    head_and_argmax<T>(m, wk, B, 1, 0, dev_next, dev_logits);
+  }
+  launch_pos_set(s, kv->pos_dev, B, 1, 1);
+  return PLT_OK;
+}
+
+extern "C" int plt_decode_step(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t* dev_next,
+                               float* dev_logits) {
+  if (!m || !kv || kv->m != m || !dev_tokens || !dev_next) return fail(PLT_EINVAL, "plt_decode_step: bad argument");
+  if (!kv->started) return fail(PLT_ESTATE, "plt_decode_step: plt_prefill (or plt_kv_set_position) must come first");
+  if (kv->pos >= kv->max_ctx) return fail(PLT_ECTXFULL, "plt_decode_step: context full (%d positions)", kv->max_ctx);
+  int rc = m->cfg.dtype == PLT_BF16 ? decode_step_t<bf16_t>(m, kv, dev_tokens, dev_next, dev_logits)
+                                    : decode_step_t<float>(m, kv, dev_tokens, dev_next, dev_logits);
+  if (rc != PLT_OK) return rc;
+  HIP_TRY(hipGetLastError());
+  kv->pos += 1;
+  return PLT_OK;
+}
+
+// ------------------------------------------------------------------------------ prefill
+static const int PREFILL_ROWS = 16384;   // activation rows per chunk of whole sequences
+
+template <typename T>
+static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n, int32_t* dev_next,
+                     float* dev_logits) {
+  const plt_config& c = m->cfg;
+  hipStream_t s = m->stream;
+  const int B = kv->B, L = c.n_loops, d = c.d_model, Hq = c.n_heads, Hkv = c.n_kv_heads, D = c.head_dim,
+            F = c.ffn_hidden, V = c.vocab, es = m->es;
+  const int Nqkv = (Hq + 2 * Hkv) * D;
+  int Bc = PREFILL_ROWS / n; if (Bc < 1) Bc = 1; if (Bc > B) Bc = B;
+  const int Rc = Bc * n;
+  if (Rc > 60000) return fail(PLT_EINVAL, "plt_prefill: prompt too long (%d positions; limit 60000)", n);
+  const int n_pad_loc = pad32(n);
+  size_t go = gemm_out_need(c, Rc, Nqkv, d), t;
+  if ((t = gemm_out_need(c, Rc, d, Hq * D)) > go) go = t;
+  if ((t = gemm_out_need(c, Rc, 2 * F, d)) > go) go = t;
+  if ((t = gemm_out_need(c, Rc, d, F)) > go) go = t;
+  if ((t = gemm_out_need(c, Bc, V, d)) > go) go = t;
+  // one temporary workspace, carved into the chunk's activation buffers
+  size_t off = 0;
+  auto carve = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * es),
+               o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
+               o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * F * es),
+               o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * es), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * es);
+  char* ws = nullptr;
+  hipError_t e = hipMalloc((void**)&ws, off);
+  if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
+  (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * es), s);
+  Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act};
+  float* hprev = (float*)(ws + o_h);
+  for (int b0 = 0; b0 < B; b0 += Bc) {
+    const int bc = b0 + Bc <= B ? Bc : B - b0;
+    const int R = bc * n;
+    const int32_t* toks = dev_tokens + (size_t)b0 * n;
+    KvView loc{}; loc.k_loc = ws + o_kl; loc.v_loc = ws + o_vl; loc.n_pad_loc = n_pad_loc; loc.b0 = b0;
+    for (int l = 0; l < L; ++l) {
+      RowMap rm{1, n, is_clp(c) ? l : 0, nullptr};
+      if (is_clp(c)) {
+        // Alg. 2 l.1-2 (l = 0) and l.4-6 (l >= 1): B = E + shift_right(H^(l))
+        launch_embed<T>(s, toks, (const T*)m->emb, nullptr, hprev, wk.x, R, d, rm, L, 1, c.vocab);
+        launch_resid_norm<T>(s, wk.x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)wk.a, R, d);
+        stack_pass<T>(m, kv, wk, R, rm, 0, false, loc, bc, n, L, nullptr);
+        if (l + 1 < L) {
+          launch_prefill_carry(s, wk.x, kv->carry, b0, bc, n, L, l, d);
+          launch_shift_copy(s, wk.x, hprev, (size_t)R * d);
+        }
+      } else {
+        if (l == 0) {
+          launch_embed<T>(s, toks, (const T*)m->emb, nullptr, nullptr, wk.x, R, d, rm, 1, 0, c.vocab);
+          launch_resid_norm<T>(s, wk.x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)wk.a, R, d);
+        }
+        stack_pass<T>(m, kv, wk, R, rm, l, true, loc, bc, n, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
+      }
+    }
+    head_and_argmax<T>(m, wk, bc, n, n - 1, dev_next + b0, dev_logits ? dev_logits + (size_t)b0 * V : nullptr);
+  }
+  launch_pos_set(s, kv->pos_dev, B, n, 0);
+  e = hipStreamSynchronize(s);
+  (void)hipFree(ws);
+  if (e != hipSuccess) return fail(PLT_EHIP, "plt_prefill: %s", hipGetErrorString(e));
+  return PLT_OK;
+}
+
+extern "C" int plt_prefill(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t n, int32_t* dev_next,
+                           float* dev_logits) {
+  if (!m || !kv || kv->m != m || !dev_tokens || !dev_next) return fail(PLT_EINVAL, "plt_prefill: bad argument");
+  if (n < 1) return fail(PLT_EINVAL, "plt_prefill: empty prompt");
+  if (n > kv->max_ctx) return fail(PLT_ECTXFULL, "plt_prefill: prompt of %d exceeds max_ctx %d", n, kv->max_ctx);
+  int rc = m->cfg.dtype == PLT_BF16 ? prefill_t<bf16_t>(m, kv, dev_tokens, n, dev_next, dev_logits)
+                                    : prefill_t<float>(m, kv, dev_tokens, n, dev_next, dev_logits);
+  if (rc != PLT_OK) return rc;
+  HIP_TRY(hipGetLastError());
+  kv->pos = n; kv->started = true;
+  return PLT_OK;
+}
+
+// ------------------------------------------------------------------------------ hooks
+extern "C" int plt_kv_set_position(plt_kv* kv, int32_t pos) {
+  if (!kv || pos < 0 || pos > kv->max_ctx) return fail(PLT_EINVAL, "plt_kv_set_position: bad argument");
+  launch_pos_set(kv->m->stream, kv->pos_dev, kv->B, pos, 0);
+  HIP_TRY(hipGetLastError());
+  kv->pos = pos; kv->started = true;
+  return PLT_OK;
+}
+
+extern "C" size_t plt_kv_export_bytes(const plt_kv* kv, int32_t n) {
+  if (!kv || n < 0 || n > kv->max_ctx) { fail(PLT_EINVAL, "plt_kv_export_bytes: bad argument"); return 0; }
+  const plt_config& c = kv->m->cfg;
+  const size_t w = c.window > 0 ? c.window : 1;
+  return ((size_t)2 * c.n_kv_heads * n * c.head_dim + (size_t)2 * kv->n_rings * c.n_kv_heads * w * c.head_dim) * kv->m->es;
+}
+
+template <typename T>
+static int kv_xfer(plt_kv* kv, int seq, int layer, int cache, int n, char* host, bool to_host) {
+  plt_model* m = kv->m;
+  const plt_config& c = m->cfg;
+  hipStream_t s = m->stream;
+  const int Hkv = c.n_kv_heads, D = c.head_dim, w = c.window > 0 ? c.window : 1, nr = kv->n_rings;
+  const size_t total = plt_kv_export_bytes(kv, n);
+  T* tmp = nullptr;
+  HIP_TRY(hipMalloc((void**)&tmp, total ? total : 256));
+  KvView v = kv_view(kv, layer, cache);
+  T* ks = (T*)v.k_share + (size_t)seq * Hkv * kv->n_pad * D;
+  T* vs = (T*)v.v_share + (size_t)seq * Hkv * kv->n_pad * D;
+  T* t_ks = tmp; T* t_vs = tmp + (size_t)Hkv * n * D;
+  T* t_kr = t_vs + (size_t)Hkv * n * D; T* t_vr = t_kr + (size_t)nr * Hkv * w * D;
+  T* kr = nr ? (T*)v.k_ring + (size_t)seq * nr * Hkv * kv->w_pad * D : nullptr;
+  T* vr = nr ? (T*)v.v_ring + (size_t)seq * nr * Hkv * kv->w_pad * D : nullptr;
+  hipError_t e = hipSuccess;
+  if (to_host) {
+    for (int h = 0; h < Hkv && e == hipSuccess && n > 0; ++h)
+      e = hipMemcpyAsync(t_ks + (size_t)h * n * D, ks + (size_t)h * kv->n_pad * D, (size_t)n * D * sizeof(T), hipMemcpyDeviceToDevice, s);
+    if (n > 0) launch_unpack_v<T>(s, vs, t_vs, Hkv, n, kv->n_pad, D);
+    for (int h = 0; h < nr * Hkv && e == hipSuccess; ++h)
+      e = hipMemcpyAsync(t_kr + (size_t)h * w * D, kr + (size_t)h * kv->w_pad * D, (size_t)w * D * sizeof(T), hipMemcpyDeviceToDevice, s);
+    if (nr) launch_unpack_v<T>(s, vr, t_vr, nr * Hkv, w, kv->w_pad, D);
+    if (e == hipSuccess) e = hipMemcpyAsync(host, tmp, total, hipMemcpyDeviceToHost, s);
+  } else {
+    e = hipMemcpyAsync(tmp, host, total, hipMemcpyHostToDevice, s);
+    if (e == hipSuccess && n > 0) {
+      // pack into the first pad32(n) rows of each stream, stream stride n_pad rows
+      for (int h = 0; h < Hkv && e == hipSuccess; ++h)
+        e = hipMemcpyAsync(ks + (size_t)h * kv->n_pad * D, t_ks + (size_t)h * n * D, (size_t)n * D * sizeof(T), hipMemcpyDeviceToDevice, s);
+      for (int h = 0; h < Hkv; ++h)
+        launch_pack_v<T>(s, t_vs + (size_t)h * n * D, vs + (size_t)h * kv->n_pad * D, 1, n, pad32(n), D);
+    }
+    for (int h = 0; h < nr * Hkv && e == hipSuccess; ++h)
+      e = hipMemcpyAsync(kr + (size_t)h * kv->w_pad * D, t_kr + (size_t)h * w * D, (size_t)w * D * sizeof(T), hipMemcpyDeviceToDevice, s);
+    if (nr && e == hipSuccess) launch_pack_v<T>(s, t_vr, vr, nr * Hkv, w, kv->w_pad, D);
+  }
+  hipError_t e2 = hipStreamSynchronize(s);
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(PLT_EHIP, "kv transfer: %s", hipGetErrorString(e));
+  if (e2 != hipSuccess) return fail(PLT_EHIP, "kv transfer: %s", hipGetErrorString(e2));
+  return PLT_OK;
+}
+
+static int kv_xfer_check(plt_kv* kv, int seq, int layer, int cache, int n, const void* host, size_t nbytes) {
+  if (!kv || !host) return fail(PLT_EINVAL, "kv export/import: null argument");
+  if (seq < 0 || seq >= kv->B || layer < 0 || layer >= kv->m->cfg.n_layers || cache < 0 || cache >= kv->n_caches ||
+      n < 0 || n > kv->max_ctx) return fail(PLT_EINVAL, "kv export/import: index out of range");
+  if (nbytes != plt_kv_export_bytes(kv, n)) return fail(PLT_EINVAL, "kv export/import: host buffer must have %zu bytes", plt_kv_export_bytes(kv, n));
+  return PLT_OK;
+}
+
+extern "C" int plt_kv_export(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n, void* host_dst,
+                             size_t host_nbytes) {
+  int rc = kv_xfer_check(kv, seq, layer, cache, n, host_dst, host_nbytes);
+  if (rc) return rc;
+  return kv->m->es == 2 ? kv_xfer<bf16_t>(kv, seq, layer, cache, n, (char*)host_dst, true)
+                        : kv_xfer<float>(kv, seq, layer, cache, n, (char*)host_dst, true);
+}
+extern "C" int plt_kv_import(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n,
+                             const void* host_src, size_t host_nbytes) {
+  int rc = kv_xfer_check(kv, seq, layer, cache, n, host_src, host_nbytes);
+  if (rc) return rc;
+  return kv->m->es == 2 ? kv_xfer<bf16_t>(kv, seq, layer, cache, n, (char*)host_src, false)
+                        : kv_xfer<float>(kv, seq, layer, cache, n, (char*)host_src, false);
+}
+
+static int copy_sync(plt_kv* kv, void* dst, const void* src, size_t bytes, hipMemcpyKind kind) {
+  HIP_TRY(hipMemcpyAsync(dst, src, bytes, kind, kv->m->stream));
+  HIP_TRY(hipStreamSynchronize(kv->m->stream));
+  return PLT_OK;
+}
+extern "C" int plt_get_carry(plt_kv* kv, float* host_dst, size_t host_nbytes) {
+  if (!kv || !host_dst) return fail(PLT_EINVAL, "plt_get_carry: null argument");
+  const size_t need = (size_t)kv->B * (kv->m->cfg.n_loops - 1) * kv->m->cfg.d_model * 4;
+  if (!is_clp(kv->m->cfg) || host_nbytes != need) return fail(PLT_EINVAL, "plt_get_carry: needs CLP mode and %zu bytes", need);
+  return need ? copy_sync(kv, host_dst, kv->carry, need, hipMemcpyDeviceToHost) : PLT_OK;
+}
+extern "C" int plt_set_carry(plt_kv* kv, const float* host_src, size_t host_nbytes) {
+  if (!kv || !host_src) return fail(PLT_EINVAL, "plt_set_carry: null argument");
+  const size_t need = (size_t)kv->B * (kv->m->cfg.n_loops - 1) * kv->m->cfg.d_model * 4;
+  if (!is_clp(kv->m->cfg) || host_nbytes != need) return fail(PLT_EINVAL, "plt_set_carry: needs CLP mode and %zu bytes", need);
+  return need ? copy_sync(kv, kv->carry, host_src, need, hipMemcpyHostToDevice) : PLT_OK;
+}
+extern "C" int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes) {
+  if (!kv || !host_dst) return fail(PLT_EINVAL, "plt_get_hidden: null argument");
+  const int rows = is_clp(kv->m->cfg) ? kv->B * kv->m->cfg.n_loops : kv->B;
+  const size_t need = (size_t)rows * kv->m->cfg.d_model * 4;
+  if (host_nbytes != need) return fail(PLT_EINVAL, "plt_get_hidden: host buffer must have %zu bytes", need);
+  return copy_sync(kv, host_dst, kv->x, need, hipMemcpyDeviceToHost);
+}
+
+// ---- kernel-only hooks ----
+extern "C" int32_t plt_attn_pad32(int32_t n) { return pad32(n); }
+
+extern "C" size_t plt_attn_scratch_bytes(int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D) {
+  if (B < 1 || L < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || (D != 64 && D != 128)) { fail(PLT_EINVAL, "plt_attn_scratch_bytes: bad shape"); return 0; }
+  size_t s = attn_mfma_scratch_bytes(B, L, Hq, Hkv, D);
+  size_t p = align256((size_t)B * 4);
+  return s > p ? s : p;
+}
+
+extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
+                               int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring, const void* q,
+                               const void* k_share, const void* v_share, const void* k_ring, const void* v_ring,
+                               const float* z, void* y, void* scratch, size_t scratch_bytes, int32_t n_splits,
+                               void* hip_stream) {
+  if (dtype != PLT_F32 && dtype != PLT_BF16) return fail(PLT_EINVAL, "plt_attn_decode: unknown dtype");
+  if (B < 1 || L < 1 || L > 16 || Hq < 1 || Hkv < 1 || Hq % Hkv || (D != 64 && D != 128))
+    return fail(PLT_EINVAL, "plt_attn_decode: bad shape");
+  if (n_ctx < 1 || n_ctx > n_alloc) return fail(PLT_EINVAL, "plt_attn_decode: need 1 <= n_ctx <= n_alloc");
+  if (L > 1 && (w < 1 || n_ring < 1 || n_ring > w)) return fail(PLT_EINVAL, "plt_attn_decode: need 1 <= n_ring <= w");
+  if (!q || !k_share || !v_share || !y || !scratch || (L > 1 && (!k_ring || !v_ring || !z)))
+    return fail(PLT_EINVAL, "plt_attn_decode: null pointer");
+  if (scratch_bytes < plt_attn_scratch_bytes(B, L, Hq, Hkv, D)) return fail(PLT_ENOMEM, "plt_attn_decode: scratch too small");
+  if ((long)B * L > 60000) return fail(PLT_EINVAL, "plt_attn_decode: B * L too large");
+  hipStream_t s = (hipStream_t)hip_stream;
+  KvView v{};
+  v.k_share = (void*)k_share; v.v_share = (void*)v_share; v.k_ring = (void*)k_ring; v.v_ring = (void*)v_ring;
+  v.n_pad = pad32(n_alloc); v.w_pad = pad32(w > 0 ? w : 1); v.w = w > 0 ? w : 1; v.n_rings = L - 1; v.b0 = 0;
+  Dims dm{B, L, Hq, Hkv, D, 0, 0, 0};
+  if (dtype == PLT_BF16) {
+    if (n_splits <= 0) n_splits = attn_mfma_default_splits(B, Hkv, L, Hq / Hkv, n_ctx);
+    launch_attn_decode_mfma(s, (const bf16_t*)q, z, (bf16_t*)y, v, nullptr, n_ctx, L > 1 ? n_ring : 0, dm, 0,
+                            scratch, n_splits);
+  } else {
+    if (L > 1 && n_ring != (n_ctx < w ? n_ctx : w))
+      return fail(PLT_EINVAL, "plt_attn_decode: float path needs n_ring == min(n_ctx, w)");
+    launch_pos_set(s, (int32_t*)scratch, B, n_ctx - 1, 0);
+    RowMap rm{0, L, 0, (const int32_t*)scratch};
+    launch_attn_f32(s, (const float*)q, z, (float*)y, v, rm, B * L, dm, 0);
+  }
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
+extern "C" int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* src, void* dst,
+                               void* hip_stream) {
+  if ((dtype != PLT_F32 && dtype != PLT_BF16) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)
+    return fail(PLT_EINVAL, "plt_attn_pack_k: bad argument");
+  if (dtype == PLT_BF16) launch_pack_k<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
+  else launch_pack_k<float>((hipStream_t)hip_stream, (const float*)src, (float*)dst, S, n, pad32(n), D);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+extern "C" int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* src, void* dst,
+                               void* hip_stream) {
+  if ((dtype != PLT_F32 && dtype != PLT_BF16) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)
+    return fail(PLT_EINVAL, "plt_attn_pack_v: bad argument");
+  if (dtype == PLT_BF16) launch_pack_v<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
+  else launch_pack_v<float>((hipStream_t)hip_stream, (const float*)src, (float*)dst, S, n, pad32(n), D);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
+__global__ void k_sum_slabs(const float* __restrict__ p, float* __restrict__ c, int S, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float v = 0.f;
+  for (int s = 0; s < S; ++s) v += p[(size_t)s * n + i];
+  c[i] = v;
+}
+
+extern "C" size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || N < 1 || K < 1) { fail(PLT_EINVAL, "plt_gemm_scratch_bytes: bad shape"); return 0; }
+  return align256((size_t)gemm_bf16_splits(M, N, K) * M * N * 4);
+}
+
+extern "C" int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* a, const void* w, float* c,
+                        void* scratch, size_t scratch_bytes, void* hip_stream) {
+  if ((dtype != PLT_F32 && dtype != PLT_BF16) || M < 1 || N < 1 || K < 1 || !a || !w || !c)
+    return fail(PLT_EINVAL, "plt_gemm: bad argument");
+  if ((long)M > 128L * 65535 || (long)N > 64L * 2147483647L) return fail(PLT_EINVAL, "plt_gemm: too large");
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (dtype == PLT_F32) {
+    launch_gemm_f32(s, (const float*)a, (const float*)w, c, M, N, K);
+  } else {
+    if (K % 64) return fail(PLT_EINVAL, "plt_gemm: bf16 needs K to be a multiple of 64");
+    const int S = gemm_bf16_splits(M, N, K);
+    if (S == 1) {
+      launch_gemm_bf16(s, (const bf16_t*)a, (const bf16_t*)w, c, M, N, K, 1);
+    } else {
+      if (!scratch || scratch_bytes < plt_gemm_scratch_bytes(M, N, K)) return fail(PLT_ENOMEM, "plt_gemm: scratch too small");
+      launch_gemm_bf16(s, (const bf16_t*)a, (const bf16_t*)w, (float*)scratch, M, N, K, S);
+      const size_t n = (size_t)M * N;
+      hipLaunchKernelGGL(k_sum_slabs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)scratch, c, S, n);
+    }
+  }
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}

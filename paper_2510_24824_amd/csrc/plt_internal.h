@@ -1,0 +1,115 @@
+// Internal declarations shared by the translation units of libplt.so (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/plt.h"
+
+namespace plt {
+
+typedef uint16_t bf16_t;  // storage only; arithmetic is always float
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v) {
+  union { uint32_t u; float f; } c; c.u = ((uint32_t)v) << 16; return c.f;
+}
+// round to nearest, ties to even (inputs are finite in this library)
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+  union { uint32_t u; float f; } c; c.f = f;
+  uint32_t lsb = (c.u >> 16) & 1u;
+  return (bf16_t)((c.u + 0x7FFFu + lsb) >> 16);
+}
+template <typename T> __device__ inline float ld(const T* p);
+template <> __device__ inline float ld<float>(const float* p) { return *p; }
+template <> __device__ inline float ld<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
+template <typename T> __device__ inline void st(T* p, float v);
+template <> __device__ inline void st<float>(float* p, float v) { *p = v; }
+template <> __device__ inline void st<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+
+inline int pad32(int n) { return (n + 31) & ~31; }
+
+// Index of element (pos, d) inside one V stream stored as blocks of 32 positions:
+// [n_pad/32][D][32], position fastest.
+__host__ __device__ inline size_t vblk_index(int pos, int d, int D) {
+  return (size_t)(pos >> 5) * (size_t)(D * 32) + (size_t)d * 32 + (size_t)(pos & 31);
+}
+
+// How a row of the activation matrices maps to (sequence, position, loop stage).
+//  decode : rows_per_seq = L, row = b*L + l, position = pos[b]
+//  prefill: rows_per_seq = n, row = b*n + p, loop stage = loop_fixed
+struct RowMap {
+  int prefill;        // 0 decode, 1 prefill
+  int rows_per_seq;   // L (decode) or n (prefill)
+  int loop_fixed;     // prefill: 0-based loop stage of every row
+  const int32_t* pos; // decode: device array [B] of the position being consumed
+};
+__device__ inline void row_decode(const RowMap& rm, int r, int& b, int& p, int& l) {
+  b = r / rm.rows_per_seq;
+  int i = r - b * rm.rows_per_seq;
+  if (rm.prefill) { p = i; l = rm.loop_fixed; } else { p = rm.pos[b]; l = i; }
+}
+
+// Geometry of one layer's caches as the attention and append kernels see them.
+struct KvView {
+  void* k_share;   // [B, Hkv, n_pad, D]
+  void* v_share;   // [B, Hkv, n_pad/32, D, 32]
+  void* k_ring;    // [B, L-1, Hkv, w_pad, D]        (null when L == 1 / vanilla mode)
+  void* v_ring;    // [B, L-1, Hkv, w_pad/32, D, 32]
+  void* k_loc;     // prefill only: this loop's own K for the chunk [Bc, Hkv, n_pad_loc, D]
+  void* v_loc;     // prefill only: [Bc, Hkv, n_pad_loc/32, D, 32]
+  int n_pad, w_pad, n_pad_loc;
+  int w;           // window
+  int n_rings;     // L-1
+  int b0;          // prefill: first sequence of the chunk (share/ring are indexed by b0 + b)
+};
+
+struct Dims { int B, L, Hq, Hkv, D, d, F, V; };
+
+// ---- launchers (each checks nothing; callers validate shapes) --------------------------
+// elem_kernels.hip
+template <typename T>
+void launch_embed(hipStream_t s, const int32_t* tokens, const T* emb, const float* carry,
+                  const float* hprev, float* x, int R, int d, RowMap rm, int n_loops, int add_prev, int vocab);
+template <typename T>
+void launch_resid_norm(hipStream_t s, float* x, int x_row_stride, int x_row_off,
+                       const float* partials, int S, size_t slab, const float* gain, float eps,
+                       T* a_out, int R, int d);
+template <typename T>
+void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
+                        const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
+                        Dims dm, float theta, int first_loop_only);
+template <typename T>
+void launch_silu_mul(hipStream_t s, const float* gu, int S, size_t slab, T* act, int R, int F);
+void launch_argmax(hipStream_t s, const float* lg, int S, size_t slab, float* logits_out,
+                   int32_t* next, int B, int V);
+void launch_carry_update(hipStream_t s, const float* x, float* carry, int B, int L, int d);
+void launch_pos_set(hipStream_t s, int32_t* pos, int B, int value, int increment);
+void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n);
+template <typename T>
+void launch_pack_k(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
+template <typename T>
+void launch_pack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
+template <typename T>
+void launch_unpack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
+void launch_prefill_carry(hipStream_t s, const float* x, float* carry, int b0, int Bc, int n,
+                          int L, int l, int d);
+
+// gemm_f32.hip / gemm_mfma.hip : c[s][M][N] slabs (float) = a[M,K] * w[N,K]^T
+void launch_gemm_f32(hipStream_t s, const float* a, const float* w, float* c, int M, int N, int K);
+int gemm_bf16_splits(int M, int N, int K);
+void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N,
+                      int K, int splits);
+
+// attn_f32.hip : one wave per (row, query head), float storage
+void launch_attn_f32(hipStream_t s, const float* q, const float* z, float* y, KvView kv,
+                     RowMap rm, int R, Dims dm, int plain);
+
+// attn_mfma.hip : bf16 storage, MFMA tiles
+size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D);
+int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx);
+void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
+                             const int32_t* pos, int n_ctx_uniform, int n_ring_uniform,
+                             Dims dm, int plain, void* scratch, int n_splits);
+void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
+                              int Bc, int n, int loop, Dims dm, int plain);
+
+}  // namespace plt

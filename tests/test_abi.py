@@ -1,0 +1,84 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol include/plt.h declares,
+and its pure-host entry points (layout queries, argument validation) behave.  No GPU needed."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2510_24824_amd import binding as B, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2510_24824_amd import build
+        build.build(verbose=False)
+    return B.lib()
+
+
+def declared_functions():
+    src = open(os.path.join(ROOT, "include", "plt.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(plt_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.EXPORTS) == names          # the binding covers exactly the header
+
+
+def test_weight_layout_queries(lib):
+    cfg = B.make_config(synth.TINY, dtype=B.PLT_F32)
+    total = lib.plt_weights_bytes(C.byref(cfg))
+    s = synth.TINY
+    params = s.vocab * s.d_model + s.n_layers * (
+        2 * s.d_model + (s.n_heads + 2 * s.n_kv_heads) * s.head_dim * s.d_model + s.n_heads * s.head_dim + s.n_heads
+        + s.d_model * s.n_heads * s.head_dim + 3 * s.ffn_hidden * s.d_model) + s.d_model
+    assert 4 * params <= total <= 4 * params + 256 * (2 + 8 * s.n_layers)
+    prev_end = 0
+    for layer, which in [(0, B.PLT_W_EMB)] + [(m, t) for m in range(s.n_layers) for t in range(B.PLT_W_NORM1, B.PLT_W_WDOWN + 1)] + [(0, B.PLT_W_NORM_F)]:
+        off, n = B.weights_offset(cfg, layer, which)
+        assert off % 256 == 0 and off >= prev_end and n > 0
+        prev_end = off + 4 * n
+    assert prev_end <= total
+    with pytest.raises(B.PltError):
+        B.weights_offset(cfg, 0, B.PLT_W_HEAD)            # tied head has no tensor
+    with pytest.raises(B.PltError):
+        B.weights_offset(cfg, s.n_layers, B.PLT_W_WO)     # layer out of range
+    # bf16 halves the matrix bytes but not the float norm / gate tensors
+    cfg16 = B.make_config(synth.TINY, dtype=B.PLT_BF16)
+    assert lib.plt_weights_bytes(C.byref(cfg16)) < total
+    off16, n16 = B.weights_offset(cfg16, 1, B.PLT_W_WGU)
+    assert n16 == 2 * s.ffn_hidden * s.d_model
+
+
+@pytest.mark.parametrize("field,value", [("head_dim", 48), ("n_kv_heads", 3), ("n_loops", 0), ("dtype", 7),
+                                         ("mode", 1), ("window", 0), ("d_model", 0)])
+def test_invalid_configs_are_rejected(lib, field, value):
+    cfg = B.make_config(synth.TINY, dtype=B.PLT_F32)
+    setattr(cfg, field, value)
+    assert lib.plt_weights_bytes(C.byref(cfg)) == 0
+    assert len(lib.plt_last_error()) > 0
+    h = C.c_void_p()
+    assert lib.plt_init(C.byref(cfg), C.c_void_p(256), 1 << 30, None, C.byref(h)) == -1
+    assert not h.value
+
+
+def test_null_and_size_argument_errors(lib):
+    cfg = B.make_config(synth.TINY, dtype=B.PLT_F32)
+    h = C.c_void_p()
+    assert lib.plt_init(C.byref(cfg), None, 1 << 30, None, C.byref(h)) == -1            # null blob
+    assert lib.plt_init(C.byref(cfg), C.c_void_p(256), 16, None, C.byref(h)) == -2      # blob too small
+    assert lib.plt_init(C.byref(cfg), C.c_void_p(257), 1 << 30, None, C.byref(h)) == -1  # misaligned
+    assert lib.plt_kv_bytes(None, 1, 8) == 0
+    assert lib.plt_kv_position(None) == -1
+    assert lib.plt_decode_step(None, None, None, None, None) == -1
+    assert lib.plt_attn_scratch_bytes(1, 1, 4, 3, 64) == 0
+    assert lib.plt_attn_pad32(33) == 64 and lib.plt_attn_pad32(64) == 64
+    assert lib.plt_gemm(B.PLT_BF16, 4, 4, 4, None, None, None, None, 0, None) == -1

@@ -1,0 +1,170 @@
+"""End-to-end parity of plt_prefill / plt_decode_step (through the C ABI) with the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import plt_oracle as O
+from paper_2510_24824_amd import binding as B, synth
+from tests.helpers import lively_weights, oshape, with_shape
+
+pytestmark = pytest.mark.gpu
+
+
+def dev_tokens(arr):
+    return torch.from_numpy(np.ascontiguousarray(arr, np.int32)).cuda()
+
+
+def run_teacher_forced(shape, dtype, mode, weights, prompts, n_steps, tol, check_hidden=True):
+    """GPU consumes the oracle's token stream; logits (and hidden rows) compared at every step."""
+    bf = dtype == B.PLT_BF16
+    cfg = B.make_config(shape, dtype=dtype, mode=mode)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    Bn, n = prompts.shape
+    kv = B.KV(model, Bn, n + n_steps + 3)
+    orcs, streams, ref_logits, ref_hidden = [], [], [], []
+    for b in range(Bn):
+        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=bf)
+        if mode == B.PLT_MODE_CLP:
+            ids, margins, lgs = orc.greedy_generate(list(prompts[b]), n_steps)
+            hidden = np.stack(orc.trace)[n - 1:]                         # [n_steps+1, L, d]
+        else:
+            toks = list(prompts[b]); lgs = []; hid = []
+            for step in range(n_steps + 1):
+                H, lg = orc.vanilla_loop_forward(toks)
+                lgs.append(lg[-1]); hid.append(H[-1:, -1]); toks.append(int(np.argmax(lg[-1])))
+            ids = toks[n:]; lgs = np.stack(lgs); hidden = np.stack(hid)
+        streams.append(ids); ref_logits.append(lgs); ref_hidden.append(hidden)
+    streams = np.array(streams); ref_logits = np.stack(ref_logits); ref_hidden = np.stack(ref_hidden)
+    worst = 0.0
+    nxt, lg = kv.prefill(dev_tokens(prompts))
+    worst = max(worst, np.max(np.abs(lg.cpu().numpy() - ref_logits[:, 0])))
+    for step in range(n_steps):
+        nxt, lg = kv.decode_step(dev_tokens(streams[:, step]))
+        worst = max(worst, np.max(np.abs(lg.cpu().numpy() - ref_logits[:, step + 1])))
+        if check_hidden:
+            worst = max(worst, np.max(np.abs(kv.get_hidden() - ref_hidden[:, step + 1])))
+    assert kv.position == n + n_steps
+    print(f"worst abs err {worst:.3e}; max |logit| {np.max(np.abs(ref_logits)):.3f}; max |hidden| {np.max(np.abs(ref_hidden)):.3f}")
+    assert worst <= tol, worst
+    kv.close(); model.close()
+    return worst
+
+
+def test_tiny_config_greedy_ids_identical():
+    """2 layers, d=256, 4 heads of 64, FFN 1024, vocab 1024, L=2, w=16, float; 64-token prompt, 32 steps."""
+    shape = synth.TINY
+    seed = 0
+    weights = synth.make_weights(shape, seed, bf16=False)
+    prompt = synth.token_ids((1, 64), shape.vocab, seed)
+    orc = O.PLTOracle(oshape(shape), weights)
+    ids, margins, lgs = orc.greedy_generate(list(prompt[0]), 32)
+    assert min(margins) > 1e-3, "seed gives a near-tie; pick another"
+    cfg = B.make_config(shape, dtype=B.PLT_F32)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    kv = B.KV(model, 1, 64 + 33)
+    got, worst = [], 0.0
+    nxt, lg = kv.prefill(dev_tokens(prompt))
+    got.append(int(nxt.cpu()[0])); worst = max(worst, np.max(np.abs(lg.cpu().numpy()[0] - lgs[0])))
+    for step in range(32):
+        nxt, lg = kv.decode_step(nxt.clone())
+        got.append(int(nxt.cpu()[0])); worst = max(worst, np.max(np.abs(lg.cpu().numpy()[0] - lgs[step + 1])))
+    assert got == ids
+    assert worst <= 1e-5, worst
+    # Table 1 row 5: logical cache bytes = 2 * layers * Hkv * D * (n + (L-1) w) * 4
+    assert model.kv_logical_bytes(1, 96) == O.kv_cache_bytes(oshape(shape), 96, 4)
+
+
+@pytest.mark.parametrize("L,w,heads", [(3, 5, (4, 2)), (2, 16, (4, 4)), (1, 1, (4, 1)), (4, 3, (2, 2))])
+def test_f32_small_models(L, w, heads):
+    shape = synth.ModelShape(n_layers=2, d_model=96, n_heads=heads[0], n_kv_heads=heads[1], head_dim=64,
+                             ffn_hidden=160, vocab=300, n_loops=L, window=w, tie_embeddings=(L != 3))
+    weights = lively_weights(shape, 3, bf16=False, std=0.08)
+    prompts = synth.token_ids((2, 11), shape.vocab, 4)
+    run_teacher_forced(shape, B.PLT_F32, B.PLT_MODE_CLP, weights, prompts, 9, 2e-5)
+
+
+@pytest.mark.parametrize("L,w,heads,D", [(3, 8, (4, 2), 64), (2, 64, (2, 2), 128), (1, 1, (4, 4), 64), (4, 40, (8, 2), 64)])
+def test_bf16_small_models(L, w, heads, D):
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=heads[0], n_kv_heads=heads[1], head_dim=D,
+                             ffn_hidden=320, vocab=500, n_loops=L, window=w)
+    weights = lively_weights(shape, 5, bf16=True, std=0.02)      # the paper-style N(0, 0.02) init
+    prompts = synth.token_ids((3, 45), shape.vocab, 6)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 12, 2e-2)
+
+
+@pytest.mark.parametrize("dtype,tol", [(B.PLT_F32, 2e-5), (B.PLT_BF16, 2e-2)])
+def test_vanilla_loop_mode(dtype, tol):
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,
+                             ffn_hidden=192, vocab=400, n_loops=3, window=8)
+    weights = lively_weights(shape, 7, bf16=dtype == B.PLT_BF16, std=0.02)
+    prompts = synth.token_ids((2, 9), shape.vocab, 8)
+    run_teacher_forced(shape, dtype, B.PLT_MODE_VANILLA_LOOP, weights, prompts, 5, tol)
+
+
+def test_state_errors_and_context_limit():
+    shape = with_shape(synth.TINY, n_layers=1)
+    weights = synth.make_weights(shape, 1, bf16=False)
+    cfg = B.make_config(shape, dtype=B.PLT_F32)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    kv = B.KV(model, 1, 6)
+    tok = dev_tokens(np.array([1]))
+    with pytest.raises(B.PltError) as e:
+        kv.decode_step(tok)
+    assert e.value.code == -5
+    with pytest.raises(B.PltError) as e:
+        kv.prefill(dev_tokens(np.zeros((1, 7))))
+    assert e.value.code == -3
+    kv.prefill(dev_tokens(np.array([[1, 2, 3, 4, 5]])))
+    kv.decode_step(tok)
+    assert kv.position == 6
+    with pytest.raises(B.PltError) as e:
+        kv.decode_step(tok)
+    assert e.value.code == -3 and kv.position == 6
+    kv.close(); model.close()
+
+
+def test_kv_export_import_roundtrip_and_resume():
+    """Export after prefill, import into a fresh kv object, continue decoding: same logits."""
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,
+                             ffn_hidden=192, vocab=400, n_loops=3, window=8)
+    weights = lively_weights(shape, 9, bf16=True, std=0.02)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    prompts = synth.token_ids((2, 21), shape.vocab, 10)
+    kv1 = B.KV(model, 2, 40)
+    nxt, _ = kv1.prefill(dev_tokens(prompts))
+    kv2 = B.KV(model, 2, 40)
+    for seq in range(2):
+        for layer in range(shape.n_layers):
+            e = kv1.export(seq, layer, 21)
+            assert e["k_share"].shape == (2, 21, 64) and e["k_ring"].shape == (2, 2, 8, 64)
+            kv2.import_(seq, layer, 21, e["k_share"], e["v_share"], e["k_ring"], e["v_ring"])
+    kv2.set_carry(kv1.get_carry())
+    kv2.set_position(21)
+    # exported keys equal the oracle's rotated keys (bf16-rounded) for one sequence
+    orc = O.PLTOracle(oshape(shape), weights, kv_bf16=True)
+    orc.clp_prefill(list(prompts[0]), 40)
+    e = kv1.export(0, 1, 21)
+    for got, ref in [(e["k_share"], orc.kv.ks[1, :21]), (e["v_share"], orc.kv.vs[1, :21]),
+                     (e["k_ring"][0], orc.kv.kr[0, 1]), (e["v_ring"][1], orc.kv.vr[1, 1])]:
+        err = float(np.max(np.abs(got - ref.transpose(1, 0, 2))))
+        assert err <= 2e-2, err
+    t = nxt.clone()
+    a = kv1.decode_step(t)[1].cpu().numpy().copy()
+    b = kv2.decode_step(t)[1].cpu().numpy().copy()
+    assert np.array_equal(a, b)
+    for k in (kv1, kv2):
+        k.close()
+    model.close()
+
+
+def test_gemm_hook_matches_float64_product():
+    rng = np.random.default_rng(0)
+    for (M, N, K) in [(128, 192, 256), (37, 100, 64), (300, 70, 704), (8, 2048, 2048)]:
+        a = synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+        w = synth.round_to_bf16(rng.standard_normal((N, K)).astype(np.float32))
+        ref = a.astype(np.float64) @ w.astype(np.float64).T
+        c = B.gemm(B.PLT_BF16, torch.from_numpy(a).cuda().to(torch.bfloat16), torch.from_numpy(w).cuda().to(torch.bfloat16))
+        assert np.max(np.abs(c.cpu().numpy() - ref)) <= 1e-5 * K + 1e-4, (M, N, K)
+        c32 = B.gemm(B.PLT_F32, torch.from_numpy(a).cuda(), torch.from_numpy(w).cuda())
+        assert np.max(np.abs(c32.cpu().numpy() - ref)) <= 1e-5 * K + 1e-4, (M, N, K)
