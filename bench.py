@@ -1,0 +1,330 @@
+#!/usr/bin/env python3
+"""Benchmark of the PLT cross-loop-parallel decode step on one MI355X.
+
+Headline workload ("c3"): one full CLP decode step of the ~1.3B dense PLT in bf16 -- 24 layers,
+d_model 2048, 16 heads of 128, SwiGLU 5632, vocab 32000, L = 2, window 64, batch 64, 2048-token
+shared KV context -- all inputs synthetic and seeded, resident in HBM before the timed region.
+A "step" is one plt_decode_step over the whole batch (every stage of the hot path, one new
+token per sequence).  Prints ONE JSON line (see the keys below); extra keys carry the
+non-looped / vanilla-loop / L-sweep latencies, the kernel-only attention configuration and the
+CPU oracle timed on the host cores.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--only-main] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+SEED = 2510
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def fill_weights_on_device(B, cfg, seed):
+    """N(0, 0.02) weights drawn on the device straight into the library's blob layout
+    (norm gains 1, gate bias 0); returns the uint8 blob tensor."""
+    import torch
+    nbytes = B.lib().plt_weights_bytes(C.byref(cfg))
+    blob = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    g = torch.Generator(device="cuda"); g.manual_seed(seed)
+
+    def view(layer, which, dtype):
+        off, n = B.weights_offset(cfg, layer, which)
+        es = 2 if dtype == torch.bfloat16 else 4
+        return blob[off:off + es * n].view(dtype), n
+
+    def normal(layer, which, dtype):
+        v, n = view(layer, which, dtype)
+        step = 1 << 26
+        for i in range(0, n, step):
+            m = min(step, n - i)
+            v[i:i + m].copy_((torch.randn(m, generator=g, device="cuda") * 0.02).to(dtype))
+
+    wd = torch.bfloat16 if cfg.dtype == B.PLT_BF16 else torch.float32
+    normal(0, B.PLT_W_EMB, wd)
+    for m in range(cfg.n_layers):
+        view(m, B.PLT_W_NORM1, torch.float32)[0].fill_(1.0)
+        normal(m, B.PLT_W_WQKV, wd)
+        normal(m, B.PLT_W_GATE_W, torch.float32)
+        normal(m, B.PLT_W_WO, wd)
+        view(m, B.PLT_W_NORM2, torch.float32)[0].fill_(1.0)
+        normal(m, B.PLT_W_WGU, wd)
+        normal(m, B.PLT_W_WDOWN, wd)
+    view(0, B.PLT_W_NORM_F, torch.float32)[0].fill_(1.0)
+    if not cfg.tie_embeddings:
+        normal(0, B.PLT_W_HEAD, wd)
+    return blob
+
+
+def weights_to_host(B, cfg, blob):
+    """The device blob as the float32 weight dict the oracle takes (same values)."""
+    import torch
+    wd = torch.bfloat16 if cfg.dtype == B.PLT_BF16 else torch.float32
+    Hq, Hkv, D, d, F = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_model, cfg.ffn_hidden
+
+    def get(layer, which, dtype, shape):
+        off, n = B.weights_offset(cfg, layer, which)
+        es = 2 if dtype == torch.bfloat16 else 4
+        return blob[off:off + es * n].view(dtype).float().cpu().numpy().reshape(shape)
+
+    w = {"emb": get(0, B.PLT_W_EMB, wd, (cfg.vocab, d)), "norm_f": get(0, B.PLT_W_NORM_F, torch.float32, (d,)), "layers": []}
+    if not cfg.tie_embeddings:
+        w["head"] = get(0, B.PLT_W_HEAD, wd, (cfg.vocab, d))
+    for m in range(cfg.n_layers):
+        qkv = get(m, B.PLT_W_WQKV, wd, ((Hq + 2 * Hkv) * D, d))
+        gu = get(m, B.PLT_W_WGU, wd, (2 * F, d))
+        w["layers"].append({
+            "norm1": get(m, B.PLT_W_NORM1, torch.float32, (d,)), "wq": qkv[:Hq * D], "wk": qkv[Hq * D:(Hq + Hkv) * D],
+            "wv": qkv[(Hq + Hkv) * D:], "gate_w": get(m, B.PLT_W_GATE_W, torch.float32, (Hq, D)),
+            "gate_b": get(m, B.PLT_W_GATE_B, torch.float32, (Hq,)), "wo": get(m, B.PLT_W_WO, wd, (d, Hq * D)),
+            "norm2": get(m, B.PLT_W_NORM2, torch.float32, (d,)), "w_gate": gu[:F], "w_up": gu[F:],
+            "w_down": get(m, B.PLT_W_WDOWN, wd, (d, F))})
+    return w
+
+
+def attn_alg_bytes(Bn, L, Hq, Hkv, D, N, w, es=2):
+    """Algorithmic HBM bytes of one fused decode-attention launch: shared K and V once, the
+    rings once, Q in, Y out."""
+    share = 2 * Bn * Hkv * N * D * es
+    ring = 2 * Bn * (L - 1) * Hkv * min(w, N) * D * es
+    qy = 2 * Bn * L * Hq * D * es
+    return share + ring + qy
+
+
+def time_steps(kv, pos, tok, warmup, steps):
+    import torch
+    for _ in range(warmup):
+        kv.set_position(pos)
+        kv.decode_step(tok, want_logits=False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        kv.set_position(pos)
+        kv.decode_step(tok, want_logits=False)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def oracle_sample(B, shape, cfg, blob, exports, carry0, token0, pos, gpu_logits0, gpu_hidden0):
+    """One decode step of sequence 0 through the CPU oracle from the exported device state."""
+    from oracle import plt_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        threads = 1
+    w = weights_to_host(B, cfg, blob)
+    osh = O.OracleShape(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
+                        shape.ffn_hidden, shape.vocab, cfg.n_loops, cfg.window, shape.rope_theta, shape.norm_eps,
+                        shape.tie_embeddings)
+    orc = O.PLTOracle(osh, w, kv_bf16=True)
+    orc.kv = O.RingKV(orc._store, osh, pos + 1)
+    for m, e in enumerate(exports):
+        orc.kv.ks[m, :pos] = e["k_share"].transpose(1, 0, 2); orc.kv.vs[m, :pos] = e["v_share"].transpose(1, 0, 2)
+        for l in range(cfg.n_loops - 1):
+            orc.kv.kr[l, m] = e["k_ring"][l].transpose(1, 0, 2); orc.kv.vr[l, m] = e["v_ring"][l].transpose(1, 0, 2)
+    orc.carry = carry0.astype(np.float64).copy(); orc.pos = pos; orc.trace = []
+    t0 = time.perf_counter()
+    nxt, lg = orc.clp_decode_step(int(token0))
+    dt = time.perf_counter() - t0
+    err_l = float(np.max(np.abs(lg - gpu_logits0)))
+    err_h = float(np.max(np.abs(orc.trace[-1] - gpu_hidden0)))
+    return {"value": 1.0 / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 of the batch's sequences, one decode step (all {cfg.n_loops} loop rows, {shape.n_layers} layers, "
+                      f"context {pos + 1}) from the device's exported KV state; {dt:.1f} s",
+            "seconds": dt, "parity_max_abs_logits": err_l, "parity_max_abs_hidden": err_h,
+            "greedy_id_equal": None}, nxt
+
+
+def bench_attn_kernel(B, steps, warmup):
+    """Kernel-only fused decode attention: batch 32, L=3, 16 q / 4 kv heads, D=128, 4096 keys, w=64.
+    Four disjoint input sets are rotated so that a launch never finds its KV in the 256 MB last-level cache."""
+    import torch
+    Bn, L, Hq, Hkv, D, N, w = 32, 3, 16, 4, 128, 4096, 64
+    g = torch.Generator(device="cuda"); g.manual_seed(SEED + 2)
+    rn = lambda *s: torch.randn(*s, generator=g, device="cuda").to(torch.bfloat16)
+    sets = []
+    for _ in range(4):
+        sets.append(dict(q=rn(Bn, L, Hq, D), ks=rn(Bn, Hkv, N, D), vs=rn(Bn, Hkv, N // 32, D, 32),
+                         kr=rn(Bn, L - 1, Hkv, w, D), vr=rn(Bn, L - 1, Hkv, w // 32, D, 32),
+                         z=torch.randn(Bn, L - 1, Hq, generator=g, device="cuda"), y=torch.empty(Bn, L, Hq, D, dtype=torch.bfloat16, device="cuda")))
+    nb = B.lib().plt_attn_scratch_bytes(Bn, L, Hq, Hkv, D)
+    scratch = torch.zeros(nb, dtype=torch.uint8, device="cuda")
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    p = lambda t: C.c_void_p(t.data_ptr())
+
+    def launch(s):
+        rc = B.lib().plt_attn_decode(B.PLT_BF16, Bn, L, Hq, Hkv, D, N, N, w, w, p(s["q"]), p(s["ks"]), p(s["vs"]), p(s["kr"]),
+                                     p(s["vr"]), p(s["z"]), p(s["y"]), p(scratch), nb, 0, stream)
+        if rc:
+            raise RuntimeError(B.lib().plt_last_error().decode())
+
+    for i in range(warmup):
+        launch(sets[i % 4])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = max(steps, 8) * 4
+    e0.record()
+    for i in range(n):
+        launch(sets[i % 4])
+    e1.record(); torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / n
+    nbytes = attn_alg_bytes(Bn, L, Hq, Hkv, D, N, w)
+    gbs = nbytes / (us * 1e-6) / 1e9
+    return {"workload": "fused decode attention, bf16, B=32, L=3, 16q/4kv heads, D=128, N=4096, w=64",
+            "us_per_launch": us, "algorithmic_bytes": nbytes, "achieved_GBps": gbs, "frac_of_8TBps": gbs / HBM_PEAK_GBS,
+            "launches_timed": n}
+
+
+def read_traffic(name):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if a summary
+    under profiles/ records it as a line `<name> = <bytes>`; else None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.strip().startswith(name) and "=" in line:
+            try:
+                return float(line.split("=", 1)[1].split()[0])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--only-main", action="store_true", help="skip the baselines, the L sweep and the kernel-only run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=64)
+    ap.add_argument("--ctx", type=int, default=2048)
+    ap.add_argument("--loops", type=int, default=2)
+    ap.add_argument("--window", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2510_24824_amd import binding as B, synth
+    B.lib()   # fails loudly if the HIP library is missing
+    shape = synth.PLT_1P3B
+    Bn, N, L, w = args.batch, args.ctx, args.loops, args.window
+    pos = N - 1                                  # the position a timed step consumes; it attends N keys
+
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=L, window=w)
+    t0 = time.perf_counter()
+    blob = fill_weights_on_device(B, cfg, SEED)
+    model = B.Model(cfg, blob)
+    kv = B.KV(model, Bn, N)
+    g = torch.Generator(device="cuda"); g.manual_seed(SEED + 1)
+    prompt = torch.randint(0, shape.vocab, (Bn, pos), generator=g, device="cuda", dtype=torch.int32)
+    torch.cuda.synchronize()
+    log(f"[bench] weights + KV allocated in {time.perf_counter() - t0:.1f} s; prefill of {Bn} x {pos} tokens ...")
+    t0 = time.perf_counter()
+    nxt, _ = kv.prefill(prompt, want_logits=False)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    log(f"[bench] prefill done in {prefill_s:.2f} s")
+
+    # state before the first decode step (for the oracle sample), then one clean step
+    cpu = None
+    if not args.no_cpu_baseline:
+        exports = [kv.export(0, m, pos) for m in range(shape.n_layers)]
+        carry0 = kv.get_carry()[0] if L > 1 else np.zeros((0, shape.d_model), np.float32)
+        token0 = int(nxt[0].item())
+    tok = nxt.clone()
+    n1, lg1 = kv.decode_step(tok)
+    gpu_logits0 = lg1[0].float().cpu().numpy().astype(np.float64)
+    gpu_hidden0 = kv.get_hidden()[0].astype(np.float64)
+    gpu_next0 = int(n1[0].item())
+
+    # ---- timed region: K steps at fixed context, attention and GEMM launches bracketed by events
+    model.profile_enable(True)
+    for _ in range(args.warmup):
+        kv.set_position(pos); kv.decode_step(tok, want_logits=False)
+    model.profile_read(B.PLT_PROF_ATTN, reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        kv.set_position(pos); kv.decode_step(tok, want_logits=False)
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    attn_ms, attn_n = model.profile_read(B.PLT_PROF_ATTN, reset=False)
+    gemm_ms, gemm_n = model.profile_read(B.PLT_PROF_GEMM, reset=True)
+    model.profile_enable(False)
+    ms_step_noevents = time_steps(kv, pos, tok, 2, args.steps)
+
+    abytes = attn_alg_bytes(Bn, L, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w)
+    attn_us = attn_ms * 1e3 / max(attn_n, 1)
+    achieved = abytes / (attn_us * 1e-6) / 1e9
+    wbytes = 2 * (shape.n_layers * ((shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim * shape.d_model
+                                    + shape.d_model * shape.n_heads * shape.head_dim + 3 * shape.ffn_hidden * shape.d_model)
+                  + shape.vocab * shape.d_model)
+    out = {
+        "metric": "decode tokens/s + step latency vs non-looped at L=2/3/4; attn HBM GB/s",
+        "value": Bn / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"full CLP decode step, ~1.3B dense PLT (24 layers, d=2048, 16 heads x 128, SwiGLU 5632, vocab 32000), "
+                               f"bf16, L={L}, window {w}, batch {Bn}, {N}-token shared KV context (configs[2])",
+                   "batch": Bn, "n_loops": L, "window": w, "context": N, "seed": SEED,
+                   "kv_fill": f"plt_prefill of {pos} uniform token ids per sequence ({prefill_s:.2f} s)"},
+        "roofline": {"bound": "hbm", "kernel": "k_attn_decode<128> (fused decode attention, one launch per layer)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": read_traffic("attn_decode_c3_bytes_per_launch"),
+                     "algorithmic_bytes_per_launch": abytes, "avg_launch_us": attn_us, "launches": attn_n},
+        "gemm": {"avg_launch_us": gemm_ms * 1e3 / max(gemm_n, 1), "launches": gemm_n,
+                 "weight_bytes_per_step": wbytes, "ms_per_step": gemm_ms / args.steps,
+                 "weight_GBps": wbytes / (gemm_ms / args.steps * 1e-3) / 1e9 if gemm_ms > 0 else None},
+        "attn_ms_per_step": attn_ms / args.steps,
+        "ms_per_step_without_event_instrumentation": ms_step_noevents,
+        "kv_bytes_logical": model.kv_logical_bytes(Bn, N),
+    }
+
+    if not args.only_main:
+        # ---- same library, same weights: non-looped, the L sweep and the vanilla sequential loop.
+        # Their caches are filled with N(0, 0.5) values on the device (timing only).
+        kv.close(); del kv
+        torch.cuda.empty_cache()
+        lat = {}
+        for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
+                               ("plt_L4", B.PLT_MODE_CLP, 4), ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2),
+                               ("vanilla_loop_L3", B.PLT_MODE_VANILLA_LOOP, 3), ("vanilla_loop_L4", B.PLT_MODE_VANILLA_LOOP, 4)]:
+            c2 = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
+            m2 = B.Model(c2, blob)
+            k2 = B.KV(m2, Bn, N)
+            k2.buf.view(torch.bfloat16).normal_(0.0, 0.5, generator=g)
+            lat[name] = time_steps(k2, pos, tok, 2, max(8, args.steps // 2))
+            log(f"[bench] {name}: {lat[name]:.3f} ms/step")
+            k2.close(); m2.close(); del k2
+            torch.cuda.empty_cache()
+        base = lat["nonlooped_L1"]
+        out["latency_ms"] = lat
+        out["latency_vs_nonlooped"] = {k: v / base for k, v in lat.items()}
+        out["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup)
+
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on one sequence (about 10-30 s) ...")
+        cpu, o_next = oracle_sample(B, shape, cfg, blob, exports, carry0, token0, pos, gpu_logits0, gpu_hidden0)
+        cpu["greedy_id_equal"] = bool(o_next == gpu_next0)
+        out["cpu_baseline"] = cpu
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

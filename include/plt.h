@@ -183,6 +183,16 @@ int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* dev_a,
              void* hip_stream);
 size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 
+/* Bench instrumentation.  While enabled, every launch of the fused attention kernel
+ * (PLT_PROF_ATTN) and of a projection GEMM (PLT_PROF_GEMM) made by plt_decode_step is bracketed
+ * by a pair of hipEvents recorded on the model's stream.  plt_profile_read synchronises the
+ * stream, returns the summed elapsed milliseconds and the number of launches of one class
+ * since the last reset, and optionally resets the counters. */
+enum { PLT_PROF_ATTN = 0, PLT_PROF_GEMM = 1 };
+int plt_profile_enable(plt_model* m, int32_t on);
+int plt_profile_read(plt_model* m, int32_t klass, double* host_ms_sum, int64_t* host_launches,
+                     int32_t reset);
+
 #ifdef __cplusplus
 }
 #endif

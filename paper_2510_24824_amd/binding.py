@@ -60,7 +60,10 @@ _SIGS = {
     "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
     "plt_gemm_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_profile_enable": (C.c_int, [_P, _I]),
+    "plt_profile_read": (C.c_int, [_P, _I, C.POINTER(C.c_double), C.POINTER(C.c_int64), _I]),
 }
+PLT_PROF_ATTN, PLT_PROF_GEMM = 0, 1
 EXPORTS = tuple(_SIGS)
 
 _lib = None
@@ -156,6 +159,15 @@ class Model:
 
     def kv_logical_bytes(self, batch, n_ctx):
         return lib().plt_kv_logical_bytes(self.h, batch, n_ctx)
+
+    def profile_enable(self, on=True):
+        _check(lib().plt_profile_enable(self.h, 1 if on else 0))
+
+    def profile_read(self, klass, reset=True):
+        """(summed milliseconds, launches) of one kernel class since the last reset."""
+        ms, cnt = C.c_double(), C.c_int64()
+        _check(lib().plt_profile_read(self.h, klass, C.byref(ms), C.byref(cnt), 1 if reset else 0))
+        return ms.value, cnt.value
 
     def close(self):
         if self.h:

@@ -28,7 +28,10 @@ struct LayerW {
   const float* norm1; const void* wqkv; const float* gate_w; const float* gate_b;
   const void* wo; const float* norm2; const void* wgu; const void* wdown;
 };
+struct ProfRec { hipEvent_t a, b; int klass; };
 struct plt_model {
+  bool profile = false;
+  std::vector<ProfRec> prof_used, prof_free;
   plt_config cfg;
   hipStream_t stream;
   const char* blob;
@@ -150,7 +153,50 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
   return PLT_OK;
 }
 
-extern "C" void plt_free(plt_model* m) { delete m; }
+extern "C" void plt_free(plt_model* m) {
+  if (!m) return;
+  for (auto* v : {&m->prof_used, &m->prof_free})
+    for (ProfRec& r : *v) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  delete m;
+}
+
+// ---- bench instrumentation: event pairs around selected launches ----
+struct ProfScope {
+  plt_model* m; ProfRec r; bool on;
+  ProfScope(plt_model* m_, int klass, bool decode) : m(m_), on(m_->profile && decode) {
+    if (!on) return;
+    if (!m->prof_free.empty()) { r = m->prof_free.back(); m->prof_free.pop_back(); }
+    else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { on = false; return; }
+    r.klass = klass;
+    (void)hipEventRecord(r.a, m->stream);
+  }
+  ~ProfScope() { if (on) { (void)hipEventRecord(r.b, m->stream); m->prof_used.push_back(r); } }
+};
+
+extern "C" int plt_profile_enable(plt_model* m, int32_t on) {
+  if (!m) return fail(PLT_EINVAL, "plt_profile_enable: null model");
+  m->profile = on != 0;
+  return PLT_OK;
+}
+
+extern "C" int plt_profile_read(plt_model* m, int32_t klass, double* ms_sum, int64_t* launches, int32_t reset) {
+  if (!m || !ms_sum || !launches || (klass != PLT_PROF_ATTN && klass != PLT_PROF_GEMM))
+    return fail(PLT_EINVAL, "plt_profile_read: bad argument");
+  HIP_TRY(hipStreamSynchronize(m->stream));
+  double sum = 0.0; int64_t cnt = 0;
+  for (const ProfRec& r : m->prof_used) {
+    if (r.klass != klass) continue;
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    sum += ms; ++cnt;
+  }
+  *ms_sum = sum; *launches = cnt;
+  if (reset) {
+    m->prof_free.insert(m->prof_free.end(), m->prof_used.begin(), m->prof_used.end());
+    m->prof_used.clear();
+  }
+  return PLT_OK;
+}
 
 // ------------------------------------------------------------------------------ KV layout
 static bool is_clp(const plt_config& c) { return c.mode == PLT_MODE_CLP; }
@@ -270,7 +316,9 @@ struct Work {            // activation buffers one pass of the stack runs on
   float* x; void* a; float* gout; void* q; float* z; void* y; void* act;
 };
 
-static int run_gemm(const plt_model* m, const void* a, const void* w, float* out, int M, int N, int K) {
+static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int M, int N, int K,
+                    bool decode = false) {
+  ProfScope prof(m, PLT_PROF_GEMM, decode);
   if (m->cfg.dtype == PLT_BF16) {
     const int S = gemm_bf16_splits(M, N, K);
     launch_gemm_bf16(m->stream, (const bf16_t*)a, (const bf16_t*)w, out, M, N, K, S);
@@ -294,10 +342,12 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     const LayerW& w = m->layers[l];
     KvView v = kv_view(kv, l, cache);
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
-    int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d);                               // Alg. 3 l.1
+    int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                               // Alg. 3 l.1
     launch_rope_append<T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
                           dm, c.rope_theta, plain ? 1 : 0);
+    const bool dec = !rm.prefill;
     if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
+      ProfScope prof(m, PLT_PROF_ATTN, dec);
       if (rm.prefill) {
         launch_attn_prefill_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, Bc, n_prefill,
                                  rm.loop_fixed, dm, plain ? 1 : 0);
@@ -308,13 +358,14 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
                                 plain ? 1 : 0, kv->attn_scratch, ns);
       }
     } else {
+      ProfScope prof(m, PLT_PROF_ATTN, dec);
       launch_attn_f32(s, (const float*)wk.q, wk.z, (float*)wk.y, v, rm, R, dm, plain ? 1 : 0);
     }
-    S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D);                                     // Alg. 3 l.6
+    S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);                                     // Alg. 3 l.6
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
-    S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d);
+    S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
     launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
-    S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F);
+    S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
     const float* gain = l + 1 < c.n_layers ? m->layers[l + 1].norm1 : next_gain;
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, gain, c.norm_eps,
                          gain ? (T*)wk.a : (T*)nullptr, R, d);
@@ -323,11 +374,11 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
 
 template <typename T>
 static void head_and_argmax(plt_model* m, const Work& wk, int rows, int row_stride, int row_off,
-                            int32_t* dev_next, float* dev_logits) {
+                            int32_t* dev_next, float* dev_logits, bool decode = false) {
   const plt_config& c = m->cfg;
   launch_resid_norm<T>(m->stream, wk.x, row_stride, row_off, nullptr, 0, 0, m->norm_f, c.norm_eps, (T*)wk.a,
                        rows, c.d_model);
-  const int S = run_gemm(m, wk.a, m->head, wk.gout, rows, c.vocab, c.d_model);
+  const int S = run_gemm(m, wk.a, m->head, wk.gout, rows, c.vocab, c.d_model, decode);
   launch_argmax(m->stream, wk.gout, S, (size_t)rows * c.vocab, dev_logits, dev_next, rows, c.vocab);
 }
 
@@ -347,7 +398,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, R, d);
     stack_pass<T>(m, kv, wk, R, rm, 0, false, none, 0, 0, L, nullptr);
     launch_carry_update(s, kv->x, kv->carry, B, L, d);
-    head_and_argmax<T>(m, wk, B, L, L - 1, dev_next, dev_logits);                       // Alg. 1 l.8-9
+    head_and_argmax<T>(m, wk, B, L, L - 1, dev_next, dev_logits, true);                       // Alg. 1 l.8-9
   } else {
     // Eq. (1): L serial passes of B rows, loop l on its own cache l
     RowMap rm{0, 1, 0, kv->pos_dev};
@@ -355,7 +406,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, B, d);
     for (int l = 0; l < L; ++l)
       stack_pass<T>(m, kv, wk, B, rm, l, true, none, 0, 0, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
-    head_and_argmax<T>(m, wk, B, 1, 0, dev_next, dev_logits);
+    head_and_argmax<T>(m, wk, B, 1, 0, dev_next, dev_logits, true);
   }
   launch_pos_set(s, kv->pos_dev, B, 1, 1);
   return PLT_OK;
