@@ -183,6 +183,14 @@ int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* dev_a,
              void* hip_stream);
 size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 
+/* Plain device-to-device copy kernel (16 bytes per lane): the known-size reference for HBM
+ * traffic counters and a practical bandwidth ceiling.  nbytes and both pointers must be
+ * multiples of 16; the buffers must not overlap. */
+int plt_stream_copy(void* dev_dst, const void* dev_src, size_t nbytes, void* hip_stream);
+/* Read-only counterpart (a practical ceiling for a pure read stream such as decode attention):
+ * reads nbytes and writes one word per thread to dev_out (>= 2 MiB). */
+int plt_stream_read(const void* dev_src, size_t nbytes, void* dev_out, size_t out_bytes, void* hip_stream);
+
 /* Bench instrumentation.  While enabled, every launch of the fused attention kernel
  * (PLT_PROF_ATTN) and of a projection GEMM (PLT_PROF_GEMM) made by plt_decode_step is bracketed
  * by a pair of hipEvents recorded on the model's stream.  plt_profile_read synchronises the

@@ -60,6 +60,8 @@ _SIGS = {
     "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
     "plt_gemm_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_stream_copy": (C.c_int, [_P, _P, _Z, _P]),
+    "plt_stream_read": (C.c_int, [_P, _Z, _P, _Z, _P]),
     "plt_profile_enable": (C.c_int, [_P, _I]),
     "plt_profile_read": (C.c_int, [_P, _I, C.POINTER(C.c_double), C.POINTER(C.c_int64), _I]),
 }

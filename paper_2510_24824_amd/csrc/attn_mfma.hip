@@ -17,7 +17,8 @@
 // softmax needs no data movement between the two contractions; the row maximum is completed
 // with two wavefront shuffles (lanes r, r+16, r+32, r+48).  The four waves of a workgroup take
 // alternate tiles and merge their (m, l, O) states through LDS; workgroups that split one
-// stream merge through an HBM scratch, the last one to finish (device-scope ticket) writes y.
+// stream leave (m, l, O) records in an HBM scratch that a small second kernel merges (a
+// device-scope fence per workgroup costs far more on this multi-die part than a launch).
 #include "plt_internal.h"
 
 namespace plt {
@@ -161,13 +162,35 @@ struct AttnDecArgs {
   float scale_log2;
   float* part;                 // [stream][rt][split] records of (16 + 16 + 16*D) floats
   float* part_loc;             // [stream][rt] records of 16*D floats (normalised local branch)
-  unsigned int* ticket;        // [stream][rt], zero between launches
 };
+
+// Normalises the two branches of one row chunk, applies the gate of Eq. (2) and stores y.
+// Thread tid covers row tid/16 of row tile rt and features (tid%16)*(D/16) .. +D/16-1.
+template <int D>
+__device__ inline void finalize_row(const AttnDecArgs& A, int b, int kvh, int rt, int tid, float Lg,
+                                    const float (&og)[D / 16], float Ll, const float (&ol)[D / 16]) {
+  const int row = rt * 16 + (tid >> 4), dc = (tid & 15) * (D / 16);
+  if (row >= A.n_rows) return;
+  const int r_loop = row / A.G, r_head = kvh * A.G + row % A.G;
+  const bool gated = !A.plain && r_loop > 0;
+  float out[D / 16];
+  const float invg = Lg > 0.f ? 1.0f / Lg : 0.f;
+  if (gated) {
+    const float zz = A.z[((size_t)b * (A.L - 1) + (r_loop - 1)) * A.Hq + r_head];
+    const float gate = 1.0f / (1.0f + __expf(-zz));
+    const float invl = Ll > 0.f ? 1.0f / Ll : 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) out[i] = gate * (ol[i] * invl) + (1.0f - gate) * (og[i] * invg);
+  } else {
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
+  }
+  store_row<D>(A.y + (((size_t)b * A.L + r_loop) * A.Hq + r_head) * D + dc, out);
+}
 
 template <int D>
 __global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
   __shared__ WgMerge<D> sm;
-  __shared__ unsigned int s_ticket;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int split = blockIdx.x % A.n_splits, rt = blockIdx.x / A.n_splits;
   const int kvh = blockIdx.y, b = blockIdx.z;
@@ -196,15 +219,22 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
   const bf16_t* vbase = A.v_share + stream * (size_t)A.n_pad * D;
   WaveState<D> st; st.init();
   {
+    // Tiles are visited in a rotated order that differs from stream to stream (softmax does not
+    // care about order): workgroups that run in lockstep then touch different HBM channels
+    // instead of the same offset of their equally aligned streams.
     KvTile<D> cur, nxt;
-    int t = t_beg + wv;
-    if (t < t_end) load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
-    for (; t < t_end; t += 4) {
-      const int tn = t + 4;
-      if (tn < t_end) load_tile<D>(nxt, kbase + (size_t)tn * 32 * D, vbase + (size_t)tn * 32 * D, m16, g);
+    const int n_my = t_end - t_beg;
+    const int rot = n_my > 0 ? (int)((stream * 13u + (unsigned)split * 7u) % (unsigned)n_my) : 0;
+    auto tile_of = [&](int u) { int t = u + rot; if (t >= n_my) t -= n_my; return t_beg + t; };
+    int u = wv;
+    if (u < n_my) { const int t = tile_of(u); load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g); }
+    for (; u < n_my; u += 4) {
+      const int t = tile_of(u);
+      const int un = u + 4;
+      if (un < n_my) { const int tn = tile_of(un); load_tile<D>(nxt, kbase + (size_t)tn * 32 * D, vbase + (size_t)tn * 32 * D, m16, g); }
       const int kb = t * 32 + 8 * g;
       tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * 32 > n_ctx, [&](int j) { return kb + j < n_ctx; });
-      if (tn < t_end) cur = nxt;
+      if (un < n_my) cur = nxt;
     }
   }
   float Mg, Lg, og[D / 16];
@@ -233,14 +263,11 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
   }
 
   // ---- thread (row, feature chunk) view from here on ----
-  const int row = rt * 16 + (tid >> 4), dc = (tid & 15) * (D / 16);
-  const bool row_ok = row < A.n_rows;
-  const int r_loop = row_ok ? row / A.G : 0, r_head = kvh * A.G + (row_ok ? row % A.G : 0);
-  const bool gated = !A.plain && r_loop > 0;
-  const size_t rec = (size_t)(16 + 16 + 16 * D);
+  const int dc = (tid & 15) * (D / 16);
   const size_t slot = stream * A.n_rt + rt;
-
   if (A.n_splits > 1) {
+    // several workgroups share this stream: leave (m, l, O) records; k_attn_combine finishes
+    const size_t rec = (size_t)(16 + 16 + 16 * D);
     float* pr = A.part + (slot * A.n_splits + split) * rec;
     if ((tid & 15) == 0) { pr[tid >> 4] = Mg; pr[16 + (tid >> 4)] = Lg; }
 #pragma unroll
@@ -251,50 +278,41 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
 #pragma unroll
       for (int i = 0; i < D / 16; ++i) pl[(tid >> 4) * D + dc + i] = ol[i] * inv;
     }
-    __threadfence();                                   // publish this workgroup's records
-    __syncthreads();
-    if (tid == 0) s_ticket = atomicAdd(&A.ticket[slot], 1u);
-    __syncthreads();
-    if (s_ticket != (unsigned)(A.n_splits - 1)) return; // not the last one: done
-    __threadfence();                                   // see every other workgroup's records
-    // merge all splits (fixed order -> bit-reproducible regardless of who arrives last)
-    const float* p0 = A.part + slot * A.n_splits * rec;
-    float M = NEG_INF;
-    for (int s = 0; s < A.n_splits; ++s) M = fmaxf(M, *(p0 + s * rec + (tid >> 4)));
-    Lg = 0.f;
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) og[i] = 0.f;
-    for (int s = 0; s < A.n_splits; ++s) {
-      const float* ps = p0 + s * rec;
-      const float ms = *(ps + (tid >> 4));
-      const float f = (ms == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
-      Lg += f * *(ps + 16 + (tid >> 4));
-#pragma unroll
-      for (int i = 0; i < D / 16; ++i) og[i] += f * *(ps + 32 + (tid >> 4) * D + dc + i);
-    }
-    if (gated) {
-      const float* pl = A.part_loc + slot * (size_t)(16 * D);
-#pragma unroll
-      for (int i = 0; i < D / 16; ++i) ol[i] = *(pl + (tid >> 4) * D + dc + i);
-      Ll = 1.f;
-    }
-    if (tid == 0) A.ticket[slot] = 0u;                 // leave the ticket clean for the next launch
+    return;
   }
+  finalize_row<D>(A, b, kvh, rt, tid, Lg, og, Ll, ol);
+}
 
-  if (!row_ok) return;
-  float out[D / 16];
-  const float invg = Lg > 0.f ? 1.0f / Lg : 0.f;
-  if (gated) {
-    const float zz = A.z[((size_t)b * (A.L - 1) + (r_loop - 1)) * A.Hq + r_head];
-    const float gate = 1.0f / (1.0f + __expf(-zz));
-    const float invl = Ll > 0.f ? 1.0f / Ll : 0.f;
+// Merges the split records of one (stream, row tile) in a fixed order (bit-reproducible) and
+// applies Eq. (2).  One workgroup per (row tile, kv head, sequence); launched after k_attn_decode
+// on the same stream whenever n_splits > 1.
+template <int D>
+__global__ __launch_bounds__(256) void k_attn_combine(AttnDecArgs A) {
+  const int tid = threadIdx.x, rt = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int dc = (tid & 15) * (D / 16);
+  const size_t stream = (size_t)b * A.Hkv + kvh, slot = stream * A.n_rt + rt;
+  const size_t rec = (size_t)(16 + 16 + 16 * D);
+  const float* p0 = A.part + slot * A.n_splits * rec;
+  float M = NEG_INF;
+  for (int s = 0; s < A.n_splits; ++s) M = fmaxf(M, p0[s * rec + (tid >> 4)]);
+  float Lg = 0.f, og[D / 16], Ll = 0.f, ol[D / 16];
 #pragma unroll
-    for (int i = 0; i < D / 16; ++i) out[i] = gate * (ol[i] * invl) + (1.0f - gate) * (og[i] * invg);
-  } else {
+  for (int i = 0; i < D / 16; ++i) { og[i] = 0.f; ol[i] = 0.f; }
+  for (int s = 0; s < A.n_splits; ++s) {
+    const float* ps = p0 + s * rec;
+    const float ms = ps[tid >> 4];
+    const float f = (ms == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(ms - M);
+    Lg += f * ps[16 + (tid >> 4)];
 #pragma unroll
-    for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
+    for (int i = 0; i < D / 16; ++i) og[i] += f * ps[32 + (tid >> 4) * D + dc + i];
   }
-  store_row<D>(A.y + (((size_t)b * A.L + r_loop) * A.Hq + r_head) * D + dc, out);
+  if (!A.plain && A.n_rings > 0) {
+    const float* pl = A.part_loc + slot * (size_t)(16 * D);
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) ol[i] = pl[(tid >> 4) * D + dc + i];
+    Ll = 1.f;
+  }
+  finalize_row<D>(A, b, kvh, rt, tid, Lg, og, Ll, ol);
 }
 
 size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D) {
@@ -302,8 +320,7 @@ size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D) {
   const size_t slots = (size_t)B * Hkv * n_rt;
   const size_t rec = (size_t)(32 + 16 * D) * sizeof(float);
   const size_t max_splits = 64;
-  size_t bytes = slots * 256;                       // tickets (one per slot, padded)
-  bytes += slots * max_splits * rec;                // split records
+  size_t bytes = slots * max_splits * rec;            // split records
   bytes += slots * (size_t)(16 * D) * sizeof(float);  // local-branch records
   return bytes;
 }
@@ -312,8 +329,11 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx) {
   const int n_rt = (L * G + 15) / 16;
   const long streams = (long)B * Hkv * n_rt;
   const int n_tiles = (n_ctx + 31) / 32;
-  // aim for >= 4 workgroups per compute unit, but keep >= 16 tiles (4 per wave) per workgroup
-  int s = (int)((4L * 256 + streams - 1) / streams);
+  // one workgroup per stream when that already covers every compute unit; else split so that
+  // about one workgroup per compute unit exists (more splits only add merge work: measured),
+  // keeping >= 16 tiles (4 per wave) per workgroup
+  if (streams >= 256) return 1;
+  int s = (int)((256 + streams - 1) / streams);
   int cap = n_tiles / 16; if (cap < 1) cap = 1;
   if (s > cap) s = cap;
   if (s > 64) s = 64;
@@ -337,13 +357,16 @@ void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf1
   A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
   const size_t slots = (size_t)dm.B * dm.Hkv * A.n_rt;
   const size_t rec = (size_t)(32 + 16 * dm.D);
-  char* sp = (char*)scratch;
-  A.ticket = (unsigned int*)sp;
-  A.part = (float*)(sp + slots * 256);
+  A.part = (float*)scratch;
   A.part_loc = A.part + slots * 64 * rec;
-  dim3 grid(A.n_splits * A.n_rt, dm.Hkv, dm.B);
-  if (dm.D == 64) hipLaunchKernelGGL(k_attn_decode<64>, grid, dim3(256), 0, s, A);
-  else hipLaunchKernelGGL(k_attn_decode<128>, grid, dim3(256), 0, s, A);
+  dim3 grid(A.n_splits * A.n_rt, dm.Hkv, dm.B), cgrid(A.n_rt, dm.Hkv, dm.B);
+  if (dm.D == 64) {
+    hipLaunchKernelGGL(k_attn_decode<64>, grid, dim3(256), 0, s, A);
+    if (A.n_splits > 1) hipLaunchKernelGGL(k_attn_combine<64>, cgrid, dim3(256), 0, s, A);
+  } else {
+    hipLaunchKernelGGL(k_attn_decode<128>, grid, dim3(256), 0, s, A);
+    if (A.n_splits > 1) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, s, A);
+  }
 }
 
 // ------------------------------------------------------------------------------- prefill

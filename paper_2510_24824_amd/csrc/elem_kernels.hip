@@ -77,12 +77,70 @@ __global__ void k_resid_norm(float* __restrict__ x, int x_row_stride, int x_row_
   float inv = 1.0f / sqrtf(ss / (float)d + eps);
   for (int i = threadIdx.x; i < d; i += 256) st<T>(a_out + (size_t)r * d + i, xr[i] * inv * gain[i]);
 }
+// float4 variant for d % 4 == 0 and d <= 4096: every thread keeps its (up to 4) float4 values in
+// registers between the accumulation and the normalisation pass, and the S slab loads of one
+// value are issued together (independent accumulators) instead of one after the other.
+template <typename T>
+__global__ __launch_bounds__(256) void k_resid_norm4(float* __restrict__ x, int x_row_stride, int x_row_off,
+                                                     const float* __restrict__ partials, int S, size_t slab,
+                                                     const float* __restrict__ gain, float eps,
+                                                     T* __restrict__ a_out, int d) {
+  __shared__ float sm[4];
+  const int r = blockIdx.x, d4 = d >> 2;
+  float4* xr = reinterpret_cast<float4*>(x + ((size_t)r * x_row_stride + x_row_off) * d);
+  float4 v[4];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = threadIdx.x + it * 256;
+    if (i >= d4) break;
+    float4 a = xr[i];
+    if (S > 0) {
+      const float4* pp = reinterpret_cast<const float4*>(partials + (size_t)r * d) + i;
+      const size_t slab4 = slab >> 2;
+      float4 acc0 = make_float4(0.f, 0.f, 0.f, 0.f), acc1 = acc0;
+      int s = 0;
+      for (; s + 4 <= S; s += 4) {
+        float4 p0 = pp[(size_t)s * slab4], p1 = pp[(size_t)(s + 1) * slab4], p2 = pp[(size_t)(s + 2) * slab4],
+               p3 = pp[(size_t)(s + 3) * slab4];
+        acc0.x += p0.x; acc0.y += p0.y; acc0.z += p0.z; acc0.w += p0.w;
+        acc1.x += p1.x; acc1.y += p1.y; acc1.z += p1.z; acc1.w += p1.w;
+        acc0.x += p2.x; acc0.y += p2.y; acc0.z += p2.z; acc0.w += p2.w;
+        acc1.x += p3.x; acc1.y += p3.y; acc1.z += p3.z; acc1.w += p3.w;
+      }
+      for (; s < S; ++s) {
+        float4 p0 = pp[(size_t)s * slab4];
+        acc0.x += p0.x; acc0.y += p0.y; acc0.z += p0.z; acc0.w += p0.w;
+      }
+      a.x += acc0.x + acc1.x; a.y += acc0.y + acc1.y; a.z += acc0.z + acc1.z; a.w += acc0.w + acc1.w;
+      xr[i] = a;
+    }
+    v[it] = a;
+    ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+  }
+  if (a_out == nullptr) return;
+  ss = block_sum_256(ss, sm);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = threadIdx.x + it * 256;
+    if (i >= d4) break;
+    const float4 gn = reinterpret_cast<const float4*>(gain)[i];
+    T* dst = a_out + (size_t)r * d + 4 * i;
+    st<T>(dst + 0, v[it].x * inv * gn.x); st<T>(dst + 1, v[it].y * inv * gn.y);
+    st<T>(dst + 2, v[it].z * inv * gn.z); st<T>(dst + 3, v[it].w * inv * gn.w);
+  }
+}
 template <typename T>
 void launch_resid_norm(hipStream_t s, float* x, int x_row_stride, int x_row_off,
                        const float* partials, int S, size_t slab, const float* gain, float eps,
                        T* a_out, int R, int d) {
-  hipLaunchKernelGGL(k_resid_norm<T>, dim3(R), dim3(256), 0, s, x, x_row_stride, x_row_off, partials,
-                     S, slab, gain, eps, a_out, d);
+  if ((d & 3) == 0 && d <= 4096 && (slab & 3) == 0)
+    hipLaunchKernelGGL(k_resid_norm4<T>, dim3(R), dim3(256), 0, s, x, x_row_stride, x_row_off, partials,
+                       S, slab, gain, eps, a_out, d);
+  else
+    hipLaunchKernelGGL(k_resid_norm<T>, dim3(R), dim3(256), 0, s, x, x_row_stride, x_row_off, partials,
+                       S, slab, gain, eps, a_out, d);
 }
 template void launch_resid_norm<float>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, float*, int, int);
 template void launch_resid_norm<bf16_t>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, bf16_t*, int, int);
@@ -93,7 +151,7 @@ template <typename T>
 __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
                               const float* __restrict__ gate_w, const float* __restrict__ gate_b,
                               T* __restrict__ q_out, float* __restrict__ z_out, KvView kv, RowMap rm,
-                              Dims dm, float theta, int plain) {
+                              Dims dm, const double* __restrict__ inv_freq, int plain) {
   const int hs = blockIdx.x, r = blockIdx.y, j = threadIdx.x;
   const int D = dm.D, half = D / 2, Hq = dm.Hq, Hkv = dm.Hkv;
   const int ncol = (Hq + 2 * Hkv) * D;
@@ -103,12 +161,21 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
   float lo = 0.f, hi = 0.f;
   if (act) {
     const float* src = qkv + (size_t)r * ncol + (size_t)hs * D;
-    for (int s = 0; s < S; ++s) { lo += src[(size_t)s * slab + j]; hi += src[(size_t)s * slab + j + half]; }
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {          // four slabs per round: eight independent loads in flight
+      const float* p0 = src + (size_t)s * slab;
+      float a0 = p0[j], b0 = p0[j + half], a1 = p0[slab + j], b1 = p0[slab + j + half];
+      float a2 = p0[2 * slab + j], b2 = p0[2 * slab + j + half], a3 = p0[3 * slab + j], b3 = p0[3 * slab + j + half];
+      lo += (a0 + a1) + (a2 + a3); hi += (b0 + b1) + (b2 + b3);
+    }
+    for (; s < S; ++s) { lo += src[(size_t)s * slab + j]; hi += src[(size_t)s * slab + j + half]; }
   }
   float c = 1.f, sn = 0.f;
   if (act && hs < Hq + Hkv) {
-    double ang = (double)p * pow((double)theta, -2.0 * (double)j / (double)D);
-    c = (float)cos(ang); sn = (float)sin(ang);
+    // angle in turns, reduced in double (exact to ~1e-13), then a float sine / cosine
+    double t = (double)p * inv_freq[j] * 0.15915494309189535;
+    t -= rint(t);
+    sincosf((float)(t * 6.283185307179586), &sn, &c);
   }
   if (hs < Hq) {
     if (!plain && l > 0) {
@@ -172,12 +239,12 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
 template <typename T>
 void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
                         const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
-                        Dims dm, float theta, int plain) {
+                        Dims dm, const double* inv_freq, int plain) {
   hipLaunchKernelGGL(k_rope_append<T>, dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
-                     gate_w, gate_b, q_out, z_out, kv, rm, dm, theta, plain);
+                     gate_w, gate_b, q_out, z_out, kv, rm, dm, inv_freq, plain);
 }
-template void launch_rope_append<float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, float, int);
-template void launch_rope_append<bf16_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, float, int);
+template void launch_rope_append<float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, const double*, int);
+template void launch_rope_append<bf16_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, const double*, int);
 
 // ---- SwiGLU: act = silu(gate) * up, gate = columns [0,F), up = columns [F,2F) ----
 template <typename T>
@@ -203,18 +270,10 @@ template void launch_silu_mul<float>(hipStream_t, const float*, int, size_t, flo
 template void launch_silu_mul<bf16_t>(hipStream_t, const float*, int, size_t, bf16_t*, int, int);
 
 // ---- greedy head: sum slabs, optional logits copy-out, argmax with lowest-index ties ----
-__global__ void k_argmax(const float* __restrict__ lg, int S, size_t slab, float* __restrict__ out,
-                         int32_t* __restrict__ next, int V) {
-  __shared__ float bv[256];
-  __shared__ int bi[256];
-  int b = blockIdx.x;
-  float best = -INFINITY; int idx = 0x7fffffff;
-  for (int i = threadIdx.x; i < V; i += 256) {
-    float v = 0.f;
-    for (int s = 0; s < S; ++s) v += lg[(size_t)s * slab + (size_t)b * V + i];
-    if (out) out[(size_t)b * V + i] = v;
-    if (v > best) { best = v; idx = i; }
-  }
+// stage 1: grid (chunks, B): each block scans one chunk of the vocabulary; stage 2: one block per
+// sequence merges the chunk winners.  Ties resolve to the lowest index in both stages.
+constexpr int ARG_CHUNKS = 32;
+__device__ inline void argmax_block_reduce(float best, int idx, float* bv, int* bi) {
   bv[threadIdx.x] = best; bi[threadIdx.x] = idx;
   __syncthreads();
   for (int o = 128; o > 0; o >>= 1) {
@@ -226,12 +285,44 @@ __global__ void k_argmax(const float* __restrict__ lg, int S, size_t slab, float
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) next[b] = bi[0] == 0x7fffffff ? 0 : bi[0];
 }
-void launch_argmax(hipStream_t s, const float* lg, int S, size_t slab, float* logits_out,
-                   int32_t* next, int B, int V) {
-  hipLaunchKernelGGL(k_argmax, dim3(B), dim3(256), 0, s, lg, S, slab, logits_out, next, V);
+__global__ __launch_bounds__(256) void k_argmax_stage1(const float* __restrict__ lg, int S, size_t slab,
+                                                       float* __restrict__ out, float* __restrict__ pv,
+                                                       int* __restrict__ pi, int V) {
+  __shared__ float bv[256];
+  __shared__ int bi[256];
+  const int b = blockIdx.y, ck = blockIdx.x;
+  const int per = (V + ARG_CHUNKS - 1) / ARG_CHUNKS;
+  const int i0 = ck * per, i1 = (i0 + per < V) ? i0 + per : V;
+  float best = -INFINITY; int idx = 0x7fffffff;
+  for (int i = i0 + threadIdx.x; i < i1; i += 256) {
+    float v = 0.f;
+    for (int s = 0; s < S; ++s) v += lg[(size_t)s * slab + (size_t)b * V + i];
+    if (out) out[(size_t)b * V + i] = v;
+    if (v > best) { best = v; idx = i; }
+  }
+  argmax_block_reduce(best, idx, bv, bi);
+  if (threadIdx.x == 0) { pv[b * ARG_CHUNKS + ck] = bv[0]; pi[b * ARG_CHUNKS + ck] = bi[0]; }
 }
+__global__ void k_argmax_stage2(const float* __restrict__ pv, const int* __restrict__ pi,
+                                int32_t* __restrict__ next) {
+  const int b = blockIdx.x, t = threadIdx.x;             // 64 threads >= ARG_CHUNKS
+  float v = t < ARG_CHUNKS ? pv[b * ARG_CHUNKS + t] : -INFINITY;
+  int i = t < ARG_CHUNKS ? pi[b * ARG_CHUNKS + t] : 0x7fffffff;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float v2 = __shfl_xor(v, o, 64); int i2 = __shfl_xor(i, o, 64);
+    if (v2 > v || (v2 == v && i2 < i)) { v = v2; i = i2; }
+  }
+  if (t == 0) next[b] = i == 0x7fffffff ? 0 : i;
+}
+void launch_argmax(hipStream_t s, const float* lg, int S, size_t slab, float* logits_out, int32_t* next,
+                   int B, int V, float* part_v, int* part_i) {
+  hipLaunchKernelGGL(k_argmax_stage1, dim3(ARG_CHUNKS, B), dim3(256), 0, s, lg, S, slab, logits_out, part_v,
+                     part_i, V);
+  hipLaunchKernelGGL(k_argmax_stage2, dim3(B), dim3(64), 0, s, part_v, part_i, next);
+}
+int argmax_scratch_elems(int B) { return B * ARG_CHUNKS; }
 
 // ---- S7: carried states for the next step: carry[b][l] = H^(l+1)[p], l = 0..L-2 ----
 __global__ void k_carry_update(const float* __restrict__ x, float* __restrict__ carry, int L, int d) {

@@ -133,3 +133,166 @@ void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c,
 }
 
 }  // namespace plt
+
+// ----------------------------------------------------------------------------------------------
+// Decode-time variant ("weight streaming"): few rows (M <= 128 per row block), weights read once.
+//
+// A workgroup owns one K range of KR = 512 and keeps the matching slice of the activations
+// (up to 128 rows x 512, bf16) resident in LDS.  Its 4 waves (one per SIMD, so each may use the
+// whole register file) walk over groups of NB 16-column strips of the weight matrix: the strips'
+// rows go from HBM straight into registers in MFMA A-operand layout (16 bytes per lane), half a
+// K range at a time, the next half prefetched while the current one is multiplied; the
+// activations come from LDS as the B operand and every fragment read from LDS feeds NB MFMAs
+// (LDS bandwidth, not HBM, bounds this kernel when NB is small).  No barrier after the prologue.
+// Each K range writes its own float slab; consumers add the slabs in a fixed order.
+namespace plt {
+
+constexpr int WS_KR = 512, WS_LDK = WS_KR + 8, WS_THREADS = 256;
+
+// MT: 16-row activation tiles (4: M <= 64, 8: M <= 128); NB: strips per group; the K range is
+// consumed in steps of WS_KH 32-wide chunks, two register buffers alternating
+template <int MT, int NB>
+__global__ __launch_bounds__(WS_THREADS) void k_gemm_wstream(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
+                                                             float* __restrict__ c, int M, int N, int K,
+                                                             int n_groups) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t As[];   // [MT*16][WS_LDK]
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int ng = blockIdx.x, rb = blockIdx.y, split = blockIdx.z;
+  const int k0 = split * WS_KR;
+  const int kr = (K - k0 < WS_KR) ? K - k0 : WS_KR;          // valid width of this K range
+  const int row0 = rb * (MT * 16);
+
+  constexpr int WS_KH = NB >= 4 ? 4 : 8, STEPS = (WS_KR / 32) / WS_KH;
+  const int n_strips = (N + 15) >> 4;
+  const int n_grp = (n_strips + NB - 1) / NB;
+  const int stride = n_groups * 4;
+  uint4 bufA[NB][WS_KH], bufB[NB][WS_KH];
+  // step h (0..STEPS-1) of the K range for the NB strips of group grp
+  auto wload = [&](uint4 (&f)[NB][WS_KH], int grp, int h) {
+#pragma unroll
+    for (int sb = 0; sb < NB; ++sb) {
+      int n = (grp * NB + sb) * 16 + m16; if (n >= N) n = N - 1;   // ragged N: clamp (stores are masked)
+      const bf16_t* wr = w + (size_t)n * K + k0 + g * 8;
+#pragma unroll
+      for (int kk = 0; kk < WS_KH; ++kk) {
+        int ko = (h * WS_KH + kk) * 32; if (ko + g * 8 + 8 > kr) ko = 0;   // beyond K: in-range chunk (meets zeros)
+        f[sb][kk] = *reinterpret_cast<const uint4*>(wr + ko);
+      }
+    }
+  };
+  // the first weight fragments are requested before the prologue so that their latency hides behind it
+  int grp = ng * 4 + wv;
+  if (grp < n_grp) wload(bufA, grp, 0);
+
+  // prologue: activation slice -> LDS (zeros beyond M and beyond K).  All loads of a thread are
+  // issued before the first LDS store so that their latencies overlap.
+  {
+    constexpr int PER = MT * 16 * (WS_KR / 8) / WS_THREADS;     // 16-byte chunks per thread
+    uint4 v[PER];
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const int ch = tid + it * WS_THREADS;
+      const int row = ch / (WS_KR / 8), kc = (ch % (WS_KR / 8)) * 8;
+      v[it] = make_uint4(0, 0, 0, 0);
+      if (row0 + row < M && kc < kr) v[it] = *reinterpret_cast<const uint4*>(a + (size_t)(row0 + row) * K + k0 + kc);
+    }
+#pragma unroll
+    for (int it = 0; it < PER; ++it) {
+      const int ch = tid + it * WS_THREADS;
+      const int row = ch / (WS_KR / 8), kc = (ch % (WS_KR / 8)) * 8;
+      *reinterpret_cast<uint4*>(&As[row * WS_LDK + kc]) = v[it];
+    }
+  }
+  __syncthreads();
+
+  f32x4 acc[NB][MT];
+  auto mac = [&](const uint4 (&f)[NB][WS_KH], int h) {
+#pragma unroll
+    for (int kk = 0; kk < WS_KH; ++kk) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const uint4 af = *reinterpret_cast<const uint4*>(&As[(i * 16 + m16) * WS_LDK + (h * WS_KH + kk) * 32 + g * 8]);
+#pragma unroll
+        for (int sb = 0; sb < NB; ++sb)
+          acc[sb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f[sb][kk]),
+                                                              __builtin_bit_cast(bf16x8, af), acc[sb][i], 0, 0, 0);
+      }
+      // keep the LDS reads of later K chunks from being hoisted up here (register pressure)
+      if ((kk & 1) == 1) __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  float* cs = c + (size_t)split * M * N;
+  for (; grp < n_grp; grp += stride) {
+#pragma unroll
+    for (int sb = 0; sb < NB; ++sb)
+#pragma unroll
+      for (int i = 0; i < MT; ++i) acc[sb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) {            // STEPS is even: buffer parity carries over to the next group
+      if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1); else wload(bufB, grp, t + 1); }
+      else if (grp + stride < n_grp) wload(bufA, grp + stride, 0);
+      if (t & 1) mac(bufB, t); else mac(bufA, t);
+    }
+    // acc[sb][i][e] = C[row0 + i*16 + m16][(grp*NB + sb)*16 + 4*g + e]
+#pragma unroll
+    for (int sb = 0; sb < NB; ++sb) {
+      const int gn = (grp * NB + sb) * 16 + 4 * g;
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        const int gm = row0 + i * 16 + m16;
+        if (gm >= M || gn >= N) continue;
+        float* dst = cs + (size_t)gm * N + gn;
+        if (gn + 3 < N && (N & 3) == 0) *reinterpret_cast<f32x4*>(dst) = acc[sb][i];
+        else for (int e = 0; e < 4; ++e) if (gn + e < N) dst[e] = acc[sb][i][e];
+      }
+    }
+  }
+}
+
+bool gemm_use_wstream(int M, int N, int K) { return M <= 256 && N >= 16; }
+
+// splits for the generic entry: the streaming kernel always splits K in ranges of 512
+int gemm_bf16_splits_any(int M, int N, int K) {
+  if (gemm_use_wstream(M, N, K)) return (K + WS_KR - 1) / WS_KR;
+  return gemm_bf16_splits(M, N, K);
+}
+
+template <int MT, int NB>
+static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K, int S, int rbs,
+                      int n_groups) {
+  const size_t lds = (size_t)MT * 16 * WS_LDK * sizeof(bf16_t);
+  static bool attr_done = false;     // one flag per template instance
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((k_gemm_wstream<MT, NB>), dim3(n_groups, rbs, S), dim3(WS_THREADS), lds, s, a, w, c, M, N, K, n_groups);
+}
+
+void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
+  if (!gemm_use_wstream(M, N, K)) { launch_gemm_bf16(s, a, w, c, M, N, K, gemm_bf16_splits(M, N, K)); return; }
+  const int S = (K + WS_KR - 1) / WS_KR;
+  const bool small = M <= 64;
+  const int rbs = small ? 1 : (M + 127) / 128;
+  const int n_strips = (N + 15) / 16;
+  // One workgroup fits per compute unit (its activation slice fills most of the LDS), so at most
+  // 256 workgroups: a second round would pay the prologue again.  Strips per wave task (NB) grow
+  // until the 4 * n_groups waves of one (K range, row block) cover the strips in one pass if possible.
+  int n_groups = 256 / (S * rbs); if (n_groups < 1) n_groups = 1;
+  const int slots = n_groups * 4;
+  int nb = (n_strips + slots - 1) / slots;
+  nb = nb >= 3 ? 4 : (nb == 2 ? 2 : 1);
+  const int n_grp = (n_strips + nb - 1) / nb;
+  if (n_groups > (n_grp + 3) / 4) n_groups = (n_grp + 3) / 4;
+  if (small) {
+    if (nb == 4) ws_launch<4, 4>(s, a, w, c, M, N, K, S, rbs, n_groups);
+    else if (nb == 2) ws_launch<4, 2>(s, a, w, c, M, N, K, S, rbs, n_groups);
+    else ws_launch<4, 1>(s, a, w, c, M, N, K, S, rbs, n_groups);
+  } else {
+    if (nb == 4) ws_launch<8, 4>(s, a, w, c, M, N, K, S, rbs, n_groups);
+    else if (nb == 2) ws_launch<8, 2>(s, a, w, c, M, N, K, S, rbs, n_groups);
+    else ws_launch<8, 1>(s, a, w, c, M, N, K, S, rbs, n_groups);
+  }
+}
+
+}  // namespace plt

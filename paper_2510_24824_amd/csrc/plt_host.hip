@@ -38,6 +38,7 @@ struct plt_model {
   std::vector<LayerW> layers;
   const void* emb; const float* norm_f; const void* head;
   int es;   // element size of the model dtype
+  double* inv_freq = nullptr;   // device [D/2]: rotary frequencies theta^(-2j/D), computed in double
 };
 struct plt_kv {
   plt_model* m;
@@ -50,6 +51,7 @@ struct plt_kv {
   // per-step activation scratch (device, library-owned)
   float* x; void* a; float* gout; size_t gout_elems; void* q; float* z; void* y; void* act;
   float* carry; int32_t* pos_dev; void* attn_scratch; size_t attn_scratch_bytes;
+  float* arg_v; int* arg_i;   // argmax chunk winners
 };
 
 static bool cfg_valid(const plt_config* c, const char** why) {
@@ -149,12 +151,20 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
     w.wo = at(l, PLT_W_WO); w.norm2 = (const float*)at(l, PLT_W_NORM2);
     w.wgu = at(l, PLT_W_WGU); w.wdown = at(l, PLT_W_WDOWN);
   }
+  {
+    std::vector<double> f(cfg->head_dim / 2);
+    for (int j = 0; j < cfg->head_dim / 2; ++j) f[j] = std::pow((double)cfg->rope_theta, -2.0 * j / cfg->head_dim);
+    hipError_t e = hipMalloc((void**)&m->inv_freq, f.size() * sizeof(double));
+    if (e == hipSuccess) e = hipMemcpy(m->inv_freq, f.data(), f.size() * sizeof(double), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { if (m->inv_freq) (void)hipFree(m->inv_freq); delete m; return fail(PLT_EHIP, "plt_init: %s", hipGetErrorString(e)); }
+  }
   *out = m;
   return PLT_OK;
 }
 
 extern "C" void plt_free(plt_model* m) {
   if (!m) return;
+  if (m->inv_freq) (void)hipFree(m->inv_freq);
   for (auto* v : {&m->prof_used, &m->prof_free})
     for (ProfRec& r : *v) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
   delete m;
@@ -221,7 +231,8 @@ extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_
 
 static void kv_release(plt_kv* kv) {
   if (!kv) return;
-  void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch};
+  void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch,
+                  kv->arg_v, kv->arg_i};
   for (void* p : ptrs) if (p) (void)hipFree(p);
   delete kv;
 }
@@ -229,7 +240,7 @@ static void kv_release(plt_kv* kv) {
 extern "C" void plt_kv_free(plt_kv* kv) { kv_release(kv); }
 
 static size_t gemm_out_need(const plt_config& c, int M, int N, int K) {
-  const int S = c.dtype == PLT_BF16 ? gemm_bf16_splits(M, N, K) : 1;
+  const int S = c.dtype == PLT_BF16 ? gemm_bf16_splits_any(M, N, K) : 1;
   return (size_t)S * M * N;
 }
 
@@ -278,6 +289,8 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   dmalloc((void**)&kv->carry, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4);
   dmalloc((void**)&kv->pos_dev, (size_t)batch * 4);
   dmalloc(&kv->attn_scratch, kv->attn_scratch_bytes);
+  dmalloc((void**)&kv->arg_v, (size_t)argmax_scratch_elems(batch) * 4);
+  dmalloc((void**)&kv->arg_i, (size_t)argmax_scratch_elems(batch) * 4);
   if (e == hipSuccess) e = hipMemsetAsync(kv->attn_scratch, 0, kv->attn_scratch_bytes, m->stream);
   if (e == hipSuccess) e = hipMemsetAsync(kv->carry, 0, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4, m->stream);
   if (e == hipSuccess) e = hipMemsetAsync(kv->x, 0, (size_t)R * d * 4, m->stream);
@@ -320,9 +333,8 @@ static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int 
                     bool decode = false) {
   ProfScope prof(m, PLT_PROF_GEMM, decode);
   if (m->cfg.dtype == PLT_BF16) {
-    const int S = gemm_bf16_splits(M, N, K);
-    launch_gemm_bf16(m->stream, (const bf16_t*)a, (const bf16_t*)w, out, M, N, K, S);
-    return S;
+    launch_gemm_bf16_any(m->stream, (const bf16_t*)a, (const bf16_t*)w, out, M, N, K);
+    return gemm_bf16_splits_any(M, N, K);
   }
   launch_gemm_f32(m->stream, (const float*)a, (const float*)w, out, M, N, K);
   return 1;
@@ -344,7 +356,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
     int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                               // Alg. 3 l.1
     launch_rope_append<T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
-                          dm, c.rope_theta, plain ? 1 : 0);
+                          dm, m->inv_freq, plain ? 1 : 0);
     const bool dec = !rm.prefill;
     if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
       ProfScope prof(m, PLT_PROF_ATTN, dec);
@@ -373,13 +385,13 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
 }
 
 template <typename T>
-static void head_and_argmax(plt_model* m, const Work& wk, int rows, int row_stride, int row_off,
+static void head_and_argmax(plt_model* m, plt_kv* kv, const Work& wk, int rows, int row_stride, int row_off,
                             int32_t* dev_next, float* dev_logits, bool decode = false) {
   const plt_config& c = m->cfg;
   launch_resid_norm<T>(m->stream, wk.x, row_stride, row_off, nullptr, 0, 0, m->norm_f, c.norm_eps, (T*)wk.a,
                        rows, c.d_model);
   const int S = run_gemm(m, wk.a, m->head, wk.gout, rows, c.vocab, c.d_model, decode);
-  launch_argmax(m->stream, wk.gout, S, (size_t)rows * c.vocab, dev_logits, dev_next, rows, c.vocab);
+  launch_argmax(m->stream, wk.gout, S, (size_t)rows * c.vocab, dev_logits, dev_next, rows, c.vocab, kv->arg_v, kv->arg_i);
 }
 
 template <typename T>
@@ -398,7 +410,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, R, d);
     stack_pass<T>(m, kv, wk, R, rm, 0, false, none, 0, 0, L, nullptr);
     launch_carry_update(s, kv->x, kv->carry, B, L, d);
-    head_and_argmax<T>(m, wk, B, L, L - 1, dev_next, dev_logits, true);                       // Alg. 1 l.8-9
+    head_and_argmax<T>(m, kv, wk, B, L, L - 1, dev_next, dev_logits, true);                       // Alg. 1 l.8-9
   } else {
     // Eq. (1): L serial passes of B rows, loop l on its own cache l
     RowMap rm{0, 1, 0, kv->pos_dev};
@@ -406,7 +418,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, B, d);
     for (int l = 0; l < L; ++l)
       stack_pass<T>(m, kv, wk, B, rm, l, true, none, 0, 0, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
-    head_and_argmax<T>(m, wk, B, 1, 0, dev_next, dev_logits, true);
+    head_and_argmax<T>(m, kv, wk, B, 1, 0, dev_next, dev_logits, true);
   }
   launch_pos_set(s, kv->pos_dev, B, 1, 1);
   return PLT_OK;
@@ -482,7 +494,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
         stack_pass<T>(m, kv, wk, R, rm, l, true, loc, bc, n, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
       }
     }
-    head_and_argmax<T>(m, wk, bc, n, n - 1, dev_next + b0, dev_logits ? dev_logits + (size_t)b0 * V : nullptr);
+    head_and_argmax<T>(m, kv, wk, bc, n, n - 1, dev_next + b0, dev_logits ? dev_logits + (size_t)b0 * V : nullptr);
   }
   launch_pos_set(s, kv->pos_dev, B, n, 0);
   e = hipStreamSynchronize(s);
@@ -676,6 +688,49 @@ extern "C" int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, c
   return PLT_OK;
 }
 
+// plain copy, 16 bytes per lane per iteration: the reference point for HBM counters and the
+// practical bandwidth ceiling the attention kernel is compared with
+__global__ __launch_bounds__(256) void k_stream_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+// read-only counterpart: every lane folds what it reads and stores one word at the end
+__global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, unsigned* __restrict__ out, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  unsigned acc = 0;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  }
+  for (; i < n16; i += stride) { uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+  out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+extern "C" int plt_stream_read(const void* dev_src, size_t nbytes, void* dev_out, size_t out_bytes, void* hip_stream) {
+  const size_t blocks = 256 * 8;
+  if (!dev_src || !dev_out || nbytes == 0 || (nbytes & 15) || (((uintptr_t)dev_src) & 15) || out_bytes < blocks * 256 * 4)
+    return fail(PLT_EINVAL, "plt_stream_read: need 16-byte multiples and an output buffer of %zu bytes", blocks * 256 * 4);
+  hipLaunchKernelGGL(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const uint4*)dev_src, (unsigned*)dev_out, nbytes / 16);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
+extern "C" int plt_stream_copy(void* dev_dst, const void* dev_src, size_t nbytes, void* hip_stream) {
+  if (!dev_dst || !dev_src || nbytes == 0 || (nbytes & 15) || (((uintptr_t)dev_dst | (uintptr_t)dev_src) & 15))
+    return fail(PLT_EINVAL, "plt_stream_copy: pointers and size must be non-null multiples of 16 bytes");
+  const size_t n16 = nbytes / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(k_stream_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const uint4*)dev_src, (uint4*)dev_dst, n16);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
 __global__ void k_sum_slabs(const float* __restrict__ p, float* __restrict__ c, int S, size_t n) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
@@ -686,7 +741,7 @@ __global__ void k_sum_slabs(const float* __restrict__ p, float* __restrict__ c, 
 
 extern "C" size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || N < 1 || K < 1) { fail(PLT_EINVAL, "plt_gemm_scratch_bytes: bad shape"); return 0; }
-  return align256((size_t)gemm_bf16_splits(M, N, K) * M * N * 4);
+  return align256((size_t)gemm_bf16_splits_any(M, N, K) * M * N * 4);
 }
 
 extern "C" int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* a, const void* w, float* c,
@@ -699,12 +754,12 @@ extern "C" int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const vo
     launch_gemm_f32(s, (const float*)a, (const float*)w, c, M, N, K);
   } else {
     if (K % 64) return fail(PLT_EINVAL, "plt_gemm: bf16 needs K to be a multiple of 64");
-    const int S = gemm_bf16_splits(M, N, K);
+    const int S = gemm_bf16_splits_any(M, N, K);
     if (S == 1) {
-      launch_gemm_bf16(s, (const bf16_t*)a, (const bf16_t*)w, c, M, N, K, 1);
+      launch_gemm_bf16_any(s, (const bf16_t*)a, (const bf16_t*)w, c, M, N, K);
     } else {
       if (!scratch || scratch_bytes < plt_gemm_scratch_bytes(M, N, K)) return fail(PLT_ENOMEM, "plt_gemm: scratch too small");
-      launch_gemm_bf16(s, (const bf16_t*)a, (const bf16_t*)w, (float*)scratch, M, N, K, S);
+      launch_gemm_bf16_any(s, (const bf16_t*)a, (const bf16_t*)w, (float*)scratch, M, N, K);
       const size_t n = (size_t)M * N;
       hipLaunchKernelGGL(k_sum_slabs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)scratch, c, S, n);
     }

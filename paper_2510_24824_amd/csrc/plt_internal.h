@@ -76,11 +76,12 @@ void launch_resid_norm(hipStream_t s, float* x, int x_row_stride, int x_row_off,
 template <typename T>
 void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
                         const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
-                        Dims dm, float theta, int first_loop_only);
+                        Dims dm, const double* inv_freq /* device [D/2]: theta^(-2j/D) */, int first_loop_only);
 template <typename T>
 void launch_silu_mul(hipStream_t s, const float* gu, int S, size_t slab, T* act, int R, int F);
 void launch_argmax(hipStream_t s, const float* lg, int S, size_t slab, float* logits_out,
-                   int32_t* next, int B, int V);
+                   int32_t* next, int B, int V, float* part_v, int* part_i);
+int argmax_scratch_elems(int B);   // elements of part_v and of part_i
 void launch_carry_update(hipStream_t s, const float* x, float* carry, int B, int L, int d);
 void launch_pos_set(hipStream_t s, int32_t* pos, int B, int value, int increment);
 void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n);
@@ -98,6 +99,9 @@ void launch_gemm_f32(hipStream_t s, const float* a, const float* w, float* c, in
 int gemm_bf16_splits(int M, int N, int K);
 void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N,
                       int K, int splits);
+// picks the weight-streaming kernel for few rows, the tiled one otherwise
+int gemm_bf16_splits_any(int M, int N, int K);
+void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
 
 // attn_f32.hip : one wave per (row, query head), float storage
 void launch_attn_f32(hipStream_t s, const float* q, const float* z, float* y, KvView kv,
