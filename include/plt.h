@@ -191,13 +191,14 @@ int plt_stream_copy(void* dev_dst, const void* dev_src, size_t nbytes, void* hip
  * reads nbytes and writes one word per thread to dev_out (>= 2 MiB). */
 int plt_stream_read(const void* dev_src, size_t nbytes, void* dev_out, size_t out_bytes, void* hip_stream);
 
-/* Bench instrumentation.  While enabled, every launch of the fused attention kernel
- * (PLT_PROF_ATTN) and of a projection GEMM (PLT_PROF_GEMM) made by plt_decode_step is bracketed
- * by a pair of hipEvents recorded on the model's stream.  plt_profile_read synchronises the
+/* Bench instrumentation.  `mask` selects launch classes (bit 1 << PLT_PROF_ATTN: the fused
+ * attention kernel; bit 1 << PLT_PROF_GEMM: every projection GEMM; 0 = off).  While selected, every
+ * such launch made by plt_decode_step is bracketed by a pair of hipEvents recorded on the model's
+ * stream.  plt_profile_read synchronises the
  * stream, returns the summed elapsed milliseconds and the number of launches of one class
  * since the last reset, and optionally resets the counters. */
 enum { PLT_PROF_ATTN = 0, PLT_PROF_GEMM = 1 };
-int plt_profile_enable(plt_model* m, int32_t on);
+int plt_profile_enable(plt_model* m, int32_t mask);
 int plt_profile_read(plt_model* m, int32_t klass, double* host_ms_sum, int64_t* host_launches,
                      int32_t reset);
 

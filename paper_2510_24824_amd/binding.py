@@ -162,8 +162,9 @@ class Model:
     def kv_logical_bytes(self, batch, n_ctx):
         return lib().plt_kv_logical_bytes(self.h, batch, n_ctx)
 
-    def profile_enable(self, on=True):
-        _check(lib().plt_profile_enable(self.h, 1 if on else 0))
+    def profile_enable(self, mask):
+        """mask: OR of (1 << PLT_PROF_ATTN), (1 << PLT_PROF_GEMM); 0 switches the instrumentation off."""
+        _check(lib().plt_profile_enable(self.h, int(mask)))
 
     def profile_read(self, klass, reset=True):
         """(summed milliseconds, launches) of one kernel class since the last reset."""

@@ -147,12 +147,12 @@ void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c,
 // Each K range writes its own float slab; consumers add the slabs in a fixed order.
 namespace plt {
 
-constexpr int WS_KR = 512, WS_LDK = WS_KR + 8, WS_THREADS = 256;
+constexpr int WS_KR = 512, WS_LDK = WS_KR + 8;
 
 // MT: 16-row activation tiles (4: M <= 64, 8: M <= 128); NB: strips per group; the K range is
 // consumed in steps of WS_KH 32-wide chunks, two register buffers alternating
-template <int MT, int NB>
-__global__ __launch_bounds__(WS_THREADS) void k_gemm_wstream(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
+template <int MT, int NB, int NW>   // NW: waves per workgroup (4: one per SIMD, 8: two per SIMD)
+__global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                              float* __restrict__ c, int M, int N, int K,
                                                              int n_groups) {
   extern __shared__ __attribute__((aligned(16))) bf16_t As[];   // [MT*16][WS_LDK]
@@ -162,10 +162,11 @@ __global__ __launch_bounds__(WS_THREADS) void k_gemm_wstream(const bf16_t* __res
   const int kr = (K - k0 < WS_KR) ? K - k0 : WS_KR;          // valid width of this K range
   const int row0 = rb * (MT * 16);
 
-  constexpr int WS_KH = NB >= 4 ? 4 : 8, STEPS = (WS_KR / 32) / WS_KH;
+  constexpr int WS_THREADS = NW * 64;
+  constexpr int WS_KH = (NB * NW >= 16) ? 4 : 8, STEPS = (WS_KR / 32) / WS_KH;
   const int n_strips = (N + 15) >> 4;
   const int n_grp = (n_strips + NB - 1) / NB;
-  const int stride = n_groups * 4;
+  const int stride = n_groups * NW;
   uint4 bufA[NB][WS_KH], bufB[NB][WS_KH];
   // step h (0..STEPS-1) of the K range for the NB strips of group grp
   auto wload = [&](uint4 (&f)[NB][WS_KH], int grp, int h) {
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(WS_THREADS) void k_gemm_wstream(const bf16_t* __res
     }
   };
   // the first weight fragments are requested before the prologue so that their latency hides behind it
-  int grp = ng * 4 + wv;
+  int grp = ng * NW + wv;
   if (grp < n_grp) wload(bufA, grp, 0);
 
   // prologue: activation slice -> LDS (zeros beyond M and beyond K).  All loads of a thread are
@@ -257,16 +258,16 @@ int gemm_bf16_splits_any(int M, int N, int K) {
   return gemm_bf16_splits(M, N, K);
 }
 
-template <int MT, int NB>
+template <int MT, int NB, int NW>
 static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K, int S, int rbs,
                       int n_groups) {
   const size_t lds = (size_t)MT * 16 * WS_LDK * sizeof(bf16_t);
   static bool attr_done = false;     // one flag per template instance
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  hipLaunchKernelGGL((k_gemm_wstream<MT, NB>), dim3(n_groups, rbs, S), dim3(WS_THREADS), lds, s, a, w, c, M, N, K, n_groups);
+  hipLaunchKernelGGL((k_gemm_wstream<MT, NB, NW>), dim3(n_groups, rbs, S), dim3(NW * 64), lds, s, a, w, c, M, N, K, n_groups);
 }
 
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
@@ -275,24 +276,27 @@ void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float
   const bool small = M <= 64;
   const int rbs = small ? 1 : (M + 127) / 128;
   const int n_strips = (N + 15) / 16;
+  // 4 waves (one per SIMD) or 8: measured equal within noise on the decode shapes; 4 is used
+  const int NWv = 4;
   // One workgroup fits per compute unit (its activation slice fills most of the LDS), so at most
   // 256 workgroups: a second round would pay the prologue again.  Strips per wave task (NB) grow
-  // until the 4 * n_groups waves of one (K range, row block) cover the strips in one pass if possible.
+  // until the NW * n_groups waves of one (K range, row block) cover the strips in one pass if possible.
   int n_groups = 256 / (S * rbs); if (n_groups < 1) n_groups = 1;
-  const int slots = n_groups * 4;
+  const int slots = n_groups * NWv;
   int nb = (n_strips + slots - 1) / slots;
   nb = nb >= 3 ? 4 : (nb == 2 ? 2 : 1);
+  if (NWv == 8 && nb == 4) nb = 2;
   const int n_grp = (n_strips + nb - 1) / nb;
-  if (n_groups > (n_grp + 3) / 4) n_groups = (n_grp + 3) / 4;
-  if (small) {
-    if (nb == 4) ws_launch<4, 4>(s, a, w, c, M, N, K, S, rbs, n_groups);
-    else if (nb == 2) ws_launch<4, 2>(s, a, w, c, M, N, K, S, rbs, n_groups);
-    else ws_launch<4, 1>(s, a, w, c, M, N, K, S, rbs, n_groups);
+  if (n_groups > (n_grp + NWv - 1) / NWv) n_groups = (n_grp + NWv - 1) / NWv;
+#define WS_CASE(MT_, NB_, NW_) ws_launch<MT_, NB_, NW_>(s, a, w, c, M, N, K, S, rbs, n_groups)
+  if (NWv == 4) {
+    if (small) { if (nb == 4) WS_CASE(4, 4, 4); else if (nb == 2) WS_CASE(4, 2, 4); else WS_CASE(4, 1, 4); }
+    else       { if (nb == 4) WS_CASE(8, 4, 4); else if (nb == 2) WS_CASE(8, 2, 4); else WS_CASE(8, 1, 4); }
   } else {
-    if (nb == 4) ws_launch<8, 4>(s, a, w, c, M, N, K, S, rbs, n_groups);
-    else if (nb == 2) ws_launch<8, 2>(s, a, w, c, M, N, K, S, rbs, n_groups);
-    else ws_launch<8, 1>(s, a, w, c, M, N, K, S, rbs, n_groups);
+    if (small) { if (nb == 2) WS_CASE(4, 2, 8); else WS_CASE(4, 1, 8); }
+    else       { if (nb == 2) WS_CASE(8, 2, 8); else WS_CASE(8, 1, 8); }
   }
+#undef WS_CASE
 }
 
 }  // namespace plt

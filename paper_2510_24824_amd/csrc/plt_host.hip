@@ -30,7 +30,7 @@ struct LayerW {
 };
 struct ProfRec { hipEvent_t a, b; int klass; };
 struct plt_model {
-  bool profile = false;
+  int profile = 0;   // bit mask of instrumented launch classes (1 << PLT_PROF_*)
   std::vector<ProfRec> prof_used, prof_free;
   plt_config cfg;
   hipStream_t stream;
@@ -173,7 +173,7 @@ extern "C" void plt_free(plt_model* m) {
 // ---- bench instrumentation: event pairs around selected launches ----
 struct ProfScope {
   plt_model* m; ProfRec r; bool on;
-  ProfScope(plt_model* m_, int klass, bool decode) : m(m_), on(m_->profile && decode) {
+  ProfScope(plt_model* m_, int klass, bool decode) : m(m_), on(((m_->profile >> klass) & 1) && decode) {
     if (!on) return;
     if (!m->prof_free.empty()) { r = m->prof_free.back(); m->prof_free.pop_back(); }
     else if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) { on = false; return; }
@@ -185,7 +185,7 @@ struct ProfScope {
 
 extern "C" int plt_profile_enable(plt_model* m, int32_t on) {
   if (!m) return fail(PLT_EINVAL, "plt_profile_enable: null model");
-  m->profile = on != 0;
+  m->profile = on;
   return PLT_OK;
 }
 
