@@ -189,7 +189,7 @@ __device__ inline void finalize_row(const AttnDecArgs& A, int b, int kvh, int rt
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
+__global__ __launch_bounds__(256, 2) void k_attn_decode(AttnDecArgs A) {
   __shared__ WgMerge<D> sm;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int split = blockIdx.x % A.n_splits, rt = blockIdx.x / A.n_splits;
@@ -217,50 +217,56 @@ __global__ __launch_bounds__(256) void k_attn_decode(AttnDecArgs A) {
   const int t_end = (t_beg + tps < n_tiles) ? t_beg + tps : n_tiles;
   const bf16_t* kbase = A.k_share + stream * (size_t)A.n_pad * D;
   const bf16_t* vbase = A.v_share + stream * (size_t)A.n_pad * D;
-  WaveState<D> st; st.init();
+  // ---- local branch (last split only): the valid 32-slot tiles of the rings of loops 2..L ----
+  const bool do_local = !A.plain && A.n_rings > 0 && split == A.n_splits - 1;
+  const int tv = (n_ring + 31) >> 5;                       // valid tiles per ring
+  const int n_loc = do_local ? A.n_rings * tv : 0;
+  // One software pipeline over both kinds of tile: entries 0..n_my-1 are this split's shared tiles,
+  // entries n_my.. are ring tiles; wave wv takes entries wv, wv+4, ...  While an entry is being
+  // multiplied the next one (of either kind) is already in flight, so the window branch adds no
+  // exposed memory latency.  The two branches keep separate online-softmax states.
+  WaveState<D> st, sl; st.init(); sl.init();
   {
-    // Tiles are visited in a rotated order that differs from stream to stream (softmax does not
-    // care about order): workgroups that run in lockstep then touch different HBM channels
+    // Shared tiles are visited in a rotated order that differs from stream to stream (softmax does
+    // not care about order): workgroups that run in lockstep then touch different HBM channels
     // instead of the same offset of their equally aligned streams.
     KvTile<D> cur, nxt;
-    const int n_my = t_end - t_beg;
+    const int n_my = t_end > t_beg ? t_end - t_beg : 0;    // a late split may own no shared tile
+    const int n_ent = n_my + n_loc;
     const int rot = n_my > 0 ? (int)((stream * 13u + (unsigned)split * 7u) % (unsigned)n_my) : 0;
     auto tile_of = [&](int u) { int t = u + rot; if (t >= n_my) t -= n_my; return t_beg + t; };
-    int u = wv;
-    if (u < n_my) { const int t = tile_of(u); load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g); }
-    for (; u < n_my; u += 4) {
-      const int t = tile_of(u);
-      const int un = u + 4;
-      if (un < n_my) { const int tn = tile_of(un); load_tile<D>(nxt, kbase + (size_t)tn * 32 * D, vbase + (size_t)tn * 32 * D, m16, g); }
-      const int kb = t * 32 + 8 * g;
-      tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * 32 > n_ctx, [&](int j) { return kb + j < n_ctx; });
-      if (un < n_my) cur = nxt;
+    auto load_entry = [&](KvTile<D>& tl, int e) {
+      if (e < n_my) {
+        const int t = tile_of(e);
+        load_tile<D>(tl, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
+      } else {
+        const int j = e - n_my, rl = j / tv, tr = j - rl * tv;
+        const size_t rs = (((size_t)b * A.n_rings + rl) * A.Hkv + kvh) * (size_t)A.w_pad * D;
+        load_tile<D>(tl, A.k_ring + rs + (size_t)tr * 32 * D, A.v_ring + rs + (size_t)tr * 32 * D, m16, g);
+      }
+    };
+    int e = wv;
+    if (e < n_ent) load_entry(cur, e);
+    for (; e < n_ent; e += 4) {
+      const int en = e + 4;
+      if (en < n_ent) load_entry(nxt, en);
+      if (e < n_my) {
+        const int t = tile_of(e), kb = t * 32 + 8 * g;
+        tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * 32 > n_ctx, [&](int j) { return kb + j < n_ctx; });
+      } else {
+        const int j0 = e - n_my, rl = j0 / tv, tr = j0 - rl * tv, sb = tr * 32 + 8 * g;
+        const bool mine = qrow_ok && (q_loop == rl + 1);
+        tile_step<D>(sl, cur, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); });
+      }
+      if (en < n_ent) cur = nxt;
     }
   }
   float Mg, Lg, og[D / 16];
   wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
-
-  // ---- local branch (last split only): the rings of loops 2..L, one ring per 32-slot tiles ----
-  const bool do_local = !A.plain && A.n_rings > 0 && split == A.n_splits - 1;
   float Ml = NEG_INF, Ll = 0.f, ol[D / 16];
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) ol[i] = 0.f;
-  if (do_local) {
-    st.init();
-    const int tpr = A.w_pad >> 5;
-    const int vt_end = A.n_rings * tpr;
-    for (int vt = wv; vt < vt_end; vt += 4) {
-      const int rl = vt / tpr, tr = vt - rl * tpr;
-      if (tr * 32 >= n_ring) continue;
-      const size_t rs = (((size_t)b * A.n_rings + rl) * A.Hkv + kvh) * (size_t)A.w_pad * D;
-      KvTile<D> cur;
-      load_tile<D>(cur, A.k_ring + rs + (size_t)tr * 32 * D, A.v_ring + rs + (size_t)tr * 32 * D, m16, g);
-      const int sb = tr * 32 + 8 * g;
-      const bool mine = qrow_ok && (q_loop == rl + 1);
-      tile_step<D>(st, cur, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); });
-    }
-    wg_merge<D>(sm, st, wv, m16, g, Ml, Ll, ol);
-  }
+  if (do_local) wg_merge<D>(sm, sl, wv, m16, g, Ml, Ll, ol);
 
   // ---- thread (row, feature chunk) view from here on ----
   const int dc = (tid & 15) * (D / 16);
