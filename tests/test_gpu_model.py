@@ -169,3 +169,43 @@ def test_gemm_hook_matches_float64_product():
         assert np.max(np.abs(c.cpu().numpy() - ref)) <= 1e-5 * K + 1e-4, (M, N, K)
         c32 = B.gemm(B.PLT_F32, torch.from_numpy(a).cuda(), torch.from_numpy(w).cuda())
         assert np.max(np.abs(c32.cpu().numpy() - ref)) <= 1e-5 * K + 1e-4, (M, N, K)
+
+
+@pytest.mark.parametrize("dtype,tol", [(B.PLT_F32, 2e-5), (B.PLT_BF16, 2e-2)])
+def test_edge_cases_single_token_prompt_and_window_larger_than_context(dtype, tol):
+    """Prompt of one token (position 0 sees only itself; every loop gets a zero shifted-in state),
+    a window larger than the whole run, batch 1, and decoding right up to max_ctx."""
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,
+                             ffn_hidden=192, vocab=300, n_loops=3, window=200)
+    weights = lively_weights(shape, 21, bf16=dtype == B.PLT_BF16, std=0.02)
+    prompts = synth.token_ids((1, 1), shape.vocab, 22)
+    run_teacher_forced(shape, dtype, B.PLT_MODE_CLP, weights, prompts, 6, tol)
+
+
+def test_window_one_and_many_loops():
+    """w = 1: the window holds only the current position, so the local branch returns its own value row."""
+    shape = synth.ModelShape(n_layers=1, d_model=64, n_heads=2, n_kv_heads=1, head_dim=64,
+                             ffn_hidden=64, vocab=100, n_loops=6, window=1)
+    weights = lively_weights(shape, 23, bf16=True, std=0.02)
+    prompts = synth.token_ids((2, 7), shape.vocab, 24)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 5, 2e-2)
+
+
+def test_prefill_then_prefill_restarts_the_cache():
+    shape = synth.ModelShape(n_layers=1, d_model=64, n_heads=2, n_kv_heads=2, head_dim=64,
+                             ffn_hidden=64, vocab=100, n_loops=2, window=4)
+    weights = lively_weights(shape, 25, bf16=False, std=0.05)
+    cfg = B.make_config(shape, dtype=B.PLT_F32)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    kv = B.KV(model, 1, 32)
+    p1 = synth.token_ids((1, 20), shape.vocab, 26)
+    p2 = synth.token_ids((1, 9), shape.vocab, 27)
+    kv.prefill(dev_tokens(p1))
+    a = kv.prefill(dev_tokens(p2))[1].cpu().numpy().copy()
+    kv_fresh = B.KV(model, 1, 32)
+    b = kv_fresh.prefill(dev_tokens(p2))[1].cpu().numpy().copy()
+    assert kv.position == 9 and np.array_equal(a, b)
+    # and the next decode step must not see anything of the first, longer prompt
+    t = dev_tokens(np.array([5]))
+    assert np.array_equal(kv.decode_step(t)[1].cpu().numpy(), kv_fresh.decode_step(t)[1].cpu().numpy())
+    kv.close(); kv_fresh.close(); model.close()
