@@ -4,9 +4,8 @@
 //   first-loop rows : y = Attn(q, K_share, V_share)                                  [Sec. 2.2.1]
 //   other rows      : y = g * SWA(q, own K/V, w) + (1 - g) * Attn(q, K_share, V_share),
 //                     g = sigmoid(z)                                      [Alg. 3 l.2-5, Eq. (2)]
-// Decode: the rows are the L loop stages x G query heads of one (sequence, kv head); K_share /
-// V_share are streamed from HBM exactly once for all of them.  Prefill: the rows are 16
-// consecutive positions of one query head, with per-row causal / window bounds.
+// The rows are the L loop stages x G query heads of one (sequence, kv head); K_share / V_share are
+// streamed from HBM exactly once for all of them.  (The prefill counterpart lives in attn_prefill.hip.)
 //
 // Tile algebra (one wave, 32 keys at a time, v_mfma_f32_16x16x32_bf16):
 //   S^T[key][row] = K[key][:] . Q[row][:]      A = K rows straight from HBM (16 B per lane),
@@ -373,99 +372,6 @@ void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf1
     hipLaunchKernelGGL(k_attn_decode<128>, grid, dim3(256), 0, s, A);
     if (A.n_splits > 1) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, s, A);
   }
-}
-
-// ------------------------------------------------------------------------------- prefill
-// Rows = 16 consecutive positions p0..p0+15 of one query head; keys of the shared cache with
-// j <= p_row; for loops >= 2 also the loop's own keys with p_row - w < j <= p_row, then Eq. (2).
-
-struct AttnPreArgs {
-  const bf16_t* q; const float* z; bf16_t* y;
-  const bf16_t* k_share; const bf16_t* v_share; const bf16_t* k_loc; const bf16_t* v_loc;
-  int n, n_pad, n_pad_loc, w, b0, Hq, Hkv, G, gated;
-  float scale_log2;
-};
-
-template <int D>
-__global__ __launch_bounds__(256) void k_attn_prefill(AttnPreArgs A) {
-  __shared__ WgMerge<D> sm;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z, kvh = h / A.G;
-  const int p0 = qt * 16;
-  const int prow = p0 + m16;                       // this lane's query position
-  const bool prow_ok = prow < A.n;
-  uint4 qf[D / 32];
-#pragma unroll
-  for (int kk = 0; kk < D / 32; ++kk) {
-    qf[kk] = make_uint4(0, 0, 0, 0);
-    if (prow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.n + prow) * A.Hq + h) * D + kk * 32 + g * 8);
-  }
-  const int p_last = (p0 + 15 < A.n ? p0 + 15 : A.n - 1);
-  WaveState<D> st; st.init();
-  {
-    const size_t stream = (size_t)(A.b0 + b) * A.Hkv + kvh;
-    const bf16_t* kbase = A.k_share + stream * (size_t)A.n_pad * D;
-    const bf16_t* vbase = A.v_share + stream * (size_t)A.n_pad * D;
-    const int t_end = (p_last >> 5) + 1;
-    for (int t = wv; t < t_end; t += 4) {
-      KvTile<D> cur;
-      load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
-      const int kb = t * 32 + 8 * g;
-      tile_step<D>(st, cur, qf, A.scale_log2, t * 32 + 31 > p0, [&](int j) { return kb + j <= prow; });
-    }
-  }
-  float Mg, Lg, og[D / 16];
-  wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
-  float Ml = NEG_INF, Ll = 0.f, ol[D / 16];
-#pragma unroll
-  for (int i = 0; i < D / 16; ++i) ol[i] = 0.f;
-  if (A.gated) {
-    st.init();
-    const size_t stream = (size_t)b * A.Hkv + kvh;
-    const bf16_t* kbase = A.k_loc + stream * (size_t)A.n_pad_loc * D;
-    const bf16_t* vbase = A.v_loc + stream * (size_t)A.n_pad_loc * D;
-    int j_lo = p0 - A.w + 1; if (j_lo < 0) j_lo = 0;
-    const int t_beg = j_lo >> 5, t_end = (p_last >> 5) + 1;
-    for (int t = t_beg + wv; t < t_end; t += 4) {
-      KvTile<D> cur;
-      load_tile<D>(cur, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
-      const int kb = t * 32 + 8 * g;
-      tile_step<D>(st, cur, qf, A.scale_log2, true,
-                   [&](int j) { return (kb + j <= prow) && (kb + j > prow - A.w); });
-    }
-    wg_merge<D>(sm, st, wv, m16, g, Ml, Ll, ol);
-  }
-  const int pr = p0 + (tid >> 4), dc = (tid & 15) * (D / 16);
-  if (pr >= A.n) return;
-  const size_t r = (size_t)b * A.n + pr;
-  float out[D / 16];
-  const float invg = Lg > 0.f ? 1.0f / Lg : 0.f;
-  if (A.gated) {
-    const float zz = A.z[r * A.Hq + h];
-    const float gate = 1.0f / (1.0f + __expf(-zz));
-    const float invl = Ll > 0.f ? 1.0f / Ll : 0.f;
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) out[i] = gate * (ol[i] * invl) + (1.0f - gate) * (og[i] * invg);
-  } else {
-#pragma unroll
-    for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
-  }
-  store_row<D>(A.y + (r * A.Hq + h) * D + dc, out);
-}
-
-void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
-                              int Bc, int n, int loop, Dims dm, int plain) {
-  AttnPreArgs A;
-  A.q = q; A.z = z; A.y = y;
-  A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
-  A.k_loc = (const bf16_t*)kv.k_loc; A.v_loc = (const bf16_t*)kv.v_loc;
-  A.n = n; A.n_pad = kv.n_pad; A.n_pad_loc = kv.n_pad_loc; A.w = kv.w; A.b0 = kv.b0;
-  A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
-  A.gated = (!plain && loop > 0) ? 1 : 0;
-  A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
-  dim3 grid((n + 15) / 16, dm.Hq, Bc);
-  if (dm.D == 64) hipLaunchKernelGGL(k_attn_prefill<64>, grid, dim3(256), 0, s, A);
-  else hipLaunchKernelGGL(k_attn_prefill<128>, grid, dim3(256), 0, s, A);
 }
 
 }  // namespace plt

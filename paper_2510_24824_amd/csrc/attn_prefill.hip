@@ -1,0 +1,261 @@
+// Prefill attention on gfx950 matrix cores (bf16 storage, float statistics): the token-parallel
+// form of the PLT attention [Alg. 2 forward; Alg. 3 l.2-5 for loops >= 2].
+//
+//   loop 1      : y[p] = Attn(q[p], K_share[0..p], V_share[0..p])                 (causal)
+//   loops >= 2  : y[p] = g * Attn(q[p], K_own[p-w+1..p], V_own[..]) + (1-g) * Attn(q[p], K_share[0..p], ..)
+//
+// A workgroup owns 128 consecutive positions of one query head: 4 waves x 2 tiles of 16 query
+// rows.  Key/value tiles of 32 positions are copied once per workgroup from the cache into LDS
+// (next tile prefetched into registers meanwhile) and every fragment a wave reads from LDS feeds
+// both of its query tiles, so a K/V byte fetched from L2 is used by 128 query rows.  The tile
+// algebra is the decode kernel's: S^T = K Q^T, O^T += V^T P^T with v_mfma_f32_16x16x32_bf16, one
+// query row per lane in S^T, P^T and O^T, row maxima via two wavefront shuffles.  A wave owns its
+// rows for the whole key range, so no cross-wave merge is needed.
+#include "plt_internal.h"
+
+namespace plt {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) float f32x8;
+
+namespace {
+
+constexpr int PF_QROWS = 128;                 // query positions per workgroup
+#define PF_NEG_INF (-INFINITY)
+
+__device__ inline bf16x8 pf_bf(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+template <int D>
+struct PfState {           // online softmax state of one 16-row query tile
+  float m, l;
+  f32x4 acc[D / 16];
+  __device__ void init() {
+    m = PF_NEG_INF; l = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+};
+
+template <int D>
+struct PfLds {
+  bf16_t k[32][D + 8];     // 32 key rows, padded: conflict-light 16-byte fragment reads
+  bf16_t v[D][32];         // the cache's V block as is: [feature][position]
+};
+
+// One 32-key tile for the two query tiles of a wave.  lo/hi: per lane (= per query row) bounds,
+// key j is attended iff lo < j <= hi.
+template <int D>
+__device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D>& sm, const uint4 (&qf)[2][D / 32],
+                               float scale_log2, int key_base, bool need_mask, const int (&lo)[2],
+                               const int (&hi)[2], int m16, int g) {
+  const int key0 = 8 * (m16 >> 2) + (m16 & 3);
+  f32x4 s[2][2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) { s[q][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[q][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+  for (int kk = 0; kk < D / 32; ++kk) {
+    const uint4 k0 = *reinterpret_cast<const uint4*>(&sm.k[key0][kk * 32 + g * 8]);
+    const uint4 k1 = *reinterpret_cast<const uint4*>(&sm.k[key0 + 4][kk * 32 + g * 8]);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      s[q][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k0), pf_bf(qf[q][kk]), s[q][0], 0, 0, 0);
+      s[q][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k1), pf_bf(qf[q][kk]), s[q][1], 0, 0, 0);
+    }
+  }
+  bf16x8 pb[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    float sv[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { sv[i] = s[q][0][i] * scale_log2; sv[4 + i] = s[q][1][i] * scale_log2; }
+    if (need_mask) {
+      const int kb = key_base + 8 * g;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) if (kb + j > hi[q] || kb + j <= lo[q]) sv[j] = PF_NEG_INF;
+    }
+    float mx = sv[0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st[q].m, mx);
+    const float m_safe = (m_new == PF_NEG_INF) ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f(st[q].m - m_safe);
+    f32x8 p; float ps = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(sv[j] - m_safe); ps += p[j]; }
+    st[q].l = st[q].l * alpha + ps;
+    st[q].m = m_new;
+    pb[q] = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      st[q].acc[dt][0] *= alpha; st[q].acc[dt][1] *= alpha; st[q].acc[dt][2] *= alpha; st[q].acc[dt][3] *= alpha;
+    }
+  }
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) {
+    const uint4 vf = *reinterpret_cast<const uint4*>(&sm.v[dt * 16 + m16][g * 8]);
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      st[q].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(vf), pb[q], st[q].acc[dt], 0, 0, 0);
+  }
+}
+
+struct PfArgs {
+  const bf16_t* q; const float* z; bf16_t* y;
+  float* tmp;      // [rows, Hq*D] float: g * y_local parked between the two passes (gated rows only)
+  const bf16_t* k_share; const bf16_t* v_share; const bf16_t* k_loc; const bf16_t* v_loc;
+  int n, n_pad, n_pad_loc, w, b0, Hq, Hkv, G, gated, n_qt;
+  float scale_log2;
+};
+
+// Streams key tiles t_beg..t_end-1 of one K/V stream through LDS and applies them to the wave's
+// two query tiles.  All 256 threads of the workgroup must call this together.
+template <int D>
+__device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const bf16_t* __restrict__ kbase,
+                               const bf16_t* __restrict__ vbase, int t_beg, int t_end, const uint4 (&qf)[2][D / 32],
+                               float scale_log2, const int (&lo)[2], const int (&hi)[2], int row_min, int row_max,
+                               int m16, int g) {
+  const int tid = threadIdx.x;
+  constexpr int KCH = 32 * D / 8 / 256;       // 16-byte chunks of the K tile per thread (1 or 2)
+  // register staging of the next tile (plain loops: the arrays must stay in registers)
+  uint4 rk[KCH], rv[KCH];
+#pragma unroll
+  for (int i = 0; i < KCH; ++i) { rk[i] = make_uint4(0, 0, 0, 0); rv[i] = make_uint4(0, 0, 0, 0); }
+  if (t_beg < t_end) {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      rk[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)t_beg * 32 * D + (size_t)(tid + i * 256) * 8);
+      rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t_beg * 32 * D + (size_t)(tid + i * 256) * 8);
+    }
+  }
+  for (int t = t_beg; t < t_end; ++t) {
+    __syncthreads();                         // every wave is done with the previous tile
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      const int ch = tid + i * 256;
+      const int row = ch / (D / 8), col = (ch % (D / 8)) * 8;
+      *reinterpret_cast<uint4*>(&sm.k[row][col]) = rk[i];
+      *reinterpret_cast<uint4*>(&sm.v[ch / 4][(ch % 4) * 8]) = rv[i];
+    }
+    __syncthreads();
+    if (t + 1 < t_end) {
+#pragma unroll
+      for (int i = 0; i < KCH; ++i) {
+        rk[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)(t + 1) * 32 * D + (size_t)(tid + i * 256) * 8);
+        rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)(t + 1) * 32 * D + (size_t)(tid + i * 256) * 8);
+      }
+    }
+    const int kb = t * 32;
+    // skip tiles no row of this wave may attend; mask only tiles that straddle a bound
+    int lo_min = lo[0] < lo[1] ? lo[0] : lo[1];
+    lo_min = __shfl(lo_min, 0, 64);          // rows ascend with the lane: lane 0 holds the smallest bound
+    if (kb > row_max || kb + 31 <= lo_min) continue;
+    const bool need_mask = (kb + 31 > row_min) || (kb <= __shfl(lo[1], 15, 64));
+    pf_tile<D>(st, sm, qf, scale_log2, kb, need_mask, lo, hi, m16, g);
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
+  __shared__ __attribute__((aligned(16))) PfLds<D> sm;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int qt = A.n_qt - 1 - (int)blockIdx.x;        // longest key ranges first
+  const int h = blockIdx.y, b = blockIdx.z, kvh = h / A.G;
+  const int p0 = qt * PF_QROWS;
+  const int p_last = (p0 + PF_QROWS - 1 < A.n ? p0 + PF_QROWS - 1 : A.n - 1);
+  // this lane's two query rows
+  int prow[2], hi[2], lo_g[2], lo_l[2];
+  uint4 qf[2][D / 32];
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    prow[q] = p0 + wv * 32 + q * 16 + m16;
+    const bool ok = prow[q] < A.n;
+    hi[q] = ok ? prow[q] : -1;                         // rows beyond the prompt attend nothing
+    lo_g[q] = -1;
+    lo_l[q] = prow[q] - A.w;                           // monotone in the row, also for rows beyond the prompt
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk) {
+      qf[q][kk] = make_uint4(0, 0, 0, 0);
+      if (ok) qf[q][kk] = *reinterpret_cast<const uint4*>(A.q + (((size_t)b * A.n + prow[q]) * A.Hq + h) * D + kk * 32 + g * 8);
+    }
+  }
+  const int row_min = p0 + wv * 32, row_max_raw = p0 + wv * 32 + 31;
+  const int row_max = row_max_raw < A.n ? row_max_raw : A.n - 1;
+
+  // One softmax state is live at a time: the window pass runs first and parks g * y_local (float)
+  // in a scratch row that the same lane reads back in the epilogue of the global pass.
+  PfState<D> st[2];
+  float gate[2] = {0.f, 0.f};
+  if (A.gated) {
+    st[0].init(); st[1].init();
+    const size_t stream = (size_t)b * A.Hkv + kvh;
+    int j_lo = p0 - A.w + 1; if (j_lo < 0) j_lo = 0;
+    pf_pass<D>(st, sm, A.k_loc + stream * (size_t)A.n_pad_loc * D, A.v_loc + stream * (size_t)A.n_pad_loc * D,
+               j_lo >> 5, (p_last >> 5) + 1, qf, A.scale_log2, lo_l, hi, row_min, row_max, m16, g);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      if (prow[q] >= A.n) continue;
+      float ll = st[q].l; ll += __shfl_xor(ll, 16, 64); ll += __shfl_xor(ll, 32, 64);
+      const size_t r = (size_t)b * A.n + prow[q];
+      gate[q] = 1.0f / (1.0f + __expf(-A.z[r * A.Hq + h]));
+      const float f = ll > 0.f ? gate[q] / ll : 0.f;
+      float* dst = A.tmp + (r * A.Hq + h) * D;
+#pragma unroll
+      for (int dt = 0; dt < D / 16; ++dt) {
+        f32x4 v = st[q].acc[dt];
+        v[0] *= f; v[1] *= f; v[2] *= f; v[3] *= f;
+        *reinterpret_cast<f32x4*>(dst + dt * 16 + 4 * g) = v;
+      }
+    }
+  }
+  st[0].init(); st[1].init();
+  {
+    const size_t stream = (size_t)(A.b0 + b) * A.Hkv + kvh;
+    pf_pass<D>(st, sm, A.k_share + stream * (size_t)A.n_pad * D, A.v_share + stream * (size_t)A.n_pad * D, 0,
+               (p_last >> 5) + 1, qf, A.scale_log2, lo_g, hi, row_min, row_max, m16, g);
+  }
+  // epilogue: lane (row m16, g) holds features dt*16 + 4g .. +3 of its two rows
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    if (prow[q] >= A.n) continue;
+    float lg = st[q].l; lg += __shfl_xor(lg, 16, 64); lg += __shfl_xor(lg, 32, 64);
+    const float fg = (lg > 0.f ? 1.0f / lg : 0.f) * (1.0f - gate[q]);     // gate = 0 for first-loop rows
+    const size_t r = (size_t)b * A.n + prow[q];
+    bf16_t* dst = A.y + (r * A.Hq + h) * D;
+    const float* loc = A.tmp + (r * A.Hq + h) * D;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      f32x4 v = st[q].acc[dt];
+      v[0] *= fg; v[1] *= fg; v[2] *= fg; v[3] *= fg;
+      if (A.gated) {
+        const f32x4 t = *reinterpret_cast<const f32x4*>(loc + dt * 16 + 4 * g);
+        v[0] += t[0]; v[1] += t[1]; v[2] += t[2]; v[3] += t[3];
+      }
+      ushort4 o;
+      o.x = f32_to_bf16(v[0]); o.y = f32_to_bf16(v[1]); o.z = f32_to_bf16(v[2]); o.w = f32_to_bf16(v[3]);
+      *reinterpret_cast<ushort4*>(dst + dt * 16 + 4 * g) = o;
+    }
+  }
+}
+
+}  // namespace
+
+void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
+                              KvView kv, int Bc, int n, int loop, Dims dm, int plain) {
+  PfArgs A;
+  A.q = q; A.z = z; A.y = y; A.tmp = local_tmp;
+  A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
+  A.k_loc = (const bf16_t*)kv.k_loc; A.v_loc = (const bf16_t*)kv.v_loc;
+  A.n = n; A.n_pad = kv.n_pad; A.n_pad_loc = kv.n_pad_loc; A.w = kv.w; A.b0 = kv.b0;
+  A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
+  A.gated = (!plain && loop > 0) ? 1 : 0;
+  A.n_qt = (n + PF_QROWS - 1) / PF_QROWS;
+  A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
+  dim3 grid(A.n_qt, dm.Hq, Bc);
+  if (dm.D == 64) hipLaunchKernelGGL(k_attn_prefill2<64>, grid, dim3(256), 0, s, A);
+  else hipLaunchKernelGGL(k_attn_prefill2<128>, grid, dim3(256), 0, s, A);
+}
+
+}  // namespace plt

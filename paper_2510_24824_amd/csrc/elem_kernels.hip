@@ -175,7 +175,11 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     // angle in turns, reduced in double (exact to ~1e-13), then a float sine / cosine
     double t = (double)p * inv_freq[j] * 0.15915494309189535;
     t -= rint(t);
-    sincosf((float)(t * 6.283185307179586), &sn, &c);
+    if (sizeof(T) == 2) {            // bf16 models: hardware sine / cosine of an angle given in turns
+      sn = __builtin_amdgcn_sinf((float)t); c = __builtin_amdgcn_cosf((float)t);
+    } else {
+      sincosf((float)(t * 6.283185307179586), &sn, &c);
+    }
   }
   if (hs < Hq) {
     if (!plain && l > 0) {

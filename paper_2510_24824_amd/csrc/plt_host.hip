@@ -327,6 +327,7 @@ static KvView kv_view(const plt_kv* kv, int layer, int cache) {
 // ------------------------------------------------------------------------------ scheduler
 struct Work {            // activation buffers one pass of the stack runs on
   float* x; void* a; float* gout; void* q; float* z; void* y; void* act;
+  float* attn_tmp;   // prefill only: float [rows, Hq*D]
 };
 
 static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int M, int N, int K,
@@ -361,7 +362,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
       ProfScope prof(m, PLT_PROF_ATTN, dec);
       if (rm.prefill) {
-        launch_attn_prefill_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, Bc, n_prefill,
+        launch_attn_prefill_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, wk.attn_tmp, v, Bc, n_prefill,
                                  rm.loop_fixed, dm, plain ? 1 : 0);
       } else {
         const int G = Hq / Hkv;
@@ -400,7 +401,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
   const plt_config& c = m->cfg;
   hipStream_t s = m->stream;
   const int B = kv->B, L = c.n_loops, d = c.d_model;
-  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act};
+  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr};
   KvView none{}; none.b0 = 0;
   if (is_clp(c)) {
     // Alg. 1 l.5-7: rows B_0 = e, B_l = e + H^l[p-1]; the L rows of a sequence run as one pass
@@ -463,12 +464,14 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * es),
                o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
                o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * F * es),
-               o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * es), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * es);
+               o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * es), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * es),
+               o_tmp = carve((L > 1 && is_clp(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
   char* ws = nullptr;
   hipError_t e = hipMalloc((void**)&ws, off);
   if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
   (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * es), s);
-  Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act};
+  Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act,
+          (float*)(ws + o_tmp)};
   float* hprev = (float*)(ws + o_h);
   for (int b0 = 0; b0 < B; b0 += Bc) {
     const int bc = b0 + Bc <= B ? Bc : B - b0;

@@ -113,7 +113,8 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx);
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform,
                              Dims dm, int plain, void* scratch, int n_splits);
-void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
-                              int Bc, int n, int loop, Dims dm, int plain);
+// local_tmp: float scratch [Bc*n, Hq*D] (used by loops >= 2 only)
+void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
+                              KvView kv, int Bc, int n, int loop, Dims dm, int plain);
 
 }  // namespace plt
