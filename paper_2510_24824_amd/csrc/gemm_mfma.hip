@@ -255,6 +255,7 @@ bool gemm_use_wstream(int M, int N, int K) { return M <= 256 && N >= 16; }
 // splits for the generic entry: the streaming kernel always splits K in ranges of 512
 int gemm_bf16_splits_any(int M, int N, int K) {
   if (gemm_use_wstream(M, N, K)) return (K + WS_KR - 1) / WS_KR;
+  if (gemm_big_applies(M, N, K)) return 1;
   return gemm_bf16_splits(M, N, K);
 }
 
@@ -271,7 +272,11 @@ static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c,
 }
 
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
-  if (!gemm_use_wstream(M, N, K)) { launch_gemm_bf16(s, a, w, c, M, N, K, gemm_bf16_splits(M, N, K)); return; }
+  if (!gemm_use_wstream(M, N, K)) {
+    if (gemm_big_applies(M, N, K)) launch_gemm_big(s, a, w, c, M, N, K);
+    else launch_gemm_bf16(s, a, w, c, M, N, K, gemm_bf16_splits(M, N, K));
+    return;
+  }
   const int S = (K + WS_KR - 1) / WS_KR;
   const bool small = M <= 64;
   const int rbs = small ? 1 : (M + 127) / 128;

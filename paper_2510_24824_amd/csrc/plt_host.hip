@@ -376,8 +376,12 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     }
     S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);                                     // Alg. 3 l.6
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
-    S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
-    launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
+    if (c.dtype == PLT_BF16 && gemm_big_applies(R, 2 * F, d)) {      // many rows: SwiGLU fused into the GEMM epilogue
+      launch_gemm_big_swiglu(s, (const bf16_t*)wk.a, (const bf16_t*)w.wgu, (bf16_t*)wk.act, R, F, d);
+    } else {
+      S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
+      launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
+    }
     S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
     const float* gain = l + 1 < c.n_layers ? m->layers[l + 1].norm1 : next_gain;
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, gain, c.norm_eps,

@@ -99,7 +99,11 @@ void launch_gemm_f32(hipStream_t s, const float* a, const float* w, float* c, in
 int gemm_bf16_splits(int M, int N, int K);
 void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N,
                       int K, int splits);
-// picks the weight-streaming kernel for few rows, the tiled one otherwise
+// gemm_big.hip: many rows (prefill), 256 x 128 tiles, no split-K; optional fused SwiGLU epilogue
+bool gemm_big_applies(int M, int N, int K);
+void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
+void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K);
+// picks the weight-streaming kernel for few rows, the big-tile one for many, the small-tile one between
 int gemm_bf16_splits_any(int M, int N, int K);
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
 
