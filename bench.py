@@ -232,6 +232,34 @@ def bench_long_context(B, shape, blob, g, steps):
     return res
 
 
+def bench_prefill(B, shape, blob, g, Bn=4, n=8192, L=3, w=64, reps=2):
+    """CLP prefill / forward (Alg. 2) of Bn prompts of n uniform token ids at L loops: all loops with the
+    cross-loop shift in one call.  MFMA-bound (projections + causal attention); flops counted as
+    2 * params * tokens * L for the projections plus 4 * D * (n^2/2 + (L-1)/L * n * w) per head and loop
+    for the attention.  Returns time, tokens/s and the matrix-core roofline fraction."""
+    import torch
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=L, window=w)
+    m = B.Model(cfg, blob)
+    kv = B.KV(m, Bn, n + 1)
+    prompt = torch.randint(0, shape.vocab, (Bn, n), generator=g, device="cuda", dtype=torch.int32)
+    kv.prefill(prompt, want_logits=False); torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        kv.prefill(prompt, want_logits=False)
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / reps
+    params = shape.n_layers * ((shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim * shape.d_model
+                               + shape.d_model * shape.n_heads * shape.head_dim + 3 * shape.ffn_hidden * shape.d_model)
+    fl_gemm = 2.0 * params * Bn * n * L + 2.0 * shape.vocab * shape.d_model * Bn
+    fl_attn = 4.0 * shape.head_dim * shape.n_heads * Bn * shape.n_layers * (L * n * n / 2 + (L - 1) * n * min(w, n))
+    kv.close(); m.close(); del kv
+    torch.cuda.empty_cache()
+    tf = (fl_gemm + fl_attn) / dt / 1e12
+    return {"workload": f"CLP prefill, ~1.3B PLT, bf16, L={L}, window {w}, batch {Bn}, {n}-token prompts (configs[4])",
+            "ms": dt * 1e3, "tokens_per_s": Bn * n / dt, "flops_projections": fl_gemm, "flops_attention": fl_attn,
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
+
+
 def read_traffic(name):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if a summary
     under profiles/ records it as a line `<name> = <bytes>`; else None."""
@@ -254,6 +282,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--only-main", action="store_true", help="skip the baselines, the L sweep and the kernel-only run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--prefill", action="store_true", help="also time the CLP prefill of 4 x 8192 tokens at L=3")
     ap.add_argument("--long-context", action="store_true",
                     help="also time one GPU's share of the L=4, window 128, 8192-token configuration (batch 128 resident)")
     ap.add_argument("--batch", type=int, default=64)
@@ -369,6 +398,9 @@ def main():
         out["latency_vs_nonlooped"] = {k: v / base for k, v in lat.items()}
         out["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup)
 
+    if args.prefill:
+        out["prefill"] = bench_prefill(B, shape, blob, g)
+        log(f"[bench] prefill 4 x 8192, L=3: {out['prefill']['ms']:.0f} ms, {out['prefill']['roofline']['achieved']:.0f} TFLOP/s")
     if args.long_context:
         out["long_context"] = bench_long_context(B, shape, blob, g, max(4, args.steps // 4))
 

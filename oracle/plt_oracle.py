@@ -13,6 +13,7 @@ Every function cites the passage of the paper (arxiv 2510.24824) it follows:
   Alg. 3    non-first-loop attention            -> gated_attention_row / decode_attention
   Eq. (2)   sigmoid gate merge                  -> gate_merge
   Sec. 2.2.2  first-loop KV sharing, window of the most recent w entries -> RingKV
+  Table 1 rows 3 and 4 (ablations: CLP with per-loop KV; CLP + KV share without the window) -> variant=
 
 Where the paper is silent the following readings are taken (each also listed in the
 design notes of the repository):
@@ -197,12 +198,22 @@ class RingKV:
         self.kr = np.zeros((nl, s.n_layers, s.window, s.n_kv_heads, s.head_dim))
         self.vr = np.zeros_like(self.kr)
 
+    def _cache(self, cache_id):
+        if cache_id == 1:
+            return self.ks, self.vs
+        if not hasattr(self, "extra"):
+            self.extra = {}
+        if cache_id not in self.extra:                # own-KV variant: one more full cache per loop
+            self.extra[cache_id] = (np.zeros_like(self.ks), np.zeros_like(self.vs))
+        return self.extra[cache_id]
+
     def put_global(self, cache_id, m, p, k, v):
-        assert cache_id == 1
-        self.ks[m, p] = self._store(k); self.vs[m, p] = self._store(v)
+        ks, vs = self._cache(cache_id)
+        ks[m, p] = self._store(k); vs[m, p] = self._store(v)
 
     def get_global(self, cache_id, m, p):
-        return self.ks[m, :p + 1], self.vs[m, :p + 1]
+        ks, vs = self._cache(cache_id)
+        return ks[m, :p + 1], vs[m, :p + 1]
 
     def put_local(self, l, m, p, k, v, w):
         self.kr[l - 2, m, p % w] = self._store(k); self.vr[l - 2, m, p % w] = self._store(v)
@@ -221,7 +232,13 @@ class RingKV:
 class PLTOracle:
     """One sequence at a time (sequences of a batch never interact)."""
 
-    def __init__(self, shape: OracleShape, weights: dict, kv_bf16: bool = False):
+    def __init__(self, shape: OracleShape, weights: dict, kv_bf16: bool = False, variant: str = "plt"):
+        """variant selects the row of Table 1 that is computed (all share the cross-loop shift):
+          "plt"            row 5: shared first-loop KV + gated sliding window (the method)
+          "clp_share_only" row 4: non-first loops attend the shared first-loop KV only (no own K/V, no gate)
+          "clp_own_kv"     row 3: every loop keeps and attends its own full KV cache (no sharing, no gate)"""
+        assert variant in ("plt", "clp_share_only", "clp_own_kv")
+        self.variant = variant
         self.s = shape
         self.w = weights
         self.kv_bf16 = kv_bf16
@@ -242,23 +259,29 @@ class PLTOracle:
         G = Hq // Hkv
         x = np.asarray(x, np.float64).copy()
         first = plain or l == 1
+        share_only = False
+        if not plain and l >= 2:
+            if self.variant == "clp_own_kv":          # Table 1 row 3: loop l on its own cache l
+                first, global_cache_id = True, l
+            elif self.variant == "clp_share_only":    # Table 1 row 4: global branch only
+                share_only = True
         for m in range(s.n_layers):
             W = self.w["layers"][m]
             a = rmsnorm(x, W["norm1"], s.norm_eps)
             q = (np.asarray(W["wq"], np.float64) @ a).reshape(Hq, D)          # Alg. 3 l.1
             k = (np.asarray(W["wk"], np.float64) @ a).reshape(Hkv, D)
             v = (np.asarray(W["wv"], np.float64) @ a).reshape(Hkv, D)
-            if not first:                                                        # Alg. 3 l.4
+            if not first and not share_only:                                     # Alg. 3 l.4
                 z = np.sum(q * np.asarray(W["gate_w"], np.float64), axis=-1) + np.asarray(W["gate_b"], np.float64)
             qr = rope(q, p, s.rope_theta)
             kr = rope(k, p, s.rope_theta)
             if first:
                 kv.put_global(global_cache_id, m, p, kr, v)
-            else:
+            elif not share_only:
                 kv.put_local(l, m, p, kr, v, s.window)
             Kg, Vg = kv.get_global(global_cache_id, m, p)                        # [p+1, Hkv, D]
             y = np.zeros((Hq, D))
-            if first:
+            if first or share_only:
                 for h in range(Hq):
                     y[h] = softmax_attend(qr[h], Kg[:, h // G], Vg[:, h // G])
             else:

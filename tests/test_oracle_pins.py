@@ -307,3 +307,39 @@ def test_greedy_generate_matches_teacher_forced_forward():
     _, lg = orc.seq_forward(full)
     assert [int(np.argmax(lg[p])) for p in range(4, 14)] == ids
     assert np.max(np.abs(lgs - lg[4:14])) < 1e-10
+
+
+# ---- Table 1 rows 3 and 4: the two ablation variants of the oracle
+def test_variant_own_kv_equals_plain_stacks_on_shifted_inputs():
+    """Row 3 (loop + CLP, per-loop KV): every loop is an ordinary transformer pass on E + shift(H)."""
+    shape = oshape(SMALL, n_loops=3)
+    wts = small_weights()
+    toks = synth.token_ids((11,), SMALL.vocab, seed=31)
+    orc = O.PLTOracle(shape, wts, variant="clp_own_kv")
+    H, lg = orc.seq_forward(toks)
+    Ht, lgt = T.plt_forward(toks, wts, shape, variant="clp_own_kv")
+    assert np.max(np.abs(H - Ht.numpy())) < 1e-10 and np.max(np.abs(lg - lgt.numpy())) < 1e-10
+    orc.clp_prefill(toks[:4], 16)
+    for t in toks[4:]:
+        orc.clp_decode_step(t)
+    assert np.max(np.abs(np.stack(orc.trace).transpose(1, 0, 2) - H)) < 1e-10       # CLP == sequential
+
+
+def test_variant_share_only_equals_plt_with_closed_gate():
+    """Row 4 (CLP + KV share, no window): identical to the full method when the gate is shut
+    (g -> 0 keeps only the global branch, Eq. 2)."""
+    shape = oshape(SMALL, n_loops=3, window=3)
+    wts = small_weights()
+    toks = synth.token_ids((10,), SMALL.vocab, seed=32)
+    orc = O.PLTOracle(shape, wts, variant="clp_share_only")
+    H, lg = orc.seq_forward(toks)
+    shut = {**wts, "layers": [{**lw, "gate_w": np.zeros_like(lw["gate_w"]), "gate_b": np.full_like(lw["gate_b"], -60.0)}
+                              for lw in wts["layers"]]}
+    H2, lg2 = O.PLTOracle(shape, shut, variant="plt").seq_forward(toks)
+    assert np.max(np.abs(H - H2)) < 1e-10 and np.max(np.abs(lg - lg2)) < 1e-10
+    Hp, _ = O.PLTOracle(shape, wts, variant="plt").seq_forward(toks)
+    assert np.max(np.abs(Hp[1:] - H[1:])) > 1e-6                                      # the window does matter
+    orc.clp_prefill(toks[:3], 16)
+    for t in toks[3:]:
+        orc.clp_decode_step(t)
+    assert np.max(np.abs(np.stack(orc.trace).transpose(1, 0, 2) - H)) < 1e-10

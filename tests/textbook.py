@@ -77,14 +77,18 @@ def head_logits(H, weights, shape):
     return F.linear(F.rms_norm(H, (shape.d_model,), t64(weights["norm_f"]), shape.norm_eps), t64(hw))
 
 
-def plt_forward(tokens, weights, shape):
-    """Token-parallel, loop-serial PLT forward (training-time form): returns H [L, n, d], logits."""
+def plt_forward(tokens, weights, shape, variant="plt"):
+    """Token-parallel, loop-serial PLT forward (training-time form): returns H [L, n, d], logits.
+    variant "clp_own_kv": every loop is a plain stack on E + shift(H) (own KV, no sharing, no gate)."""
     E = t64(weights["emb"])[torch.as_tensor(tokens, dtype=torch.long)]
     H1, kv = decoder_stack(E, weights, shape, return_kv=True)
     Hs = [H1]
     for _ in range(1, shape.n_loops):
         shifted = torch.cat([torch.zeros(1, shape.d_model, dtype=torch.float64), Hs[-1][:-1]], dim=0)
-        Hs.append(decoder_stack(E + shifted, weights, shape, shared_kv=kv, window=shape.window))
+        if variant == "clp_own_kv":
+            Hs.append(decoder_stack(E + shifted, weights, shape))
+        else:
+            Hs.append(decoder_stack(E + shifted, weights, shape, shared_kv=kv, window=shape.window))
     return torch.stack(Hs), head_logits(Hs[-1], weights, shape)
 
 
