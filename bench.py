@@ -384,7 +384,9 @@ def main():
         lat = {}
         for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
                                ("plt_L4", B.PLT_MODE_CLP, 4), ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2),
-                               ("vanilla_loop_L3", B.PLT_MODE_VANILLA_LOOP, 3), ("vanilla_loop_L4", B.PLT_MODE_VANILLA_LOOP, 4)]:
+                               ("vanilla_loop_L3", B.PLT_MODE_VANILLA_LOOP, 3), ("vanilla_loop_L4", B.PLT_MODE_VANILLA_LOOP, 4),
+                               # the paper's component table at L = 2: + CLP (per-loop KV), + KV share, + G-SWA (= plt_L2)
+                               ("clp_own_kv_L2", B.PLT_MODE_CLP_OWN_KV, 2), ("clp_share_only_L2", B.PLT_MODE_CLP_SHARE_ONLY, 2)]:
             c2 = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
             m2 = B.Model(c2, blob)
             k2 = B.KV(m2, Bn, N)
@@ -396,6 +398,10 @@ def main():
         base = lat["nonlooped_L1"]
         out["latency_ms"] = lat
         out["latency_vs_nonlooped"] = {k: v / base for k, v in lat.items()}
+        out["component_table_L2"] = {"rows": ["(1) non-looped", "(2) + loop-2 (sequential, 2x KV)", "(3) + CLP (per-loop KV)",
+                                              "(4) + KV share", "(5) + G-SWA = PLT-2"],
+                                     "ms": [lat["nonlooped_L1"], lat["vanilla_loop_L2"], lat["clp_own_kv_L2"],
+                                            lat["clp_share_only_L2"], lat["plt_L2"]]}
         out["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup)
 
     if args.prefill:

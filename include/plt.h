@@ -51,8 +51,12 @@ enum { PLT_F32 = 0, PLT_BF16 = 1 };
 /* mode: which schedule / cache organisation the model object runs.                        */
 enum {
   PLT_MODE_CLP = 0,          /* PLT: Alg. 1 decoding, shared first-loop KV, gated window    */
-  PLT_MODE_VANILLA_LOOP = 2  /* Eq. (1): L serial passes per token, one full cache per loop,
+  PLT_MODE_VANILLA_LOOP = 2, /* Eq. (1): L serial passes per token, one full cache per loop,
                                 no shift, no gate, no window (the paper's baseline row 2)   */
+  PLT_MODE_CLP_SHARE_ONLY = 3, /* Table 1 row 4: cross-loop parallel, non-first loops attend the
+                                shared first-loop cache only (no own K/V, no window, no gate) */
+  PLT_MODE_CLP_OWN_KV = 4    /* Table 1 row 3: cross-loop parallel, every loop keeps and attends
+                                its own full cache (no sharing, no window, no gate)         */
 };
 
 typedef struct plt_config {
@@ -95,7 +99,7 @@ void plt_free(plt_model* m);
 /* Bytes of device memory a KV object for `batch` sequences of up to max_ctx positions needs
  * (physical: positions are padded to multiples of 32), and the logical size
  * 2 * layers * Hkv * D * (n_ctx + (L-1) * w) * sizeof(elem) * batch of Table 1 (row 5; row 2
- * in vanilla-loop mode: 2 * layers * Hkv * D * L * n_ctx). */
+ * in vanilla-loop and own-KV modes: 2 * layers * Hkv * D * L * n_ctx; row 4: ... * n_ctx). */
 size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx);
 size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_t n_ctx);
 
@@ -134,7 +138,7 @@ int plt_kv_set_position(plt_kv* kv, int32_t pos);
  * element type = model dtype:
  *   shared K [Hkv, n, D], shared V [Hkv, n, D], then (CLP mode, L > 1) ring K
  *   [L-1, Hkv, w, D] and ring V [L-1, Hkv, w, D] in slot order (slot = position mod w).
- * `cache` selects the loop's cache in vanilla-loop mode (0-based), must be 0 otherwise.
+ * `cache` selects the loop's cache in vanilla-loop and own-KV modes (0-based), must be 0 otherwise.
  * host_nbytes must equal plt_kv_export_bytes(kv, n). */
 size_t plt_kv_export_bytes(const plt_kv* kv, int32_t n);
 int plt_kv_export(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n,

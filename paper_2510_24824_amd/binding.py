@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libplt.so")
 
 PLT_F32, PLT_BF16 = 0, 1
-PLT_MODE_CLP, PLT_MODE_VANILLA_LOOP = 0, 2
+PLT_MODE_CLP, PLT_MODE_VANILLA_LOOP, PLT_MODE_CLP_SHARE_ONLY, PLT_MODE_CLP_OWN_KV = 0, 2, 3, 4
 (PLT_W_EMB, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO, PLT_W_NORM2, PLT_W_WGU,
  PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD) = range(11)
 STATUS = {0: "PLT_OK", -1: "PLT_EINVAL", -2: "PLT_ENOMEM", -3: "PLT_ECTXFULL", -4: "PLT_EHIP", -5: "PLT_ESTATE"}
@@ -257,7 +257,7 @@ class KV:
 
     def get_hidden(self):
         c = self.model.cfg
-        rows = c.n_loops if c.mode == PLT_MODE_CLP else 1
+        rows = 1 if c.mode == PLT_MODE_VANILLA_LOOP else c.n_loops
         out = np.zeros((self.batch, rows, c.d_model), np.float32)
         _check(lib().plt_get_hidden(self.h, out.ctypes.data_as(_P), out.nbytes))
         return out

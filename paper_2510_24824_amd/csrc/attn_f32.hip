@@ -73,8 +73,9 @@ __global__ __launch_bounds__(64) void k_attn_f32(const float* __restrict__ q, co
   const float scale = 1.0f / sqrtf((float)D);
   {
     size_t stream = (size_t)bg * Hkv + kh;
-    attend_range<D>(qs, (const float*)kv.k_share + stream * kv.n_pad * D,
-                    (const float*)kv.v_share + stream * (size_t)kv.n_pad * D, 0, p + 1, scale, yg);
+    const size_t coff = plain == 3 ? (size_t)l * kv.cache_stride : 0;      // per-loop caches (own-KV ablation)
+    attend_range<D>(qs, (const float*)kv.k_share + coff + stream * kv.n_pad * D,
+                    (const float*)kv.v_share + coff + stream * (size_t)kv.n_pad * D, 0, p + 1, scale, yg);
   }
   const bool gated = !plain && l > 0;
   if (gated) {

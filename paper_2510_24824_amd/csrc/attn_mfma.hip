@@ -158,6 +158,7 @@ struct AttnDecArgs {
   int n_ctx_uniform, n_ring_uniform;
   int n_pad, w_pad, w, n_rings;
   int L, Hq, Hkv, G, n_rows, n_rt, n_splits, plain;
+  int l_off, l_stride;         // q / y row of (sequence b, loop l) = b * l_stride + l_off + l
   float scale_log2;
   float* part;                 // [stream][rt][split] records of (16 + 16 + 16*D) floats
   float* part_loc;             // [stream][rt] records of 16*D floats (normalised local branch)
@@ -184,7 +185,7 @@ __device__ inline void finalize_row(const AttnDecArgs& A, int b, int kvh, int rt
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
   }
-  store_row<D>(A.y + (((size_t)b * A.L + r_loop) * A.Hq + r_head) * D + dc, out);
+  store_row<D>(A.y + (((size_t)b * A.l_stride + A.l_off + r_loop) * A.Hq + r_head) * D + dc, out);
 }
 
 template <int D>
@@ -206,7 +207,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode(AttnDecArgs A) {
 #pragma unroll
   for (int kk = 0; kk < D / 32; ++kk) {
     qf[kk] = make_uint4(0, 0, 0, 0);
-    if (qrow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.L + q_loop) * A.Hq + q_head) * D + kk * 32 + g * 8);
+    if (qrow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.l_stride + A.l_off + q_loop) * A.Hq + q_head) * D + kk * 32 + g * 8);
   }
 
   // ---- global branch: this split's share of the shared cache, alternate tiles per wave ----
@@ -348,8 +349,9 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx) {
 
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform, Dims dm,
-                             int plain, void* scratch, int n_splits) {
+                             int plain, void* scratch, int n_splits, int l_off, int l_stride) {
   AttnDecArgs A;
+  A.l_off = l_off; A.l_stride = l_stride > 0 ? l_stride : dm.L;
   A.q = q; A.z = z; A.y = y;
   A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
   A.k_ring = (const bf16_t*)kv.k_ring; A.v_ring = (const bf16_t*)kv.v_ring;

@@ -151,7 +151,8 @@ template <typename T>
 __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
                               const float* __restrict__ gate_w, const float* __restrict__ gate_b,
                               T* __restrict__ q_out, float* __restrict__ z_out, KvView kv, RowMap rm,
-                              Dims dm, const double* __restrict__ inv_freq, int plain) {
+                              Dims dm, const double* __restrict__ inv_freq, int mode) {
+  // mode: 0 = PLT (rings + gate), 1 = plain, 2 = loops >= 2 append nothing, 3 = row of loop l -> cache l
   const int hs = blockIdx.x, r = blockIdx.y, j = threadIdx.x;
   const int D = dm.D, half = D / 2, Hq = dm.Hq, Hkv = dm.Hkv;
   const int ncol = (Hq + 2 * Hkv) * D;
@@ -182,7 +183,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     }
   }
   if (hs < Hq) {
-    if (!plain && l > 0) {
+    if (mode == 0 && l > 0) {
       float zp = act ? lo * gate_w[hs * D + j] + hi * gate_w[hs * D + j + half] : 0.f;
       zp = wave_sum(zp);
       if (j == 0) {
@@ -204,13 +205,15 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
   float v0 = lo, v1 = hi;
   if (is_k) { v0 = lo * c - hi * sn; v1 = hi * c + lo * sn; }
   const int bg = kv.b0 + b;
-  if (plain || l == 0) {                       // first loop: the shared cache [Sec. 2.2.2]
+  if (mode == 2 && l > 0) return;              // KV-share ablation: non-first loops keep no K/V
+  if (mode != 0 || l == 0) {                   // first loop: the shared cache [Sec. 2.2.2]
     size_t stream = (size_t)bg * Hkv + kh;
+    const size_t coff = mode == 3 ? (size_t)l * kv.cache_stride : 0;
     if (is_k) {
-      T* dst = (T*)kv.k_share + (stream * kv.n_pad + p) * D;
+      T* dst = (T*)kv.k_share + coff + (stream * kv.n_pad + p) * D;
       st<T>(dst + j, v0); st<T>(dst + j + half, v1);
     } else {
-      T* dst = (T*)kv.v_share + stream * (size_t)kv.n_pad * D;
+      T* dst = (T*)kv.v_share + coff + stream * (size_t)kv.n_pad * D;
       st<T>(dst + vblk_index(p, j, D), v0); st<T>(dst + vblk_index(p, j + half, D), v1);
     }
     return;
@@ -243,9 +246,9 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
 template <typename T>
 void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
                         const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
-                        Dims dm, const double* inv_freq, int plain) {
+                        Dims dm, const double* inv_freq, int mode) {
   hipLaunchKernelGGL(k_rope_append<T>, dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
-                     gate_w, gate_b, q_out, z_out, kv, rm, dm, inv_freq, plain);
+                     gate_w, gate_b, q_out, z_out, kv, rm, dm, inv_freq, mode);
 }
 template void launch_rope_append<float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, const double*, int);
 template void launch_rope_append<bf16_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, const double*, int);

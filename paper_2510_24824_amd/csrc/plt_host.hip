@@ -62,7 +62,8 @@ static bool cfg_valid(const plt_config* c, const char** why) {
   if (c->head_dim != 64 && c->head_dim != 128) { *why = "head_dim must be 64 or 128"; return false; }
   if (c->n_heads % c->n_kv_heads) { *why = "n_heads must be a multiple of n_kv_heads"; return false; }
   if (c->n_loops < 1 || c->n_loops > 16) { *why = "n_loops must be in 1..16"; return false; }
-  if (c->mode != PLT_MODE_CLP && c->mode != PLT_MODE_VANILLA_LOOP) { *why = "unknown mode"; return false; }
+  if (c->mode != PLT_MODE_CLP && c->mode != PLT_MODE_VANILLA_LOOP && c->mode != PLT_MODE_CLP_SHARE_ONLY &&
+      c->mode != PLT_MODE_CLP_OWN_KV) { *why = "unknown mode"; return false; }
   if (c->mode == PLT_MODE_CLP && c->n_loops > 1 && c->window < 1) { *why = "window must be >= 1"; return false; }
   if (c->dtype != PLT_F32 && c->dtype != PLT_BF16) { *why = "unknown dtype"; return false; }
   if (c->dtype == PLT_BF16 && (c->d_model % 64 || c->ffn_hidden % 64)) {
@@ -209,9 +210,19 @@ extern "C" int plt_profile_read(plt_model* m, int32_t klass, double* ms_sum, int
 }
 
 // ------------------------------------------------------------------------------ KV layout
-static bool is_clp(const plt_config& c) { return c.mode == PLT_MODE_CLP; }
-static int n_caches_of(const plt_config& c) { return is_clp(c) ? 1 : c.n_loops; }
-static int n_rings_of(const plt_config& c) { return is_clp(c) ? c.n_loops - 1 : 0; }
+// is_clp: the cross-loop-parallel schedule (L rows per sequence in one pass, shift + carry): the
+// method itself and its two ablations; only PLT_MODE_CLP has the gated window (rings).
+static bool is_clp(const plt_config& c) { return c.mode != PLT_MODE_VANILLA_LOOP; }
+static bool is_plt(const plt_config& c) { return c.mode == PLT_MODE_CLP; }
+static int n_caches_of(const plt_config& c) {
+  return (c.mode == PLT_MODE_CLP || c.mode == PLT_MODE_CLP_SHARE_ONLY) ? 1 : c.n_loops;
+}
+static int n_rings_of(const plt_config& c) { return is_plt(c) ? c.n_loops - 1 : 0; }
+// how one pass of the stack treats K/V and attention
+enum { V_PLT = 0,         // loop 1: shared cache; loops >= 2: ring + gated window + shared cache (Alg. 3)
+       V_PLAIN = 1,       // every row: plain causal attention over the cache it also appends to
+       V_SHARE_ONLY = 2,  // loop 1 appends; loops >= 2 append nothing and attend the shared cache only
+       V_OWN_KV = 3 };    // decode rows of loop l append to and attend cache l (one pass, L caches)
 
 extern "C" size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx) {
   if (!m || batch < 1 || max_ctx < 1) { fail(PLT_EINVAL, "plt_kv_bytes: bad argument"); return 0; }
@@ -225,8 +236,8 @@ extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_
   if (!m || batch < 1 || n_ctx < 0) { fail(PLT_EINVAL, "plt_kv_logical_bytes: bad argument"); return 0; }
   const plt_config& c = m->cfg;
   const size_t per = (size_t)2 * c.n_layers * c.n_kv_heads * c.head_dim * m->es * batch;
-  if (is_clp(c)) return per * ((size_t)n_ctx + (size_t)(c.n_loops - 1) * c.window);
-  return per * (size_t)c.n_loops * n_ctx;
+  if (is_plt(c)) return per * ((size_t)n_ctx + (size_t)(c.n_loops - 1) * c.window);
+  return per * (size_t)n_caches_of(c) * n_ctx;
 }
 
 static void kv_release(plt_kv* kv) {
@@ -321,6 +332,7 @@ static KvView kv_view(const plt_kv* kv, int layer, int cache) {
   v.k_loc = nullptr; v.v_loc = nullptr;
   v.n_pad = kv->n_pad; v.w_pad = kv->w_pad; v.n_pad_loc = 0;
   v.w = c.window > 0 ? c.window : 1; v.n_rings = kv->n_rings; v.b0 = 0;
+  v.cache_stride = (size_t)c.n_layers * 2 * kv->share_elems;   // elements between cache c and c + 1 of one layer
   return v;
 }
 
@@ -342,7 +354,7 @@ static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int 
 }
 
 template <typename T>
-static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap rm, int cache, bool plain,
+static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap rm, int cache, int variant,
                        KvView loc /*prefill local K/V + b0*/, int Bc, int n_prefill, int attn_L,
                        const float* next_gain /*norm applied after the last layer, or null*/) {
   // Runs all layers of block f on the R rows in wk.x (a = RMSNorm(x) is already in wk.a).
@@ -357,8 +369,9 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
     int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                               // Alg. 3 l.1
     launch_rope_append<T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
-                          dm, m->inv_freq, plain ? 1 : 0);
+                          dm, m->inv_freq, variant);
     const bool dec = !rm.prefill;
+    const int plain = variant != V_PLT;
     if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
       ProfScope prof(m, PLT_PROF_ATTN, dec);
       if (rm.prefill) {
@@ -366,13 +379,26 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
                                  rm.loop_fixed, dm, plain ? 1 : 0);
       } else {
         const int G = Hq / Hkv;
-        const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1);
-        launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, kv->pos_dev, 0, 0, dm,
-                                plain ? 1 : 0, kv->attn_scratch, ns);
+        if (variant == V_OWN_KV) {
+          // loop l's rows attend cache l: one launch per loop, G rows per (sequence, kv head) stream
+          Dims d1 = dm; d1.L = 1;
+          const int ns = attn_mfma_default_splits(kv->B, Hkv, 1, G, kv->pos + 1);
+          for (int lp = 0; lp < attn_L; ++lp) {
+            KvView vl = v;
+            vl.k_share = (char*)v.k_share + (size_t)lp * v.cache_stride * m->es;
+            vl.v_share = (char*)v.v_share + (size_t)lp * v.cache_stride * m->es;
+            launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, vl, kv->pos_dev, 0, 0, d1, 1,
+                                    kv->attn_scratch, ns, lp, attn_L);
+          }
+        } else {
+          const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1);
+          launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, kv->pos_dev, 0, 0, dm,
+                                  plain ? 1 : 0, kv->attn_scratch, ns);
+        }
       }
     } else {
       ProfScope prof(m, PLT_PROF_ATTN, dec);
-      launch_attn_f32(s, (const float*)wk.q, wk.z, (float*)wk.y, v, rm, R, dm, plain ? 1 : 0);
+      launch_attn_f32(s, (const float*)wk.q, wk.z, (float*)wk.y, v, rm, R, dm, variant == V_OWN_KV && dec ? 3 : plain);
     }
     S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);                                     // Alg. 3 l.6
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
@@ -413,7 +439,8 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     RowMap rm{0, L, 0, kv->pos_dev};
     launch_embed<T>(s, dev_tokens, (const T*)m->emb, kv->carry, nullptr, kv->x, R, d, rm, L, 1, c.vocab);
     launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, R, d);
-    stack_pass<T>(m, kv, wk, R, rm, 0, false, none, 0, 0, L, nullptr);
+    const int variant = c.mode == PLT_MODE_CLP ? V_PLT : (c.mode == PLT_MODE_CLP_SHARE_ONLY ? V_SHARE_ONLY : V_OWN_KV);
+    stack_pass<T>(m, kv, wk, R, rm, 0, variant, none, 0, 0, L, nullptr);
     launch_carry_update(s, kv->x, kv->carry, B, L, d);
     head_and_argmax<T>(m, kv, wk, B, L, L - 1, dev_next, dev_logits, true);                       // Alg. 1 l.8-9
   } else {
@@ -422,7 +449,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     launch_embed<T>(s, dev_tokens, (const T*)m->emb, nullptr, nullptr, kv->x, B, d, rm, 1, 0, c.vocab);
     launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, B, d);
     for (int l = 0; l < L; ++l)
-      stack_pass<T>(m, kv, wk, B, rm, l, true, none, 0, 0, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
+      stack_pass<T>(m, kv, wk, B, rm, l, V_PLAIN, none, 0, 0, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
     head_and_argmax<T>(m, kv, wk, B, 1, 0, dev_next, dev_logits, true);
   }
   launch_pos_set(s, kv->pos_dev, B, 1, 1);
@@ -469,7 +496,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
                o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
                o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * F * es),
                o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * es), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * es),
-               o_tmp = carve((L > 1 && is_clp(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
+               o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
   char* ws = nullptr;
   hipError_t e = hipMalloc((void**)&ws, off);
   if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
@@ -488,7 +515,9 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
         // Alg. 2 l.1-2 (l = 0) and l.4-6 (l >= 1): B = E + shift_right(H^(l))
         launch_embed<T>(s, toks, (const T*)m->emb, nullptr, hprev, wk.x, R, d, rm, L, 1, c.vocab);
         launch_resid_norm<T>(s, wk.x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)wk.a, R, d);
-        stack_pass<T>(m, kv, wk, R, rm, 0, false, loc, bc, n, L, nullptr);
+        // own-KV ablation: loop l is a plain pass over its own cache l; share-only: loops >= 2 append nothing
+        const int variant = c.mode == PLT_MODE_CLP ? V_PLT : (c.mode == PLT_MODE_CLP_SHARE_ONLY ? V_SHARE_ONLY : V_PLAIN);
+        stack_pass<T>(m, kv, wk, R, rm, c.mode == PLT_MODE_CLP_OWN_KV ? l : 0, variant, loc, bc, n, L, nullptr);
         if (l + 1 < L) {
           launch_prefill_carry(s, wk.x, kv->carry, b0, bc, n, L, l, d);
           launch_shift_copy(s, wk.x, hprev, (size_t)R * d);
@@ -498,7 +527,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
           launch_embed<T>(s, toks, (const T*)m->emb, nullptr, nullptr, wk.x, R, d, rm, 1, 0, c.vocab);
           launch_resid_norm<T>(s, wk.x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)wk.a, R, d);
         }
-        stack_pass<T>(m, kv, wk, R, rm, l, true, loc, bc, n, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
+        stack_pass<T>(m, kv, wk, R, rm, l, V_PLAIN, loc, bc, n, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
       }
     }
     head_and_argmax<T>(m, kv, wk, bc, n, n - 1, dev_next + b0, dev_logits ? dev_logits + (size_t)b0 * V : nullptr);

@@ -60,6 +60,7 @@ struct KvView {
   int w;           // window
   int n_rings;     // L-1
   int b0;          // prefill: first sequence of the chunk (share/ring are indexed by b0 + b)
+  size_t cache_stride;   // elements from this layer's cache c to cache c + 1 (per-loop caches)
 };
 
 struct Dims { int B, L, Hq, Hkv, D, d, F, V; };
@@ -116,7 +117,8 @@ size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D);
 int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx);
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform,
-                             Dims dm, int plain, void* scratch, int n_splits);
+                             Dims dm, int plain, void* scratch, int n_splits,
+                             int l_off = 0, int l_stride = 0 /* rows per sequence in q / y; 0 = dm.L */);
 // local_tmp: float scratch [Bc*n, Hq*D] (used by loops >= 2 only)
 void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
                               KvView kv, int Bc, int n, int loop, Dims dm, int plain);

@@ -59,7 +59,7 @@ def test_weight_layout_queries(lib):
 
 
 @pytest.mark.parametrize("field,value", [("head_dim", 48), ("n_kv_heads", 3), ("n_loops", 0), ("dtype", 7),
-                                         ("mode", 1), ("window", 0), ("d_model", 0)])
+                                         ("mode", 1), ("mode", 5), ("window", 0), ("d_model", 0)])
 def test_invalid_configs_are_rejected(lib, field, value):
     cfg = B.make_config(synth.TINY, dtype=B.PLT_F32)
     setattr(cfg, field, value)

@@ -23,8 +23,9 @@ def run_teacher_forced(shape, dtype, mode, weights, prompts, n_steps, tol, check
     kv = B.KV(model, Bn, n + n_steps + 3)
     orcs, streams, ref_logits, ref_hidden = [], [], [], []
     for b in range(Bn):
-        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=bf)
-        if mode == B.PLT_MODE_CLP:
+        variant = {B.PLT_MODE_CLP_SHARE_ONLY: "clp_share_only", B.PLT_MODE_CLP_OWN_KV: "clp_own_kv"}.get(mode, "plt")
+        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=bf, variant=variant)
+        if mode != B.PLT_MODE_VANILLA_LOOP:
             ids, margins, lgs = orc.greedy_generate(list(prompts[b]), n_steps)
             hidden = np.stack(orc.trace)[n - 1:]                         # [n_steps+1, L, d]
         else:
@@ -210,3 +211,21 @@ def test_prefill_then_prefill_restarts_the_cache():
     t = dev_tokens(np.array([5]))
     assert np.array_equal(kv.decode_step(t)[1].cpu().numpy(), kv_fresh.decode_step(t)[1].cpu().numpy())
     kv.close(); kv_fresh.close(); model.close()
+
+
+@pytest.mark.parametrize("mode", [B.PLT_MODE_CLP_SHARE_ONLY, B.PLT_MODE_CLP_OWN_KV])
+@pytest.mark.parametrize("dtype,tol", [(B.PLT_F32, 2e-5), (B.PLT_BF16, 2e-2)])
+def test_ablation_modes(mode, dtype, tol):
+    """Table 1 rows 3 and 4 in the same library: cross-loop parallel with per-loop KV, and with the
+    shared first-loop KV but no window; kv bytes follow the table (L*n and n entries)."""
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,
+                             ffn_hidden=192, vocab=400, n_loops=3, window=8)
+    weights = lively_weights(shape, 41, bf16=dtype == B.PLT_BF16, std=0.02)
+    prompts = synth.token_ids((2, 37), shape.vocab, 42)
+    run_teacher_forced(shape, dtype, mode, weights, prompts, 7, tol)
+    cfg = B.make_config(shape, dtype=dtype, mode=mode)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    es = 2 if dtype == B.PLT_BF16 else 4
+    per = 2 * shape.n_layers * shape.n_kv_heads * shape.head_dim * es
+    assert model.kv_logical_bytes(1, 1000) == per * 1000 * (3 if mode == B.PLT_MODE_CLP_OWN_KV else 1)
+    model.close()
