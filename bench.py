@@ -260,6 +260,50 @@ def bench_prefill(B, shape, blob, g, Bn=4, n=8192, L=3, w=64, reps=2):
             "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
 
 
+def bench_sweep(B, shape, blob, g, n_new=256, runs=2):
+    """The paper's serving recipe on synthetic inputs: prefill context {1024, 2048, 5000}, batch 1..256,
+    n_new consecutive greedy decode steps (the context grows), mean per-token latency over `runs` runs,
+    for the non-looped model, PLT-2 and the vanilla sequential loop-2 in the same library.  Caches are
+    filled with N(0, 0.5) values on the device (timing only)."""
+    import torch
+    free_bytes = torch.cuda.mem_get_info()[0]
+    table = []
+    for ctx in (1024, 2048, 5000):
+        for bs in (1, 4, 16, 64, 256):
+            row = {"context": ctx, "batch": bs}
+            for name, mode, Lx in [("nonlooped", B.PLT_MODE_CLP, 1), ("plt2", B.PLT_MODE_CLP, 2), ("vanilla_loop2", B.PLT_MODE_VANILLA_LOOP, 2)]:
+                cfg = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=64)
+                m = B.Model(cfg, blob)
+                need = m.kv_bytes(bs, ctx + n_new)
+                if need > free_bytes - (8 << 30):
+                    row[name] = None
+                    m.close()
+                    continue
+                kv = B.KV(m, bs, ctx + n_new)
+                kv.buf.view(torch.bfloat16).normal_(0.0, 0.5, generator=g)
+                tok = torch.randint(0, shape.vocab, (bs,), generator=g, device="cuda", dtype=torch.int32)
+                ms = []
+                for r in range(runs + 1):
+                    kv.set_position(ctx)
+                    nxt = tok
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(n_new):
+                        nxt, _ = kv.decode_step(nxt, want_logits=False)
+                    torch.cuda.synchronize()
+                    if r > 0:                       # run 0 warms up
+                        ms.append((time.perf_counter() - t0) * 1e3 / n_new)
+                row[name] = sum(ms) / len(ms)
+                kv.close(); m.close(); del kv
+                torch.cuda.empty_cache()
+            if row["nonlooped"]:
+                row["plt2_vs_nonlooped"] = row["plt2"] / row["nonlooped"] if row["plt2"] else None
+                row["vanilla_loop2_vs_nonlooped"] = row["vanilla_loop2"] / row["nonlooped"] if row["vanilla_loop2"] else None
+            log(f"[bench] sweep {row}")
+            table.append(row)
+    return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "rows": table}
+
+
 def read_traffic(name):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if a summary
     under profiles/ records it as a line `<name> = <bytes>`; else None."""
@@ -282,6 +326,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--only-main", action="store_true", help="skip the baselines, the L sweep and the kernel-only run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also run the batch x context serving sweep (several minutes)")
     ap.add_argument("--prefill", action="store_true", help="also time the CLP prefill of 4 x 8192 tokens at L=3")
     ap.add_argument("--long-context", action="store_true",
                     help="also time one GPU's share of the L=4, window 128, 8192-token configuration (batch 128 resident)")
@@ -404,6 +449,8 @@ def main():
                                             lat["clp_share_only_L2"], lat["plt_L2"]]}
         out["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup)
 
+    if args.sweep:
+        out["serving_sweep"] = bench_sweep(B, shape, blob, g)
     if args.prefill:
         out["prefill"] = bench_prefill(B, shape, blob, g)
         log(f"[bench] prefill 4 x 8192, L=3: {out['prefill']['ms']:.0f} ms, {out['prefill']['roofline']['achieved']:.0f} TFLOP/s")

@@ -337,10 +337,10 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx) {
   const int n_tiles = (n_ctx + 31) / 32;
   // one workgroup per stream when that already covers every compute unit; else split so that
   // about one workgroup per compute unit exists (more splits only add merge work: measured),
-  // keeping >= 16 tiles (4 per wave) per workgroup
+  // keeping >= 8 tiles (2 per wave) per workgroup (an eight-wave workgroup variant measured slower)
   if (streams >= 256) return 1;
   int s = (int)((256 + streams - 1) / streams);
-  int cap = n_tiles / 16; if (cap < 1) cap = 1;
+  int cap = n_tiles / 8; if (cap < 1) cap = 1;           // at least two tiles per wave
   if (s > cap) s = cap;
   if (s > 64) s = 64;
   if (s < 1) s = 1;
