@@ -131,7 +131,12 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
 
 }  // namespace
 
-bool gemm_big_applies(int M, int N, int K) { return M >= 512 && (K % GB_BK) == 0; }
+// Worth it only when the 256 x 128 tiles still fill the chip (prefill-sized row counts); decode-sized
+// launches with a few hundred rows keep the small-tile split-K kernel.
+bool gemm_big_applies(int M, int N, int K) {
+  const long tiles = (long)((M + GB_BM - 1) / GB_BM) * ((N + GB_BN - 1) / GB_BN);
+  return M >= 512 && tiles >= 256 && (K % GB_BK) == 0;
+}
 
 void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
   dim3 grid((N + GB_BN - 1) / GB_BN, (M + GB_BM - 1) / GB_BM);
