@@ -304,6 +304,23 @@ def bench_sweep(B, shape, blob, g, n_new=256, runs=2):
     return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "rows": table}
 
 
+def measure_read_ceiling(B):
+    """Practical HBM read ceiling on this machine: the library's plain read-only stream kernel over 4 GiB."""
+    import torch
+    src = torch.zeros(4 << 30, dtype=torch.uint8, device="cuda")
+    out = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    call = lambda: B.lib().plt_stream_read(C.c_void_p(src.data_ptr()), src.numel(), C.c_void_p(out.data_ptr()), out.numel(), stream)
+    for _ in range(3):
+        assert call() == 0
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        call()
+    e1.record(); torch.cuda.synchronize()
+    return src.numel() / (e0.elapsed_time(e1) * 1e-3 / 10) / 1e9
+
+
 def read_traffic(name):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), if a summary
     under profiles/ records it as a line `<name> = <bytes>`; else None."""
@@ -420,6 +437,9 @@ def main():
         "ms_per_step_without_event_instrumentation": ms_step_noevents,
         "kv_bytes_logical": model.kv_logical_bytes(Bn, N),
     }
+    ceiling = measure_read_ceiling(B)
+    out["roofline"]["measured_stream_read_GBps"] = ceiling          # context: what a plain read kernel reaches here
+    out["roofline"]["frac_of_measured_stream_read"] = achieved / ceiling
 
     if not args.only_main:
         # ---- same library, same weights: non-looped, the L sweep and the vanilla sequential loop.

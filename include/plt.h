@@ -192,7 +192,7 @@ size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
  * multiples of 16; the buffers must not overlap. */
 int plt_stream_copy(void* dev_dst, const void* dev_src, size_t nbytes, void* hip_stream);
 /* Read-only counterpart (a practical ceiling for a pure read stream such as decode attention):
- * reads nbytes and writes one word per thread to dev_out (>= 2 MiB). */
+ * reads nbytes (a multiple of 32 KiB) and writes one word per thread to dev_out (>= 2 MiB). */
 int plt_stream_read(const void* dev_src, size_t nbytes, void* dev_out, size_t out_bytes, void* hip_stream);
 
 /* Bench instrumentation.  `mask` selects launch classes (bit 1 << PLT_PROF_ATTN: the fused

@@ -732,23 +732,29 @@ __global__ __launch_bounds__(256) void k_stream_copy(const uint4* __restrict__ s
   for (; i < n16; i += stride) dst[i] = src[i];
 }
 
-// read-only counterpart: every lane folds what it reads and stores one word at the end
+// read-only counterpart: every workgroup walks one contiguous chunk (like one K/V stream), eight
+// 16-byte loads in flight per lane; every lane folds what it reads and stores one word at the end
 __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, unsigned* __restrict__ out, size_t n16) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t per = n16 / gridDim.x;
+  const uint4* p = src + (size_t)blockIdx.x * per;
   unsigned acc = 0;
-  for (; i + 3 * stride < n16; i += 4 * stride) {
-    uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+  size_t i = threadIdx.x;
+  for (; i + 7 * 256 < per; i += 8 * 256) {
+    uint4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p[i + u * 256];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
-  for (; i < n16; i += stride) { uint4 a = src[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
+  for (; i < per; i += 256) { uint4 a = p[i]; acc ^= a.x ^ a.y ^ a.z ^ a.w; }
   out[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 
 extern "C" int plt_stream_read(const void* dev_src, size_t nbytes, void* dev_out, size_t out_bytes, void* hip_stream) {
   const size_t blocks = 256 * 8;
-  if (!dev_src || !dev_out || nbytes == 0 || (nbytes & 15) || (((uintptr_t)dev_src) & 15) || out_bytes < blocks * 256 * 4)
-    return fail(PLT_EINVAL, "plt_stream_read: need 16-byte multiples and an output buffer of %zu bytes", blocks * 256 * 4);
+  if (!dev_src || !dev_out || nbytes == 0 || (nbytes % (16 * blocks)) || (((uintptr_t)dev_src) & 15) || out_bytes < blocks * 256 * 4)
+    return fail(PLT_EINVAL, "plt_stream_read: need a multiple of %zu bytes, 16-byte alignment and an output buffer of %zu bytes",
+                16 * blocks, blocks * 256 * 4);
   hipLaunchKernelGGL(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
                      (const uint4*)dev_src, (unsigned*)dev_out, nbytes / 16);
   HIP_TRY(hipGetLastError());
