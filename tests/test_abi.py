@@ -82,3 +82,31 @@ def test_null_and_size_argument_errors(lib):
     assert lib.plt_attn_scratch_bytes(1, 1, 4, 3, 64) == 0
     assert lib.plt_attn_pad32(33) == 64 and lib.plt_attn_pad32(64) == 64
     assert lib.plt_gemm(B.PLT_BF16, 4, 4, 4, None, None, None, None, 0, None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """No fallback path: without libplt.so the binding raises instead of computing on the CPU."""
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", os.path.join(ROOT, "paper_2510_24824_amd", "no_such_libplt.so"))
+    with pytest.raises(FileNotFoundError):
+        B.lib()
+
+
+def test_product_path_does_not_import_the_oracle():
+    """The oracle is test infrastructure: nothing under the package (nor bench's timed path) imports it
+    at module level."""
+    pkg = os.path.join(ROOT, "paper_2510_24824_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            src = open(os.path.join(pkg, name)).read()
+            assert "oracle" not in src, name
+    bench_src = open(os.path.join(ROOT, "bench.py")).read()
+    head = bench_src.split("def oracle_sample")[0]
+    assert "import plt_oracle" not in head and "from oracle" not in head
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
