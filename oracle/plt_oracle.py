@@ -31,6 +31,11 @@ design notes of the repository):
 
 Precision: float64 everywhere.  With kv_bf16=True the K and V entries are rounded to
 bfloat16 when they are stored (the device keeps its caches in bfloat16), nothing else is.
+With kv_fp8=True they are instead rounded to the 8-bit float format e4m3 (4 exponent bits, 3
+mantissa bits, no infinities, largest value 448; the OCP "e4m3fn" format) with saturation: the
+paper serves its models with FP8 self-attention [inference efficiency evaluation recipe]; the
+reading taken here is an FP8 *storage* format for every cached K and V (after RoPE, unit scale),
+while queries, softmax weights and all sums keep full precision.
 Parity status: every function here is pinned by tests/test_oracle_pins.py.
 """
 from __future__ import annotations
@@ -39,7 +44,7 @@ import math
 import numpy as np
 
 __all__ = ["OracleShape", "PLTOracle", "rmsnorm", "rope", "softmax_attend", "gate_merge",
-           "gated_attention_row", "decode_attention", "kv_cache_bytes", "bf16_round"]
+           "gated_attention_row", "decode_attention", "kv_cache_bytes", "bf16_round", "e4m3_round"]
 
 
 # ----------------------------------------------------------------------------- helpers
@@ -51,6 +56,21 @@ def bf16_round(x: np.ndarray) -> np.ndarray:
     keep_odd = (bits >> 16) & 1
     bits = ((bits + 0x7FFF + keep_odd) >> 16) << 16
     return bits.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+def e4m3_round(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to the 8-bit float e4m3 (OCP e4m3fn), saturating at +-448.
+
+    Format: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits; normal values
+    2^(e-7) * (1 + m/8) for e = 1..15 (e = 15, m = 7 is NaN, so the largest is 1.75 * 2^8 = 448);
+    subnormals m/8 * 2^-6.  Neighbouring values in the binade [2^E, 2^(E+1)) are 2^(E-3) apart,
+    and 2^-9 apart below 2^-6."""
+    a = np.clip(np.asarray(x, np.float64), -448.0, 448.0)
+    mag = np.abs(a)
+    _, ex = np.frexp(mag)                       # mag = f * 2^ex with f in [0.5, 1)
+    E = np.maximum(ex - 1, -6)                  # binade of mag, clamped to the subnormal range
+    step = np.ldexp(1.0, E - 3)
+    return np.sign(a) * np.rint(mag / step) * step      # rint: ties to even
 
 
 class OracleShape:
@@ -232,7 +252,8 @@ class RingKV:
 class PLTOracle:
     """One sequence at a time (sequences of a batch never interact)."""
 
-    def __init__(self, shape: OracleShape, weights: dict, kv_bf16: bool = False, variant: str = "plt"):
+    def __init__(self, shape: OracleShape, weights: dict, kv_bf16: bool = False, variant: str = "plt",
+                 kv_fp8: bool = False):
         """variant selects the row of Table 1 that is computed (all share the cross-loop shift):
           "plt"            row 5: shared first-loop KV + gated sliding window (the method)
           "clp_share_only" row 4: non-first loops attend the shared first-loop KV only (no own K/V, no gate)
@@ -241,8 +262,9 @@ class PLTOracle:
         self.variant = variant
         self.s = shape
         self.w = weights
-        self.kv_bf16 = kv_bf16
-        self._store = bf16_round if kv_bf16 else (lambda a: np.asarray(a, np.float64))
+        assert not (kv_bf16 and kv_fp8)
+        self.kv_bf16, self.kv_fp8 = kv_bf16, kv_fp8
+        self._store = bf16_round if kv_bf16 else e4m3_round if kv_fp8 else (lambda a: np.asarray(a, np.float64))
         self._head = weights["emb"] if shape.tie_embeddings else weights["head"]
 
     # -- block f: one pass of the whole layer stack for one row at position p in loop l (1-based)

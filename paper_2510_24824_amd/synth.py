@@ -60,6 +60,36 @@ def bf16_from_bits(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << 16).view(np.float32).reshape(b.shape)
 
 
+def _e4m3_table() -> np.ndarray:
+    """The 127 finite non-negative values of the 8-bit float e4m3 (OCP e4m3fn) by bit pattern
+    0x00..0x7E: exponent field e (bias 7), mantissa m: 2^(e-7) (1 + m/8), subnormal m/8 * 2^-6."""
+    code = np.arange(127)
+    e, m = code >> 3, code & 7
+    return np.where(e == 0, m / 8.0 * 2.0 ** -6, 2.0 ** (e - 7.0) * (1 + m / 8.0)).astype(np.float32)
+
+
+def e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """uint8 e4m3 codes nearest to x (ties to the even code, saturating at +-448)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    tab = _e4m3_table().astype(np.float64)
+    mag = np.minimum(np.abs(x.astype(np.float64)), 448.0)
+    hi = np.clip(np.searchsorted(tab, mag, side="left"), 1, 126)       # tab[hi-1] <= mag <= tab[hi]
+    lo = hi - 1
+    dl, dh = mag - tab[lo], tab[hi] - mag
+    code = np.where(dl < dh, lo, np.where(dh < dl, hi, np.where(lo % 2 == 0, lo, hi)))
+    return (code | np.where(np.signbit(x), 0x80, 0)).astype(np.uint8).reshape(x.shape)
+
+
+def e4m3_from_bits(b: np.ndarray) -> np.ndarray:
+    b = np.asarray(b, np.uint8)
+    v = _e4m3_table()[np.minimum(b & 0x7F, 126)]
+    return np.where(b & 0x80, -v, v).astype(np.float32).reshape(b.shape)
+
+
+def round_to_e4m3(x: np.ndarray) -> np.ndarray:
+    return e4m3_from_bits(e4m3_bits(x))
+
+
 def normal(shape, seed: int, stream: int, std: float = 1.0, bf16: bool = False) -> np.ndarray:
     x = _rng(seed, stream).standard_normal(size=shape, dtype=np.float32) * np.float32(std)
     return round_to_bf16(x) if bf16 else x

@@ -109,3 +109,31 @@ def test_missing_shift_is_caught(monkeypatch):
         return H, np.stack([self.logits(H[-1, p]) for p in range(n)])
     monkeypatch.setattr(O.PLTOracle, "seq_forward", seq_forward)
     assert some_pin_fails()
+
+
+def _e4m3_truncating(x):
+    a = np.clip(np.asarray(x, np.float64), -448.0, 448.0)
+    _, ex = np.frexp(np.abs(a))
+    step = np.ldexp(1.0, np.maximum(ex - 1, -6) - 3)
+    return np.sign(a) * np.floor(np.abs(a) / step) * step
+
+
+def _e4m3_no_subnormals(x):
+    a = np.clip(np.asarray(x, np.float64), -448.0, 448.0)
+    _, ex = np.frexp(np.abs(a))
+    step = np.ldexp(1.0, ex - 1 - 3)
+    return np.sign(a) * np.rint(np.abs(a) / step) * step
+
+
+def _e4m3_wrong_max(x):
+    a = np.clip(np.asarray(x, np.float64), -480.0, 480.0)
+    _, ex = np.frexp(np.abs(a))
+    step = np.ldexp(1.0, np.maximum(ex - 1, -6) - 3)
+    return np.sign(a) * np.rint(np.abs(a) / step) * step
+
+
+@pytest.mark.parametrize("repl", [_e4m3_truncating, _e4m3_no_subnormals, _e4m3_wrong_max])
+def test_e4m3_mutations_are_caught(monkeypatch, repl):
+    monkeypatch.setattr(O, "e4m3_round", repl)
+    with pytest.raises(AssertionError):
+        P.test_e4m3_round_matches_torch_and_the_format()

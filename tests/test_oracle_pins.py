@@ -295,6 +295,54 @@ def test_bf16_round_matches_torch():
     assert np.array_equal(synth.bf16_from_bits(synth.bf16_bits(synth.round_to_bf16(x))), synth.round_to_bf16(x))
 
 
+# ---- e4m3 rounding (FP8 K/V storage) against torch's float8_e4m3fn conversion and the format's definition
+def test_e4m3_round_matches_torch_and_the_format():
+    codes = torch.arange(256, dtype=torch.int16).to(torch.uint8)
+    vals = codes.view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    finite = vals[np.isfinite(vals)]
+    assert finite.size == 254 and finite.max() == 448.0 and np.min(np.abs(finite[finite != 0])) == 2.0 ** -9
+    assert np.array_equal(O.e4m3_round(finite), finite)                         # every code is a fixed point
+    pos = np.sort(finite[finite >= 0])[1:]                                      # drop one of the two zeros
+    mid = (pos[:-1] + pos[1:]) / 2                                              # exact ties
+    x = np.concatenate([synth.normal((1 << 16,), 5, 78, s) for s in (0.003, 0.05, 1.0, 40.0, 300.0)]
+                       + [mid, -mid, np.nextafter(mid, 0).astype(np.float32), [0.0, 448.0, 449.0, 479.0, 1e9, -1e9]])
+    x = x.astype(np.float32)
+    ref = torch.from_numpy(x).clamp(-448, 448).to(torch.float8_e4m3fn).to(torch.float64).numpy()
+    got = O.e4m3_round(x)
+    assert np.array_equal(got, ref)
+    # ties go to the even mantissa: the tie between codes c and c + 1 lands on the even one
+    tie = O.e4m3_round(mid)
+    even = np.where(np.arange(mid.size) % 2 == 0, pos[:-1], pos[1:])
+    assert np.array_equal(tie, even)
+    # relative error of normal values <= 2^-4, saturation beyond the largest value
+    nrm = np.abs(x) >= 2.0 ** -6
+    assert np.max(np.abs(got[nrm] - np.clip(x[nrm], -448, 448)) / np.abs(np.clip(x[nrm], -448, 448))) <= 2.0 ** -4
+    assert O.e4m3_round(np.array([1e9]))[0] == 448.0 and O.e4m3_round(np.array([-500.0]))[0] == -448.0
+    # the input generators' own code table agrees (they hand the same values to both sides)
+    assert np.array_equal(synth.round_to_e4m3(x).astype(np.float64), ref)
+    assert np.array_equal(synth.e4m3_bits(x), torch.from_numpy(x).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy())
+    assert np.array_equal(synth.e4m3_from_bits(np.arange(256, dtype=np.uint8))[np.isfinite(vals)], finite.astype(np.float32))
+
+
+def test_kv_fp8_rounds_only_what_is_stored():
+    """kv_fp8: the cached K/V are e4m3 values; with weights that make K and V exactly representable
+    nothing changes; otherwise the result differs from the unrounded run but Alg. 1 still equals Alg. 2."""
+    shape = oshape(SMALL, n_loops=2, window=3)
+    wts = small_weights()
+    toks = synth.token_ids((9,), SMALL.vocab, seed=41)
+    o8 = O.PLTOracle(shape, wts, kv_fp8=True)
+    H8, lg8 = o8.seq_forward(toks)
+    H, lg = O.PLTOracle(shape, wts).seq_forward(toks)
+    d = np.max(np.abs(H8 - H))
+    assert 1e-6 < d < 0.2 * np.max(np.abs(H))
+    o8.clp_prefill(toks[:4], 16)
+    for t in toks[4:]:
+        o8.clp_decode_step(t)
+    assert np.max(np.abs(np.stack(o8.trace).transpose(1, 0, 2) - H8)) < 1e-10
+    for arr in (o8.kv.ks, o8.kv.vs, o8.kv.kr, o8.kv.vr):
+        assert np.array_equal(O.e4m3_round(arr), arr)
+
+
 # ---- greedy generation bookkeeping (Alg. 1): ids, ring wrap beyond w steps, margins reported
 def test_greedy_generate_matches_teacher_forced_forward():
     shape = oshape(SMALL, n_loops=2, window=4)
