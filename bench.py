@@ -95,13 +95,27 @@ def weights_to_host(B, cfg, blob):
     return w
 
 
-def attn_alg_bytes(Bn, L, Hq, Hkv, D, N, w, es=2):
+def attn_alg_bytes(Bn, L, Hq, Hkv, D, N, w, es=2, kes=None):
     """Algorithmic HBM bytes of one fused decode-attention launch: shared K and V once, the
-    rings once, Q in, Y out."""
-    share = 2 * Bn * Hkv * N * D * es
-    ring = 2 * Bn * (L - 1) * Hkv * min(w, N) * D * es
+    rings once, Q in, Y out (es: bytes per q / y element, kes: per cache element)."""
+    kes = es if kes is None else kes
+    share = 2 * Bn * Hkv * N * D * kes
+    ring = 2 * Bn * (L - 1) * Hkv * min(w, N) * D * kes
     qy = 2 * Bn * L * Hq * D * es
     return share + ring + qy
+
+
+def fill_kv_random(B, kv, g, std=0.5):
+    """Timing-only cache contents drawn on the device: N(0, std) in the cache's element type."""
+    import torch
+    if kv.model.cfg.kv_dtype == B.PLT_FP8_E4M3:
+        step = 1 << 28
+        for i in range(0, kv.buf.numel(), step):
+            m = min(step, kv.buf.numel() - i)
+            kv.buf[i:i + m].copy_((torch.randn(m, generator=g, device="cuda", dtype=torch.bfloat16) * std)
+                                  .to(torch.float8_e4m3fn).view(torch.uint8))
+    else:
+        kv.buf.view(torch.bfloat16).normal_(0.0, std, generator=g)
 
 
 def time_steps(kv, pos, tok, warmup, steps):
@@ -161,17 +175,21 @@ def cfg_batch_note(state):
     return "sampled (" + ",".join(str(k) for k in state) + ")"
 
 
-def bench_attn_kernel(B, steps, warmup):
+def bench_attn_kernel(B, steps, warmup, fp8=False):
     """Kernel-only fused decode attention: batch 32, L=3, 16 q / 4 kv heads, D=128, 4096 keys, w=64.
-    Four disjoint input sets are rotated so that a launch never finds its KV in the 256 MB last-level cache."""
+    Four disjoint input sets are rotated so that a launch never finds its KV in the 256 MB last-level cache.
+    fp8: the four cache arrays hold e4m3 bytes (q, y stay bf16); eight sets are rotated then."""
     import torch
     Bn, L, Hq, Hkv, D, N, w = 32, 3, 16, 4, 128, 4096, 64
     g = torch.Generator(device="cuda"); g.manual_seed(SEED + 2)
     rn = lambda *s: torch.randn(*s, generator=g, device="cuda").to(torch.bfloat16)
+    rc = (lambda *s: rn(*s).to(torch.float8_e4m3fn).view(torch.uint8)) if fp8 else rn
+    dt = B.PLT_FP8_E4M3 if fp8 else B.PLT_BF16
+    n_sets = 8 if fp8 else 4
     sets = []
-    for _ in range(4):
-        sets.append(dict(q=rn(Bn, L, Hq, D), ks=rn(Bn, Hkv, N, D), vs=rn(Bn, Hkv, N // 32, D, 32),
-                         kr=rn(Bn, L - 1, Hkv, w, D), vr=rn(Bn, L - 1, Hkv, w // 32, D, 32),
+    for _ in range(n_sets):
+        sets.append(dict(q=rn(Bn, L, Hq, D), ks=rc(Bn, Hkv, N, D), vs=rc(Bn, Hkv, N // 32, D, 32),
+                         kr=rc(Bn, L - 1, Hkv, w, D), vr=rc(Bn, L - 1, Hkv, w // 32, D, 32),
                          z=torch.randn(Bn, L - 1, Hq, generator=g, device="cuda"), y=torch.empty(Bn, L, Hq, D, dtype=torch.bfloat16, device="cuda")))
     nb = B.lib().plt_attn_scratch_bytes(Bn, L, Hq, Hkv, D)
     scratch = torch.zeros(nb, dtype=torch.uint8, device="cuda")
@@ -179,23 +197,23 @@ def bench_attn_kernel(B, steps, warmup):
     p = lambda t: C.c_void_p(t.data_ptr())
 
     def launch(s):
-        rc = B.lib().plt_attn_decode(B.PLT_BF16, Bn, L, Hq, Hkv, D, N, N, w, w, p(s["q"]), p(s["ks"]), p(s["vs"]), p(s["kr"]),
+        st = B.lib().plt_attn_decode(dt, Bn, L, Hq, Hkv, D, N, N, w, w, p(s["q"]), p(s["ks"]), p(s["vs"]), p(s["kr"]),
                                      p(s["vr"]), p(s["z"]), p(s["y"]), p(scratch), nb, 0, stream)
-        if rc:
+        if st:
             raise RuntimeError(B.lib().plt_last_error().decode())
 
     for i in range(warmup):
-        launch(sets[i % 4])
+        launch(sets[i % n_sets])
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     n = max(steps, 8) * 4
     e0.record()
     for i in range(n):
-        launch(sets[i % 4])
+        launch(sets[i % n_sets])
     e1.record(); torch.cuda.synchronize()
     us = e0.elapsed_time(e1) * 1e3 / n
-    nbytes = attn_alg_bytes(Bn, L, Hq, Hkv, D, N, w)
+    nbytes = attn_alg_bytes(Bn, L, Hq, Hkv, D, N, w, 2, 1 if fp8 else 2)
     gbs = nbytes / (us * 1e-6) / 1e9
-    return {"workload": "fused decode attention, bf16, B=32, L=3, 16q/4kv heads, D=128, N=4096, w=64",
+    return {"workload": f"fused decode attention, {'bf16 q/y + e4m3 caches' if fp8 else 'bf16'}, B=32, L=3, 16q/4kv heads, D=128, N=4096, w=64",
             "us_per_launch": us, "algorithmic_bytes": nbytes, "achieved_GBps": gbs, "frac_of_8TBps": gbs / HBM_PEAK_GBS,
             "launches_timed": n}
 
@@ -210,17 +228,21 @@ def bench_long_context(B, shape, blob, g, steps):
     N, w = 8192, 128
     pos = N - 1
     res = {"context": N, "window": w, "note": "batch 256 (412 GB of KV) exceeds 288 GB; one GPU's share (batch 128) timed"}
-    for name, mode, Lx, Bn in [("plt_L4_b128", B.PLT_MODE_CLP, 4, 128), ("nonlooped_L1_b128", B.PLT_MODE_CLP, 1, 128),
-                               ("plt_L4_b32", B.PLT_MODE_CLP, 4, 32), ("vanilla_loop_L4_b32", B.PLT_MODE_VANILLA_LOOP, 4, 32)]:
-        cfg = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
+    for name, mode, Lx, Bn, kvd in [("plt_L4_b128", B.PLT_MODE_CLP, 4, 128, 0), ("nonlooped_L1_b128", B.PLT_MODE_CLP, 1, 128, 0),
+                                    ("plt_L4_b32", B.PLT_MODE_CLP, 4, 32, 0), ("vanilla_loop_L4_b32", B.PLT_MODE_VANILLA_LOOP, 4, 32, 0),
+                                    # e4m3 caches: the whole batch-256 configuration is resident (206 GB + 4.8 GB of rings)
+                                    ("plt_L4_b256_fp8kv", B.PLT_MODE_CLP, 4, 256, B.PLT_FP8_E4M3),
+                                    ("nonlooped_L1_b256_fp8kv", B.PLT_MODE_CLP, 1, 256, B.PLT_FP8_E4M3)]:
+        cfg = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w, kv_dtype=kvd)
         m = B.Model(cfg, blob)
         kv = B.KV(m, Bn, N)
-        kv.buf.view(torch.bfloat16).normal_(0.0, 0.5, generator=g)
+        fill_kv_random(B, kv, g)
         tok = torch.randint(0, shape.vocab, (Bn,), generator=g, device="cuda", dtype=torch.int32)
         m.profile_enable(1 << B.PLT_PROF_ATTN)
         ms = time_steps(kv, pos, tok, 1, steps)
         attn_ms, attn_n = m.profile_read(B.PLT_PROF_ATTN, reset=True)
-        ab = attn_alg_bytes(Bn, Lx if mode == B.PLT_MODE_CLP else 1, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w)
+        ab = attn_alg_bytes(Bn, Lx if mode == B.PLT_MODE_CLP else 1, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w,
+                            2, 1 if kvd else 2)
         us = attn_ms * 1e3 / max(attn_n, 1)
         res[name] = {"ms_per_step": ms, "tokens_per_s": Bn / (ms * 1e-3), "attn_us_per_launch": us,
                      "attn_GBps": ab / (us * 1e-6) / 1e9, "kv_bytes": m.kv_logical_bytes(Bn, N)}
@@ -229,6 +251,8 @@ def bench_long_context(B, shape, blob, g, steps):
         torch.cuda.empty_cache()
     res["latency_plt_L4_vs_nonlooped_b128"] = res["plt_L4_b128"]["ms_per_step"] / res["nonlooped_L1_b128"]["ms_per_step"]
     res["latency_vanilla_L4_vs_plt_L4_b32"] = res["vanilla_loop_L4_b32"]["ms_per_step"] / res["plt_L4_b32"]["ms_per_step"]
+    res["latency_plt_L4_vs_nonlooped_b256_fp8kv"] = (res["plt_L4_b256_fp8kv"]["ms_per_step"]
+                                                      / res["nonlooped_L1_b256_fp8kv"]["ms_per_step"])
     return res
 
 
@@ -455,7 +479,7 @@ def main():
             c2 = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
             m2 = B.Model(c2, blob)
             k2 = B.KV(m2, Bn, N)
-            k2.buf.view(torch.bfloat16).normal_(0.0, 0.5, generator=g)
+            fill_kv_random(B, k2, g)
             lat[name] = time_steps(k2, pos, tok, 2, max(8, args.steps // 2))
             log(f"[bench] {name}: {lat[name]:.3f} ms/step")
             k2.close(); m2.close(); del k2
@@ -468,6 +492,28 @@ def main():
                                      "ms": [lat["nonlooped_L1"], lat["vanilla_loop_L2"], lat["clp_own_kv_L2"],
                                             lat["clp_share_only_L2"], lat["plt_L2"]]}
         out["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup)
+        # ---- the same step with e4m3 (FP8) K/V caches: the paper's serving setting, half the KV bytes.
+        # Separate rows: `value` above is the bf16-cache number.
+        f8 = {}
+        for name, Lx in [("nonlooped_L1", 1), ("plt_L2", 2), ("plt_L3", 3), ("plt_L4", 4)]:
+            c8 = B.make_config(shape, dtype=B.PLT_BF16, n_loops=Lx, window=w, kv_dtype=B.PLT_FP8_E4M3)
+            m8 = B.Model(c8, blob)
+            k8 = B.KV(m8, Bn, N)
+            fill_kv_random(B, k8, g)
+            m8.profile_enable(1 << B.PLT_PROF_ATTN)
+            ms8 = time_steps(k8, pos, tok, 2, max(8, args.steps // 2))
+            a_ms, a_n = m8.profile_read(B.PLT_PROF_ATTN, reset=True)
+            ab8 = attn_alg_bytes(Bn, Lx, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w, 2, 1)
+            us8 = a_ms * 1e3 / max(a_n, 1)
+            f8[name] = {"ms_per_step": ms8, "tokens_per_s": Bn / (ms8 * 1e-3), "attn_us_per_launch": us8,
+                        "attn_algorithmic_bytes": ab8, "attn_GBps": ab8 / (us8 * 1e-6) / 1e9,
+                        "kv_bytes_logical": m8.kv_logical_bytes(Bn, N)}
+            log(f"[bench] e4m3 caches {name}: {ms8:.3f} ms/step, attention {us8:.0f} us = {ab8 / (us8 * 1e-6) / 1e12:.2f} TB/s")
+            k8.close(); m8.close(); del k8
+            torch.cuda.empty_cache()
+        f8["latency_vs_nonlooped"] = {k: f8[k]["ms_per_step"] / f8["nonlooped_L1"]["ms_per_step"] for k in ("plt_L2", "plt_L3", "plt_L4")}
+        f8["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup, fp8=True)
+        out["fp8_kv_cache"] = f8
 
     if args.sweep:
         out["serving_sweep"] = bench_sweep(B, shape, blob, g)

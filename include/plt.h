@@ -47,6 +47,13 @@ typedef enum {
 } plt_status;
 
 enum { PLT_F32 = 0, PLT_BF16 = 1 };
+/* Cache-only element type: the 8-bit float e4m3 (1 sign, 4 exponent bits with bias 7, 3 mantissa
+ * bits, no infinities, largest value 448; the OCP "e4m3fn" encoding).  The paper serves its
+ * models with FP8 self-attention [inference efficiency evaluation recipe]; here that is a
+ * storage format: every K (after RoPE) and V is rounded once, to nearest even with saturation
+ * at +-448 and unit scale, when it enters a cache; attention reads the stored values exactly
+ * and keeps bf16 queries / softmax weights and float statistics.  bf16 models only. */
+enum { PLT_FP8_E4M3 = 2 };
 
 /* mode: which schedule / cache organisation the model object runs.                        */
 enum {
@@ -68,6 +75,8 @@ typedef struct plt_config {
   int32_t tie_embeddings; /* 1: classifier head = embedding matrix                          */
   float rope_theta;       /* rotary base (10000)                                            */
   float norm_eps;         /* RMSNorm epsilon                                                */
+  int32_t kv_dtype;       /* 0: caches hold the model dtype; PLT_FP8_E4M3: caches hold e4m3
+                             (needs dtype == PLT_BF16; halves the KV bytes of Table 1)      */
 } plt_config;
 
 typedef struct plt_model plt_model; /* opaque */
@@ -97,7 +106,7 @@ int plt_init(const plt_config* cfg, const void* dev_weights, size_t nbytes, void
 void plt_free(plt_model* m);
 
 /* Bytes of device memory a KV object for `batch` sequences of up to max_ctx positions needs
- * (physical: positions are padded to multiples of 32), and the logical size
+ * (physical: positions are padded to multiples of 32, of 64 for e4m3 caches), and the logical size
  * 2 * layers * Hkv * D * (n_ctx + (L-1) * w) * sizeof(elem) * batch of Table 1 (row 5; row 2
  * in vanilla-loop and own-KV modes: 2 * layers * Hkv * D * L * n_ctx; row 4: ... * n_ctx). */
 size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx);
@@ -135,7 +144,7 @@ const char* plt_last_error(void);
 int plt_kv_set_position(plt_kv* kv, int32_t pos);
 
 /* Copies one sequence's cache of one layer to / from host memory in a plain layout,
- * element type = model dtype:
+ * element type = the cache's (model dtype, or one e4m3 byte per element):
  *   shared K [Hkv, n, D], shared V [Hkv, n, D], then (CLP mode, L > 1) ring K
  *   [L-1, Hkv, w, D] and ring V [L-1, Hkv, w, D] in slot order (slot = position mod w).
  * `cache` selects the loop's cache in vanilla-loop and own-KV modes (0-based), must be 0 otherwise.
@@ -156,15 +165,19 @@ int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes);
 /* Kernel-only fused decode attention [Alg. 3 l.2-5, Eq. 2; first-loop row: global only].
  * All pointers are device pointers, element type `dtype`, in the cache's native layout:
  *   q        [B, L, Hq, D]                       (already rotated)
- *   k_share  [B, Hkv, n_pad, D]                  n_pad = plt_attn_pad32(n_alloc)
+ *   k_share  [B, Hkv, n_pad, D]                  n_pad = plt_attn_pad(dtype, n_alloc)
  *   v_share  [B, Hkv, n_pad/32, D, 32]           blocks of 32 positions, position fastest
- *   k_ring   [B, L-1, Hkv, w_pad, D]             w_pad = plt_attn_pad32(w)
+ *   k_ring   [B, L-1, Hkv, w_pad, D]             w_pad = plt_attn_pad(dtype, w)
  *   v_ring   [B, L-1, Hkv, w_pad/32, D, 32]
  *   z        [B, L-1, Hq] float gate logits;  y [B, L, Hq, D] output
+ * dtype PLT_FP8_E4M3: q and y are bf16, the four cache arrays hold e4m3 bytes.
  * n_ctx shared entries and n_ring (<= w) ring slots are valid for every sequence.
  * scratch: device buffer of plt_attn_scratch_bytes(...) bytes (split partials).
- * n_splits <= 0 lets the library choose.  Rows of loop 0 get the global branch only. */
+ * n_splits <= 0 lets the library choose.  Rows of loop 0 get the global branch only.
+ * plt_attn_pad: positions are padded to a multiple of 32 (64 for PLT_FP8_E4M3);
+ * plt_attn_pad32(n) = plt_attn_pad(PLT_BF16, n). */
 int32_t plt_attn_pad32(int32_t n);
+int32_t plt_attn_pad(int32_t dtype, int32_t n);
 size_t plt_attn_scratch_bytes(int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D);
 int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
                     int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring,
@@ -174,7 +187,8 @@ int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv
                     void* hip_stream);
 
 /* Device-side layout conversion for the hook above: plain [S, n, D] (S independent streams,
- * e.g. B*Hkv) -> K layout [S, n_pad, D] (pad rows zeroed) and V layout [S, n_pad/32, D, 32]. */
+ * e.g. B*Hkv) -> K layout [S, n_pad, D] (pad rows zeroed) and V layout [S, n_pad/32, D, 32].
+ * Elements are moved, never converted: for PLT_FP8_E4M3 source and destination hold e4m3 bytes. */
 int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,
                     void* dev_dst, void* hip_stream);
 int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,

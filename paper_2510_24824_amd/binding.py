@@ -14,6 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libplt.so")
 
 PLT_F32, PLT_BF16 = 0, 1
+PLT_FP8_E4M3 = 2      # cache-only element type (e4m3 bytes); q / y / weights stay bf16
 PLT_MODE_CLP, PLT_MODE_VANILLA_LOOP, PLT_MODE_CLP_SHARE_ONLY, PLT_MODE_CLP_OWN_KV = 0, 2, 3, 4
 (PLT_W_EMB, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO, PLT_W_NORM2, PLT_W_WGU,
  PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD) = range(11)
@@ -29,7 +30,8 @@ class PltError(RuntimeError):
 class plt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim",
                                          "ffn_hidden", "vocab", "n_loops", "window", "dtype", "mode",
-                                         "tie_embeddings")] + [("rope_theta", C.c_float), ("norm_eps", C.c_float)]
+                                         "tie_embeddings")] + [("rope_theta", C.c_float), ("norm_eps", C.c_float),
+                                                               ("kv_dtype", C.c_int32)]
 
 
 _P, _I, _Z = C.c_void_p, C.c_int32, C.c_size_t
@@ -54,6 +56,7 @@ _SIGS = {
     "plt_set_carry": (C.c_int, [_P, _P, _Z]),
     "plt_get_hidden": (C.c_int, [_P, _P, _Z]),
     "plt_attn_pad32": (_I, [_I]),
+    "plt_attn_pad": (_I, [_I, _I]),
     "plt_attn_scratch_bytes": (_Z, [_I, _I, _I, _I, _I]),
     "plt_attn_decode": (C.c_int, [_I] * 10 + [_P] * 8 + [_Z, _I, _P]),
     "plt_attn_pack_k": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
@@ -91,11 +94,11 @@ def _check(rc):
         raise PltError(rc, lib().plt_last_error().decode())
 
 
-def make_config(shape, dtype=PLT_BF16, mode=PLT_MODE_CLP, n_loops=None, window=None) -> plt_config:
+def make_config(shape, dtype=PLT_BF16, mode=PLT_MODE_CLP, n_loops=None, window=None, kv_dtype=0) -> plt_config:
     return plt_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                       shape.ffn_hidden, shape.vocab, shape.n_loops if n_loops is None else n_loops,
                       shape.window if window is None else window, dtype, mode,
-                      1 if shape.tie_embeddings else 0, shape.rope_theta, shape.norm_eps)
+                      1 if shape.tie_embeddings else 0, shape.rope_theta, shape.norm_eps, kv_dtype)
 
 
 def _stream():
@@ -218,6 +221,8 @@ class KV:
         _check(lib().plt_kv_set_position(self.h, pos))
 
     def _np_dtype(self):
+        if self.model.cfg.kv_dtype == PLT_FP8_E4M3:
+            return np.uint8
         return np.uint16 if self.model.cfg.dtype == PLT_BF16 else np.float32
 
     def export(self, seq, layer, n, cache=0):
@@ -227,7 +232,8 @@ class KV:
         nbytes = lib().plt_kv_export_bytes(self.h, n)
         host = np.zeros(nbytes // np.dtype(self._np_dtype()).itemsize, self._np_dtype())
         _check(lib().plt_kv_export(self.h, seq, layer, cache, n, host.ctypes.data_as(_P), nbytes))
-        vals = synth.bf16_from_bits(host) if c.dtype == PLT_BF16 else host
+        vals = (synth.e4m3_from_bits(host) if c.kv_dtype == PLT_FP8_E4M3 else
+                synth.bf16_from_bits(host) if c.dtype == PLT_BF16 else host)
         Hkv, D, w = c.n_kv_heads, c.head_dim, max(c.window, 1)
         nr = c.n_loops - 1 if c.mode == PLT_MODE_CLP else 0
         a = Hkv * n * D
@@ -242,7 +248,8 @@ class KV:
         c = self.model.cfg
         parts = [k_share, v_share] + ([k_ring, v_ring] if k_ring is not None else [])
         flat = np.concatenate([np.ascontiguousarray(p, np.float32).reshape(-1) for p in parts])
-        host = synth.bf16_bits(flat) if c.dtype == PLT_BF16 else flat
+        host = (synth.e4m3_bits(flat) if c.kv_dtype == PLT_FP8_E4M3 else
+                synth.bf16_bits(flat) if c.dtype == PLT_BF16 else flat)
         _check(lib().plt_kv_import(self.h, seq, layer, cache, n, host.ctypes.data_as(_P), host.nbytes))
 
     def get_carry(self):
@@ -271,17 +278,21 @@ class KV:
 # ---- kernel-only hooks -------------------------------------------------------------------
 
 def _to_dev(arr, dtype):
-    """float32 numpy (bf16-representable when dtype is bf16) -> device tensor of the storage type."""
+    """float32 numpy (exactly representable in the storage type) -> device tensor of the storage type
+    (e4m3: a uint8 tensor of codes)."""
     import torch
+    if dtype == PLT_FP8_E4M3:
+        from . import synth
+        return torch.from_numpy(synth.e4m3_bits(np.ascontiguousarray(arr, np.float32))).cuda()
     t = torch.from_numpy(np.ascontiguousarray(arr, np.float32)).cuda()
     return t.to(torch.bfloat16) if dtype == PLT_BF16 else t
 
 
 def attn_pack_k(dtype, src, n):
-    """src: device tensor [S, n, D] -> K layout [S, pad32(n), D]."""
+    """src: device tensor [S, n, D] -> K layout [S, pad(n), D]."""
     import torch
     S, _, D = src.shape
-    dst = torch.empty(S, lib().plt_attn_pad32(n), D, dtype=src.dtype, device="cuda")
+    dst = torch.empty(S, lib().plt_attn_pad(dtype, n), D, dtype=src.dtype, device="cuda")
     _check(lib().plt_attn_pack_k(dtype, S, n, D, _ptr(src.contiguous()), _ptr(dst), _stream()))
     return dst
 
@@ -290,7 +301,7 @@ def attn_pack_v(dtype, src, n):
     """src: device tensor [S, n, D] -> V layout [S, pad32(n)/32, D, 32]."""
     import torch
     S, _, D = src.shape
-    npad = lib().plt_attn_pad32(n)
+    npad = lib().plt_attn_pad(dtype, n)
     dst = torch.empty(S, npad // 32, D, 32, dtype=src.dtype, device="cuda")
     _check(lib().plt_attn_pack_v(dtype, S, n, D, _ptr(src.contiguous()), _ptr(dst), _stream()))
     return dst
@@ -306,7 +317,7 @@ class AttnDecode:
         Hkv, N = k_share.shape[1], k_share.shape[2]
         w = k_ring.shape[3] if L > 1 else 1
         self.dims = (B, L, Hq, Hkv, D, N, w)
-        self.q = _to_dev(q, dtype)
+        self.q = _to_dev(q, PLT_BF16 if dtype == PLT_FP8_E4M3 else dtype)
         self.ks = attn_pack_k(dtype, _to_dev(k_share, dtype).reshape(B * Hkv, N, D), N)
         self.vs = attn_pack_v(dtype, _to_dev(v_share, dtype).reshape(B * Hkv, N, D), N)
         if L > 1:

@@ -18,11 +18,15 @@
 // alternate tiles and merge their (m, l, O) states through LDS; workgroups that split one
 // stream leave (m, l, O) records in an HBM scratch that a small second kernel merges (a
 // device-scope fence per workgroup costs far more on this multi-die part than a launch).
+//
+// e4m3 caches (F8 = true): the same algebra on tiles of 64 keys.  A lane still fetches 16 bytes
+// per load, now 16 features of a key row (two MFMA K-chunks; the query fragments are laid out to
+// match) or 16 positions of a V row; v_cvt_scalef32_pk_bf16_fp8 expands the bytes exactly to the
+// bf16 operands the matrix cores take, so only the bytes streamed from HBM change (halved).
 #include "plt_internal.h"
 
 namespace plt {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
 
@@ -43,37 +47,66 @@ struct WaveState {
   }
 };
 
+template <int D, bool F8> struct KvTile;
 template <int D>
-struct KvTile {
+struct KvTile<D, false> {  // 32 keys of bf16
   uint4 k[2][D / 32];      // two 16-key sub-tiles, D/32 chunks of 8 features each
   uint4 v[D / 16];         // D/16 groups of 16 features, 8 keys per lane
+};
+template <int D>
+struct KvTile<D, true> {   // 64 keys of e4m3
+  uint4 k[4][D / 64];      // four 16-key sub-tiles, D/64 chunks of 16 features each
+  uint4 v[D / 16];         // D/16 groups of 16 features, 16 keys per lane
 };
 
 // kt -> first of the tile's 32 key rows (row stride D); vt -> the tile's V block [D][32]
 template <int D>
-__device__ inline void load_tile(KvTile<D>& t, const bf16_t* __restrict__ kt,
-                                 const bf16_t* __restrict__ vt, int m16, int g) {
+__device__ inline void load_tile_k(KvTile<D, false>& t, const char* __restrict__ kt, int m16, int g) {
+  const bf16_t* kp = (const bf16_t*)kt;
   const int key0 = 8 * (m16 >> 2) + (m16 & 3);   // A-row m16 of sub-tile a <-> key key0 + 4a
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
-      t.k[a][kk] = ldg16(kt + (size_t)(key0 + 4 * a) * D + kk * 32 + g * 8);
+      t.k[a][kk] = ldg16(kp + (size_t)(key0 + 4 * a) * D + kk * 32 + g * 8);
+}
+template <int D>
+__device__ inline void load_tile_v(KvTile<D, false>& t, const char* __restrict__ vt, int m16, int g) {
+  const bf16_t* vp = (const bf16_t*)vt;
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16(vt + (dt * 16 + m16) * 32 + g * 8);
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16(vp + (dt * 16 + m16) * 32 + g * 8);
+}
+// e4m3: kt -> first of the tile's 64 key rows (D bytes each); vt -> the tile's two V blocks [D][32]
+template <int D>
+__device__ inline void load_tile_k(KvTile<D, true>& t, const char* __restrict__ kt, int m16, int g) {
+  const int key0 = 16 * (m16 >> 2) + (m16 & 3);  // A-row m16 of sub-tile a <-> key key0 + 4a
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int kk = 0; kk < D / 64; ++kk)
+      t.k[a][kk] = *reinterpret_cast<const uint4*>(kt + (size_t)(key0 + 4 * a) * D + kk * 64 + g * 16);
+}
+template <int D>
+__device__ inline void load_tile_v(KvTile<D, true>& t, const char* __restrict__ vt, int m16, int g) {
+  // lane g: positions 16g .. 16g+15 of the tile = half a row of block g/2
+  const char* vb = vt + (size_t)(g >> 1) * (D * 32) + (g & 1) * 16;
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = *reinterpret_cast<const uint4*>(vb + (dt * 16 + m16) * 32);
 }
 
 // One 32-key step of the online softmax.  valid(j) tells whether key j (0..7 -> tile key 8g+j)
 // may be attended by this lane's row; it is consulted only when need_mask is set.
-template <int D, typename Valid>
-__device__ inline void tile_step(WaveState<D>& st, const KvTile<D>& t, const uint4 (&qf)[D / 32],
-                                 float scale_log2, bool need_mask, Valid valid) {
+// mid() runs between the two contractions (when the K half of the tile is no longer needed).
+template <int D, typename Valid, typename Mid>
+__device__ inline void tile_step(WaveState<D>& st, const KvTile<D, false>& t, const uint4 (&qf)[D / 32],
+                                 float scale_log2, bool need_mask, Valid valid, Mid mid) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kk = 0; kk < D / 32; ++kk) {
     s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[0][kk]), as_bf16x8(qf[kk]), s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.k[1][kk]), as_bf16x8(qf[kk]), s1, 0, 0, 0);
   }
+  mid();
   float sv[8];
 #pragma unroll
   for (int i = 0; i < 4; ++i) { sv[i] = s0[i] * scale_log2; sv[4 + i] = s1[i] * scale_log2; }
@@ -104,6 +137,60 @@ __device__ inline void tile_step(WaveState<D>& st, const KvTile<D>& t, const uin
   }
 }
 
+// The same step on a 64-key e4m3 tile.  valid(j), j = 0..15 <-> tile key 16g + j.  qf[2c + h] holds
+// the lane's query features c*64 + 16g + 8h .. +7, matching the two halves of a 16-byte key load.
+template <int D, typename Valid, typename Mid>
+__device__ inline void tile_step(WaveState<D>& st, const KvTile<D, true>& t, const uint4 (&qf)[D / 32],
+                                 float scale_log2, bool need_mask, Valid valid, Mid mid) {
+  f32x4 s[4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    s[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < D / 64; ++kk) {
+      const uint4 r = t.k[a][kk];
+      s[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.x, r.y), as_bf16x8(qf[2 * kk]), s[a], 0, 0, 0);
+      s[a] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.z, r.w), as_bf16x8(qf[2 * kk + 1]), s[a], 0, 0, 0);
+    }
+  }
+  mid();
+  float sv[16];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sv[4 * a + i] = s[a][i] * scale_log2;
+  if (need_mask) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) if (!valid(j)) sv[j] = NEG_INF;
+  }
+  float mx = sv[0];
+#pragma unroll
+  for (int j = 1; j < 16; ++j) mx = fmaxf(mx, sv[j]);
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(st.m, mx);
+  const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+  f32x8 p0, p1;
+  float ps = 0.f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    p0[j] = __builtin_amdgcn_exp2f(sv[j] - m_safe); p1[j] = __builtin_amdgcn_exp2f(sv[8 + j] - m_safe);
+    ps += p0[j] + p1[j];
+  }
+  st.l = st.l * alpha + ps;
+  st.m = m_new;
+  const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8), pb1 = __builtin_convertvector(p1, bf16x8);
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt) {
+    f32x4 a = st.acc[dt];
+    a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
+    const uint4 r = t.v[dt];
+    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.x, r.y), pb0, a, 0, 0, 0);
+    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.z, r.w), pb1, a, 0, 0, 0);
+  }
+}
+
 // LDS block used to merge the four waves of a workgroup.
 template <int D>
 struct WgMerge {
@@ -112,21 +199,23 @@ struct WgMerge {
   float acc[4][16][D + 4];
 };
 
-// After this call thread tid holds, for row tid/16 and features (tid%16)*(D/16) .. +D/16-1, the
-// workgroup-wide unnormalised output o[], the row maximum M and the denominator Lsum.
+// wg_park: a wave leaves its (m, l, O) state in its own part of the LDS block (no barrier inside).
 template <int D>
-__device__ inline void wg_merge(WgMerge<D>& sm, WaveState<D>& st, int wv, int m16, int g,
-                                float& M, float& Lsum, float (&o)[D / 16]) {
+__device__ inline void wg_park(WgMerge<D>& sm, const WaveState<D>& st, int wv, int m16, int g) {
   float l = st.l;
   l += __shfl_xor(l, 16, 64);
   l += __shfl_xor(l, 32, 64);
-  __syncthreads();                       // previous users of sm are done
   if (g == 0) { sm.m[wv][m16] = st.m; sm.l[wv][m16] = l; }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt)
 #pragma unroll
     for (int i = 0; i < 4; ++i) sm.acc[wv][m16][dt * 16 + 4 * g + i] = st.acc[dt][i];
-  __syncthreads();
+}
+// wg_collect (after a barrier that follows the four parks): thread tid gets, for row tid/16 and
+// features (tid%16)*(D/16) .. +D/16-1, the workgroup-wide unnormalised output o[], the row maximum
+// M and the denominator Lsum.
+template <int D>
+__device__ inline void wg_collect(const WgMerge<D>& sm, float& M, float& Lsum, float (&o)[D / 16]) {
   const int row = threadIdx.x >> 4, dc = (threadIdx.x & 15) * (D / 16);
   M = fmaxf(fmaxf(sm.m[0][row], sm.m[1][row]), fmaxf(sm.m[2][row], sm.m[3][row]));
   Lsum = 0.f;
@@ -141,6 +230,14 @@ __device__ inline void wg_merge(WgMerge<D>& sm, WaveState<D>& st, int wv, int m1
     for (int i = 0; i < D / 16; ++i) o[i] += f * sm.acc[w][row][dc + i];
   }
 }
+template <int D>
+__device__ inline void wg_merge(WgMerge<D>& sm, WaveState<D>& st, int wv, int m16, int g,
+                                float& M, float& Lsum, float (&o)[D / 16]) {
+  __syncthreads();                       // previous users of sm are done
+  wg_park<D>(sm, st, wv, m16, g);
+  __syncthreads();
+  wg_collect<D>(sm, M, Lsum, o);
+}
 
 template <int D>
 __device__ inline void store_row(bf16_t* __restrict__ dst, const float (&v)[D / 16]) {
@@ -153,7 +250,7 @@ __device__ inline void store_row(bf16_t* __restrict__ dst, const float (&v)[D / 
 
 struct AttnDecArgs {
   const bf16_t* q; const float* z; bf16_t* y;
-  const bf16_t* k_share; const bf16_t* v_share; const bf16_t* k_ring; const bf16_t* v_ring;
+  const char* k_share; const char* v_share; const char* k_ring; const char* v_ring;   // bf16 or e4m3 elements
   const int32_t* pos;          // per-sequence position being consumed, or null
   int n_ctx_uniform, n_ring_uniform;
   int n_pad, w_pad, w, n_rings;
@@ -188,8 +285,11 @@ __device__ inline void finalize_row(const AttnDecArgs& A, int b, int kvh, int rt
   store_row<D>(A.y + (((size_t)b * A.l_stride + A.l_off + r_loop) * A.Hq + r_head) * D + dc, out);
 }
 
-template <int D>
+template <int D, bool F8>
 __global__ __launch_bounds__(256, 2) void k_attn_decode(AttnDecArgs A) {
+  constexpr int TK = F8 ? 64 : 32;            // keys per tile
+  constexpr int ES = F8 ? 1 : 2;              // bytes per cache element
+  constexpr int KL = F8 ? 16 : 8;             // tile keys per lane group g: TK/4 consecutive ones
   __shared__ WgMerge<D> sm;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int split = blockIdx.x % A.n_splits, rt = blockIdx.x / A.n_splits;
@@ -198,7 +298,8 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode(AttnDecArgs A) {
   const int n_ring = A.pos ? (A.pos[b] + 1 < A.w ? A.pos[b] + 1 : A.w) : A.n_ring_uniform;
   const size_t stream = (size_t)b * A.Hkv + kvh;
 
-  // this lane's query row (B operand: lane (row, g) holds features kk*32 + g*8 .. +7)
+  // this lane's query row (B operand: lane (row, g) holds features kk*32 + g*8 .. +7; for e4m3
+  // caches fragment 2c + h holds features c*64 + 16g + 8h .. +7)
   const int qrow = rt * 16 + m16;
   const bool qrow_ok = qrow < A.n_rows;
   const int q_loop = qrow_ok ? qrow / A.G : 0;
@@ -207,66 +308,90 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode(AttnDecArgs A) {
 #pragma unroll
   for (int kk = 0; kk < D / 32; ++kk) {
     qf[kk] = make_uint4(0, 0, 0, 0);
-    if (qrow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.l_stride + A.l_off + q_loop) * A.Hq + q_head) * D + kk * 32 + g * 8);
+    const int qo = F8 ? (kk >> 1) * 64 + g * 16 + (kk & 1) * 8 : kk * 32 + g * 8;
+    if (qrow_ok) qf[kk] = ldg16(A.q + (((size_t)b * A.l_stride + A.l_off + q_loop) * A.Hq + q_head) * D + qo);
   }
 
   // ---- global branch: this split's share of the shared cache, alternate tiles per wave ----
-  const int n_tiles = (n_ctx + 31) >> 5;
+  const int n_tiles = (n_ctx + TK - 1) / TK;
   const int tps = (n_tiles + A.n_splits - 1) / A.n_splits;
   const int t_beg = split * tps;
   const int t_end = (t_beg + tps < n_tiles) ? t_beg + tps : n_tiles;
-  const bf16_t* kbase = A.k_share + stream * (size_t)A.n_pad * D;
-  const bf16_t* vbase = A.v_share + stream * (size_t)A.n_pad * D;
-  // ---- local branch (last split only): the valid 32-slot tiles of the rings of loops 2..L ----
+  const char* kbase = A.k_share + stream * (size_t)A.n_pad * D * ES;
+  const char* vbase = A.v_share + stream * (size_t)A.n_pad * D * ES;
+  // ---- local branch (last split only): the valid tiles of the rings of loops 2..L ----
   const bool do_local = !A.plain && A.n_rings > 0 && split == A.n_splits - 1;
-  const int tv = (n_ring + 31) >> 5;                       // valid tiles per ring
+  const int tv = (n_ring + TK - 1) / TK;                   // valid tiles per ring
   const int n_loc = do_local ? A.n_rings * tv : 0;
-  // One software pipeline over both kinds of tile: entries 0..n_my-1 are this split's shared tiles,
-  // entries n_my.. are ring tiles; wave wv takes entries wv, wv+4, ...  While an entry is being
-  // multiplied the next one (of either kind) is already in flight, so the window branch adds no
-  // exposed memory latency.  The two branches keep separate online-softmax states.
+  // One software pipeline over both kinds of tile; wave wv takes entries wv, wv+4, ...  While an
+  // entry is being multiplied the next one (of either kind) is already in flight, so the window
+  // branch adds no exposed memory latency.  bf16 caches: entries 0..n_my-1 are this split's shared
+  // tiles, then the ring tiles, and the two branches keep separate online-softmax states.  e4m3
+  // caches (RING_FIRST; their 64-key tiles leave no room for a second state): the ring tiles come
+  // first, and when a wave moves on to its shared tiles it parks the window state in LDS and
+  // starts over.
+  constexpr bool RING_FIRST = F8;
   WaveState<D> st, sl; st.init(); sl.init();
   {
     // Shared tiles are visited in a rotated order that differs from stream to stream (softmax does
     // not care about order): workgroups that run in lockstep then touch different HBM channels
     // instead of the same offset of their equally aligned streams.
-    KvTile<D> cur, nxt;
+    KvTile<D, F8> cur, nxt;
     const int n_my = t_end > t_beg ? t_end - t_beg : 0;    // a late split may own no shared tile
     const int n_ent = n_my + n_loc;
     const int rot = n_my > 0 ? (int)((stream * 13u + (unsigned)split * 7u) % (unsigned)n_my) : 0;
     auto tile_of = [&](int u) { int t = u + rot; if (t >= n_my) t -= n_my; return t_beg + t; };
-    auto load_entry = [&](KvTile<D>& tl, int e) {
-      if (e < n_my) {
-        const int t = tile_of(e);
-        load_tile<D>(tl, kbase + (size_t)t * 32 * D, vbase + (size_t)t * 32 * D, m16, g);
+    auto is_ring = [&](int e) { return RING_FIRST ? e < n_loc : e >= n_my; };
+    auto ring_idx = [&](int e) { return RING_FIRST ? e : e - n_my; };
+    auto share_idx = [&](int e) { return RING_FIRST ? e - n_loc : e; };
+    // which = 1: the K half of entry e, 2: the V half, 3: both
+    auto load_entry = [&](KvTile<D, F8>& tl, int e, int which) {
+      const char* kp; const char* vp;
+      if (!is_ring(e)) {
+        const size_t to = (size_t)tile_of(share_idx(e)) * TK * D * ES;
+        kp = kbase + to; vp = vbase + to;
       } else {
-        const int j = e - n_my, rl = j / tv, tr = j - rl * tv;
-        const size_t rs = (((size_t)b * A.n_rings + rl) * A.Hkv + kvh) * (size_t)A.w_pad * D;
-        load_tile<D>(tl, A.k_ring + rs + (size_t)tr * 32 * D, A.v_ring + rs + (size_t)tr * 32 * D, m16, g);
+        const int j = ring_idx(e), rl = j / tv, tr = j - rl * tv;
+        const size_t ro = ((((size_t)b * A.n_rings + rl) * A.Hkv + kvh) * (size_t)A.w_pad + (size_t)tr * TK) * D * ES;
+        kp = A.k_ring + ro; vp = A.v_ring + ro;
       }
+      if (which & 1) load_tile_k<D>(tl, kp, m16, g);
+      if (which & 2) load_tile_v<D>(tl, vp, m16, g);
     };
+    // e4m3 tiles: the next tile's V half is requested only after the current K half has been
+    // multiplied (its registers are free by then); bf16 tiles fit and are requested whole
+    constexpr int EARLY = F8 ? 1 : 3;
+    bool parked = !(RING_FIRST && do_local);     // is the window state already out of the way?
     int e = wv;
-    if (e < n_ent) load_entry(cur, e);
+    if (e < n_ent) load_entry(cur, e, 3);
     for (; e < n_ent; e += 4) {
       const int en = e + 4;
-      if (en < n_ent) load_entry(nxt, en);
-      if (e < n_my) {
-        const int t = tile_of(e), kb = t * 32 + 8 * g;
-        tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * 32 > n_ctx, [&](int j) { return kb + j < n_ctx; });
+      if (en < n_ent) load_entry(nxt, en, EARLY);
+      auto mid = [&]() { if (F8 && en < n_ent) load_entry(nxt, en, 2); };
+      if (!is_ring(e)) {
+        if (!parked) { wg_park<D>(sm, st, wv, m16, g); st.init(); parked = true; }
+        const int t = tile_of(share_idx(e)), kb = t * TK + KL * g;
+        tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * TK > n_ctx, [&](int j) { return kb + j < n_ctx; }, mid);
       } else {
-        const int j0 = e - n_my, rl = j0 / tv, tr = j0 - rl * tv, sb = tr * 32 + 8 * g;
+        const int j0 = ring_idx(e), rl = j0 / tv, tr = j0 - rl * tv, sb = tr * TK + KL * g;
         const bool mine = qrow_ok && (q_loop == rl + 1);
-        tile_step<D>(sl, cur, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); });
+        tile_step<D>(RING_FIRST ? st : sl, cur, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); }, mid);
       }
       if (en < n_ent) cur = nxt;
     }
+    if (!parked) { wg_park<D>(sm, st, wv, m16, g); st.init(); }   // this wave had ring tiles only
   }
   float Mg, Lg, og[D / 16];
-  wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
   float Ml = NEG_INF, Ll = 0.f, ol[D / 16];
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) ol[i] = 0.f;
-  if (do_local) wg_merge<D>(sm, sl, wv, m16, g, Ml, Ll, ol);
+  if (RING_FIRST) {
+    if (do_local) { __syncthreads(); wg_collect<D>(sm, Ml, Ll, ol); }
+    wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
+  } else {
+    wg_merge<D>(sm, st, wv, m16, g, Mg, Lg, og);
+    if (do_local) wg_merge<D>(sm, sl, wv, m16, g, Ml, Ll, ol);
+  }
 
   // ---- thread (row, feature chunk) view from here on ----
   const int dc = (tid & 15) * (D / 16);
@@ -331,10 +456,11 @@ size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D) {
   return bytes;
 }
 
-int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx) {
+int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx, int kv_fp8) {
   const int n_rt = (L * G + 15) / 16;
   const long streams = (long)B * Hkv * n_rt;
-  const int n_tiles = (n_ctx + 31) / 32;
+  const int tk = kv_fp8 ? 64 : 32;
+  const int n_tiles = (n_ctx + tk - 1) / tk;
   // one workgroup per stream when that already covers every compute unit; else split so that
   // about one workgroup per compute unit exists (more splits only add merge work: measured),
   // keeping >= 8 tiles (2 per wave) per workgroup (an eight-wave workgroup variant measured slower)
@@ -349,12 +475,12 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx) {
 
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform, Dims dm,
-                             int plain, void* scratch, int n_splits, int l_off, int l_stride) {
+                             int plain, void* scratch, int n_splits, int l_off, int l_stride, int kv_fp8) {
   AttnDecArgs A;
   A.l_off = l_off; A.l_stride = l_stride > 0 ? l_stride : dm.L;
   A.q = q; A.z = z; A.y = y;
-  A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
-  A.k_ring = (const bf16_t*)kv.k_ring; A.v_ring = (const bf16_t*)kv.v_ring;
+  A.k_share = (const char*)kv.k_share; A.v_share = (const char*)kv.v_share;
+  A.k_ring = (const char*)kv.k_ring; A.v_ring = (const char*)kv.v_ring;
   A.pos = pos; A.n_ctx_uniform = n_ctx_uniform; A.n_ring_uniform = n_ring_uniform;
   A.n_pad = kv.n_pad; A.w_pad = kv.w_pad; A.w = kv.w; A.n_rings = plain ? 0 : kv.n_rings;
   A.L = dm.L; A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
@@ -368,10 +494,12 @@ void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf1
   A.part_loc = A.part + slots * 64 * rec;
   dim3 grid(A.n_splits * A.n_rt, dm.Hkv, dm.B), cgrid(A.n_rt, dm.Hkv, dm.B);
   if (dm.D == 64) {
-    hipLaunchKernelGGL(k_attn_decode<64>, grid, dim3(256), 0, s, A);
+    if (kv_fp8) hipLaunchKernelGGL((k_attn_decode<64, true>), grid, dim3(256), 0, s, A);
+    else hipLaunchKernelGGL((k_attn_decode<64, false>), grid, dim3(256), 0, s, A);
     if (A.n_splits > 1) hipLaunchKernelGGL(k_attn_combine<64>, cgrid, dim3(256), 0, s, A);
   } else {
-    hipLaunchKernelGGL(k_attn_decode<128>, grid, dim3(256), 0, s, A);
+    if (kv_fp8) hipLaunchKernelGGL((k_attn_decode<128, true>), grid, dim3(256), 0, s, A);
+    else hipLaunchKernelGGL((k_attn_decode<128, false>), grid, dim3(256), 0, s, A);
     if (A.n_splits > 1) hipLaunchKernelGGL(k_attn_combine<128>, cgrid, dim3(256), 0, s, A);
   }
 }

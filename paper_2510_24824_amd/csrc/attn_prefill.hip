@@ -11,11 +11,11 @@
 // algebra is the decode kernel's: S^T = K Q^T, O^T += V^T P^T with v_mfma_f32_16x16x32_bf16, one
 // query row per lane in S^T, P^T and O^T, row maxima via two wavefront shuffles.  A wave owns its
 // rows for the whole key range, so no cross-wave merge is needed.
+// e4m3 caches (F8): the bytes are expanded to bf16 (exactly) on their way into LDS; the rest is shared.
 #include "plt_internal.h"
 
 namespace plt {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) float f32x8;
 
@@ -105,48 +105,59 @@ __device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D>& sm,
 struct PfArgs {
   const bf16_t* q; const float* z; bf16_t* y;
   float* tmp;      // [rows, Hq*D] float: g * y_local parked between the two passes (gated rows only)
-  const bf16_t* k_share; const bf16_t* v_share; const bf16_t* k_loc; const bf16_t* v_loc;
+  const char* k_share; const char* v_share; const char* k_loc; const char* v_loc;   // bf16 or e4m3 elements
   int n, n_pad, n_pad_loc, w, b0, Hq, Hkv, G, gated, n_qt;
   float scale_log2;
 };
 
 // Streams key tiles t_beg..t_end-1 of one K/V stream through LDS and applies them to the wave's
 // two query tiles.  All 256 threads of the workgroup must call this together.
-template <int D>
-__device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const bf16_t* __restrict__ kbase,
-                               const bf16_t* __restrict__ vbase, int t_beg, int t_end, const uint4 (&qf)[2][D / 32],
+template <int D, bool F8>
+__device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const char* __restrict__ kbase,
+                               const char* __restrict__ vbase, int t_beg, int t_end, const uint4 (&qf)[2][D / 32],
                                float scale_log2, const int (&lo)[2], const int (&hi)[2], int row_min, int row_max,
                                int m16, int g) {
   const int tid = threadIdx.x;
-  constexpr int KCH = 32 * D / 8 / 256;       // 16-byte chunks of the K tile per thread (1 or 2)
+  constexpr int ES = F8 ? 1 : 2;
+  constexpr int TILE_BYTES = 32 * D * ES;                       // of the K tile and of the V block alike
+  constexpr int KCH = (TILE_BYTES / 16 + 255) / 256;            // 16-byte chunks per thread (1 or 2)
+  constexpr int NCH = TILE_BYTES / 16;                          // chunks per tile (may be < 256)
   // register staging of the next tile (plain loops: the arrays must stay in registers)
   uint4 rk[KCH], rv[KCH];
 #pragma unroll
   for (int i = 0; i < KCH; ++i) { rk[i] = make_uint4(0, 0, 0, 0); rv[i] = make_uint4(0, 0, 0, 0); }
-  if (t_beg < t_end) {
+  auto fetch = [&](int t) {
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
-      rk[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)t_beg * 32 * D + (size_t)(tid + i * 256) * 8);
-      rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t_beg * 32 * D + (size_t)(tid + i * 256) * 8);
+      const int ch = tid + i * 256;
+      if (NCH % 256 == 0 || ch < NCH) {
+        rk[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
+        rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
+      }
     }
-  }
+  };
+  if (t_beg < t_end) fetch(t_beg);
   for (int t = t_beg; t < t_end; ++t) {
     __syncthreads();                         // every wave is done with the previous tile
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int ch = tid + i * 256;
-      const int row = ch / (D / 8), col = (ch % (D / 8)) * 8;
-      *reinterpret_cast<uint4*>(&sm.k[row][col]) = rk[i];
-      *reinterpret_cast<uint4*>(&sm.v[ch / 4][(ch % 4) * 8]) = rv[i];
-    }
-    __syncthreads();
-    if (t + 1 < t_end) {
-#pragma unroll
-      for (int i = 0; i < KCH; ++i) {
-        rk[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)(t + 1) * 32 * D + (size_t)(tid + i * 256) * 8);
-        rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)(t + 1) * 32 * D + (size_t)(tid + i * 256) * 8);
+      if (F8) {
+        if (NCH % 256 == 0 || ch < NCH) {
+          const int row = ch / (D / 16), col = (ch % (D / 16)) * 16;
+          *reinterpret_cast<bf16x8*>(&sm.k[row][col]) = e4m3x8_to_bf16(rk[i].x, rk[i].y);
+          *reinterpret_cast<bf16x8*>(&sm.k[row][col + 8]) = e4m3x8_to_bf16(rk[i].z, rk[i].w);
+          *reinterpret_cast<bf16x8*>(&sm.v[ch >> 1][(ch & 1) * 16]) = e4m3x8_to_bf16(rv[i].x, rv[i].y);
+          *reinterpret_cast<bf16x8*>(&sm.v[ch >> 1][(ch & 1) * 16 + 8]) = e4m3x8_to_bf16(rv[i].z, rv[i].w);
+        }
+      } else {
+        const int row = ch / (D / 8), col = (ch % (D / 8)) * 8;
+        *reinterpret_cast<uint4*>(&sm.k[row][col]) = rk[i];
+        *reinterpret_cast<uint4*>(&sm.v[ch / 4][(ch % 4) * 8]) = rv[i];
       }
     }
+    __syncthreads();
+    if (t + 1 < t_end) fetch(t + 1);
     const int kb = t * 32;
     // skip tiles no row of this wave may attend; mask only tiles that straddle a bound
     int lo_min = lo[0] < lo[1] ? lo[0] : lo[1];
@@ -157,8 +168,9 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const
   }
 }
 
-template <int D>
+template <int D, bool F8>
 __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
+  constexpr int ES = F8 ? 1 : 2;
   __shared__ __attribute__((aligned(16))) PfLds<D> sm;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int qt = A.n_qt - 1 - (int)blockIdx.x;        // longest key ranges first
@@ -192,7 +204,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
     st[0].init(); st[1].init();
     const size_t stream = (size_t)b * A.Hkv + kvh;
     int j_lo = p0 - A.w + 1; if (j_lo < 0) j_lo = 0;
-    pf_pass<D>(st, sm, A.k_loc + stream * (size_t)A.n_pad_loc * D, A.v_loc + stream * (size_t)A.n_pad_loc * D,
+    pf_pass<D, F8>(st, sm, A.k_loc + stream * (size_t)A.n_pad_loc * D * ES, A.v_loc + stream * (size_t)A.n_pad_loc * D * ES,
                j_lo >> 5, (p_last >> 5) + 1, qf, A.scale_log2, lo_l, hi, row_min, row_max, m16, g);
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
@@ -213,7 +225,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
   st[0].init(); st[1].init();
   {
     const size_t stream = (size_t)(A.b0 + b) * A.Hkv + kvh;
-    pf_pass<D>(st, sm, A.k_share + stream * (size_t)A.n_pad * D, A.v_share + stream * (size_t)A.n_pad * D, 0,
+    pf_pass<D, F8>(st, sm, A.k_share + stream * (size_t)A.n_pad * D * ES, A.v_share + stream * (size_t)A.n_pad * D * ES, 0,
                (p_last >> 5) + 1, qf, A.scale_log2, lo_g, hi, row_min, row_max, m16, g);
   }
   // epilogue: lane (row m16, g) holds features dt*16 + 4g .. +3 of its two rows
@@ -243,19 +255,24 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
 }  // namespace
 
 void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
-                              KvView kv, int Bc, int n, int loop, Dims dm, int plain) {
+                              KvView kv, int Bc, int n, int loop, Dims dm, int plain, int kv_fp8) {
   PfArgs A;
   A.q = q; A.z = z; A.y = y; A.tmp = local_tmp;
-  A.k_share = (const bf16_t*)kv.k_share; A.v_share = (const bf16_t*)kv.v_share;
-  A.k_loc = (const bf16_t*)kv.k_loc; A.v_loc = (const bf16_t*)kv.v_loc;
+  A.k_share = (const char*)kv.k_share; A.v_share = (const char*)kv.v_share;
+  A.k_loc = (const char*)kv.k_loc; A.v_loc = (const char*)kv.v_loc;
   A.n = n; A.n_pad = kv.n_pad; A.n_pad_loc = kv.n_pad_loc; A.w = kv.w; A.b0 = kv.b0;
   A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
   A.gated = (!plain && loop > 0) ? 1 : 0;
   A.n_qt = (n + PF_QROWS - 1) / PF_QROWS;
   A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
   dim3 grid(A.n_qt, dm.Hq, Bc);
-  if (dm.D == 64) hipLaunchKernelGGL(k_attn_prefill2<64>, grid, dim3(256), 0, s, A);
-  else hipLaunchKernelGGL(k_attn_prefill2<128>, grid, dim3(256), 0, s, A);
+  if (dm.D == 64) {
+    if (kv_fp8) hipLaunchKernelGGL((k_attn_prefill2<64, true>), grid, dim3(256), 0, s, A);
+    else hipLaunchKernelGGL((k_attn_prefill2<64, false>), grid, dim3(256), 0, s, A);
+  } else {
+    if (kv_fp8) hipLaunchKernelGGL((k_attn_prefill2<128, true>), grid, dim3(256), 0, s, A);
+    else hipLaunchKernelGGL((k_attn_prefill2<128, false>), grid, dim3(256), 0, s, A);
+  }
 }
 
 }  // namespace plt

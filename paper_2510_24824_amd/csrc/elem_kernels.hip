@@ -147,7 +147,7 @@ template void launch_resid_norm<bf16_t>(hipStream_t, float*, int, int, const flo
 
 // ---- S3: RoPE, gate logit (Eq. 2, on the un-rotated query), cache append ----
 // grid (Hq + 2*Hkv, R), 64 threads: thread j < D/2 owns the pair (j, j + D/2) of one head vector.
-template <typename T>
+template <typename T, typename KT>
 __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
                               const float* __restrict__ gate_w, const float* __restrict__ gate_b,
                               T* __restrict__ q_out, float* __restrict__ z_out, KvView kv, RowMap rm,
@@ -210,11 +210,11 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     size_t stream = (size_t)bg * Hkv + kh;
     const size_t coff = mode == 3 ? (size_t)l * kv.cache_stride : 0;
     if (is_k) {
-      T* dst = (T*)kv.k_share + coff + (stream * kv.n_pad + p) * D;
-      st<T>(dst + j, v0); st<T>(dst + j + half, v1);
+      KT* dst = (KT*)kv.k_share + coff + (stream * kv.n_pad + p) * D;
+      st<KT>(dst + j, v0); st<KT>(dst + j + half, v1);
     } else {
-      T* dst = (T*)kv.v_share + coff + stream * (size_t)kv.n_pad * D;
-      st<T>(dst + vblk_index(p, j, D), v0); st<T>(dst + vblk_index(p, j + half, D), v1);
+      KT* dst = (KT*)kv.v_share + coff + stream * (size_t)kv.n_pad * D;
+      st<KT>(dst + vblk_index(p, j, D), v0); st<KT>(dst + vblk_index(p, j + half, D), v1);
     }
     return;
   }
@@ -223,11 +223,11 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
   if (rm.prefill) {
     size_t stream = (size_t)b * Hkv + kh;
     if (is_k) {
-      T* dst = (T*)kv.k_loc + (stream * kv.n_pad_loc + p) * D;
-      st<T>(dst + j, v0); st<T>(dst + j + half, v1);
+      KT* dst = (KT*)kv.k_loc + (stream * kv.n_pad_loc + p) * D;
+      st<KT>(dst + j, v0); st<KT>(dst + j + half, v1);
     } else {
-      T* dst = (T*)kv.v_loc + stream * (size_t)kv.n_pad_loc * D;
-      st<T>(dst + vblk_index(p, j, D), v0); st<T>(dst + vblk_index(p, j + half, D), v1);
+      KT* dst = (KT*)kv.v_loc + stream * (size_t)kv.n_pad_loc * D;
+      st<KT>(dst + vblk_index(p, j, D), v0); st<KT>(dst + vblk_index(p, j + half, D), v1);
     }
     if (p < n - kv.w) return;
   }
@@ -235,23 +235,24 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     const int slot = p % kv.w;
     size_t stream = ((size_t)bg * kv.n_rings + (l - 1)) * Hkv + kh;
     if (is_k) {
-      T* dst = (T*)kv.k_ring + (stream * kv.w_pad + slot) * D;
-      st<T>(dst + j, v0); st<T>(dst + j + half, v1);
+      KT* dst = (KT*)kv.k_ring + (stream * kv.w_pad + slot) * D;
+      st<KT>(dst + j, v0); st<KT>(dst + j + half, v1);
     } else {
-      T* dst = (T*)kv.v_ring + stream * (size_t)kv.w_pad * D;
-      st<T>(dst + vblk_index(slot, j, D), v0); st<T>(dst + vblk_index(slot, j + half, D), v1);
+      KT* dst = (KT*)kv.v_ring + stream * (size_t)kv.w_pad * D;
+      st<KT>(dst + vblk_index(slot, j, D), v0); st<KT>(dst + vblk_index(slot, j + half, D), v1);
     }
   }
 }
-template <typename T>
+template <typename T, typename KT>
 void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
                         const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
                         Dims dm, const double* inv_freq, int mode) {
-  hipLaunchKernelGGL(k_rope_append<T>, dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
+  hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
                      gate_w, gate_b, q_out, z_out, kv, rm, dm, inv_freq, mode);
 }
-template void launch_rope_append<float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, const double*, int);
-template void launch_rope_append<bf16_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, const double*, int);
+template void launch_rope_append<float, float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, const double*, int);
+template void launch_rope_append<bf16_t, bf16_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, const double*, int);
+template void launch_rope_append<bf16_t, fp8_t>(hipStream_t, const float*, int, size_t, const float*, const float*, bf16_t*, float*, KvView, RowMap, int, Dims, const double*, int);
 
 // ---- SwiGLU: act = silu(gate) * up, gate = columns [0,F), up = columns [F,2F) ----
 template <typename T>
@@ -420,5 +421,8 @@ template void launch_pack_v<float>(hipStream_t, const float*, float*, int, int, 
 template void launch_pack_v<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, int, int, int);
 template void launch_unpack_v<float>(hipStream_t, const float*, float*, int, int, int, int);
 template void launch_unpack_v<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, int, int, int);
+template void launch_pack_k<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
+template void launch_pack_v<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
+template void launch_unpack_v<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
 
 }  // namespace plt

@@ -15,7 +15,6 @@
 
 namespace plt {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int BM = 128, BN = 64, BK = 64, LDK = BK + 8;   // LDS row stride 144 B: conflict-light

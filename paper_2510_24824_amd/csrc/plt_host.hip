@@ -38,6 +38,8 @@ struct plt_model {
   std::vector<LayerW> layers;
   const void* emb; const float* norm_f; const void* head;
   int es;   // element size of the model dtype
+  int kes;  // element size of the caches (es, or 1 for e4m3 caches)
+  bool kv8; // caches hold e4m3 bytes
   double* inv_freq = nullptr;   // device [D/2]: rotary frequencies theta^(-2j/D), computed in double
 };
 struct plt_kv {
@@ -70,6 +72,8 @@ static bool cfg_valid(const plt_config* c, const char** why) {
     *why = "bf16 needs d_model and ffn_hidden to be multiples of 64"; return false;
   }
   if (!(c->rope_theta > 0.f) || !(c->norm_eps >= 0.f)) { *why = "bad rope_theta / norm_eps"; return false; }
+  if (c->kv_dtype != 0 && c->kv_dtype != PLT_FP8_E4M3) { *why = "unknown kv_dtype"; return false; }
+  if (c->kv_dtype == PLT_FP8_E4M3 && c->dtype != PLT_BF16) { *why = "e4m3 caches need dtype PLT_BF16"; return false; }
   return true;
 }
 
@@ -138,6 +142,8 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
   if (!m) return fail(PLT_ENOMEM, "plt_init: out of host memory");
   m->cfg = *cfg; m->stream = (hipStream_t)hip_stream; m->blob = (const char*)dev_weights;
   m->es = cfg->dtype == PLT_BF16 ? 2 : 4;
+  m->kv8 = cfg->kv_dtype == PLT_FP8_E4M3;
+  m->kes = m->kv8 ? 1 : m->es;
   auto at = [&](int layer, int which) -> const void* {
     size_t off = 0, n = 0; blob_walk(cfg, layer, which, &off, &n); return m->blob + off;
   };
@@ -227,15 +233,15 @@ enum { V_PLT = 0,         // loop 1: shared cache; loops >= 2: ring + gated wind
 extern "C" size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx) {
   if (!m || batch < 1 || max_ctx < 1) { fail(PLT_EINVAL, "plt_kv_bytes: bad argument"); return 0; }
   const plt_config& c = m->cfg;
-  const size_t share = (size_t)batch * c.n_kv_heads * pad32(max_ctx) * c.head_dim;
-  const size_t ring = (size_t)batch * n_rings_of(c) * c.n_kv_heads * pad32(c.window > 0 ? c.window : 1) * c.head_dim;
-  return align256(2 * share * c.n_layers * n_caches_of(c) * m->es) + align256(2 * ring * c.n_layers * m->es);
+  const size_t share = (size_t)batch * c.n_kv_heads * pad_kv(max_ctx, m->kv8) * c.head_dim;
+  const size_t ring = (size_t)batch * n_rings_of(c) * c.n_kv_heads * pad_kv(c.window > 0 ? c.window : 1, m->kv8) * c.head_dim;
+  return align256(2 * share * c.n_layers * n_caches_of(c) * m->kes) + align256(2 * ring * c.n_layers * m->kes);
 }
 
 extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_t n_ctx) {
   if (!m || batch < 1 || n_ctx < 0) { fail(PLT_EINVAL, "plt_kv_logical_bytes: bad argument"); return 0; }
   const plt_config& c = m->cfg;
-  const size_t per = (size_t)2 * c.n_layers * c.n_kv_heads * c.head_dim * m->es * batch;
+  const size_t per = (size_t)2 * c.n_layers * c.n_kv_heads * c.head_dim * m->kes * batch;
   if (is_plt(c)) return per * ((size_t)n_ctx + (size_t)(c.n_loops - 1) * c.window);
   return per * (size_t)n_caches_of(c) * n_ctx;
 }
@@ -267,13 +273,13 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   if ((long)batch * c.n_loops > 60000) return fail(PLT_EINVAL, "plt_kv_alloc: batch * n_loops too large");
   plt_kv* kv = new (std::nothrow) plt_kv();
   if (!kv) return fail(PLT_ENOMEM, "plt_kv_alloc: out of host memory");
-  kv->m = m; kv->B = batch; kv->max_ctx = max_ctx; kv->n_pad = pad32(max_ctx);
-  kv->w_pad = pad32(c.window > 0 ? c.window : 1);
+  kv->m = m; kv->B = batch; kv->max_ctx = max_ctx; kv->n_pad = pad_kv(max_ctx, m->kv8);
+  kv->w_pad = pad_kv(c.window > 0 ? c.window : 1, m->kv8);
   kv->n_caches = n_caches_of(c); kv->n_rings = n_rings_of(c);
   kv->buf = (char*)dev_buf;
   kv->share_elems = (size_t)batch * c.n_kv_heads * kv->n_pad * c.head_dim;
   kv->ring_elems = (size_t)batch * kv->n_rings * c.n_kv_heads * kv->w_pad * c.head_dim;
-  kv->ring_base = align256(2 * kv->share_elems * c.n_layers * kv->n_caches * m->es);
+  kv->ring_base = align256(2 * kv->share_elems * c.n_layers * kv->n_caches * m->kes);
   kv->pos = 0; kv->started = false;
   // cleared so that padded / not-yet-written slots hold finite values (masked keys multiply
   // their value rows by zero weights, which must not meet NaN bit patterns)
@@ -322,7 +328,7 @@ static KvView kv_view(const plt_kv* kv, int layer, int cache) {
   const plt_model* m = kv->m;
   const plt_config& c = m->cfg;
   KvView v;
-  const size_t es = m->es;
+  const size_t es = m->kes;
   char* sb = kv->buf + ((size_t)cache * c.n_layers + layer) * 2 * kv->share_elems * es;
   v.k_share = sb; v.v_share = sb + kv->share_elems * es;
   if (kv->n_rings > 0) {
@@ -368,32 +374,36 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     KvView v = kv_view(kv, l, cache);
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
     int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                               // Alg. 3 l.1
-    launch_rope_append<T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
-                          dm, m->inv_freq, variant);
+    if (m->kv8)
+      launch_rope_append<bf16_t, fp8_t>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (bf16_t*)wk.q, wk.z, v, rm,
+                                        R, dm, m->inv_freq, variant);
+    else
+      launch_rope_append<T, T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
+                               dm, m->inv_freq, variant);
     const bool dec = !rm.prefill;
     const int plain = variant != V_PLT;
     if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
       ProfScope prof(m, PLT_PROF_ATTN, dec);
       if (rm.prefill) {
         launch_attn_prefill_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, wk.attn_tmp, v, Bc, n_prefill,
-                                 rm.loop_fixed, dm, plain ? 1 : 0);
+                                 rm.loop_fixed, dm, plain ? 1 : 0, m->kv8);
       } else {
         const int G = Hq / Hkv;
         if (variant == V_OWN_KV) {
           // loop l's rows attend cache l: one launch per loop, G rows per (sequence, kv head) stream
           Dims d1 = dm; d1.L = 1;
-          const int ns = attn_mfma_default_splits(kv->B, Hkv, 1, G, kv->pos + 1);
+          const int ns = attn_mfma_default_splits(kv->B, Hkv, 1, G, kv->pos + 1, m->kv8);
           for (int lp = 0; lp < attn_L; ++lp) {
             KvView vl = v;
-            vl.k_share = (char*)v.k_share + (size_t)lp * v.cache_stride * m->es;
-            vl.v_share = (char*)v.v_share + (size_t)lp * v.cache_stride * m->es;
+            vl.k_share = (char*)v.k_share + (size_t)lp * v.cache_stride * m->kes;
+            vl.v_share = (char*)v.v_share + (size_t)lp * v.cache_stride * m->kes;
             launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, vl, kv->pos_dev, 0, 0, d1, 1,
-                                    kv->attn_scratch, ns, lp, attn_L);
+                                    kv->attn_scratch, ns, lp, attn_L, m->kv8);
           }
         } else {
-          const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1);
+          const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1, m->kv8);
           launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, kv->pos_dev, 0, 0, dm,
-                                  plain ? 1 : 0, kv->attn_scratch, ns);
+                                  plain ? 1 : 0, kv->attn_scratch, ns, 0, 0, m->kv8);
         }
       }
     } else {
@@ -478,12 +488,12 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   const plt_config& c = m->cfg;
   hipStream_t s = m->stream;
   const int B = kv->B, L = c.n_loops, d = c.d_model, Hq = c.n_heads, Hkv = c.n_kv_heads, D = c.head_dim,
-            F = c.ffn_hidden, V = c.vocab, es = m->es;
+            F = c.ffn_hidden, V = c.vocab, es = m->es, kes = m->kes;
   const int Nqkv = (Hq + 2 * Hkv) * D;
   int Bc = PREFILL_ROWS / n; if (Bc < 1) Bc = 1; if (Bc > B) Bc = B;
   const int Rc = Bc * n;
   if (Rc > 60000) return fail(PLT_EINVAL, "plt_prefill: prompt too long (%d positions; limit 60000)", n);
-  const int n_pad_loc = pad32(n);
+  const int n_pad_loc = pad_kv(n, m->kv8);
   size_t go = gemm_out_need(c, Rc, Nqkv, d), t;
   if ((t = gemm_out_need(c, Rc, d, Hq * D)) > go) go = t;
   if ((t = gemm_out_need(c, Rc, 2 * F, d)) > go) go = t;
@@ -495,12 +505,12 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * es),
                o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
                o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * F * es),
-               o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * es), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * es),
+               o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes),
                o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
   char* ws = nullptr;
   hipError_t e = hipMalloc((void**)&ws, off);
   if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
-  (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * es), s);
+  (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * kes), s);
   Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act,
           (float*)(ws + o_tmp)};
   float* hprev = (float*)(ws + o_h);
@@ -565,7 +575,7 @@ extern "C" size_t plt_kv_export_bytes(const plt_kv* kv, int32_t n) {
   if (!kv || n < 0 || n > kv->max_ctx) { fail(PLT_EINVAL, "plt_kv_export_bytes: bad argument"); return 0; }
   const plt_config& c = kv->m->cfg;
   const size_t w = c.window > 0 ? c.window : 1;
-  return ((size_t)2 * c.n_kv_heads * n * c.head_dim + (size_t)2 * kv->n_rings * c.n_kv_heads * w * c.head_dim) * kv->m->es;
+  return ((size_t)2 * c.n_kv_heads * n * c.head_dim + (size_t)2 * kv->n_rings * c.n_kv_heads * w * c.head_dim) * kv->m->kes;
 }
 
 template <typename T>
@@ -625,15 +635,17 @@ extern "C" int plt_kv_export(plt_kv* kv, int32_t seq, int32_t layer, int32_t cac
                              size_t host_nbytes) {
   int rc = kv_xfer_check(kv, seq, layer, cache, n, host_dst, host_nbytes);
   if (rc) return rc;
-  return kv->m->es == 2 ? kv_xfer<bf16_t>(kv, seq, layer, cache, n, (char*)host_dst, true)
-                        : kv_xfer<float>(kv, seq, layer, cache, n, (char*)host_dst, true);
+  return kv->m->kes == 1 ? kv_xfer<fp8_t>(kv, seq, layer, cache, n, (char*)host_dst, true)
+       : kv->m->kes == 2 ? kv_xfer<bf16_t>(kv, seq, layer, cache, n, (char*)host_dst, true)
+                         : kv_xfer<float>(kv, seq, layer, cache, n, (char*)host_dst, true);
 }
 extern "C" int plt_kv_import(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n,
                              const void* host_src, size_t host_nbytes) {
   int rc = kv_xfer_check(kv, seq, layer, cache, n, host_src, host_nbytes);
   if (rc) return rc;
-  return kv->m->es == 2 ? kv_xfer<bf16_t>(kv, seq, layer, cache, n, (char*)host_src, false)
-                        : kv_xfer<float>(kv, seq, layer, cache, n, (char*)host_src, false);
+  return kv->m->kes == 1 ? kv_xfer<fp8_t>(kv, seq, layer, cache, n, (char*)host_src, false)
+       : kv->m->kes == 2 ? kv_xfer<bf16_t>(kv, seq, layer, cache, n, (char*)host_src, false)
+                         : kv_xfer<float>(kv, seq, layer, cache, n, (char*)host_src, false);
 }
 
 static int copy_sync(plt_kv* kv, void* dst, const void* src, size_t bytes, hipMemcpyKind kind) {
@@ -663,6 +675,7 @@ extern "C" int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes) {
 
 // ---- kernel-only hooks ----
 extern "C" int32_t plt_attn_pad32(int32_t n) { return pad32(n); }
+extern "C" int32_t plt_attn_pad(int32_t dtype, int32_t n) { return pad_kv(n, dtype == PLT_FP8_E4M3); }
 
 extern "C" size_t plt_attn_scratch_bytes(int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D) {
   if (B < 1 || L < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv || (D != 64 && D != 128)) { fail(PLT_EINVAL, "plt_attn_scratch_bytes: bad shape"); return 0; }
@@ -676,7 +689,8 @@ extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, 
                                const void* k_share, const void* v_share, const void* k_ring, const void* v_ring,
                                const float* z, void* y, void* scratch, size_t scratch_bytes, int32_t n_splits,
                                void* hip_stream) {
-  if (dtype != PLT_F32 && dtype != PLT_BF16) return fail(PLT_EINVAL, "plt_attn_decode: unknown dtype");
+  if (dtype != PLT_F32 && dtype != PLT_BF16 && dtype != PLT_FP8_E4M3) return fail(PLT_EINVAL, "plt_attn_decode: unknown dtype");
+  const bool kv8 = dtype == PLT_FP8_E4M3;
   if (B < 1 || L < 1 || L > 16 || Hq < 1 || Hkv < 1 || Hq % Hkv || (D != 64 && D != 128))
     return fail(PLT_EINVAL, "plt_attn_decode: bad shape");
   if (n_ctx < 1 || n_ctx > n_alloc) return fail(PLT_EINVAL, "plt_attn_decode: need 1 <= n_ctx <= n_alloc");
@@ -688,12 +702,12 @@ extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, 
   hipStream_t s = (hipStream_t)hip_stream;
   KvView v{};
   v.k_share = (void*)k_share; v.v_share = (void*)v_share; v.k_ring = (void*)k_ring; v.v_ring = (void*)v_ring;
-  v.n_pad = pad32(n_alloc); v.w_pad = pad32(w > 0 ? w : 1); v.w = w > 0 ? w : 1; v.n_rings = L - 1; v.b0 = 0;
+  v.n_pad = pad_kv(n_alloc, kv8); v.w_pad = pad_kv(w > 0 ? w : 1, kv8); v.w = w > 0 ? w : 1; v.n_rings = L - 1; v.b0 = 0;
   Dims dm{B, L, Hq, Hkv, D, 0, 0, 0};
-  if (dtype == PLT_BF16) {
-    if (n_splits <= 0) n_splits = attn_mfma_default_splits(B, Hkv, L, Hq / Hkv, n_ctx);
+  if (dtype == PLT_BF16 || kv8) {
+    if (n_splits <= 0) n_splits = attn_mfma_default_splits(B, Hkv, L, Hq / Hkv, n_ctx, kv8);
     launch_attn_decode_mfma(s, (const bf16_t*)q, z, (bf16_t*)y, v, nullptr, n_ctx, L > 1 ? n_ring : 0, dm, 0,
-                            scratch, n_splits);
+                            scratch, n_splits, 0, 0, kv8);
   } else {
     if (L > 1 && n_ring != (n_ctx < w ? n_ctx : w))
       return fail(PLT_EINVAL, "plt_attn_decode: float path needs n_ring == min(n_ctx, w)");
@@ -707,18 +721,20 @@ extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, 
 
 extern "C" int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* src, void* dst,
                                void* hip_stream) {
-  if ((dtype != PLT_F32 && dtype != PLT_BF16) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)
+  if ((dtype != PLT_F32 && dtype != PLT_BF16 && dtype != PLT_FP8_E4M3) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)
     return fail(PLT_EINVAL, "plt_attn_pack_k: bad argument");
-  if (dtype == PLT_BF16) launch_pack_k<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
+  if (dtype == PLT_FP8_E4M3) launch_pack_k<fp8_t>((hipStream_t)hip_stream, (const fp8_t*)src, (fp8_t*)dst, S, n, pad_kv(n, true), D);
+  else if (dtype == PLT_BF16) launch_pack_k<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
   else launch_pack_k<float>((hipStream_t)hip_stream, (const float*)src, (float*)dst, S, n, pad32(n), D);
   HIP_TRY(hipGetLastError());
   return PLT_OK;
 }
 extern "C" int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* src, void* dst,
                                void* hip_stream) {
-  if ((dtype != PLT_F32 && dtype != PLT_BF16) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)
+  if ((dtype != PLT_F32 && dtype != PLT_BF16 && dtype != PLT_FP8_E4M3) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)
     return fail(PLT_EINVAL, "plt_attn_pack_v: bad argument");
-  if (dtype == PLT_BF16) launch_pack_v<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
+  if (dtype == PLT_FP8_E4M3) launch_pack_v<fp8_t>((hipStream_t)hip_stream, (const fp8_t*)src, (fp8_t*)dst, S, n, pad_kv(n, true), D);
+  else if (dtype == PLT_BF16) launch_pack_v<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
   else launch_pack_v<float>((hipStream_t)hip_stream, (const float*)src, (float*)dst, S, n, pad32(n), D);
   HIP_TRY(hipGetLastError());
   return PLT_OK;

@@ -18,14 +18,38 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
   uint32_t lsb = (c.u >> 16) & 1u;
   return (bf16_t)((c.u + 0x7FFFu + lsb) >> 16);
 }
+// e4m3 cache bytes (OCP e4m3fn): hardware conversions; stores saturate at +-448, nearest even
+typedef uint8_t fp8_t;
+__device__ inline fp8_t f32_to_e4m3(float f) {
+  f = fminf(fmaxf(f, -448.f), 448.f);
+  return (fp8_t)(__builtin_amdgcn_cvt_pk_fp8_f32(f, f, 0, false) & 0xff);
+}
+__device__ inline float e4m3_to_f32(fp8_t v) { return __builtin_amdgcn_cvt_f32_fp8((int)v, 0); }
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+// eight e4m3 bytes (two dwords, memory order) -> eight bf16 values, exact
+__device__ inline bf16x8 e4m3x8_to_bf16(unsigned a, unsigned b) {
+  const bf16x2 r0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a, 1.0f, false);
+  const bf16x2 r1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(a, 1.0f, true);
+  const bf16x2 r2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(b, 1.0f, false);
+  const bf16x2 r3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(b, 1.0f, true);
+  const bf16x4 lo = __builtin_shufflevector(r0, r1, 0, 1, 2, 3);
+  const bf16x4 hi = __builtin_shufflevector(r2, r3, 0, 1, 2, 3);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
 template <typename T> __device__ inline float ld(const T* p);
 template <> __device__ inline float ld<float>(const float* p) { return *p; }
 template <> __device__ inline float ld<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
 template <typename T> __device__ inline void st(T* p, float v);
 template <> __device__ inline void st<float>(float* p, float v) { *p = v; }
 template <> __device__ inline void st<bf16_t>(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+template <> __device__ inline float ld<fp8_t>(const fp8_t* p) { return e4m3_to_f32(*p); }
+template <> __device__ inline void st<fp8_t>(fp8_t* p, float v) { *p = f32_to_e4m3(v); }
 
 inline int pad32(int n) { return (n + 31) & ~31; }
+// cache rows are padded to whole attention tiles: 32 positions, 64 for one-byte (e4m3) caches
+inline int pad_kv(int n, bool fp8) { return fp8 ? (n + 63) & ~63 : pad32(n); }
 
 // Index of element (pos, d) inside one V stream stored as blocks of 32 positions:
 // [n_pad/32][D][32], position fastest.
@@ -74,7 +98,8 @@ template <typename T>
 void launch_resid_norm(hipStream_t s, float* x, int x_row_stride, int x_row_off,
                        const float* partials, int S, size_t slab, const float* gain, float eps,
                        T* a_out, int R, int d);
-template <typename T>
+// T: type of q_out (the model dtype); KT: element type of the caches (T, or fp8_t)
+template <typename T, typename KT>
 void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
                         const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
                         Dims dm, const double* inv_freq /* device [D/2]: theta^(-2j/D) */, int first_loop_only);
@@ -100,7 +125,7 @@ void launch_gemm_f32(hipStream_t s, const float* a, const float* w, float* c, in
 int gemm_bf16_splits(int M, int N, int K);
 void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N,
                       int K, int splits);
-// gemm_big.hip: many rows (prefill), 256 x 128 tiles, no split-K; optional fused SwiGLU epilogue
+// gemm_big.hip: many rows (prefill), 256 x 256 tiles, no split-K; optional fused SwiGLU epilogue
 bool gemm_big_applies(int M, int N, int K);
 void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
 void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K);
@@ -112,15 +137,16 @@ void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float
 void launch_attn_f32(hipStream_t s, const float* q, const float* z, float* y, KvView kv,
                      RowMap rm, int R, Dims dm, int plain);
 
-// attn_mfma.hip : bf16 storage, MFMA tiles
+// attn_mfma.hip : bf16 q / y, caches in bf16 or e4m3 (kv_fp8), MFMA tiles
 size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D);
-int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx);
+int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx, int kv_fp8 = 0);
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform,
                              Dims dm, int plain, void* scratch, int n_splits,
-                             int l_off = 0, int l_stride = 0 /* rows per sequence in q / y; 0 = dm.L */);
+                             int l_off = 0, int l_stride = 0 /* rows per sequence in q / y; 0 = dm.L */,
+                             int kv_fp8 = 0);
 // local_tmp: float scratch [Bc*n, Hq*D] (used by loops >= 2 only)
 void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
-                              KvView kv, int Bc, int n, int loop, Dims dm, int plain);
+                              KvView kv, int Bc, int n, int loop, Dims dm, int plain, int kv_fp8 = 0);
 
 }  // namespace plt

@@ -14,10 +14,11 @@ pytestmark = pytest.mark.gpu
 
 
 def oracle_step(shape, cfg, weights_host, exports, carry, token, pos):
+    fp8 = cfg.kv_dtype == B.PLT_FP8_E4M3
     osh = O.OracleShape(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                         shape.ffn_hidden, shape.vocab, cfg.n_loops, cfg.window, shape.rope_theta, shape.norm_eps,
                         shape.tie_embeddings)
-    orc = O.PLTOracle(osh, weights_host, kv_bf16=True)
+    orc = O.PLTOracle(osh, weights_host, kv_bf16=not fp8, kv_fp8=fp8)
     orc.kv = O.RingKV(orc._store, osh, pos + 1)
     for m, e in enumerate(exports):
         orc.kv.ks[m, :pos] = e["k_share"].transpose(1, 0, 2); orc.kv.vs[m, :pos] = e["v_share"].transpose(1, 0, 2)
@@ -28,13 +29,15 @@ def oracle_step(shape, cfg, weights_host, exports, carry, token, pos):
     return nxt, lg, orc.trace[-1]
 
 
-def test_decode_step_1p3b_L2_batch64_ctx2048_sampled():
+@pytest.mark.parametrize("kv_dtype", [0, B.PLT_FP8_E4M3])
+def test_decode_step_1p3b_L2_batch64_ctx2048_sampled(kv_dtype):
     """The headline workload: 24 layers, d=2048, 16x128 heads, FFN 5632, vocab 32000, L=2, w=64,
-    batch 64, 2048-token context built by plt_prefill; sequences 0 and 41 checked against the oracle."""
+    batch 64, 2048-token context built by plt_prefill; sequences 0 and 41 checked against the oracle.
+    Also with e4m3 caches (the oracle then rounds the new position's K and V to e4m3 as well)."""
     shape = synth.PLT_1P3B
     Bn, N = 64, 2048
     pos = N - 1
-    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=2, window=64)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=2, window=64, kv_dtype=kv_dtype)
     blob = bench.fill_weights_on_device(B, cfg, bench.SEED)
     model = B.Model(cfg, blob)
     kv = B.KV(model, Bn, N)
