@@ -10,6 +10,10 @@ non-looped / vanilla-loop / L-sweep latencies, the kernel-only attention configu
 CPU oracle timed on the host cores.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--only-main] [--no-cpu-baseline]
+
+Single-section runs for profiling (each prints its own JSON line): --attn-kernel-only, --prefill-only,
+--copy-reference; --kv-fp8 runs the main workload with e4m3 K/V caches (a labelled variant, not the
+headline).
 """
 from __future__ import annotations
 
@@ -132,6 +136,23 @@ def time_steps(kv, pos, tok, warmup, steps):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def copy_reference(B):
+    """Four launches of the library's plain copy kernel, 1 GiB read + 1 GiB written each: the known-size
+    reference that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings."""
+    import torch
+    n = 1 << 30
+    a = torch.zeros(n, dtype=torch.uint8, device="cuda"); b = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    assert B.lib().plt_stream_copy(C.c_void_p(b.data_ptr()), C.c_void_p(a.data_ptr()), n, stream) == 0
+    e0.record()
+    for _ in range(3):
+        assert B.lib().plt_stream_copy(C.c_void_p(b.data_ptr()), C.c_void_p(a.data_ptr()), n, stream) == 0
+    e1.record(); torch.cuda.synchronize()
+    return {"workload": "k_stream_copy, 4 launches, 1 GiB read + 1 GiB written each", "bytes_read_per_launch": n,
+            "bytes_written_per_launch": n, "GBps_read_plus_write": 2 * n / (e0.elapsed_time(e1) * 1e-3 / 3) / 1e9}
+
+
 def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_next):
     """One decode step of each sampled sequence through the CPU oracle, from the exported device
     state.  state: {seq: (exports per layer, carry, token)}; gpu_*: {seq: array}."""
@@ -147,7 +168,8 @@ def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_n
                         shape.tie_embeddings)
     total, err_l, err_h, rel_h, same = 0.0, 0.0, 0.0, 0.0, True
     for seq, (exports, carry0, token0) in state.items():
-        orc = O.PLTOracle(osh, w, kv_bf16=True)
+        fp8 = cfg.kv_dtype == B.PLT_FP8_E4M3
+        orc = O.PLTOracle(osh, w, kv_bf16=not fp8, kv_fp8=fp8)
         orc.kv = O.RingKV(orc._store, osh, pos + 1)
         for m, e in enumerate(exports):
             orc.kv.ks[m, :pos] = e["k_share"].transpose(1, 0, 2); orc.kv.vs[m, :pos] = e["v_share"].transpose(1, 0, 2)
@@ -371,6 +393,10 @@ def main():
     ap.add_argument("--prefill", action="store_true", help="also time the CLP prefill of 4 x 8192 tokens at L=3")
     ap.add_argument("--long-context", action="store_true",
                     help="also time one GPU's share of the L=4, window 128, 8192-token configuration (batch 128 resident)")
+    ap.add_argument("--attn-kernel-only", action="store_true", help="only the kernel-only fused attention configuration (bf16 and e4m3 caches)")
+    ap.add_argument("--prefill-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3")
+    ap.add_argument("--copy-reference", action="store_true", help="only the plain copy kernel (reference for HBM traffic counters)")
+    ap.add_argument("--kv-fp8", action="store_true", help="main workload with e4m3 K/V caches (labelled variant)")
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--ctx", type=int, default=2048)
     ap.add_argument("--loops", type=int, default=2)
@@ -384,10 +410,23 @@ def main():
     from paper_2510_24824_amd import binding as B, synth
     B.lib()   # fails loudly if the HIP library is missing
     shape = synth.PLT_1P3B
+    if args.copy_reference:
+        print(json.dumps(copy_reference(B)), flush=True)
+        return
+    if args.attn_kernel_only:
+        print(json.dumps({"attn_kernel_only": bench_attn_kernel(B, args.steps, args.warmup),
+                          "attn_kernel_only_fp8_kv": bench_attn_kernel(B, args.steps, args.warmup, fp8=True)}), flush=True)
+        return
+    if args.prefill_only:
+        cfg0 = B.make_config(shape, dtype=B.PLT_BF16)
+        g0 = torch.Generator(device="cuda"); g0.manual_seed(SEED + 1)
+        print(json.dumps({"prefill": bench_prefill(B, shape, fill_weights_on_device(B, cfg0, SEED), g0)}), flush=True)
+        return
+    kvd = B.PLT_FP8_E4M3 if args.kv_fp8 else 0
     Bn, N, L, w = args.batch, args.ctx, args.loops, args.window
     pos = N - 1                                  # the position a timed step consumes; it attends N keys
 
-    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=L, window=w)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=L, window=w, kv_dtype=kvd)
     t0 = time.perf_counter()
     blob = fill_weights_on_device(B, cfg, SEED)
     model = B.Model(cfg, blob)
@@ -435,7 +474,7 @@ def main():
     model.profile_enable(0)
     ms_step_noevents = time_steps(kv, pos, tok, 2, args.steps)
 
-    abytes = attn_alg_bytes(Bn, L, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w)
+    abytes = attn_alg_bytes(Bn, L, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w, 2, 1 if kvd else 2)
     attn_us = attn_ms * 1e3 / max(attn_n, 1)
     achieved = abytes / (attn_us * 1e-6) / 1e9
     wbytes = 2 * (shape.n_layers * ((shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim * shape.d_model
@@ -444,15 +483,17 @@ def main():
     out = {
         "metric": "decode tokens/s + step latency vs non-looped at L=2/3/4; attn HBM GB/s",
         "value": Bn / (ms_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 (e4m3 K/V caches)" if kvd else "bf16",
         "data": "synthetic",
         "config": {"workload": f"full CLP decode step, ~1.3B dense PLT (24 layers, d=2048, 16 heads x 128, SwiGLU 5632, vocab 32000), "
-                               f"bf16, L={L}, window {w}, batch {Bn}, {N}-token shared KV context (configs[2])",
+                               f"bf16{' with e4m3 K/V caches' if kvd else ''}, L={L}, window {w}, batch {Bn}, {N}-token shared KV context (configs[2])",
                    "batch": Bn, "n_loops": L, "window": w, "context": N, "seed": SEED,
                    "kv_fill": f"plt_prefill of {pos} uniform token ids per sequence ({prefill_s:.2f} s)"},
-        "roofline": {"bound": "hbm", "kernel": "k_attn_decode<128> (fused decode attention, one launch per layer)",
+        "roofline": {"bound": "hbm", "kernel": f"k_attn_decode<128{', e4m3' if kvd else ''}> (fused decode attention, one launch per layer)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": read_traffic("attn_decode_c3_bytes_per_launch"),
+                     "traffic": read_traffic("attn_decode_c3_fp8kv_bytes_per_launch" if kvd else "attn_decode_c3_bytes_per_launch")
+                     if (Bn, N, L, w) == (64, 2048, 2, 64) else None,
                      "algorithmic_bytes_per_launch": abytes, "avg_launch_us": attn_us, "launches": attn_n},
         "gemm": {"avg_launch_us": gemm_ms * 1e3 / max(gemm_n, 1), "launches": gemm_n,
                  "weight_bytes_per_step": wbytes, "ms_per_step": gemm_ms / args.steps,
@@ -465,7 +506,7 @@ def main():
     out["roofline"]["measured_stream_read_GBps"] = ceiling          # context: what a plain read kernel reaches here
     out["roofline"]["frac_of_measured_stream_read"] = achieved / ceiling
 
-    if not args.only_main:
+    if not args.only_main and not kvd:
         # ---- same library, same weights: non-looped, the L sweep and the vanilla sequential loop.
         # Their caches are filled with N(0, 0.5) values on the device (timing only).
         kv.close(); del kv

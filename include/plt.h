@@ -165,9 +165,12 @@ int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes);
 /* Kernel-only fused decode attention [Alg. 3 l.2-5, Eq. 2; first-loop row: global only].
  * All pointers are device pointers, element type `dtype`, in the cache's native layout:
  *   q        [B, L, Hq, D]                       (already rotated)
- *   k_share  [B, Hkv, n_pad, D]                  n_pad = plt_attn_pad(dtype, n_alloc)
+ *   k_share  [B, Hkv, n_pad * D]                 n_pad = plt_attn_pad(dtype, n_alloc); PLT_F32: rows
+ *                                                [n_pad, D]; PLT_BF16 / PLT_FP8_E4M3: tiles of 32 / 64
+ *                                                positions in the kernel's matrix-core load order
+ *                                                (written by plt_attn_pack_k; see below)
  *   v_share  [B, Hkv, n_pad/32, D, 32]           blocks of 32 positions, position fastest
- *   k_ring   [B, L-1, Hkv, w_pad, D]             w_pad = plt_attn_pad(dtype, w)
+ *   k_ring   [B, L-1, Hkv, w_pad * D]            w_pad = plt_attn_pad(dtype, w); layout as k_share
  *   v_ring   [B, L-1, Hkv, w_pad/32, D, 32]
  *   z        [B, L-1, Hq] float gate logits;  y [B, L, Hq, D] output
  * dtype PLT_FP8_E4M3: q and y are bf16, the four cache arrays hold e4m3 bytes.
@@ -187,7 +190,12 @@ int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv
                     void* hip_stream);
 
 /* Device-side layout conversion for the hook above: plain [S, n, D] (S independent streams,
- * e.g. B*Hkv) -> K layout [S, n_pad, D] (pad rows zeroed) and V layout [S, n_pad/32, D, 32].
+ * e.g. B*Hkv) -> K layout [S, n_pad * D] (pad positions zeroed) and V layout [S, n_pad/32, D, 32].
+ * K layout of the 2-byte and 1-byte types: a tile of T = 32 (64) positions is T*D elements stored as
+ * [a][kk][g][m][c] with c = 16 bytes' worth of consecutive features (8 / 16), m in 0..15, g in 0..3,
+ * kk in 0..D/(4c)-1, a in 0..T/16-1; the element is position 2T/8*(m>>2) + (m&3) + 4a of the tile
+ * (i.e. 8*(m>>2) + (m&3) + 4a, resp. 16*(m>>2) + (m&3) + 4a), feature kk*4c + g*c + its index in c:
+ * one wavefront load of the attention kernel (lane = 16g + m) is then one contiguous KiB.
  * Elements are moved, never converted: for PLT_FP8_E4M3 source and destination hold e4m3 bytes. */
 int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,
                     void* dev_dst, void* hip_stream);

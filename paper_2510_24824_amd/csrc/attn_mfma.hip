@@ -8,8 +8,8 @@
 // streamed from HBM exactly once for all of them.  (The prefill counterpart lives in attn_prefill.hip.)
 //
 // Tile algebra (one wave, 32 keys at a time, v_mfma_f32_16x16x32_bf16):
-//   S^T[key][row] = K[key][:] . Q[row][:]      A = K rows straight from HBM (16 B per lane),
-//                                              B = Q held in registers
+//   S^T[key][row] = K[key][:] . Q[row][:]      A = K straight from HBM (16 B per lane; the cache keeps
+//                                              K tiles in exactly this load order), B = Q in registers
 //   O^T[d][row]  += V^T[d][key] * P^T[key][row]  A = V^T, 16 B per lane thanks to the cache's
 //                                              V layout (blocks of 32 positions, position fastest)
 // With this orientation a lane owns one query row in S^T, P^T and O^T alike, so the online
@@ -35,6 +35,7 @@ typedef __attribute__((ext_vector_type(8))) float f32x8;
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ inline uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
 
+
 template <int D>
 struct WaveState {
   float m;                 // running row maximum (log2 domain), identical in the 4 lanes of a row
@@ -59,47 +60,47 @@ struct KvTile<D, true> {   // 64 keys of e4m3
   uint4 v[D / 16];         // D/16 groups of 16 features, 16 keys per lane
 };
 
-// kt -> first of the tile's 32 key rows (row stride D); vt -> the tile's V block [D][32]
+// kt -> the tile's K block (32 keys, stored in load order: see kblk_index); vt -> the tile's V block [D][32]
 template <int D>
 __device__ inline void load_tile_k(KvTile<D, false>& t, const char* __restrict__ kt, int m16, int g) {
-  const bf16_t* kp = (const bf16_t*)kt;
-  const int key0 = 8 * (m16 >> 2) + (m16 & 3);   // A-row m16 of sub-tile a <-> key key0 + 4a
+  const char* kp = kt + (g * 16 + m16) * 16;     // A-row m16 of sub-tile a <-> key 8*(m16>>2) + (m16&3) + 4a
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
-      t.k[a][kk] = ldg16(kp + (size_t)(key0 + 4 * a) * D + kk * 32 + g * 8);
+      t.k[a][kk] = ldg16_stream(kp + (a * (D / 32) + kk) * 1024);
 }
 template <int D>
 __device__ inline void load_tile_v(KvTile<D, false>& t, const char* __restrict__ vt, int m16, int g) {
   const bf16_t* vp = (const bf16_t*)vt;
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16(vp + (dt * 16 + m16) * 32 + g * 8);
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16_stream(vp + (dt * 16 + m16) * 32 + g * 8);
 }
-// e4m3: kt -> first of the tile's 64 key rows (D bytes each); vt -> the tile's two V blocks [D][32]
+// e4m3: kt -> the tile's K block (64 keys, load order); vt -> the tile's two V blocks [D][32]
 template <int D>
 __device__ inline void load_tile_k(KvTile<D, true>& t, const char* __restrict__ kt, int m16, int g) {
-  const int key0 = 16 * (m16 >> 2) + (m16 & 3);  // A-row m16 of sub-tile a <-> key key0 + 4a
+  const char* kp = kt + (g * 16 + m16) * 16;     // A-row m16 of sub-tile a <-> key 16*(m16>>2) + (m16&3) + 4a
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
     for (int kk = 0; kk < D / 64; ++kk)
-      t.k[a][kk] = *reinterpret_cast<const uint4*>(kt + (size_t)(key0 + 4 * a) * D + kk * 64 + g * 16);
+      t.k[a][kk] = ldg16_stream(kp + (a * (D / 64) + kk) * 1024);
 }
 template <int D>
 __device__ inline void load_tile_v(KvTile<D, true>& t, const char* __restrict__ vt, int m16, int g) {
   // lane g: positions 16g .. 16g+15 of the tile = half a row of block g/2
   const char* vb = vt + (size_t)(g >> 1) * (D * 32) + (g & 1) * 16;
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = *reinterpret_cast<const uint4*>(vb + (dt * 16 + m16) * 32);
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16_stream(vb + (dt * 16 + m16) * 32);
 }
 
 // One 32-key step of the online softmax.  valid(j) tells whether key j (0..7 -> tile key 8g+j)
 // may be attended by this lane's row; it is consulted only when need_mask is set.
-// mid() runs between the two contractions (when the K half of the tile is no longer needed).
-template <int D, typename Valid, typename Mid>
-__device__ inline void tile_step(WaveState<D>& st, const KvTile<D, false>& t, const uint4 (&qf)[D / 32],
-                                 float scale_log2, bool need_mask, Valid valid, Mid mid) {
+// mid() runs between the two contractions, when the K half of the tile is no longer needed, and end()
+// after the second one, when the V half is not either: the caller refills those registers there.
+template <int D, typename Valid, typename Mid, typename End>
+__device__ inline void tile_step(WaveState<D>& st, KvTile<D, false>& t, const uint4 (&qf)[D / 32],
+                                 float scale_log2, bool need_mask, Valid valid, Mid mid, End end) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int kk = 0; kk < D / 32; ++kk) {
@@ -135,13 +136,14 @@ __device__ inline void tile_step(WaveState<D>& st, const KvTile<D, false>& t, co
     a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
     st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.v[dt]), pb, a, 0, 0, 0);
   }
+  end();
 }
 
 // The same step on a 64-key e4m3 tile.  valid(j), j = 0..15 <-> tile key 16g + j.  qf[2c + h] holds
 // the lane's query features c*64 + 16g + 8h .. +7, matching the two halves of a 16-byte key load.
-template <int D, typename Valid, typename Mid>
-__device__ inline void tile_step(WaveState<D>& st, const KvTile<D, true>& t, const uint4 (&qf)[D / 32],
-                                 float scale_log2, bool need_mask, Valid valid, Mid mid) {
+template <int D, typename Valid, typename Mid, typename End>
+__device__ inline void tile_step(WaveState<D>& st, KvTile<D, true>& t, const uint4 (&qf)[D / 32],
+                                 float scale_log2, bool need_mask, Valid valid, Mid mid, End end) {
   f32x4 s[4];
 #pragma unroll
   for (int a = 0; a < 4; ++a) {
@@ -189,6 +191,7 @@ __device__ inline void tile_step(WaveState<D>& st, const KvTile<D, true>& t, con
     a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.x, r.y), pb0, a, 0, 0, 0);
     st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.z, r.w), pb1, a, 0, 0, 0);
   }
+  end();
 }
 
 // LDS block used to merge the four waves of a workgroup.
@@ -358,26 +361,32 @@ __global__ __launch_bounds__(256, 2) void k_attn_decode(AttnDecArgs A) {
       if (which & 1) load_tile_k<D>(tl, kp, m16, g);
       if (which & 2) load_tile_v<D>(tl, vp, m16, g);
     };
-    // e4m3 tiles: the next tile's V half is requested only after the current K half has been
-    // multiplied (its registers are free by then); bf16 tiles fit and are requested whole
-    constexpr int EARLY = F8 ? 1 : 3;
+    // Two tile buffers per wave, refilled in halves as soon as a half has been consumed: while entry e
+    // is being multiplied, entry e + 4 is resident or in flight, and the K half (then the V half) of
+    // entry e + 8 is requested into the registers entry e has just released.  Between one and two
+    // tiles per wave are in flight at any time, in the registers of two.
     bool parked = !(RING_FIRST && do_local);     // is the window state already out of the way?
-    int e = wv;
-    if (e < n_ent) load_entry(cur, e, 3);
-    for (; e < n_ent; e += 4) {
-      const int en = e + 4;
-      if (en < n_ent) load_entry(nxt, en, EARLY);
-      auto mid = [&]() { if (F8 && en < n_ent) load_entry(nxt, en, 2); };
+    auto process = [&](KvTile<D, F8>& tl, int e) {
+      const int e2 = e + 8;
+      auto mid = [&]() { if (e2 < n_ent) load_entry(tl, e2, 1); };
+      auto end = [&]() { if (e2 < n_ent) load_entry(tl, e2, 2); };
       if (!is_ring(e)) {
         if (!parked) { wg_park<D>(sm, st, wv, m16, g); st.init(); parked = true; }
         const int t = tile_of(share_idx(e)), kb = t * TK + KL * g;
-        tile_step<D>(st, cur, qf, A.scale_log2, (t + 1) * TK > n_ctx, [&](int j) { return kb + j < n_ctx; }, mid);
+        tile_step<D>(st, tl, qf, A.scale_log2, (t + 1) * TK > n_ctx, [&](int j) { return kb + j < n_ctx; }, mid, end);
       } else {
         const int j0 = ring_idx(e), rl = j0 / tv, tr = j0 - rl * tv, sb = tr * TK + KL * g;
         const bool mine = qrow_ok && (q_loop == rl + 1);
-        tile_step<D>(RING_FIRST ? st : sl, cur, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); }, mid);
+        tile_step<D>(RING_FIRST ? st : sl, tl, qf, A.scale_log2, true, [&](int j) { return mine && (sb + j < n_ring); }, mid, end);
       }
-      if (en < n_ent) cur = nxt;
+    };
+    KvTile<D, F8>& ta = cur; KvTile<D, F8>& tb = nxt;
+    int e = wv;
+    if (e < n_ent) load_entry(ta, e, 3);
+    if (e + 4 < n_ent) load_entry(tb, e + 4, 3);
+    for (; e < n_ent; e += 8) {
+      process(ta, e);
+      if (e + 4 < n_ent) process(tb, e + 4);
     }
     if (!parked) { wg_park<D>(sm, st, wv, m16, g); st.init(); }   // this wave had ring tiles only
   }

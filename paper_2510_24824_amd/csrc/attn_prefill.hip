@@ -126,12 +126,27 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const
   uint4 rk[KCH], rv[KCH];
 #pragma unroll
   for (int i = 0; i < KCH; ++i) { rk[i] = make_uint4(0, 0, 0, 0); rv[i] = make_uint4(0, 0, 0, 0); }
+  // The cache keeps K in the decode kernel's load order (kblk_index): a 16-byte chunk of the tile is
+  // (sub-tile a, feature chunk kk, lane group g, row m) and belongs to key kkey, features kcol ..
+  auto k_chunk = [&](int t, int ch, size_t& off, int& kkey, int& kcol) {
+    if (F8) {   // 64-key blocks; this 32-key tile is half (t & 1): rows m with (m >> 2) in {2h, 2h+1}
+      const int m = 8 * (t & 1) + (ch & 7), g = (ch >> 3) & 3, kk = (ch >> 5) % (D / 64), a = (ch >> 5) / (D / 64);
+      off = (size_t)(t >> 1) * 64 * D + (size_t)(((a * (D / 64) + kk) * 64 + g * 16 + m) * 16);
+      kkey = 16 * ((m >> 2) & 1) + (m & 3) + 4 * a; kcol = kk * 64 + g * 16;
+    } else {
+      const int m = ch & 15, g = (ch >> 4) & 3, kk = (ch >> 6) % (D / 32), a = (ch >> 6) / (D / 32);
+      off = (size_t)t * TILE_BYTES + (size_t)ch * 16;
+      kkey = 8 * (m >> 2) + (m & 3) + 4 * a; kcol = kk * 32 + g * 8;
+    }
+  };
   auto fetch = [&](int t) {
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int ch = tid + i * 256;
       if (NCH % 256 == 0 || ch < NCH) {
-        rk[i] = *reinterpret_cast<const uint4*>(kbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
+        size_t off; int kkey, kcol;
+        k_chunk(t, ch, off, kkey, kcol);
+        rk[i] = *reinterpret_cast<const uint4*>(kbase + off);
         rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
       }
     }
@@ -142,18 +157,18 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int ch = tid + i * 256;
-      if (F8) {
-        if (NCH % 256 == 0 || ch < NCH) {
-          const int row = ch / (D / 16), col = (ch % (D / 16)) * 16;
-          *reinterpret_cast<bf16x8*>(&sm.k[row][col]) = e4m3x8_to_bf16(rk[i].x, rk[i].y);
-          *reinterpret_cast<bf16x8*>(&sm.k[row][col + 8]) = e4m3x8_to_bf16(rk[i].z, rk[i].w);
+      if (NCH % 256 == 0 || ch < NCH) {
+        size_t off; int kkey, kcol;
+        k_chunk(t, ch, off, kkey, kcol);
+        if (F8) {
+          *reinterpret_cast<bf16x8*>(&sm.k[kkey][kcol]) = e4m3x8_to_bf16(rk[i].x, rk[i].y);
+          *reinterpret_cast<bf16x8*>(&sm.k[kkey][kcol + 8]) = e4m3x8_to_bf16(rk[i].z, rk[i].w);
           *reinterpret_cast<bf16x8*>(&sm.v[ch >> 1][(ch & 1) * 16]) = e4m3x8_to_bf16(rv[i].x, rv[i].y);
           *reinterpret_cast<bf16x8*>(&sm.v[ch >> 1][(ch & 1) * 16 + 8]) = e4m3x8_to_bf16(rv[i].z, rv[i].w);
+        } else {
+          *reinterpret_cast<uint4*>(&sm.k[kkey][kcol]) = rk[i];
+          *reinterpret_cast<uint4*>(&sm.v[ch / 4][(ch % 4) * 8]) = rv[i];
         }
-      } else {
-        const int row = ch / (D / 8), col = (ch % (D / 8)) * 8;
-        *reinterpret_cast<uint4*>(&sm.k[row][col]) = rk[i];
-        *reinterpret_cast<uint4*>(&sm.v[ch / 4][(ch % 4) * 8]) = rv[i];
       }
     }
     __syncthreads();

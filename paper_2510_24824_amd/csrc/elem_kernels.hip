@@ -210,8 +210,8 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     size_t stream = (size_t)bg * Hkv + kh;
     const size_t coff = mode == 3 ? (size_t)l * kv.cache_stride : 0;
     if (is_k) {
-      KT* dst = (KT*)kv.k_share + coff + (stream * kv.n_pad + p) * D;
-      st<KT>(dst + j, v0); st<KT>(dst + j + half, v1);
+      KT* dst = (KT*)kv.k_share + coff + stream * (size_t)kv.n_pad * D;
+      st<KT>(dst + kblk_index<KT>(p, j, D), v0); st<KT>(dst + kblk_index<KT>(p, j + half, D), v1);
     } else {
       KT* dst = (KT*)kv.v_share + coff + stream * (size_t)kv.n_pad * D;
       st<KT>(dst + vblk_index(p, j, D), v0); st<KT>(dst + vblk_index(p, j + half, D), v1);
@@ -223,8 +223,8 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
   if (rm.prefill) {
     size_t stream = (size_t)b * Hkv + kh;
     if (is_k) {
-      KT* dst = (KT*)kv.k_loc + (stream * kv.n_pad_loc + p) * D;
-      st<KT>(dst + j, v0); st<KT>(dst + j + half, v1);
+      KT* dst = (KT*)kv.k_loc + stream * (size_t)kv.n_pad_loc * D;
+      st<KT>(dst + kblk_index<KT>(p, j, D), v0); st<KT>(dst + kblk_index<KT>(p, j + half, D), v1);
     } else {
       KT* dst = (KT*)kv.v_loc + stream * (size_t)kv.n_pad_loc * D;
       st<KT>(dst + vblk_index(p, j, D), v0); st<KT>(dst + vblk_index(p, j + half, D), v1);
@@ -235,8 +235,8 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     const int slot = p % kv.w;
     size_t stream = ((size_t)bg * kv.n_rings + (l - 1)) * Hkv + kh;
     if (is_k) {
-      KT* dst = (KT*)kv.k_ring + (stream * kv.w_pad + slot) * D;
-      st<KT>(dst + j, v0); st<KT>(dst + j + half, v1);
+      KT* dst = (KT*)kv.k_ring + stream * (size_t)kv.w_pad * D;
+      st<KT>(dst + kblk_index<KT>(slot, j, D), v0); st<KT>(dst + kblk_index<KT>(slot, j + half, D), v1);
     } else {
       KT* dst = (KT*)kv.v_ring + stream * (size_t)kv.w_pad * D;
       st<KT>(dst + vblk_index(slot, j, D), v0); st<KT>(dst + vblk_index(slot, j + half, D), v1);
@@ -374,15 +374,20 @@ void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n) {
   hipLaunchKernelGGL(k_copy_f32, dim3(g), dim3(256), 0, s, x, hprev, n);
 }
 
-// ---- layout packs: plain [S, n, D] <-> K [S, n_pad, D] / V [S, n_pad/32, D, 32] ----
+// ---- layout packs: plain [S, n, D] <-> K [S, n_pad * D] (kblk_index order) / V [S, n_pad/32, D, 32] ----
 template <typename T>
-__global__ void k_pack_k(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D) {
+__global__ void k_pack_k(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D, int unpack) {
   int sidx = blockIdx.y;
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;     // enumerates (pos, f) of the padded plain layout
   if (i >= (size_t)n_pad * D) return;
-  int pos = (int)(i / D);
-  T zero; st<T>(&zero, 0.f);
-  dst[(size_t)sidx * n_pad * D + i] = pos < n ? src[(size_t)sidx * n * D + i] : zero;
+  int pos = (int)(i / D), f = (int)(i - (size_t)pos * D);
+  const size_t li = (size_t)sidx * n_pad * D + kblk_index<T>(pos, f, D);
+  if (unpack) {
+    if (pos < n) dst[(size_t)sidx * n * D + i] = src[li];
+  } else {
+    T zero; st<T>(&zero, 0.f);
+    dst[li] = pos < n ? src[(size_t)sidx * n * D + i] : zero;
+  }
 }
 template <typename T>
 __global__ void k_pack_v(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D, int unpack) {
@@ -403,7 +408,12 @@ __global__ void k_pack_v(const T* __restrict__ src, T* __restrict__ dst, int n, 
 template <typename T>
 void launch_pack_k(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D) {
   size_t per = (size_t)n_pad * D;
-  hipLaunchKernelGGL(k_pack_k<T>, dim3((unsigned)((per + 255) / 256), S), dim3(256), 0, s, src, dst, n, n_pad, D);
+  hipLaunchKernelGGL(k_pack_k<T>, dim3((unsigned)((per + 255) / 256), S), dim3(256), 0, s, src, dst, n, n_pad, D, 0);
+}
+template <typename T>
+void launch_unpack_k(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D) {
+  size_t per = (size_t)n_pad * D;
+  hipLaunchKernelGGL(k_pack_k<T>, dim3((unsigned)((per + 255) / 256), S), dim3(256), 0, s, src, dst, n, n_pad, D, 1);
 }
 template <typename T>
 void launch_pack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D) {
@@ -424,5 +434,8 @@ template void launch_unpack_v<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, 
 template void launch_pack_k<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
 template void launch_pack_v<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
 template void launch_unpack_v<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
+template void launch_unpack_k<float>(hipStream_t, const float*, float*, int, int, int, int);
+template void launch_unpack_k<bf16_t>(hipStream_t, const bf16_t*, bf16_t*, int, int, int, int);
+template void launch_unpack_k<fp8_t>(hipStream_t, const fp8_t*, fp8_t*, int, int, int, int);
 
 }  // namespace plt

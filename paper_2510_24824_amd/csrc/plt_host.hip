@@ -596,25 +596,24 @@ static int kv_xfer(plt_kv* kv, int seq, int layer, int cache, int n, char* host,
   T* vr = nr ? (T*)v.v_ring + (size_t)seq * nr * Hkv * kv->w_pad * D : nullptr;
   hipError_t e = hipSuccess;
   if (to_host) {
-    for (int h = 0; h < Hkv && e == hipSuccess && n > 0; ++h)
-      e = hipMemcpyAsync(t_ks + (size_t)h * n * D, ks + (size_t)h * kv->n_pad * D, (size_t)n * D * sizeof(T), hipMemcpyDeviceToDevice, s);
+    if (n > 0) launch_unpack_k<T>(s, ks, t_ks, Hkv, n, kv->n_pad, D);
     if (n > 0) launch_unpack_v<T>(s, vs, t_vs, Hkv, n, kv->n_pad, D);
-    for (int h = 0; h < nr * Hkv && e == hipSuccess; ++h)
-      e = hipMemcpyAsync(t_kr + (size_t)h * w * D, kr + (size_t)h * kv->w_pad * D, (size_t)w * D * sizeof(T), hipMemcpyDeviceToDevice, s);
+    if (nr) launch_unpack_k<T>(s, kr, t_kr, nr * Hkv, w, kv->w_pad, D);
     if (nr) launch_unpack_v<T>(s, vr, t_vr, nr * Hkv, w, kv->w_pad, D);
     if (e == hipSuccess) e = hipMemcpyAsync(host, tmp, total, hipMemcpyDeviceToHost, s);
   } else {
     e = hipMemcpyAsync(tmp, host, total, hipMemcpyHostToDevice, s);
     if (e == hipSuccess && n > 0) {
-      // pack into the first pad32(n) rows of each stream, stream stride n_pad rows
-      for (int h = 0; h < Hkv && e == hipSuccess; ++h)
-        e = hipMemcpyAsync(ks + (size_t)h * kv->n_pad * D, t_ks + (size_t)h * n * D, (size_t)n * D * sizeof(T), hipMemcpyDeviceToDevice, s);
-      for (int h = 0; h < Hkv; ++h)
+      // pack into the first whole tiles of each stream (stream stride n_pad positions)
+      for (int h = 0; h < Hkv; ++h) {
+        launch_pack_k<T>(s, t_ks + (size_t)h * n * D, ks + (size_t)h * kv->n_pad * D, 1, n, pad_kv(n, m->kv8), D);
         launch_pack_v<T>(s, t_vs + (size_t)h * n * D, vs + (size_t)h * kv->n_pad * D, 1, n, pad32(n), D);
+      }
     }
-    for (int h = 0; h < nr * Hkv && e == hipSuccess; ++h)
-      e = hipMemcpyAsync(kr + (size_t)h * kv->w_pad * D, t_kr + (size_t)h * w * D, (size_t)w * D * sizeof(T), hipMemcpyDeviceToDevice, s);
-    if (nr && e == hipSuccess) launch_pack_v<T>(s, t_vr, vr, nr * Hkv, w, kv->w_pad, D);
+    if (nr && e == hipSuccess) {
+      launch_pack_k<T>(s, t_kr, kr, nr * Hkv, w, kv->w_pad, D);
+      launch_pack_v<T>(s, t_vr, vr, nr * Hkv, w, kv->w_pad, D);
+    }
   }
   hipError_t e2 = hipStreamSynchronize(s);
   (void)hipFree(tmp);
@@ -749,7 +748,8 @@ __global__ __launch_bounds__(256) void k_stream_copy(const uint4* __restrict__ s
 }
 
 // read-only counterpart: every workgroup walks one contiguous chunk (like one K/V stream), eight
-// 16-byte loads in flight per lane; every lane folds what it reads and stores one word at the end
+// 16-byte non-temporal loads in flight per lane (the fastest plain read found on this part: 512
+// workgroups, 64 KB in flight per compute unit); every lane folds what it reads and stores one word
 __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, unsigned* __restrict__ out, size_t n16) {
   const size_t per = n16 / gridDim.x;
   const uint4* p = src + (size_t)blockIdx.x * per;
@@ -758,7 +758,7 @@ __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ s
   for (; i + 7 * 256 < per; i += 8 * 256) {
     uint4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = p[i + u * 256];
+    for (int u = 0; u < 8; ++u) v[u] = ldg16_stream(p + i + u * 256);
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
   }
@@ -767,10 +767,10 @@ __global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ s
 }
 
 extern "C" int plt_stream_read(const void* dev_src, size_t nbytes, void* dev_out, size_t out_bytes, void* hip_stream) {
-  const size_t blocks = 256 * 8;
-  if (!dev_src || !dev_out || nbytes == 0 || (nbytes % (16 * blocks)) || (((uintptr_t)dev_src) & 15) || out_bytes < blocks * 256 * 4)
+  const size_t blocks = 256 * 2, gran = 32768, out_need = (size_t)2 << 20;
+  if (!dev_src || !dev_out || nbytes == 0 || (nbytes % gran) || (((uintptr_t)dev_src) & 15) || out_bytes < out_need)
     return fail(PLT_EINVAL, "plt_stream_read: need a multiple of %zu bytes, 16-byte alignment and an output buffer of %zu bytes",
-                16 * blocks, blocks * 256 * 4);
+                gran, out_need);
   hipLaunchKernelGGL(k_stream_read, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
                      (const uint4*)dev_src, (unsigned*)dev_out, nbytes / 16);
   HIP_TRY(hipGetLastError());

@@ -38,6 +38,14 @@ __device__ inline bf16x8 e4m3x8_to_bf16(unsigned a, unsigned b) {
   const bf16x4 hi = __builtin_shufflevector(r2, r3, 0, 1, 2, 3);
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
+// 16-byte load with the non-temporal hint: for the cache contents that decode attention streams
+// once per step, so that they do not push the step's small, re-read buffers (activations, split-K
+// slabs) out of the last-level cache (the same hint on the GEMMs' weight stream measured neutral)
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+__device__ inline uint4 ldg16_stream(const void* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
 template <typename T> __device__ inline float ld(const T* p);
 template <> __device__ inline float ld<float>(const float* p) { return *p; }
 template <> __device__ inline float ld<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
@@ -50,6 +58,27 @@ template <> __device__ inline void st<fp8_t>(fp8_t* p, float v) { *p = f32_to_e4
 inline int pad32(int n) { return (n + 31) & ~31; }
 // cache rows are padded to whole attention tiles: 32 positions, 64 for one-byte (e4m3) caches
 inline int pad_kv(int n, bool fp8) { return fp8 ? (n + 63) & ~63 : pad32(n); }
+
+// Index of element (pos, f) inside one K stream.  float caches: row-major [n_pad][D].  bf16 and
+// e4m3 caches: tiles of 32 (64) positions stored in the order the decode attention kernel's
+// matrix-core loads consume them, [sub-tile a][feature chunk kk][lane = g*16 + m][16 bytes], where
+// lane (m, g) of load (a, kk) holds the 16 bytes of key 8*(m>>2) + (m&3) + 4a, features kk*32 + 8g ..
+// (bf16; e4m3: key 16*(m>>2) + (m&3) + 4a, features kk*64 + 16g ..): every wavefront load is then one
+// contiguous 1 KB, which streams measurably faster from HBM than 16 separate 64-byte row pieces.
+template <typename KT> __host__ __device__ inline size_t kblk_index(int pos, int f, int D);
+template <> __host__ __device__ inline size_t kblk_index<float>(int pos, int f, int D) { return (size_t)pos * D + f; }
+template <> __host__ __device__ inline size_t kblk_index<bf16_t>(int pos, int f, int D) {
+  const int t = pos >> 5, j = pos & 31;
+  const int a = (j >> 2) & 1, m = ((j >> 3) << 2) | (j & 3);
+  const int kk = f >> 5, g = (f >> 3) & 3, e = f & 7;
+  return (size_t)t * 32 * D + (size_t)(((a * (D >> 5) + kk) * 64 + g * 16 + m) * 8 + e);
+}
+template <> __host__ __device__ inline size_t kblk_index<uint8_t>(int pos, int f, int D) {
+  const int t = pos >> 6, j = pos & 63;
+  const int a = (j >> 2) & 3, m = ((j >> 4) << 2) | (j & 3);
+  const int kk = f >> 6, g = (f >> 4) & 3, e = f & 15;
+  return (size_t)t * 64 * D + (size_t)(((a * (D >> 6) + kk) * 64 + g * 16 + m) * 16 + e);
+}
 
 // Index of element (pos, d) inside one V stream stored as blocks of 32 positions:
 // [n_pad/32][D][32], position fastest.
@@ -74,7 +103,7 @@ __device__ inline void row_decode(const RowMap& rm, int r, int& b, int& p, int& 
 
 // Geometry of one layer's caches as the attention and append kernels see them.
 struct KvView {
-  void* k_share;   // [B, Hkv, n_pad, D]
+  void* k_share;   // [B, Hkv, n_pad, D] (float) / tiled, see kblk_index (bf16, e4m3)
   void* v_share;   // [B, Hkv, n_pad/32, D, 32]
   void* k_ring;    // [B, L-1, Hkv, w_pad, D]        (null when L == 1 / vanilla mode)
   void* v_ring;    // [B, L-1, Hkv, w_pad/32, D, 32]
@@ -117,6 +146,8 @@ template <typename T>
 void launch_pack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
 template <typename T>
 void launch_unpack_v(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
+template <typename T>
+void launch_unpack_k(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
 void launch_prefill_carry(hipStream_t s, const float* x, float* carry, int b0, int Bc, int n,
                           int L, int l, int d);
 
