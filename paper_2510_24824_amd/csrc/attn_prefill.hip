@@ -88,9 +88,13 @@ __device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D>& sm,
     st[q].l = st[q].l * alpha + ps;
     st[q].m = m_new;
     pb[q] = __builtin_convertvector(p, bf16x8);
+    // alpha == 1 in every lane (no row of this tile raised its maximum: the usual case after the first
+    // few tiles): the rescale of the accumulators is skipped for the whole wave
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) {
-      st[q].acc[dt][0] *= alpha; st[q].acc[dt][1] *= alpha; st[q].acc[dt][2] *= alpha; st[q].acc[dt][3] *= alpha;
+      for (int dt = 0; dt < D / 16; ++dt) {
+        st[q].acc[dt][0] *= alpha; st[q].acc[dt][1] *= alpha; st[q].acc[dt][2] *= alpha; st[q].acc[dt][3] *= alpha;
+      }
     }
   }
 #pragma unroll
@@ -106,7 +110,7 @@ struct PfArgs {
   const bf16_t* q; const float* z; bf16_t* y;
   float* tmp;      // [rows, Hq*D] float: g * y_local parked between the two passes (gated rows only)
   const char* k_share; const char* v_share; const char* k_loc; const char* v_loc;   // bf16 or e4m3 elements
-  int n, n_pad, n_pad_loc, w, b0, Hq, Hkv, G, gated, n_qt;
+  int n, n_pad, n_pad_loc, w, b0, Hq, Hkv, G, gated, n_qt, Bc;
   float scale_log2;
 };
 
@@ -188,8 +192,12 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
   constexpr int ES = F8 ? 1 : 2;
   __shared__ __attribute__((aligned(16))) PfLds<D> sm;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  const int qt = A.n_qt - 1 - (int)blockIdx.x;        // longest key ranges first
-  const int h = blockIdx.y, b = blockIdx.z, kvh = h / A.G;
+  // Workgroups are dispatched in blockIdx.x order: all (head, sequence) pairs of the query tile with
+  // the longest key range first, the shortest ranges last, so the causal imbalance does not leave a
+  // few long workgroups running alone at the end.
+  const int hb = (int)blockIdx.x % (A.Hq * A.Bc);
+  const int qt = A.n_qt - 1 - (int)blockIdx.x / (A.Hq * A.Bc);
+  const int h = hb % A.Hq, b = hb / A.Hq, kvh = h / A.G;
   const int p0 = qt * PF_QROWS;
   const int p_last = (p0 + PF_QROWS - 1 < A.n ? p0 + PF_QROWS - 1 : A.n - 1);
   // this lane's two query rows
@@ -280,7 +288,8 @@ void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf
   A.gated = (!plain && loop > 0) ? 1 : 0;
   A.n_qt = (n + PF_QROWS - 1) / PF_QROWS;
   A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
-  dim3 grid(A.n_qt, dm.Hq, Bc);
+  A.Bc = Bc;
+  dim3 grid((unsigned)A.n_qt * dm.Hq * Bc);
   if (dm.D == 64) {
     if (kv_fp8) hipLaunchKernelGGL((k_attn_prefill2<64, true>), grid, dim3(256), 0, s, A);
     else hipLaunchKernelGGL((k_attn_prefill2<64, false>), grid, dim3(256), 0, s, A);
