@@ -1,6 +1,6 @@
 // bf16 projections with many rows (prefill: M = sequences x positions): c = a[M,K] * w[N,K]^T on
 // gfx950 matrix cores, MFMA-bound.  Workgroup tile 256 rows x 256 columns, K in slices of 64 through
-// LDS with the next slice prefetched into registers; 8 waves as 2 x 4, each 128 rows x 64 columns =
+// LDS, loaded HBM -> LDS directly and two slices deep; 8 waves as 2 x 4, each 128 rows x 64 columns =
 // 8 x 4 tiles of v_mfma_f32_16x16x32_bf16 (weights = A operand, activations = B operand: a lane ends
 // up with 4 consecutive columns of one row).  The wave tile is what bounds this kernel: every MFMA
 // needs 0.375 KB of LDS fragment reads (0.5 KB with 64 x 64 wave tiles, which ran LDS-bound).
@@ -16,28 +16,60 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
-constexpr int GB_BM = 256, GB_BN = 256, GB_BK = 64, GB_LDK = GB_BK + 8, GB_THREADS = 512;
+constexpr int GB_BM = 256, GB_BN = 256, GB_BK = 64, GB_THREADS = 512;
 constexpr int GB_HALF = GB_BN / 2;   // SwiGLU tile: GB_HALF gate columns + the matching GB_HALF up columns
+constexpr int GB_TILE_BYTES = GB_BM * GB_BK * 2;                 // one operand tile of one K slice: 32 KB
+constexpr int GB_LDS_BYTES = 2 * 2 * GB_TILE_BYTES;              // two stages x (A tile + W tile) = 128 KB
 enum { EPI_F32 = 0, EPI_SWIGLU = 1 };
 
+// Operand tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no register staging), two
+// stages deep, one barrier per K slice.  A tile row holds 64 K-values = 8 chunks of 16 bytes; chunk kc of
+// row r sits in slot r*8 + (kc ^ (r & 7)): the direct load writes lane l of a wave to consecutive slots,
+// so each lane simply fetches the chunk that belongs in its slot, and the XOR makes the fragment reads
+// (16 rows x one chunk column per quarter wave) touch every bank once.
 template <int EPI>
 __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                          void* __restrict__ out, int M, int N, int K) {
   // N: EPI_F32: output columns (= rows of w); EPI_SWIGLU: F (w has 2F rows, the output F columns)
-  __shared__ __attribute__((aligned(16))) bf16_t As[GB_BM * GB_LDK];
-  __shared__ __attribute__((aligned(16))) bf16_t Ws[GB_BN * GB_LDK];
+  extern __shared__ __attribute__((aligned(16))) char gb_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int wm = wv >> 2, wn = wv & 3;
   const int m0 = blockIdx.y * GB_BM;
   const int n0 = blockIdx.x * (EPI == EPI_SWIGLU ? GB_HALF : GB_BN);
-  // global row of w behind local tile row r
+  const int w_rows = EPI == EPI_SWIGLU ? 2 * N : N;
+  // global row of w behind local tile row r (rows beyond the matrix: clamped, their outputs are never stored)
   auto wrow = [&](int r) -> int {
-    if (EPI == EPI_SWIGLU) { const int c = n0 + (r & (GB_HALF - 1)); return c < N ? (r < GB_HALF ? c : N + c) : -1; }
-    const int c = n0 + r; return c < N ? c : -1;
+    int gr;
+    if (EPI == EPI_SWIGLU) { const int c = n0 + (r & (GB_HALF - 1)); gr = r < GB_HALF ? c : N + c; if (c >= N) gr = w_rows - 1; }
+    else { gr = n0 + r; }
+    return gr < w_rows ? gr : w_rows - 1;
   };
-  uint4 ra[4], rw[4];
+  // this thread's four chunks of the A tile and of the W tile: slot s = i*512 + tid -> row s/8, chunk (s%8) ^ (row%8)
+  const bf16_t* pa[4]; const bf16_t* pw[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { ra[i] = make_uint4(0, 0, 0, 0); rw[i] = make_uint4(0, 0, 0, 0); }
+  for (int i = 0; i < 4; ++i) {
+    const int sl = i * GB_THREADS + tid, row = sl >> 3, kc = (sl & 7) ^ (row & 7);
+    int gm = m0 + row; if (gm >= M) gm = M - 1;
+    pa[i] = a + (size_t)gm * K + kc * 8;
+    pw[i] = w + (size_t)wrow(row) * K + kc * 8;
+  }
+  // Direct load issued as an instruction of its own (not through the compiler's builtin): the compiler
+  // orders every later LDS read after a builtin direct load (it cannot tell the two stages apart), which
+  // would serialise load and compute.  Here the only wait is the explicit one in front of the barrier.
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)gb_lds;
+  auto dma16 = [](const bf16_t* src, unsigned lds_wave_base) {   // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(src) : "m0", "memory");
+  };
+  auto issue = [&](int ks) {
+    const unsigned stage = lds0 + (unsigned)(ks & 1) * (2 * GB_TILE_BYTES);
+    const int k0 = ks * GB_BK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const unsigned o = __builtin_amdgcn_readfirstlane((unsigned)(i * GB_THREADS + wv * 64) * 16);
+      dma16(pa[i] + k0, stage + o);
+      dma16(pw[i] + k0, stage + GB_TILE_BYTES + o);
+    }
+  };
   const int ks_total = K / GB_BK;
 
   f32x4 acc[8][4];
@@ -46,49 +78,29 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int ks = -1; ks < ks_total; ++ks) {
-    if (ks >= 0) {
-      __syncthreads();                 // previous slice consumed
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ch = tid + i * GB_THREADS, row = ch >> 3, kc = (ch & 7) * 8;
-        *reinterpret_cast<uint4*>(&As[row * GB_LDK + kc]) = ra[i];
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ch = tid + i * GB_THREADS, row = ch >> 3, kc = (ch & 7) * 8;
-        *reinterpret_cast<uint4*>(&Ws[row * GB_LDK + kc]) = rw[i];
-      }
-      __syncthreads();
-    }
-    if (ks + 1 < ks_total) {           // prefetch slice ks + 1 into registers
-      const int k0 = (ks + 1) * GB_BK;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ch = tid + i * GB_THREADS, row = ch >> 3, kc = (ch & 7) * 8;
-        const int gm = m0 + row;
-        ra[i] = gm < M ? *reinterpret_cast<const uint4*>(a + (size_t)gm * K + k0 + kc) : make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ch = tid + i * GB_THREADS, row = ch >> 3, kc = (ch & 7) * 8;
-        const int gr = wrow(row);
-        rw[i] = gr >= 0 ? *reinterpret_cast<const uint4*>(w + (size_t)gr * K + k0 + kc) : make_uint4(0, 0, 0, 0);
-      }
-    }
-    if (ks < 0) continue;
+  // fragment addressing: row r = (multiple of 16) + m16, chunk kc = k32*4 + g -> slot r*8 + (kc ^ (m16 & 7))
+  const int sw0 = (g ^ (m16 & 7)) * 16;                 // byte offset of the lane's chunk inside its row, k32 = 0
+  issue(0);
+  for (int ks = 0; ks < ks_total; ++ks) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of slice ks has landed
+    __syncthreads();                   // ... and everyone's; every wave is done with slice ks - 1, whose
+                                       // stage is refilled next
+    if (ks + 1 < ks_total) issue(ks + 1);
+    const char* As = gb_lds + (ks & 1) * (2 * GB_TILE_BYTES);
+    const char* Ws = As + GB_TILE_BYTES;
 #pragma unroll
     for (int k32 = 0; k32 < GB_BK / 32; ++k32) {
+      const int sw = sw0 ^ (k32 * 64);                  // chunk index ^ 4
       uint4 fw[4];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         // EPI_SWIGLU: tiles 0,1 = this wave's 32 gate columns, tiles 2,3 = the matching up columns
         const int r = EPI == EPI_SWIGLU ? (j < 2 ? wn * 32 + j * 16 : GB_HALF + wn * 32 + (j - 2) * 16) : wn * 64 + j * 16;
-        fw[j] = *reinterpret_cast<const uint4*>(&Ws[(r + m16) * GB_LDK + k32 * 32 + g * 8]);
+        fw[j] = *reinterpret_cast<const uint4*>(Ws + (r + m16) * 128 + sw);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const uint4 fa = *reinterpret_cast<const uint4*>(&As[(wm * 128 + i * 16 + m16) * GB_LDK + k32 * 32 + g * 8]);
+        const uint4 fa = *reinterpret_cast<const uint4*>(As + (wm * 128 + i * 16 + m16) * 128 + sw);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[j]),
@@ -137,14 +149,24 @@ bool gemm_big_applies(int M, int N, int K) {
   return M >= 512 && tiles >= 200 && (K % GB_BK) == 0;
 }
 
+template <int EPI>
+static void gb_launch(hipStream_t s, dim3 grid, const bf16_t* a, const bf16_t* w, void* out, int M, int N, int K) {
+  static bool attr_done = false;     // one flag per template instance: 128 KB of dynamic LDS needs the opt-in
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_gemm_big<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, GB_LDS_BYTES);
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(k_gemm_big<EPI>, grid, dim3(GB_THREADS), GB_LDS_BYTES, s, a, w, out, M, N, K);
+}
+
 void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
   dim3 grid((N + GB_BN - 1) / GB_BN, (M + GB_BM - 1) / GB_BM);
-  hipLaunchKernelGGL(k_gemm_big<EPI_F32>, grid, dim3(GB_THREADS), 0, s, a, w, (void*)c, M, N, K);
+  gb_launch<EPI_F32>(s, grid, a, w, (void*)c, M, N, K);
 }
 
 void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
   dim3 grid((F + GB_HALF - 1) / GB_HALF, (M + GB_BM - 1) / GB_BM);
-  hipLaunchKernelGGL(k_gemm_big<EPI_SWIGLU>, grid, dim3(GB_THREADS), 0, s, a, wgu, (void*)act, M, F, K);
+  gb_launch<EPI_SWIGLU>(s, grid, a, wgu, (void*)act, M, F, K);
 }
 
 }  // namespace plt
