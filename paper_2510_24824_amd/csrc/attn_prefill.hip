@@ -37,10 +37,17 @@ struct PfState {           // online softmax state of one 16-row query tile
   }
 };
 
+// LDS tile of 32 keys.  16-byte chunks are XOR-swizzled so that the eight lanes the LDS serves together
+// (same chunk column, rows 0-3 and 8-11 of a K sub-tile, or eight consecutive V rows of 64 bytes) fall
+// into eight different bank groups.
 template <int D>
 struct PfLds {
-  bf16_t k[32][D + 8];     // 32 key rows, padded: conflict-light 16-byte fragment reads
-  bf16_t v[D][32];         // the cache's V block as is: [feature][position]
+  bf16_t k[32][D];         // [key][feature]; chunk c of row r at chunk c ^ ((r & 3) | ((r >> 3) & 1) << 2)
+  bf16_t v[D][32];         // [feature][position]; chunk c of row d at chunk c ^ ((d >> 1) & 3)
+  __device__ bf16_t* kp(int r, int c) { return &k[r][(c ^ ((r & 3) | (((r >> 3) & 1) << 2))) * 8]; }
+  __device__ const bf16_t* kp(int r, int c) const { return &k[r][(c ^ ((r & 3) | (((r >> 3) & 1) << 2))) * 8]; }
+  __device__ bf16_t* vp(int d, int c) { return &v[d][(c ^ ((d >> 1) & 3)) * 8]; }
+  __device__ const bf16_t* vp(int d, int c) const { return &v[d][(c ^ ((d >> 1) & 3)) * 8]; }
 };
 
 // One 32-key tile for the two query tiles of a wave.  lo/hi: per lane (= per query row) bounds,
@@ -55,8 +62,8 @@ __device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D>& sm,
   for (int q = 0; q < 2; ++q) { s[q][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[q][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
   for (int kk = 0; kk < D / 32; ++kk) {
-    const uint4 k0 = *reinterpret_cast<const uint4*>(&sm.k[key0][kk * 32 + g * 8]);
-    const uint4 k1 = *reinterpret_cast<const uint4*>(&sm.k[key0 + 4][kk * 32 + g * 8]);
+    const uint4 k0 = *reinterpret_cast<const uint4*>(sm.kp(key0, kk * 4 + g));
+    const uint4 k1 = *reinterpret_cast<const uint4*>(sm.kp(key0 + 4, kk * 4 + g));
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       s[q][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k0), pf_bf(qf[q][kk]), s[q][0], 0, 0, 0);
@@ -99,7 +106,7 @@ __device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D>& sm,
   }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
-    const uint4 vf = *reinterpret_cast<const uint4*>(&sm.v[dt * 16 + m16][g * 8]);
+    const uint4 vf = *reinterpret_cast<const uint4*>(sm.vp(dt * 16 + m16, g));
 #pragma unroll
     for (int q = 0; q < 2; ++q)
       st[q].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(vf), pb[q], st[q].acc[dt], 0, 0, 0);
@@ -165,23 +172,23 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const
         size_t off; int kkey, kcol;
         k_chunk(t, ch, off, kkey, kcol);
         if (F8) {
-          *reinterpret_cast<bf16x8*>(&sm.k[kkey][kcol]) = e4m3x8_to_bf16(rk[i].x, rk[i].y);
-          *reinterpret_cast<bf16x8*>(&sm.k[kkey][kcol + 8]) = e4m3x8_to_bf16(rk[i].z, rk[i].w);
-          *reinterpret_cast<bf16x8*>(&sm.v[ch >> 1][(ch & 1) * 16]) = e4m3x8_to_bf16(rv[i].x, rv[i].y);
-          *reinterpret_cast<bf16x8*>(&sm.v[ch >> 1][(ch & 1) * 16 + 8]) = e4m3x8_to_bf16(rv[i].z, rv[i].w);
+          *reinterpret_cast<bf16x8*>(sm.kp(kkey, kcol / 8)) = e4m3x8_to_bf16(rk[i].x, rk[i].y);
+          *reinterpret_cast<bf16x8*>(sm.kp(kkey, kcol / 8 + 1)) = e4m3x8_to_bf16(rk[i].z, rk[i].w);
+          *reinterpret_cast<bf16x8*>(sm.vp(ch >> 1, (ch & 1) * 2)) = e4m3x8_to_bf16(rv[i].x, rv[i].y);
+          *reinterpret_cast<bf16x8*>(sm.vp(ch >> 1, (ch & 1) * 2 + 1)) = e4m3x8_to_bf16(rv[i].z, rv[i].w);
         } else {
-          *reinterpret_cast<uint4*>(&sm.k[kkey][kcol]) = rk[i];
-          *reinterpret_cast<uint4*>(&sm.v[ch / 4][(ch % 4) * 8]) = rv[i];
+          *reinterpret_cast<uint4*>(sm.kp(kkey, kcol / 8)) = rk[i];
+          *reinterpret_cast<uint4*>(sm.vp(ch / 4, ch % 4)) = rv[i];
         }
       }
     }
     __syncthreads();
     if (t + 1 < t_end) fetch(t + 1);
     const int kb = t * 32;
-    // skip tiles no row of this wave may attend; mask only tiles that straddle a bound
-    int lo_min = lo[0] < lo[1] ? lo[0] : lo[1];
-    lo_min = __shfl(lo_min, 0, 64);          // rows ascend with the lane: lane 0 holds the smallest bound
-    if (kb > row_max || kb + 31 <= lo_min) continue;
+    // Every wave multiplies every tile of the workgroup's range, also the few that none of its rows may
+    // attend (they are masked out entirely): skipping them made the accumulators take two paths through
+    // the loop, which cost a copy of all 64 accumulator registers per tile.  Tiles that straddle a bound
+    // of some row are masked, the others are not.
     const bool need_mask = (kb + 31 > row_min) || (kb <= __shfl(lo[1], 15, 64));
     pf_tile<D>(st, sm, qf, scale_log2, kb, need_mask, lo, hi, m16, g);
   }

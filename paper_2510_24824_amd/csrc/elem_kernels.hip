@@ -243,10 +243,149 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
     }
   }
 }
+// ---- S3 for prefill-sized row counts: the same operation on tiles of 32 positions of one head ----
+// N consecutive values -> N consecutive cache elements with one or two wide stores (dst suitably aligned)
+template <int N>
+__device__ inline void store_packed(bf16_t* dst, const float (&v)[N]) {
+  unsigned w[N / 2];
+#pragma unroll
+  for (int i = 0; i < N / 2; ++i) w[i] = (unsigned)f32_to_bf16(v[2 * i]) | ((unsigned)f32_to_bf16(v[2 * i + 1]) << 16);
+  if (N == 4) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+  else
+#pragma unroll
+    for (int i = 0; i < N / 8; ++i) reinterpret_cast<uint4*>(dst)[i] = make_uint4(w[4 * i], w[4 * i + 1], w[4 * i + 2], w[4 * i + 3]);
+}
+template <int N>
+__device__ inline void store_packed(fp8_t* dst, const float (&v)[N]) {
+  unsigned w[N / 4];
+#pragma unroll
+  for (int i = 0; i < N / 4; ++i) {
+    float c[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) c[e] = fminf(fmaxf(v[4 * i + e], -448.f), 448.f);
+    int pk = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], 0, false);
+    w[i] = (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], pk, true);
+  }
+  if (N == 4) *reinterpret_cast<unsigned*>(dst) = w[0];
+  else if (N == 8) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+  else *reinterpret_cast<uint4*>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// grid (ceil(n/32), Hq + 2*Hkv, Bc), 256 threads: thread (r = t/8, c = t%8) owns D/16 rotation pairs
+// (j, j + D/2), j = c*D/16 .., of position p0 + r.  Q and K leave as 8- or 16-byte pieces (K straight into
+// its tiled cache layout); V is transposed through LDS and leaves as one whole [D][32] cache block.
+template <int D, typename KT>
+__global__ __launch_bounds__(256) void k_rope_append_tile(const float* __restrict__ qkv, int S, size_t slab,
+                                                          const float* __restrict__ gate_w, const float* __restrict__ gate_b,
+                                                          bf16_t* __restrict__ q_out, float* __restrict__ z_out, KvView kv,
+                                                          int n, int loop, Dims dm, const double* __restrict__ inv_freq, int mode) {
+  constexpr int PP = D / 16, half = D / 2;
+  constexpr int PPT = 32 * D / 256;          // positions per thread when the V block is written out
+  __shared__ float vt[D][33];
+  const int t = threadIdx.x, r = t >> 3, jb = (t & 7) * PP;
+  const int hs = blockIdx.y, b = blockIdx.z, p0 = blockIdx.x * 32, p = p0 + r;
+  const int Hq = dm.Hq, Hkv = dm.Hkv, ncol = (Hq + 2 * Hkv) * D;
+  const bool ok = p < n;
+  const size_t row = (size_t)b * n + (ok ? p : 0);
+  float lo[PP], hi[PP];
+#pragma unroll
+  for (int i = 0; i < PP; ++i) { lo[i] = 0.f; hi[i] = 0.f; }
+  if (ok) {
+    const float* src = qkv + row * ncol + (size_t)hs * D + jb;
+    for (int s = 0; s < S; ++s) {
+#pragma unroll
+      for (int i = 0; i < PP / 4; ++i) {
+        const float4 a = *reinterpret_cast<const float4*>(src + (size_t)s * slab + 4 * i);
+        const float4 c = *reinterpret_cast<const float4*>(src + (size_t)s * slab + half + 4 * i);
+        lo[4 * i] += a.x; lo[4 * i + 1] += a.y; lo[4 * i + 2] += a.z; lo[4 * i + 3] += a.w;
+        hi[4 * i] += c.x; hi[4 * i + 1] += c.y; hi[4 * i + 2] += c.z; hi[4 * i + 3] += c.w;
+      }
+    }
+  }
+  const bool is_q = hs < Hq, is_k = !is_q && hs < Hq + Hkv;
+  float rl[PP], rh[PP];
+#pragma unroll
+  for (int i = 0; i < PP; ++i) { rl[i] = lo[i]; rh[i] = hi[i]; }
+  if (is_q || is_k) {
+#pragma unroll
+    for (int i = 0; i < PP; ++i) {
+      // angle in turns, reduced in double, then the hardware sine / cosine (as in k_rope_append)
+      double a = (double)p * inv_freq[jb + i] * 0.15915494309189535;
+      a -= rint(a);
+      const float sn = __builtin_amdgcn_sinf((float)a), c = __builtin_amdgcn_cosf((float)a);
+      rl[i] = lo[i] * c - hi[i] * sn; rh[i] = hi[i] * c + lo[i] * sn;
+    }
+  }
+  if (is_q) {
+    if (mode == 0 && loop > 0) {                       // gate logit on the un-rotated query [Alg. 3 l.4]
+      float zp = 0.f;
+#pragma unroll
+      for (int i = 0; i < PP; ++i) zp += lo[i] * gate_w[hs * D + jb + i] + hi[i] * gate_w[hs * D + half + jb + i];
+      zp += __shfl_xor(zp, 1, 64); zp += __shfl_xor(zp, 2, 64); zp += __shfl_xor(zp, 4, 64);
+      if (ok && (t & 7) == 0) z_out[row * Hq + hs] = zp + gate_b[hs];
+    }
+    if (ok) {
+      bf16_t* dst = q_out + row * Hq * D + (size_t)hs * D + jb;
+      store_packed<PP>(dst, rl); store_packed<PP>(dst + half, rh);
+    }
+    return;
+  }
+  if (mode == 2 && loop > 0) return;                   // KV-share ablation: non-first loops keep no K/V
+  const int kh = is_k ? hs - Hq : hs - Hq - Hkv;
+  const bool own = mode == 0 && loop > 0;              // non-first loop of the method: own K/V (+ ring tail)
+  const size_t stream = own ? (size_t)b * Hkv + kh : (size_t)(kv.b0 + b) * Hkv + kh;
+  const size_t stream_elems = (size_t)(own ? kv.n_pad_loc : kv.n_pad) * D;
+  const bool ring = own && ok && p >= n - kv.w;        // the w most recent entries also enter the ring
+  const int slot = p % kv.w;
+  const size_t rstream = (((size_t)(kv.b0 + b) * kv.n_rings + (loop - 1)) * Hkv + kh) * (size_t)kv.w_pad * D;
+  if (is_k) {
+    if (ok) {
+      KT* dst = (KT*)(own ? kv.k_loc : kv.k_share) + stream * stream_elems;
+      store_packed<PP>(dst + kblk_index<KT>(p, jb, D), rl);
+      store_packed<PP>(dst + kblk_index<KT>(p, jb + half, D), rh);
+      if (ring) {
+        KT* rd = (KT*)kv.k_ring + rstream;
+        store_packed<PP>(rd + kblk_index<KT>(slot, jb, D), rl);
+        store_packed<PP>(rd + kblk_index<KT>(slot, jb + half, D), rh);
+      }
+    }
+    return;
+  }
+  // V: values are not rotated; transpose the tile through LDS and write the whole [D][32] block
+  if (ring) {
+    KT* rd = (KT*)kv.v_ring + rstream;
+#pragma unroll
+    for (int i = 0; i < PP; ++i) { st<KT>(rd + vblk_index(slot, jb + i, D), lo[i]); st<KT>(rd + vblk_index(slot, jb + half + i, D), hi[i]); }
+  }
+#pragma unroll
+  for (int i = 0; i < PP; ++i) { vt[jb + i][r] = lo[i]; vt[jb + half + i][r] = hi[i]; }   // zeros beyond the prompt
+  __syncthreads();
+  {
+    const int d = t / (32 / PPT), q0 = (t % (32 / PPT)) * PPT;
+    float o[PPT];
+#pragma unroll
+    for (int i = 0; i < PPT; ++i) o[i] = vt[d][q0 + i];
+    KT* dst = (KT*)(own ? kv.v_loc : kv.v_share) + stream * stream_elems + (size_t)(p0 >> 5) * (D * 32) + d * 32 + q0;
+    store_packed<PPT>(dst, o);
+  }
+}
+
 template <typename T, typename KT>
 void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, const float* gate_w,
                         const float* gate_b, T* q_out, float* z_out, KvView kv, RowMap rm, int R,
                         Dims dm, const double* inv_freq, int mode) {
+  if constexpr (sizeof(T) == 2) if (rm.prefill && mode != 3 && (slab & 3) == 0 && R % rm.rows_per_seq == 0 && rm.rows_per_seq >= 32) {
+    // bf16 models, many positions per sequence: 32-position tiles with wide, contiguous cache stores
+    const int n = rm.rows_per_seq, Bc = R / n;
+    dim3 grid((n + 31) / 32, dm.Hq + 2 * dm.Hkv, Bc);
+    if (dm.D == 128)
+      hipLaunchKernelGGL((k_rope_append_tile<128, KT>), grid, dim3(256), 0, s, qkv, S, slab, gate_w, gate_b, (bf16_t*)q_out,
+                         z_out, kv, n, rm.loop_fixed, dm, inv_freq, mode);
+    else
+      hipLaunchKernelGGL((k_rope_append_tile<64, KT>), grid, dim3(256), 0, s, qkv, S, slab, gate_w, gate_b, (bf16_t*)q_out,
+                         z_out, kv, n, rm.loop_fixed, dm, inv_freq, mode);
+    return;
+  }
   hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
                      gate_w, gate_b, q_out, z_out, kv, rm, dm, inv_freq, mode);
 }

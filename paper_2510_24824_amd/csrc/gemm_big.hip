@@ -58,7 +58,9 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
   // would serialise load and compute.  Here the only wait is the explicit one in front of the barrier.
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)gb_lds;
   auto dma16 = [](const bf16_t* src, unsigned lds_wave_base) {   // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(src) : "m0", "memory");
+    unsigned keep_m0;                                            // m0 is left as it was found
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
   };
   auto issue = [&](int ks) {
     const unsigned stage = lds0 + (unsigned)(ks & 1) * (2 * GB_TILE_BYTES);
