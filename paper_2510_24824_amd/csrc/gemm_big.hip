@@ -16,7 +16,14 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
-constexpr int GB_BM = 256, GB_BN = 256, GB_BK = 64, GB_THREADS = 512;
+constexpr int GB_BM = 256, GB_BN = 256, GB_BK = 64;
+constexpr int GB_WN = 4;                        // waves along N (x 2 along M): wave tile 128 x 64.  Two waves
+                                                // along N (128 x 128 per wave, accumulators in AGPRs, one wave
+                                                // per SIMD) halve the LDS reads per MFMA but measured 1.5x slower:
+                                                // a single wave per SIMD cannot hide the LDS and barrier latency
+constexpr int GB_THREADS = 2 * GB_WN * 64;
+constexpr int GB_NT = GB_BN / GB_WN / 16;       // 16-column tiles per wave
+constexpr int GB_DMA = GB_BM * GB_BK / 8 / GB_THREADS;   // 16-byte chunks of one operand tile per thread
 constexpr int GB_HALF = GB_BN / 2;   // SwiGLU tile: GB_HALF gate columns + the matching GB_HALF up columns
 constexpr int GB_TILE_BYTES = GB_BM * GB_BK * 2;                 // one operand tile of one K slice: 32 KB
 constexpr int GB_LDS_BYTES = 2 * 2 * GB_TILE_BYTES;              // two stages x (A tile + W tile) = 128 KB
@@ -33,7 +40,7 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
   // N: EPI_F32: output columns (= rows of w); EPI_SWIGLU: F (w has 2F rows, the output F columns)
   extern __shared__ __attribute__((aligned(16))) char gb_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
-  const int wm = wv >> 2, wn = wv & 3;
+  const int wm = wv / GB_WN, wn = wv % GB_WN;
   const int m0 = blockIdx.y * GB_BM;
   const int n0 = blockIdx.x * (EPI == EPI_SWIGLU ? GB_HALF : GB_BN);
   const int w_rows = EPI == EPI_SWIGLU ? 2 * N : N;
@@ -44,10 +51,10 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
     else { gr = n0 + r; }
     return gr < w_rows ? gr : w_rows - 1;
   };
-  // this thread's four chunks of the A tile and of the W tile: slot s = i*512 + tid -> row s/8, chunk (s%8) ^ (row%8)
-  const bf16_t* pa[4]; const bf16_t* pw[4];
+  // this thread's chunks of the A tile and of the W tile: slot s = i*THREADS + tid -> row s/8, chunk (s%8) ^ (row%8)
+  const bf16_t* pa[GB_DMA]; const bf16_t* pw[GB_DMA];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < GB_DMA; ++i) {
     const int sl = i * GB_THREADS + tid, row = sl >> 3, kc = (sl & 7) ^ (row & 7);
     int gm = m0 + row; if (gm >= M) gm = M - 1;
     pa[i] = a + (size_t)gm * K + kc * 8;
@@ -66,7 +73,7 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
     const unsigned stage = lds0 + (unsigned)(ks & 1) * (2 * GB_TILE_BYTES);
     const int k0 = ks * GB_BK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < GB_DMA; ++i) {
       const unsigned o = __builtin_amdgcn_readfirstlane((unsigned)(i * GB_THREADS + wv * 64) * 16);
       dma16(pa[i] + k0, stage + o);
       dma16(pw[i] + k0, stage + GB_TILE_BYTES + o);
@@ -74,11 +81,11 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
   };
   const int ks_total = K / GB_BK;
 
-  f32x4 acc[8][4];
+  f32x4 acc[8][GB_NT];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < GB_NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // fragment addressing: row r = (multiple of 16) + m16, chunk kc = k32*4 + g -> slot r*8 + (kc ^ (m16 & 7))
   const int sw0 = (g ^ (m16 & 7)) * 16;                 // byte offset of the lane's chunk inside its row, k32 = 0
@@ -93,18 +100,19 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
 #pragma unroll
     for (int k32 = 0; k32 < GB_BK / 32; ++k32) {
       const int sw = sw0 ^ (k32 * 64);                  // chunk index ^ 4
-      uint4 fw[4];
+      uint4 fw[GB_NT];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        // EPI_SWIGLU: tiles 0,1 = this wave's 32 gate columns, tiles 2,3 = the matching up columns
-        const int r = EPI == EPI_SWIGLU ? (j < 2 ? wn * 32 + j * 16 : GB_HALF + wn * 32 + (j - 2) * 16) : wn * 64 + j * 16;
+      for (int j = 0; j < GB_NT; ++j) {
+        // EPI_SWIGLU: the first half of the tiles = this wave's gate columns, the second half = the matching up columns
+        const int r = EPI == EPI_SWIGLU ? (j < GB_NT / 2 ? wn * (GB_NT * 8) + j * 16 : GB_HALF + wn * (GB_NT * 8) + (j - GB_NT / 2) * 16)
+                                        : wn * (GB_NT * 16) + j * 16;
         fw[j] = *reinterpret_cast<const uint4*>(Ws + (r + m16) * 128 + sw);
       }
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const uint4 fa = *reinterpret_cast<const uint4*>(As + (wm * 128 + i * 16 + m16) * 128 + sw);
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < GB_NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[j]),
                                                              __builtin_bit_cast(bf16x8, fa), acc[i][j], 0, 0, 0);
       }
@@ -118,11 +126,11 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
     if (EPI == EPI_SWIGLU) {
       bf16_t* o = (bf16_t*)out + (size_t)gm * N;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int gn = n0 + wn * 32 + j * 16 + 4 * g;
+      for (int j = 0; j < GB_NT / 2; ++j) {
+        const int gn = n0 + wn * (GB_NT * 8) + j * 16 + 4 * g;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { const float gt = acc[i][j][e]; v[e] = gt / (1.0f + __expf(-gt)) * acc[i][j + 2][e]; }
+        for (int e = 0; e < 4; ++e) { const float gt = acc[i][j][e]; v[e] = gt / (1.0f + __expf(-gt)) * acc[i][j + GB_NT / 2][e]; }
         if (gn + 3 < N && (N & 3) == 0) {
           ushort4 p; p.x = f32_to_bf16(v[0]); p.y = f32_to_bf16(v[1]); p.z = f32_to_bf16(v[2]); p.w = f32_to_bf16(v[3]);
           *reinterpret_cast<ushort4*>(o + gn) = p;
@@ -133,8 +141,8 @@ __global__ __launch_bounds__(GB_THREADS) void k_gemm_big(const bf16_t* __restric
     } else {
       float* o = (float*)out + (size_t)gm * N;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int gn = n0 + wn * 64 + j * 16 + 4 * g;
+      for (int j = 0; j < GB_NT; ++j) {
+        const int gn = n0 + wn * (GB_NT * 16) + j * 16 + 4 * g;
         if (gn + 3 < N && (N & 3) == 0) *reinterpret_cast<f32x4*>(o + gn) = acc[i][j];
         else for (int e = 0; e < 4; ++e) if (gn + e < N) o[gn + e] = acc[i][j][e];
       }
