@@ -197,6 +197,10 @@ int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv
  * (i.e. 8*(m>>2) + (m&3) + 4a, resp. 16*(m>>2) + (m&3) + 4a), feature kk*4c + g*c + its index in c:
  * one wavefront load of the attention kernel (lane = 16g + m) is then one contiguous KiB.
  * Elements are moved, never converted: for PLT_FP8_E4M3 source and destination hold e4m3 bytes. */
+/* Host-side statement of the K layout above: element index of (position pos, feature f) inside one
+ * stream of head size D (no device work; -1 for a bad argument).  The append, pack and attention
+ * kernels use the same function. */
+int64_t plt_attn_k_index(int32_t dtype, int32_t pos, int32_t f, int32_t D);
 int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,
                     void* dev_dst, void* hip_stream);
 int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,

@@ -4,6 +4,7 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2510_24824_amd import binding as B, synth
@@ -110,3 +111,26 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "ONE GPU" in r.stderr
+
+
+def test_k_cache_layout_is_a_tiling_in_matrix_core_load_order():
+    """The K cache keeps tiles of 32 (bf16) / 64 (e4m3) positions; inside a tile the 16-byte pieces
+    follow [sub-tile a][feature chunk kk][lane group g][row m]; float caches stay row-major.  Checked
+    on the host function the kernels share: a bijection per tile, 16-byte pieces intact, and lane
+    (m, g) of load (a, kk) holding key step*(m>>2) + (m&3) + 4a, features kk*4c + g*c .."""
+    lib = B.lib()
+    for dtype, T, c in ((B.PLT_BF16, 32, 8), (B.PLT_FP8_E4M3, 64, 16)):
+        for D in (64, 128):
+            idx = np.array([[lib.plt_attn_k_index(dtype, p, f, D) for f in range(D)] for p in range(2 * T)])
+            assert sorted(idx[:T].ravel()) == list(range(T * D))                  # tile 0 <-> [0, T*D)
+            assert np.array_equal(idx[T:], idx[:T] + T * D)                       # tile 1 follows
+            step = T // 4
+            for a in range(T // 16):
+                for kk in range(D // (4 * c)):
+                    for g in range(4):
+                        for m in range(16):
+                            key, f0 = step * (m >> 2) + (m & 3) + 4 * a, kk * 4 * c + g * c
+                            base = ((a * (D // (4 * c)) + kk) * 64 + g * 16 + m) * c
+                            assert list(idx[key, f0:f0 + c]) == list(range(base, base + c))
+    assert lib.plt_attn_k_index(B.PLT_F32, 5, 7, 64) == 5 * 64 + 7
+    assert lib.plt_attn_k_index(B.PLT_BF16, 0, 64, 64) == -1 and lib.plt_attn_k_index(9, 0, 0, 64) == -1
