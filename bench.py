@@ -442,7 +442,7 @@ def main():
     log(f"[bench] prefill done in {prefill_s:.2f} s")
 
     # state before the first decode step (for the oracle sample), then one clean step
-    sample = sorted(set([0, Bn // 3, (2 * Bn) // 3, Bn - 1]))
+    sample = sorted(set(int(round(i * (Bn - 1) / 5)) for i in range(6)))   # six sequences: 10-15 s of CPU work
     state = {}
     if not args.no_cpu_baseline:
         carry_all = kv.get_carry() if L > 1 else np.zeros((Bn, 0, shape.d_model), np.float32)
@@ -565,7 +565,7 @@ def main():
         out["long_context"] = bench_long_context(B, shape, blob, g, max(4, args.steps // 4))
 
     if not args.no_cpu_baseline:
-        log(f"[bench] timing the CPU oracle on {len(sample)} sequences (about 10-30 s) ...")
+        log(f"[bench] timing the CPU oracle on {len(sample)} sequences (10-15 s) ...")
         out["cpu_baseline"] = oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_next)
     print(json.dumps(out), flush=True)
 
