@@ -555,6 +555,32 @@ def main():
         f8["latency_vs_nonlooped"] = {k: f8[k]["ms_per_step"] / f8["nonlooped_L1"]["ms_per_step"] for k in ("plt_L2", "plt_L3", "plt_L4")}
         f8["attn_kernel_only"] = bench_attn_kernel(B, args.steps, args.warmup, fp8=True)
         out["fp8_kv_cache"] = f8
+        # ---- the paper's open-source dense recipe: 16 layers, FFN 16384, 32 query / 8 kv heads of 64 (GQA)
+        gq = {}
+        gshape = synth.PLT_DENSE_GQA
+        gblob = fill_weights_on_device(B, B.make_config(gshape, dtype=B.PLT_BF16), SEED + 3)
+        gtok = torch.randint(0, gshape.vocab, (Bn,), generator=g, device="cuda", dtype=torch.int32)
+        for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
+                               ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2)]:
+            cg = B.make_config(gshape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
+            mg = B.Model(cg, gblob)
+            kg = B.KV(mg, Bn, N)
+            fill_kv_random(B, kg, g)
+            mg.profile_enable(1 << B.PLT_PROF_ATTN)
+            msg = time_steps(kg, pos, gtok, 2, max(8, args.steps // 2))
+            a_ms, a_n = mg.profile_read(B.PLT_PROF_ATTN, reset=True)
+            abg = attn_alg_bytes(Bn, Lx if mode == B.PLT_MODE_CLP else 1, gshape.n_heads, gshape.n_kv_heads, gshape.head_dim, N, w)
+            usg = a_ms * 1e3 / max(a_n, 1)
+            gq[name] = {"ms_per_step": msg, "tokens_per_s": Bn / (msg * 1e-3), "attn_us_per_launch": usg,
+                        "attn_GBps": abg / (usg * 1e-6) / 1e9}
+            log(f"[bench] dense GQA shape {name}: {msg:.3f} ms/step, attention {usg:.0f} us = {abg / (usg * 1e-6) / 1e12:.2f} TB/s")
+            kg.close(); mg.close(); del kg
+            torch.cuda.empty_cache()
+        gq["latency_vs_nonlooped"] = {k: gq[k]["ms_per_step"] / gq["nonlooped_L1"]["ms_per_step"] for k in ("plt_L2", "plt_L3", "vanilla_loop_L2")}
+        gq["workload"] = "16 layers, d=2048, FFN 16384, 32 query / 8 kv heads x 64, vocab 50304, batch %d, %d-token context" % (Bn, N)
+        del gblob
+        torch.cuda.empty_cache()
+        out["dense_gqa_shape"] = gq
 
     if args.sweep:
         out["serving_sweep"] = bench_sweep(B, shape, blob, g)

@@ -37,6 +37,12 @@ PLT_1P3B = ModelShape(n_layers=24, d_model=2048, n_heads=16, n_kv_heads=16, head
                       ffn_hidden=5632, vocab=32000, n_loops=2, window=64)
 
 
+# the paper's open-source dense recipe (appendix, "Dense Models Recipe"): 16 layers, hidden 2048, MLP hidden
+# 16384, grouped-query attention with 32 query / 8 key-value heads, tied head (its extra norms are not modelled)
+PLT_DENSE_GQA = ModelShape(n_layers=16, d_model=2048, n_heads=32, n_kv_heads=8, head_dim=64,
+                           ffn_hidden=16384, vocab=50304, n_loops=2, window=64)
+
+
 def _rng(seed: int, stream: int) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, stream]))
 

@@ -29,12 +29,13 @@ def oracle_step(shape, cfg, weights_host, exports, carry, token, pos):
     return nxt, lg, orc.trace[-1]
 
 
-@pytest.mark.parametrize("kv_dtype", [0, B.PLT_FP8_E4M3])
-def test_decode_step_1p3b_L2_batch64_ctx2048_sampled(kv_dtype):
+@pytest.mark.parametrize("kv_dtype,shape", [(0, synth.PLT_1P3B), (B.PLT_FP8_E4M3, synth.PLT_1P3B), (0, synth.PLT_DENSE_GQA)],
+                         ids=["1p3b-bf16kv", "1p3b-e4m3kv", "dense-gqa-32q8kv"])
+def test_decode_step_1p3b_L2_batch64_ctx2048_sampled(kv_dtype, shape):
     """The headline workload: 24 layers, d=2048, 16x128 heads, FFN 5632, vocab 32000, L=2, w=64,
     batch 64, 2048-token context built by plt_prefill; sequences 0 and 41 checked against the oracle.
-    Also with e4m3 caches (the oracle then rounds the new position's K and V to e4m3 as well)."""
-    shape = synth.PLT_1P3B
+    Also with e4m3 caches (the oracle then rounds the new position's K and V to e4m3 as well), and on
+    the paper's open-source dense shape (16 layers, FFN 16384, 32 query / 8 kv heads of 64)."""
     Bn, N = 64, 2048
     pos = N - 1
     cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=2, window=64, kv_dtype=kv_dtype)
