@@ -455,14 +455,22 @@ __global__ __launch_bounds__(256) void k_attn_combine(AttnDecArgs A) {
   finalize_row<D>(A, b, kvh, rt, tid, Lg, og, Ll, ol);
 }
 
-size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D) {
+size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D, int max_splits_in) {
   const int G = Hq / Hkv, n_rt = (L * G + 15) / 16;
   const size_t slots = (size_t)B * Hkv * n_rt;
   const size_t rec = (size_t)(32 + 16 * D) * sizeof(float);
-  const size_t max_splits = 64;
+  const size_t max_splits = max_splits_in < 1 ? 1 : (max_splits_in > 64 ? 64 : max_splits_in);
   size_t bytes = slots * max_splits * rec;            // split records
   bytes += slots * (size_t)(16 * D) * sizeof(float);  // local-branch records
   return bytes;
+}
+
+// the largest value attn_mfma_default_splits can return for any context length and any rows per stream
+int attn_mfma_max_default_splits(int B, int Hkv) {
+  const long streams = (long)B * Hkv;
+  if (streams >= 256) return 1;
+  const int s = (int)((256 + streams - 1) / streams);
+  return s > 64 ? 64 : s;
 }
 
 int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx, int kv_fp8) {
@@ -484,7 +492,8 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx, int kv_fp8
 
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform, Dims dm,
-                             int plain, void* scratch, int n_splits, int l_off, int l_stride, int kv_fp8) {
+                             int plain, void* scratch, int n_splits, int l_off, int l_stride, int kv_fp8,
+                             int scratch_splits) {
   AttnDecArgs A;
   A.l_off = l_off; A.l_stride = l_stride > 0 ? l_stride : dm.L;
   A.q = q; A.z = z; A.y = y;
@@ -494,13 +503,14 @@ void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf1
   A.n_pad = kv.n_pad; A.w_pad = kv.w_pad; A.w = kv.w; A.n_rings = plain ? 0 : kv.n_rings;
   A.L = dm.L; A.Hq = dm.Hq; A.Hkv = dm.Hkv; A.G = dm.Hq / dm.Hkv;
   A.n_rows = dm.L * A.G; A.n_rt = (A.n_rows + 15) / 16;
-  A.n_splits = n_splits < 1 ? 1 : (n_splits > 64 ? 64 : n_splits);
+  if (scratch_splits < 1 || scratch_splits > 64) scratch_splits = 64;    // split records the scratch was sized for
+  A.n_splits = n_splits < 1 ? 1 : (n_splits > scratch_splits ? scratch_splits : n_splits);
   A.plain = plain;
   A.scale_log2 = 1.4426950408889634f / sqrtf((float)dm.D);
   const size_t slots = (size_t)dm.B * dm.Hkv * A.n_rt;
   const size_t rec = (size_t)(32 + 16 * dm.D);
   A.part = (float*)scratch;
-  A.part_loc = A.part + slots * 64 * rec;
+  A.part_loc = A.part + slots * (size_t)scratch_splits * rec;
   dim3 grid(A.n_splits * A.n_rt, dm.Hkv, dm.B), cgrid(A.n_rt, dm.Hkv, dm.B);
   if (dm.D == 64) {
     if (kv_fp8) hipLaunchKernelGGL((k_attn_decode<64, true>), grid, dim3(256), 0, s, A);

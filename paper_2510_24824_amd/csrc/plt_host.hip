@@ -294,7 +294,7 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   if ((t = gemm_out_need(c, R, d, F)) > go) go = t;
   if ((t = gemm_out_need(c, batch, V, d)) > go) go = t;
   kv->gout_elems = go;
-  kv->attn_scratch_bytes = attn_mfma_scratch_bytes(batch, is_clp(c) ? L : 1, Hq, Hkv, D);
+  kv->attn_scratch_bytes = attn_mfma_scratch_bytes(batch, is_clp(c) ? L : 1, Hq, Hkv, D, attn_mfma_max_default_splits(batch, Hkv));
   auto dmalloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 256); };
   dmalloc((void**)&kv->x, (size_t)R * d * 4);
   dmalloc(&kv->a, (size_t)R * d * m->es);
@@ -398,12 +398,12 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
             vl.k_share = (char*)v.k_share + (size_t)lp * v.cache_stride * m->kes;
             vl.v_share = (char*)v.v_share + (size_t)lp * v.cache_stride * m->kes;
             launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, vl, kv->pos_dev, 0, 0, d1, 1,
-                                    kv->attn_scratch, ns, lp, attn_L, m->kv8);
+                                    kv->attn_scratch, ns, lp, attn_L, m->kv8, attn_mfma_max_default_splits(kv->B, Hkv));
           }
         } else {
           const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1, m->kv8);
           launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, kv->pos_dev, 0, 0, dm,
-                                  plain ? 1 : 0, kv->attn_scratch, ns, 0, 0, m->kv8);
+                                  plain ? 1 : 0, kv->attn_scratch, ns, 0, 0, m->kv8, attn_mfma_max_default_splits(kv->B, Hkv));
         }
       }
     } else {

@@ -169,13 +169,14 @@ void launch_attn_f32(hipStream_t s, const float* q, const float* z, float* y, Kv
                      RowMap rm, int R, Dims dm, int plain);
 
 // attn_mfma.hip : bf16 q / y, caches in bf16 or e4m3 (kv_fp8), MFMA tiles
-size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D);
+size_t attn_mfma_scratch_bytes(int B, int L, int Hq, int Hkv, int D, int max_splits = 64);
+int attn_mfma_max_default_splits(int B, int Hkv);
 int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx, int kv_fp8 = 0);
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform,
                              Dims dm, int plain, void* scratch, int n_splits,
                              int l_off = 0, int l_stride = 0 /* rows per sequence in q / y; 0 = dm.L */,
-                             int kv_fp8 = 0);
+                             int kv_fp8 = 0, int scratch_splits = 64 /* max_splits the scratch was sized with */);
 // local_tmp: float scratch [Bc*n, Hq*D] (used by loops >= 2 only)
 void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
                               KvView kv, int Bc, int n, int loop, Dims dm, int plain, int kv_fp8 = 0);
