@@ -146,15 +146,17 @@ template void launch_resid_norm<float>(hipStream_t, float*, int, int, const floa
 template void launch_resid_norm<bf16_t>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, bf16_t*, int, int);
 
 // ---- S3: RoPE, gate logit (Eq. 2, on the un-rotated query), cache append ----
-// grid (Hq + 2*Hkv, R), 64 threads: thread j < D/2 owns the pair (j, j + D/2) of one head vector.
+// grid (ceil((Hq + 2*Hkv) / 4), R), 256 threads = 4 head vectors: lane j < D/2 of a wave owns the pair (j, j + D/2).
 template <typename T, typename KT>
 __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
                               const float* __restrict__ gate_w, const float* __restrict__ gate_b,
                               T* __restrict__ q_out, float* __restrict__ z_out, KvView kv, RowMap rm,
                               Dims dm, const double* __restrict__ inv_freq, int mode) {
   // mode: 0 = PLT (rings + gate), 1 = plain, 2 = loops >= 2 append nothing, 3 = row of loop l -> cache l
-  const int hs = blockIdx.x, r = blockIdx.y, j = threadIdx.x;
+  // one wave per head vector, four head vectors per workgroup (fewer, fatter workgroups dispatch faster)
+  const int hs = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6), r = blockIdx.y, j = threadIdx.x & 63;
   const int D = dm.D, half = D / 2, Hq = dm.Hq, Hkv = dm.Hkv;
+  if (hs >= Hq + 2 * Hkv) return;
   const int ncol = (Hq + 2 * Hkv) * D;
   int b, p, l;
   row_decode(rm, r, b, p, l);
@@ -386,7 +388,7 @@ void launch_rope_append(hipStream_t s, const float* qkv, int S, size_t slab, con
                          z_out, kv, n, rm.loop_fixed, dm, inv_freq, mode);
     return;
   }
-  hipLaunchKernelGGL((k_rope_append<T, KT>), dim3(dm.Hq + 2 * dm.Hkv, R), dim3(64), 0, s, qkv, S, slab,
+  hipLaunchKernelGGL((k_rope_append<T, KT>), dim3((dm.Hq + 2 * dm.Hkv + 3) / 4, R), dim3(256), 0, s, qkv, S, slab,
                      gate_w, gate_b, q_out, z_out, kv, rm, dm, inv_freq, mode);
 }
 template void launch_rope_append<float, float>(hipStream_t, const float*, int, size_t, const float*, const float*, float*, float*, KvView, RowMap, int, Dims, const double*, int);
