@@ -150,16 +150,20 @@ constexpr int WS_KR = 512, WS_LDK = WS_KR + 8;
 
 // MT: 16-row activation tiles (4: M <= 64, 8: M <= 128); NB: strips per group; the K range is
 // consumed in steps of WS_KH 32-wide chunks, two register buffers alternating
-template <int MT, int NB, int NW>   // NW: waves per workgroup (4: one per SIMD, 8: two per SIMD)
+template <int MT, int NB, int NW, bool MULTI>   // NW: waves per workgroup; MULTI: several K ranges per workgroup
 __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                              float* __restrict__ c, int M, int N, int K,
-                                                             int n_groups) {
+                                                             int n_groups, int R) {
+  // R: consecutive K ranges one workgroup walks through (slab = blockIdx.z holds their sum).  R > 1
+  // needs every wave to own at most one strip group (the launcher guarantees it): the accumulators
+  // then simply stay in registers while the activation slice in LDS is exchanged range by range.
   extern __shared__ __attribute__((aligned(16))) bf16_t As[];   // [MT*16][WS_LDK]
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int ng = blockIdx.x, rb = blockIdx.y, split = blockIdx.z;
-  const int k0 = split * WS_KR;
-  const int kr = (K - k0 < WS_KR) ? K - k0 : WS_KR;          // valid width of this K range
   const int row0 = rb * (MT * 16);
+  const int n_ranges_total = (K + WS_KR - 1) / WS_KR;
+  const int range0 = split * R;
+  const int n_rng = (range0 + R <= n_ranges_total) ? R : n_ranges_total - range0;
 
   constexpr int WS_THREADS = NW * 64;
   constexpr int WS_KH = (NB * NW >= 16) ? 4 : 8, STEPS = (WS_KR / 32) / WS_KH;
@@ -167,8 +171,10 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restri
   const int n_grp = (n_strips + NB - 1) / NB;
   const int stride = n_groups * NW;
   uint4 bufA[NB][WS_KH], bufB[NB][WS_KH];
-  // step h (0..STEPS-1) of the K range for the NB strips of group grp
-  auto wload = [&](uint4 (&f)[NB][WS_KH], int grp, int h) {
+  // step h (0..STEPS-1) of K range `rng` for the NB strips of group grp
+  auto wload = [&](uint4 (&f)[NB][WS_KH], int grp, int h, int rng) {
+    const int k0 = rng * WS_KR;
+    const int kr = (K - k0 < WS_KR) ? K - k0 : WS_KR;          // valid width of this K range
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb) {
       int n = (grp * NB + sb) * 16 + m16; if (n >= N) n = N - 1;   // ragged N: clamp (stores are masked)
@@ -180,29 +186,51 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restri
       }
     }
   };
+  // Activation slice of K range `rng` -> LDS.  A full range goes HBM/L2 -> LDS directly, one row (1 KB) per
+  // wavefront load, no registers involved (rows beyond M repeat row M-1; their outputs are never stored).
+  // The ragged last range of a K that is no multiple of 512 is staged through registers in small batches
+  // so that the columns beyond K can be zero-filled.
+  const unsigned lds_as = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)As;
+  auto load_slice = [&](int rng) {
+    const int k0 = rng * WS_KR;
+    const int kr = (K - k0 < WS_KR) ? K - k0 : WS_KR;
+    if (kr == WS_KR) {
+#pragma unroll 4
+      for (int row = wv; row < MT * 16; row += NW) {
+        int gm = row0 + row; if (gm >= M) gm = M - 1;
+        const bf16_t* src = a + (size_t)gm * K + k0 + lane * 8;
+        const unsigned dst = __builtin_amdgcn_readfirstlane(lds_as + (unsigned)row * (WS_LDK * 2));
+        unsigned keep_m0;                                          // m0 is left as it was found
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep_m0) : "s"(dst), "v"(src) : "memory");
+      }
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      return;
+    }
+    constexpr int TOTAL = MT * 16 * (WS_KR / 8) / WS_THREADS;   // 16-byte chunks per thread
+    constexpr int BATCH = 8;
+#pragma unroll 1
+    for (int b0 = 0; b0 < TOTAL; b0 += BATCH) {
+      uint4 v[BATCH];
+#pragma unroll
+      for (int it = 0; it < BATCH; ++it) {
+        const int ch = tid + (b0 + it) * WS_THREADS;
+        const int row = ch / (WS_KR / 8), kc = (ch % (WS_KR / 8)) * 8;
+        v[it] = make_uint4(0, 0, 0, 0);
+        if (row0 + row < M && kc < kr) v[it] = *reinterpret_cast<const uint4*>(a + (size_t)(row0 + row) * K + k0 + kc);
+      }
+#pragma unroll
+      for (int it = 0; it < BATCH; ++it) {
+        const int ch = tid + (b0 + it) * WS_THREADS;
+        const int row = ch / (WS_KR / 8), kc = (ch % (WS_KR / 8)) * 8;
+        *reinterpret_cast<uint4*>(&As[row * WS_LDK + kc]) = v[it];
+      }
+    }
+  };
   // the first weight fragments are requested before the prologue so that their latency hides behind it
   int grp = ng * NW + wv;
-  if (grp < n_grp) wload(bufA, grp, 0);
-
-  // prologue: activation slice -> LDS (zeros beyond M and beyond K).  All loads of a thread are
-  // issued before the first LDS store so that their latencies overlap.
-  {
-    constexpr int PER = MT * 16 * (WS_KR / 8) / WS_THREADS;     // 16-byte chunks per thread
-    uint4 v[PER];
-#pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int ch = tid + it * WS_THREADS;
-      const int row = ch / (WS_KR / 8), kc = (ch % (WS_KR / 8)) * 8;
-      v[it] = make_uint4(0, 0, 0, 0);
-      if (row0 + row < M && kc < kr) v[it] = *reinterpret_cast<const uint4*>(a + (size_t)(row0 + row) * K + k0 + kc);
-    }
-#pragma unroll
-    for (int it = 0; it < PER; ++it) {
-      const int ch = tid + it * WS_THREADS;
-      const int row = ch / (WS_KR / 8), kc = (ch % (WS_KR / 8)) * 8;
-      *reinterpret_cast<uint4*>(&As[row * WS_LDK + kc]) = v[it];
-    }
-  }
+  if (grp < n_grp) wload(bufA, grp, 0, range0);
+  load_slice(range0);
   __syncthreads();
 
   f32x4 acc[NB][MT];
@@ -221,22 +249,18 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restri
       if ((kk & 1) == 1) __builtin_amdgcn_sched_barrier(0);
     }
   };
-  float* cs = c + (size_t)split * M * N;
-  for (; grp < n_grp; grp += stride) {
+  auto zero_acc = [&]() {
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb)
 #pragma unroll
       for (int i = 0; i < MT; ++i) acc[sb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int t = 0; t < STEPS; ++t) {            // STEPS is even: buffer parity carries over to the next group
-      if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1); else wload(bufB, grp, t + 1); }
-      else if (grp + stride < n_grp) wload(bufA, grp + stride, 0);
-      if (t & 1) mac(bufB, t); else mac(bufA, t);
-    }
-    // acc[sb][i][e] = C[row0 + i*16 + m16][(grp*NB + sb)*16 + 4*g + e]
+  };
+  float* cs = c + (size_t)split * M * N;
+  auto store_acc = [&](int gq) {
+    // acc[sb][i][e] = C[row0 + i*16 + m16][(gq*NB + sb)*16 + 4*g + e]
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb) {
-      const int gn = (grp * NB + sb) * 16 + 4 * g;
+      const int gn = (gq * NB + sb) * 16 + 4 * g;
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const int gm = row0 + i * 16 + m16;
@@ -246,28 +270,100 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restri
         else for (int e = 0; e < 4; ++e) if (gn + e < N) dst[e] = acc[sb][i][e];
       }
     }
+  };
+  if (!MULTI) {
+    for (; grp < n_grp; grp += stride) {
+      zero_acc();
+#pragma unroll
+      for (int t = 0; t < STEPS; ++t) {            // STEPS is even: buffer parity carries over to the next group
+        if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1, range0); else wload(bufB, grp, t + 1, range0); }
+        else if (grp + stride < n_grp) wload(bufA, grp + stride, 0, range0);
+        if (t & 1) mac(bufB, t); else mac(bufA, t);
+      }
+      store_acc(grp);
+    }
+    return;
   }
+  // several K ranges, one strip group per wave: accumulate across the ranges
+  const bool has = grp < n_grp;
+  zero_acc();
+  for (int rr = 0; rr < n_rng; ++rr) {
+    if (rr > 0) {
+      __syncthreads();                              // every wave is done with the previous slice
+      load_slice(range0 + rr);
+      __syncthreads();
+    }
+    if (has) {
+#pragma unroll
+      for (int t = 0; t < STEPS; ++t) {
+        if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1, range0 + rr); else wload(bufB, grp, t + 1, range0 + rr); }
+        else if (rr + 1 < n_rng) wload(bufA, grp, 0, range0 + rr + 1);    // next range's weights fly during the slice exchange
+        if (t & 1) mac(bufB, t); else mac(bufA, t);
+      }
+    }
+  }
+  if (has) store_acc(grp);
 }
 
 bool gemm_use_wstream(int M, int N, int K) { return M <= 256 && N >= 16; }
 
-// splits for the generic entry: the streaming kernel always splits K in ranges of 512
+// Launch shape of the streaming kernel.  One workgroup fits per compute unit (its activation slice fills
+// most of the LDS), so at most 256 workgroups: a second round would pay the prologue again.  Strips per
+// wave task (NB) grow until the NW * n_groups waves of one (slab, row block) cover the strips in one pass
+// if possible.  R K-ranges per workgroup divide the number of slabs (whose bytes rival the weights' for
+// wide outputs) by R; that needs one strip group per wave and is taken only while enough workgroups remain.
+struct WsPlan { int S, R, rbs, n_groups, nb; bool small; };
+#ifndef WS_FORCE_R
+#define WS_FORCE_R 0           // build-time measurement override: ranges per workgroup (0 = policy below)
+#endif
+static const int ws_force_r = WS_FORCE_R;
+static WsPlan ws_plan(int M, int N, int K) {
+  WsPlan p;
+  const int T = (K + WS_KR - 1) / WS_KR, NWv = 4;
+  p.small = M <= 64;
+  p.rbs = p.small ? 1 : (M + 127) / 128;
+  const int n_strips = (N + 15) / 16;
+  auto shape = [&](int R, WsPlan& q) {
+    q = p; q.R = R; q.S = (T + R - 1) / R;
+    int n_groups = 256 / (q.S * q.rbs); if (n_groups < 1) n_groups = 1;
+    const int slots = n_groups * NWv;
+    int nb = (n_strips + slots - 1) / slots;
+    nb = nb >= 3 ? 4 : (nb == 2 ? 2 : 1);
+    const int n_grp = (n_strips + nb - 1) / nb;
+    if (n_groups > (n_grp + NWv - 1) / NWv) n_groups = (n_grp + NWv - 1) / NWv;
+    q.n_groups = n_groups; q.nb = nb;
+    return n_grp <= n_groups * NWv;          // one strip group per wave at most?
+  };
+  WsPlan best; shape(1, best);
+  for (int R = 2; R <= 4; R *= 2) {
+    if (ws_force_r && R != ws_force_r) continue;
+    WsPlan q;
+    if (R > T || !shape(R, q)) continue;
+    const long wgs = (long)q.n_groups * q.rbs * q.S;
+    // measured on the decode shapes: two ranges pay whenever enough workgroups remain; four (no slabs
+    // at all for K = 2048) only for very wide outputs, where the slab bytes rival the weights'
+    if (ws_force_r || (wgs >= 160 && (R == 2 || n_strips >= 1024))) best = q;
+  }
+  return best;
+}
+
+// splits for the generic entry: the streaming kernel writes one slab per workgroup K span
 int gemm_bf16_splits_any(int M, int N, int K) {
-  if (gemm_use_wstream(M, N, K)) return (K + WS_KR - 1) / WS_KR;
+  if (gemm_use_wstream(M, N, K)) return ws_plan(M, N, K).S;
   if (gemm_big_applies(M, N, K)) return 1;
   return gemm_bf16_splits(M, N, K);
 }
 
-template <int MT, int NB, int NW>
-static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K, int S, int rbs,
-                      int n_groups) {
+template <int MT, int NB, int NW, bool MULTI>
+static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K, const WsPlan& p) {
   const size_t lds = (size_t)MT * 16 * WS_LDK * sizeof(bf16_t);
   static bool attr_done = false;     // one flag per template instance
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW, MULTI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  hipLaunchKernelGGL((k_gemm_wstream<MT, NB, NW>), dim3(n_groups, rbs, S), dim3(NW * 64), lds, s, a, w, c, M, N, K, n_groups);
+  hipLaunchKernelGGL((k_gemm_wstream<MT, NB, NW, MULTI>), dim3(p.n_groups, p.rbs, p.S), dim3(NW * 64), lds, s, a, w, c, M, N, K,
+                     p.n_groups, p.R);
 }
 
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
@@ -276,30 +372,12 @@ void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float
     else launch_gemm_bf16(s, a, w, c, M, N, K, gemm_bf16_splits(M, N, K));
     return;
   }
-  const int S = (K + WS_KR - 1) / WS_KR;
-  const bool small = M <= 64;
-  const int rbs = small ? 1 : (M + 127) / 128;
-  const int n_strips = (N + 15) / 16;
   // 4 waves (one per SIMD) or 8: measured equal within noise on the decode shapes; 4 is used
-  const int NWv = 4;
-  // One workgroup fits per compute unit (its activation slice fills most of the LDS), so at most
-  // 256 workgroups: a second round would pay the prologue again.  Strips per wave task (NB) grow
-  // until the NW * n_groups waves of one (K range, row block) cover the strips in one pass if possible.
-  int n_groups = 256 / (S * rbs); if (n_groups < 1) n_groups = 1;
-  const int slots = n_groups * NWv;
-  int nb = (n_strips + slots - 1) / slots;
-  nb = nb >= 3 ? 4 : (nb == 2 ? 2 : 1);
-  if (NWv == 8 && nb == 4) nb = 2;
-  const int n_grp = (n_strips + nb - 1) / nb;
-  if (n_groups > (n_grp + NWv - 1) / NWv) n_groups = (n_grp + NWv - 1) / NWv;
-#define WS_CASE(MT_, NB_, NW_) ws_launch<MT_, NB_, NW_>(s, a, w, c, M, N, K, S, rbs, n_groups)
-  if (NWv == 4) {
-    if (small) { if (nb == 4) WS_CASE(4, 4, 4); else if (nb == 2) WS_CASE(4, 2, 4); else WS_CASE(4, 1, 4); }
-    else       { if (nb == 4) WS_CASE(8, 4, 4); else if (nb == 2) WS_CASE(8, 2, 4); else WS_CASE(8, 1, 4); }
-  } else {
-    if (small) { if (nb == 2) WS_CASE(4, 2, 8); else WS_CASE(4, 1, 8); }
-    else       { if (nb == 2) WS_CASE(8, 2, 8); else WS_CASE(8, 1, 8); }
-  }
+  const WsPlan p = ws_plan(M, N, K);
+#define WS_CASE(MT_, NB_) do { if (p.R > 1) ws_launch<MT_, NB_, 4, true>(s, a, w, c, M, N, K, p); \
+                               else ws_launch<MT_, NB_, 4, false>(s, a, w, c, M, N, K, p); } while (0)
+  if (p.small) { if (p.nb == 4) WS_CASE(4, 4); else if (p.nb == 2) WS_CASE(4, 2); else WS_CASE(4, 1); }
+  else         { if (p.nb == 4) WS_CASE(8, 4); else if (p.nb == 2) WS_CASE(8, 2); else WS_CASE(8, 1); }
 #undef WS_CASE
 }
 
