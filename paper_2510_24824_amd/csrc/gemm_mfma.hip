@@ -150,20 +150,15 @@ constexpr int WS_KR = 512, WS_LDK = WS_KR + 8;
 
 // MT: 16-row activation tiles (4: M <= 64, 8: M <= 128); NB: strips per group; the K range is
 // consumed in steps of WS_KH 32-wide chunks, two register buffers alternating
-template <int MT, int NB, int NW, bool MULTI>   // NW: waves per workgroup; MULTI: several K ranges per workgroup
+template <int MT, int NB, int NW>   // NW: waves per workgroup (4: one per SIMD, 8: two per SIMD)
 __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                              float* __restrict__ c, int M, int N, int K,
-                                                             int n_groups, int R) {
-  // R: consecutive K ranges one workgroup walks through (slab = blockIdx.z holds their sum).  R > 1
-  // needs every wave to own at most one strip group (the launcher guarantees it): the accumulators
-  // then simply stay in registers while the activation slice in LDS is exchanged range by range.
+                                                             int n_groups) {
   extern __shared__ __attribute__((aligned(16))) bf16_t As[];   // [MT*16][WS_LDK]
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int ng = blockIdx.x, rb = blockIdx.y, split = blockIdx.z;
   const int row0 = rb * (MT * 16);
-  const int n_ranges_total = (K + WS_KR - 1) / WS_KR;
-  const int range0 = split * R;
-  const int n_rng = (range0 + R <= n_ranges_total) ? R : n_ranges_total - range0;
+  const int range0 = split;                    // this workgroup's K range (slab = blockIdx.z)
 
   constexpr int WS_THREADS = NW * 64;
   constexpr int WS_KH = (NB * NW >= 16) ? 4 : 8, STEPS = (WS_KR / 32) / WS_KH;
@@ -271,80 +266,41 @@ __global__ __launch_bounds__(NW * 64) void k_gemm_wstream(const bf16_t* __restri
       }
     }
   };
-  if (!MULTI) {
-    for (; grp < n_grp; grp += stride) {
-      zero_acc();
+  for (; grp < n_grp; grp += stride) {
+    zero_acc();
 #pragma unroll
-      for (int t = 0; t < STEPS; ++t) {            // STEPS is even: buffer parity carries over to the next group
-        if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1, range0); else wload(bufB, grp, t + 1, range0); }
-        else if (grp + stride < n_grp) wload(bufA, grp + stride, 0, range0);
-        if (t & 1) mac(bufB, t); else mac(bufA, t);
-      }
-      store_acc(grp);
+    for (int t = 0; t < STEPS; ++t) {            // STEPS is even: buffer parity carries over to the next group
+      if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1, range0); else wload(bufB, grp, t + 1, range0); }
+      else if (grp + stride < n_grp) wload(bufA, grp + stride, 0, range0);
+      if (t & 1) mac(bufB, t); else mac(bufA, t);
     }
-    return;
+    store_acc(grp);
   }
-  // several K ranges, one strip group per wave: accumulate across the ranges
-  const bool has = grp < n_grp;
-  zero_acc();
-  for (int rr = 0; rr < n_rng; ++rr) {
-    if (rr > 0) {
-      __syncthreads();                              // every wave is done with the previous slice
-      load_slice(range0 + rr);
-      __syncthreads();
-    }
-    if (has) {
-#pragma unroll
-      for (int t = 0; t < STEPS; ++t) {
-        if (t + 1 < STEPS) { if (t & 1) wload(bufA, grp, t + 1, range0 + rr); else wload(bufB, grp, t + 1, range0 + rr); }
-        else if (rr + 1 < n_rng) wload(bufA, grp, 0, range0 + rr + 1);    // next range's weights fly during the slice exchange
-        if (t & 1) mac(bufB, t); else mac(bufA, t);
-      }
-    }
-  }
-  if (has) store_acc(grp);
 }
 
 bool gemm_use_wstream(int M, int N, int K) { return M <= 256 && N >= 16; }
 
 // Launch shape of the streaming kernel.  One workgroup fits per compute unit (its activation slice fills
 // most of the LDS), so at most 256 workgroups: a second round would pay the prologue again.  Strips per
-// wave task (NB) grow until the NW * n_groups waves of one (slab, row block) cover the strips in one pass
-// if possible.  R K-ranges per workgroup divide the number of slabs (whose bytes rival the weights' for
-// wide outputs) by R; that needs one strip group per wave and is taken only while enough workgroups remain.
-struct WsPlan { int S, R, rbs, n_groups, nb; bool small; };
-#ifndef WS_FORCE_R
-#define WS_FORCE_R 0           // build-time measurement override: ranges per workgroup (0 = policy below)
-#endif
-static const int ws_force_r = WS_FORCE_R;
+// wave task (NB) grow until the NW * n_groups waves of one (K range, row block) cover the strips in one pass
+// if possible.  (Letting a workgroup walk 2 or 4 K ranges with the accumulators kept in registers halves
+// or removes the split-K slabs; measured inside the decode step it was slower than one range per workgroup.)
+struct WsPlan { int S, rbs, n_groups, nb; bool small; };
 static WsPlan ws_plan(int M, int N, int K) {
   WsPlan p;
-  const int T = (K + WS_KR - 1) / WS_KR, NWv = 4;
+  const int NWv = 4;
+  p.S = (K + WS_KR - 1) / WS_KR;
   p.small = M <= 64;
   p.rbs = p.small ? 1 : (M + 127) / 128;
   const int n_strips = (N + 15) / 16;
-  auto shape = [&](int R, WsPlan& q) {
-    q = p; q.R = R; q.S = (T + R - 1) / R;
-    int n_groups = 256 / (q.S * q.rbs); if (n_groups < 1) n_groups = 1;
-    const int slots = n_groups * NWv;
-    int nb = (n_strips + slots - 1) / slots;
-    nb = nb >= 3 ? 4 : (nb == 2 ? 2 : 1);
-    const int n_grp = (n_strips + nb - 1) / nb;
-    if (n_groups > (n_grp + NWv - 1) / NWv) n_groups = (n_grp + NWv - 1) / NWv;
-    q.n_groups = n_groups; q.nb = nb;
-    return n_grp <= n_groups * NWv;          // one strip group per wave at most?
-  };
-  WsPlan best; shape(1, best);
-  for (int R = 2; R <= 4; R *= 2) {
-    if (ws_force_r && R != ws_force_r) continue;
-    WsPlan q;
-    if (R > T || !shape(R, q)) continue;
-    const long wgs = (long)q.n_groups * q.rbs * q.S;
-    // measured on the decode shapes: two ranges pay whenever enough workgroups remain; four (no slabs
-    // at all for K = 2048) only for very wide outputs, where the slab bytes rival the weights'
-    if (ws_force_r || (wgs >= 160 && (R == 2 || n_strips >= 1024))) best = q;
-  }
-  return best;
+  int n_groups = 256 / (p.S * p.rbs); if (n_groups < 1) n_groups = 1;
+  const int slots = n_groups * NWv;
+  int nb = (n_strips + slots - 1) / slots;
+  nb = nb >= 3 ? 4 : (nb == 2 ? 2 : 1);
+  const int n_grp = (n_strips + nb - 1) / nb;
+  if (n_groups > (n_grp + NWv - 1) / NWv) n_groups = (n_grp + NWv - 1) / NWv;
+  p.n_groups = n_groups; p.nb = nb;
+  return p;
 }
 
 // splits for the generic entry: the streaming kernel writes one slab per workgroup K span
@@ -354,16 +310,16 @@ int gemm_bf16_splits_any(int M, int N, int K) {
   return gemm_bf16_splits(M, N, K);
 }
 
-template <int MT, int NB, int NW, bool MULTI>
+template <int MT, int NB, int NW>
 static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K, const WsPlan& p) {
   const size_t lds = (size_t)MT * 16 * WS_LDK * sizeof(bf16_t);
   static bool attr_done = false;     // one flag per template instance
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW, MULTI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  hipLaunchKernelGGL((k_gemm_wstream<MT, NB, NW, MULTI>), dim3(p.n_groups, p.rbs, p.S), dim3(NW * 64), lds, s, a, w, c, M, N, K,
-                     p.n_groups, p.R);
+  hipLaunchKernelGGL((k_gemm_wstream<MT, NB, NW>), dim3(p.n_groups, p.rbs, p.S), dim3(NW * 64), lds, s, a, w, c, M, N, K,
+                     p.n_groups);
 }
 
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
@@ -374,8 +330,7 @@ void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float
   }
   // 4 waves (one per SIMD) or 8: measured equal within noise on the decode shapes; 4 is used
   const WsPlan p = ws_plan(M, N, K);
-#define WS_CASE(MT_, NB_) do { if (p.R > 1) ws_launch<MT_, NB_, 4, true>(s, a, w, c, M, N, K, p); \
-                               else ws_launch<MT_, NB_, 4, false>(s, a, w, c, M, N, K, p); } while (0)
+#define WS_CASE(MT_, NB_) ws_launch<MT_, NB_, 4>(s, a, w, c, M, N, K, p)
   if (p.small) { if (p.nb == 4) WS_CASE(4, 4); else if (p.nb == 2) WS_CASE(4, 2); else WS_CASE(4, 1); }
   else         { if (p.nb == 4) WS_CASE(8, 4); else if (p.nb == 2) WS_CASE(8, 2); else WS_CASE(8, 1); }
 #undef WS_CASE
