@@ -414,6 +414,9 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
     if (c.dtype == PLT_BF16 && gemm_big_applies(R, 2 * F, d)) {      // many rows: SwiGLU fused into the GEMM epilogue
       launch_gemm_big_swiglu(s, (const bf16_t*)wk.a, (const bf16_t*)w.wgu, (bf16_t*)wk.act, R, F, d);
+    } else if (c.dtype == PLT_BF16 && gemm_swiglu_rows_applies(R, F, d)) {   // decode rows: likewise, one tile of rows
+      ProfScope prof(m, PLT_PROF_GEMM, dec);
+      launch_gemm_swiglu_rows(s, (const bf16_t*)wk.a, (const bf16_t*)w.wgu, (bf16_t*)wk.act, R, F, d);
     } else {
       S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
       launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);

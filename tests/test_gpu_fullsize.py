@@ -100,3 +100,31 @@ def test_decode_step_L4_w128_ctx8192_sampled():
     _, lg_solo = kv1.decode_step(tok[b:b + 1].clone())
     assert float(torch.max(torch.abs(lg_solo[0] - lg1[b]))) <= 1e-2
     kv1.close(); kv.close(); model.close()
+
+
+def test_decode_step_160_rows_sampled():
+    """Batch 40 x L = 4 = 160 rows per step: the row count (129..256) at which the gate/up projection
+    runs as one fused-SwiGLU tile per 32 output columns; short context so that the oracle is quick."""
+    shape = synth.PLT_1P3B
+    Bn, N, L, w = 40, 300, 4, 64
+    pos = N - 1
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=L, window=w)
+    blob = bench.fill_weights_on_device(B, cfg, bench.SEED)
+    model = B.Model(cfg, blob)
+    kv = B.KV(model, Bn, N)
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    prompt = torch.randint(0, shape.vocab, (Bn, pos), generator=g, device="cuda", dtype=torch.int32)
+    nxt, _ = kv.prefill(prompt, want_logits=False)
+    b = 23
+    exports = [kv.export(b, m, pos) for m in range(shape.n_layers)]
+    carry = kv.get_carry()
+    tok = nxt.clone()
+    n1, lg1 = kv.decode_step(tok)
+    hidden = kv.get_hidden()
+    wh = bench.weights_to_host(B, cfg, blob)
+    o_next, o_lg, o_hid = oracle_step(shape, cfg, wh, exports, carry[b], int(tok[b].item()), pos)
+    err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
+    rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
+    print(f"logits max-abs {err:.3e}; hidden max rel {rel_h:.3e}")
+    assert err <= 2e-2 and rel_h <= 2e-2, (err, rel_h)
+    kv.close(); model.close()
