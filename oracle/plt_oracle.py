@@ -14,6 +14,7 @@ Every function cites the passage of the paper (arxiv 2510.24824) it follows:
   Eq. (2)   sigmoid gate merge                  -> gate_merge
   Sec. 2.2.2  first-loop KV sharing, window of the most recent w entries -> RingKV
   Table 1 rows 3 and 4 (ablations: CLP with per-loop KV; CLP + KV share without the window) -> variant=
+  Appendix, "MoE Models Recipe" (SwiGLU experts, k of E experts per token)              -> moe_route / moe_ffn
 
 Where the paper is silent the following readings are taken (each also listed in the
 design notes of the repository):
@@ -28,6 +29,11 @@ design notes of the repository):
     one scalar per head; g multiplies the LOCAL branch (Eq. 2)
   * one weight set serves every loop; query head h reads kv head h // (H_q / H_kv)
   * argmax ties resolve to the lowest index
+  * mixture-of-experts feed-forward (n_experts > 0; the paper names only "SwiGLU experts" and "8 in 64" and
+    builds on OLMoE, whose router is the one taken here): router logits r = W_r b on the normed
+    row b, p = softmax(r) over all E experts, the k experts with the largest p are evaluated
+    (equal p: lowest index first) and their outputs are summed with weights p_e as they are --
+    the k selected probabilities are NOT renormalised to sum to one; no shared expert, no bias
 
 Precision: float64 everywhere.  With kv_bf16=True the K and V entries are rounded to
 bfloat16 when they are stored (the device keeps its caches in bfloat16), nothing else is.
@@ -44,7 +50,8 @@ import math
 import numpy as np
 
 __all__ = ["OracleShape", "PLTOracle", "rmsnorm", "rope", "softmax_attend", "gate_merge",
-           "gated_attention_row", "decode_attention", "kv_cache_bytes", "bf16_round", "e4m3_round"]
+           "gated_attention_row", "decode_attention", "kv_cache_bytes", "bf16_round", "e4m3_round",
+           "swiglu_ffn", "moe_route", "moe_ffn"]
 
 
 # ----------------------------------------------------------------------------- helpers
@@ -75,13 +82,17 @@ def e4m3_round(x: np.ndarray) -> np.ndarray:
 
 class OracleShape:
     def __init__(self, n_layers, d_model, n_heads, n_kv_heads, head_dim, ffn_hidden, vocab,
-                 n_loops, window, rope_theta=10000.0, norm_eps=1e-5, tie_embeddings=True):
+                 n_loops, window, rope_theta=10000.0, norm_eps=1e-5, tie_embeddings=True,
+                 n_experts=0, top_k=0):
         self.n_layers, self.d_model = int(n_layers), int(d_model)
         self.n_heads, self.n_kv_heads, self.head_dim = int(n_heads), int(n_kv_heads), int(head_dim)
         self.ffn_hidden, self.vocab = int(ffn_hidden), int(vocab)
         self.n_loops, self.window = int(n_loops), int(window)
         self.rope_theta, self.norm_eps = float(rope_theta), float(norm_eps)
         self.tie_embeddings = bool(tie_embeddings)
+        # n_experts = 0: dense SwiGLU feed-forward; > 0: ffn_hidden is the hidden size of each expert
+        self.n_experts, self.top_k = int(n_experts), int(top_k)
+        assert self.n_experts == 0 or 1 <= self.top_k <= self.n_experts
         assert self.n_heads % self.n_kv_heads == 0 and self.head_dim % 2 == 0
 
 
@@ -158,6 +169,42 @@ def decode_attention(q, k_share, v_share, k_ring, v_ring, z, n_ctx=None, n_ring=
                                                  k_ring[b, l - 1, kh, :nr], v_ring[b, l - 1, kh, :nr],
                                                  z[b, l - 1, h])
     return y
+
+
+def swiglu_ffn(b, w_gate, w_up, w_down) -> np.ndarray:
+    """W_down (silu(W_gate b) * (W_up b)) for one row b[d]; matrices are [out, in]."""
+    b = np.asarray(b, np.float64)
+    gte = np.asarray(w_gate, np.float64) @ b
+    up = np.asarray(w_up, np.float64) @ b
+    return np.asarray(w_down, np.float64) @ (gte / (1.0 + np.exp(-gte)) * up)
+
+
+def moe_route(b, router, top_k):
+    """Router of the mixture-of-experts feed-forward for one row b[d], router [E, d].
+
+    p = softmax(router b) over all E experts; returns (ids, p[ids], margin): the top_k experts
+    in order of decreasing p (equal p: lowest index first), their probabilities (not
+    renormalised) and the logit gap between the last selected and the best rejected expert
+    (inf when top_k == E) -- tests use the gap to tell decisions that rounding could flip."""
+    r = np.asarray(router, np.float64) @ np.asarray(b, np.float64)
+    e = np.exp(r - np.max(r))
+    p = e / np.sum(e)
+    order = np.argsort(-p, kind="stable")
+    ids = order[:top_k]
+    margin = float(r[order[top_k - 1]] - r[order[top_k]]) if top_k < len(r) else math.inf
+    return ids, p[ids], margin
+
+
+def moe_ffn(b, W, top_k, margins=None) -> np.ndarray:
+    """sum over the selected experts e of p_e * SwiGLU_e(b) [appendix, MoE models recipe; router
+    reading in the header].  W: "router" [E, d], "w_gate" / "w_up" [E, F, d], "w_down" [E, d, F]."""
+    ids, p, margin = moe_route(b, W["router"], top_k)
+    if margins is not None:
+        margins.append(margin)
+    out = np.zeros(np.asarray(W["w_down"]).shape[1], np.float64)
+    for e, pe in zip(ids, p):
+        out += pe * swiglu_ffn(b, W["w_gate"][e], W["w_up"][e], W["w_down"][e])
+    return out
 
 
 def kv_cache_bytes(shape: OracleShape, n_ctx: int, elem_bytes: int, n_loops: int | None = None,
@@ -266,6 +313,7 @@ class PLTOracle:
         self.kv_bf16, self.kv_fp8 = kv_bf16, kv_fp8
         self._store = bf16_round if kv_bf16 else e4m3_round if kv_fp8 else (lambda a: np.asarray(a, np.float64))
         self._head = weights["emb"] if shape.tie_embeddings else weights["head"]
+        self.route_margins = []     # logit gap of every routing decision taken (MoE models)
 
     # -- block f: one pass of the whole layer stack for one row at position p in loop l (1-based)
     def f(self, x, p, l, kv, global_cache_id=1, plain=False):
@@ -313,9 +361,10 @@ class PLTOracle:
                                                Kl[:, h // G], Vl[:, h // G], z[h])  # Alg. 3 l.2-5
             x = x + np.asarray(W["wo"], np.float64) @ y.reshape(Hq * D)         # Alg. 3 l.6
             b = rmsnorm(x, W["norm2"], s.norm_eps)
-            gte = np.asarray(W["w_gate"], np.float64) @ b
-            up = np.asarray(W["w_up"], np.float64) @ b
-            x = x + np.asarray(W["w_down"], np.float64) @ (gte / (1.0 + np.exp(-gte)) * up)
+            if s.n_experts > 0:
+                x = x + moe_ffn(b, W, s.top_k, self.route_margins)
+            else:
+                x = x + swiglu_ffn(b, W["w_gate"], W["w_up"], W["w_down"])
         return x
 
     def embed(self, t):

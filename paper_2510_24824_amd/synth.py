@@ -29,6 +29,8 @@ class ModelShape:
     rope_theta: float = 10000.0
     norm_eps: float = 1e-5
     tie_embeddings: bool = True
+    n_experts: int = 0     # E; 0 = dense feed-forward, > 0: ffn_hidden is each expert's hidden size
+    top_k: int = 0         # experts evaluated per row
 
 
 TINY = ModelShape(n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, head_dim=64,
@@ -41,6 +43,15 @@ PLT_1P3B = ModelShape(n_layers=24, d_model=2048, n_heads=16, n_kv_heads=16, head
 # 16384, grouped-query attention with 32 query / 8 key-value heads, tied head (its extra norms are not modelled)
 PLT_DENSE_GQA = ModelShape(n_layers=16, d_model=2048, n_heads=32, n_kv_heads=8, head_dim=64,
                            ffn_hidden=16384, vocab=50304, n_loops=2, window=64)
+
+
+# the paper's open-source mixture-of-experts recipe (appendix, "MoE Models Recipe"): 16 layers, hidden 2048,
+# 16 attention heads, SwiGLU experts, 8 of 64 per token; the expert hidden size is not printed -- 1024 (the
+# value of the OLMoE model the recipe builds on) gives the quoted ~1B active / ~7B total parameters
+PLT_MOE_1B7B = ModelShape(n_layers=16, d_model=2048, n_heads=16, n_kv_heads=16, head_dim=128,
+                          ffn_hidden=1024, vocab=50304, n_loops=2, window=64, n_experts=64, top_k=8)
+TINY_MOE = ModelShape(n_layers=2, d_model=256, n_heads=4, n_kv_heads=4, head_dim=64,
+                      ffn_hidden=128, vocab=1024, n_loops=2, window=16, n_experts=8, top_k=2)
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:
@@ -106,22 +117,26 @@ def token_ids(shape, vocab: int, seed: int, stream: int = 1000) -> np.ndarray:
 
 
 def make_weights(shape: ModelShape, seed: int, bf16: bool, std: float = 0.02,
-                 gate_std: float | None = None) -> dict:
+                 gate_std: float | None = None, router_std: float | None = None) -> dict:
     """Weights N(0, std); norm gains 1; gate bias 0.  Matrices are [out_features, in_features].
 
     Returns {"emb", "norm_f", "head" (absent when tied), "layers": [ {...} ]}, float32 arrays
-    whose values are bf16-representable when bf16=True.
+    whose values are bf16-representable when bf16=True.  Mixture-of-experts shapes: "router" [E, d] and
+    "w_gate" / "w_up" [E, F, d], "w_down" [E, d, F].
     """
     s = shape
     hq, hkv, dh, d, f = s.n_heads, s.n_kv_heads, s.head_dim, s.d_model, s.ffn_hidden
     gstd = std if gate_std is None else gate_std
+    rstd = std if router_std is None else router_std
+    E = shape.n_experts
+    ex = (E,) if E > 0 else ()       # expert matrices carry a leading expert axis
     w = {"emb": normal((s.vocab, d), seed, 1, std, bf16),
          "norm_f": np.ones(d, np.float32), "layers": []}
     if not s.tie_embeddings:
         w["head"] = normal((s.vocab, d), seed, 2, std, bf16)
     for m in range(s.n_layers):
         base = 100 + 16 * m
-        w["layers"].append({
+        layer = {
             "norm1": np.ones(d, np.float32),
             "wq": normal((hq * dh, d), seed, base + 0, std, bf16),
             "wk": normal((hkv * dh, d), seed, base + 1, std, bf16),
@@ -130,10 +145,13 @@ def make_weights(shape: ModelShape, seed: int, bf16: bool, std: float = 0.02,
             "gate_b": np.zeros(hq, np.float32),
             "wo": normal((d, hq * dh), seed, base + 4, std, bf16),
             "norm2": np.ones(d, np.float32),
-            "w_gate": normal((f, d), seed, base + 5, std, bf16),
-            "w_up": normal((f, d), seed, base + 6, std, bf16),
-            "w_down": normal((d, f), seed, base + 7, std, bf16),
-        })
+            "w_gate": normal(ex + (f, d), seed, base + 5, std, bf16),
+            "w_up": normal(ex + (f, d), seed, base + 6, std, bf16),
+            "w_down": normal(ex + (d, f), seed, base + 7, std, bf16),
+        }
+        if E > 0:
+            layer["router"] = normal((E, d), seed, base + 8, rstd, bf16)
+        w["layers"].append(layer)
     return w
 
 

@@ -68,8 +68,23 @@ def decoder_stack(X, weights, shape, shared_kv=None, window=None, return_kv=Fals
             y = g * own + (1 - g) * glob
         x = x + F.linear(y.transpose(0, 1).reshape(n, Hq * D), t64(W["wo"]))
         b = F.rms_norm(x, (s.d_model,), t64(W["norm2"]), s.norm_eps)
-        x = x + F.linear(F.silu(F.linear(b, t64(W["w_gate"]))) * F.linear(b, t64(W["w_up"])), t64(W["w_down"]))
+        if getattr(s, "n_experts", 0) > 0:
+            x = x + moe_ffn_dense(b, W, s.top_k)
+        else:
+            x = x + F.linear(F.silu(F.linear(b, t64(W["w_gate"]))) * F.linear(b, t64(W["w_up"])), t64(W["w_down"]))
     return (x, kv_out) if return_kv else x
+
+
+def moe_ffn_dense(b, W, top_k):
+    """Mixture-of-experts feed-forward, token-parallel and dense: every expert is evaluated on every
+    row b [n, d] (batched matmuls), and a 0/1 mask built from torch.topk of the softmax probabilities
+    keeps the top_k experts of each row, weighted by their probabilities as they are."""
+    prob = torch.softmax(F.linear(b, t64(W["router"])), dim=-1)                    # [n, E]
+    keep = torch.zeros_like(prob).scatter_(1, torch.topk(prob, top_k, dim=-1).indices, 1.0)
+    gate = torch.einsum("efd,nd->nef", t64(W["w_gate"]), b)
+    up = torch.einsum("efd,nd->nef", t64(W["w_up"]), b)
+    out = torch.einsum("edf,nef->ned", t64(W["w_down"]), F.silu(gate) * up)        # [n, E, d]
+    return torch.einsum("ne,ned->nd", prob * keep, out)
 
 
 def head_logits(H, weights, shape):
