@@ -65,6 +65,8 @@ def fill_weights_on_device(B, cfg, seed):
         normal(m, B.PLT_W_GATE_W, torch.float32)
         normal(m, B.PLT_W_WO, wd)
         view(m, B.PLT_W_NORM2, torch.float32)[0].fill_(1.0)
+        if cfg.n_experts > 0:
+            normal(m, B.PLT_W_ROUTER, wd)
         normal(m, B.PLT_W_WGU, wd)
         normal(m, B.PLT_W_WDOWN, wd)
     view(0, B.PLT_W_NORM_F, torch.float32)[0].fill_(1.0)
@@ -87,8 +89,18 @@ def weights_to_host(B, cfg, blob):
     w = {"emb": get(0, B.PLT_W_EMB, wd, (cfg.vocab, d)), "norm_f": get(0, B.PLT_W_NORM_F, torch.float32, (d,)), "layers": []}
     if not cfg.tie_embeddings:
         w["head"] = get(0, B.PLT_W_HEAD, wd, (cfg.vocab, d))
+    E = cfg.n_experts
     for m in range(cfg.n_layers):
         qkv = get(m, B.PLT_W_WQKV, wd, ((Hq + 2 * Hkv) * D, d))
+        if E > 0:
+            gu = get(m, B.PLT_W_WGU, wd, (E, 2 * F, d))
+            w["layers"].append({
+                "norm1": get(m, B.PLT_W_NORM1, torch.float32, (d,)), "wq": qkv[:Hq * D], "wk": qkv[Hq * D:(Hq + Hkv) * D],
+                "wv": qkv[(Hq + Hkv) * D:], "gate_w": get(m, B.PLT_W_GATE_W, torch.float32, (Hq, D)),
+                "gate_b": get(m, B.PLT_W_GATE_B, torch.float32, (Hq,)), "wo": get(m, B.PLT_W_WO, wd, (d, Hq * D)),
+                "norm2": get(m, B.PLT_W_NORM2, torch.float32, (d,)), "router": get(m, B.PLT_W_ROUTER, wd, (E, d)),
+                "w_gate": gu[:, :F], "w_up": gu[:, F:], "w_down": get(m, B.PLT_W_WDOWN, wd, (E, d, F))})
+            continue
         gu = get(m, B.PLT_W_WGU, wd, (2 * F, d))
         w["layers"].append({
             "norm1": get(m, B.PLT_W_NORM1, torch.float32, (d,)), "wq": qkv[:Hq * D], "wk": qkv[Hq * D:(Hq + Hkv) * D],

@@ -26,6 +26,11 @@
  * last w keys/values, merged per head by g = sigmoid(<q_h, wg_h> + bg_h):
  * y = g * y_local + (1 - g) * y_global [Alg. 3; Eq. 2].  While decoding, the L loop stages
  * of one position form one micro-batch of L rows and run as a single pass [Alg. 1].
+ * With n_experts > 0 the feed-forward of every layer is a mixture of SwiGLU experts [appendix,
+ * "MoE Models Recipe": k of E experts per token].  The paper does not print the router; the reading
+ * taken is: logits r = W_r b on the normed row b, p = softmax(r) over all E experts, the k experts
+ * with the largest logits are evaluated (equal logits: lowest index first) and their outputs are
+ * summed with weights p_e as they are (not renormalised).
  */
 #ifndef PLT_H_
 #define PLT_H_
@@ -77,6 +82,9 @@ typedef struct plt_config {
   float norm_eps;         /* RMSNorm epsilon                                                */
   int32_t kv_dtype;       /* 0: caches hold the model dtype; PLT_FP8_E4M3: caches hold e4m3
                              (needs dtype == PLT_BF16; halves the KV bytes of Table 1)      */
+  int32_t n_experts;      /* E: 0 = dense SwiGLU feed-forward; 1..256 = mixture of E SwiGLU
+                             experts of hidden size ffn_hidden each [appendix, MoE recipe]  */
+  int32_t top_k;          /* experts evaluated per row (1..min(E, 32)); ignored when E == 0 */
 } plt_config;
 
 typedef struct plt_model plt_model; /* opaque */
@@ -87,9 +95,12 @@ typedef struct plt_kv plt_kv;       /* opaque */
  *   K heads, then all V heads), GATE_W [Hq, D], GATE_B [Hq], WO [d, Hq*D], NORM2 [d],
  *   WGU [2F, d] (rows: W_gate then W_up), WDOWN [d, F]; then NORM_F [d]; then HEAD [vocab, d]
  *   (absent when tie_embeddings).  Norm gains, gate weight and gate bias are always float;
- *   the other tensors have the model dtype.  Every tensor starts at a multiple of 256 bytes. */
+ *   the other tensors have the model dtype.  Every tensor starts at a multiple of 256 bytes.
+ *   Mixture-of-experts models (n_experts = E > 0): ROUTER [E, d] follows NORM2, and the expert
+ *   matrices carry a leading expert axis: WGU [E, 2F, d] (per expert: its W_gate rows, then its
+ *   W_up rows), WDOWN [E, d, F]. */
 enum { PLT_W_EMB = 0, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO,
-       PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD };
+       PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER };
 
 /* Total size of the weight blob in bytes (0 if the configuration is invalid). */
 size_t plt_weights_bytes(const plt_config* cfg);
@@ -212,6 +223,20 @@ int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* dev_a,
              const void* dev_w, float* dev_c, void* dev_scratch, size_t scratch_bytes,
              void* hip_stream);
 size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+
+/* Kernel-only mixture-of-experts feed-forward [appendix, "MoE Models Recipe"; router reading in the
+ * header comment]: for R rows a [R, d] (already normed), router [E, d], wgu [E, 2F, d], wdown [E, d, F]
+ * (all of type `dtype`, device memory) writes
+ *   y [R, d] float       = sum over the k selected experts e of p_e * W_down^e (silu(W_gate^e a) * W_up^e a)
+ *   sel_e [R, k] int32   the selected experts in order of decreasing probability
+ *   sel_p [R, k] float   their softmax probabilities
+ * PLT_BF16 needs d % 64 == 0 and F % 64 == 0; E <= 256, k <= min(E, 32).  dev_scratch: device buffer of
+ * plt_moe_scratch_bytes(...) bytes (index lists, the experts' hidden activations, k output slabs). */
+size_t plt_moe_scratch_bytes(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k);
+int plt_moe_ffn(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k, const void* dev_a,
+                const void* dev_router, const void* dev_wgu, const void* dev_wdown, float* dev_y,
+                int32_t* dev_sel_e, float* dev_sel_p, void* dev_scratch, size_t scratch_bytes,
+                void* hip_stream);
 
 /* Plain device-to-device copy kernel (16 bytes per lane): the known-size reference for HBM
  * traffic counters and a practical bandwidth ceiling.  nbytes and both pointers must be

@@ -17,7 +17,7 @@ PLT_F32, PLT_BF16 = 0, 1
 PLT_FP8_E4M3 = 2      # cache-only element type (e4m3 bytes); q / y / weights stay bf16
 PLT_MODE_CLP, PLT_MODE_VANILLA_LOOP, PLT_MODE_CLP_SHARE_ONLY, PLT_MODE_CLP_OWN_KV = 0, 2, 3, 4
 (PLT_W_EMB, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO, PLT_W_NORM2, PLT_W_WGU,
- PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD) = range(11)
+ PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER) = range(12)
 STATUS = {0: "PLT_OK", -1: "PLT_EINVAL", -2: "PLT_ENOMEM", -3: "PLT_ECTXFULL", -4: "PLT_EHIP", -5: "PLT_ESTATE"}
 
 
@@ -31,7 +31,8 @@ class plt_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim",
                                          "ffn_hidden", "vocab", "n_loops", "window", "dtype", "mode",
                                          "tie_embeddings")] + [("rope_theta", C.c_float), ("norm_eps", C.c_float),
-                                                               ("kv_dtype", C.c_int32)]
+                                                               ("kv_dtype", C.c_int32), ("n_experts", C.c_int32),
+                                                               ("top_k", C.c_int32)]
 
 
 _P, _I, _Z = C.c_void_p, C.c_int32, C.c_size_t
@@ -64,6 +65,8 @@ _SIGS = {
     "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
     "plt_gemm_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_moe_scratch_bytes": (_Z, [_I] * 6),
+    "plt_moe_ffn": (C.c_int, [_I] * 6 + [_P] * 8 + [_Z, _P]),
     "plt_stream_copy": (C.c_int, [_P, _P, _Z, _P]),
     "plt_stream_read": (C.c_int, [_P, _Z, _P, _Z, _P]),
     "plt_profile_enable": (C.c_int, [_P, _I]),
@@ -99,7 +102,8 @@ def make_config(shape, dtype=PLT_BF16, mode=PLT_MODE_CLP, n_loops=None, window=N
     return plt_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                       shape.ffn_hidden, shape.vocab, shape.n_loops if n_loops is None else n_loops,
                       shape.window if window is None else window, dtype, mode,
-                      1 if shape.tie_embeddings else 0, shape.rope_theta, shape.norm_eps, kv_dtype)
+                      1 if shape.tie_embeddings else 0, shape.rope_theta, shape.norm_eps, kv_dtype,
+                      getattr(shape, "n_experts", 0), getattr(shape, "top_k", 0))
 
 
 def _stream():
@@ -143,7 +147,11 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
         put(m, PLT_W_GATE_B, lw["gate_b"], False)
         put(m, PLT_W_WO, lw["wo"], True)
         put(m, PLT_W_NORM2, lw["norm2"], False)
-        put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=0), True)
+        if cfg.n_experts > 0:       # expert axis first; per expert its gate rows, then its up rows
+            put(m, PLT_W_ROUTER, lw["router"], True)
+            put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=1), True)
+        else:
+            put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=0), True)
         put(m, PLT_W_WDOWN, lw["w_down"], True)
     put(0, PLT_W_NORM_F, weights["norm_f"], False)
     if not cfg.tie_embeddings:
@@ -351,3 +359,25 @@ def gemm(dtype, a, w):
     scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
     _check(lib().plt_gemm(dtype, M, N, K, _ptr(a.contiguous()), _ptr(w.contiguous()), _ptr(c), _ptr(scratch), nb, _stream()))
     return c
+
+
+def moe_ffn(dtype, a, router, w_gate, w_up, w_down, top_k):
+    """Kernel-only mixture-of-experts feed-forward.  a [R, d], router [E, d], w_gate / w_up [E, F, d],
+    w_down [E, d, F]: float32 numpy arrays exactly representable in the storage type.  Returns
+    (y [R, d] float32, sel_e [R, k] int32, sel_p [R, k] float32) as numpy arrays."""
+    import torch
+    R, d = a.shape
+    E, F = w_gate.shape[0], w_gate.shape[1]
+    da, dr, dd = _to_dev(a, dtype), _to_dev(router, dtype), _to_dev(w_down, dtype)
+    dgu = _to_dev(np.concatenate([w_gate, w_up], axis=1), dtype)
+    y = torch.empty(R, d, dtype=torch.float32, device="cuda")
+    sel_e = torch.empty(R, top_k, dtype=torch.int32, device="cuda")
+    sel_p = torch.empty(R, top_k, dtype=torch.float32, device="cuda")
+    nb = lib().plt_moe_scratch_bytes(dtype, R, d, F, E, top_k)
+    if nb == 0:
+        raise PltError(-1, lib().plt_last_error().decode())
+    scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    _check(lib().plt_moe_ffn(dtype, R, d, F, E, top_k, _ptr(da), _ptr(dr), _ptr(dgu), _ptr(dd), _ptr(y), _ptr(sel_e),
+                             _ptr(sel_p), _ptr(scratch), nb, _stream()))
+    torch.cuda.synchronize()
+    return y.cpu().numpy(), sel_e.cpu().numpy(), sel_p.cpu().numpy()

@@ -27,6 +27,7 @@ extern "C" const char* plt_last_error(void) { return g_err; }
 struct LayerW {
   const float* norm1; const void* wqkv; const float* gate_w; const float* gate_b;
   const void* wo; const float* norm2; const void* wgu; const void* wdown;
+  const void* router;   // mixture-of-experts models only
 };
 struct ProfRec { hipEvent_t a, b; int klass; };
 struct plt_model {
@@ -53,6 +54,7 @@ struct plt_kv {
   // per-step activation scratch (device, library-owned)
   float* x; void* a; float* gout; size_t gout_elems; void* q; float* z; void* y; void* act;
   float* carry; int32_t* pos_dev; void* attn_scratch; size_t attn_scratch_bytes;
+  void* moe_idx;       // mixture-of-experts models: routing lists of one pass (moe_index_bytes)
   float* arg_v; int* arg_i;   // argmax chunk winners
 };
 
@@ -74,6 +76,10 @@ static bool cfg_valid(const plt_config* c, const char** why) {
   if (!(c->rope_theta > 0.f) || !(c->norm_eps >= 0.f)) { *why = "bad rope_theta / norm_eps"; return false; }
   if (c->kv_dtype != 0 && c->kv_dtype != PLT_FP8_E4M3) { *why = "unknown kv_dtype"; return false; }
   if (c->kv_dtype == PLT_FP8_E4M3 && c->dtype != PLT_BF16) { *why = "e4m3 caches need dtype PLT_BF16"; return false; }
+  if (c->n_experts < 0 || c->n_experts > 256) { *why = "n_experts must be in 0..256"; return false; }
+  if (c->n_experts > 0 && (c->top_k < 1 || c->top_k > c->n_experts || c->top_k > 32)) {
+    *why = "top_k must be in 1..min(n_experts, 32)"; return false;
+  }
   return true;
 }
 
@@ -83,7 +89,7 @@ static size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static size_t blob_walk(const plt_config* c, int want_layer, int want_which, size_t* off, size_t* nelem) {
   const size_t es = c->dtype == PLT_BF16 ? 2 : 4;
   const size_t d = c->d_model, Hq = c->n_heads, Hkv = c->n_kv_heads, D = c->head_dim, F = c->ffn_hidden,
-               V = c->vocab;
+               V = c->vocab, E = c->n_experts, Ex = E > 0 ? E : 1;
   size_t cur = 0;
   auto put = [&](int layer, int which, size_t n, size_t esz) {
     cur = align256(cur);
@@ -98,8 +104,9 @@ static size_t blob_walk(const plt_config* c, int want_layer, int want_which, siz
     put(m, PLT_W_GATE_B, Hq, 4);
     put(m, PLT_W_WO, d * Hq * D, es);
     put(m, PLT_W_NORM2, d, 4);
-    put(m, PLT_W_WGU, 2 * F * d, es);
-    put(m, PLT_W_WDOWN, d * F, es);
+    if (E > 0) put(m, PLT_W_ROUTER, E * d, es);
+    put(m, PLT_W_WGU, Ex * 2 * F * d, es);
+    put(m, PLT_W_WDOWN, Ex * d * F, es);
   }
   put(-1, PLT_W_NORM_F, d, 4);
   if (!c->tie_embeddings) put(-1, PLT_W_HEAD, V * d, es);
@@ -116,9 +123,10 @@ extern "C" int plt_weights_offset(const plt_config* cfg, int32_t layer, int32_t 
                                   size_t* nelem) {
   const char* why;
   if (!cfg_valid(cfg, &why)) return fail(PLT_EINVAL, "plt_weights_offset: %s", why);
-  if (which < PLT_W_EMB || which > PLT_W_HEAD || !off || !nelem) return fail(PLT_EINVAL, "plt_weights_offset: bad tensor id or null output");
+  if (which < PLT_W_EMB || which > PLT_W_ROUTER || !off || !nelem) return fail(PLT_EINVAL, "plt_weights_offset: bad tensor id or null output");
   const bool global = which == PLT_W_EMB || which == PLT_W_NORM_F || which == PLT_W_HEAD;
   if (which == PLT_W_HEAD && cfg->tie_embeddings) return fail(PLT_EINVAL, "plt_weights_offset: head is tied to the embedding");
+  if (which == PLT_W_ROUTER && cfg->n_experts == 0) return fail(PLT_EINVAL, "plt_weights_offset: a dense model has no router");
   if (!global && (layer < 0 || layer >= cfg->n_layers)) return fail(PLT_EINVAL, "plt_weights_offset: layer out of range");
   *off = (size_t)-1;
   blob_walk(cfg, global ? -1 : layer, which, off, nelem);
@@ -157,6 +165,7 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
     w.gate_w = (const float*)at(l, PLT_W_GATE_W); w.gate_b = (const float*)at(l, PLT_W_GATE_B);
     w.wo = at(l, PLT_W_WO); w.norm2 = (const float*)at(l, PLT_W_NORM2);
     w.wgu = at(l, PLT_W_WGU); w.wdown = at(l, PLT_W_WDOWN);
+    w.router = cfg->n_experts > 0 ? at(l, PLT_W_ROUTER) : nullptr;
   }
   {
     std::vector<double> f(cfg->head_dim / 2);
@@ -249,7 +258,7 @@ extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_
 static void kv_release(plt_kv* kv) {
   if (!kv) return;
   void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch,
-                  kv->arg_v, kv->arg_i};
+                  kv->arg_v, kv->arg_i, kv->moe_idx};
   for (void* p : ptrs) if (p) (void)hipFree(p);
   delete kv;
 }
@@ -290,8 +299,12 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   size_t go = gemm_out_need(c, R, Nqkv, d);
   size_t t;
   if ((t = gemm_out_need(c, R, d, Hq * D)) > go) go = t;
-  if ((t = gemm_out_need(c, R, 2 * F, d)) > go) go = t;
-  if ((t = gemm_out_need(c, R, d, F)) > go) go = t;
+  if (c.n_experts > 0) {
+    if ((t = (size_t)c.top_k * R * d) > go) go = t;                  // one output slab per selected expert
+  } else {
+    if ((t = gemm_out_need(c, R, 2 * F, d)) > go) go = t;
+    if ((t = gemm_out_need(c, R, d, F)) > go) go = t;
+  }
   if ((t = gemm_out_need(c, batch, V, d)) > go) go = t;
   kv->gout_elems = go;
   kv->attn_scratch_bytes = attn_mfma_scratch_bytes(batch, is_clp(c) ? L : 1, Hq, Hkv, D, attn_mfma_max_default_splits(batch, Hkv));
@@ -302,7 +315,8 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   dmalloc(&kv->q, (size_t)R * Hq * D * m->es);
   dmalloc((void**)&kv->z, (size_t)R * Hq * 4);
   dmalloc(&kv->y, (size_t)R * Hq * D * m->es);
-  dmalloc(&kv->act, (size_t)R * F * m->es);
+  dmalloc(&kv->act, (size_t)R * (c.n_experts > 0 ? c.top_k : 1) * F * m->es);
+  if (c.n_experts > 0) dmalloc(&kv->moe_idx, moe_index_bytes(R, c.top_k, c.n_experts));
   dmalloc((void**)&kv->carry, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4);
   dmalloc((void**)&kv->pos_dev, (size_t)batch * 4);
   dmalloc(&kv->attn_scratch, kv->attn_scratch_bytes);
@@ -346,6 +360,7 @@ static KvView kv_view(const plt_kv* kv, int layer, int cache) {
 struct Work {            // activation buffers one pass of the stack runs on
   float* x; void* a; float* gout; void* q; float* z; void* y; void* act;
   float* attn_tmp;   // prefill only: float [rows, Hq*D]
+  void* moe_idx;     // mixture-of-experts models: routing lists (moe_index_bytes for the pass's rows)
 };
 
 static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int M, int N, int K,
@@ -412,7 +427,12 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     }
     S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);                                     // Alg. 3 l.6
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
-    if (c.dtype == PLT_BF16 && gemm_big_applies(R, 2 * F, d)) {      // many rows: SwiGLU fused into the GEMM epilogue
+    if (c.n_experts > 0) {                                   // mixture of experts: k slabs, one per selected expert
+      ProfScope prof(m, PLT_PROF_GEMM, dec);
+      launch_moe_ffn<T>(s, (const T*)wk.a, (const T*)w.router, (const T*)w.wgu, (const T*)w.wdown, (T*)wk.act, wk.gout,
+                        moe_index_carve(wk.moe_idx, R, c.top_k, c.n_experts), R, d, F, c.n_experts, c.top_k);
+      S = c.top_k;
+    } else if (c.dtype == PLT_BF16 && gemm_big_applies(R, 2 * F, d)) {      // many rows: SwiGLU fused into the GEMM epilogue
       launch_gemm_big_swiglu(s, (const bf16_t*)wk.a, (const bf16_t*)w.wgu, (bf16_t*)wk.act, R, F, d);
     } else if (c.dtype == PLT_BF16 && gemm_swiglu_rows_applies(R, F, d)) {   // decode rows: likewise, one tile of rows
       ProfScope prof(m, PLT_PROF_GEMM, dec);
@@ -421,7 +441,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
       launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
     }
-    S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
+    if (c.n_experts == 0) S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
     const float* gain = l + 1 < c.n_layers ? m->layers[l + 1].norm1 : next_gain;
     launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, gain, c.norm_eps,
                          gain ? (T*)wk.a : (T*)nullptr, R, d);
@@ -444,7 +464,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
   const plt_config& c = m->cfg;
   hipStream_t s = m->stream;
   const int B = kv->B, L = c.n_loops, d = c.d_model;
-  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr};
+  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr, kv->moe_idx};
   KvView none{}; none.b0 = 0;
   if (is_clp(c)) {
     // Alg. 1 l.5-7: rows B_0 = e, B_l = e + H^l[p-1]; the L rows of a sequence run as one pass
@@ -499,15 +519,21 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   const int n_pad_loc = pad_kv(n, m->kv8);
   size_t go = gemm_out_need(c, Rc, Nqkv, d), t;
   if ((t = gemm_out_need(c, Rc, d, Hq * D)) > go) go = t;
-  if ((t = gemm_out_need(c, Rc, 2 * F, d)) > go) go = t;
-  if ((t = gemm_out_need(c, Rc, d, F)) > go) go = t;
+  const int E = c.n_experts, topk = E > 0 ? c.top_k : 1;
+  if (E > 0) {
+    if ((t = (size_t)topk * Rc * d) > go) go = t;
+  } else {
+    if ((t = gemm_out_need(c, Rc, 2 * F, d)) > go) go = t;
+    if ((t = gemm_out_need(c, Rc, d, F)) > go) go = t;
+  }
   if ((t = gemm_out_need(c, Bc, V, d)) > go) go = t;
   // one temporary workspace, carved into the chunk's activation buffers
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * es),
                o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
-               o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * F * es),
+               o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * topk * F * es),
+               o_moe = carve(E > 0 ? moe_index_bytes(Rc, topk, E) : 256),
                o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes),
                o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
   char* ws = nullptr;
@@ -515,7 +541,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
   (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * kes), s);
   Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act,
-          (float*)(ws + o_tmp)};
+          (float*)(ws + o_tmp), ws + o_moe};
   float* hprev = (float*)(ws + o_h);
   for (int b0 = 0; b0 < B; b0 += Bc) {
     const int bc = b0 + Bc <= B ? Bc : B - b0;
@@ -676,6 +702,7 @@ extern "C" int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes) {
 }
 
 // ---- kernel-only hooks ----
+__global__ void k_sum_slabs(const float* __restrict__ p, float* __restrict__ c, int S, size_t n);
 extern "C" int32_t plt_attn_pad32(int32_t n) { return pad32(n); }
 extern "C" int32_t plt_attn_pad(int32_t dtype, int32_t n) { return pad_kv(n, dtype == PLT_FP8_E4M3); }
 
@@ -746,6 +773,43 @@ extern "C" int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, c
   if (dtype == PLT_FP8_E4M3) launch_pack_v<fp8_t>((hipStream_t)hip_stream, (const fp8_t*)src, (fp8_t*)dst, S, n, pad_kv(n, true), D);
   else if (dtype == PLT_BF16) launch_pack_v<bf16_t>((hipStream_t)hip_stream, (const bf16_t*)src, (bf16_t*)dst, S, n, pad32(n), D);
   else launch_pack_v<float>((hipStream_t)hip_stream, (const float*)src, (float*)dst, S, n, pad32(n), D);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
+extern "C" size_t plt_moe_scratch_bytes(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k) {
+  if ((dtype != PLT_F32 && dtype != PLT_BF16) || R < 1 || d < 1 || F < 1 || E < 1 || E > 256 || k < 1 || k > E || k > 32) {
+    fail(PLT_EINVAL, "plt_moe_scratch_bytes: bad argument"); return 0;
+  }
+  const size_t es = dtype == PLT_BF16 ? 2 : 4;
+  return moe_index_bytes(R, k, E) + align256((size_t)R * k * F * es) + align256((size_t)k * R * d * 4);
+}
+
+extern "C" int plt_moe_ffn(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k, const void* a,
+                           const void* router, const void* wgu, const void* wdown, float* y, int32_t* sel_e,
+                           float* sel_p, void* scratch, size_t scratch_bytes, void* hip_stream) {
+  const size_t need = plt_moe_scratch_bytes(dtype, R, d, F, E, k);
+  if (need == 0) return fail(PLT_EINVAL, "plt_moe_ffn: bad shape or dtype");
+  if (dtype == PLT_BF16 && (d % 64 || F % 64)) return fail(PLT_EINVAL, "plt_moe_ffn: bf16 needs d and F to be multiples of 64");
+  if ((long)R * k > 2000000L) return fail(PLT_EINVAL, "plt_moe_ffn: R * k too large");
+  if (!a || !router || !wgu || !wdown || !y || !sel_e || !sel_p || !scratch) return fail(PLT_EINVAL, "plt_moe_ffn: null pointer");
+  if (scratch_bytes < need || (((uintptr_t)scratch) & 255)) return fail(PLT_ENOMEM, "plt_moe_ffn: scratch too small or not 256-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const size_t es = dtype == PLT_BF16 ? 2 : 4;
+  char* base = (char*)scratch;
+  MoeIndex mi = moe_index_carve(base, R, k, E);
+  void* act = base + moe_index_bytes(R, k, E);
+  float* slabs = (float*)((char*)act + align256((size_t)R * k * F * es));
+  if (dtype == PLT_BF16)
+    launch_moe_ffn<bf16_t>(s, (const bf16_t*)a, (const bf16_t*)router, (const bf16_t*)wgu, (const bf16_t*)wdown, (bf16_t*)act,
+                           slabs, mi, R, d, F, E, k);
+  else
+    launch_moe_ffn<float>(s, (const float*)a, (const float*)router, (const float*)wgu, (const float*)wdown, (float*)act,
+                          slabs, mi, R, d, F, E, k);
+  const size_t n = (size_t)R * d;
+  hipLaunchKernelGGL(k_sum_slabs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)slabs, y, k, n);
+  HIP_TRY(hipMemcpyAsync(sel_e, mi.sel_e, (size_t)R * k * 4, hipMemcpyDeviceToDevice, s));
+  HIP_TRY(hipMemcpyAsync(sel_p, mi.sel_p, (size_t)R * k * 4, hipMemcpyDeviceToDevice, s));
   HIP_TRY(hipGetLastError());
   return PLT_OK;
 }

@@ -167,6 +167,17 @@ void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, 
 int gemm_bf16_splits_any(int M, int N, int K);
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
 
+// moe.hip : mixture-of-experts feed-forward.  Index arrays of one call (device): the selected experts and
+// their probabilities per row, the (row, slot) pairs sorted by expert and every expert's span in that list.
+struct MoeIndex { int32_t* sel_e; float* sel_p; int32_t* pair; int32_t* off; };
+size_t moe_index_bytes(int R, int k, int E);
+MoeIndex moe_index_carve(void* base, int R, int k, int E);
+// a [R, d] normed rows; router [E, d]; wgu [E, 2F, d] (per expert: gate rows, then up rows); wdown [E, d, F];
+// act: scratch [R*k, F]; y: k slabs [k][R][d] (slab s, row r = p * the output of row r's s-th expert)
+template <typename T>
+void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, const T* wdown, T* act, float* y,
+                    MoeIndex mi, int R, int d, int F, int E, int k);
+
 // attn_f32.hip : one wave per (row, query head), float storage
 void launch_attn_f32(hipStream_t s, const float* q, const float* z, float* y, KvView kv,
                      RowMap rm, int R, Dims dm, int plain);

@@ -57,13 +57,38 @@ def test_weight_layout_queries(lib):
     assert lib.plt_weights_bytes(C.byref(cfg16)) < total
     off16, n16 = B.weights_offset(cfg16, 1, B.PLT_W_WGU)
     assert n16 == 2 * s.ffn_hidden * s.d_model
+    with pytest.raises(B.PltError):
+        B.weights_offset(cfg16, 0, B.PLT_W_ROUTER)        # a dense model has no router
+    # mixture of experts: a router after NORM2 and a leading expert axis on the feed-forward matrices
+    m = synth.TINY_MOE
+    cfgm = B.make_config(m, dtype=B.PLT_BF16)
+    o_n2, _ = B.weights_offset(cfgm, 1, B.PLT_W_NORM2)
+    o_r, n_r = B.weights_offset(cfgm, 1, B.PLT_W_ROUTER)
+    o_gu, n_gu = B.weights_offset(cfgm, 1, B.PLT_W_WGU)
+    o_dn, n_dn = B.weights_offset(cfgm, 1, B.PLT_W_WDOWN)
+    assert n_r == m.n_experts * m.d_model and n_gu == m.n_experts * 2 * m.ffn_hidden * m.d_model
+    assert n_dn == m.n_experts * m.d_model * m.ffn_hidden
+    assert o_n2 < o_r < o_gu < o_dn and o_gu >= o_r + 2 * n_r and o_dn >= o_gu + 2 * n_gu
+    assert lib.plt_weights_bytes(C.byref(cfgm)) >= o_dn + 2 * n_dn
 
 
 @pytest.mark.parametrize("field,value", [("head_dim", 48), ("n_kv_heads", 3), ("n_loops", 0), ("dtype", 7),
-                                         ("mode", 1), ("mode", 5), ("window", 0), ("d_model", 0)])
+                                         ("mode", 1), ("mode", 5), ("window", 0), ("d_model", 0),
+                                         ("n_experts", -1), ("n_experts", 257), ("kv_dtype", 1)])
 def test_invalid_configs_are_rejected(lib, field, value):
     cfg = B.make_config(synth.TINY, dtype=B.PLT_F32)
     setattr(cfg, field, value)
+    _expect_rejected(lib, cfg)
+
+
+@pytest.mark.parametrize("top_k", [0, 9, -1])
+def test_invalid_expert_counts_are_rejected(lib, top_k):
+    cfg = B.make_config(synth.TINY_MOE, dtype=B.PLT_F32)
+    cfg.top_k = top_k
+    _expect_rejected(lib, cfg)
+
+
+def _expect_rejected(lib, cfg):
     assert lib.plt_weights_bytes(C.byref(cfg)) == 0
     assert len(lib.plt_last_error()) > 0
     h = C.c_void_p()
