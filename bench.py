@@ -75,6 +75,15 @@ def fill_weights_on_device(B, cfg, seed):
     return blob
 
 
+def moe_untile(t):
+    """Inverse of the blob's strip order of bf16 expert matrices (binding.moe_tile_weights): [..., N, K] row-major."""
+    *lead, N, K = t.shape
+    nl = len(lead)
+    x = t.reshape(*lead, N // 16, K // 32, 4, 16, 8)
+    x = np.transpose(x, tuple(range(nl)) + (nl, nl + 3, nl + 1, nl + 2, nl + 4))
+    return np.ascontiguousarray(x).reshape(*lead, N, K)
+
+
 def weights_to_host(B, cfg, blob):
     """The device blob as the float32 weight dict the oracle takes (same values)."""
     import torch
@@ -93,13 +102,14 @@ def weights_to_host(B, cfg, blob):
     for m in range(cfg.n_layers):
         qkv = get(m, B.PLT_W_WQKV, wd, ((Hq + 2 * Hkv) * D, d))
         if E > 0:
-            gu = get(m, B.PLT_W_WGU, wd, (E, 2 * F, d))
+            untile = moe_untile if cfg.dtype == B.PLT_BF16 else (lambda x: x)
+            gu = untile(get(m, B.PLT_W_WGU, wd, (E, 2 * F, d)))
             w["layers"].append({
                 "norm1": get(m, B.PLT_W_NORM1, torch.float32, (d,)), "wq": qkv[:Hq * D], "wk": qkv[Hq * D:(Hq + Hkv) * D],
                 "wv": qkv[(Hq + Hkv) * D:], "gate_w": get(m, B.PLT_W_GATE_W, torch.float32, (Hq, D)),
                 "gate_b": get(m, B.PLT_W_GATE_B, torch.float32, (Hq,)), "wo": get(m, B.PLT_W_WO, wd, (d, Hq * D)),
                 "norm2": get(m, B.PLT_W_NORM2, torch.float32, (d,)), "router": get(m, B.PLT_W_ROUTER, wd, (E, d)),
-                "w_gate": gu[:, :F], "w_up": gu[:, F:], "w_down": get(m, B.PLT_W_WDOWN, wd, (E, d, F))})
+                "w_gate": gu[:, :F], "w_up": gu[:, F:], "w_down": untile(get(m, B.PLT_W_WDOWN, wd, (E, d, F)))})
             continue
         gu = get(m, B.PLT_W_WGU, wd, (2 * F, d))
         w["layers"].append({

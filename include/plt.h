@@ -98,7 +98,11 @@ typedef struct plt_kv plt_kv;       /* opaque */
  *   the other tensors have the model dtype.  Every tensor starts at a multiple of 256 bytes.
  *   Mixture-of-experts models (n_experts = E > 0): ROUTER [E, d] follows NORM2, and the expert
  *   matrices carry a leading expert axis: WGU [E, 2F, d] (per expert: its W_gate rows, then its
- *   W_up rows), WDOWN [E, d, F]. */
+ *   W_up rows), WDOWN [E, d, F].  PLT_F32 keeps every expert matrix row-major; PLT_BF16 stores each
+ *   expert matrix [N, K] strip by strip in matrix-core load order: element (n, k) of the matrix
+ *   sits at element index plt_moe_weight_index(n, k, K) of that expert's N*K block (16-row strips;
+ *   inside a strip 32-wide k chunks; inside a chunk [k/8 mod 4][n mod 16][k mod 8]), so that the
+ *   grouped GEMM streams every strip as one contiguous run. */
 enum { PLT_W_EMB = 0, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO,
        PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER };
 
@@ -226,12 +230,14 @@ size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
 
 /* Kernel-only mixture-of-experts feed-forward [appendix, "MoE Models Recipe"; router reading in the
  * header comment]: for R rows a [R, d] (already normed), router [E, d], wgu [E, 2F, d], wdown [E, d, F]
- * (all of type `dtype`, device memory) writes
+ * (all of type `dtype`, device memory; PLT_BF16: the expert matrices in the strip order of
+ * plt_moe_weight_index, as in the weight blob) writes
  *   y [R, d] float       = sum over the k selected experts e of p_e * W_down^e (silu(W_gate^e a) * W_up^e a)
  *   sel_e [R, k] int32   the selected experts in order of decreasing probability
  *   sel_p [R, k] float   their softmax probabilities
  * PLT_BF16 needs d % 64 == 0 and F % 64 == 0; E <= 256, k <= min(E, 32).  dev_scratch: device buffer of
  * plt_moe_scratch_bytes(...) bytes (index lists, the experts' hidden activations, k output slabs). */
+int64_t plt_moe_weight_index(int32_t n, int32_t k, int32_t K); /* host only; -1 for a bad argument */
 size_t plt_moe_scratch_bytes(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k);
 int plt_moe_ffn(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k, const void* dev_a,
                 const void* dev_router, const void* dev_wgu, const void* dev_wdown, float* dev_y,

@@ -65,6 +65,7 @@ _SIGS = {
     "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
     "plt_gemm_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_moe_weight_index": (C.c_int64, [_I, _I, _I]),
     "plt_moe_scratch_bytes": (_Z, [_I] * 6),
     "plt_moe_ffn": (C.c_int, [_I] * 6 + [_P] * 8 + [_Z, _P]),
     "plt_stream_copy": (C.c_int, [_P, _P, _Z, _P]),
@@ -121,6 +122,17 @@ def weights_offset(cfg, layer, which):
     return off.value, n.value
 
 
+def moe_tile_weights(w: np.ndarray) -> np.ndarray:
+    """Expert matrices [..., N, K] (N % 16 == 0, K % 32 == 0) -> the strip order of the bf16 blob:
+    [..., strip, k chunk, k/8 mod 4, n mod 16, k mod 8] (see plt_moe_weight_index); a pure permutation."""
+    *lead, N, K = w.shape
+    assert N % 16 == 0 and K % 32 == 0, (N, K)
+    t = w.reshape(*lead, N // 16, 16, K // 32, 4, 8)
+    nl = len(lead)
+    t = np.transpose(t, tuple(range(nl)) + (nl, nl + 2, nl + 3, nl + 1, nl + 4))
+    return np.ascontiguousarray(t).reshape(*lead, N, K)
+
+
 def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
     """Copies a weight dict (float32 arrays, [out, in]) into a device blob in the library's layout."""
     import torch
@@ -148,11 +160,13 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
         put(m, PLT_W_WO, lw["wo"], True)
         put(m, PLT_W_NORM2, lw["norm2"], False)
         if cfg.n_experts > 0:       # expert axis first; per expert its gate rows, then its up rows
+            tile = moe_tile_weights if cfg.dtype == PLT_BF16 else (lambda x: x)
             put(m, PLT_W_ROUTER, lw["router"], True)
-            put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=1), True)
+            put(m, PLT_W_WGU, tile(np.concatenate([lw["w_gate"], lw["w_up"]], axis=1)), True)
+            put(m, PLT_W_WDOWN, tile(np.asarray(lw["w_down"])), True)
         else:
             put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=0), True)
-        put(m, PLT_W_WDOWN, lw["w_down"], True)
+            put(m, PLT_W_WDOWN, lw["w_down"], True)
     put(0, PLT_W_NORM_F, weights["norm_f"], False)
     if not cfg.tie_embeddings:
         put(0, PLT_W_HEAD, weights["head"], True)
@@ -368,8 +382,9 @@ def moe_ffn(dtype, a, router, w_gate, w_up, w_down, top_k):
     import torch
     R, d = a.shape
     E, F = w_gate.shape[0], w_gate.shape[1]
-    da, dr, dd = _to_dev(a, dtype), _to_dev(router, dtype), _to_dev(w_down, dtype)
-    dgu = _to_dev(np.concatenate([w_gate, w_up], axis=1), dtype)
+    tile = moe_tile_weights if dtype == PLT_BF16 else (lambda x: x)
+    da, dr, dd = _to_dev(a, dtype), _to_dev(router, dtype), _to_dev(tile(np.asarray(w_down)), dtype)
+    dgu = _to_dev(tile(np.concatenate([w_gate, w_up], axis=1)), dtype)
     y = torch.empty(R, d, dtype=torch.float32, device="cuda")
     sel_e = torch.empty(R, top_k, dtype=torch.int32, device="cuda")
     sel_p = torch.empty(R, top_k, dtype=torch.float32, device="cuda")

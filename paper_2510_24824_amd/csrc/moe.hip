@@ -24,39 +24,63 @@ namespace plt {
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 // ---------------------------------------------------------------------------------------------- router
+// One workgroup of 8 waves per row.  Wave v owns experts v, v + 8, ...; it takes them 8 at a time with the
+// loads of all 8 weight rows issued together (the router matrix is small and cache-resident: what costs
+// here is load latency, not bytes).
+constexpr int ROUTE_WAVES = 8, ROUTE_EB = 8;
 template <typename T>
-__global__ __launch_bounds__(256) void k_moe_route(const T* __restrict__ a, const T* __restrict__ wr,
-                                                   int32_t* __restrict__ sel_e, float* __restrict__ sel_p,
-                                                   int d, int E, int k) {
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const T* __restrict__ a, const T* __restrict__ wr,
+                                                                int32_t* __restrict__ sel_e, float* __restrict__ sel_p,
+                                                                int d, int E, int k) {
   extern __shared__ float sm_route[];       // [d] the row as float, then [E] logits
   float* xr = sm_route;
   float* lg = sm_route + d;
   const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  for (int i = tid; i < d; i += 256) xr[i] = ld<T>(a + (size_t)r * d + i);
+  for (int i = tid; i < d; i += ROUTE_WAVES * 64) xr[i] = ld<T>(a + (size_t)r * d + i);
   __syncthreads();
-  for (int e = wv; e < E; e += 4) {
-    const T* w = wr + (size_t)e * d;
-    float acc = 0.f;
-    if constexpr (sizeof(T) == 2) {
-      if ((d & 7) == 0) {
-        for (int i = lane * 8; i < d; i += 512) {
-          const uint4 v = *reinterpret_cast<const uint4*>(w + i);
-          const unsigned u[4] = {v.x, v.y, v.z, v.w};
+  for (int e0 = wv; e0 < E; e0 += ROUTE_WAVES * ROUTE_EB) {
+    float acc[ROUTE_EB];
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            acc += xr[i + 2 * j] * bf16_to_f32((bf16_t)(u[j] & 0xffffu));
-            acc += xr[i + 2 * j + 1] * bf16_to_f32((bf16_t)(u[j] >> 16));
+    for (int j = 0; j < ROUTE_EB; ++j) acc[j] = 0.f;
+    if (sizeof(T) == 2 && (d & 7) == 0) {
+      for (int i = lane * 8; i < d; i += 512) {
+        uint4 v[ROUTE_EB];
+#pragma unroll
+        for (int j = 0; j < ROUTE_EB; ++j) {
+          int e = e0 + j * ROUTE_WAVES; if (e >= E) e = E - 1;            // clamped: computed, never stored
+          v[j] = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(wr) + (size_t)e * d + i);
+        }
+        float x[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) x[c] = xr[i + c];
+#pragma unroll
+        for (int j = 0; j < ROUTE_EB; ++j) {
+          const unsigned u[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            acc[j] += x[2 * c] * bf16_to_f32((bf16_t)(u[c] & 0xffffu));
+            acc[j] += x[2 * c + 1] * bf16_to_f32((bf16_t)(u[c] >> 16));
           }
         }
-      } else {
-        for (int i = lane; i < d; i += 64) acc += xr[i] * ld<T>(w + i);
       }
     } else {
-      for (int i = lane; i < d; i += 64) acc += xr[i] * ld<T>(w + i);
+      for (int i = lane; i < d; i += 64) {
+        const float x = xr[i];
+#pragma unroll
+        for (int j = 0; j < ROUTE_EB; ++j) {
+          int e = e0 + j * ROUTE_WAVES; if (e >= E) e = E - 1;
+          acc[j] += x * ld<T>(wr + (size_t)e * d + i);
+        }
+      }
     }
 #pragma unroll
-    for (int o = 32; o; o >>= 1) acc += __shfl_xor(acc, o);
-    if (lane == 0) lg[e] = acc;
+    for (int j = 0; j < ROUTE_EB; ++j) {
+      float s = acc[j];
+#pragma unroll
+      for (int o = 32; o; o >>= 1) s += __shfl_xor(s, o);
+      const int e = e0 + j * ROUTE_WAVES;
+      if (lane == 0 && e < E) lg[e] = s;
+    }
   }
   __syncthreads();
   if (wv != 0) return;
@@ -82,125 +106,145 @@ __global__ __launch_bounds__(256) void k_moe_route(const T* __restrict__ a, cons
       if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
     }
     if (lane == 0) { sel_e[(size_t)r * k + t] = bi; sel_p[(size_t)r * k + t] = expf(bv - mx) / sum; }
-    if (lane == (bi & 63)) {
-      const int j = bi >> 6;
-      if (j == 0) v[0] = -INFINITY; else if (j == 1) v[1] = -INFINITY; else if (j == 2) v[2] = -INFINITY; else v[3] = -INFINITY;
-    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = (lane + 64 * j == bi) ? -INFINITY : v[j];     // taken: out of the running
   }
 }
 
 // ---------------------------------------------------------------------------------------------- bucket
 // Stable counting sort of the P = R*k pairs (index i = row*k + slot) by expert: pair[off[e] .. off[e+1])
 // lists expert e's pairs in increasing i.  One workgroup of 16 waves; wave w owns a contiguous span of
-// pairs.  Counting: the lanes of a 64-pair chunk that share an expert are found by ballot, so positions
-// follow from population counts and the result does not depend on any execution order.
-__device__ inline void lane_counter_add(int (&c)[4], int j, int n) {
-  if (j == 0) c[0] += n; else if (j == 1) c[1] += n; else if (j == 2) c[2] += n; else c[3] += n;
-}
-__device__ inline int lane_counter_get(const int (&c)[4], int j) {
-  return j == 0 ? c[0] : (j == 1 ? c[1] : (j == 2 ? c[2] : c[3]));
-}
+// pairs and walks it 64 pairs at a time: the chunk sits in one register across the wave, entry t is
+// broadcast with a lane read, and lane (e mod 64) keeps the running counter of expert e -- positions
+// follow from counts alone, so the result does not depend on any execution order.  The walk is a chain
+// of vector instructions per pair, so it is kept to a handful: EW = ceil(E / 64) counters per lane.
+template <int EW>
 __global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__ sel_e, int32_t* __restrict__ off,
                                                      int32_t* __restrict__ pair, int P, int E) {
-  __shared__ int cnt[16][256];
-  __shared__ int offs[257];
+  __shared__ int cnt[16][EW * 64];
+  __shared__ int offs[EW * 64 + 1];
+  __shared__ int wave_tot[EW];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const int per = (((P + 15) / 16) + 63) & ~63;
   const int beg = wv * per < P ? wv * per : P;
   const int end = beg + per < P ? beg + per : P;
-  int c[4] = {0, 0, 0, 0};                       // lane holds the counters of experts lane + 64 j
+  int c[EW];                                     // lane holds the counters of experts lane + 64 j
+#pragma unroll
+  for (int j = 0; j < EW; ++j) c[j] = 0;
   for (int i0 = beg; i0 < end; i0 += 64) {
-    const int i = i0 + lane;
-    const int e = i < end ? sel_e[i] : -1;
-    unsigned long long todo = __ballot(i < end);
-    while (todo) {
-      const int el = __shfl(e, __ffsll((long long)todo) - 1);
-      const unsigned long long m = __ballot(e == el);
-      if (lane == (el & 63)) lane_counter_add(c, el >> 6, __popcll(m));
-      todo &= ~m;
+    const int v = i0 + lane < end ? sel_e[i0 + lane] : -1;
+    const int nt = end - i0 < 64 ? end - i0 : 64;
+    for (int t = 0; t < nt; ++t) {
+      const int el = __builtin_amdgcn_readlane(v, t);
+      if (EW == 1) { c[0] += lane == el; }
+      else {
+#pragma unroll
+        for (int j = 0; j < EW; ++j) c[j] += lane + 64 * j == el;
+      }
     }
   }
 #pragma unroll
-  for (int j = 0; j < 4; ++j) cnt[wv][lane + 64 * j] = c[j];
+  for (int j = 0; j < EW; ++j) cnt[wv][lane + 64 * j] = c[j];
   __syncthreads();
-  if (tid == 0) {
-    int run = 0;
-    for (int e = 0; e < E; ++e) {
-      offs[e] = run;
-      for (int w = 0; w < 16; ++w) run += cnt[w][e];
-    }
-    offs[E] = run;
+  // exclusive prefix sum of the per-expert totals over EW * 64 slots (EW waves, shuffle scan)
+  int tot = 0, incl = 0;
+  if (tid < EW * 64) {
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += cnt[w][tid];
+    incl = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
+    if (lane == 63) wave_tot[wv] = incl;
   }
   __syncthreads();
-  if (tid <= E) off[tid] = offs[tid];
+  if (tid < EW * 64) {
+    int base = 0;
+    for (int w = 0; w < wv; ++w) base += wave_tot[w];
+    offs[tid] = base + incl - tot;
+    if (tid == EW * 64 - 1) offs[EW * 64] = base + incl;
+  }
+  __syncthreads();
+  if (tid <= E) off[tid] = offs[tid];          // experts >= E have no pairs: offs[E] is the total
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < EW; ++j) {
     const int e = lane + 64 * j;
-    int b = e < E ? offs[e] : 0;
+    int b = offs[e];
     for (int w = 0; w < wv; ++w) b += cnt[w][e];
     c[j] = b;
   }
   for (int i0 = beg; i0 < end; i0 += 64) {
-    const int i = i0 + lane;
-    const int e = i < end ? sel_e[i] : -1;
-    unsigned long long todo = __ballot(i < end);
-    while (todo) {
-      const int el = __shfl(e, __ffsll((long long)todo) - 1);
-      const unsigned long long m = __ballot(e == el);
-      const int base = __shfl(lane_counter_get(c, el >> 6), el & 63);
-      if (e == el) pair[base + __popcll(m & ((1ull << lane) - 1ull))] = i;
-      if (lane == (el & 63)) lane_counter_add(c, el >> 6, __popcll(m));
-      todo &= ~m;
+    const int v = i0 + lane < end ? sel_e[i0 + lane] : -1;
+    const int nt = end - i0 < 64 ? end - i0 : 64;
+    int mypos = 0;                               // lane t ends up with the list position of entry i0 + t
+    for (int t = 0; t < nt; ++t) {
+      const int el = __builtin_amdgcn_readlane(v, t);
+      int pos;
+      if (EW == 1) { pos = __builtin_amdgcn_readlane(c[0], el); c[0] += lane == el; }
+      else {
+        int cj = c[0];
+#pragma unroll
+        for (int j = 1; j < EW; ++j) cj = (el >> 6) == j ? c[j] : cj;
+        pos = __builtin_amdgcn_readlane(cj, el & 63);
+#pragma unroll
+        for (int j = 0; j < EW; ++j) c[j] += lane + 64 * j == el;
+      }
+      if (lane == t) mypos = pos;
     }
+    if (lane < nt) pair[mypos] = i0 + lane;      // one store per chunk, after the loop
   }
 }
 
 // ---------------------------------------------------------------------------------------------- grouped GEMM
-// c[rows of expert e][N] = rows x w[e][N][K]^T on the matrix cores.  The expert's rows (MT*16 at a time)
-// sit in LDS, one K range of KR at a time; each of the 4 waves streams two 16-row strips of the expert's
-// weight matrix straight from HBM into registers in MFMA A-operand layout (16 bytes per lane), 256 k per
-// step, the next step prefetched while the current one is multiplied.  GU: the two strips are the gate
-// and the up rows of the same 16 hidden columns, SwiGLU in the epilogue.
-template <int MT, int KR, bool GU>
+// c[rows of expert e][N] = rows x W_e[N][K]^T on the matrix cores.  The expert's rows (MT*16 at a time)
+// sit in LDS, one K range of KR at a time; each of the 4 waves streams NS 16-row strips of the expert's
+// weight matrix straight from HBM into registers (MFMA A operand, 16 bytes per lane), KH 32-wide chunks
+// per step, the next step prefetched while the current one is multiplied.  The expert matrices of bf16
+// models are stored strip by strip in exactly that load order (moe_wtile_index): a wave load is one
+// contiguous KiB and a strip one contiguous stream, read with the non-temporal hint (every weight byte
+// is used once per step).  GU: strips come in pairs, the gate and the up rows of the same 16 hidden
+// columns, SwiGLU in the epilogue.
+template <int MT, int KR, bool GU, int NS, int KH>
 __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                   const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
                                                   const float* __restrict__ sel_p, bf16_t* __restrict__ act_out,
                                                   float* __restrict__ y_out, int R, int N, int K, int topk) {
   extern __shared__ __attribute__((aligned(16))) bf16_t As_moe[];   // [MT*16][KR + 8]
   bf16_t* As = As_moe;
-  constexpr int LDK = KR + 8, KH = 8, STEPS = KR / (32 * KH);
+  constexpr int LDK = KR + 8, STEPS = KR / (32 * KH);
   static_assert(STEPS >= 2 && STEPS % 2 == 0, "two register buffers alternate over an even number of steps");
+  static_assert(!GU || NS % 2 == 0, "gate and up strips come in pairs");
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int e = blockIdx.y;
   const int beg = off[e], n_e = off[e + 1] - beg;
   if (n_e <= 0) return;
-  // the two weight strips of this wave: first output column and first weight row of each
-  int col0[2];
-  const bf16_t* wp[2];
-  if (GU) {
-    col0[0] = col0[1] = (blockIdx.x * 4 + wv) * 16;
-    int n = col0[0] + m16; if (n >= N) n = N - 1;
-    wp[0] = w + ((size_t)e * 2 * N + n) * K + g * 8;
-    wp[1] = w + ((size_t)e * 2 * N + N + n) * K + g * 8;
-  } else {
+  // this wave's weight strips: first output column of each and where its stream starts
+  constexpr int NC = GU ? NS / 2 : NS;           // 16-column groups of the output per wave
+  int col0[NC];
+  const bf16_t* wp[NS];
+  const int n_strips = N >> 4;                   // N is a multiple of 16
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      col0[sb] = ((blockIdx.x * 4 + wv) * 2 + sb) * 16;
-      int n = col0[sb] + m16; if (n >= N) n = N - 1;
-      wp[sb] = w + ((size_t)e * N + n) * K + g * 8;
+  for (int c = 0; c < NC; ++c) {
+    int strip = (blockIdx.x * 4 + wv) * NC + c;
+    col0[c] = strip * 16;
+    if (strip >= n_strips) strip = n_strips - 1;         // beyond N: a valid strip, its results are not stored
+    if (GU) {
+      wp[2 * c] = w + ((size_t)e * 2 * N + (size_t)strip * 16) * K + lane * 8;
+      wp[2 * c + 1] = w + ((size_t)e * 2 * N + N + (size_t)strip * 16) * K + lane * 8;
+    } else {
+      wp[c] = w + ((size_t)e * N + (size_t)strip * 16) * K + lane * 8;
     }
   }
   const int n_rng = (K + KR - 1) / KR;
-  uint4 bufA[2][KH], bufB[2][KH];
-  auto wload = [&](uint4 (&f)[2][KH], int t, int rng) {
+  uint4 bufA[NS][KH], bufB[NS][KH];
+  auto wload = [&](uint4 (&f)[NS][KH], int t, int rng) {
     const int k0 = rng * KR;
     const int kr = (K - k0 < KR) ? K - k0 : KR;
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
+    for (int sb = 0; sb < NS; ++sb)
 #pragma unroll
       for (int kk = 0; kk < KH; ++kk) {
-        int ko = (t * KH + kk) * 32; if (ko + g * 8 + 8 > kr) ko = 0;      // beyond K: an in-range chunk (meets zeros in LDS)
-        f[sb][kk] = *reinterpret_cast<const uint4*>(wp[sb] + k0 + ko);
+        int ko = (t * KH + kk) * 32; if (ko + 32 > kr) ko = 0;       // beyond K: an in-range chunk (meets zeros in LDS)
+        f[sb][kk] = ldg16_stream(wp[sb] + (size_t)((k0 + ko) >> 5) * 512);
       }
   };
   const unsigned lds_as = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)As;
@@ -233,26 +277,25 @@ __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, 
       *reinterpret_cast<uint4*>(&As[row * LDK + kc]) = v;
     }
   };
-  f32x4 acc[2][MT];
-  auto mac = [&](const uint4 (&f)[2][KH], int t) {
+  f32x4 acc[NS][MT];
+  auto mac = [&](const uint4 (&f)[NS][KH], int t) {
 #pragma unroll
     for (int kk = 0; kk < KH; ++kk) {
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
         const uint4 af = *reinterpret_cast<const uint4*>(&As[(i * 16 + m16) * LDK + (t * KH + kk) * 32 + g * 8]);
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb)
+        for (int sb = 0; sb < NS; ++sb)
           acc[sb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f[sb][kk]),
                                                               __builtin_bit_cast(bf16x8, af), acc[sb][i], 0, 0, 0);
       }
       if ((kk & 1) == 1) __builtin_amdgcn_sched_barrier(0);
     }
   };
-  // the wait for a prefetched weight step must not be merged into the LDS slice's wait: order them
   wload(bufA, 0, 0);
   for (int m0 = 0; m0 < n_e; m0 += MT * 16) {
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
+    for (int sb = 0; sb < NS; ++sb)
 #pragma unroll
       for (int i = 0; i < MT; ++i) acc[sb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
     for (int rng = 0; rng < n_rng; ++rng) {
@@ -267,28 +310,34 @@ __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, 
         if (t & 1) mac(bufB, t); else mac(bufA, t);
       }
     }
-    // acc[sb][i][c] = C[list row m0 + i*16 + m16][col0[sb] + 4*g + c]
+    // acc[sb][i][c] = C[list row m0 + i*16 + m16][column of strip sb + 4*g + c]
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
       const int li = m0 + i * 16 + m16;
       if (li >= n_e) continue;
       if (GU) {
-        const int col = col0[0] + 4 * g;
-        if (col >= N) continue;
-        bf16_t o[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) { const float gt = acc[0][i][c]; o[c] = f32_to_bf16(gt / (1.0f + expf(-gt)) * acc[1][i][c]); }
-        uint2 pk; pk.x = (unsigned)o[0] | ((unsigned)o[1] << 16); pk.y = (unsigned)o[2] | ((unsigned)o[3] << 16);
-        *reinterpret_cast<uint2*>(act_out + (size_t)(beg + li) * N + col) = pk;
+        for (int c = 0; c < NC; ++c) {
+          const int col = col0[c] + 4 * g;
+          if (col >= N) continue;
+          bf16_t o[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const float gt = acc[2 * c][i][x];
+            o[x] = f32_to_bf16(gt / (1.0f + expf(-gt)) * acc[2 * c + 1][i][x]);
+          }
+          uint2 pk; pk.x = (unsigned)o[0] | ((unsigned)o[1] << 16); pk.y = (unsigned)o[2] | ((unsigned)o[3] << 16);
+          *reinterpret_cast<uint2*>(act_out + (size_t)(beg + li) * N + col) = pk;
+        }
       } else {
         const int pr = pair[beg + li];
         const int row = pr / topk, slot = pr - row * topk;
         const float p = sel_p[pr];
 #pragma unroll
-        for (int sb = 0; sb < 2; ++sb) {
-          const int col = col0[sb] + 4 * g;
+        for (int c = 0; c < NC; ++c) {
+          const int col = col0[c] + 4 * g;
           if (col >= N) continue;
-          f32x4 o = acc[sb][i];
+          f32x4 o = acc[c][i];
           o[0] *= p; o[1] *= p; o[2] *= p; o[3] *= p;
           *reinterpret_cast<f32x4*>(y_out + ((size_t)slot * R + row) * N + col) = o;
         }
@@ -353,39 +402,43 @@ MoeIndex moe_index_carve(void* base, int R, int k, int E) {
   return mi;
 }
 
-template <int MT, int KR, bool GU>
-static void moe_gemm_launch(hipStream_t s, dim3 grid, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act,
-                            float* y, int R, int N, int K, int k) {
+template <int MT, int KR, bool GU, int NS, int KH>
+static void moe_gemm_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act,
+                            float* y, int R, int N, int K, int k, int E) {
   const size_t lds = (size_t)MT * 16 * (KR + 8) * sizeof(bf16_t);
   static bool attr_done = false;     // one flag per template instance
   if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_moe_gemm<MT, KR, GU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute((const void*)k_moe_gemm<MT, KR, GU, NS, KH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  hipLaunchKernelGGL((k_moe_gemm<MT, KR, GU>), grid, dim3(256), lds, s, a, w, mi.off, mi.pair, mi.sel_p, act, y, R, N, K, k);
+  const int cols_per_wg = 4 * 16 * (GU ? NS / 2 : NS);
+  hipLaunchKernelGGL((k_moe_gemm<MT, KR, GU, NS, KH>), dim3((N + cols_per_wg - 1) / cols_per_wg, E), dim3(256), lds, s, a, w,
+                     mi.off, mi.pair, mi.sel_p, act, y, R, N, K, k);
 }
 
 // rows per LDS tile by the mean number of rows per expert: 32 (two workgroups per compute unit, K range
 // 1024), 64 (two per unit, K range 512) or 128 (prefill-sized batches)
 template <bool GU>
-static void moe_gemm_pick(hipStream_t s, dim3 grid, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act,
+static void moe_gemm_pick(hipStream_t s, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act,
                           float* y, int R, int N, int K, int k, int E) {
   const long mean = ((long)R * k + E - 1) / E;
-  if (mean <= 24) moe_gemm_launch<2, 1024, GU>(s, grid, a, w, mi, act, y, R, N, K, k);
-  else if (mean <= 48) moe_gemm_launch<4, 512, GU>(s, grid, a, w, mi, act, y, R, N, K, k);
-  else moe_gemm_launch<8, 512, GU>(s, grid, a, w, mi, act, y, R, N, K, k);
+  if (mean <= 24) moe_gemm_launch<2, 1024, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
+  else if (mean <= 48) moe_gemm_launch<4, 512, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
+  else moe_gemm_launch<8, 512, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
 }
 
 template <typename T>
 void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, const T* wdown, T* act, float* y,
                     MoeIndex mi, int R, int d, int F, int E, int k) {
   const int P = R * k;
-  hipLaunchKernelGGL(k_moe_route<T>, dim3(R), dim3(256), (size_t)(d + E) * sizeof(float), s, a, router, mi.sel_e, mi.sel_p,
+  hipLaunchKernelGGL(k_moe_route<T>, dim3(R), dim3(ROUTE_WAVES * 64), (size_t)(d + E) * sizeof(float), s, a, router, mi.sel_e, mi.sel_p,
                      d, E, k);
-  hipLaunchKernelGGL(k_moe_bucket, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   if constexpr (sizeof(T) == 2) {
-    moe_gemm_pick<true>(s, dim3((F + 63) / 64, E), (const bf16_t*)a, (const bf16_t*)wgu, mi, (bf16_t*)act, nullptr, R, F, d, k, E);
-    moe_gemm_pick<false>(s, dim3((d + 127) / 128, E), (const bf16_t*)act, (const bf16_t*)wdown, mi, nullptr, y, R, d, F, k, E);
+    moe_gemm_pick<true>(s, (const bf16_t*)a, (const bf16_t*)wgu, mi, (bf16_t*)act, nullptr, R, F, d, k, E);
+    moe_gemm_pick<false>(s, (const bf16_t*)act, (const bf16_t*)wdown, mi, nullptr, y, R, d, F, k, E);
   } else {
     hipLaunchKernelGGL(k_moe_gu_f32, dim3(P, (F + 15) / 16), dim3(256), 0, s, a, wgu, mi.sel_e, mi.pair, act, F, d, k);
     hipLaunchKernelGGL(k_moe_down_f32, dim3(P, (d + 15) / 16), dim3(256), 0, s, act, wdown, mi.sel_e, mi.pair, mi.sel_p,

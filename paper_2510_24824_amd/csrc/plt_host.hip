@@ -777,6 +777,11 @@ extern "C" int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, c
   return PLT_OK;
 }
 
+extern "C" int64_t plt_moe_weight_index(int32_t n, int32_t k, int32_t K) {
+  if (n < 0 || k < 0 || K < 32 || (K & 31) || k >= K) return -1;
+  return (int64_t)moe_wtile_index(n, k, K);
+}
+
 extern "C" size_t plt_moe_scratch_bytes(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32_t k) {
   if ((dtype != PLT_F32 && dtype != PLT_BF16) || R < 1 || d < 1 || F < 1 || E < 1 || E > 256 || k < 1 || k > E || k > 32) {
     fail(PLT_EINVAL, "plt_moe_scratch_bytes: bad argument"); return 0;

@@ -167,12 +167,20 @@ void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, 
 int gemm_bf16_splits_any(int M, int N, int K);
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
 
+// Expert matrices [N][K] of bf16 models are stored strip by strip (16 rows) in the order the grouped GEMM's
+// matrix-core loads consume them: [strip][32-wide k chunk][lane = 16 g + m][8 elements], where lane (m, g)
+// holds row 16*strip + m, columns 32*chunk + 8 g ..: one wavefront load is one contiguous KiB and a
+// strip is one contiguous stream.  N is a multiple of 16 and K of 32.
+__host__ __device__ inline size_t moe_wtile_index(int n, int k, int K) {
+  return ((size_t)(n >> 4) * (K >> 5) + (k >> 5)) * 512 + (size_t)((((k >> 3) & 3) * 16 + (n & 15)) * 8 + (k & 7));
+}
 // moe.hip : mixture-of-experts feed-forward.  Index arrays of one call (device): the selected experts and
 // their probabilities per row, the (row, slot) pairs sorted by expert and every expert's span in that list.
 struct MoeIndex { int32_t* sel_e; float* sel_p; int32_t* pair; int32_t* off; };
 size_t moe_index_bytes(int R, int k, int E);
 MoeIndex moe_index_carve(void* base, int R, int k, int E);
-// a [R, d] normed rows; router [E, d]; wgu [E, 2F, d] (per expert: gate rows, then up rows); wdown [E, d, F];
+// a [R, d] normed rows; router [E, d]; wgu [E, 2F, d] (per expert: gate rows, then up rows); wdown [E, d, F]
+// (bf16: every expert matrix in the strip order of moe_wtile_index; float: row-major);
 // act: scratch [R*k, F]; y: k slabs [k][R][d] (slab s, row r = p * the output of row r's s-th expert)
 template <typename T>
 void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, const T* wdown, T* act, float* y,

@@ -159,3 +159,24 @@ def test_k_cache_layout_is_a_tiling_in_matrix_core_load_order():
                             assert list(idx[key, f0:f0 + c]) == list(range(base, base + c))
     assert lib.plt_attn_k_index(B.PLT_F32, 5, 7, 64) == 5 * 64 + 7
     assert lib.plt_attn_k_index(B.PLT_BF16, 0, 64, 64) == -1 and lib.plt_attn_k_index(9, 0, 0, 64) == -1
+
+
+def test_expert_weight_layout_is_a_permutation_in_strip_order():
+    """plt_moe_weight_index: a bijection on [0, N*K); a strip of 16 rows is one contiguous run, and inside it
+    lane (m, g) of k chunk c holds row m, columns 32 c + 8 g .. + 7 as 8 consecutive elements.  The
+    binding's host-side packing is the same permutation."""
+    lib = B.lib()
+    N, K = 48, 96
+    idx = np.array([[lib.plt_moe_weight_index(n, k, K) for k in range(K)] for n in range(N)])
+    assert sorted(idx.reshape(-1)) == list(range(N * K))
+    for strip in range(N // 16):
+        blk = idx[strip * 16:(strip + 1) * 16]
+        assert blk.min() == strip * 16 * K and blk.max() == (strip + 1) * 16 * K - 1
+    for (n, k) in [(0, 0), (5, 40), (17, 95), (47, 64)]:
+        lane = ((k >> 3) & 3) * 16 + (n & 15)
+        assert idx[n, k] == ((n >> 4) * (K >> 5) + (k >> 5)) * 512 + lane * 8 + (k & 7)
+    w = np.arange(2 * N * K, dtype=np.float32).reshape(2, N, K)
+    t = B.moe_tile_weights(w)
+    for e in range(2):
+        assert np.array_equal(t[e].reshape(-1)[idx], w[e])
+    assert lib.plt_moe_weight_index(0, 0, 48) == -1 and lib.plt_moe_weight_index(0, 96, 96) == -1

@@ -39,6 +39,9 @@ CASES = [
     (B.PLT_BF16,  96,  256,  128,  16, 2, 0.05, 0.6),  # skewed router: crowded and empty experts
     (B.PLT_BF16,  7,   128,  64,   1,  1, 0.05, 0.0),  # one expert: p = 1, the dense feed-forward
     (B.PLT_BF16,  1,   2048, 1024, 64, 8, 0.02, 0.0),  # a single row
+    (B.PLT_BF16,  70,  128,  64,  100, 4, 0.05, 0.0),  # more than 64 experts (two counters per lane in the sort)
+    (B.PLT_F32,   33,  64,   32,  200, 3, 0.1,  0.0),  # more than 128 experts
+    (B.PLT_BF16,  2100, 128, 64,   8,  2, 0.05, 0.0),  # prefill-sized row count: several chunks per wave in the sort
 ]
 
 
