@@ -75,6 +75,12 @@ def fill_weights_on_device(B, cfg, seed):
     return blob
 
 
+def with_layers(shape, n_layers):
+    """The same per-layer shape at another depth."""
+    import dataclasses
+    return dataclasses.replace(shape, n_layers=n_layers)
+
+
 def moe_untile(t):
     """Inverse of the blob's strip order of bf16 expert matrices (binding.moe_tile_weights): [..., N, K] row-major."""
     *lead, N, K = t.shape
@@ -603,6 +609,33 @@ def main():
         del gblob
         torch.cuda.empty_cache()
         out["dense_gqa_shape"] = gq
+        # ---- the paper's open-source mixture-of-experts recipe: 16 layers, hidden 2048, 16 heads of 128, 64 SwiGLU
+        # experts of hidden 1024 each, 8 per token (about 1B active / 7B total parameters)
+        mo = {}
+        mshape = synth.PLT_MOE_1B7B
+        mblob = fill_weights_on_device(B, B.make_config(mshape, dtype=B.PLT_BF16), SEED + 4)
+        for bn in (4, 16, Bn):
+            mtok = torch.randint(0, mshape.vocab, (bn,), generator=g, device="cuda", dtype=torch.int32)
+            row = {}
+            for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
+                                   ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2)]:
+                cm = B.make_config(mshape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
+                mm = B.Model(cm, mblob)
+                km = B.KV(mm, bn, N)
+                fill_kv_random(B, km, g)
+                row[name] = time_steps(km, pos, mtok, 2, max(8, args.steps // 2))
+                km.close(); mm.close(); del km
+                torch.cuda.empty_cache()
+            row["latency_vs_nonlooped"] = {k: row[k] / row["nonlooped_L1"] for k in ("plt_L2", "plt_L3", "vanilla_loop_L2")}
+            mo["batch_%d_ms_per_step" % bn] = row
+            log(f"[bench] MoE 8-of-64 shape, batch {bn}: non-looped {row['nonlooped_L1']:.3f} ms, PLT-2 {row['plt_L2']:.3f}, "
+                f"PLT-3 {row['plt_L3']:.3f}, vanilla loop 2 {row['vanilla_loop_L2']:.3f}")
+        mo["expert_weight_bytes_per_layer"] = 64 * 3 * mshape.ffn_hidden * mshape.d_model * 2
+        mo["workload"] = ("16 layers, d=2048, 16 heads x 128, 64 SwiGLU experts of hidden 1024 (8 per row), vocab 50304, "
+                          "%d-token context, bf16 caches" % N)
+        del mblob
+        torch.cuda.empty_cache()
+        out["moe_shape"] = mo
 
     if args.sweep:
         out["serving_sweep"] = bench_sweep(B, shape, blob, g)

@@ -17,7 +17,7 @@ def oracle_step(shape, cfg, weights_host, exports, carry, token, pos):
     fp8 = cfg.kv_dtype == B.PLT_FP8_E4M3
     osh = O.OracleShape(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                         shape.ffn_hidden, shape.vocab, cfg.n_loops, cfg.window, shape.rope_theta, shape.norm_eps,
-                        shape.tie_embeddings)
+                        shape.tie_embeddings, n_experts=cfg.n_experts, top_k=cfg.top_k)
     orc = O.PLTOracle(osh, weights_host, kv_bf16=not fp8, kv_fp8=fp8)
     orc.kv = O.RingKV(orc._store, osh, pos + 1)
     for m, e in enumerate(exports):
@@ -26,6 +26,7 @@ def oracle_step(shape, cfg, weights_host, exports, carry, token, pos):
             orc.kv.kr[l, m] = e["k_ring"][l].transpose(1, 0, 2); orc.kv.vr[l, m] = e["v_ring"][l].transpose(1, 0, 2)
     orc.carry = carry.astype(np.float64).copy(); orc.pos = pos; orc.trace = []
     nxt, lg = orc.clp_decode_step(int(token))
+    oracle_step.route_margins = list(orc.route_margins)     # mixture-of-experts models: the step's routing gaps
     return nxt, lg, orc.trace[-1]
 
 
@@ -127,4 +128,43 @@ def test_decode_step_160_rows_sampled():
     rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
     print(f"logits max-abs {err:.3e}; hidden max rel {rel_h:.3e}")
     assert err <= 2e-2 and rel_h <= 2e-2, (err, rel_h)
+    kv.close(); model.close()
+
+
+def test_decode_step_moe_8_of_64_batch64_ctx2048_sampled():
+    """The paper's open-source mixture-of-experts recipe per layer (hidden 2048, 16 heads of 128, 64 SwiGLU
+    experts of hidden 1024, 8 per token), two layers deep so that the host copy of the weights stays small;
+    batch 64 x L = 2 at a 2048-token context built by plt_prefill (which routes 16k rows per chunk through the
+    same grouped kernels).  Sampled sequences are recomputed by the oracle from the exported state.  A
+    sequence that disagrees while its smallest routing gap in this step is within reach of bf16 rounding is
+    reported and skipped; at least two of the three samples must agree."""
+    shape = bench.with_layers(synth.PLT_MOE_1B7B, 2)
+    Bn, N = 64, 2048
+    pos = N - 1
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=2, window=64)
+    blob = bench.fill_weights_on_device(B, cfg, bench.SEED)
+    model = B.Model(cfg, blob)
+    kv = B.KV(model, Bn, N)
+    g = torch.Generator(device="cuda"); g.manual_seed(bench.SEED + 3)
+    prompt = torch.randint(0, shape.vocab, (Bn, pos), generator=g, device="cuda", dtype=torch.int32)
+    nxt, _ = kv.prefill(prompt, want_logits=False)
+    sample = [0, 29, 63]
+    state = {b: ([kv.export(b, m, pos) for m in range(shape.n_layers)], kv.get_carry()[b], int(nxt[b].item())) for b in sample}
+    n1, lg1 = kv.decode_step(nxt.clone())
+    hidden = kv.get_hidden()
+    wh = bench.weights_to_host(B, cfg, blob)
+    clear = 0
+    for b in sample:
+        exports, carry, token = state[b]
+        o_next, o_lg, o_hid = oracle_step(shape, cfg, wh, exports, carry, token, pos)
+        gap = min(oracle_step.route_margins)
+        err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
+        rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
+        print(f"seq {b}: smallest routing gap {gap:.3e}; logits max-abs {err:.3e}; hidden max rel {rel_h:.3e}")
+        ok = err <= 2e-2 and rel_h <= 2e-2
+        if not ok and gap < 4e-3:      # router logits are ~N(0, 0.9); bf16 activations move them by ~2e-3
+            continue
+        assert ok, (b, err, rel_h, gap)
+        clear += 1
+    assert clear >= 2
     kv.close(); model.close()
