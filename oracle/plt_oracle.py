@@ -15,6 +15,7 @@ Every function cites the passage of the paper (arxiv 2510.24824) it follows:
   Sec. 2.2.2  first-loop KV sharing, window of the most recent w entries -> RingKV
   Table 1 rows 3 and 4 (ablations: CLP with per-loop KV; CLP + KV share without the window) -> variant=
   Appendix, "MoE Models Recipe" (SwiGLU experts, k of E experts per token)              -> moe_route / moe_ffn
+  Inference efficiency evaluation recipe ("W4A8 quantization of linear layers")         -> mx_quantize / mx_linear
 
 Where the paper is silent the following readings are taken (each also listed in the
 design notes of the repository):
@@ -35,6 +36,18 @@ design notes of the repository):
     (equal p: lowest index first) and their outputs are summed with weights p_e as they are --
     the k selected probabilities are NOT renormalised to sum to one; no shared expert, no bias
 
+  * low-bit linear layers (w_mx=True).  The paper serves its models with 4-bit weights and 8-bit
+    activations in the linear layers and names no format.  Reading taken: the OCP microscaling
+    formats.  A tensor is cut into blocks of 32 consecutive elements along the contraction axis; a
+    block stores a shared power-of-two scale X = 2^(floor(log2(max |v|)) - emax) (emax = largest
+    exponent of the element format; an all-zero block: 2^-127) and 32 elements v / X rounded to the
+    element format, nearest even, saturating.  Weights: element format e2m1 (values 0, 0.5, 1, 1.5, 2,
+    3, 4, 6 and their negatives; emax 2), quantised once from the bf16 weights.  Activations: element
+    format e4m3 (emax 8), quantised where they enter a projection (the normed rows, the attention
+    output, the SwiGLU product).  A projection is the exact product of the two dequantised operands.
+    The four per-layer projections (QKV, output, gate/up, down) are quantised; embedding, classifier
+    head, norms, gate vector and every other operation keep their precision.
+
 Precision: float64 everywhere.  With kv_bf16=True the K and V entries are rounded to
 bfloat16 when they are stored (the device keeps its caches in bfloat16), nothing else is.
 With kv_fp8=True they are instead rounded to the 8-bit float format e4m3 (4 exponent bits, 3
@@ -42,7 +55,8 @@ mantissa bits, no infinities, largest value 448; the OCP "e4m3fn" format) with s
 paper serves its models with FP8 self-attention [inference efficiency evaluation recipe]; the
 reading taken here is an FP8 *storage* format for every cached K and V (after RoPE, unit scale),
 while queries, softmax weights and all sums keep full precision.
-Parity status: every function here is pinned by tests/test_oracle_pins.py.
+Parity status: every function here is pinned by tests/test_oracle_pins.py, test_oracle_moe_pins.py
+and test_oracle_mx_pins.py.
 """
 from __future__ import annotations
 
@@ -51,7 +65,7 @@ import numpy as np
 
 __all__ = ["OracleShape", "PLTOracle", "rmsnorm", "rope", "softmax_attend", "gate_merge",
            "gated_attention_row", "decode_attention", "kv_cache_bytes", "bf16_round", "e4m3_round",
-           "swiglu_ffn", "moe_route", "moe_ffn"]
+           "swiglu_ffn", "moe_route", "moe_ffn", "e2m1_round", "mx_quantize", "mx_dequantize", "mx_linear"]
 
 
 # ----------------------------------------------------------------------------- helpers
@@ -78,6 +92,53 @@ def e4m3_round(x: np.ndarray) -> np.ndarray:
     E = np.maximum(ex - 1, -6)                  # binade of mag, clamped to the subnormal range
     step = np.ldexp(1.0, E - 3)
     return np.sign(a) * np.rint(mag / step) * step      # rint: ties to even
+
+
+def e2m1_round(x: np.ndarray) -> np.ndarray:
+    """Nearest-even rounding to the 4-bit float e2m1 (1 sign, 2 exponent bits with bias 1, 1 mantissa bit):
+    magnitudes 0, 0.5 (subnormal), 1, 1.5, 2, 3, 4, 6; saturating at +-6.  Neighbours are 0.5 apart below 2,
+    1 apart in [2, 4) and 2 apart in [4, 8)."""
+    a = np.clip(np.asarray(x, np.float64), -6.0, 6.0)
+    mag = np.abs(a)
+    _, ex = np.frexp(mag)
+    E = np.maximum(ex - 1, 0)                   # binade of mag; everything below 1 shares the subnormal step
+    step = np.ldexp(1.0, E - 1)
+    return np.sign(a) * np.minimum(np.rint(mag / step) * step, 6.0)     # rint: ties to even
+
+
+MX_BLOCK = 32
+_MX_FORMATS = {"e2m1": (2, e2m1_round), "e4m3": (8, e4m3_round)}      # element format -> (emax, rounding)
+
+
+def mx_quantize(x: np.ndarray, fmt: str):
+    """Microscaling quantisation of x[..., K] (K a multiple of 32) along the last axis.
+
+    Returns (q, e): q[..., K] the element values (on the element format's grid, float64) and
+    e[..., K/32] the integer scale exponents, so that the represented tensor is q * 2^e per block.
+    e = floor(log2(max |block|)) - emax, clamped to [-127, 127]; an all-zero block gets -127."""
+    emax, rnd = _MX_FORMATS[fmt]
+    x = np.asarray(x, np.float64)
+    K = x.shape[-1]
+    assert K % MX_BLOCK == 0
+    blk = x.reshape(*x.shape[:-1], K // MX_BLOCK, MX_BLOCK)
+    amax = np.max(np.abs(blk), axis=-1)
+    _, ex = np.frexp(amax)                      # amax = f * 2^ex, f in [0.5, 1): floor(log2(amax)) = ex - 1
+    e = np.where(amax > 0, np.clip(ex - 1 - emax, -127, 127), -127).astype(np.int64)
+    q = rnd(blk * np.ldexp(1.0, -e)[..., None])
+    return q.reshape(x.shape), e
+
+
+def mx_dequantize(q: np.ndarray, e: np.ndarray) -> np.ndarray:
+    q = np.asarray(q, np.float64)
+    blk = q.reshape(*q.shape[:-1], q.shape[-1] // MX_BLOCK, MX_BLOCK)
+    return (blk * np.ldexp(1.0, np.asarray(e))[..., None]).reshape(q.shape)
+
+
+def mx_linear(a: np.ndarray, w_q: np.ndarray, w_e: np.ndarray) -> np.ndarray:
+    """y = W_dq a_dq for one row a[K]: a is quantised to e4m3 blocks here, W [N, K] arrives quantised
+    (e2m1 element values w_q and block exponents w_e [N, K/32])."""
+    a_q, a_e = mx_quantize(a, "e4m3")
+    return mx_dequantize(w_q, w_e) @ mx_dequantize(a_q, a_e)
 
 
 class OracleShape:
@@ -300,7 +361,7 @@ class PLTOracle:
     """One sequence at a time (sequences of a batch never interact)."""
 
     def __init__(self, shape: OracleShape, weights: dict, kv_bf16: bool = False, variant: str = "plt",
-                 kv_fp8: bool = False):
+                 kv_fp8: bool = False, w_mx: bool = False):
         """variant selects the row of Table 1 that is computed (all share the cross-loop shift):
           "plt"            row 5: shared first-loop KV + gated sliding window (the method)
           "clp_share_only" row 4: non-first loops attend the shared first-loop KV only (no own K/V, no gate)
@@ -314,6 +375,14 @@ class PLTOracle:
         self._store = bf16_round if kv_bf16 else e4m3_round if kv_fp8 else (lambda a: np.asarray(a, np.float64))
         self._head = weights["emb"] if shape.tie_embeddings else weights["head"]
         self.route_margins = []     # logit gap of every routing decision taken (MoE models)
+        # low-bit linear layers: the four projections of every layer on microscaling operands
+        self.w_mx = w_mx
+        if w_mx:
+            assert shape.n_experts == 0
+            self.wq_mx = []
+            for W in weights["layers"]:
+                self.wq_mx.append({name: mx_dequantize(*mx_quantize(W[name], "e2m1"))
+                                   for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")})
 
     # -- block f: one pass of the whole layer stack for one row at position p in loop l (1-based)
     def f(self, x, p, l, kv, global_cache_id=1, plain=False):
@@ -338,6 +407,11 @@ class PLTOracle:
         for m in range(s.n_layers):
             W = self.w["layers"][m]
             a = rmsnorm(x, W["norm1"], s.norm_eps)
+            act_in = (lambda t: t)
+            if self.w_mx:                       # quantised projections: dequantised weights, e4m3-block inputs
+                W = {**W, **self.wq_mx[m]}
+                act_in = lambda t: mx_dequantize(*mx_quantize(t, "e4m3"))
+            a = act_in(a)
             q = (np.asarray(W["wq"], np.float64) @ a).reshape(Hq, D)          # Alg. 3 l.1
             k = (np.asarray(W["wk"], np.float64) @ a).reshape(Hkv, D)
             v = (np.asarray(W["wv"], np.float64) @ a).reshape(Hkv, D)
@@ -359,10 +433,14 @@ class PLTOracle:
                 for h in range(Hq):
                     y[h] = gated_attention_row(qr[h], Kg[:, h // G], Vg[:, h // G],
                                                Kl[:, h // G], Vl[:, h // G], z[h])  # Alg. 3 l.2-5
-            x = x + np.asarray(W["wo"], np.float64) @ y.reshape(Hq * D)         # Alg. 3 l.6
-            b = rmsnorm(x, W["norm2"], s.norm_eps)
+            x = x + np.asarray(W["wo"], np.float64) @ act_in(y.reshape(Hq * D))         # Alg. 3 l.6
+            b = act_in(rmsnorm(x, W["norm2"], s.norm_eps))
             if s.n_experts > 0:
                 x = x + moe_ffn(b, W, s.top_k, self.route_margins)
+            elif self.w_mx:
+                gte = np.asarray(W["w_gate"], np.float64) @ b
+                h = gte / (1.0 + np.exp(-gte)) * (np.asarray(W["w_up"], np.float64) @ b)
+                x = x + np.asarray(W["w_down"], np.float64) @ act_in(h)
             else:
                 x = x + swiglu_ffn(b, W["w_gate"], W["w_up"], W["w_down"])
         return x
