@@ -244,6 +244,41 @@ int plt_moe_ffn(int32_t dtype, int32_t R, int32_t d, int32_t F, int32_t E, int32
                 int32_t* dev_sel_e, float* dev_sel_p, void* dev_scratch, size_t scratch_bytes,
                 void* hip_stream);
 
+/* Low-bit projections [inference efficiency evaluation recipe: "W4A8 quantization of linear layers"; the
+ * paper names no format].  Reading taken: the OCP microscaling formats, which gfx950's block-scaled
+ * matrix-core instruction consumes directly.  A tensor is cut into blocks of 32 consecutive elements along
+ * the contraction axis k; a block stores one scale byte s (the power of two 2^(s - 127), with
+ * s - 127 = floor(log2(max |v|)) - emax, clamped to -127..127; an all-zero block stores 0) and 32 elements
+ * v / 2^(s - 127) rounded to the element format, nearest even, saturating:
+ *   weights      e2m1, 4 bits (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6; emax 2), two per byte, even k low nibble
+ *   activations  e4m3, 8 bits (the cache format above; emax 8)
+ * Layouts (all device memory, N % 16 == 0, K % 128 == 0):
+ *   weight codes  [N/16 strips][K/128 chunks][64 lanes][16 bytes]: lane 16 g + m of a chunk holds row m of
+ *                 the strip, k = 32 g .. 32 g + 31 of the chunk; plt_mx_weight_code_index(n, k, K) is the byte
+ *   weight scales [N/16][ceil(K/512)][64 lanes][4]: plt_mx_weight_scale_index(n, b, K) is the byte of row n,
+ *                 k block b; bytes of chunks beyond K are 0
+ *   act codes     row-major [M][K]
+ *   act scales    [M][16 * ceil(K/512)]: the byte of k block b of a row is plt_mx_act_scale_index(b)
+ *                 = 16 (b / 16) + 4 (b mod 4) + (b / 4) mod 4; bytes of blocks beyond K are 0
+ * plt_mx_quantize_weights: bf16 [N, K] row-major -> codes + scales.  plt_mx_quantize_act: float or bf16
+ * [M, K] (K % 32 == 0) -> codes + scales.  plt_gemm_mx: c [M, N] float = the exact product of the two
+ * dequantised operands, float accumulation; dev_scratch of plt_gemm_mx_scratch_bytes bytes (K-range slabs).
+ * The index functions run on the host; they return -1 for a bad argument. */
+size_t plt_mx_weight_code_bytes(int32_t N, int32_t K);
+size_t plt_mx_weight_scale_bytes(int32_t N, int32_t K);
+size_t plt_mx_act_scale_bytes(int32_t M, int32_t K);
+int64_t plt_mx_weight_code_index(int32_t n, int32_t k, int32_t K);
+int64_t plt_mx_weight_scale_index(int32_t n, int32_t b, int32_t K);
+int32_t plt_mx_act_scale_index(int32_t b);
+int plt_mx_quantize_weights(int32_t N, int32_t K, const void* dev_src_bf16, void* dev_codes, void* dev_scales,
+                            void* hip_stream);
+int plt_mx_quantize_act(int32_t dtype, int32_t M, int32_t K, const void* dev_src, void* dev_codes,
+                        void* dev_scales, void* hip_stream);
+size_t plt_gemm_mx_scratch_bytes(int32_t M, int32_t N, int32_t K);
+int plt_gemm_mx(int32_t M, int32_t N, int32_t K, const void* dev_a_codes, const void* dev_a_scales,
+                const void* dev_w_codes, const void* dev_w_scales, float* dev_c, void* dev_scratch,
+                size_t scratch_bytes, void* hip_stream);
+
 /* Plain device-to-device copy kernel (16 bytes per lane): the known-size reference for HBM
  * traffic counters and a practical bandwidth ceiling.  nbytes and both pointers must be
  * multiples of 16; the buffers must not overlap. */

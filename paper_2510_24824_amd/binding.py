@@ -68,6 +68,16 @@ _SIGS = {
     "plt_moe_weight_index": (C.c_int64, [_I, _I, _I]),
     "plt_moe_scratch_bytes": (_Z, [_I] * 6),
     "plt_moe_ffn": (C.c_int, [_I] * 6 + [_P] * 8 + [_Z, _P]),
+    "plt_mx_weight_code_bytes": (_Z, [_I, _I]),
+    "plt_mx_weight_scale_bytes": (_Z, [_I, _I]),
+    "plt_mx_act_scale_bytes": (_Z, [_I, _I]),
+    "plt_mx_weight_code_index": (C.c_int64, [_I, _I, _I]),
+    "plt_mx_weight_scale_index": (C.c_int64, [_I, _I, _I]),
+    "plt_mx_act_scale_index": (_I, [_I]),
+    "plt_mx_quantize_weights": (C.c_int, [_I, _I, _P, _P, _P, _P]),
+    "plt_mx_quantize_act": (C.c_int, [_I, _I, _I, _P, _P, _P, _P]),
+    "plt_gemm_mx_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_gemm_mx": (C.c_int, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "plt_stream_copy": (C.c_int, [_P, _P, _Z, _P]),
     "plt_stream_read": (C.c_int, [_P, _Z, _P, _Z, _P]),
     "plt_profile_enable": (C.c_int, [_P, _I]),
@@ -396,3 +406,45 @@ def moe_ffn(dtype, a, router, w_gate, w_up, w_down, top_k):
                              _ptr(sel_p), _ptr(scratch), nb, _stream()))
     torch.cuda.synchronize()
     return y.cpu().numpy(), sel_e.cpu().numpy(), sel_p.cpu().numpy()
+
+
+# ---- low-bit (microscaling) projections ----------------------------------------------------
+
+def mx_quantize_weights(w):
+    """w: bf16 device tensor [N, K] -> (e2m1 codes, e8m0 scales) uint8 device tensors in the GEMM's layout."""
+    import torch
+    N, K = w.shape
+    nc, ns = lib().plt_mx_weight_code_bytes(N, K), lib().plt_mx_weight_scale_bytes(N, K)
+    if nc == 0 or ns == 0:
+        raise PltError(-1, lib().plt_last_error().decode())
+    codes = torch.empty(nc, dtype=torch.uint8, device="cuda")
+    scales = torch.empty(ns, dtype=torch.uint8, device="cuda")
+    _check(lib().plt_mx_quantize_weights(N, K, _ptr(w.contiguous()), _ptr(codes), _ptr(scales), _stream()))
+    return codes, scales
+
+
+def mx_quantize_act(x):
+    """x: float32 or bf16 device tensor [M, K] -> (e4m3 codes [M, K], e8m0 scales [M, 16 * ceil(K / 512)])."""
+    import torch
+    M, K = x.shape
+    ns = lib().plt_mx_act_scale_bytes(M, K)
+    if ns == 0:
+        raise PltError(-1, lib().plt_last_error().decode())
+    codes = torch.empty(M, K, dtype=torch.uint8, device="cuda")
+    scales = torch.empty(M, ns // M, dtype=torch.uint8, device="cuda")
+    dt = PLT_F32 if x.dtype == torch.float32 else PLT_BF16
+    _check(lib().plt_mx_quantize_act(dt, M, K, _ptr(x.contiguous()), _ptr(codes), _ptr(scales), _stream()))
+    return codes, scales
+
+
+def gemm_mx(a_codes, a_scales, w_codes, w_scales, M, N, K):
+    """float32 [M, N] = dequantised a [M, K] times dequantised w [N, K]^T on the block-scaled matrix cores."""
+    import torch
+    c = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    nb = lib().plt_gemm_mx_scratch_bytes(M, N, K)
+    if nb == 0:
+        raise PltError(-1, lib().plt_last_error().decode())
+    scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    _check(lib().plt_gemm_mx(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), _ptr(c), _ptr(scratch), nb,
+                             _stream()))
+    return c

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libplt.so")
-SOURCES = ["plt_host.hip", "elem_kernels.hip", "gemm_f32.hip", "gemm_mfma.hip", "gemm_big.hip", "moe.hip", "attn_f32.hip", "attn_mfma.hip", "attn_prefill.hip"]
+SOURCES = ["plt_host.hip", "elem_kernels.hip", "gemm_f32.hip", "gemm_mfma.hip", "gemm_big.hip", "moe.hip", "gemm_mx.hip", "attn_f32.hip", "attn_mfma.hip", "attn_prefill.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-FP32 instructions are kept out of every kernel of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -819,6 +819,74 @@ extern "C" int plt_moe_ffn(int32_t dtype, int32_t R, int32_t d, int32_t F, int32
   return PLT_OK;
 }
 
+// ---- low-bit (microscaling) projection hooks ----
+static bool mx_shape_ok(int N, int K) { return N >= 16 && (N % 16) == 0 && K >= 128 && (K % 128) == 0; }
+extern "C" size_t plt_mx_weight_code_bytes(int32_t N, int32_t K) {
+  if (!mx_shape_ok(N, K)) { fail(PLT_EINVAL, "plt_mx_weight_code_bytes: N must be a multiple of 16, K of 128"); return 0; }
+  return (size_t)N * K / 2;
+}
+extern "C" size_t plt_mx_weight_scale_bytes(int32_t N, int32_t K) {
+  if (!mx_shape_ok(N, K)) { fail(PLT_EINVAL, "plt_mx_weight_scale_bytes: N must be a multiple of 16, K of 128"); return 0; }
+  return mx_wscale_bytes(N, K);
+}
+extern "C" size_t plt_mx_act_scale_bytes(int32_t M, int32_t K) {
+  if (M < 1 || K < 32 || (K % 32)) { fail(PLT_EINVAL, "plt_mx_act_scale_bytes: bad shape"); return 0; }
+  return (size_t)M * mx_ascale_row_bytes(K);
+}
+extern "C" int64_t plt_mx_weight_code_index(int32_t n, int32_t k, int32_t K) {
+  if (n < 0 || k < 0 || k >= K || K % 128) return -1;
+  return (int64_t)mx_wcode_index(n, k, K);
+}
+extern "C" int64_t plt_mx_weight_scale_index(int32_t n, int32_t b, int32_t K) {
+  if (n < 0 || b < 0 || b * 32 >= K || K % 128) return -1;
+  return (int64_t)mx_wscale_index(n, b, K);
+}
+extern "C" int32_t plt_mx_act_scale_index(int32_t b) { return b < 0 ? -1 : mx_ascale_index(b); }
+
+extern "C" int plt_mx_quantize_weights(int32_t N, int32_t K, const void* src_bf16, void* codes, void* scales, void* hip_stream) {
+  if (!mx_shape_ok(N, K) || !src_bf16 || !codes || !scales) return fail(PLT_EINVAL, "plt_mx_quantize_weights: bad argument (N %% 16, K %% 128)");
+  if ((((uintptr_t)codes) | ((uintptr_t)scales) | ((uintptr_t)src_bf16)) & 15) return fail(PLT_EINVAL, "plt_mx_quantize_weights: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  HIP_TRY(hipMemsetAsync(scales, 0, mx_wscale_bytes(N, K), s));      // scale bytes of chunks beyond K stay 0
+  launch_mx_quant_w(s, (const bf16_t*)src_bf16, (uint8_t*)codes, (uint8_t*)scales, N, K);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+extern "C" int plt_mx_quantize_act(int32_t dtype, int32_t M, int32_t K, const void* src, void* codes, void* scales, void* hip_stream) {
+  if ((dtype != PLT_F32 && dtype != PLT_BF16) || M < 1 || K < 32 || (K % 32) || !src || !codes || !scales)
+    return fail(PLT_EINVAL, "plt_mx_quantize_act: bad argument (K %% 32)");
+  if ((((uintptr_t)codes) | ((uintptr_t)src)) & 15) return fail(PLT_EINVAL, "plt_mx_quantize_act: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (dtype == PLT_F32) launch_mx_quant_a<float>(s, (const float*)src, (uint8_t*)codes, (uint8_t*)scales, M, K);
+  else launch_mx_quant_a<bf16_t>(s, (const bf16_t*)src, (uint8_t*)codes, (uint8_t*)scales, M, K);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+extern "C" size_t plt_gemm_mx_scratch_bytes(int32_t M, int32_t N, int32_t K) {
+  if (M < 1 || !mx_shape_ok(N, K)) { fail(PLT_EINVAL, "plt_gemm_mx_scratch_bytes: bad shape"); return 0; }
+  return align256((size_t)gemm_mx_splits(K) * M * N * 4);
+}
+extern "C" int plt_gemm_mx(int32_t M, int32_t N, int32_t K, const void* a_codes, const void* a_scales, const void* w_codes,
+                           const void* w_scales, float* c, void* scratch, size_t scratch_bytes, void* hip_stream) {
+  if (M < 1 || M > 128 * 65535 || !mx_shape_ok(N, K) || !a_codes || !a_scales || !w_codes || !w_scales || !c)
+    return fail(PLT_EINVAL, "plt_gemm_mx: bad argument (N %% 16, K %% 128)");
+  if ((((uintptr_t)a_codes) | ((uintptr_t)a_scales) | ((uintptr_t)w_codes) | ((uintptr_t)w_scales) | ((uintptr_t)c)) & 15)
+    return fail(PLT_EINVAL, "plt_gemm_mx: pointers must be 16-byte aligned");
+  hipStream_t s = (hipStream_t)hip_stream;
+  const int S = gemm_mx_splits(K);
+  if (S == 1) {
+    launch_gemm_mx(s, (const uint8_t*)a_codes, (const uint8_t*)a_scales, (const uint8_t*)w_codes, (const uint8_t*)w_scales, c, M, N, K);
+  } else {
+    if (!scratch || scratch_bytes < plt_gemm_mx_scratch_bytes(M, N, K)) return fail(PLT_ENOMEM, "plt_gemm_mx: scratch too small");
+    launch_gemm_mx(s, (const uint8_t*)a_codes, (const uint8_t*)a_scales, (const uint8_t*)w_codes, (const uint8_t*)w_scales,
+                   (float*)scratch, M, N, K);
+    const size_t n = (size_t)M * N;
+    hipLaunchKernelGGL(k_sum_slabs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)scratch, c, S, n);
+  }
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
 // plain copy, 16 bytes per lane per iteration: the reference point for HBM counters and the
 // practical bandwidth ceiling the attention kernel is compared with
 __global__ __launch_bounds__(256) void k_stream_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {

@@ -174,6 +174,29 @@ void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float
 __host__ __device__ inline size_t moe_wtile_index(int n, int k, int K) {
   return ((size_t)(n >> 4) * (K >> 5) + (k >> 5)) * 512 + (size_t)((((k >> 3) & 3) * 16 + (n & 15)) * 8 + (k & 7));
 }
+// ---- microscaling (MX) operands of the low-bit projections: see gemm_mx.hip for the formats
+// byte that holds weight element (n, k) of an [N, K] matrix (low nibble: even k): strips of 16 rows, chunks of
+// 128 k, inside a chunk lane 16 g + m holds row m, k = 32 g .. 32 g + 31 in 16 bytes
+__host__ __device__ inline size_t mx_wcode_index(int n, int k, int K) {
+  return ((size_t)(n >> 4) * (K >> 7) + (k >> 7)) * 1024 + (size_t)((((k >> 5) & 3) * 16 + (n & 15)) * 16 + ((k & 31) >> 1));
+}
+// scale byte of weight row n, k block b (32 k): [strip][group of 4 chunks][lane][chunk in group]
+__host__ __device__ inline size_t mx_wscale_index(int n, int b, int K) {
+  const int chunk = b >> 2, g = b & 3, n_cgrp = ((K >> 7) + 3) >> 2;
+  return (((size_t)(n >> 4) * n_cgrp + (chunk >> 2)) * 64 + g * 16 + (n & 15)) * 4 + (chunk & 3);
+}
+inline size_t mx_wscale_bytes(int N, int K) { return (size_t)(N >> 4) * ((((K >> 7) + 3) >> 2)) * 256; }
+// scale byte of k block b inside one activation row: groups of 16 blocks stored [g = b mod 4][c = (b / 4) mod 4]
+__host__ __device__ inline int mx_ascale_index(int b) { return (b >> 4) * 16 + (b & 3) * 4 + ((b >> 2) & 3); }
+__host__ __device__ inline int mx_ascale_row_bytes(int K) { return ((K + 511) >> 9) * 16; }
+// gemm_mx.hip
+void launch_mx_quant_w(hipStream_t s, const bf16_t* w, uint8_t* codes, uint8_t* scales, int N, int K);
+template <typename T>
+void launch_mx_quant_a(hipStream_t s, const T* a, uint8_t* codes, uint8_t* scales, int M, int K);
+int gemm_mx_splits(int K);
+void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
+                    int M, int N, int K);
+
 // moe.hip : mixture-of-experts feed-forward.  Index arrays of one call (device): the selected experts and
 // their probabilities per row, the (row, slot) pairs sorted by expert and every expert's span in that list.
 struct MoeIndex { int32_t* sel_e; float* sel_p; int32_t* pair; int32_t* off; };

@@ -103,6 +103,13 @@ def e4m3_from_bits(b: np.ndarray) -> np.ndarray:
     return np.where(b & 0x80, -v, v).astype(np.float32).reshape(b.shape)
 
 
+def e2m1_from_bits(b: np.ndarray) -> np.ndarray:
+    """Values of 4-bit e2m1 codes (bit 3 sign; magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6 by code 0..7)."""
+    b = np.asarray(b, np.uint8)
+    v = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], np.float32)[b & 7]
+    return np.where(b & 8, -v, v).astype(np.float32)
+
+
 def round_to_e4m3(x: np.ndarray) -> np.ndarray:
     return e4m3_from_bits(e4m3_bits(x))
 

@@ -1,0 +1,128 @@
+"""Low-bit (microscaling) projections: the device quantisers and the block-scaled GEMM against the oracle.
+
+The quantisers decide integers (codes, scale bytes) from floats; both sides get the same float32 / bf16
+inputs, and every step of the rule (power-of-two scaling, rounding to the element grid) is exact in float,
+so codes and scales must be bit-identical.  The GEMM multiplies the codes exactly (products of grid values)
+and accumulates in float: it is compared with the float64 product of the dequantised operands within an
+element-wise bound from the accumulation alone."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import plt_oracle as O
+from paper_2510_24824_amd import binding as B, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def decode_weights(codes, scales, N, K):
+    """Device layout -> (element values [N, K], exponents [N, K/32]) using the layout's closed form."""
+    codes, scales = codes.cpu().numpy(), scales.cpu().numpy()
+    n = np.arange(N)[:, None]; k = np.arange(K)[None, :]
+    byte = ((n >> 4) * (K >> 7) + (k >> 7)) * 1024 + (((k >> 5) & 3) * 16 + (n & 15)) * 16 + ((k & 31) >> 1)
+    nib = np.where(k & 1, codes[byte] >> 4, codes[byte] & 15)
+    b = np.arange(K // 32)[None, :]
+    n_cgrp = ((K >> 7) + 3) >> 2
+    sidx = (((n >> 4) * n_cgrp + (b >> 4)) * 64 + (b & 3) * 16 + (n & 15)) * 4 + ((b >> 2) & 3)
+    return synth.e2m1_from_bits(nib).astype(np.float64), scales[sidx].astype(np.int64) - 127
+
+
+def decode_acts(codes, scales, M, K):
+    codes, scales = codes.cpu().numpy(), scales.cpu().numpy()
+    b = np.arange(K // 32)
+    sidx = (b >> 4) * 16 + (b & 3) * 4 + ((b >> 2) & 3)
+    return synth.e4m3_from_bits(codes).astype(np.float64), scales[:, sidx].astype(np.int64) - 127
+
+
+def test_layout_closed_forms_match_the_abi():
+    l = B.lib()
+    K = 640
+    for n, k in [(0, 0), (17, 33), (31, 639), (5, 128), (40, 511)]:
+        want = ((n >> 4) * (K >> 7) + (k >> 7)) * 1024 + (((k >> 5) & 3) * 16 + (n & 15)) * 16 + ((k & 31) >> 1)
+        assert l.plt_mx_weight_code_index(n, k, K) == want
+        b = k >> 5
+        assert l.plt_mx_weight_scale_index(n, b, K) == (((n >> 4) * 2 + (b >> 4)) * 64 + (b & 3) * 16 + (n & 15)) * 4 + ((b >> 2) & 3)
+    assert [l.plt_mx_act_scale_index(b) for b in (0, 1, 4, 5, 15, 16, 21)] == [0, 4, 1, 5, 15, 16, 16 + 4 + 1]
+    assert l.plt_mx_weight_code_bytes(48, 640) == 48 * 320 and l.plt_mx_weight_scale_bytes(48, 640) == 3 * 2 * 256
+    assert l.plt_mx_act_scale_bytes(7, 640) == 7 * 32
+    assert l.plt_mx_weight_code_bytes(40, 640) == 0 and l.plt_mx_weight_code_bytes(48, 600) == 0
+
+
+def _weights(N, K, seed):
+    w = synth.normal((N, K), seed, 70, 0.02, True)
+    w[0, :32] = 0.0                                         # an all-zero block
+    w[1, :64] *= 2.0 ** 40; w[2, :64] *= 2.0 ** -60         # large and tiny blocks
+    # exact ties of the e2m1 grid at block scale 1 (maximum 6 -> exponent 0): 0.25 .75 1.25 1.75 2.5 3.5 5
+    w[3, :32] = 0.0; w[3, :9] = [6.0, 0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0, -2.5]
+    w[4, :32] = 0.0; w[4, :3] = [7.5, -7.0, 0.3]            # 7.5 and 7 exceed the largest element: saturate to 6
+    return synth.round_to_bf16(w)
+
+
+@pytest.mark.parametrize("N,K", [(48, 640), (6144, 2048), (16, 128)])
+def test_weight_quantiser_is_bit_exact(N, K):
+    w = _weights(N, K, 5)
+    codes, scales = B.mx_quantize_weights(torch.from_numpy(w).cuda().to(torch.bfloat16))
+    got_q, got_e = decode_weights(codes, scales, N, K)
+    want_q, want_e = O.mx_quantize(w, "e2m1")
+    assert np.array_equal(got_e, want_e)
+    assert np.array_equal(got_q, want_q)
+    assert list(got_q[3, :9]) == [6.0, 0.0, 1.0, 1.0, 2.0, 2.0, 4.0, 4.0, -2.0] and list(got_q[4, :2]) == [6.0, -6.0]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("M,K", [(37, 640), (128, 2048), (3, 32)])
+def test_activation_quantiser_is_bit_exact(dtype, M, K):
+    x = synth.normal((M, K), 6, 71, 1.0, dtype == torch.bfloat16)
+    x[0, :32] = 0.0
+    x[1 % M, :32] *= 1e-30
+    x[2 % M, 0] = 500.0; x[2 % M, 1] = 465.0                 # block maximum 500: exponent 0; 500 and 465 saturate to 448
+    if dtype == torch.bfloat16:
+        x = synth.round_to_bf16(x)
+    codes, scales = B.mx_quantize_act(torch.from_numpy(x).cuda().to(dtype))
+    got_q, got_e = decode_acts(codes, scales, M, K)
+    want_q, want_e = O.mx_quantize(x, "e4m3")
+    assert np.array_equal(got_e, want_e)
+    assert np.array_equal(got_q, want_q)
+    assert got_q[2 % M, 0] == 448.0 and got_q[2 % M, 1] == 448.0
+    pad = np.setdiff1d(np.arange(scales.shape[1]), [(b >> 4) * 16 + (b & 3) * 4 + ((b >> 2) & 3) for b in range(K // 32)])
+    assert np.all(scales.cpu().numpy()[:, pad] == 0)         # scale bytes of blocks beyond K
+
+
+GEMM_CASES = [(128, 6144, 2048),   # QKV projection of the 1.3B model at 64 sequences x 2 loops
+              (128, 2048, 5632),   # down projection: 5.5 K ranges (a ragged last range)
+              (64, 2048, 2048),    # output projection, 64 rows (two workgroups per compute unit)
+              (256, 11264, 2048),  # gate/up at L = 4: two row blocks, four strips per wave task
+              (37, 80, 384),       # nothing a multiple of a tile
+              (130, 2048, 1024),   # second row block with two rows
+              (1, 16, 128)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_CASES)
+def test_gemm_mx_matches_oracle(M, N, K):
+    w = synth.normal((N, K), 7, 72, 0.02, True)
+    x = synth.normal((M, K), 7, 73, 1.0, False)
+    x[:, : K // 2] *= np.exp(synth.normal((M, 1), 7, 74, 2.0, False))       # rows and halves on different scales
+    wc, ws = B.mx_quantize_weights(torch.from_numpy(w).cuda().to(torch.bfloat16))
+    ac, asc = B.mx_quantize_act(torch.from_numpy(x).cuda())
+    got = B.gemm_mx(ac, asc, wc, ws, M, N, K).cpu().numpy()
+    wq, we = O.mx_quantize(w, "e2m1")
+    aq, ae = O.mx_quantize(x, "e4m3")
+    wd, ad = O.mx_dequantize(wq, we), O.mx_dequantize(aq, ae)
+    ref = ad @ wd.T
+    # products are exact; the instruction adds the 128 products of a step after aligning them to a common
+    # exponent (a fixed-point sum narrower than a chain of float additions: measured up to 2^-17.9 of the sum
+    # of |terms|, independent of K), then the float accumulator and the slab additions round as usual
+    bound = 2.0 ** -16 * (np.abs(ad) @ np.abs(wd).T) + 1e-30
+    err = np.abs(got - ref)
+    print(f"max |c| {np.abs(ref).max():.3e}; max err {err.max():.3e}; max err / bound {np.max(err / bound):.3f}")
+    assert np.all(err <= bound)
+    # and the quantised product is close to the unquantised one (sanity of the whole chain)
+    exact = x.astype(np.float64) @ w.astype(np.float64).T
+    assert np.abs(ref - exact).max() <= 0.25 * np.abs(exact).max()
+
+
+def test_gemm_mx_rejects_bad_shapes():
+    z = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    for M, N, K in [(4, 40, 128), (4, 48, 96), (0, 48, 128)]:
+        c = torch.zeros(max(M, 1), N, device="cuda")
+        assert B.lib().plt_gemm_mx(M, N, K, B._ptr(z), B._ptr(z), B._ptr(z), B._ptr(z), B._ptr(c), B._ptr(z), z.numel(), None) == -1
