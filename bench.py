@@ -378,6 +378,59 @@ def bench_sweep(B, shape, blob, g, n_new=256, runs=2):
     return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "rows": table}
 
 
+def bench_lowbit_gemm(B, Mrows=128, reps=30):
+    """Kernel-only: the four per-layer projections of the 1.3B model as block-scaled low-bit GEMMs (MXFP4
+    weights x MXFP8 activations) next to the bf16 decode GEMM, each timed over back-to-back calls that
+    rotate through 8 weight copies (so that no call finds its weights in a cache), slab-sum kernel included."""
+    import torch
+    g = torch.Generator(device="cuda"); g.manual_seed(SEED + 9)
+    l = B.lib()
+    st = B._stream()
+
+    def timed(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record(); torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e3
+
+    out = {"rows": Mrows, "projections": {}}
+    for name, N, K in (("qkv", 6144, 2048), ("out", 2048, 2048), ("gate_up", 11264, 2048), ("down", 2048, 5632)):
+        ws = [(torch.randn(N, K, generator=g, device="cuda") * 0.02).to(torch.bfloat16) for _ in range(8)]
+        x = torch.randn(Mrows, K, generator=g, device="cuda")
+        xb = x.to(torch.bfloat16)
+        q = [B.mx_quantize_weights(w) for w in ws]
+        ac, asc = B.mx_quantize_act(x)
+        c = torch.empty(Mrows, N, device="cuda")
+        nb1 = l.plt_gemm_mx_scratch_bytes(Mrows, N, K); s1 = torch.empty(nb1, dtype=torch.uint8, device="cuda")
+        nb2 = l.plt_gemm_scratch_bytes(Mrows, N, K); s2 = torch.empty(nb2, dtype=torch.uint8, device="cuda")
+        i = [0]
+
+        def run_mx():
+            wc, wsc = q[i[0] % 8]; i[0] += 1
+            B._check(l.plt_gemm_mx(Mrows, N, K, B._ptr(ac), B._ptr(asc), B._ptr(wc), B._ptr(wsc), B._ptr(c), B._ptr(s1), nb1, st))
+
+        def run_bf():
+            w = ws[i[0] % 8]; i[0] += 1
+            B._check(l.plt_gemm(B.PLT_BF16, Mrows, N, K, B._ptr(xb), B._ptr(w), B._ptr(c), B._ptr(s2), nb2, st))
+
+        def run_q():
+            B._check(l.plt_mx_quantize_act(B.PLT_F32, Mrows, K, B._ptr(x), B._ptr(ac), B._ptr(asc), st))
+
+        t_mx, t_bf, t_q = timed(run_mx), timed(run_bf), timed(run_q)
+        out["projections"][name] = {"N": N, "K": K, "mxfp4_us": t_mx, "bf16_us": t_bf, "act_quant_us": t_q,
+                                    "mx_weight_bytes": N * K // 2 + N * K // 32, "bf16_weight_bytes": N * K * 2}
+        log(f"[bench] low-bit GEMM {name} {Mrows}x{N}x{K}: MXFP4 {t_mx:.1f} us, bf16 {t_bf:.1f} us, activation quantiser {t_q:.1f} us")
+        del ws, q
+    pr = out["projections"]
+    out["per_layer_us"] = {"mxfp4": sum(v["mxfp4_us"] for v in pr.values()), "bf16": sum(v["bf16_us"] for v in pr.values())}
+    return out
+
+
 def measure_read_ceiling(B):
     """Practical HBM read ceiling on this machine: the library's plain read-only stream kernel over 4 GiB."""
     import torch
@@ -636,6 +689,7 @@ def main():
         del mblob
         torch.cuda.empty_cache()
         out["moe_shape"] = mo
+        out["lowbit_gemm"] = bench_lowbit_gemm(B, Bn * L)
 
     if args.sweep:
         out["serving_sweep"] = bench_sweep(B, shape, blob, g)
