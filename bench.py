@@ -431,6 +431,40 @@ def bench_lowbit_gemm(B, Mrows=128, reps=30):
     return out
 
 
+def bench_moe(B, g, Bn, N, w, steps, batches):
+    """Decode steps of the paper's open-source mixture-of-experts recipe (random cache contents, fixed context)."""
+    import torch
+    from paper_2510_24824_amd import synth
+    pos = N - 1
+    # ---- the paper's open-source mixture-of-experts recipe: 16 layers, hidden 2048, 16 heads of 128, 64 SwiGLU
+    # experts of hidden 1024 each, 8 per token (about 1B active / 7B total parameters)
+    mo = {}
+    mshape = synth.PLT_MOE_1B7B
+    mblob = fill_weights_on_device(B, B.make_config(mshape, dtype=B.PLT_BF16), SEED + 4)
+    for bn in batches:
+        mtok = torch.randint(0, mshape.vocab, (bn,), generator=g, device="cuda", dtype=torch.int32)
+        row = {}
+        for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
+                               ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2)]:
+            cm = B.make_config(mshape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
+            mm = B.Model(cm, mblob)
+            km = B.KV(mm, bn, N)
+            fill_kv_random(B, km, g)
+            row[name] = time_steps(km, pos, mtok, 2, steps)
+            km.close(); mm.close(); del km
+            torch.cuda.empty_cache()
+        row["latency_vs_nonlooped"] = {k: row[k] / row["nonlooped_L1"] for k in ("plt_L2", "plt_L3", "vanilla_loop_L2")}
+        mo["batch_%d_ms_per_step" % bn] = row
+        log(f"[bench] MoE 8-of-64 shape, batch {bn}: non-looped {row['nonlooped_L1']:.3f} ms, PLT-2 {row['plt_L2']:.3f}, "
+            f"PLT-3 {row['plt_L3']:.3f}, vanilla loop 2 {row['vanilla_loop_L2']:.3f}")
+    mo["expert_weight_bytes_per_layer"] = 64 * 3 * mshape.ffn_hidden * mshape.d_model * 2
+    mo["workload"] = ("16 layers, d=2048, 16 heads x 128, 64 SwiGLU experts of hidden 1024 (8 per row), vocab 50304, "
+                      "%d-token context, bf16 caches" % N)
+    del mblob
+    torch.cuda.empty_cache()
+    return mo
+
+
 def measure_read_ceiling(B):
     """Practical HBM read ceiling on this machine: the library's plain read-only stream kernel over 4 GiB."""
     import torch
@@ -477,6 +511,8 @@ def main():
     ap.add_argument("--attn-kernel-only", action="store_true", help="only the kernel-only fused attention configuration (bf16 and e4m3 caches)")
     ap.add_argument("--prefill-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3")
     ap.add_argument("--copy-reference", action="store_true", help="only the plain copy kernel (reference for HBM traffic counters)")
+    ap.add_argument("--moe-only", action="store_true", help="only the mixture-of-experts shape (8 of 64 experts) at batch 64")
+    ap.add_argument("--lowbit-gemm-only", action="store_true", help="only the kernel-only low-bit (MXFP4 x MXFP8) GEMM comparison")
     ap.add_argument("--kv-fp8", action="store_true", help="main workload with e4m3 K/V caches (labelled variant)")
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--ctx", type=int, default=2048)
@@ -497,6 +533,13 @@ def main():
     if args.attn_kernel_only:
         print(json.dumps({"attn_kernel_only": bench_attn_kernel(B, args.steps, args.warmup),
                           "attn_kernel_only_fp8_kv": bench_attn_kernel(B, args.steps, args.warmup, fp8=True)}), flush=True)
+        return
+    if args.moe_only:
+        g0 = torch.Generator(device="cuda"); g0.manual_seed(SEED + 1)
+        print(json.dumps({"moe_shape": bench_moe(B, g0, args.batch, args.ctx, args.window, max(8, args.steps // 2), (args.batch,))}), flush=True)
+        return
+    if args.lowbit_gemm_only:
+        print(json.dumps({"lowbit_gemm": bench_lowbit_gemm(B, args.batch * args.loops)}), flush=True)
         return
     if args.prefill_only:
         cfg0 = B.make_config(shape, dtype=B.PLT_BF16)
@@ -662,33 +705,7 @@ def main():
         del gblob
         torch.cuda.empty_cache()
         out["dense_gqa_shape"] = gq
-        # ---- the paper's open-source mixture-of-experts recipe: 16 layers, hidden 2048, 16 heads of 128, 64 SwiGLU
-        # experts of hidden 1024 each, 8 per token (about 1B active / 7B total parameters)
-        mo = {}
-        mshape = synth.PLT_MOE_1B7B
-        mblob = fill_weights_on_device(B, B.make_config(mshape, dtype=B.PLT_BF16), SEED + 4)
-        for bn in (4, 16, Bn):
-            mtok = torch.randint(0, mshape.vocab, (bn,), generator=g, device="cuda", dtype=torch.int32)
-            row = {}
-            for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
-                                   ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2)]:
-                cm = B.make_config(mshape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w)
-                mm = B.Model(cm, mblob)
-                km = B.KV(mm, bn, N)
-                fill_kv_random(B, km, g)
-                row[name] = time_steps(km, pos, mtok, 2, max(8, args.steps // 2))
-                km.close(); mm.close(); del km
-                torch.cuda.empty_cache()
-            row["latency_vs_nonlooped"] = {k: row[k] / row["nonlooped_L1"] for k in ("plt_L2", "plt_L3", "vanilla_loop_L2")}
-            mo["batch_%d_ms_per_step" % bn] = row
-            log(f"[bench] MoE 8-of-64 shape, batch {bn}: non-looped {row['nonlooped_L1']:.3f} ms, PLT-2 {row['plt_L2']:.3f}, "
-                f"PLT-3 {row['plt_L3']:.3f}, vanilla loop 2 {row['vanilla_loop_L2']:.3f}")
-        mo["expert_weight_bytes_per_layer"] = 64 * 3 * mshape.ffn_hidden * mshape.d_model * 2
-        mo["workload"] = ("16 layers, d=2048, 16 heads x 128, 64 SwiGLU experts of hidden 1024 (8 per row), vocab 50304, "
-                          "%d-token context, bf16 caches" % N)
-        del mblob
-        torch.cuda.empty_cache()
-        out["moe_shape"] = mo
+        out["moe_shape"] = bench_moe(B, g, Bn, N, w, max(8, args.steps // 2), (4, 16, Bn))
         out["lowbit_gemm"] = bench_lowbit_gemm(B, Bn * L)
 
     if args.sweep:
