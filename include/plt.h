@@ -59,6 +59,8 @@ enum { PLT_F32 = 0, PLT_BF16 = 1 };
  * at +-448 and unit scale, when it enters a cache; attention reads the stored values exactly
  * and keeps bf16 queries / softmax weights and float statistics.  bf16 models only. */
 enum { PLT_FP8_E4M3 = 2 };
+/* Weight-only element type of the low-bit projections (e2m1 in blocks of 32 with power-of-two scales). */
+enum { PLT_MXFP4 = 3 };
 
 /* mode: which schedule / cache organisation the model object runs.                        */
 enum {
@@ -85,6 +87,10 @@ typedef struct plt_config {
   int32_t n_experts;      /* E: 0 = dense SwiGLU feed-forward; 1..256 = mixture of E SwiGLU
                              experts of hidden size ffn_hidden each [appendix, MoE recipe]  */
   int32_t top_k;          /* experts evaluated per row (1..min(E, 32)); ignored when E == 0 */
+  int32_t w_dtype;        /* 0: projections in the model dtype; PLT_MXFP4: the four per-layer projections
+                             (QKV, output, gate/up, down) on MXFP4 weights and MXFP8 activations, see
+                             "Low-bit projections" below (needs dtype == PLT_BF16, n_experts == 0, and
+                             d_model, ffn_hidden, n_heads * head_dim multiples of 128)              */
 } plt_config;
 
 typedef struct plt_model plt_model; /* opaque */
@@ -102,9 +108,13 @@ typedef struct plt_kv plt_kv;       /* opaque */
  *   expert matrix [N, K] strip by strip in matrix-core load order: element (n, k) of the matrix
  *   sits at element index plt_moe_weight_index(n, k, K) of that expert's N*K block (16-row strips;
  *   inside a strip 32-wide k chunks; inside a chunk [k/8 mod 4][n mod 16][k mod 8]), so that the
- *   grouped GEMM streams every strip as one contiguous run. */
+ *   grouped GEMM streams every strip as one contiguous run.
+ *   Low-bit models (w_dtype = PLT_MXFP4): WQKV, WO, WGU, WDOWN hold e2m1 codes (element count N*K, two per
+ *   byte) and each is followed by its scale tensor WQKV_SC, WO_SC, WGU_SC, WDOWN_SC (element count = bytes),
+ *   both in the layouts plt_mx_quantize_weights writes; embedding, head and float tensors are unchanged. */
 enum { PLT_W_EMB = 0, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO,
-       PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER };
+       PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER,
+       PLT_W_WQKV_SC, PLT_W_WO_SC, PLT_W_WGU_SC, PLT_W_WDOWN_SC };
 
 /* Total size of the weight blob in bytes (0 if the configuration is invalid). */
 size_t plt_weights_bytes(const plt_config* cfg);

@@ -15,9 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libplt.so")
 
 PLT_F32, PLT_BF16 = 0, 1
 PLT_FP8_E4M3 = 2      # cache-only element type (e4m3 bytes); q / y / weights stay bf16
+PLT_MXFP4 = 3         # weight-only element type of the low-bit projections
 PLT_MODE_CLP, PLT_MODE_VANILLA_LOOP, PLT_MODE_CLP_SHARE_ONLY, PLT_MODE_CLP_OWN_KV = 0, 2, 3, 4
 (PLT_W_EMB, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO, PLT_W_NORM2, PLT_W_WGU,
- PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER) = range(12)
+ PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER, PLT_W_WQKV_SC, PLT_W_WO_SC, PLT_W_WGU_SC,
+ PLT_W_WDOWN_SC) = range(16)
 STATUS = {0: "PLT_OK", -1: "PLT_EINVAL", -2: "PLT_ENOMEM", -3: "PLT_ECTXFULL", -4: "PLT_EHIP", -5: "PLT_ESTATE"}
 
 
@@ -32,7 +34,7 @@ class plt_config(C.Structure):
                                          "ffn_hidden", "vocab", "n_loops", "window", "dtype", "mode",
                                          "tie_embeddings")] + [("rope_theta", C.c_float), ("norm_eps", C.c_float),
                                                                ("kv_dtype", C.c_int32), ("n_experts", C.c_int32),
-                                                               ("top_k", C.c_int32)]
+                                                               ("top_k", C.c_int32), ("w_dtype", C.c_int32)]
 
 
 _P, _I, _Z = C.c_void_p, C.c_int32, C.c_size_t
@@ -109,12 +111,12 @@ def _check(rc):
         raise PltError(rc, lib().plt_last_error().decode())
 
 
-def make_config(shape, dtype=PLT_BF16, mode=PLT_MODE_CLP, n_loops=None, window=None, kv_dtype=0) -> plt_config:
+def make_config(shape, dtype=PLT_BF16, mode=PLT_MODE_CLP, n_loops=None, window=None, kv_dtype=0, w_dtype=0) -> plt_config:
     return plt_config(shape.n_layers, shape.d_model, shape.n_heads, shape.n_kv_heads, shape.head_dim,
                       shape.ffn_hidden, shape.vocab, shape.n_loops if n_loops is None else n_loops,
                       shape.window if window is None else window, dtype, mode,
                       1 if shape.tie_embeddings else 0, shape.rope_theta, shape.norm_eps, kv_dtype,
-                      getattr(shape, "n_experts", 0), getattr(shape, "top_k", 0))
+                      getattr(shape, "n_experts", 0), getattr(shape, "top_k", 0), w_dtype)
 
 
 def _stream():
@@ -161,13 +163,22 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
         else:
             host[off:off + 4 * n] = arr.view(np.uint8)
 
+    mx = cfg.w_dtype == PLT_MXFP4
+    later = []          # low-bit projections: quantised on the device, straight into the blob
+
+    def put_w(layer, which, which_sc, arr):
+        if mx:
+            later.append((layer, which, which_sc, np.ascontiguousarray(arr, np.float32)))
+        else:
+            put(layer, which, arr, True)
+
     put(0, PLT_W_EMB, weights["emb"], True)
     for m, lw in enumerate(weights["layers"]):
         put(m, PLT_W_NORM1, lw["norm1"], False)
-        put(m, PLT_W_WQKV, np.concatenate([lw["wq"], lw["wk"], lw["wv"]], axis=0), True)
+        put_w(m, PLT_W_WQKV, PLT_W_WQKV_SC, np.concatenate([lw["wq"], lw["wk"], lw["wv"]], axis=0))
         put(m, PLT_W_GATE_W, lw["gate_w"], False)
         put(m, PLT_W_GATE_B, lw["gate_b"], False)
-        put(m, PLT_W_WO, lw["wo"], True)
+        put_w(m, PLT_W_WO, PLT_W_WO_SC, lw["wo"])
         put(m, PLT_W_NORM2, lw["norm2"], False)
         if cfg.n_experts > 0:       # expert axis first; per expert its gate rows, then its up rows
             tile = moe_tile_weights if cfg.dtype == PLT_BF16 else (lambda x: x)
@@ -175,12 +186,25 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
             put(m, PLT_W_WGU, tile(np.concatenate([lw["w_gate"], lw["w_up"]], axis=1)), True)
             put(m, PLT_W_WDOWN, tile(np.asarray(lw["w_down"])), True)
         else:
-            put(m, PLT_W_WGU, np.concatenate([lw["w_gate"], lw["w_up"]], axis=0), True)
-            put(m, PLT_W_WDOWN, lw["w_down"], True)
+            put_w(m, PLT_W_WGU, PLT_W_WGU_SC, np.concatenate([lw["w_gate"], lw["w_up"]], axis=0))
+            put_w(m, PLT_W_WDOWN, PLT_W_WDOWN_SC, lw["w_down"])
     put(0, PLT_W_NORM_F, weights["norm_f"], False)
     if not cfg.tie_embeddings:
         put(0, PLT_W_HEAD, weights["head"], True)
-    return torch.from_numpy(host).to(device)
+    blob = torch.from_numpy(host).to(device)
+    for layer, which, which_sc, arr in later:
+        quantize_into_blob(cfg, blob, layer, which, which_sc, torch.from_numpy(arr).to(device).to(torch.bfloat16))
+    return blob
+
+
+def quantize_into_blob(cfg, blob, layer, which, which_sc, w_bf16):
+    """Low-bit models: quantises one bf16 projection matrix [N, K] (device) into its two blob tensors."""
+    N, K = w_bf16.shape
+    off, n = weights_offset(cfg, layer, which)
+    off_sc, n_sc = weights_offset(cfg, layer, which_sc)
+    assert n == N * K and n_sc == lib().plt_mx_weight_scale_bytes(N, K), (which, n, N, K)
+    _check(lib().plt_mx_quantize_weights(N, K, _ptr(w_bf16.contiguous()), C.c_void_p(blob.data_ptr() + off),
+                                         C.c_void_p(blob.data_ptr() + off_sc), _stream()))
 
 
 class Model:

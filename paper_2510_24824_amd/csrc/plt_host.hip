@@ -28,6 +28,7 @@ struct LayerW {
   const float* norm1; const void* wqkv; const float* gate_w; const float* gate_b;
   const void* wo; const float* norm2; const void* wgu; const void* wdown;
   const void* router;   // mixture-of-experts models only
+  const uint8_t *wqkv_sc, *wo_sc, *wgu_sc, *wdown_sc;   // low-bit models: block scales of the four projections
 };
 struct ProfRec { hipEvent_t a, b; int klass; };
 struct plt_model {
@@ -41,6 +42,7 @@ struct plt_model {
   int es;   // element size of the model dtype
   int kes;  // element size of the caches (es, or 1 for e4m3 caches)
   bool kv8; // caches hold e4m3 bytes
+  bool mx;  // the four per-layer projections run on MXFP4 weights and MXFP8 activations
   double* inv_freq = nullptr;   // device [D/2]: rotary frequencies theta^(-2j/D), computed in double
 };
 struct plt_kv {
@@ -55,6 +57,7 @@ struct plt_kv {
   float* x; void* a; float* gout; size_t gout_elems; void* q; float* z; void* y; void* act;
   float* carry; int32_t* pos_dev; void* attn_scratch; size_t attn_scratch_bytes;
   void* moe_idx;       // mixture-of-experts models: routing lists of one pass (moe_index_bytes)
+  uint8_t *a_codes, *a_scales;   // low-bit models: the quantised input of the next projection
   float* arg_v; int* arg_i;   // argmax chunk winners
 };
 
@@ -76,6 +79,13 @@ static bool cfg_valid(const plt_config* c, const char** why) {
   if (!(c->rope_theta > 0.f) || !(c->norm_eps >= 0.f)) { *why = "bad rope_theta / norm_eps"; return false; }
   if (c->kv_dtype != 0 && c->kv_dtype != PLT_FP8_E4M3) { *why = "unknown kv_dtype"; return false; }
   if (c->kv_dtype == PLT_FP8_E4M3 && c->dtype != PLT_BF16) { *why = "e4m3 caches need dtype PLT_BF16"; return false; }
+  if (c->w_dtype != 0 && c->w_dtype != PLT_MXFP4) { *why = "unknown w_dtype"; return false; }
+  if (c->w_dtype == PLT_MXFP4) {
+    if (c->dtype != PLT_BF16 || c->n_experts != 0) { *why = "MXFP4 projections need dtype PLT_BF16 and a dense feed-forward"; return false; }
+    if (c->d_model % 128 || c->ffn_hidden % 128 || (c->n_heads * c->head_dim) % 128) {
+      *why = "MXFP4 projections need d_model, ffn_hidden and n_heads * head_dim to be multiples of 128"; return false;
+    }
+  }
   if (c->n_experts < 0 || c->n_experts > 256) { *why = "n_experts must be in 0..256"; return false; }
   if (c->n_experts > 0 && (c->top_k < 1 || c->top_k > c->n_experts || c->top_k > 32)) {
     *why = "top_k must be in 1..min(n_experts, 32)"; return false;
@@ -96,17 +106,29 @@ static size_t blob_walk(const plt_config* c, int want_layer, int want_which, siz
     if (which == want_which && (layer == want_layer || layer < 0)) { if (off) *off = cur; if (nelem) *nelem = n; }
     cur += n * esz;
   };
+  // low-bit projection [N, K]: e2m1 codes (reported element count N*K, two per byte), then its scale bytes
+  const bool mx = c->w_dtype == PLT_MXFP4;
+  auto put_w = [&](int layer, int which, int which_sc, size_t N, size_t K) {
+    if (!mx) { put(layer, which, N * K, es); return; }
+    cur = align256(cur);
+    if (which == want_which && layer == want_layer) { if (off) *off = cur; if (nelem) *nelem = N * K; }
+    cur += N * K / 2;
+    cur = align256(cur);
+    const size_t sb = mx_wscale_bytes((int)N, (int)K);
+    if (which_sc == want_which && layer == want_layer) { if (off) *off = cur; if (nelem) *nelem = sb; }
+    cur += sb;
+  };
   put(-1, PLT_W_EMB, V * d, es);
   for (int m = 0; m < c->n_layers; ++m) {
     put(m, PLT_W_NORM1, d, 4);
-    put(m, PLT_W_WQKV, (Hq + 2 * Hkv) * D * d, es);
+    put_w(m, PLT_W_WQKV, PLT_W_WQKV_SC, (Hq + 2 * Hkv) * D, d);
     put(m, PLT_W_GATE_W, Hq * D, 4);
     put(m, PLT_W_GATE_B, Hq, 4);
-    put(m, PLT_W_WO, d * Hq * D, es);
+    put_w(m, PLT_W_WO, PLT_W_WO_SC, d, Hq * D);
     put(m, PLT_W_NORM2, d, 4);
     if (E > 0) put(m, PLT_W_ROUTER, E * d, es);
-    put(m, PLT_W_WGU, Ex * 2 * F * d, es);
-    put(m, PLT_W_WDOWN, Ex * d * F, es);
+    if (mx) { put_w(m, PLT_W_WGU, PLT_W_WGU_SC, 2 * F, d); put_w(m, PLT_W_WDOWN, PLT_W_WDOWN_SC, d, F); }
+    else { put(m, PLT_W_WGU, Ex * 2 * F * d, es); put(m, PLT_W_WDOWN, Ex * d * F, es); }
   }
   put(-1, PLT_W_NORM_F, d, 4);
   if (!c->tie_embeddings) put(-1, PLT_W_HEAD, V * d, es);
@@ -123,10 +145,11 @@ extern "C" int plt_weights_offset(const plt_config* cfg, int32_t layer, int32_t 
                                   size_t* nelem) {
   const char* why;
   if (!cfg_valid(cfg, &why)) return fail(PLT_EINVAL, "plt_weights_offset: %s", why);
-  if (which < PLT_W_EMB || which > PLT_W_ROUTER || !off || !nelem) return fail(PLT_EINVAL, "plt_weights_offset: bad tensor id or null output");
+  if (which < PLT_W_EMB || which > PLT_W_WDOWN_SC || !off || !nelem) return fail(PLT_EINVAL, "plt_weights_offset: bad tensor id or null output");
   const bool global = which == PLT_W_EMB || which == PLT_W_NORM_F || which == PLT_W_HEAD;
   if (which == PLT_W_HEAD && cfg->tie_embeddings) return fail(PLT_EINVAL, "plt_weights_offset: head is tied to the embedding");
   if (which == PLT_W_ROUTER && cfg->n_experts == 0) return fail(PLT_EINVAL, "plt_weights_offset: a dense model has no router");
+  if (which >= PLT_W_WQKV_SC && cfg->w_dtype != PLT_MXFP4) return fail(PLT_EINVAL, "plt_weights_offset: only MXFP4 models have scale tensors");
   if (!global && (layer < 0 || layer >= cfg->n_layers)) return fail(PLT_EINVAL, "plt_weights_offset: layer out of range");
   *off = (size_t)-1;
   blob_walk(cfg, global ? -1 : layer, which, off, nelem);
@@ -152,6 +175,7 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
   m->es = cfg->dtype == PLT_BF16 ? 2 : 4;
   m->kv8 = cfg->kv_dtype == PLT_FP8_E4M3;
   m->kes = m->kv8 ? 1 : m->es;
+  m->mx = cfg->w_dtype == PLT_MXFP4;
   auto at = [&](int layer, int which) -> const void* {
     size_t off = 0, n = 0; blob_walk(cfg, layer, which, &off, &n); return m->blob + off;
   };
@@ -166,6 +190,11 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
     w.wo = at(l, PLT_W_WO); w.norm2 = (const float*)at(l, PLT_W_NORM2);
     w.wgu = at(l, PLT_W_WGU); w.wdown = at(l, PLT_W_WDOWN);
     w.router = cfg->n_experts > 0 ? at(l, PLT_W_ROUTER) : nullptr;
+    w.wqkv_sc = w.wo_sc = w.wgu_sc = w.wdown_sc = nullptr;
+    if (m->mx) {
+      w.wqkv_sc = (const uint8_t*)at(l, PLT_W_WQKV_SC); w.wo_sc = (const uint8_t*)at(l, PLT_W_WO_SC);
+      w.wgu_sc = (const uint8_t*)at(l, PLT_W_WGU_SC); w.wdown_sc = (const uint8_t*)at(l, PLT_W_WDOWN_SC);
+    }
   }
   {
     std::vector<double> f(cfg->head_dim / 2);
@@ -258,14 +287,19 @@ extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_
 static void kv_release(plt_kv* kv) {
   if (!kv) return;
   void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch,
-                  kv->arg_v, kv->arg_i, kv->moe_idx};
+                  kv->arg_v, kv->arg_i, kv->moe_idx, kv->a_codes, kv->a_scales};
   for (void* p : ptrs) if (p) (void)hipFree(p);
   delete kv;
 }
 
 extern "C" void plt_kv_free(plt_kv* kv) { kv_release(kv); }
 
-static size_t gemm_out_need(const plt_config& c, int M, int N, int K) {
+static int mx_max_k(const plt_config& c) {
+  int k = c.d_model; if (c.ffn_hidden > k) k = c.ffn_hidden; if (c.n_heads * c.head_dim > k) k = c.n_heads * c.head_dim;
+  return k;
+}
+static size_t gemm_out_need(const plt_config& c, int M, int N, int K, bool head = false) {
+  if (c.w_dtype == PLT_MXFP4 && !head) return (size_t)gemm_mx_splits(K) * M * N;
   const int S = c.dtype == PLT_BF16 ? gemm_bf16_splits_any(M, N, K) : 1;
   return (size_t)S * M * N;
 }
@@ -305,17 +339,22 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
     if ((t = gemm_out_need(c, R, 2 * F, d)) > go) go = t;
     if ((t = gemm_out_need(c, R, d, F)) > go) go = t;
   }
-  if ((t = gemm_out_need(c, batch, V, d)) > go) go = t;
+  if ((t = gemm_out_need(c, batch, V, d, true)) > go) go = t;
   kv->gout_elems = go;
   kv->attn_scratch_bytes = attn_mfma_scratch_bytes(batch, is_clp(c) ? L : 1, Hq, Hkv, D, attn_mfma_max_default_splits(batch, Hkv));
   auto dmalloc = [&](void** p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 256); };
   dmalloc((void**)&kv->x, (size_t)R * d * 4);
-  dmalloc(&kv->a, (size_t)R * d * m->es);
+  dmalloc(&kv->a, (size_t)R * d * (m->mx ? 4 : m->es));
   dmalloc((void**)&kv->gout, go * 4);
   dmalloc(&kv->q, (size_t)R * Hq * D * m->es);
   dmalloc((void**)&kv->z, (size_t)R * Hq * 4);
   dmalloc(&kv->y, (size_t)R * Hq * D * m->es);
-  dmalloc(&kv->act, (size_t)R * (c.n_experts > 0 ? c.top_k : 1) * F * m->es);
+  dmalloc(&kv->act, (size_t)R * (c.n_experts > 0 ? c.top_k : 1) * F * (m->mx ? 4 : m->es));
+  if (m->mx) {
+    const int maxK = mx_max_k(c);
+    dmalloc((void**)&kv->a_codes, (size_t)R * maxK);
+    dmalloc((void**)&kv->a_scales, (size_t)R * mx_ascale_row_bytes(maxK));
+  }
   if (c.n_experts > 0) dmalloc(&kv->moe_idx, moe_index_bytes(R, c.top_k, c.n_experts));
   dmalloc((void**)&kv->carry, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4);
   dmalloc((void**)&kv->pos_dev, (size_t)batch * 4);
@@ -361,6 +400,7 @@ struct Work {            // activation buffers one pass of the stack runs on
   float* x; void* a; float* gout; void* q; float* z; void* y; void* act;
   float* attn_tmp;   // prefill only: float [rows, Hq*D]
   void* moe_idx;     // mixture-of-experts models: routing lists (moe_index_bytes for the pass's rows)
+  uint8_t *a_codes, *a_scales;   // low-bit models: e4m3 codes / block scales of the next projection's input
 };
 
 static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int M, int N, int K,
@@ -372,6 +412,24 @@ static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int 
   }
   launch_gemm_f32(m->stream, (const float*)a, (const float*)w, out, M, N, K);
   return 1;
+}
+
+// x += sum of the GEMM slabs; a = RMSNorm(x) * gain as the next projection's input: the model dtype, or (low-bit
+// models) float rows quantised to e4m3 blocks
+template <typename T>
+static void norm_to_a(plt_model* m, const Work& wk, const float* partials, int S, size_t slab, const float* gain, int R) {
+  const plt_config& c = m->cfg;
+  if (m->mx && gain) {
+    launch_resid_norm<float>(m->stream, wk.x, 1, 0, partials, S, slab, gain, c.norm_eps, (float*)wk.a, R, c.d_model);
+    launch_mx_quant_a<float>(m->stream, (const float*)wk.a, wk.a_codes, wk.a_scales, R, c.d_model);
+  } else {
+    launch_resid_norm<T>(m->stream, wk.x, 1, 0, partials, S, slab, gain, c.norm_eps, gain ? (T*)wk.a : (T*)nullptr, R, c.d_model);
+  }
+}
+static int run_gemm_mx(plt_model* m, const Work& wk, const void* w, const uint8_t* w_sc, int M, int N, int K, bool decode) {
+  ProfScope prof(m, PLT_PROF_GEMM, decode);
+  launch_gemm_mx(m->stream, wk.a_codes, wk.a_scales, (const uint8_t*)w, w_sc, wk.gout, M, N, K);
+  return gemm_mx_splits(K);
 }
 
 template <typename T>
@@ -388,7 +446,8 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     const LayerW& w = m->layers[l];
     KvView v = kv_view(kv, l, cache);
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
-    int S = run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                               // Alg. 3 l.1
+    int S = m->mx ? run_gemm_mx(m, wk, w.wqkv, w.wqkv_sc, R, Nqkv, d, !rm.prefill)
+                  : run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                       // Alg. 3 l.1
     if (m->kv8)
       launch_rope_append<bf16_t, fp8_t>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (bf16_t*)wk.q, wk.z, v, rm,
                                         R, dm, m->inv_freq, variant);
@@ -425,9 +484,19 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       ProfScope prof(m, PLT_PROF_ATTN, dec);
       launch_attn_f32(s, (const float*)wk.q, wk.z, (float*)wk.y, v, rm, R, dm, variant == V_OWN_KV && dec ? 3 : plain);
     }
-    S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);                                     // Alg. 3 l.6
-    launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, w.norm2, c.norm_eps, (T*)wk.a, R, d);
-    if (c.n_experts > 0) {                                   // mixture of experts: k slabs, one per selected expert
+    if (m->mx) {                                                                                 // Alg. 3 l.6
+      launch_mx_quant_a<bf16_t>(s, (const bf16_t*)wk.y, wk.a_codes, wk.a_scales, R, Hq * D);
+      S = run_gemm_mx(m, wk, w.wo, w.wo_sc, R, d, Hq * D, dec);
+    } else {
+      S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);
+    }
+    norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, w.norm2, R);
+    if (m->mx) {                                             // low-bit gate/up and down projections
+      S = run_gemm_mx(m, wk, w.wgu, w.wgu_sc, R, 2 * F, d, dec);
+      launch_silu_mul<float>(s, wk.gout, S, (size_t)R * 2 * F, (float*)wk.act, R, F);
+      launch_mx_quant_a<float>(s, (const float*)wk.act, wk.a_codes, wk.a_scales, R, F);
+      S = run_gemm_mx(m, wk, w.wdown, w.wdown_sc, R, d, F, dec);
+    } else if (c.n_experts > 0) {                                   // mixture of experts: k slabs, one per selected expert
       ProfScope prof(m, PLT_PROF_GEMM, dec);
       launch_moe_ffn<T>(s, (const T*)wk.a, (const T*)w.router, (const T*)w.wgu, (const T*)w.wdown, (T*)wk.act, wk.gout,
                         moe_index_carve(wk.moe_idx, R, c.top_k, c.n_experts), R, d, F, c.n_experts, c.top_k);
@@ -441,10 +510,9 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
       launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
     }
-    if (c.n_experts == 0) S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
+    if (c.n_experts == 0 && !m->mx) S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
     const float* gain = l + 1 < c.n_layers ? m->layers[l + 1].norm1 : next_gain;
-    launch_resid_norm<T>(s, wk.x, 1, 0, wk.gout, S, (size_t)R * d, gain, c.norm_eps,
-                         gain ? (T*)wk.a : (T*)nullptr, R, d);
+    norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, gain, R);
   }
 }
 
@@ -464,14 +532,14 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
   const plt_config& c = m->cfg;
   hipStream_t s = m->stream;
   const int B = kv->B, L = c.n_loops, d = c.d_model;
-  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr, kv->moe_idx};
+  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr, kv->moe_idx, kv->a_codes, kv->a_scales};
   KvView none{}; none.b0 = 0;
   if (is_clp(c)) {
     // Alg. 1 l.5-7: rows B_0 = e, B_l = e + H^l[p-1]; the L rows of a sequence run as one pass
     const int R = B * L;
     RowMap rm{0, L, 0, kv->pos_dev};
     launch_embed<T>(s, dev_tokens, (const T*)m->emb, kv->carry, nullptr, kv->x, R, d, rm, L, 1, c.vocab);
-    launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, R, d);
+    norm_to_a<T>(m, wk, nullptr, 0, 0, m->layers[0].norm1, R);
     const int variant = c.mode == PLT_MODE_CLP ? V_PLT : (c.mode == PLT_MODE_CLP_SHARE_ONLY ? V_SHARE_ONLY : V_OWN_KV);
     stack_pass<T>(m, kv, wk, R, rm, 0, variant, none, 0, 0, L, nullptr);
     launch_carry_update(s, kv->x, kv->carry, B, L, d);
@@ -480,7 +548,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
     // Eq. (1): L serial passes of B rows, loop l on its own cache l
     RowMap rm{0, 1, 0, kv->pos_dev};
     launch_embed<T>(s, dev_tokens, (const T*)m->emb, nullptr, nullptr, kv->x, B, d, rm, 1, 0, c.vocab);
-    launch_resid_norm<T>(s, kv->x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)kv->a, B, d);
+    norm_to_a<T>(m, wk, nullptr, 0, 0, m->layers[0].norm1, B);
     for (int l = 0; l < L; ++l)
       stack_pass<T>(m, kv, wk, B, rm, l, V_PLAIN, none, 0, 0, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
     head_and_argmax<T>(m, kv, wk, B, 1, 0, dev_next, dev_logits, true);
@@ -526,13 +594,15 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
     if ((t = gemm_out_need(c, Rc, 2 * F, d)) > go) go = t;
     if ((t = gemm_out_need(c, Rc, d, F)) > go) go = t;
   }
-  if ((t = gemm_out_need(c, Bc, V, d)) > go) go = t;
+  if ((t = gemm_out_need(c, Bc, V, d, true)) > go) go = t;
   // one temporary workspace, carved into the chunk's activation buffers
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
-  const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * es),
+  const size_t wes = m->mx ? 4 : es;      // low-bit models keep projection inputs as float until they are quantised
+  const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * wes),
                o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
-               o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * topk * F * es),
+               o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * topk * F * wes),
+               o_ac = carve(m->mx ? (size_t)Rc * mx_max_k(c) : 256), o_as = carve(m->mx ? (size_t)Rc * mx_ascale_row_bytes(mx_max_k(c)) : 256),
                o_moe = carve(E > 0 ? moe_index_bytes(Rc, topk, E) : 256),
                o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes),
                o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
@@ -541,7 +611,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
   (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * kes), s);
   Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act,
-          (float*)(ws + o_tmp), ws + o_moe};
+          (float*)(ws + o_tmp), ws + o_moe, (uint8_t*)(ws + o_ac), (uint8_t*)(ws + o_as)};
   float* hprev = (float*)(ws + o_h);
   for (int b0 = 0; b0 < B; b0 += Bc) {
     const int bc = b0 + Bc <= B ? Bc : B - b0;
@@ -553,7 +623,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
       if (is_clp(c)) {
         // Alg. 2 l.1-2 (l = 0) and l.4-6 (l >= 1): B = E + shift_right(H^(l))
         launch_embed<T>(s, toks, (const T*)m->emb, nullptr, hprev, wk.x, R, d, rm, L, 1, c.vocab);
-        launch_resid_norm<T>(s, wk.x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)wk.a, R, d);
+        norm_to_a<T>(m, wk, nullptr, 0, 0, m->layers[0].norm1, R);
         // own-KV ablation: loop l is a plain pass over its own cache l; share-only: loops >= 2 append nothing
         const int variant = c.mode == PLT_MODE_CLP ? V_PLT : (c.mode == PLT_MODE_CLP_SHARE_ONLY ? V_SHARE_ONLY : V_PLAIN);
         stack_pass<T>(m, kv, wk, R, rm, c.mode == PLT_MODE_CLP_OWN_KV ? l : 0, variant, loc, bc, n, L, nullptr);
@@ -564,7 +634,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
       } else {
         if (l == 0) {
           launch_embed<T>(s, toks, (const T*)m->emb, nullptr, nullptr, wk.x, R, d, rm, 1, 0, c.vocab);
-          launch_resid_norm<T>(s, wk.x, 1, 0, nullptr, 0, 0, m->layers[0].norm1, c.norm_eps, (T*)wk.a, R, d);
+          norm_to_a<T>(m, wk, nullptr, 0, 0, m->layers[0].norm1, R);
         }
         stack_pass<T>(m, kv, wk, R, rm, l, V_PLAIN, loc, bc, n, 1, l + 1 < L ? m->layers[0].norm1 : nullptr);
       }

@@ -14,18 +14,18 @@ def dev_tokens(arr):
     return torch.from_numpy(np.ascontiguousarray(arr, np.int32)).cuda()
 
 
-def run_teacher_forced(shape, dtype, mode, weights, prompts, n_steps, tol, check_hidden=True, kv_dtype=0):
+def run_teacher_forced(shape, dtype, mode, weights, prompts, n_steps, tol, check_hidden=True, kv_dtype=0, w_dtype=0):
     """GPU consumes the oracle's token stream; logits (and hidden rows) compared at every step."""
     fp8 = kv_dtype == B.PLT_FP8_E4M3
     bf = dtype == B.PLT_BF16 and not fp8
-    cfg = B.make_config(shape, dtype=dtype, mode=mode, kv_dtype=kv_dtype)
+    cfg = B.make_config(shape, dtype=dtype, mode=mode, kv_dtype=kv_dtype, w_dtype=w_dtype)
     model = B.Model(cfg, B.pack_weights(cfg, weights))
     Bn, n = prompts.shape
     kv = B.KV(model, Bn, n + n_steps + 3)
     orcs, streams, ref_logits, ref_hidden = [], [], [], []
     for b in range(Bn):
         variant = {B.PLT_MODE_CLP_SHARE_ONLY: "clp_share_only", B.PLT_MODE_CLP_OWN_KV: "clp_own_kv"}.get(mode, "plt")
-        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=bf, variant=variant, kv_fp8=fp8)
+        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=bf, variant=variant, kv_fp8=fp8, w_mx=w_dtype == B.PLT_MXFP4)
         if mode != B.PLT_MODE_VANILLA_LOOP:
             ids, margins, lgs = orc.greedy_generate(list(prompts[b]), n_steps)
             hidden = np.stack(orc.trace)[n - 1:]                         # [n_steps+1, L, d]

@@ -11,6 +11,8 @@ import torch
 
 from oracle import plt_oracle as O
 from paper_2510_24824_amd import binding as B, synth
+from tests.helpers import lively_weights
+from tests.test_gpu_model import run_teacher_forced
 
 pytestmark = pytest.mark.gpu
 
@@ -126,3 +128,38 @@ def test_gemm_mx_rejects_bad_shapes():
     for M, N, K in [(4, 40, 128), (4, 48, 96), (0, 48, 128)]:
         c = torch.zeros(max(M, 1), N, device="cuda")
         assert B.lib().plt_gemm_mx(M, N, K, B._ptr(z), B._ptr(z), B._ptr(z), B._ptr(z), B._ptr(c), B._ptr(z), z.numel(), None) == -1
+
+
+MX_SMALL = synth.ModelShape(n_layers=2, d_model=128, n_heads=2, n_kv_heads=1, head_dim=64, ffn_hidden=256,
+                            vocab=300, n_loops=3, window=5)
+
+
+@pytest.mark.parametrize("mode,kv_dtype", [(B.PLT_MODE_CLP, 0), (B.PLT_MODE_VANILLA_LOOP, 0), (B.PLT_MODE_CLP, B.PLT_FP8_E4M3)])
+def test_model_with_lowbit_projections(mode, kv_dtype):
+    """Whole model with the four per-layer projections on MXFP4 weights / MXFP8 activations against the oracle's
+    w_mx model (same quantisation rule, float64 arithmetic)."""
+    weights = lively_weights(MX_SMALL, 9, bf16=True, std=0.05)
+    prompts = synth.token_ids((2, 9), MX_SMALL.vocab, 10)
+    run_teacher_forced(MX_SMALL, B.PLT_BF16, mode, weights, prompts, 6, MX_MODEL_TOL, kv_dtype=kv_dtype, w_dtype=B.PLT_MXFP4)
+
+
+def test_lowbit_model_single_position():
+    """One position, L = 1: softmax over a single key returns the (bf16-stored) value row on both sides, so the
+    values entering a quantiser differ only by float-level arithmetic -- dominated by the matrix-core
+    instruction's fixed-point block sums, about 1e-4 relative.  A quantiser turns such a difference into a
+    changed e4m3 code (one grid step, 6-12 % of that element) for about 1e-4 / 2^-4 = 0.2 % of the elements:
+    a fraction of a flip per row and projection, each worth about 1 / sqrt(K) * 10 % of that projection's
+    output.  Bar: 2 % of the largest logit (measured 1.2 %); a wrong layout, scale tensor or operand order is
+    off by 100 %."""
+    from tests.helpers import with_shape
+    shape = with_shape(MX_SMALL, n_loops=1)
+    weights = lively_weights(shape, 11, bf16=True, std=0.05)
+    prompts = synth.token_ids((8, 1), shape.vocab, 12)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 0, 0.02 * 2.7, w_dtype=B.PLT_MXFP4)
+
+
+# Several positions and loops: bf16 queries, softmax weights and attention outputs move the quantiser inputs by
+# about 2^-9, so about 2^-9 / 2^-4 = 3 % of the e4m3 codes differ by one step between the two sides; a projection
+# output then differs by about sqrt(0.03) * 2^-4.5 = 0.8 % (rms), and the differences add up over 4 projections,
+# 2 layers and the loop-to-loop carry: a few per cent of the state's magnitude (~3), measured 0.13-0.15 max-abs.
+MX_MODEL_TOL = 0.25
