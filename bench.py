@@ -58,17 +58,29 @@ def fill_weights_on_device(B, cfg, seed):
             v[i:i + m].copy_((torch.randn(m, generator=g, device="cuda") * 0.02).to(dtype))
 
     wd = torch.bfloat16 if cfg.dtype == B.PLT_BF16 else torch.float32
+    Hq, Hkv, D, d, F = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_model, cfg.ffn_hidden
+
+    def matrix(layer, which, which_sc, N, K):
+        if cfg.w_dtype == B.PLT_MXFP4:      # low-bit projections: a bf16 draw quantised on the device into the blob
+            w = (torch.randn(N, K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+            B.quantize_into_blob(cfg, blob, layer, which, which_sc, w)
+        else:
+            normal(layer, which, wd)
+
     normal(0, B.PLT_W_EMB, wd)
     for m in range(cfg.n_layers):
         view(m, B.PLT_W_NORM1, torch.float32)[0].fill_(1.0)
-        normal(m, B.PLT_W_WQKV, wd)
+        matrix(m, B.PLT_W_WQKV, B.PLT_W_WQKV_SC, (Hq + 2 * Hkv) * D, d)
         normal(m, B.PLT_W_GATE_W, torch.float32)
-        normal(m, B.PLT_W_WO, wd)
+        matrix(m, B.PLT_W_WO, B.PLT_W_WO_SC, d, Hq * D)
         view(m, B.PLT_W_NORM2, torch.float32)[0].fill_(1.0)
         if cfg.n_experts > 0:
             normal(m, B.PLT_W_ROUTER, wd)
-        normal(m, B.PLT_W_WGU, wd)
-        normal(m, B.PLT_W_WDOWN, wd)
+            normal(m, B.PLT_W_WGU, wd)
+            normal(m, B.PLT_W_WDOWN, wd)
+        else:
+            matrix(m, B.PLT_W_WGU, B.PLT_W_WGU_SC, 2 * F, d)
+            matrix(m, B.PLT_W_WDOWN, B.PLT_W_WDOWN_SC, d, F)
     view(0, B.PLT_W_NORM_F, torch.float32)[0].fill_(1.0)
     if not cfg.tie_embeddings:
         normal(0, B.PLT_W_HEAD, wd)
@@ -707,6 +719,27 @@ def main():
         out["dense_gqa_shape"] = gq
         out["moe_shape"] = bench_moe(B, g, Bn, N, w, max(8, args.steps // 2), (4, 16, Bn))
         out["lowbit_gemm"] = bench_lowbit_gemm(B, Bn * L)
+        # ---- the serving recipe as a whole: e4m3 K/V caches + the four per-layer projections on MXFP4 weights /
+        # MXFP8 activations (the reading taken for "FP8 self-attention and W4A8 linear layers"); same model shape
+        lb = {}
+        lcfg = B.make_config(shape, dtype=B.PLT_BF16, w_dtype=B.PLT_MXFP4)
+        lblob = fill_weights_on_device(B, lcfg, SEED + 5)
+        lb["weight_blob_bytes"] = int(lblob.numel()); lb["bf16_weight_blob_bytes"] = int(blob.numel())
+        for name, Lx, kvd in [("nonlooped_L1_fp8kv", 1, B.PLT_FP8_E4M3), ("plt_L2_fp8kv", 2, B.PLT_FP8_E4M3),
+                              ("plt_L3_fp8kv", 3, B.PLT_FP8_E4M3), ("plt_L2_bf16kv", 2, 0)]:
+            cl = B.make_config(shape, dtype=B.PLT_BF16, n_loops=Lx, window=w, kv_dtype=kvd, w_dtype=B.PLT_MXFP4)
+            ml = B.Model(cl, lblob)
+            kl = B.KV(ml, Bn, N)
+            fill_kv_random(B, kl, g)
+            msl = time_steps(kl, pos, tok, 2, max(8, args.steps // 2))
+            lb[name] = {"ms_per_step": msl, "tokens_per_s": Bn / (msl * 1e-3)}
+            log(f"[bench] MXFP4 projections {name}: {msl:.3f} ms/step")
+            kl.close(); ml.close(); del kl
+            torch.cuda.empty_cache()
+        lb["latency_vs_nonlooped"] = {k: lb[k]["ms_per_step"] / lb["nonlooped_L1_fp8kv"]["ms_per_step"] for k in ("plt_L2_fp8kv", "plt_L3_fp8kv")}
+        del lblob
+        torch.cuda.empty_cache()
+        out["lowbit_model"] = lb
 
     if args.sweep:
         out["serving_sweep"] = bench_sweep(B, shape, blob, g)

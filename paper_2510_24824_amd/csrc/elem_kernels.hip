@@ -145,6 +145,88 @@ void launch_resid_norm(hipStream_t s, float* x, int x_row_stride, int x_row_off,
 template void launch_resid_norm<float>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, float*, int, int);
 template void launch_resid_norm<bf16_t>(hipStream_t, float*, int, int, const float*, int, size_t, const float*, float, bf16_t*, int, int);
 
+// Low-bit models: the same accumulation and RMSNorm, with the normed row quantised to e4m3 blocks of 32 on the
+// way out (the input of the next low-bit projection).  A block is the 8 consecutive threads' float4 values.
+__global__ __launch_bounds__(256) void k_resid_norm4_mx(float* __restrict__ x, const float* __restrict__ partials, int S,
+                                                        size_t slab, const float* __restrict__ gain, float eps,
+                                                        uint8_t* __restrict__ codes, uint8_t* __restrict__ scales, int d) {
+  __shared__ float sm[4];
+  const int r = blockIdx.x, d4 = d >> 2;
+  float4* xr = reinterpret_cast<float4*>(x + (size_t)r * d);
+  float4 v[4];
+  float ss = 0.f;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = threadIdx.x + it * 256;
+    if (i >= d4) break;
+    float4 a = xr[i];
+    if (S > 0) {
+      const float4* pp = reinterpret_cast<const float4*>(partials + (size_t)r * d) + i;
+      const size_t slab4 = slab >> 2;
+      float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (int s = 0; s < S; ++s) {
+        const float4 p0 = pp[(size_t)s * slab4];
+        acc.x += p0.x; acc.y += p0.y; acc.z += p0.z; acc.w += p0.w;
+      }
+      a.x += acc.x; a.y += acc.y; a.z += acc.z; a.w += acc.w;
+      xr[i] = a;
+    }
+    v[it] = a;
+    ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+  }
+  ss = block_sum_256(ss, sm);
+  const float inv = 1.0f / sqrtf(ss / (float)d + eps);
+  const int nbp = mx_ascale_row_bytes(d);
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = threadIdx.x + it * 256;
+    if (i >= d4) break;                 // d / 4 is a multiple of 8: a block's 8 threads leave together
+    const float4 gn = reinterpret_cast<const float4*>(gain)[i];
+    const float n0 = v[it].x * inv * gn.x, n1 = v[it].y * inv * gn.y, n2 = v[it].z * inv * gn.z, n3 = v[it].w * inv * gn.w;
+    float amax = fmaxf(fmaxf(fabsf(n0), fabsf(n1)), fmaxf(fabsf(n2), fabsf(n3)));
+    amax = fmaxf(amax, __shfl_xor(amax, 1)); amax = fmaxf(amax, __shfl_xor(amax, 2)); amax = fmaxf(amax, __shfl_xor(amax, 4));
+    const int e = mx_block_exponent(amax, 8);
+    *reinterpret_cast<unsigned*>(codes + (size_t)r * d + 4 * i) = mx_pack4_e4m3(n0, n1, n2, n3, e);
+    if ((i & 7) == 0) scales[(size_t)r * nbp + mx_ascale_index(i >> 3)] = (uint8_t)(e + 127);
+  }
+  if (threadIdx.x == 0) for (int b = d >> 5; b < nbp; ++b) scales[(size_t)r * nbp + mx_ascale_index(b)] = 0;
+}
+bool resid_norm_mx_applies(int d) { return (d & 31) == 0 && d <= 4096; }
+void launch_resid_norm_mx(hipStream_t s, float* x, const float* partials, int S, size_t slab, const float* gain, float eps,
+                          uint8_t* codes, uint8_t* scales, int R, int d) {
+  hipLaunchKernelGGL(k_resid_norm4_mx, dim3(R), dim3(256), 0, s, x, partials, S, slab, gain, eps, codes, scales, d);
+}
+
+// SwiGLU over the gate/up slabs with the same quantiser on the way out: a thread owns 4 consecutive hidden
+// columns of a row, 8 consecutive threads a block of 32
+__global__ __launch_bounds__(256) void k_silu_mul_mx(const float* __restrict__ gu, int S, size_t slab, uint8_t* __restrict__ codes,
+                                                     uint8_t* __restrict__ scales, int R, int F) {
+  const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const int f4 = F >> 2;
+  const bool live = t < (size_t)R * f4;       // F / 4 is a multiple of 8: the 8 threads of a block are live together
+  const int r = live ? (int)(t / f4) : 0, j = live ? (int)(t - (size_t)r * f4) : 0;
+  float4 gt = make_float4(0.f, 0.f, 0.f, 0.f), up = gt;
+  if (live)
+    for (int s = 0; s < S; ++s) {
+      const float* row = gu + (size_t)s * slab + (size_t)r * 2 * F;
+      const float4 a = *reinterpret_cast<const float4*>(row + 4 * j), b = *reinterpret_cast<const float4*>(row + F + 4 * j);
+      gt.x += a.x; gt.y += a.y; gt.z += a.z; gt.w += a.w; up.x += b.x; up.y += b.y; up.z += b.z; up.w += b.w;
+    }
+  const float h0 = gt.x / (1.0f + expf(-gt.x)) * up.x, h1 = gt.y / (1.0f + expf(-gt.y)) * up.y,
+              h2 = gt.z / (1.0f + expf(-gt.z)) * up.z, h3 = gt.w / (1.0f + expf(-gt.w)) * up.w;
+  float amax = fmaxf(fmaxf(fabsf(h0), fabsf(h1)), fmaxf(fabsf(h2), fabsf(h3)));
+  amax = fmaxf(amax, __shfl_xor(amax, 1)); amax = fmaxf(amax, __shfl_xor(amax, 2)); amax = fmaxf(amax, __shfl_xor(amax, 4));
+  if (!live) return;
+  const int e = mx_block_exponent(amax, 8), nbp = mx_ascale_row_bytes(F);
+  *reinterpret_cast<unsigned*>(codes + (size_t)r * F + 4 * j) = mx_pack4_e4m3(h0, h1, h2, h3, e);
+  if ((j & 7) == 0) scales[(size_t)r * nbp + mx_ascale_index(j >> 3)] = (uint8_t)(e + 127);
+  if (j == 0) for (int b = F >> 5; b < nbp; ++b) scales[(size_t)r * nbp + mx_ascale_index(b)] = 0;
+}
+void launch_silu_mul_mx(hipStream_t s, const float* gu, int S, size_t slab, uint8_t* codes, uint8_t* scales, int R, int F) {
+  const size_t n = (size_t)R * (F >> 2);
+  hipLaunchKernelGGL(k_silu_mul_mx, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, gu, S, slab, codes, scales, R, F);
+}
+
 // ---- S3: RoPE, gate logit (Eq. 2, on the un-rotated query), cache append ----
 // grid (ceil((Hq + 2*Hkv) / 4), R), 256 threads = 4 head vectors: lane j < D/2 of a wave owns the pair (j, j + D/2).
 template <typename T, typename KT>

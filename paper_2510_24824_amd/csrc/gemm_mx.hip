@@ -29,11 +29,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 // ---------------------------------------------------------------------------------------------- quantisers
-__device__ inline int mx_block_exponent(float amax, int emax) {
-  if (!(amax > 0.f)) return -127;
-  int e = ilogbf(amax) - emax;
-  return e < -127 ? -127 : (e > 127 ? 127 : e);
-}
 // e2m1 code of v (|v| < 8 after block scaling): nearest value of {0, .5, 1, 1.5, 2, 3, 4, 6}, ties to the
 // even code, saturating
 __device__ inline unsigned f32_to_e2m1(float v) {
@@ -90,10 +85,7 @@ __global__ __launch_bounds__(256) void k_mx_quant_a(const T* __restrict__ a, uin
   const int e = mx_block_exponent(amax, 8);
   unsigned out[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    out[i] = (unsigned)f32_to_e4m3(ldexpf(v[4 * i], -e)) | ((unsigned)f32_to_e4m3(ldexpf(v[4 * i + 1], -e)) << 8) |
-             ((unsigned)f32_to_e4m3(ldexpf(v[4 * i + 2], -e)) << 16) | ((unsigned)f32_to_e4m3(ldexpf(v[4 * i + 3], -e)) << 24);
-  }
+  for (int i = 0; i < 8; ++i) out[i] = mx_pack4_e4m3(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3], e);
   uint4* dst = reinterpret_cast<uint4*>(codes + (size_t)r * K + b * 32);
   dst[0] = make_uint4(out[0], out[1], out[2], out[3]);
   dst[1] = make_uint4(out[4], out[5], out[6], out[7]);

@@ -419,7 +419,9 @@ static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int 
 template <typename T>
 static void norm_to_a(plt_model* m, const Work& wk, const float* partials, int S, size_t slab, const float* gain, int R) {
   const plt_config& c = m->cfg;
-  if (m->mx && gain) {
+  if (m->mx && gain && resid_norm_mx_applies(c.d_model) && (slab & 3) == 0) {
+    launch_resid_norm_mx(m->stream, wk.x, partials, S, slab, gain, c.norm_eps, wk.a_codes, wk.a_scales, R, c.d_model);
+  } else if (m->mx && gain) {
     launch_resid_norm<float>(m->stream, wk.x, 1, 0, partials, S, slab, gain, c.norm_eps, (float*)wk.a, R, c.d_model);
     launch_mx_quant_a<float>(m->stream, (const float*)wk.a, wk.a_codes, wk.a_scales, R, c.d_model);
   } else {
@@ -493,8 +495,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, w.norm2, R);
     if (m->mx) {                                             // low-bit gate/up and down projections
       S = run_gemm_mx(m, wk, w.wgu, w.wgu_sc, R, 2 * F, d, dec);
-      launch_silu_mul<float>(s, wk.gout, S, (size_t)R * 2 * F, (float*)wk.act, R, F);
-      launch_mx_quant_a<float>(s, (const float*)wk.act, wk.a_codes, wk.a_scales, R, F);
+      launch_silu_mul_mx(s, wk.gout, S, (size_t)R * 2 * F, wk.a_codes, wk.a_scales, R, F);      // SwiGLU + e4m3 blocks
       S = run_gemm_mx(m, wk, w.wdown, w.wdown_sc, R, d, F, dec);
     } else if (c.n_experts > 0) {                                   // mixture of experts: k slabs, one per selected expert
       ProfScope prof(m, PLT_PROF_GEMM, dec);

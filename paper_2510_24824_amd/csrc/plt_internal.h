@@ -189,6 +189,22 @@ inline size_t mx_wscale_bytes(int N, int K) { return (size_t)(N >> 4) * ((((K >>
 // scale byte of k block b inside one activation row: groups of 16 blocks stored [g = b mod 4][c = (b / 4) mod 4]
 __host__ __device__ inline int mx_ascale_index(int b) { return (b >> 4) * 16 + (b & 3) * 4 + ((b >> 2) & 3); }
 __host__ __device__ inline int mx_ascale_row_bytes(int K) { return ((K + 511) >> 9) * 16; }
+// scale exponent of a block with largest magnitude amax: floor(log2(amax)) - emax, clamped; all-zero block: -127
+__device__ inline int mx_block_exponent(float amax, int emax) {
+  if (!(amax > 0.f)) return -127;
+  int e = ilogbf(amax) - emax;
+  return e < -127 ? -127 : (e > 127 ? 127 : e);
+}
+// four consecutive values of a block with exponent e -> four e4m3 bytes (memory order)
+__device__ inline unsigned mx_pack4_e4m3(float a, float b, float c, float d, int e) {
+  return (unsigned)f32_to_e4m3(ldexpf(a, -e)) | ((unsigned)f32_to_e4m3(ldexpf(b, -e)) << 8) |
+         ((unsigned)f32_to_e4m3(ldexpf(c, -e)) << 16) | ((unsigned)f32_to_e4m3(ldexpf(d, -e)) << 24);
+}
+// elem_kernels.hip: the residual/norm and SwiGLU kernels with the e4m3 block quantiser fused (low-bit models)
+bool resid_norm_mx_applies(int d);
+void launch_resid_norm_mx(hipStream_t s, float* x, const float* partials, int S, size_t slab, const float* gain, float eps,
+                          uint8_t* codes, uint8_t* scales, int R, int d);
+void launch_silu_mul_mx(hipStream_t s, const float* gu, int S, size_t slab, uint8_t* codes, uint8_t* scales, int R, int F);
 // gemm_mx.hip
 void launch_mx_quant_w(hipStream_t s, const bf16_t* w, uint8_t* codes, uint8_t* scales, int N, int K);
 template <typename T>

@@ -149,13 +149,13 @@ def test_lowbit_model_single_position():
     instruction's fixed-point block sums, about 1e-4 relative.  A quantiser turns such a difference into a
     changed e4m3 code (one grid step, 6-12 % of that element) for about 1e-4 / 2^-4 = 0.2 % of the elements:
     a fraction of a flip per row and projection, each worth about 1 / sqrt(K) * 10 % of that projection's
-    output.  Bar: 2 % of the largest logit (measured 1.2 %); a wrong layout, scale tensor or operand order is
-    off by 100 %."""
+    output.  Bar: 3 % of the largest logit (1.84; measured 1.8 %); a wrong layout, scale tensor or operand order
+    is off by 100 %."""
     from tests.helpers import with_shape
     shape = with_shape(MX_SMALL, n_loops=1)
     weights = lively_weights(shape, 11, bf16=True, std=0.05)
     prompts = synth.token_ids((8, 1), shape.vocab, 12)
-    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 0, 0.02 * 2.7, w_dtype=B.PLT_MXFP4)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 0, 0.03 * 1.84, w_dtype=B.PLT_MXFP4)
 
 
 # Several positions and loops: bf16 queries, softmax weights and attention outputs move the quantiser inputs by
