@@ -45,8 +45,10 @@ design notes of the repository):
     3, 4, 6 and their negatives; emax 2), quantised once from the bf16 weights.  Activations: element
     format e4m3 (emax 8), quantised where they enter a projection (the normed rows, the attention
     output, the SwiGLU product).  A projection is the exact product of the two dequantised operands.
-    The four per-layer projections (QKV, output, gate/up, down) are quantised; embedding, classifier
-    head, norms, gate vector and every other operation keep their precision.
+    The four per-layer projections (QKV, output, gate/up, down) are quantised -- in a mixture-of-experts
+    model every expert's gate, up and down matrices, while the router matrix keeps its precision and reads the
+    quantised normed row; embedding, classifier head, norms, gate vector and every other operation keep
+    their precision.
 
 Precision: float64 everywhere.  With kv_bf16=True the K and V entries are rounded to
 bfloat16 when they are stored (the device keeps its caches in bfloat16), nothing else is.
@@ -232,12 +234,14 @@ def decode_attention(q, k_share, v_share, k_ring, v_ring, z, n_ctx=None, n_ring=
     return y
 
 
-def swiglu_ffn(b, w_gate, w_up, w_down) -> np.ndarray:
-    """W_down (silu(W_gate b) * (W_up b)) for one row b[d]; matrices are [out, in]."""
+def swiglu_ffn(b, w_gate, w_up, w_down, hidden_in=None) -> np.ndarray:
+    """W_down (silu(W_gate b) * (W_up b)) for one row b[d]; matrices are [out, in].  hidden_in, if given, is
+    applied to the hidden vector before the down projection (low-bit models: its e4m3 block quantiser)."""
     b = np.asarray(b, np.float64)
     gte = np.asarray(w_gate, np.float64) @ b
     up = np.asarray(w_up, np.float64) @ b
-    return np.asarray(w_down, np.float64) @ (gte / (1.0 + np.exp(-gte)) * up)
+    h = gte / (1.0 + np.exp(-gte)) * up
+    return np.asarray(w_down, np.float64) @ (h if hidden_in is None else hidden_in(h))
 
 
 def moe_route(b, router, top_k):
@@ -256,7 +260,7 @@ def moe_route(b, router, top_k):
     return ids, p[ids], margin
 
 
-def moe_ffn(b, W, top_k, margins=None) -> np.ndarray:
+def moe_ffn(b, W, top_k, margins=None, hidden_in=None) -> np.ndarray:
     """sum over the selected experts e of p_e * SwiGLU_e(b) [appendix, MoE models recipe; router
     reading in the header].  W: "router" [E, d], "w_gate" / "w_up" [E, F, d], "w_down" [E, d, F]."""
     ids, p, margin = moe_route(b, W["router"], top_k)
@@ -264,7 +268,7 @@ def moe_ffn(b, W, top_k, margins=None) -> np.ndarray:
         margins.append(margin)
     out = np.zeros(np.asarray(W["w_down"]).shape[1], np.float64)
     for e, pe in zip(ids, p):
-        out += pe * swiglu_ffn(b, W["w_gate"][e], W["w_up"][e], W["w_down"][e])
+        out += pe * swiglu_ffn(b, W["w_gate"][e], W["w_up"][e], W["w_down"][e], hidden_in)
     return out
 
 
@@ -378,8 +382,7 @@ class PLTOracle:
         # low-bit linear layers: the four projections of every layer on microscaling operands
         self.w_mx = w_mx
         if w_mx:
-            assert shape.n_experts == 0
-            self.wq_mx = []
+            self.wq_mx = []             # (expert matrices: blocks run along the last axis as well; the router keeps its precision)
             for W in weights["layers"]:
                 self.wq_mx.append({name: mx_dequantize(*mx_quantize(W[name], "e2m1"))
                                    for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")})
@@ -435,14 +438,11 @@ class PLTOracle:
                                                Kl[:, h // G], Vl[:, h // G], z[h])  # Alg. 3 l.2-5
             x = x + np.asarray(W["wo"], np.float64) @ act_in(y.reshape(Hq * D))         # Alg. 3 l.6
             b = act_in(rmsnorm(x, W["norm2"], s.norm_eps))
+            hid = act_in if self.w_mx else None
             if s.n_experts > 0:
-                x = x + moe_ffn(b, W, s.top_k, self.route_margins)
-            elif self.w_mx:
-                gte = np.asarray(W["w_gate"], np.float64) @ b
-                h = gte / (1.0 + np.exp(-gte)) * (np.asarray(W["w_up"], np.float64) @ b)
-                x = x + np.asarray(W["w_down"], np.float64) @ act_in(h)
+                x = x + moe_ffn(b, W, s.top_k, self.route_margins, hid)
             else:
-                x = x + swiglu_ffn(b, W["w_gate"], W["w_up"], W["w_down"])
+                x = x + swiglu_ffn(b, W["w_gate"], W["w_up"], W["w_down"], hid)
         return x
 
     def embed(self, t):

@@ -163,12 +163,12 @@ def test_route_mutations_are_caught(monkeypatch, kind):
     assert some_pin_fails()
 
 
-def _ffn_no_up(b, w_gate, w_up, w_down):
+def _ffn_no_up(b, w_gate, w_up, w_down, hidden_in=None):
     g = np.asarray(w_gate, np.float64) @ b
     return np.asarray(w_down, np.float64) @ (g / (1.0 + np.exp(-g)))
 
 
-def _ffn_silu_on_up(b, w_gate, w_up, w_down):
+def _ffn_silu_on_up(b, w_gate, w_up, w_down, hidden_in=None):
     g = np.asarray(w_gate, np.float64) @ b; u = np.asarray(w_up, np.float64) @ b
     return np.asarray(w_down, np.float64) @ (g * (u / (1.0 + np.exp(-u))))
 
@@ -180,7 +180,7 @@ def test_expert_ffn_mutations_are_caught(monkeypatch, repl):
 
 
 def test_wrong_expert_matrix_is_caught(monkeypatch):
-    def moe_ffn(b, W, top_k, margins=None):
+    def moe_ffn(b, W, top_k, margins=None, hidden_in=None):
         ids, p, margin = O.moe_route(b, W["router"], top_k)
         out = np.zeros(np.asarray(W["w_down"]).shape[1])
         for e, pe in zip(ids, p):

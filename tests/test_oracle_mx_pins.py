@@ -151,12 +151,40 @@ def test_model_with_mx_linear_layers_equals_a_model_on_dequantised_weights_and_q
     assert 1e-3 < rel < 1.5
 
 
+def test_moe_model_with_mx_experts_equals_hand_composition():
+    """Mixture-of-experts feed-forward on low-bit operands, one position by hand: the router reads the quantised
+    normed row with its own (unquantised) matrix; every selected expert runs on dequantised e2m1 matrices, its
+    hidden vector passes the e4m3 quantiser before the down projection."""
+    ms = synth.ModelShape(n_layers=1, d_model=32, n_heads=4, n_kv_heads=2, head_dim=8, ffn_hidden=32, vocab=37,
+                          n_loops=1, window=4, n_experts=5, top_k=2)
+    shape = oshape(ms, n_experts=5, top_k=2)
+    wts = synth.make_weights(ms, 4, bf16=False, std=0.3, gate_std=1.0, router_std=0.5)
+    toks = synth.token_ids((3,), ms.vocab, seed=5)
+    H, _ = O.PLTOracle(shape, wts, w_mx=True).seq_forward(toks)
+    W = wts["layers"][0]
+    dq = lambda M: O.mx_dequantize(*O.mx_quantize(M, "e2m1"))
+    qa = lambda t: O.mx_dequantize(*O.mx_quantize(t, "e4m3"))
+    x = wts["emb"][toks[0]].astype(np.float64)
+    a = qa(O.rmsnorm(x, W["norm1"], shape.norm_eps))
+    v = (dq(W["wv"]) @ a).reshape(shape.n_kv_heads, shape.head_dim)
+    x = x + dq(W["wo"]) @ qa(np.repeat(v, 2, axis=0).reshape(-1))
+    b = qa(O.rmsnorm(x, W["norm2"], shape.norm_eps))
+    r = W["router"].astype(np.float64) @ b
+    p = np.exp(r - r.max()); p /= p.sum()
+    top = np.argsort(-p)[:2]
+    for e in top:
+        g = dq(W["w_gate"][e]) @ b
+        x = x + p[e] * (dq(W["w_down"][e]) @ qa(g / (1 + np.exp(-g)) * (dq(W["w_up"][e]) @ b)))
+    assert np.max(np.abs(H[0, 0] - x)) < 1e-10
+
+
 # ---- planted mistakes
 PINS = [test_e2m1_round_is_the_nearest_value_ties_to_even_saturating,
         test_mx_scale_is_the_power_of_two_that_puts_the_block_maximum_in_the_top_binade,
         test_mx_zero_block_and_exact_round_trip, test_mx_e4m3_elements_match_torch_conversion,
         test_mx_error_bounds, test_mx_linear_equals_explicit_block_sums,
-        test_model_with_mx_linear_layers_equals_a_model_on_dequantised_weights_and_quantised_inputs]
+        test_model_with_mx_linear_layers_equals_a_model_on_dequantised_weights_and_quantised_inputs,
+        test_moe_model_with_mx_experts_equals_hand_composition]
 
 
 def some_pin_fails():
@@ -226,4 +254,10 @@ def test_mx_quantize_mutations_are_caught(monkeypatch, kind):
 
 def test_quantising_the_wrong_operand_is_caught(monkeypatch):
     monkeypatch.setattr(O, "mx_linear", lambda a, w_q, w_e: O.mx_dequantize(w_q, w_e) @ np.asarray(a, np.float64))
+    assert some_pin_fails()
+
+
+def test_unquantised_expert_hidden_is_caught(monkeypatch):
+    orig = O.swiglu_ffn
+    monkeypatch.setattr(O, "swiglu_ffn", lambda b, wg, wu, wd, hidden_in=None: orig(b, wg, wu, wd, None))
     assert some_pin_fails()
