@@ -60,10 +60,11 @@ def fill_weights_on_device(B, cfg, seed):
     wd = torch.bfloat16 if cfg.dtype == B.PLT_BF16 else torch.float32
     Hq, Hkv, D, d, F = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_model, cfg.ffn_hidden
 
-    def matrix(layer, which, which_sc, N, K):
+    def matrix(layer, which, which_sc, N, K, count=1):
         if cfg.w_dtype == B.PLT_MXFP4:      # low-bit projections: a bf16 draw quantised on the device into the blob
-            w = (torch.randn(N, K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
-            B.quantize_into_blob(cfg, blob, layer, which, which_sc, w)
+            for index in range(count):
+                w = (torch.randn(N, K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+                B.quantize_into_blob(cfg, blob, layer, which, which_sc, w, index)
         else:
             normal(layer, which, wd)
 
@@ -76,8 +77,8 @@ def fill_weights_on_device(B, cfg, seed):
         view(m, B.PLT_W_NORM2, torch.float32)[0].fill_(1.0)
         if cfg.n_experts > 0:
             normal(m, B.PLT_W_ROUTER, wd)
-            normal(m, B.PLT_W_WGU, wd)
-            normal(m, B.PLT_W_WDOWN, wd)
+            matrix(m, B.PLT_W_WGU, B.PLT_W_WGU_SC, 2 * F, d, cfg.n_experts)
+            matrix(m, B.PLT_W_WDOWN, B.PLT_W_WDOWN_SC, d, F, cfg.n_experts)
         else:
             matrix(m, B.PLT_W_WGU, B.PLT_W_WGU_SC, 2 * F, d)
             matrix(m, B.PLT_W_WDOWN, B.PLT_W_WDOWN_SC, d, F)

@@ -168,7 +168,7 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
 
     def put_w(layer, which, which_sc, arr):
         if mx:
-            later.append((layer, which, which_sc, np.ascontiguousarray(arr, np.float32)))
+            later.append((layer, which, which_sc, np.ascontiguousarray(arr, np.float32), 0))
         else:
             put(layer, which, arr, True)
 
@@ -180,7 +180,13 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
         put(m, PLT_W_GATE_B, lw["gate_b"], False)
         put_w(m, PLT_W_WO, PLT_W_WO_SC, lw["wo"])
         put(m, PLT_W_NORM2, lw["norm2"], False)
-        if cfg.n_experts > 0:       # expert axis first; per expert its gate rows, then its up rows
+        if cfg.n_experts > 0 and mx:     # every expert's matrices quantised one by one
+            put(m, PLT_W_ROUTER, lw["router"], True)
+            gu = np.concatenate([lw["w_gate"], lw["w_up"]], axis=1)
+            for e in range(cfg.n_experts):
+                later.append((m, PLT_W_WGU, PLT_W_WGU_SC, np.ascontiguousarray(gu[e], np.float32), e))
+                later.append((m, PLT_W_WDOWN, PLT_W_WDOWN_SC, np.ascontiguousarray(lw["w_down"][e], np.float32), e))
+        elif cfg.n_experts > 0:       # expert axis first; per expert its gate rows, then its up rows
             tile = moe_tile_weights if cfg.dtype == PLT_BF16 else (lambda x: x)
             put(m, PLT_W_ROUTER, lw["router"], True)
             put(m, PLT_W_WGU, tile(np.concatenate([lw["w_gate"], lw["w_up"]], axis=1)), True)
@@ -192,19 +198,22 @@ def pack_weights(cfg: plt_config, weights: dict, device="cuda"):
     if not cfg.tie_embeddings:
         put(0, PLT_W_HEAD, weights["head"], True)
     blob = torch.from_numpy(host).to(device)
-    for layer, which, which_sc, arr in later:
-        quantize_into_blob(cfg, blob, layer, which, which_sc, torch.from_numpy(arr).to(device).to(torch.bfloat16))
+    for layer, which, which_sc, arr, index in later:
+        quantize_into_blob(cfg, blob, layer, which, which_sc, torch.from_numpy(arr).to(device).to(torch.bfloat16), index)
     return blob
 
 
-def quantize_into_blob(cfg, blob, layer, which, which_sc, w_bf16):
-    """Low-bit models: quantises one bf16 projection matrix [N, K] (device) into its two blob tensors."""
+def quantize_into_blob(cfg, blob, layer, which, which_sc, w_bf16, index=0):
+    """Low-bit models: quantises one bf16 projection matrix [N, K] (device) into its two blob tensors
+    (index: which of the tensor's back-to-back matrices, i.e. the expert)."""
     N, K = w_bf16.shape
     off, n = weights_offset(cfg, layer, which)
     off_sc, n_sc = weights_offset(cfg, layer, which_sc)
-    assert n == N * K and n_sc == lib().plt_mx_weight_scale_bytes(N, K), (which, n, N, K)
-    _check(lib().plt_mx_quantize_weights(N, K, _ptr(w_bf16.contiguous()), C.c_void_p(blob.data_ptr() + off),
-                                         C.c_void_p(blob.data_ptr() + off_sc), _stream()))
+    sb = lib().plt_mx_weight_scale_bytes(N, K)
+    count = max(cfg.n_experts, 1) if which in (PLT_W_WGU, PLT_W_WDOWN) else 1
+    assert n == count * N * K and n_sc == count * sb and index < count, (which, n, N, K)
+    _check(lib().plt_mx_quantize_weights(N, K, _ptr(w_bf16.contiguous()), C.c_void_p(blob.data_ptr() + off + index * (N * K // 2)),
+                                         C.c_void_p(blob.data_ptr() + off_sc + index * sb), _stream()))
 
 
 class Model:

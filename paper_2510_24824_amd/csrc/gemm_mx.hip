@@ -113,7 +113,6 @@ template void launch_mx_quant_a<bf16_t>(hipStream_t, const bf16_t*, uint8_t*, ui
 // half a K range at a time, the next half prefetched while the current one is multiplied.  One B fragment
 // read from LDS feeds NB MFMAs.  Each K range writes its own float slab; consumers add the slabs in a
 // fixed order.
-constexpr int MX_KR = 1024, MX_LDA = MX_KR + 16, MX_SB = MX_KR / 32;     // slice row: 1024 code bytes (+ pad); 32 scale bytes
 
 template <int MT, int NB>
 __global__ __launch_bounds__(256) void k_gemm_mx(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,

@@ -28,15 +28,23 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 // loads of all 8 weight rows issued together (the router matrix is small and cache-resident: what costs
 // here is load latency, not bytes).
 constexpr int ROUTE_WAVES = 8, ROUTE_EB = 8;
-template <typename T>
-__global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const T* __restrict__ a, const T* __restrict__ wr,
+// TA: type of the row (model dtype, or fp8_t: e4m3 codes with block scales a_sc of a low-bit model); T: router matrix
+template <typename TA, typename T>
+__global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __restrict__ a, const uint8_t* __restrict__ a_sc,
+                                                                const T* __restrict__ wr,
                                                                 int32_t* __restrict__ sel_e, float* __restrict__ sel_p,
                                                                 int d, int E, int k) {
   extern __shared__ float sm_route[];       // [d] the row as float, then [E] logits
   float* xr = sm_route;
   float* lg = sm_route + d;
   const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  for (int i = tid; i < d; i += ROUTE_WAVES * 64) xr[i] = ld<T>(a + (size_t)r * d + i);
+  if constexpr (sizeof(TA) == 1) {
+    const int nbp = mx_ascale_row_bytes(d);
+    for (int i = tid; i < d; i += ROUTE_WAVES * 64)
+      xr[i] = ldexpf(e4m3_to_f32(a[(size_t)r * d + i]), (int)a_sc[(size_t)r * nbp + mx_ascale_index(i >> 5)] - 127);
+  } else {
+    for (int i = tid; i < d; i += ROUTE_WAVES * 64) xr[i] = ld<TA>(a + (size_t)r * d + i);
+  }
   __syncthreads();
   for (int e0 = wv; e0 < E; e0 += ROUTE_WAVES * ROUTE_EB) {
     float acc[ROUTE_EB];
@@ -431,8 +439,8 @@ template <typename T>
 void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, const T* wdown, T* act, float* y,
                     MoeIndex mi, int R, int d, int F, int E, int k) {
   const int P = R * k;
-  hipLaunchKernelGGL(k_moe_route<T>, dim3(R), dim3(ROUTE_WAVES * 64), (size_t)(d + E) * sizeof(float), s, a, router, mi.sel_e, mi.sel_p,
-                     d, E, k);
+  hipLaunchKernelGGL((k_moe_route<T, T>), dim3(R), dim3(ROUTE_WAVES * 64), (size_t)(d + E) * sizeof(float), s, a,
+                     (const uint8_t*)nullptr, router, mi.sel_e, mi.sel_p, d, E, k);
   if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
@@ -449,5 +457,220 @@ template void launch_moe_ffn<float>(hipStream_t, const float*, const float*, con
                                     MoeIndex, int, int, int, int, int);
 template void launch_moe_ffn<bf16_t>(hipStream_t, const bf16_t*, const bf16_t*, const bf16_t*, const bf16_t*, bf16_t*,
                                      float*, MoeIndex, int, int, int, int, int);
+
+// ---------------------------------------------------------------------------------------------- low-bit experts
+// The grouped GEMM on MXFP4 expert weights and MXFP8 rows (block-scaled matrix cores, operand layouts as in
+// gemm_mx.hip).  Workgroup = (expert, 128 output columns, GU: 128 hidden columns); a wave streams 4 strips
+// (GU: the gate and up strips of 32 hidden columns, so that a wave owns whole 32-wide blocks of the hidden
+// vector and can quantise them to e4m3 in its epilogue).
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+template <int MT, bool GU>
+__global__ __launch_bounds__(256) void k_moe_gemm_mx(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
+                                                     const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
+                                                     const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
+                                                     const float* __restrict__ sel_p, uint8_t* __restrict__ act_out,
+                                                     uint8_t* __restrict__ act_sc_out, float* __restrict__ y_out,
+                                                     int R, int N, int K, int topk) {
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds_moe_mx[];   // [MT*16][MX_LDA] codes, then [MT*16][MX_SB] scales
+  uint8_t* As = lds_moe_mx;
+  uint8_t* Ss = lds_moe_mx + MT * 16 * MX_LDA;
+  constexpr int NS = 4;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int e = blockIdx.y;
+  const int beg = off[e], n_e = off[e + 1] - beg;
+  if (n_e <= 0) return;
+  const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, n_rng = (K + MX_KR - 1) / MX_KR;
+  const int NR = GU ? 2 * N : N;                                 // rows of one expert's matrix
+  const int out_strips = N >> 4;
+  // the wave's four weight streams: strip (within the expert's matrix) and output column of each
+  int col0[NS];
+  const uint8_t* wp[NS];
+  const uint8_t* sp[NS];
+#pragma unroll
+  for (int sb = 0; sb < NS; ++sb) {
+    int strip = GU ? (blockIdx.x * 4 + wv) * 2 + (sb & 1) : (blockIdx.x * 4 + wv) * 4 + sb;
+    col0[sb] = strip * 16;
+    if (strip >= out_strips) strip = out_strips - 1;             // beyond N: a valid strip, results not stored
+    const int strip_abs = (GU && sb >= 2) ? out_strips + strip : strip;      // up rows follow the gate rows
+    wp[sb] = w + (size_t)e * ((size_t)NR * K / 2) + (size_t)strip_abs * n_chunks * 1024 + lane * 16;
+    sp[sb] = w_sc + (size_t)e * mx_wscale_bytes(NR, K) + ((size_t)strip_abs * n_cgrp * 64 + lane) * 4;
+  }
+  struct WBuf { uint4 q[NS][4]; unsigned sc[NS]; };
+  WBuf bufA, bufB;
+  auto wload = [&](WBuf& f, int h, int rng) {      // half h of K range rng: 4 chunks of codes + their scale dword
+    const int cg = rng * 2 + h;
+    const int cgs = cg < n_cgrp ? cg : n_cgrp - 1;                // beyond K: any finite scale will do
+#pragma unroll
+    for (int sb = 0; sb < NS; ++sb) {
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        int ch = cg * 4 + kk; if (ch >= n_chunks) ch = 0;         // beyond K: an in-range chunk (meets zero codes)
+        f.q[sb][kk] = ldg16_stream(wp[sb] + (size_t)ch * 1024);
+      }
+      f.sc[sb] = *reinterpret_cast<const unsigned*>(sp[sb] + (size_t)cgs * 256);
+    }
+  };
+  const unsigned lds_as = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)As;
+  const int asb = mx_ascale_row_bytes(K);
+  auto load_slice = [&](int m0, int rng) {
+    const int k0 = rng * MX_KR;
+    const int kr = (K - k0 < MX_KR) ? K - k0 : MX_KR;
+    if (kr == MX_KR) {
+      for (int row = wv; row < MT * 16; row += 4) {
+        int li = m0 + row; if (li >= n_e) li = n_e - 1;
+        const int src_row = GU ? pair[beg + li] / topk : beg + li;
+        const uint8_t* src = a + (size_t)src_row * K + k0 + lane * 16;
+        const unsigned dst = __builtin_amdgcn_readfirstlane(lds_as + (unsigned)row * MX_LDA);
+        unsigned keep_m0;                                          // m0 is left as it was found
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep_m0) : "s"(dst), "v"(src) : "memory");
+      }
+    } else {
+      for (int ch = tid; ch < MT * 16 * (MX_KR / 16); ch += 256) {  // ragged range: zero-filled beyond K
+        const int row = ch / (MX_KR / 16), kc = (ch % (MX_KR / 16)) * 16;
+        int li = m0 + row; if (li >= n_e) li = n_e - 1;
+        const int src_row = GU ? pair[beg + li] / topk : beg + li;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (kc < kr) v = *reinterpret_cast<const uint4*>(a + (size_t)src_row * K + k0 + kc);
+        *reinterpret_cast<uint4*>(&As[row * MX_LDA + kc]) = v;
+      }
+    }
+    for (int ch = tid; ch < MT * 16 * 2; ch += 256) {               // two 16-byte scale groups per row and range
+      const int row = ch >> 1, h = ch & 1;
+      int li = m0 + row; if (li >= n_e) li = n_e - 1;
+      const int src_row = GU ? pair[beg + li] / topk : beg + li;
+      const int cg = rng * 2 + h;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (cg * 16 < asb) v = *reinterpret_cast<const uint4*>(a_sc + (size_t)src_row * asb + cg * 16);
+      *reinterpret_cast<uint4*>(&Ss[row * MX_SB + h * 16]) = v;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  };
+  f32x4 acc[NS][MT];
+  struct BFrag { uint4 lo, hi; };
+  auto bload = [&](int h, int idx) {
+    const int kk = idx / MT, i = idx - kk * MT;
+    const uint8_t* ap = &As[(i * 16 + m16) * MX_LDA + (h * 4 + kk) * 128 + g * 16];
+    BFrag r; r.lo = *reinterpret_cast<const uint4*>(ap); r.hi = *reinterpret_cast<const uint4*>(ap + 64);
+    return r;
+  };
+  auto mac = [&](const WBuf& f, int h) {
+    unsigned bsc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) bsc[i] = *reinterpret_cast<const unsigned*>(&Ss[(i * 16 + m16) * MX_SB + h * 16 + g * 4]);
+    BFrag cur = bload(h, 0);
+#pragma unroll
+    for (int idx = 0; idx < 4 * MT; ++idx) {
+      const int kk = idx / MT, i = idx - kk * MT;
+      BFrag nxt = cur;
+      if (idx + 1 < 4 * MT) nxt = bload(h, idx + 1);
+      const i32x8 bv = {(int)cur.lo.x, (int)cur.lo.y, (int)cur.lo.z, (int)cur.lo.w, (int)cur.hi.x, (int)cur.hi.y, (int)cur.hi.z, (int)cur.hi.w};
+#pragma unroll
+      for (int sb = 0; sb < NS; ++sb) {
+        const i32x8 av = {(int)f.q[sb][kk].x, (int)f.q[sb][kk].y, (int)f.q[sb][kk].z, (int)f.q[sb][kk].w, 0, 0, 0, 0};
+        if (kk == 0) acc[sb][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[sb][i], 4, 0, 0, (int)f.sc[sb], 0, (int)bsc[i]);
+        else if (kk == 1) acc[sb][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[sb][i], 4, 0, 1, (int)f.sc[sb], 1, (int)bsc[i]);
+        else if (kk == 2) acc[sb][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[sb][i], 4, 0, 2, (int)f.sc[sb], 2, (int)bsc[i]);
+        else acc[sb][i] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[sb][i], 4, 0, 3, (int)f.sc[sb], 3, (int)bsc[i]);
+      }
+      cur = nxt;
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    // keeps the compiler from moving this half's MFMAs into later blocks (and their operands alive until then)
+#pragma unroll
+    for (int sb = 0; sb < NS; ++sb)
+#pragma unroll
+      for (int i = 0; i < MT; ++i) asm volatile("" : "+v"(acc[sb][i]));
+  };
+  wload(bufA, 0, 0);
+  for (int m0 = 0; m0 < n_e; m0 += MT * 16) {
+#pragma unroll
+    for (int sb = 0; sb < NS; ++sb)
+#pragma unroll
+      for (int i = 0; i < MT; ++i) acc[sb][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int rng = 0; rng < n_rng; ++rng) {
+      __syncthreads();                       // every wave is done with the previous slice
+      load_slice(m0, rng);
+      __syncthreads();
+      wload(bufB, 1, rng);
+      mac(bufA, 0);
+      wload(bufA, 0, rng + 1 < n_rng ? rng + 1 : 0);     // next range, or range 0 again for the next row tile (unused at the end)
+      mac(bufB, 1);
+    }
+    const int nbp = mx_ascale_row_bytes(N);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      const int li = m0 + i * 16 + m16;
+      if (GU) {
+        // hidden values of row li: columns col0[j] + 4 g + x (j = 0, 1); the 32-wide block = both strips x the 4 lane groups
+        float h[2][4];
+        float amax = 0.f;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const float gt = acc[j][i][x];
+            h[j][x] = gt / (1.0f + expf(-gt)) * acc[2 + j][i][x];
+            amax = fmaxf(amax, fabsf(h[j][x]));
+          }
+        amax = fmaxf(amax, __shfl_xor(amax, 16)); amax = fmaxf(amax, __shfl_xor(amax, 32));
+        const int ex = mx_block_exponent(amax, 8);
+        if (li < n_e && col0[0] < N) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            *reinterpret_cast<unsigned*>(act_out + (size_t)(beg + li) * N + col0[j] + 4 * g) = mx_pack4_e4m3(h[j][0], h[j][1], h[j][2], h[j][3], ex);
+          if (g == 0) act_sc_out[(size_t)(beg + li) * nbp + mx_ascale_index(col0[0] >> 5)] = (uint8_t)(ex + 127);
+        }
+      } else {
+        if (li >= n_e) continue;
+        const int pr = pair[beg + li];
+        const int row = pr / topk, slot = pr - row * topk;
+        const float p = sel_p[pr];
+#pragma unroll
+        for (int sb = 0; sb < NS; ++sb) {
+          const int col = col0[sb] + 4 * g;
+          if (col >= N) continue;
+          f32x4 o = acc[sb][i];
+          o[0] *= p; o[1] *= p; o[2] *= p; o[3] *= p;
+          *reinterpret_cast<f32x4*>(y_out + ((size_t)slot * R + row) * N + col) = o;
+        }
+      }
+    }
+  }
+}
+
+template <int MT, bool GU>
+static void moe_gemm_mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc,
+                               const MoeIndex& mi, uint8_t* act, uint8_t* act_sc, float* y, int R, int N, int K, int k, int E) {
+  const size_t lds = (size_t)MT * 16 * (MX_LDA + MX_SB);
+  static bool attr_done = false;     // one flag per template instance
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_moe_gemm_mx<MT, GU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    attr_done = true;
+  }
+  const int cols_per_wg = GU ? 128 : 256;
+  hipLaunchKernelGGL((k_moe_gemm_mx<MT, GU>), dim3((N + cols_per_wg - 1) / cols_per_wg, E), dim3(256), lds, s, a, a_sc, w, w_sc,
+                     mi.off, mi.pair, mi.sel_p, act, act_sc, y, R, N, K, k);
+}
+
+void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const bf16_t* router, const uint8_t* wgu,
+                       const uint8_t* wgu_sc, const uint8_t* wdown, const uint8_t* wdown_sc, uint8_t* act_codes,
+                       uint8_t* act_scales, float* y, MoeIndex mi, int R, int d, int F, int E, int k) {
+  const int P = R * k;
+  hipLaunchKernelGGL((k_moe_route<fp8_t, bf16_t>), dim3(R), dim3(ROUTE_WAVES * 64), (size_t)(d + E) * sizeof(float), s, a, a_sc,
+                     router, mi.sel_e, mi.sel_p, d, E, k);
+  if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  const long mean = ((long)P + E - 1) / E;
+  if (mean <= 40) {
+    moe_gemm_mx_launch<2, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
+    moe_gemm_mx_launch<2, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
+  } else {
+    moe_gemm_mx_launch<8, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
+    moe_gemm_mx_launch<8, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
+  }
+}
 
 }  // namespace plt

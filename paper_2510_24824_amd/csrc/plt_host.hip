@@ -58,6 +58,7 @@ struct plt_kv {
   float* carry; int32_t* pos_dev; void* attn_scratch; size_t attn_scratch_bytes;
   void* moe_idx;       // mixture-of-experts models: routing lists of one pass (moe_index_bytes)
   uint8_t *a_codes, *a_scales;   // low-bit models: the quantised input of the next projection
+  uint8_t* act_sc;               // low-bit mixture-of-experts models: block scales of the experts' hidden rows
   float* arg_v; int* arg_i;   // argmax chunk winners
 };
 
@@ -81,7 +82,7 @@ static bool cfg_valid(const plt_config* c, const char** why) {
   if (c->kv_dtype == PLT_FP8_E4M3 && c->dtype != PLT_BF16) { *why = "e4m3 caches need dtype PLT_BF16"; return false; }
   if (c->w_dtype != 0 && c->w_dtype != PLT_MXFP4) { *why = "unknown w_dtype"; return false; }
   if (c->w_dtype == PLT_MXFP4) {
-    if (c->dtype != PLT_BF16 || c->n_experts != 0) { *why = "MXFP4 projections need dtype PLT_BF16 and a dense feed-forward"; return false; }
+    if (c->dtype != PLT_BF16) { *why = "MXFP4 projections need dtype PLT_BF16"; return false; }
     if (c->d_model % 128 || c->ffn_hidden % 128 || (c->n_heads * c->head_dim) % 128) {
       *why = "MXFP4 projections need d_model, ffn_hidden and n_heads * head_dim to be multiples of 128"; return false;
     }
@@ -108,13 +109,13 @@ static size_t blob_walk(const plt_config* c, int want_layer, int want_which, siz
   };
   // low-bit projection [N, K]: e2m1 codes (reported element count N*K, two per byte), then its scale bytes
   const bool mx = c->w_dtype == PLT_MXFP4;
-  auto put_w = [&](int layer, int which, int which_sc, size_t N, size_t K) {
-    if (!mx) { put(layer, which, N * K, es); return; }
+  auto put_w = [&](int layer, int which, int which_sc, size_t N, size_t K, size_t count = 1) {   // count matrices back to back
+    if (!mx) { put(layer, which, count * N * K, es); return; }
     cur = align256(cur);
-    if (which == want_which && layer == want_layer) { if (off) *off = cur; if (nelem) *nelem = N * K; }
-    cur += N * K / 2;
+    if (which == want_which && layer == want_layer) { if (off) *off = cur; if (nelem) *nelem = count * N * K; }
+    cur += count * N * K / 2;
     cur = align256(cur);
-    const size_t sb = mx_wscale_bytes((int)N, (int)K);
+    const size_t sb = count * mx_wscale_bytes((int)N, (int)K);
     if (which_sc == want_which && layer == want_layer) { if (off) *off = cur; if (nelem) *nelem = sb; }
     cur += sb;
   };
@@ -127,7 +128,7 @@ static size_t blob_walk(const plt_config* c, int want_layer, int want_which, siz
     put_w(m, PLT_W_WO, PLT_W_WO_SC, d, Hq * D);
     put(m, PLT_W_NORM2, d, 4);
     if (E > 0) put(m, PLT_W_ROUTER, E * d, es);
-    if (mx) { put_w(m, PLT_W_WGU, PLT_W_WGU_SC, 2 * F, d); put_w(m, PLT_W_WDOWN, PLT_W_WDOWN_SC, d, F); }
+    if (mx) { put_w(m, PLT_W_WGU, PLT_W_WGU_SC, 2 * F, d, Ex); put_w(m, PLT_W_WDOWN, PLT_W_WDOWN_SC, d, F, Ex); }
     else { put(m, PLT_W_WGU, Ex * 2 * F * d, es); put(m, PLT_W_WDOWN, Ex * d * F, es); }
   }
   put(-1, PLT_W_NORM_F, d, 4);
@@ -287,7 +288,7 @@ extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_
 static void kv_release(plt_kv* kv) {
   if (!kv) return;
   void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch,
-                  kv->arg_v, kv->arg_i, kv->moe_idx, kv->a_codes, kv->a_scales};
+                  kv->arg_v, kv->arg_i, kv->moe_idx, kv->a_codes, kv->a_scales, kv->act_sc};
   for (void* p : ptrs) if (p) (void)hipFree(p);
   delete kv;
 }
@@ -354,6 +355,11 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
     const int maxK = mx_max_k(c);
     dmalloc((void**)&kv->a_codes, (size_t)R * maxK);
     dmalloc((void**)&kv->a_scales, (size_t)R * mx_ascale_row_bytes(maxK));
+    if (c.n_experts > 0) {
+      const size_t nb = (size_t)R * c.top_k * mx_ascale_row_bytes(F);
+      dmalloc((void**)&kv->act_sc, nb);
+      if (e == hipSuccess) e = hipMemsetAsync(kv->act_sc, 0, nb, m->stream);     // pad bytes stay 0
+    }
   }
   if (c.n_experts > 0) dmalloc(&kv->moe_idx, moe_index_bytes(R, c.top_k, c.n_experts));
   dmalloc((void**)&kv->carry, (size_t)batch * (L > 1 ? L - 1 : 1) * d * 4);
@@ -401,6 +407,7 @@ struct Work {            // activation buffers one pass of the stack runs on
   float* attn_tmp;   // prefill only: float [rows, Hq*D]
   void* moe_idx;     // mixture-of-experts models: routing lists (moe_index_bytes for the pass's rows)
   uint8_t *a_codes, *a_scales;   // low-bit models: e4m3 codes / block scales of the next projection's input
+  uint8_t* act_sc;               // low-bit mixture-of-experts models: block scales of the experts' hidden rows
 };
 
 static int run_gemm(plt_model* m, const void* a, const void* w, float* out, int M, int N, int K,
@@ -493,7 +500,13 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);
     }
     norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, w.norm2, R);
-    if (m->mx) {                                             // low-bit gate/up and down projections
+    if (m->mx && c.n_experts > 0) {                          // mixture of experts on low-bit operands
+      ProfScope prof(m, PLT_PROF_GEMM, dec);
+      launch_moe_ffn_mx(s, wk.a_codes, wk.a_scales, (const bf16_t*)w.router, (const uint8_t*)w.wgu, w.wgu_sc,
+                        (const uint8_t*)w.wdown, w.wdown_sc, (uint8_t*)wk.act, wk.act_sc, wk.gout,
+                        moe_index_carve(wk.moe_idx, R, c.top_k, c.n_experts), R, d, F, c.n_experts, c.top_k);
+      S = c.top_k;
+    } else if (m->mx) {                                      // low-bit gate/up and down projections
       S = run_gemm_mx(m, wk, w.wgu, w.wgu_sc, R, 2 * F, d, dec);
       launch_silu_mul_mx(s, wk.gout, S, (size_t)R * 2 * F, wk.a_codes, wk.a_scales, R, F);      // SwiGLU + e4m3 blocks
       S = run_gemm_mx(m, wk, w.wdown, w.wdown_sc, R, d, F, dec);
@@ -533,7 +546,7 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
   const plt_config& c = m->cfg;
   hipStream_t s = m->stream;
   const int B = kv->B, L = c.n_loops, d = c.d_model;
-  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr, kv->moe_idx, kv->a_codes, kv->a_scales};
+  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr, kv->moe_idx, kv->a_codes, kv->a_scales, kv->act_sc};
   KvView none{}; none.b0 = 0;
   if (is_clp(c)) {
     // Alg. 1 l.5-7: rows B_0 = e, B_l = e + H^l[p-1]; the L rows of a sequence run as one pass
@@ -604,6 +617,7 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
                o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
                o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * topk * F * wes),
                o_ac = carve(m->mx ? (size_t)Rc * mx_max_k(c) : 256), o_as = carve(m->mx ? (size_t)Rc * mx_ascale_row_bytes(mx_max_k(c)) : 256),
+               o_hs = carve(m->mx && E > 0 ? (size_t)Rc * topk * mx_ascale_row_bytes(F) : 256),
                o_moe = carve(E > 0 ? moe_index_bytes(Rc, topk, E) : 256),
                o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes),
                o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
@@ -612,7 +626,8 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
   if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
   (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * kes), s);
   Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act,
-          (float*)(ws + o_tmp), ws + o_moe, (uint8_t*)(ws + o_ac), (uint8_t*)(ws + o_as)};
+          (float*)(ws + o_tmp), ws + o_moe, (uint8_t*)(ws + o_ac), (uint8_t*)(ws + o_as), (uint8_t*)(ws + o_hs)};
+  if (m->mx && E > 0) (void)hipMemsetAsync(ws + o_hs, 0, (size_t)Rc * topk * mx_ascale_row_bytes(F), s);
   float* hprev = (float*)(ws + o_h);
   for (int b0 = 0; b0 < B; b0 += Bc) {
     const int bc = b0 + Bc <= B ? Bc : B - b0;

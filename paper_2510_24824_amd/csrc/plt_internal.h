@@ -185,7 +185,7 @@ __host__ __device__ inline size_t mx_wscale_index(int n, int b, int K) {
   const int chunk = b >> 2, g = b & 3, n_cgrp = ((K >> 7) + 3) >> 2;
   return (((size_t)(n >> 4) * n_cgrp + (chunk >> 2)) * 64 + g * 16 + (n & 15)) * 4 + (chunk & 3);
 }
-inline size_t mx_wscale_bytes(int N, int K) { return (size_t)(N >> 4) * ((((K >> 7) + 3) >> 2)) * 256; }
+__host__ __device__ inline size_t mx_wscale_bytes(int N, int K) { return (size_t)(N >> 4) * ((((K >> 7) + 3) >> 2)) * 256; }
 // scale byte of k block b inside one activation row: groups of 16 blocks stored [g = b mod 4][c = (b / 4) mod 4]
 __host__ __device__ inline int mx_ascale_index(int b) { return (b >> 4) * 16 + (b & 3) * 4 + ((b >> 2) & 3); }
 __host__ __device__ inline int mx_ascale_row_bytes(int K) { return ((K + 511) >> 9) * 16; }
@@ -205,6 +205,8 @@ bool resid_norm_mx_applies(int d);
 void launch_resid_norm_mx(hipStream_t s, float* x, const float* partials, int S, size_t slab, const float* gain, float eps,
                           uint8_t* codes, uint8_t* scales, int R, int d);
 void launch_silu_mul_mx(hipStream_t s, const float* gu, int S, size_t slab, uint8_t* codes, uint8_t* scales, int R, int F);
+// LDS slice of the low-bit GEMMs: one K range of 1024 per row = 1024 code bytes (+ pad) and 32 scale bytes
+constexpr int MX_KR = 1024, MX_LDA = MX_KR + 16, MX_SB = MX_KR / 32;
 // gemm_mx.hip
 void launch_mx_quant_w(hipStream_t s, const bf16_t* w, uint8_t* codes, uint8_t* scales, int N, int K);
 template <typename T>
@@ -224,6 +226,13 @@ MoeIndex moe_index_carve(void* base, int R, int k, int E);
 template <typename T>
 void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, const T* wdown, T* act, float* y,
                     MoeIndex mi, int R, int d, int F, int E, int k);
+// the same layer on low-bit operands: a as e4m3 codes + block scales [R, d]; router bf16 [E, d]; per expert the
+// gate/up matrix [2F, d] and the down matrix [d, F] as e2m1 codes + scales in the layouts of gemm_mx.hip
+// (expert e's tensors start at e times the size of one); act_codes / act_scales: scratch [R*k, F] e4m3 blocks
+// (the pad bytes of act_scales must be zero)
+void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const bf16_t* router, const uint8_t* wgu,
+                       const uint8_t* wgu_sc, const uint8_t* wdown, const uint8_t* wdown_sc, uint8_t* act_codes,
+                       uint8_t* act_scales, float* y, MoeIndex mi, int R, int d, int F, int E, int k);
 
 // attn_f32.hip : one wave per (row, query head), float storage
 void launch_attn_f32(hipStream_t s, const float* q, const float* z, float* y, KvView kv,

@@ -163,3 +163,44 @@ def test_lowbit_model_single_position():
 # output then differs by about sqrt(0.03) * 2^-4.5 = 0.8 % (rms), and the differences add up over 4 projections,
 # 2 layers and the loop-to-loop carry: a few per cent of the state's magnitude (~3), measured 0.13-0.15 max-abs.
 MX_MODEL_TOL = 0.25
+
+
+MX_MOE = synth.ModelShape(n_layers=2, d_model=128, n_heads=2, n_kv_heads=2, head_dim=64, ffn_hidden=128, vocab=300,
+                          n_loops=2, window=5, n_experts=6, top_k=2)
+
+
+def test_moe_model_with_lowbit_experts_single_position():
+    """Mixture of experts on low-bit operands, one position and L = 1 (no code flips from attention, see the dense
+    single-position test): router on the quantised row, grouped block-scaled GEMMs, hidden rows quantised in the
+    gate/up epilogue.  Seed chosen (from the oracle alone) so that every routing gap exceeds 0.05."""
+    from tests.helpers import with_shape
+    from tests.helpers import oshape
+    shape = with_shape(MX_MOE, n_loops=1)
+    weights = lively_weights(shape, MX_MOE_SEED, bf16=True, std=0.05, router_std=0.2)
+    prompts = synth.token_ids((8, 1), shape.vocab, MX_MOE_SEED + 1)
+    gaps = []
+    for b in range(8):
+        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=True, w_mx=True)
+        orc.greedy_generate(list(prompts[b]), 0)
+        gaps += orc.route_margins
+    assert min(gaps) > 0.05, min(gaps)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 0, 2e-2, w_dtype=B.PLT_MXFP4)
+
+
+def test_moe_model_with_lowbit_experts():
+    """Several positions and loops; tolerance and its reason as for the dense low-bit model above.  The seed keeps
+    every routing gap of the oracle above 0.05 (router logits are ~N(0, 2.3)), several times the logit noise
+    that flipped e4m3 codes cause."""
+    from tests.helpers import oshape
+    weights = lively_weights(MX_MOE, 8, bf16=True, std=0.05, router_std=0.2)
+    prompts = synth.token_ids((2, 4), MX_MOE.vocab, 10)
+    gaps = []
+    for b in range(2):
+        orc = O.PLTOracle(oshape(MX_MOE), weights, kv_bf16=True, w_mx=True)
+        orc.greedy_generate(list(prompts[b]), 3)
+        gaps += orc.route_margins
+    assert min(gaps) > 0.05, min(gaps)
+    run_teacher_forced(MX_MOE, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 3, MX_MODEL_TOL, w_dtype=B.PLT_MXFP4)
+
+
+MX_MOE_SEED = 0
