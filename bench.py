@@ -470,6 +470,27 @@ def bench_moe(B, g, Bn, N, w, steps, batches):
         mo["batch_%d_ms_per_step" % bn] = row
         log(f"[bench] MoE 8-of-64 shape, batch {bn}: non-looped {row['nonlooped_L1']:.3f} ms, PLT-2 {row['plt_L2']:.3f}, "
             f"PLT-3 {row['plt_L3']:.3f}, vanilla loop 2 {row['vanilla_loop_L2']:.3f}")
+    # the serving recipe on this shape: e4m3 caches + MXFP4 projections and experts (MXFP8 rows)
+    lblob = fill_weights_on_device(B, B.make_config(mshape, dtype=B.PLT_BF16, w_dtype=B.PLT_MXFP4), SEED + 6)
+    for bn in batches:
+        mtok = torch.randint(0, mshape.vocab, (bn,), generator=g, device="cuda", dtype=torch.int32)
+        row = {}
+        for name, mode, Lx in [("nonlooped_L1", B.PLT_MODE_CLP, 1), ("plt_L2", B.PLT_MODE_CLP, 2), ("plt_L3", B.PLT_MODE_CLP, 3),
+                               ("vanilla_loop_L2", B.PLT_MODE_VANILLA_LOOP, 2)]:
+            cm = B.make_config(mshape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w, kv_dtype=B.PLT_FP8_E4M3, w_dtype=B.PLT_MXFP4)
+            mm = B.Model(cm, lblob)
+            km = B.KV(mm, bn, N)
+            fill_kv_random(B, km, g)
+            row[name] = time_steps(km, pos, mtok, 2, steps)
+            km.close(); mm.close(); del km
+            torch.cuda.empty_cache()
+        row["latency_vs_nonlooped"] = {k: row[k] / row["nonlooped_L1"] for k in ("plt_L2", "plt_L3", "vanilla_loop_L2")}
+        row["tokens_per_s_plt_L2"] = bn / (row["plt_L2"] * 1e-3)
+        mo["mxfp4_e4m3kv_batch_%d_ms_per_step" % bn] = row
+        log(f"[bench] MoE shape, MXFP4 experts + e4m3 caches, batch {bn}: non-looped {row['nonlooped_L1']:.3f} ms, PLT-2 {row['plt_L2']:.3f}, "
+            f"PLT-3 {row['plt_L3']:.3f}, vanilla loop 2 {row['vanilla_loop_L2']:.3f}")
+    mo["mxfp4_weight_blob_bytes"] = int(lblob.numel()); mo["bf16_weight_blob_bytes"] = int(mblob.numel())
+    del lblob
     mo["expert_weight_bytes_per_layer"] = 64 * 3 * mshape.ffn_hidden * mshape.d_model * 2
     mo["workload"] = ("16 layers, d=2048, 16 heads x 128, 64 SwiGLU experts of hidden 1024 (8 per row), vocab 50304, "
                       "%d-token context, bf16 caches" % N)

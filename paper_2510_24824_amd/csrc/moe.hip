@@ -466,7 +466,7 @@ template void launch_moe_ffn<bf16_t>(hipStream_t, const bf16_t*, const bf16_t*, 
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 template <int MT, bool GU>
-__global__ __launch_bounds__(256) void k_moe_gemm_mx(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
+__global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
                                                      const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
                                                      const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
                                                      const float* __restrict__ sel_p, uint8_t* __restrict__ act_out,
@@ -664,9 +664,12 @@ void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, con
   else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   const long mean = ((long)P + E - 1) / E;
-  if (mean <= 40) {
+  if (mean <= 24) {
     moe_gemm_mx_launch<2, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
     moe_gemm_mx_launch<2, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
+  } else if (mean <= 48) {
+    moe_gemm_mx_launch<4, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
+    moe_gemm_mx_launch<4, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
   } else {
     moe_gemm_mx_launch<8, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
     moe_gemm_mx_launch<8, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
