@@ -89,8 +89,9 @@ typedef struct plt_config {
   int32_t top_k;          /* experts evaluated per row (1..min(E, 32)); ignored when E == 0 */
   int32_t w_dtype;        /* 0: projections in the model dtype; PLT_MXFP4: the four per-layer projections
                              (QKV, output, gate/up, down) on MXFP4 weights and MXFP8 activations, see
-                             "Low-bit projections" below (needs dtype == PLT_BF16, n_experts == 0, and
-                             d_model, ffn_hidden, n_heads * head_dim multiples of 128)              */
+                             "Low-bit projections" below; in a mixture-of-experts model every expert's
+                             gate/up and down matrices, the router staying in bf16 (needs dtype ==
+                             PLT_BF16 and d_model, ffn_hidden, n_heads * head_dim multiples of 128) */
 } plt_config;
 
 typedef struct plt_model plt_model; /* opaque */
@@ -111,7 +112,9 @@ typedef struct plt_kv plt_kv;       /* opaque */
  *   grouped GEMM streams every strip as one contiguous run.
  *   Low-bit models (w_dtype = PLT_MXFP4): WQKV, WO, WGU, WDOWN hold e2m1 codes (element count N*K, two per
  *   byte) and each is followed by its scale tensor WQKV_SC, WO_SC, WGU_SC, WDOWN_SC (element count = bytes),
- *   both in the layouts plt_mx_quantize_weights writes; embedding, head and float tensors are unchanged. */
+ *   both in the layouts plt_mx_quantize_weights writes; embedding, head, router and float tensors are
+ *   unchanged.  With experts, WGU holds E matrices [2F, d] and WDOWN E matrices [d, F] back to back (expert e's
+ *   codes start at e * N*K/2 bytes, its scales at e * plt_mx_weight_scale_bytes(N, K)). */
 enum { PLT_W_EMB = 0, PLT_W_NORM1, PLT_W_WQKV, PLT_W_GATE_W, PLT_W_GATE_B, PLT_W_WO,
        PLT_W_NORM2, PLT_W_WGU, PLT_W_WDOWN, PLT_W_NORM_F, PLT_W_HEAD, PLT_W_ROUTER,
        PLT_W_WQKV_SC, PLT_W_WO_SC, PLT_W_WGU_SC, PLT_W_WDOWN_SC };
