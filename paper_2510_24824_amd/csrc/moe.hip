@@ -430,7 +430,7 @@ template <bool GU>
 static void moe_gemm_pick(hipStream_t s, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act,
                           float* y, int R, int N, int K, int k, int E) {
   const long mean = ((long)R * k + E - 1) / E;
-  if (mean <= 24) moe_gemm_launch<2, 1024, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
+  if (mean <= 20) moe_gemm_launch<2, 1024, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
   else if (mean <= 48) moe_gemm_launch<4, 512, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
   else moe_gemm_launch<8, 512, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
 }
@@ -664,7 +664,7 @@ void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, con
   else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   const long mean = ((long)P + E - 1) / E;
-  if (mean <= 24) {
+  if (mean <= 20) {
     moe_gemm_mx_launch<2, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
     moe_gemm_mx_launch<2, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
   } else if (mean <= 48) {
