@@ -262,6 +262,8 @@ struct AttnDecArgs {
   float scale_log2;
   float* part;                 // [stream][rt][split] records of (16 + 16 + 16*D) floats
   float* part_loc;             // [stream][rt] records of 16*D floats (normalised local branch)
+  // low-bit models: y leaves as e4m3 blocks of 32 (the input format of the output projection) instead of bf16
+  uint8_t* y_codes; uint8_t* y_scales; int y_nbp;   // codes [rows, Hq*D], scale bytes [rows, y_nbp]; null = bf16 y
 };
 
 // Normalises the two branches of one row chunk, applies the gate of Eq. (2) and stores y.
@@ -285,7 +287,23 @@ __device__ inline void finalize_row(const AttnDecArgs& A, int b, int kvh, int rt
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) out[i] = og[i] * invg;
   }
-  store_row<D>(A.y + (((size_t)b * A.l_stride + A.l_off + r_loop) * A.Hq + r_head) * D + dc, out);
+  const size_t yrow = (size_t)b * A.l_stride + A.l_off + r_loop;
+  if (A.y_codes == nullptr) {
+    store_row<D>(A.y + (yrow * A.Hq + r_head) * D + dc, out);
+    return;
+  }
+  // a block of 32 features = 32 / (D/16) consecutive threads of this row (4 for D = 128, 8 for D = 64)
+  float amax = 0.f;
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) amax = fmaxf(amax, fabsf(out[i]));
+  amax = fmaxf(amax, __shfl_xor(amax, 1)); amax = fmaxf(amax, __shfl_xor(amax, 2));
+  if (D == 64) amax = fmaxf(amax, __shfl_xor(amax, 4));
+  const int e = mx_block_exponent(amax, 8);
+  const int col = r_head * D + dc;
+  unsigned* dst = reinterpret_cast<unsigned*>(A.y_codes + yrow * (size_t)(A.Hq * D) + col);
+#pragma unroll
+  for (int i = 0; i < D / 64; ++i) dst[i] = mx_pack4_e4m3(out[4 * i], out[4 * i + 1], out[4 * i + 2], out[4 * i + 3], e);
+  if ((col & 31) == 0) A.y_scales[yrow * A.y_nbp + mx_ascale_index(col >> 5)] = (uint8_t)(e + 127);
 }
 
 template <int D, bool F8>
@@ -493,8 +511,9 @@ int attn_mfma_default_splits(int B, int Hkv, int L, int G, int n_ctx, int kv_fp8
 void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, KvView kv,
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform, Dims dm,
                              int plain, void* scratch, int n_splits, int l_off, int l_stride, int kv_fp8,
-                             int scratch_splits) {
+                             int scratch_splits, uint8_t* y_codes, uint8_t* y_scales) {
   AttnDecArgs A;
+  A.y_codes = y_codes; A.y_scales = y_scales; A.y_nbp = mx_ascale_row_bytes(dm.Hq * dm.D);
   A.l_off = l_off; A.l_stride = l_stride > 0 ? l_stride : dm.L;
   A.q = q; A.z = z; A.y = y;
   A.k_share = (const char*)kv.k_share; A.v_share = (const char*)kv.v_share;

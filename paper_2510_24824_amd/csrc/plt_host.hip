@@ -465,6 +465,10 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
                                dm, m->inv_freq, variant);
     const bool dec = !rm.prefill;
     const int plain = variant != V_PLT;
+    // low-bit models, decode: the attention kernel writes y as e4m3 blocks itself (no scale padding needed)
+    const bool y_mx = m->mx && dec && ((Hq * D) % 512) == 0;
+    uint8_t* yc = y_mx ? wk.a_codes : nullptr;
+    uint8_t* ysc = y_mx ? wk.a_scales : nullptr;
     if (c.dtype == PLT_BF16) {                                                              // Alg. 3 l.2-5
       ProfScope prof(m, PLT_PROF_ATTN, dec);
       if (rm.prefill) {
@@ -481,12 +485,13 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
             vl.k_share = (char*)v.k_share + (size_t)lp * v.cache_stride * m->kes;
             vl.v_share = (char*)v.v_share + (size_t)lp * v.cache_stride * m->kes;
             launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, vl, kv->pos_dev, 0, 0, d1, 1,
-                                    kv->attn_scratch, ns, lp, attn_L, m->kv8, attn_mfma_max_default_splits(kv->B, Hkv));
+                                    kv->attn_scratch, ns, lp, attn_L, m->kv8, attn_mfma_max_default_splits(kv->B, Hkv), yc, ysc);
           }
         } else {
           const int ns = attn_mfma_default_splits(kv->B, Hkv, attn_L, G, kv->pos + 1, m->kv8);
           launch_attn_decode_mfma(s, (const bf16_t*)wk.q, wk.z, (bf16_t*)wk.y, v, kv->pos_dev, 0, 0, dm,
-                                  plain ? 1 : 0, kv->attn_scratch, ns, 0, 0, m->kv8, attn_mfma_max_default_splits(kv->B, Hkv));
+                                  plain ? 1 : 0, kv->attn_scratch, ns, 0, 0, m->kv8, attn_mfma_max_default_splits(kv->B, Hkv),
+                                  yc, ysc);
         }
       }
     } else {
@@ -494,7 +499,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       launch_attn_f32(s, (const float*)wk.q, wk.z, (float*)wk.y, v, rm, R, dm, variant == V_OWN_KV && dec ? 3 : plain);
     }
     if (m->mx) {                                                                                 // Alg. 3 l.6
-      launch_mx_quant_a<bf16_t>(s, (const bf16_t*)wk.y, wk.a_codes, wk.a_scales, R, Hq * D);
+      if (!y_mx) launch_mx_quant_a<bf16_t>(s, (const bf16_t*)wk.y, wk.a_codes, wk.a_scales, R, Hq * D);
       S = run_gemm_mx(m, wk, w.wo, w.wo_sc, R, d, Hq * D, dec);
     } else {
       S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);

@@ -246,7 +246,9 @@ void launch_attn_decode_mfma(hipStream_t s, const bf16_t* q, const float* z, bf1
                              const int32_t* pos, int n_ctx_uniform, int n_ring_uniform,
                              Dims dm, int plain, void* scratch, int n_splits,
                              int l_off = 0, int l_stride = 0 /* rows per sequence in q / y; 0 = dm.L */,
-                             int kv_fp8 = 0, int scratch_splits = 64 /* max_splits the scratch was sized with */);
+                             int kv_fp8 = 0, int scratch_splits = 64 /* max_splits the scratch was sized with */,
+                             uint8_t* y_codes = nullptr, uint8_t* y_scales = nullptr /* low-bit models: y as e4m3
+                             blocks [rows, Hq*D] + scale bytes instead of bf16 (Hq*D a multiple of 512) */);
 // local_tmp: float scratch [Bc*n, Hq*D] (used by loops >= 2 only)
 void launch_attn_prefill_mfma(hipStream_t s, const bf16_t* q, const float* z, bf16_t* y, float* local_tmp,
                               KvView kv, int Bc, int n, int loop, Dims dm, int plain, int kv_fp8 = 0);
