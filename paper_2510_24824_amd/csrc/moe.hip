@@ -16,7 +16,8 @@
 //   k_moe_gemm<DOWN>  workgroup = (expert, 128 model columns): act rows x the expert's down matrix, scaled
 //                     by p_e, scattered to y [slot][row][d]: k slabs that the residual kernel adds in slot
 //                     order (deterministic, no atomics)
-// Experts nobody selected cost no weight traffic (their workgroups leave at once).
+// Experts nobody selected cost no weight traffic (their workgroups leave at once).  Batches of up to 1024 rows
+// (decode steps) skip k_moe_bucket: the grouped GEMMs derive their expert's list from sel_e themselves.
 #include "plt_internal.h"
 
 namespace plt {
@@ -202,6 +203,32 @@ __global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__
   }
 }
 
+// ---------------------------------------------------------------------------------------------- expert lists
+// Decode-sized batches skip the sort kernel: every workgroup of the grouped GEMMs scans the R*k selections
+// itself (a few KB, cache-resident) and derives its expert's list -- the pairs i = row*k + slot with
+// sel_e[i] == e in increasing i -- and the list's first position beg = number of pairs of experts below e.
+// Same order and positions as the sort kernel produces, so both paths give identical results.
+constexpr int MOE_FLY_ROWS = 1024;          // longest expert list (= rows) handled this way; R*k <= 65535 as well
+__device__ inline void moe_expert_list(const int32_t* __restrict__ sel_e, int P, int e, uint16_t* list /* LDS [MOE_FLY_ROWS] */,
+                                       int* cnt /* LDS [8] */, int& beg, int& n_e) {
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int base = 0, n = 0;
+  for (int i0 = 0; i0 < P; i0 += 256) {
+    const int i = i0 + tid;
+    const int v = i < P ? sel_e[i] : 0x7fffffff;
+    const unsigned long long mlt = __ballot(v < e), meq = __ballot(v == e);
+    if (lane == 0) { cnt[wv] = __popcll(mlt); cnt[4 + wv] = __popcll(meq); }
+    __syncthreads();
+    int before = 0, all_eq = 0, all_lt = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { const int c = cnt[4 + w]; if (w < wv) before += c; all_eq += c; all_lt += cnt[w]; }
+    if (v == e) list[n + before + __popcll(meq & ((1ull << lane) - 1ull))] = (uint16_t)i;
+    n += all_eq; base += all_lt;
+    __syncthreads();
+  }
+  beg = base; n_e = n;
+}
+
 // ---------------------------------------------------------------------------------------------- grouped GEMM
 // c[rows of expert e][N] = rows x W_e[N][K]^T on the matrix cores.  The expert's rows (MT*16 at a time)
 // sit in LDS, one K range of KR at a time; each of the 4 waves streams NS 16-row strips of the expert's
@@ -214,8 +241,11 @@ __global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__
 template <int MT, int KR, bool GU, int NS, int KH>
 __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                   const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
+                                                  const int32_t* __restrict__ sel_e,
                                                   const float* __restrict__ sel_p, bf16_t* __restrict__ act_out,
                                                   float* __restrict__ y_out, int R, int N, int K, int topk) {
+  __shared__ uint16_t s_list[MOE_FLY_ROWS];
+  __shared__ int s_cnt[8];
   extern __shared__ __attribute__((aligned(16))) bf16_t As_moe[];   // [MT*16][KR + 8]
   bf16_t* As = As_moe;
   constexpr int LDK = KR + 8, STEPS = KR / (32 * KH);
@@ -223,8 +253,12 @@ __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, 
   static_assert(!GU || NS % 2 == 0, "gate and up strips come in pairs");
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int e = blockIdx.y;
-  const int beg = off[e], n_e = off[e + 1] - beg;
+  const bool fly = pair == nullptr;              // no sorted lists: derive this expert's list from the selections
+  int beg, n_e;
+  if (fly) moe_expert_list(sel_e, R * topk, e, s_list, s_cnt, beg, n_e);
+  else { beg = off[e]; n_e = off[e + 1] - beg; }
   if (n_e <= 0) return;
+  auto pair_at = [&](int li) -> int { return fly ? (int)s_list[li] : pair[beg + li]; };
   // this wave's weight strips: first output column of each and where its stream starts
   constexpr int NC = GU ? NS / 2 : NS;           // 16-column groups of the output per wave
   int col0[NC];
@@ -263,7 +297,7 @@ __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, 
     if (kr == KR) {
       for (int row = wv; row < MT * 16; row += 4) {
         int li = m0 + row; if (li >= n_e) li = n_e - 1;
-        const int src_row = GU ? pair[beg + li] / topk : beg + li;
+        const int src_row = GU ? pair_at(li) / topk : beg + li;
         const bf16_t* src = a + (size_t)src_row * K + k0 + lane * 8;
 #pragma unroll
         for (int seg = 0; seg < KR / 512; ++seg) {
@@ -279,7 +313,7 @@ __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, 
     for (int ch = tid; ch < MT * 16 * (KR / 8); ch += 256) {       // ragged range: zero-filled beyond K
       const int row = ch / (KR / 8), kc = (ch % (KR / 8)) * 8;
       int li = m0 + row; if (li >= n_e) li = n_e - 1;
-      const int src_row = GU ? pair[beg + li] / topk : beg + li;
+      const int src_row = GU ? pair_at(li) / topk : beg + li;
       uint4 v = make_uint4(0, 0, 0, 0);
       if (kc < kr) v = *reinterpret_cast<const uint4*>(a + (size_t)src_row * K + k0 + kc);
       *reinterpret_cast<uint4*>(&As[row * LDK + kc]) = v;
@@ -338,7 +372,7 @@ __global__ __launch_bounds__(256) void k_moe_gemm(const bf16_t* __restrict__ a, 
           *reinterpret_cast<uint2*>(act_out + (size_t)(beg + li) * N + col) = pk;
         }
       } else {
-        const int pr = pair[beg + li];
+        const int pr = pair_at(li);
         const int row = pr / topk, slot = pr - row * topk;
         const float p = sel_p[pr];
 #pragma unroll
@@ -421,7 +455,7 @@ static void moe_gemm_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, con
   }
   const int cols_per_wg = 4 * 16 * (GU ? NS / 2 : NS);
   hipLaunchKernelGGL((k_moe_gemm<MT, KR, GU, NS, KH>), dim3((N + cols_per_wg - 1) / cols_per_wg, E), dim3(256), lds, s, a, w,
-                     mi.off, mi.pair, mi.sel_p, act, y, R, N, K, k);
+                     mi.off, mi.pair, mi.sel_e, mi.sel_p, act, y, R, N, K, k);
 }
 
 // rows per LDS tile by the mean number of rows per expert: 32 (two workgroups per compute unit, K range
@@ -441,7 +475,10 @@ void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, co
   const int P = R * k;
   hipLaunchKernelGGL((k_moe_route<T, T>), dim3(R), dim3(ROUTE_WAVES * 64), (size_t)(d + E) * sizeof(float), s, a,
                      (const uint8_t*)nullptr, router, mi.sel_e, mi.sel_p, d, E, k);
-  if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  // decode-sized batches of bf16 models: the grouped GEMMs find their lists themselves (mi.pair = null)
+  const bool fly = sizeof(T) == 2 && R <= MOE_FLY_ROWS && P <= 65535;
+  if (fly) mi.pair = nullptr;
+  else if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   if constexpr (sizeof(T) == 2) {
@@ -469,17 +506,24 @@ template <int MT, bool GU>
 __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
                                                      const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
                                                      const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
+                                                     const int32_t* __restrict__ sel_e,
                                                      const float* __restrict__ sel_p, uint8_t* __restrict__ act_out,
                                                      uint8_t* __restrict__ act_sc_out, float* __restrict__ y_out,
                                                      int R, int N, int K, int topk) {
+  __shared__ uint16_t s_list[MOE_FLY_ROWS];
+  __shared__ int s_cnt[8];
   extern __shared__ __attribute__((aligned(16))) uint8_t lds_moe_mx[];   // [MT*16][MX_LDA] codes, then [MT*16][MX_SB] scales
   uint8_t* As = lds_moe_mx;
   uint8_t* Ss = lds_moe_mx + MT * 16 * MX_LDA;
   constexpr int NS = 4;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int e = blockIdx.y;
-  const int beg = off[e], n_e = off[e + 1] - beg;
+  const bool fly = pair == nullptr;              // no sorted lists: derive this expert's list from the selections
+  int beg, n_e;
+  if (fly) moe_expert_list(sel_e, R * topk, e, s_list, s_cnt, beg, n_e);
+  else { beg = off[e]; n_e = off[e + 1] - beg; }
   if (n_e <= 0) return;
+  auto pair_at = [&](int li) -> int { return fly ? (int)s_list[li] : pair[beg + li]; };
   const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, n_rng = (K + MX_KR - 1) / MX_KR;
   const int NR = GU ? 2 * N : N;                                 // rows of one expert's matrix
   const int out_strips = N >> 4;
@@ -519,7 +563,7 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
     if (kr == MX_KR) {
       for (int row = wv; row < MT * 16; row += 4) {
         int li = m0 + row; if (li >= n_e) li = n_e - 1;
-        const int src_row = GU ? pair[beg + li] / topk : beg + li;
+        const int src_row = GU ? pair_at(li) / topk : beg + li;
         const uint8_t* src = a + (size_t)src_row * K + k0 + lane * 16;
         const unsigned dst = __builtin_amdgcn_readfirstlane(lds_as + (unsigned)row * MX_LDA);
         unsigned keep_m0;                                          // m0 is left as it was found
@@ -530,7 +574,7 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
       for (int ch = tid; ch < MT * 16 * (MX_KR / 16); ch += 256) {  // ragged range: zero-filled beyond K
         const int row = ch / (MX_KR / 16), kc = (ch % (MX_KR / 16)) * 16;
         int li = m0 + row; if (li >= n_e) li = n_e - 1;
-        const int src_row = GU ? pair[beg + li] / topk : beg + li;
+        const int src_row = GU ? pair_at(li) / topk : beg + li;
         uint4 v = make_uint4(0, 0, 0, 0);
         if (kc < kr) v = *reinterpret_cast<const uint4*>(a + (size_t)src_row * K + k0 + kc);
         *reinterpret_cast<uint4*>(&As[row * MX_LDA + kc]) = v;
@@ -539,7 +583,7 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
     for (int ch = tid; ch < MT * 16 * 2; ch += 256) {               // two 16-byte scale groups per row and range
       const int row = ch >> 1, h = ch & 1;
       int li = m0 + row; if (li >= n_e) li = n_e - 1;
-      const int src_row = GU ? pair[beg + li] / topk : beg + li;
+      const int src_row = GU ? pair_at(li) / topk : beg + li;
       const int cg = rng * 2 + h;
       uint4 v = make_uint4(0, 0, 0, 0);
       if (cg * 16 < asb) v = *reinterpret_cast<const uint4*>(a_sc + (size_t)src_row * asb + cg * 16);
@@ -624,7 +668,7 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
         }
       } else {
         if (li >= n_e) continue;
-        const int pr = pair[beg + li];
+        const int pr = pair_at(li);
         const int row = pr / topk, slot = pr - row * topk;
         const float p = sel_p[pr];
 #pragma unroll
@@ -651,7 +695,7 @@ static void moe_gemm_mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a
   }
   const int cols_per_wg = GU ? 128 : 256;
   hipLaunchKernelGGL((k_moe_gemm_mx<MT, GU>), dim3((N + cols_per_wg - 1) / cols_per_wg, E), dim3(256), lds, s, a, a_sc, w, w_sc,
-                     mi.off, mi.pair, mi.sel_p, act, act_sc, y, R, N, K, k);
+                     mi.off, mi.pair, mi.sel_e, mi.sel_p, act, act_sc, y, R, N, K, k);
 }
 
 void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const bf16_t* router, const uint8_t* wgu,
@@ -660,7 +704,9 @@ void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, con
   const int P = R * k;
   hipLaunchKernelGGL((k_moe_route<fp8_t, bf16_t>), dim3(R), dim3(ROUTE_WAVES * 64), (size_t)(d + E) * sizeof(float), s, a, a_sc,
                      router, mi.sel_e, mi.sel_p, d, E, k);
-  if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  const bool fly = R <= MOE_FLY_ROWS && P <= 65535;
+  if (fly) mi.pair = nullptr;
+  else if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   const long mean = ((long)P + E - 1) / E;
