@@ -347,7 +347,7 @@ def bench_prefill(B, shape, blob, g, Bn=4, n=8192, L=3, w=64, reps=2):
             "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
 
 
-def bench_sweep(B, shape, blob, g, n_new=256, runs=2):
+def bench_sweep(B, shape, blob, g, n_new=256, runs=5):
     """The paper's serving recipe on synthetic inputs: prefill context {1024, 2048, 5000}, batch 1..256,
     n_new consecutive greedy decode steps (the context grows), mean per-token latency over `runs` runs,
     for the non-looped model, PLT-2 and the vanilla sequential loop-2 in the same library.  Caches are
@@ -389,6 +389,47 @@ def bench_sweep(B, shape, blob, g, n_new=256, runs=2):
             log(f"[bench] sweep {row}")
             table.append(row)
     return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "rows": table}
+
+
+def bench_sweep_moe(B, g, n_new=256, runs=5, ctx=5000):
+    """The protocol of the paper's mixture-of-experts latency table on synthetic inputs: prefill context 5000,
+    batch 4..64, 256 consecutive greedy decode steps, mean per-token latency over 5 runs, with the serving
+    formats (here: e4m3 caches, MXFP4 projections and experts) -- on the open-source 8-of-64 recipe's shape, for
+    the non-looped model, PLT-2, PLT-3 and the vanilla sequential loop-2.  Caches hold N(0, 0.5) values."""
+    import torch
+    from paper_2510_24824_amd import synth
+    shape = synth.PLT_MOE_1B7B
+    blob = fill_weights_on_device(B, B.make_config(shape, dtype=B.PLT_BF16, w_dtype=B.PLT_MXFP4), SEED + 7)
+    table = []
+    for bs in (4, 8, 16, 32, 64):
+        row = {"context": ctx, "batch": bs}
+        for name, mode, Lx in [("nonlooped", B.PLT_MODE_CLP, 1), ("plt2", B.PLT_MODE_CLP, 2), ("plt3", B.PLT_MODE_CLP, 3),
+                               ("vanilla_loop2", B.PLT_MODE_VANILLA_LOOP, 2)]:
+            cfg = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=64, kv_dtype=B.PLT_FP8_E4M3, w_dtype=B.PLT_MXFP4)
+            m = B.Model(cfg, blob)
+            kv = B.KV(m, bs, ctx + n_new)
+            fill_kv_random(B, kv, g)
+            tok = torch.randint(0, shape.vocab, (bs,), generator=g, device="cuda", dtype=torch.int32)
+            ms = []
+            for r in range(runs + 1):
+                kv.set_position(ctx)
+                nxt = tok
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(n_new):
+                    nxt, _ = kv.decode_step(nxt, want_logits=False)
+                torch.cuda.synchronize()
+                if r > 0:                       # run 0 warms up
+                    ms.append((time.perf_counter() - t0) * 1e3 / n_new)
+            row[name] = sum(ms) / len(ms)
+            kv.close(); m.close(); del kv
+            torch.cuda.empty_cache()
+        for k in ("plt2", "plt3", "vanilla_loop2"):
+            row[k + "_vs_nonlooped"] = row[k] / row["nonlooped"]
+        log(f"[bench] MoE sweep {row}")
+        table.append(row)
+    return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "rows": table,
+            "workload": "8-of-64 MoE shape, e4m3 caches + MXFP4 projections and experts"}
 
 
 def bench_lowbit_gemm(B, Mrows=128, reps=30):
@@ -545,6 +586,7 @@ def main():
     ap.add_argument("--attn-kernel-only", action="store_true", help="only the kernel-only fused attention configuration (bf16 and e4m3 caches)")
     ap.add_argument("--prefill-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3")
     ap.add_argument("--copy-reference", action="store_true", help="only the plain copy kernel (reference for HBM traffic counters)")
+    ap.add_argument("--sweep-moe", action="store_true", help="only the mixture-of-experts serving sweep (batch 4..64, context 5000, 256 tokens, 5 runs)")
     ap.add_argument("--moe-only", action="store_true", help="only the mixture-of-experts shape (8 of 64 experts) at batch 64")
     ap.add_argument("--lowbit-gemm-only", action="store_true", help="only the kernel-only low-bit (MXFP4 x MXFP8) GEMM comparison")
     ap.add_argument("--kv-fp8", action="store_true", help="main workload with e4m3 K/V caches (labelled variant)")
@@ -567,6 +609,10 @@ def main():
     if args.attn_kernel_only:
         print(json.dumps({"attn_kernel_only": bench_attn_kernel(B, args.steps, args.warmup),
                           "attn_kernel_only_fp8_kv": bench_attn_kernel(B, args.steps, args.warmup, fp8=True)}), flush=True)
+        return
+    if args.sweep_moe:
+        g0 = torch.Generator(device="cuda"); g0.manual_seed(SEED + 1)
+        print(json.dumps({"serving_sweep_moe": bench_sweep_moe(B, g0)}), flush=True)
         return
     if args.moe_only:
         g0 = torch.Generator(device="cuda"); g0.manual_seed(SEED + 1)
