@@ -26,6 +26,20 @@ constexpr int PF_QROWS = 128;                 // query positions per workgroup
 
 __device__ inline bf16x8 pf_bf(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// max over the four lanes r, r+16, r+32, r+48 (the lanes that share a query row), left in all four: gfx950's row
+// and half-wave swaps run on the vector ALU, a wavefront shuffle would take the much longer way through the LDS
+__device__ __forceinline__ float pf_row_max(float v) {
+  // v_permlane16_swap exchanges the first register's odd rows with the second's even rows (rows of 16 lanes),
+  // v_permlane32_swap the first's upper half wave with the second's lower half; given two copies of one value,
+  // the element-wise max of the two registers afterwards is the pairwise max.  Written as asm: the compiler
+  // folds the builtin's two results into one.  The s_nop cover the instruction's read/write hazards.
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  a = fmaxf(a, b); b = a;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+  return fmaxf(a, b);
+}
+
 template <int D>
 struct PfState {           // online softmax state of one 16-row query tile
   float m, l;
@@ -50,67 +64,88 @@ struct PfLds {
   __device__ const bf16_t* vp(int d, int c) const { return &v[d][(c ^ ((d >> 1) & 3)) * 8]; }
 };
 
-// One 32-key tile for the two query tiles of a wave.  lo/hi: per lane (= per query row) bounds,
-// key j is attended iff lo < j <= hi.
+// Online-softmax update of one 16-row query tile for a 64-key tile made of two 32-key halves: s[h][a] are the
+// raw scores of half h, 16-key sub-tile a (this lane: keys 32h + 8g + 4a + i of the tile).  Returns the bf16
+// probabilities per half (B operands of the second contraction) and rescales the accumulators when some row's
+// maximum moved.  Key j is attended iff lo < j <= hi.
 template <int D>
-__device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D>& sm, const uint4 (&qf)[2][D / 32],
+__device__ __forceinline__ void pf_softmax(PfState<D>& st, const f32x4 (&s)[2][2], float scale_log2, int key_base,
+                                           bool need_mask, int lo, int hi, int g, bf16x8 (&pb)[2]) {
+  float sv[16];
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { sv[8 * h + i] = s[h][0][i]; sv[8 * h + 4 + i] = s[h][1][i]; }
+  if (need_mask) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int kb = key_base + 32 * h + 8 * g;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) if (kb + j > hi || kb + j <= lo) sv[8 * h + j] = PF_NEG_INF;
+    }
+  }
+  float mx = sv[0];
+#pragma unroll
+  for (int j = 1; j < 16; ++j) mx = fmaxf(mx, sv[j]);
+  mx = pf_row_max(mx);
+  const float m_new = fmaxf(st.m, mx * scale_log2);        // the scale is positive: max and scaling commute
+  const float m_safe = (m_new == PF_NEG_INF) ? 0.f : m_new;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
+  f32x8 p[2]; float ps = 0.f;
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { p[h][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * h + j], scale_log2, -m_safe)); ps += p[h][j]; }
+  st.l = st.l * alpha + ps;
+  st.m = m_new;
+  // alpha == 1 in every lane (no row of this tile raised its maximum: the usual case after the first
+  // few tiles): the rescale of the accumulators is skipped for the whole wave
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      st.acc[dt][0] *= alpha; st.acc[dt][1] *= alpha; st.acc[dt][2] *= alpha; st.acc[dt][3] *= alpha;
+    }
+  }
+  pb[0] = __builtin_convertvector(p[0], bf16x8); pb[1] = __builtin_convertvector(p[1], bf16x8);
+}
+
+// One 64-key tile (two 32-key halves in LDS) for the two query tiles of a wave.  lo/hi: per lane (= per query
+// row) bounds.  One softmax step per 64 keys: its fixed cost (row maximum across lanes, rescale test, state
+// update) is paid half as often as with 32-key steps, and the vector ALU is what bounds this kernel.
+template <int D>
+__device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D> (&sm)[2], const uint4 (&qf)[2][D / 32],
                                float scale_log2, int key_base, bool need_mask, const int (&lo)[2],
                                const int (&hi)[2], int m16, int g) {
   const int key0 = 8 * (m16 >> 2) + (m16 & 3);
-  f32x4 s[2][2];
+  f32x4 s[2][2][2];                 // [query tile][half][sub-tile]
 #pragma unroll
-  for (int q = 0; q < 2; ++q) { s[q][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[q][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+  for (int q = 0; q < 2; ++q)
 #pragma unroll
-  for (int kk = 0; kk < D / 32; ++kk) {
-    const uint4 k0 = *reinterpret_cast<const uint4*>(sm.kp(key0, kk * 4 + g));
-    const uint4 k1 = *reinterpret_cast<const uint4*>(sm.kp(key0 + 4, kk * 4 + g));
+    for (int h = 0; h < 2; ++h) { s[q][h][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[q][h][1] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      s[q][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k0), pf_bf(qf[q][kk]), s[q][0], 0, 0, 0);
-      s[q][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k1), pf_bf(qf[q][kk]), s[q][1], 0, 0, 0);
-    }
-  }
-  bf16x8 pb[2];
+  for (int h = 0; h < 2; ++h)
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    float sv[8];
+    for (int kk = 0; kk < D / 32; ++kk) {
+      const uint4 k0 = *reinterpret_cast<const uint4*>(sm[h].kp(key0, kk * 4 + g));
+      const uint4 k1 = *reinterpret_cast<const uint4*>(sm[h].kp(key0 + 4, kk * 4 + g));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { sv[i] = s[q][0][i] * scale_log2; sv[4 + i] = s[q][1][i] * scale_log2; }
-    if (need_mask) {
-      const int kb = key_base + 8 * g;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) if (kb + j > hi[q] || kb + j <= lo[q]) sv[j] = PF_NEG_INF;
-    }
-    float mx = sv[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(st[q].m, mx);
-    const float m_safe = (m_new == PF_NEG_INF) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f(st[q].m - m_safe);
-    f32x8 p; float ps = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(sv[j] - m_safe); ps += p[j]; }
-    st[q].l = st[q].l * alpha + ps;
-    st[q].m = m_new;
-    pb[q] = __builtin_convertvector(p, bf16x8);
-    // alpha == 1 in every lane (no row of this tile raised its maximum: the usual case after the first
-    // few tiles): the rescale of the accumulators is skipped for the whole wave
-    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-#pragma unroll
-      for (int dt = 0; dt < D / 16; ++dt) {
-        st[q].acc[dt][0] *= alpha; st[q].acc[dt][1] *= alpha; st[q].acc[dt][2] *= alpha; st[q].acc[dt][3] *= alpha;
+      for (int q = 0; q < 2; ++q) {
+        s[q][h][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k0), pf_bf(qf[q][kk]), s[q][h][0], 0, 0, 0);
+        s[q][h][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(k1), pf_bf(qf[q][kk]), s[q][h][1], 0, 0, 0);
       }
     }
-  }
+  bf16x8 pb[2][2];
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) {
-    const uint4 vf = *reinterpret_cast<const uint4*>(sm.vp(dt * 16 + m16, g));
+  for (int q = 0; q < 2; ++q) pf_softmax<D>(st[q], s[q], scale_log2, key_base, need_mask, lo[q], hi[q], g, pb[q]);
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
-      st[q].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(vf), pb[q], st[q].acc[dt], 0, 0, 0);
-  }
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+      const uint4 vf = *reinterpret_cast<const uint4*>(sm[h].vp(dt * 16 + m16, g));
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+        st[q].acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(vf), pb[q][h], st[q].acc[dt], 0, 0, 0);
+    }
 }
 
 struct PfArgs {
@@ -121,26 +156,26 @@ struct PfArgs {
   float scale_log2;
 };
 
-// Streams key tiles t_beg..t_end-1 of one K/V stream through LDS and applies them to the wave's
-// two query tiles.  All 256 threads of the workgroup must call this together.
+// Streams the 32-key blocks t_beg..t_end-1 of one K/V stream (n_blk blocks are allocated) through LDS, two
+// blocks (64 keys) per step, and applies them to the wave's two query tiles; a block outside the range that
+// shares a step with one inside is masked by the rows' bounds (an unallocated one is replaced by zeros).
+// All 256 threads of the workgroup must call this together.
 template <int D, bool F8>
-__device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const char* __restrict__ kbase,
-                               const char* __restrict__ vbase, int t_beg, int t_end, const uint4 (&qf)[2][D / 32],
+__device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D> (&sm)[2], const char* __restrict__ kbase,
+                               const char* __restrict__ vbase, int t_beg, int t_end, int n_blk, const uint4 (&qf)[2][D / 32],
                                float scale_log2, const int (&lo)[2], const int (&hi)[2], int row_min, int row_max,
                                int m16, int g) {
   const int tid = threadIdx.x;
   constexpr int ES = F8 ? 1 : 2;
-  constexpr int TILE_BYTES = 32 * D * ES;                       // of the K tile and of the V block alike
-  constexpr int KCH = (TILE_BYTES / 16 + 255) / 256;            // 16-byte chunks per thread (1 or 2)
-  constexpr int NCH = TILE_BYTES / 16;                          // chunks per tile (may be < 256)
-  // register staging of the next tile (plain loops: the arrays must stay in registers)
-  uint4 rk[KCH], rv[KCH];
-#pragma unroll
-  for (int i = 0; i < KCH; ++i) { rk[i] = make_uint4(0, 0, 0, 0); rv[i] = make_uint4(0, 0, 0, 0); }
+  constexpr int TILE_BYTES = 32 * D * ES;                       // of a block's K tile and of its V block alike
+  constexpr int KCH = (TILE_BYTES / 16 + 255) / 256;            // 16-byte chunks per thread and block (1 or 2)
+  constexpr int NCH = TILE_BYTES / 16;                          // chunks per block (may be < 256)
+  // register staging of the next step (plain loops: the arrays must stay in registers)
+  uint4 rk[2][KCH], rv[2][KCH];
   // The cache keeps K in the decode kernel's load order (kblk_index): a 16-byte chunk of the tile is
   // (sub-tile a, feature chunk kk, lane group g, row m) and belongs to key kkey, features kcol ..
   auto k_chunk = [&](int t, int ch, size_t& off, int& kkey, int& kcol) {
-    if (F8) {   // 64-key blocks; this 32-key tile is half (t & 1): rows m with (m >> 2) in {2h, 2h+1}
+    if (F8) {   // 64-key blocks; this 32-key block is half (t & 1): rows m with (m >> 2) in {2h, 2h+1}
       const int m = 8 * (t & 1) + (ch & 7), g = (ch >> 3) & 3, kk = (ch >> 5) % (D / 64), a = (ch >> 5) / (D / 64);
       off = (size_t)(t >> 1) * 64 * D + (size_t)(((a * (D / 64) + kk) * 64 + g * 16 + m) * 16);
       kkey = 16 * ((m >> 2) & 1) + (m & 3) + 4 * a; kcol = kk * 64 + g * 16;
@@ -150,46 +185,55 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const
       kkey = 8 * (m >> 2) + (m & 3) + 4 * a; kcol = kk * 32 + g * 8;
     }
   };
-  auto fetch = [&](int t) {
+  auto fetch = [&](int T) {
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int ch = tid + i * 256;
-      if (NCH % 256 == 0 || ch < NCH) {
-        size_t off; int kkey, kcol;
-        k_chunk(t, ch, off, kkey, kcol);
-        rk[i] = *reinterpret_cast<const uint4*>(kbase + off);
-        rv[i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
+    for (int h = 0; h < 2; ++h) {
+      const int t = 2 * T + h;
+#pragma unroll
+      for (int i = 0; i < KCH; ++i) {
+        const int ch = tid + i * 256;
+        rk[h][i] = make_uint4(0, 0, 0, 0); rv[h][i] = make_uint4(0, 0, 0, 0);
+        if ((NCH % 256 == 0 || ch < NCH) && t < n_blk) {
+          size_t off; int kkey, kcol;
+          k_chunk(t, ch, off, kkey, kcol);
+          rk[h][i] = *reinterpret_cast<const uint4*>(kbase + off);
+          rv[h][i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
+        }
       }
     }
   };
-  if (t_beg < t_end) fetch(t_beg);
-  for (int t = t_beg; t < t_end; ++t) {
-    __syncthreads();                         // every wave is done with the previous tile
+  const int T_beg = t_beg >> 1, T_end = (t_end + 1) >> 1;
+  if (T_beg < T_end) fetch(T_beg);
+  for (int T = T_beg; T < T_end; ++T) {
+    __syncthreads();                         // every wave is done with the previous step
 #pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-      const int ch = tid + i * 256;
-      if (NCH % 256 == 0 || ch < NCH) {
-        size_t off; int kkey, kcol;
-        k_chunk(t, ch, off, kkey, kcol);
-        if (F8) {
-          *reinterpret_cast<bf16x8*>(sm.kp(kkey, kcol / 8)) = e4m3x8_to_bf16(rk[i].x, rk[i].y);
-          *reinterpret_cast<bf16x8*>(sm.kp(kkey, kcol / 8 + 1)) = e4m3x8_to_bf16(rk[i].z, rk[i].w);
-          *reinterpret_cast<bf16x8*>(sm.vp(ch >> 1, (ch & 1) * 2)) = e4m3x8_to_bf16(rv[i].x, rv[i].y);
-          *reinterpret_cast<bf16x8*>(sm.vp(ch >> 1, (ch & 1) * 2 + 1)) = e4m3x8_to_bf16(rv[i].z, rv[i].w);
-        } else {
-          *reinterpret_cast<uint4*>(sm.kp(kkey, kcol / 8)) = rk[i];
-          *reinterpret_cast<uint4*>(sm.vp(ch / 4, ch % 4)) = rv[i];
+    for (int h = 0; h < 2; ++h) {
+#pragma unroll
+      for (int i = 0; i < KCH; ++i) {
+        const int ch = tid + i * 256;
+        if (NCH % 256 == 0 || ch < NCH) {
+          size_t off; int kkey, kcol;
+          k_chunk(2 * T + h, ch, off, kkey, kcol);
+          if (F8) {
+            *reinterpret_cast<bf16x8*>(sm[h].kp(kkey, kcol / 8)) = e4m3x8_to_bf16(rk[h][i].x, rk[h][i].y);
+            *reinterpret_cast<bf16x8*>(sm[h].kp(kkey, kcol / 8 + 1)) = e4m3x8_to_bf16(rk[h][i].z, rk[h][i].w);
+            *reinterpret_cast<bf16x8*>(sm[h].vp(ch >> 1, (ch & 1) * 2)) = e4m3x8_to_bf16(rv[h][i].x, rv[h][i].y);
+            *reinterpret_cast<bf16x8*>(sm[h].vp(ch >> 1, (ch & 1) * 2 + 1)) = e4m3x8_to_bf16(rv[h][i].z, rv[h][i].w);
+          } else {
+            *reinterpret_cast<uint4*>(sm[h].kp(kkey, kcol / 8)) = rk[h][i];
+            *reinterpret_cast<uint4*>(sm[h].vp(ch / 4, ch % 4)) = rv[h][i];
+          }
         }
       }
     }
     __syncthreads();
-    if (t + 1 < t_end) fetch(t + 1);
-    const int kb = t * 32;
-    // Every wave multiplies every tile of the workgroup's range, also the few that none of its rows may
+    if (T + 1 < T_end) fetch(T + 1);
+    const int kb = T * 64;
+    // Every wave multiplies every step of the workgroup's range, also the few that none of its rows may
     // attend (they are masked out entirely): skipping them made the accumulators take two paths through
-    // the loop, which cost a copy of all 64 accumulator registers per tile.  Tiles that straddle a bound
+    // the loop, which cost a copy of all 64 accumulator registers per step.  Steps that straddle a bound
     // of some row are masked, the others are not.
-    const bool need_mask = (kb + 31 > row_min) || (kb <= __shfl(lo[1], 15, 64));
+    const bool need_mask = (kb + 63 > row_min) || (kb <= __shfl(lo[1], 15, 64));
     pf_tile<D>(st, sm, qf, scale_log2, kb, need_mask, lo, hi, m16, g);
   }
 }
@@ -197,7 +241,7 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D>& sm, const
 template <int D, bool F8>
 __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
   constexpr int ES = F8 ? 1 : 2;
-  __shared__ __attribute__((aligned(16))) PfLds<D> sm;
+  __shared__ __attribute__((aligned(16))) PfLds<D> sm[2];      // the two 32-key halves of a step
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   // Workgroups are dispatched in blockIdx.x order: all (head, sequence) pairs of the query tile with
   // the longest key range first, the shortest ranges last, so the causal imbalance does not leave a
@@ -235,7 +279,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
     const size_t stream = (size_t)b * A.Hkv + kvh;
     int j_lo = p0 - A.w + 1; if (j_lo < 0) j_lo = 0;
     pf_pass<D, F8>(st, sm, A.k_loc + stream * (size_t)A.n_pad_loc * D * ES, A.v_loc + stream * (size_t)A.n_pad_loc * D * ES,
-               j_lo >> 5, (p_last >> 5) + 1, qf, A.scale_log2, lo_l, hi, row_min, row_max, m16, g);
+               j_lo >> 5, (p_last >> 5) + 1, A.n_pad_loc >> 5, qf, A.scale_log2, lo_l, hi, row_min, row_max, m16, g);
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       if (prow[q] >= A.n) continue;
@@ -256,7 +300,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
   {
     const size_t stream = (size_t)(A.b0 + b) * A.Hkv + kvh;
     pf_pass<D, F8>(st, sm, A.k_share + stream * (size_t)A.n_pad * D * ES, A.v_share + stream * (size_t)A.n_pad * D * ES, 0,
-               (p_last >> 5) + 1, qf, A.scale_log2, lo_g, hi, row_min, row_max, m16, g);
+               (p_last >> 5) + 1, A.n_pad >> 5, qf, A.scale_log2, lo_g, hi, row_min, row_max, m16, g);
   }
   // epilogue: lane (row m16, g) holds features dt*16 + 4g .. +3 of its two rows
 #pragma unroll
