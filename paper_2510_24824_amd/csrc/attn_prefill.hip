@@ -23,6 +23,7 @@ namespace {
 
 constexpr int PF_QROWS = 128;                 // query positions per workgroup
 #define PF_NEG_INF (-INFINITY)
+#define PF_M_INIT (-1.0e30f)
 
 __device__ inline bf16x8 pf_bf(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -32,20 +33,22 @@ __device__ __forceinline__ float pf_row_max(float v) {
   // v_permlane16_swap exchanges the first register's odd rows with the second's even rows (rows of 16 lanes),
   // v_permlane32_swap the first's upper half wave with the second's lower half; given two copies of one value,
   // the element-wise max of the two registers afterwards is the pairwise max.  Written as asm: the compiler
-  // folds the builtin's two results into one.  The s_nop cover the instruction's read/write hazards.
+  // folds the builtin's two results into one.  The s_nop cover the instructions' read/write hazards.
   float a = v, b = v;
-  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-  a = fmaxf(a, b); b = a;
-  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
-  return fmaxf(a, b);
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t"
+               "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1"
+               : "+v"(a), "+v"(b));
+  return a;
 }
 
 template <int D>
 struct PfState {           // online softmax state of one 16-row query tile
-  float m, l;
+  float m;                 // running maximum (log2 domain); starts at a large negative finite value, so that
+                           // m - m is 0 and not NaN for rows that have attended nothing yet
+  f32x4 l;                 // softmax denominator: every element holds the row's full sum (see pf_tile)
   f32x4 acc[D / 16];
   __device__ void init() {
-    m = PF_NEG_INF; l = 0.f;
+    m = PF_M_INIT; l = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
@@ -89,14 +92,12 @@ __device__ __forceinline__ void pf_softmax(PfState<D>& st, const f32x4 (&s)[2][2
   for (int j = 1; j < 16; ++j) mx = fmaxf(mx, sv[j]);
   mx = pf_row_max(mx);
   const float m_new = fmaxf(st.m, mx * scale_log2);        // the scale is positive: max and scaling commute
-  const float m_safe = (m_new == PF_NEG_INF) ? 0.f : m_new;
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
-  f32x8 p[2]; float ps = 0.f;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+  f32x8 p[2];
 #pragma unroll
   for (int h = 0; h < 2; ++h)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) { p[h][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * h + j], scale_log2, -m_safe)); ps += p[h][j]; }
-  st.l = st.l * alpha + ps;
+    for (int j = 0; j < 8; ++j) p[h][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 * h + j], scale_log2, -m_new));
   st.m = m_new;
   // alpha == 1 in every lane (no row of this tile raised its maximum: the usual case after the first
   // few tiles): the rescale of the accumulators is skipped for the whole wave
@@ -105,6 +106,7 @@ __device__ __forceinline__ void pf_softmax(PfState<D>& st, const f32x4 (&s)[2][2
     for (int dt = 0; dt < D / 16; ++dt) {
       st.acc[dt][0] *= alpha; st.acc[dt][1] *= alpha; st.acc[dt][2] *= alpha; st.acc[dt][3] *= alpha;
     }
+    st.l[0] *= alpha; st.l[1] *= alpha; st.l[2] *= alpha; st.l[3] *= alpha;
   }
   pb[0] = __builtin_convertvector(p[0], bf16x8); pb[1] = __builtin_convertvector(p[1], bf16x8);
 }
@@ -137,6 +139,13 @@ __device__ __forceinline__ void pf_tile(PfState<D> (&st)[2], const PfLds<D> (&sm
   bf16x8 pb[2][2];
 #pragma unroll
   for (int q = 0; q < 2; ++q) pf_softmax<D>(st[q], s[q], scale_log2, key_base, need_mask, lo[q], hi[q], g, pb[q]);
+  // the softmax denominators come from the matrix cores as well: a block of ones in place of V^T sums the (bf16)
+  // probabilities over the 32 keys of a half, into every element of l
+  const uint4 ones = make_uint4(0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u);
+#pragma unroll
+  for (int h = 0; h < 2; ++h)
+#pragma unroll
+    for (int q = 0; q < 2; ++q) st[q].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pf_bf(ones), pb[q][h], st[q].l, 0, 0, 0);
 #pragma unroll
   for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -158,7 +167,7 @@ struct PfArgs {
 
 // Streams the 32-key blocks t_beg..t_end-1 of one K/V stream (n_blk blocks are allocated) through LDS, two
 // blocks (64 keys) per step, and applies them to the wave's two query tiles; a block outside the range that
-// shares a step with one inside is masked by the rows' bounds (an unallocated one is replaced by zeros).
+// shares a step with one inside is masked by the rows' bounds.
 // All 256 threads of the workgroup must call this together.
 template <int D, bool F8>
 __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D> (&sm)[2], const char* __restrict__ kbase,
@@ -172,60 +181,72 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D> (&sm)[2], 
   constexpr int NCH = TILE_BYTES / 16;                          // chunks per block (may be < 256)
   // register staging of the next step (plain loops: the arrays must stay in registers)
   uint4 rk[2][KCH], rv[2][KCH];
-  // The cache keeps K in the decode kernel's load order (kblk_index): a 16-byte chunk of the tile is
-  // (sub-tile a, feature chunk kk, lane group g, row m) and belongs to key kkey, features kcol ..
-  auto k_chunk = [&](int t, int ch, size_t& off, int& kkey, int& kcol) {
-    if (F8) {   // 64-key blocks; this 32-key block is half (t & 1): rows m with (m >> 2) in {2h, 2h+1}
-      const int m = 8 * (t & 1) + (ch & 7), g = (ch >> 3) & 3, kk = (ch >> 5) % (D / 64), a = (ch >> 5) / (D / 64);
-      off = (size_t)(t >> 1) * 64 * D + (size_t)(((a * (D / 64) + kk) * 64 + g * 16 + m) * 16);
+#pragma unroll
+  for (int i = 0; i < KCH; ++i) { rk[0][i] = rk[1][i] = make_uint4(0, 0, 0, 0); rv[0][i] = rv[1][i] = make_uint4(0, 0, 0, 0); }
+  // The cache keeps K in the decode kernel's load order (kblk_index): a 16-byte chunk of a block is
+  // (sub-tile a, feature chunk kk, lane group g, row m) and belongs to key kkey, features kcol ..; its address
+  // is a block offset (the same for all threads: scalar registers) plus a per-thread constant koff.
+  auto k_chunk = [&](int h, int ch, unsigned& koff, int& kkey, int& kcol) {
+    if (F8) {   // 64-key blocks; the 32-key block is half h of one: rows m with (m >> 2) in {2h, 2h+1}
+      const int m = 8 * h + (ch & 7), g = (ch >> 3) & 3, kk = (ch >> 5) % (D / 64), a = (ch >> 5) / (D / 64);
+      koff = (unsigned)(((a * (D / 64) + kk) * 64 + g * 16 + m) * 16);
       kkey = 16 * ((m >> 2) & 1) + (m & 3) + 4 * a; kcol = kk * 64 + g * 16;
     } else {
       const int m = ch & 15, g = (ch >> 4) & 3, kk = (ch >> 6) % (D / 32), a = (ch >> 6) / (D / 32);
-      off = (size_t)t * TILE_BYTES + (size_t)ch * 16;
+      koff = (unsigned)ch * 16u;
       kkey = 8 * (m >> 2) + (m & 3) + 4 * a; kcol = kk * 32 + g * 8;
     }
   };
   auto fetch = [&](int T) {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int t = 2 * T + h;
+      // a block beyond the allocation is replaced by the last allocated one (finite values; its keys lie
+      // beyond every row's bound and are masked)
+      const int t = (2 * T + h < n_blk) ? 2 * T + h : n_blk - 1;          // the same for all threads
+      const char* kt = kbase + (F8 ? (size_t)(t >> 1) * 64 * D : (size_t)t * TILE_BYTES);
+      const char* vt = vbase + (size_t)t * TILE_BYTES;
 #pragma unroll
       for (int i = 0; i < KCH; ++i) {
         const int ch = tid + i * 256;
-        rk[h][i] = make_uint4(0, 0, 0, 0); rv[h][i] = make_uint4(0, 0, 0, 0);
-        if ((NCH % 256 == 0 || ch < NCH) && t < n_blk) {
-          size_t off; int kkey, kcol;
-          k_chunk(t, ch, off, kkey, kcol);
-          rk[h][i] = *reinterpret_cast<const uint4*>(kbase + off);
-          rv[h][i] = *reinterpret_cast<const uint4*>(vbase + (size_t)t * TILE_BYTES + (size_t)ch * 16);
+        if (NCH % 256 == 0 || ch < NCH) {
+          unsigned koff; int kkey, kcol;
+          k_chunk(F8 ? (t & 1) : h, ch, koff, kkey, kcol);
+          rk[h][i] = *reinterpret_cast<const uint4*>(kt + koff);
+          rv[h][i] = *reinterpret_cast<const uint4*>(vt + (unsigned)ch * 16u);
+        }
+      }
+    }
+  };
+  // staged registers -> LDS (e4m3 bytes are expanded to bf16 here)
+  auto store = [&]() {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      PfLds<D>& dst = sm[h];
+#pragma unroll
+      for (int i = 0; i < KCH; ++i) {
+        const int ch = tid + i * 256;
+        if (NCH % 256 == 0 || ch < NCH) {
+          unsigned koff; int kkey, kcol;
+          k_chunk(h, ch, koff, kkey, kcol);
+          if (F8) {
+            *reinterpret_cast<bf16x8*>(dst.kp(kkey, kcol / 8)) = e4m3x8_to_bf16(rk[h][i].x, rk[h][i].y);
+            *reinterpret_cast<bf16x8*>(dst.kp(kkey, kcol / 8 + 1)) = e4m3x8_to_bf16(rk[h][i].z, rk[h][i].w);
+            *reinterpret_cast<bf16x8*>(dst.vp(ch >> 1, (ch & 1) * 2)) = e4m3x8_to_bf16(rv[h][i].x, rv[h][i].y);
+            *reinterpret_cast<bf16x8*>(dst.vp(ch >> 1, (ch & 1) * 2 + 1)) = e4m3x8_to_bf16(rv[h][i].z, rv[h][i].w);
+          } else {
+            *reinterpret_cast<uint4*>(dst.kp(kkey, kcol / 8)) = rk[h][i];
+            *reinterpret_cast<uint4*>(dst.vp(ch / 4, ch % 4)) = rv[h][i];
+          }
         }
       }
     }
   };
   const int T_beg = t_beg >> 1, T_end = (t_end + 1) >> 1;
+  const int lo_max = __builtin_amdgcn_readlane(lo[1], 15);      // the wave's last row has the largest lower bound
   if (T_beg < T_end) fetch(T_beg);
   for (int T = T_beg; T < T_end; ++T) {
     __syncthreads();                         // every wave is done with the previous step
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-#pragma unroll
-      for (int i = 0; i < KCH; ++i) {
-        const int ch = tid + i * 256;
-        if (NCH % 256 == 0 || ch < NCH) {
-          size_t off; int kkey, kcol;
-          k_chunk(2 * T + h, ch, off, kkey, kcol);
-          if (F8) {
-            *reinterpret_cast<bf16x8*>(sm[h].kp(kkey, kcol / 8)) = e4m3x8_to_bf16(rk[h][i].x, rk[h][i].y);
-            *reinterpret_cast<bf16x8*>(sm[h].kp(kkey, kcol / 8 + 1)) = e4m3x8_to_bf16(rk[h][i].z, rk[h][i].w);
-            *reinterpret_cast<bf16x8*>(sm[h].vp(ch >> 1, (ch & 1) * 2)) = e4m3x8_to_bf16(rv[h][i].x, rv[h][i].y);
-            *reinterpret_cast<bf16x8*>(sm[h].vp(ch >> 1, (ch & 1) * 2 + 1)) = e4m3x8_to_bf16(rv[h][i].z, rv[h][i].w);
-          } else {
-            *reinterpret_cast<uint4*>(sm[h].kp(kkey, kcol / 8)) = rk[h][i];
-            *reinterpret_cast<uint4*>(sm[h].vp(ch / 4, ch % 4)) = rv[h][i];
-          }
-        }
-      }
-    }
+    store();
     __syncthreads();
     if (T + 1 < T_end) fetch(T + 1);
     const int kb = T * 64;
@@ -233,7 +254,7 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D> (&sm)[2], 
     // attend (they are masked out entirely): skipping them made the accumulators take two paths through
     // the loop, which cost a copy of all 64 accumulator registers per step.  Steps that straddle a bound
     // of some row are masked, the others are not.
-    const bool need_mask = (kb + 63 > row_min) || (kb <= __shfl(lo[1], 15, 64));
+    const bool need_mask = (kb + 63 > row_min) || (kb <= lo_max);
     pf_tile<D>(st, sm, qf, scale_log2, kb, need_mask, lo, hi, m16, g);
   }
 }
@@ -283,7 +304,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       if (prow[q] >= A.n) continue;
-      float ll = st[q].l; ll += __shfl_xor(ll, 16, 64); ll += __shfl_xor(ll, 32, 64);
+      const float ll = st[q].l[0];
       const size_t r = (size_t)b * A.n + prow[q];
       gate[q] = 1.0f / (1.0f + __expf(-A.z[r * A.Hq + h]));
       const float f = ll > 0.f ? gate[q] / ll : 0.f;
@@ -306,7 +327,7 @@ __global__ __launch_bounds__(256, 2) void k_attn_prefill2(PfArgs A) {
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
     if (prow[q] >= A.n) continue;
-    float lg = st[q].l; lg += __shfl_xor(lg, 16, 64); lg += __shfl_xor(lg, 32, 64);
+    const float lg = st[q].l[0];
     const float fg = (lg > 0.f ? 1.0f / lg : 0.f) * (1.0f - gate[q]);     // gate = 0 for first-loop rows
     const size_t r = (size_t)b * A.n + prow[q];
     bf16_t* dst = A.y + (r * A.Hq + h) * D;
