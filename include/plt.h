@@ -197,9 +197,12 @@ int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes);
  *                                                [n_pad, D]; PLT_BF16 / PLT_FP8_E4M3: tiles of 32 / 64
  *                                                positions in the kernel's matrix-core load order
  *                                                (written by plt_attn_pack_k; see below)
- *   v_share  [B, Hkv, n_pad/32, D, 32]           blocks of 32 positions, position fastest
+ *   v_share  [B, Hkv, n_pad * D]                 blocks of 32 positions; PLT_F32: [D, 32], position
+ *                                                fastest; PLT_BF16 / PLT_FP8_E4M3: 16-byte chunks (8 / 16
+ *                                                positions of one feature) ordered [D/16][chunk of
+ *                                                positions][feature % 16] (written by plt_attn_pack_v)
  *   k_ring   [B, L-1, Hkv, w_pad * D]            w_pad = plt_attn_pad(dtype, w); layout as k_share
- *   v_ring   [B, L-1, Hkv, w_pad/32, D, 32]
+ *   v_ring   [B, L-1, Hkv, w_pad * D]            layout as v_share
  *   z        [B, L-1, Hq] float gate logits;  y [B, L, Hq, D] output
  * dtype PLT_FP8_E4M3: q and y are bf16, the four cache arrays hold e4m3 bytes.
  * n_ctx shared entries and n_ring (<= w) ring slots are valid for every sequence.

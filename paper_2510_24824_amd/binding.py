@@ -364,7 +364,7 @@ def attn_pack_k(dtype, src, n):
 
 
 def attn_pack_v(dtype, src, n):
-    """src: device tensor [S, n, D] -> V layout [S, pad32(n)/32, D, 32]."""
+    """src: device tensor [S, n, D] -> the cache's V layout [S, pad(n) * D] (blocks of 32 positions in 16-byte chunks)."""
     import torch
     S, _, D = src.shape
     npad = lib().plt_attn_pad(dtype, n)

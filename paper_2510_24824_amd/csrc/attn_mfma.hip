@@ -11,7 +11,7 @@
 //   S^T[key][row] = K[key][:] . Q[row][:]      A = K straight from HBM (16 B per lane; the cache keeps
 //                                              K tiles in exactly this load order), B = Q in registers
 //   O^T[d][row]  += V^T[d][key] * P^T[key][row]  A = V^T, 16 B per lane thanks to the cache's
-//                                              V layout (blocks of 32 positions, position fastest)
+//                                              V layout (16-byte chunks of consecutive positions)
 // With this orientation a lane owns one query row in S^T, P^T and O^T alike, so the online
 // softmax needs no data movement between the two contractions; the row maximum is completed
 // with two wavefront shuffles (lanes r, r+16, r+32, r+48).  The four waves of a workgroup take
@@ -60,7 +60,7 @@ struct KvTile<D, true> {   // 64 keys of e4m3
   uint4 v[D / 16];         // D/16 groups of 16 features, 16 keys per lane
 };
 
-// kt -> the tile's K block (32 keys, stored in load order: see kblk_index); vt -> the tile's V block [D][32]
+// kt -> the tile's K block (32 keys, stored in load order: see kblk_index); vt -> the tile's V block (vblk_index)
 template <int D>
 __device__ inline void load_tile_k(KvTile<D, false>& t, const char* __restrict__ kt, int m16, int g) {
   const char* kp = kt + (g * 16 + m16) * 16;     // A-row m16 of sub-tile a <-> key 8*(m16>>2) + (m16&3) + 4a
@@ -72,11 +72,11 @@ __device__ inline void load_tile_k(KvTile<D, false>& t, const char* __restrict__
 }
 template <int D>
 __device__ inline void load_tile_v(KvTile<D, false>& t, const char* __restrict__ vt, int m16, int g) {
-  const bf16_t* vp = (const bf16_t*)vt;
+  const char* vp = vt + (g * 16 + m16) * 16;      // chunk (dt, g, m16): positions 8g .. 8g+7 of feature 16 dt + m16
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16_stream(vp + (dt * 16 + m16) * 32 + g * 8);
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16_stream(vp + dt * 1024);
 }
-// e4m3: kt -> the tile's K block (64 keys, load order); vt -> the tile's two V blocks [D][32]
+// e4m3: kt -> the tile's K block (64 keys, load order); vt -> the tile's two V blocks
 template <int D>
 __device__ inline void load_tile_k(KvTile<D, true>& t, const char* __restrict__ kt, int m16, int g) {
   const char* kp = kt + (g * 16 + m16) * 16;     // A-row m16 of sub-tile a <-> key 16*(m16>>2) + (m16&3) + 4a
@@ -88,10 +88,10 @@ __device__ inline void load_tile_k(KvTile<D, true>& t, const char* __restrict__ 
 }
 template <int D>
 __device__ inline void load_tile_v(KvTile<D, true>& t, const char* __restrict__ vt, int m16, int g) {
-  // lane g: positions 16g .. 16g+15 of the tile = half a row of block g/2
-  const char* vb = vt + (size_t)(g >> 1) * (D * 32) + (g & 1) * 16;
+  // lane g: positions 16g .. 16g+15 of the tile = chunk (dt, g & 1, m16) of block g / 2
+  const char* vb = vt + (size_t)(g >> 1) * (D * 32) + ((g & 1) * 16 + m16) * 16;
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16_stream(vb + (dt * 16 + m16) * 32);
+  for (int dt = 0; dt < D / 16; ++dt) t.v[dt] = ldg16_stream(vb + dt * 512);
 }
 
 // One 32-key step of the online softmax.  valid(j) tells whether key j (0..7 -> tile key 8g+j)

@@ -231,11 +231,14 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D> (&sm)[2], 
           if (F8) {
             *reinterpret_cast<bf16x8*>(dst.kp(kkey, kcol / 8)) = e4m3x8_to_bf16(rk[h][i].x, rk[h][i].y);
             *reinterpret_cast<bf16x8*>(dst.kp(kkey, kcol / 8 + 1)) = e4m3x8_to_bf16(rk[h][i].z, rk[h][i].w);
-            *reinterpret_cast<bf16x8*>(dst.vp(ch >> 1, (ch & 1) * 2)) = e4m3x8_to_bf16(rv[h][i].x, rv[h][i].y);
-            *reinterpret_cast<bf16x8*>(dst.vp(ch >> 1, (ch & 1) * 2 + 1)) = e4m3x8_to_bf16(rv[h][i].z, rv[h][i].w);
+            // V chunk ch of the block = (feature group ch / 32, position half (ch / 16) % 2, feature ch % 16)
+            const int vd = (ch >> 5) * 16 + (ch & 15), vc = ((ch >> 4) & 1) * 2;
+            *reinterpret_cast<bf16x8*>(dst.vp(vd, vc)) = e4m3x8_to_bf16(rv[h][i].x, rv[h][i].y);
+            *reinterpret_cast<bf16x8*>(dst.vp(vd, vc + 1)) = e4m3x8_to_bf16(rv[h][i].z, rv[h][i].w);
           } else {
             *reinterpret_cast<uint4*>(dst.kp(kkey, kcol / 8)) = rk[h][i];
-            *reinterpret_cast<uint4*>(dst.vp(ch / 4, ch % 4)) = rv[h][i];
+            // V chunk ch of the block = (feature group ch / 64, position chunk (ch / 16) % 4, feature ch % 16)
+            *reinterpret_cast<uint4*>(dst.vp((ch >> 6) * 16 + (ch & 15), (ch >> 4) & 3)) = rv[h][i];
           }
         }
       }

@@ -298,7 +298,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
       st<KT>(dst + kblk_index<KT>(p, j, D), v0); st<KT>(dst + kblk_index<KT>(p, j + half, D), v1);
     } else {
       KT* dst = (KT*)kv.v_share + coff + stream * (size_t)kv.n_pad * D;
-      st<KT>(dst + vblk_index(p, j, D), v0); st<KT>(dst + vblk_index(p, j + half, D), v1);
+      st<KT>(dst + vblk_index<KT>(p, j, D), v0); st<KT>(dst + vblk_index<KT>(p, j + half, D), v1);
     }
     return;
   }
@@ -311,7 +311,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
       st<KT>(dst + kblk_index<KT>(p, j, D), v0); st<KT>(dst + kblk_index<KT>(p, j + half, D), v1);
     } else {
       KT* dst = (KT*)kv.v_loc + stream * (size_t)kv.n_pad_loc * D;
-      st<KT>(dst + vblk_index(p, j, D), v0); st<KT>(dst + vblk_index(p, j + half, D), v1);
+      st<KT>(dst + vblk_index<KT>(p, j, D), v0); st<KT>(dst + vblk_index<KT>(p, j + half, D), v1);
     }
     if (p < n - kv.w) return;
   }
@@ -323,7 +323,7 @@ __global__ void k_rope_append(const float* __restrict__ qkv, int S, size_t slab,
       st<KT>(dst + kblk_index<KT>(slot, j, D), v0); st<KT>(dst + kblk_index<KT>(slot, j + half, D), v1);
     } else {
       KT* dst = (KT*)kv.v_ring + stream * (size_t)kv.w_pad * D;
-      st<KT>(dst + vblk_index(slot, j, D), v0); st<KT>(dst + vblk_index(slot, j + half, D), v1);
+      st<KT>(dst + vblk_index<KT>(slot, j, D), v0); st<KT>(dst + vblk_index<KT>(slot, j + half, D), v1);
     }
   }
 }
@@ -357,7 +357,7 @@ __device__ inline void store_packed(fp8_t* dst, const float (&v)[N]) {
 
 // grid (ceil(n/32), Hq + 2*Hkv, Bc), 256 threads: thread (r = t/8, c = t%8) owns D/16 rotation pairs
 // (j, j + D/2), j = c*D/16 .., of position p0 + r.  Q and K leave as 8- or 16-byte pieces (K straight into
-// its tiled cache layout); V is transposed through LDS and leaves as one whole [D][32] cache block.
+// its tiled cache layout); V is transposed through LDS and leaves as the 16-byte chunks of one whole cache block.
 template <int D, typename KT>
 __global__ __launch_bounds__(256) void k_rope_append_tile(const float* __restrict__ qkv, int S, size_t slab,
                                                           const float* __restrict__ gate_w, const float* __restrict__ gate_b,
@@ -435,11 +435,11 @@ __global__ __launch_bounds__(256) void k_rope_append_tile(const float* __restric
     }
     return;
   }
-  // V: values are not rotated; transpose the tile through LDS and write the whole [D][32] block
+  // V: values are not rotated; transpose the tile through LDS and write the whole 32-position block
   if (ring) {
     KT* rd = (KT*)kv.v_ring + rstream;
 #pragma unroll
-    for (int i = 0; i < PP; ++i) { st<KT>(rd + vblk_index(slot, jb + i, D), lo[i]); st<KT>(rd + vblk_index(slot, jb + half + i, D), hi[i]); }
+    for (int i = 0; i < PP; ++i) { st<KT>(rd + vblk_index<KT>(slot, jb + i, D), lo[i]); st<KT>(rd + vblk_index<KT>(slot, jb + half + i, D), hi[i]); }
   }
 #pragma unroll
   for (int i = 0; i < PP; ++i) { vt[jb + i][r] = lo[i]; vt[jb + half + i][r] = hi[i]; }   // zeros beyond the prompt
@@ -449,8 +449,16 @@ __global__ __launch_bounds__(256) void k_rope_append_tile(const float* __restric
     float o[PPT];
 #pragma unroll
     for (int i = 0; i < PPT; ++i) o[i] = vt[d][q0 + i];
-    KT* dst = (KT*)(own ? kv.v_loc : kv.v_share) + stream * stream_elems + (size_t)(p0 >> 5) * (D * 32) + d * 32 + q0;
-    store_packed<PPT>(dst, o);
+    // the thread's PPT consecutive positions of feature d: one or two 16-byte chunks of the blocked layout
+    constexpr int CH = 16 / (int)sizeof(KT), RUN = PPT < CH ? PPT : CH;
+    KT* dst = (KT*)(own ? kv.v_loc : kv.v_share) + stream * stream_elems;
+#pragma unroll
+    for (int c = 0; c < PPT / RUN; ++c) {
+      float piece[RUN];
+#pragma unroll
+      for (int i = 0; i < RUN; ++i) piece[i] = o[c * RUN + i];
+      store_packed<RUN>(dst + vblk_index<KT>(p0 + q0 + c * RUN, d, D), piece);
+    }
   }
 }
 
@@ -597,7 +605,7 @@ void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n) {
   hipLaunchKernelGGL(k_copy_f32, dim3(g), dim3(256), 0, s, x, hprev, n);
 }
 
-// ---- layout packs: plain [S, n, D] <-> K [S, n_pad * D] (kblk_index order) / V [S, n_pad/32, D, 32] ----
+// ---- layout packs: plain [S, n, D] <-> K [S, n_pad * D] (kblk_index order) / V [S, n_pad * D] (vblk_index order) ----
 template <typename T>
 __global__ void k_pack_k(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D, int unpack) {
   int sidx = blockIdx.y;
@@ -615,17 +623,15 @@ __global__ void k_pack_k(const T* __restrict__ src, T* __restrict__ dst, int n, 
 template <typename T>
 __global__ void k_pack_v(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D, int unpack) {
   int sidx = blockIdx.y;
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;     // enumerates (pos, d) of the padded plain layout
   if (i >= (size_t)n_pad * D) return;
-  // i enumerates the blocked layout: [blk][d][32]
-  int blk = (int)(i / ((size_t)D * 32));
-  int rem = (int)(i - (size_t)blk * D * 32);
-  int dd = rem >> 5, pos = blk * 32 + (rem & 31);
+  int pos = (int)(i / D), dd = (int)(i - (size_t)pos * D);
+  const size_t li = (size_t)sidx * n_pad * D + vblk_index<T>(pos, dd, D);
   if (unpack) {
-    if (pos < n) dst[(size_t)sidx * n * D + (size_t)pos * D + dd] = src[(size_t)sidx * n_pad * D + i];
+    if (pos < n) dst[(size_t)sidx * n * D + i] = src[li];
   } else {
     T zero; st<T>(&zero, 0.f);
-    dst[(size_t)sidx * n_pad * D + i] = pos < n ? src[(size_t)sidx * n * D + (size_t)pos * D + dd] : zero;
+    dst[li] = pos < n ? src[(size_t)sidx * n * D + i] : zero;
   }
 }
 template <typename T>

@@ -80,10 +80,23 @@ template <> __host__ __device__ inline size_t kblk_index<uint8_t>(int pos, int f
   return (size_t)t * 64 * D + (size_t)(((a * (D >> 6) + kk) * 64 + g * 16 + m) * 16 + e);
 }
 
-// Index of element (pos, d) inside one V stream stored as blocks of 32 positions:
-// [n_pad/32][D][32], position fastest.
-__host__ __device__ inline size_t vblk_index(int pos, int d, int D) {
+// Index of element (pos, d) inside one V stream stored as blocks of 32 positions.  float caches: [n_pad/32][D][32],
+// position fastest.  bf16 and e4m3 caches: the block is cut into 16-byte chunks of CH = 8 (16) consecutive
+// positions of one feature, the unit a matrix-core lane loads, ordered [d / 16][position chunk][d % 16]: the 64
+// chunks one wavefront load of the decode attention kernel fetches (16 features x 32 positions) are one contiguous
+// KiB, and the chunks that the append of ONE position touches (one per feature) lie 16 in a row, so a new
+// position dirties D/8 cache lines of 128 bytes per head instead of the D/2 it would with whole feature rows.
+template <typename KT> __host__ __device__ inline size_t vblk_index(int pos, int d, int D);
+template <> __host__ __device__ inline size_t vblk_index<float>(int pos, int d, int D) {
   return (size_t)(pos >> 5) * (size_t)(D * 32) + (size_t)d * 32 + (size_t)(pos & 31);
+}
+template <> __host__ __device__ inline size_t vblk_index<bf16_t>(int pos, int d, int D) {
+  const int j = pos & 31;
+  return (size_t)(pos >> 5) * (size_t)(D * 32) + (size_t)((((d >> 4) * 4 + (j >> 3)) * 16 + (d & 15)) * 8 + (j & 7));
+}
+template <> __host__ __device__ inline size_t vblk_index<uint8_t>(int pos, int d, int D) {
+  const int j = pos & 31;
+  return (size_t)(pos >> 5) * (size_t)(D * 32) + (size_t)((((d >> 4) * 2 + (j >> 4)) * 16 + (d & 15)) * 16 + (j & 15));
 }
 
 // How a row of the activation matrices maps to (sequence, position, loop stage).
