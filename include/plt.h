@@ -221,12 +221,13 @@ int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv
                     void* hip_stream);
 
 /* Device-side layout conversion for the hook above: plain [S, n, D] (S independent streams,
- * e.g. B*Hkv) -> K layout [S, n_pad * D] (pad positions zeroed) and V layout [S, n_pad/32, D, 32].
+ * e.g. B*Hkv) -> K layout [S, n_pad * D] (pad positions zeroed) and V layout [S, n_pad * D] (see v_share above).
  * K layout of the 2-byte and 1-byte types: a tile of T = 32 (64) positions is T*D elements stored as
- * [a][kk][g][m][c] with c = 16 bytes' worth of consecutive features (8 / 16), m in 0..15, g in 0..3,
+ * [a][kk][m][g][c] with c = 16 bytes' worth of consecutive features (8 / 16), m in 0..15, g in 0..3,
  * kk in 0..D/(4c)-1, a in 0..T/16-1; the element is position 2T/8*(m>>2) + (m&3) + 4a of the tile
  * (i.e. 8*(m>>2) + (m&3) + 4a, resp. 16*(m>>2) + (m&3) + 4a), feature kk*4c + g*c + its index in c:
- * one wavefront load of the attention kernel (lane = 16g + m) is then one contiguous KiB.
+ * one wavefront load of the attention kernel (lane = 16g + m reads piece 4m + g) is then one contiguous KiB,
+ * and the 4c features of one key in chunk kk are 64 adjacent bytes.
  * Elements are moved, never converted: for PLT_FP8_E4M3 source and destination hold e4m3 bytes. */
 /* Host-side statement of the K layout above: element index of (position pos, feature f) inside one
  * stream of head size D (no device work; -1 for a bad argument).  The append, pack and attention

@@ -63,7 +63,7 @@ struct KvTile<D, true> {   // 64 keys of e4m3
 // kt -> the tile's K block (32 keys, stored in load order: see kblk_index); vt -> the tile's V block (vblk_index)
 template <int D>
 __device__ inline void load_tile_k(KvTile<D, false>& t, const char* __restrict__ kt, int m16, int g) {
-  const char* kp = kt + (g * 16 + m16) * 16;     // A-row m16 of sub-tile a <-> key 8*(m16>>2) + (m16&3) + 4a
+  const char* kp = kt + (m16 * 4 + g) * 16;      // A-row m16 of sub-tile a <-> key 8*(m16>>2) + (m16&3) + 4a
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -79,7 +79,7 @@ __device__ inline void load_tile_v(KvTile<D, false>& t, const char* __restrict__
 // e4m3: kt -> the tile's K block (64 keys, load order); vt -> the tile's two V blocks
 template <int D>
 __device__ inline void load_tile_k(KvTile<D, true>& t, const char* __restrict__ kt, int m16, int g) {
-  const char* kp = kt + (g * 16 + m16) * 16;     // A-row m16 of sub-tile a <-> key 16*(m16>>2) + (m16&3) + 4a
+  const char* kp = kt + (m16 * 4 + g) * 16;      // A-row m16 of sub-tile a <-> key 16*(m16>>2) + (m16&3) + 4a
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll

@@ -184,15 +184,15 @@ __device__ __forceinline__ void pf_pass(PfState<D> (&st)[2], PfLds<D> (&sm)[2], 
 #pragma unroll
   for (int i = 0; i < KCH; ++i) { rk[0][i] = rk[1][i] = make_uint4(0, 0, 0, 0); rv[0][i] = rv[1][i] = make_uint4(0, 0, 0, 0); }
   // The cache keeps K in the decode kernel's load order (kblk_index): a 16-byte chunk of a block is
-  // (sub-tile a, feature chunk kk, lane group g, row m) and belongs to key kkey, features kcol ..; its address
+  // (sub-tile a, feature chunk kk, row m, lane group g) and belongs to key kkey, features kcol ..; its address
   // is a block offset (the same for all threads: scalar registers) plus a per-thread constant koff.
   auto k_chunk = [&](int h, int ch, unsigned& koff, int& kkey, int& kcol) {
     if (F8) {   // 64-key blocks; the 32-key block is half h of one: rows m with (m >> 2) in {2h, 2h+1}
-      const int m = 8 * h + (ch & 7), g = (ch >> 3) & 3, kk = (ch >> 5) % (D / 64), a = (ch >> 5) / (D / 64);
-      koff = (unsigned)(((a * (D / 64) + kk) * 64 + g * 16 + m) * 16);
+      const int g = ch & 3, m = 8 * h + ((ch >> 2) & 7), kk = (ch >> 5) % (D / 64), a = (ch >> 5) / (D / 64);
+      koff = (unsigned)(((a * (D / 64) + kk) * 64 + m * 4 + g) * 16);
       kkey = 16 * ((m >> 2) & 1) + (m & 3) + 4 * a; kcol = kk * 64 + g * 16;
     } else {
-      const int m = ch & 15, g = (ch >> 4) & 3, kk = (ch >> 6) % (D / 32), a = (ch >> 6) / (D / 32);
+      const int g = ch & 3, m = (ch >> 2) & 15, kk = (ch >> 6) % (D / 32), a = (ch >> 6) / (D / 32);
       koff = (unsigned)ch * 16u;
       kkey = 8 * (m >> 2) + (m & 3) + 4 * a; kcol = kk * 32 + g * 8;
     }

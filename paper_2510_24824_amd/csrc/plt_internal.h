@@ -61,23 +61,25 @@ inline int pad_kv(int n, bool fp8) { return fp8 ? (n + 63) & ~63 : pad32(n); }
 
 // Index of element (pos, f) inside one K stream.  float caches: row-major [n_pad][D].  bf16 and
 // e4m3 caches: tiles of 32 (64) positions stored in the order the decode attention kernel's
-// matrix-core loads consume them, [sub-tile a][feature chunk kk][lane = g*16 + m][16 bytes], where
+// matrix-core loads consume them, [sub-tile a][feature chunk kk][row m][lane group g][16 bytes], where
 // lane (m, g) of load (a, kk) holds the 16 bytes of key 8*(m>>2) + (m&3) + 4a, features kk*32 + 8g ..
 // (bf16; e4m3: key 16*(m>>2) + (m&3) + 4a, features kk*64 + 16g ..): every wavefront load is then one
-// contiguous 1 KB, which streams measurably faster from HBM than 16 separate 64-byte row pieces.
+// contiguous 1 KB (the lanes read it in a permuted order, which the memory pipeline does not mind), which
+// streams measurably faster from HBM than 16 separate 64-byte row pieces, and the four pieces of one key
+// (g = 0..3) are 64 adjacent bytes, so appending a key dirties one cache line per feature chunk kk.
 template <typename KT> __host__ __device__ inline size_t kblk_index(int pos, int f, int D);
 template <> __host__ __device__ inline size_t kblk_index<float>(int pos, int f, int D) { return (size_t)pos * D + f; }
 template <> __host__ __device__ inline size_t kblk_index<bf16_t>(int pos, int f, int D) {
   const int t = pos >> 5, j = pos & 31;
   const int a = (j >> 2) & 1, m = ((j >> 3) << 2) | (j & 3);
   const int kk = f >> 5, g = (f >> 3) & 3, e = f & 7;
-  return (size_t)t * 32 * D + (size_t)(((a * (D >> 5) + kk) * 64 + g * 16 + m) * 8 + e);
+  return (size_t)t * 32 * D + (size_t)(((a * (D >> 5) + kk) * 64 + m * 4 + g) * 8 + e);
 }
 template <> __host__ __device__ inline size_t kblk_index<uint8_t>(int pos, int f, int D) {
   const int t = pos >> 6, j = pos & 63;
   const int a = (j >> 2) & 3, m = ((j >> 4) << 2) | (j & 3);
   const int kk = f >> 6, g = (f >> 4) & 3, e = f & 15;
-  return (size_t)t * 64 * D + (size_t)(((a * (D >> 6) + kk) * 64 + g * 16 + m) * 16 + e);
+  return (size_t)t * 64 * D + (size_t)(((a * (D >> 6) + kk) * 64 + m * 4 + g) * 16 + e);
 }
 
 // Index of element (pos, d) inside one V stream stored as blocks of 32 positions.  float caches: [n_pad/32][D][32],

@@ -140,7 +140,7 @@ def test_bench_refuses_more_than_one_gpu():
 
 def test_k_cache_layout_is_a_tiling_in_matrix_core_load_order():
     """The K cache keeps tiles of 32 (bf16) / 64 (e4m3) positions; inside a tile the 16-byte pieces
-    follow [sub-tile a][feature chunk kk][lane group g][row m]; float caches stay row-major.  Checked
+    follow [sub-tile a][feature chunk kk][row m][lane group g]; float caches stay row-major.  Checked
     on the host function the kernels share: a bijection per tile, 16-byte pieces intact, and lane
     (m, g) of load (a, kk) holding key step*(m>>2) + (m&3) + 4a, features kk*4c + g*c .."""
     lib = B.lib()
@@ -155,7 +155,7 @@ def test_k_cache_layout_is_a_tiling_in_matrix_core_load_order():
                     for g in range(4):
                         for m in range(16):
                             key, f0 = step * (m >> 2) + (m & 3) + 4 * a, kk * 4 * c + g * c
-                            base = ((a * (D // (4 * c)) + kk) * 64 + g * 16 + m) * c
+                            base = ((a * (D // (4 * c)) + kk) * 64 + m * 4 + g) * c
                             assert list(idx[key, f0:f0 + c]) == list(range(base, base + c))
     assert lib.plt_attn_k_index(B.PLT_F32, 5, 7, 64) == 5 * 64 + 7
     assert lib.plt_attn_k_index(B.PLT_BF16, 0, 64, 64) == -1 and lib.plt_attn_k_index(9, 0, 0, 64) == -1
