@@ -233,6 +233,12 @@ int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv
  * stream of head size D (no device work; -1 for a bad argument).  The append, pack and attention
  * kernels use the same function. */
 int64_t plt_attn_k_index(int32_t dtype, int32_t pos, int32_t f, int32_t D);
+/* The same for the V layout (v_share above): element index of (position pos, feature d) inside one stream.
+ * PLT_F32: blocks of 32 positions stored [D][32].  PLT_BF16 / PLT_FP8_E4M3: a block's 16-byte chunks
+ * (c = 8 / 16 consecutive positions of one feature) in the order [d / 16][position chunk][d % 16]: the 64
+ * chunks of 16 features x 32 positions are one contiguous KiB (one wavefront load of the attention kernel),
+ * and the chunks that one appended position touches lie 16 in a row. */
+int64_t plt_attn_v_index(int32_t dtype, int32_t pos, int32_t d, int32_t D);
 int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,
                     void* dev_dst, void* hip_stream);
 int plt_attn_pack_v(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* dev_src,

@@ -63,6 +63,7 @@ _SIGS = {
     "plt_attn_scratch_bytes": (_Z, [_I, _I, _I, _I, _I]),
     "plt_attn_decode": (C.c_int, [_I] * 10 + [_P] * 8 + [_Z, _I, _P]),
     "plt_attn_k_index": (C.c_int64, [_I, _I, _I, _I]),
+    "plt_attn_v_index": (C.c_int64, [_I, _I, _I, _I]),
     "plt_attn_pack_k": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),

@@ -847,6 +847,14 @@ extern "C" int64_t plt_attn_k_index(int32_t dtype, int32_t pos, int32_t f, int32
   return -1;
 }
 
+extern "C" int64_t plt_attn_v_index(int32_t dtype, int32_t pos, int32_t d, int32_t D) {
+  if (pos < 0 || d < 0 || d >= D || (D != 64 && D != 128)) return -1;
+  if (dtype == PLT_F32) return (int64_t)vblk_index<float>(pos, d, D);
+  if (dtype == PLT_BF16) return (int64_t)vblk_index<bf16_t>(pos, d, D);
+  if (dtype == PLT_FP8_E4M3) return (int64_t)vblk_index<fp8_t>(pos, d, D);
+  return -1;
+}
+
 extern "C" int plt_attn_pack_k(int32_t dtype, int32_t S, int32_t n, int32_t D, const void* src, void* dst,
                                void* hip_stream) {
   if ((dtype != PLT_F32 && dtype != PLT_BF16 && dtype != PLT_FP8_E4M3) || S < 1 || S > 65535 || n < 1 || D < 1 || !src || !dst)

@@ -161,6 +161,35 @@ def test_k_cache_layout_is_a_tiling_in_matrix_core_load_order():
     assert lib.plt_attn_k_index(B.PLT_BF16, 0, 64, 64) == -1 and lib.plt_attn_k_index(9, 0, 0, 64) == -1
 
 
+def test_v_cache_layout_keeps_the_chunks_of_one_position_together():
+    """The V cache keeps blocks of 32 positions; in the 2-byte and 1-byte types a block is cut into 16-byte
+    chunks (c = 8 / 16 consecutive positions of one feature) ordered [d / 16][position chunk][d % 16].  Checked
+    on the host function the kernels share: a bijection per block, chunks intact, the 64 (32) chunks of 16
+    features contiguous (one wavefront load), and the chunks one position touches in runs of 16 (= D/8 cache
+    lines of 128 bytes per appended position and head; whole feature rows would touch D/2)."""
+    lib = B.lib()
+    for dtype, c in ((B.PLT_BF16, 8), (B.PLT_FP8_E4M3, 16)):
+        es = 16 // c                                                # bytes per element
+        for D in (64, 128):
+            idx = np.array([[lib.plt_attn_v_index(dtype, p, d, D) for d in range(D)] for p in range(64)])
+            assert sorted(idx[:32].ravel()) == list(range(32 * D))              # block 0 <-> [0, 32*D)
+            assert np.array_equal(idx[32:], idx[:32] + 32 * D)                  # block 1 follows
+            for d in range(D):
+                for p0 in range(0, 32, c):                                      # chunks of c positions intact
+                    assert list(idx[p0:p0 + c, d]) == list(range(idx[p0, d], idx[p0, d] + c))
+            for dt in range(D // 16):                                           # 16 features x 32 positions: contiguous
+                blk = idx[:32, dt * 16:(dt + 1) * 16]
+                assert blk.max() - blk.min() + 1 == 32 * 16
+            for p in (0, 5, 31):
+                lines = {int(i) * es // 128 for i in idx[p]}
+                assert len(lines) == D // 8
+                chunks = sorted(int(i) // c for i in idx[p])
+                for k in range(0, D, 16):                                       # 16 chunks in a row per feature group
+                    assert chunks[k:k + 16] == list(range(chunks[k], chunks[k] + 16))
+    assert lib.plt_attn_v_index(B.PLT_F32, 37, 3, 64) == 32 * 64 + 3 * 32 + 5
+    assert lib.plt_attn_v_index(B.PLT_BF16, 0, 64, 64) == -1 and lib.plt_attn_v_index(9, 0, 0, 64) == -1
+
+
 def test_expert_weight_layout_is_a_permutation_in_strip_order():
     """plt_moe_weight_index: a bijection on [0, N*K); a strip of 16 rows is one contiguous run, and inside it
     lane (m, g) of k chunk c holds row m, columns 32 c + 8 g .. + 7 as 8 consecutive elements.  The
