@@ -109,6 +109,17 @@ def test_fp8_small_models(L, w, heads, D):
     run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 12, 4e-2, kv_dtype=FP8)
 
 
+@pytest.mark.parametrize("n,L,w,heads,D", [(333, 3, 40, (4, 2), 64), (200, 2, 100, (2, 2), 128)])
+def test_fp8_prompts_of_several_key_tiles(n, L, w, heads, D):
+    """As the bf16 test of the same name: prompts that span several 64-key steps and more than one 128-row query
+    tile, lengths and windows that are no multiples of 32, with e4m3 caches."""
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=heads[0], n_kv_heads=heads[1], head_dim=D,
+                             ffn_hidden=320, vocab=500, n_loops=L, window=w)
+    weights = lively_weights(shape, 9, bf16=True, std=0.02)
+    prompts = synth.token_ids((2, n), shape.vocab, 12)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 4, 4e-2, kv_dtype=FP8)
+
+
 @pytest.mark.parametrize("mode", [B.PLT_MODE_VANILLA_LOOP, B.PLT_MODE_CLP_SHARE_ONLY, B.PLT_MODE_CLP_OWN_KV])
 def test_fp8_other_modes(mode):
     shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,

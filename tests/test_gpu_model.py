@@ -94,6 +94,19 @@ def test_bf16_small_models(L, w, heads, D):
     run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 12, 2e-2)
 
 
+@pytest.mark.parametrize("n,L,w,heads,D", [(333, 3, 40, (4, 2), 64), (200, 2, 100, (2, 2), 128), (130, 2, 64, (2, 1), 128)])
+def test_bf16_prompts_of_several_key_tiles(n, L, w, heads, D):
+    """Prompts longer than one workgroup's 128 query rows and than several 64-key steps, with lengths and windows
+    that are no multiples of 32: the prefill attention's step ranges start and end inside 64-key steps (odd first
+    32-key block of a window, last block beyond the prompt), and the state it hands to the decode steps that
+    follow crosses tile boundaries.  Teacher-forced against the oracle like the small cases."""
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=heads[0], n_kv_heads=heads[1], head_dim=D,
+                             ffn_hidden=320, vocab=500, n_loops=L, window=w)
+    weights = lively_weights(shape, 9, bf16=True, std=0.02)
+    prompts = synth.token_ids((2, n), shape.vocab, 12)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 4, 2e-2)
+
+
 @pytest.mark.parametrize("dtype,tol", [(B.PLT_F32, 2e-5), (B.PLT_BF16, 2e-2)])
 def test_vanilla_loop_mode(dtype, tol):
     shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,
