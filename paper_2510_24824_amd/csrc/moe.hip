@@ -469,6 +469,174 @@ static void moe_gemm_pick(hipStream_t s, const bf16_t* a, const bf16_t* w, const
   else moe_gemm_launch<8, 512, GU, 2, 8>(s, a, w, mi, act, y, R, N, K, k, E);
 }
 
+// ---------------------------------------------------------------------------------------------- prefill-sized batches
+// Grouped GEMM for hundreds of rows per expert (matrix-core-bound): the tile algebra of the dense prefill GEMM
+// (workgroup tile 256 list rows x 256 weight rows, K in slices of 64 through two LDS stages filled HBM -> LDS
+// directly, 8 waves of 128 x 64) on one expert's sorted list.  The activation rows of a tile are gathered
+// through the list (GU) or lie contiguous by list position (DOWN); the weight tile is read out of the expert's
+// strip-ordered matrix chunk by chunk.  GU: the tile holds 128 gate rows and the matching 128 up rows,
+// SwiGLU in the epilogue.  grid (column tiles, row-tile slots): slot s belongs to the expert whose run of
+// ceil(n_e / 256) row tiles contains s; P/256 + E slots always suffice, the surplus workgroups leave at once.
+// Consecutive workgroups are the column tiles of one row tile: a compute die keeps meeting the same 1 MB
+// column block of the expert's matrix while that expert's row tiles pass by.
+template <bool GU>
+__global__ __launch_bounds__(512) void k_moe_gemm_tile(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
+                                                       const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
+                                                       const float* __restrict__ sel_p, bf16_t* __restrict__ act_out,
+                                                       float* __restrict__ y_out, int R, int N, int K, int topk, int E) {
+  constexpr int BM = 256, BN = 256, BK = 64, THREADS = 512, WN = 4, MI = 8, NT = 4, HALF = 128;
+  constexpr int A_BYTES = BM * BK * 2, W_BYTES = BN * BK * 2, STAGE_BYTES = A_BYTES + W_BYTES;
+  extern __shared__ __attribute__((aligned(16))) char mt_lds[];
+  __shared__ int s_where[3];                         // expert, first list position, rows of the expert
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int wm = wv / WN, wn = wv % WN;
+  if (wv == 0) {
+    // which expert owns row-tile slot blockIdx.y: lanes scan 64 experts at a time
+    const int slot = blockIdx.y;
+    int base = 0, found = -1;
+    for (int e0 = 0; e0 < E && found < 0; e0 += 64) {
+      const int e = e0 + lane;
+      const int n_e = e < E ? off[e + 1] - off[e] : 0;
+      const int nt = (n_e + BM - 1) / BM;
+      int incl = nt;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o, 64); if (lane >= o) incl += v; }
+      const bool mine = slot >= base + incl - nt && slot < base + incl;
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(mine);
+      if (bal) {
+        found = e0 + __builtin_ctzll(bal);
+        if (mine) { s_where[0] = e; s_where[1] = off[e] + (slot - (base + incl - nt)) * BM; s_where[2] = off[e + 1]; }
+      }
+      base += __shfl(incl, 63, 64);
+    }
+    if (found < 0 && lane == 0) s_where[0] = -1;
+  }
+  __syncthreads();
+  const int e = s_where[0];
+  if (e < 0) return;
+  const int p0 = s_where[1], p_end = s_where[2];     // list positions [p0, min(p0 + 256, p_end)) are this tile's rows
+  const int NR = GU ? 2 * N : N;                     // rows of one expert's matrix
+  const int n0 = blockIdx.x * (GU ? HALF : BN);
+  const bf16_t* we = w + (size_t)e * NR * K;
+  // weight row behind local tile row r (rows beyond the matrix: clamped, their outputs are never stored)
+  auto wrow = [&](int r) -> int {
+    int gr;
+    if (GU) { const int c = n0 + (r & (HALF - 1)); gr = r < HALF ? c : N + c; if (c >= N) gr = NR - 1; }
+    else gr = n0 + r;
+    return gr < NR ? gr : NR - 1;
+  };
+  // this thread's chunks: slot s = i*THREADS + tid -> tile row s/8, chunk (s%8) ^ (row%8)  (as in the dense kernel)
+  const bf16_t* pa[4]; const bf16_t* pw[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int sl = i * THREADS + tid, row = sl >> 3, kc = (sl & 7) ^ (row & 7);
+    int pos = p0 + row; if (pos >= p_end) pos = p_end - 1;
+    const size_t src_row = GU ? (size_t)(pair[pos] / topk) : (size_t)pos;
+    pa[i] = a + src_row * K + kc * 8;
+    pw[i] = we + moe_wtile_index(wrow(row), kc * 8, K);          // + 1024 elements per slice of 64
+  }
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mt_lds;
+  auto dma16 = [](const bf16_t* src, unsigned lds_wave_base) {   // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
+    unsigned keep_m0;                                            // m0 is left as it was found
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
+  };
+  auto issue = [&](int ks) {
+    const unsigned stage = lds0 + (unsigned)(ks & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      dma16(pa[i] + ks * BK, stage + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      dma16(pw[i] + (size_t)ks * 1024, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+  };
+  const int ks_total = K / BK;
+  f32x4 acc[MI][NT];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int sw0 = (g ^ (m16 & 7)) * 16;
+  issue(0);
+  for (int ks = 0; ks < ks_total; ++ks) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of slice ks has landed
+    __syncthreads();                                   // ... and everyone's; slice ks - 1 is no longer read
+    if (ks + 1 < ks_total) issue(ks + 1);
+    const char* As = mt_lds + (ks & 1) * STAGE_BYTES;
+    const char* Ws = As + A_BYTES;
+#pragma unroll
+    for (int k32 = 0; k32 < BK / 32; ++k32) {
+      const int sw = sw0 ^ (k32 * 64);
+      uint4 fw[NT];
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        // GU: tiles 0, 1 = this wave's 32 gate columns, tiles 2, 3 = the matching up columns
+        const int r = GU ? (j < NT / 2 ? wn * 32 + j * 16 : HALF + wn * 32 + (j - NT / 2) * 16) : wn * 64 + j * 16;
+        fw[j] = *reinterpret_cast<const uint4*>(Ws + (r + m16) * 128 + sw);
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+        const uint4 fa = *reinterpret_cast<const uint4*>(As + (wm * 128 + i * 16 + m16) * 128 + sw);
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[j]),
+                                                             __builtin_bit_cast(bf16x8, fa), acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+  // acc[i][j][x]: list row p0 + wm*128 + i*16 + m16, column (tile j) + 4 g + x
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int pos = p0 + wm * 128 + i * 16 + m16;
+    if (pos >= p_end) continue;
+    if (GU) {
+      bf16_t* o = act_out + (size_t)pos * N;
+#pragma unroll
+      for (int j = 0; j < NT / 2; ++j) {
+        const int gn = n0 + wn * 32 + j * 16 + 4 * g;
+        if (gn >= N) continue;                       // N is a multiple of 16: whole groups of 4 columns
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) { const float gt = acc[i][j][x]; v[x] = gt / (1.0f + expf(-gt)) * acc[i][j + NT / 2][x]; }
+        ushort4 pk; pk.x = f32_to_bf16(v[0]); pk.y = f32_to_bf16(v[1]); pk.z = f32_to_bf16(v[2]); pk.w = f32_to_bf16(v[3]);
+        *reinterpret_cast<ushort4*>(o + gn) = pk;
+      }
+    } else {
+      const int pr = pair[pos];
+      const int row = pr / topk, slot = pr - row * topk;
+      const float p = sel_p[pr];
+      float* o = y_out + ((size_t)slot * R + row) * N;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int gn = n0 + wn * 64 + j * 16 + 4 * g;
+        if (gn >= N) continue;
+        f32x4 v = acc[i][j];
+        v[0] *= p; v[1] *= p; v[2] *= p; v[3] *= p;
+        *reinterpret_cast<f32x4*>(o + gn) = v;
+      }
+    }
+  }
+}
+
+// rows per expert from which the tiled kernel is used, and what it needs of the shapes
+static bool moe_gemm_tile_applies(int R, int k, int E, int N, int K) {
+  return (long)R * k >= (long)E * 192 && (K % 64) == 0 && (N % 16) == 0;
+}
+template <bool GU>
+static void moe_gemm_tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act, float* y,
+                                 int R, int N, int K, int k, int E) {
+  constexpr int LDS_BYTES = 2 * (256 + 256) * 64 * 2;
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_moe_gemm_tile<GU>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    attr_done = true;
+  }
+  const int ncols = GU ? 128 : 256;
+  const long P = (long)R * k;
+  dim3 grid((N + ncols - 1) / ncols, (unsigned)(P / 256 + E));
+  hipLaunchKernelGGL(k_moe_gemm_tile<GU>, grid, dim3(512), LDS_BYTES, s, a, w, mi.off, mi.pair, mi.sel_p, act, y, R, N, K, k, E);
+}
+
 template <typename T>
 void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, const T* wdown, T* act, float* y,
                     MoeIndex mi, int R, int d, int F, int E, int k) {
@@ -482,8 +650,13 @@ void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, co
   else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
   if constexpr (sizeof(T) == 2) {
-    moe_gemm_pick<true>(s, (const bf16_t*)a, (const bf16_t*)wgu, mi, (bf16_t*)act, nullptr, R, F, d, k, E);
-    moe_gemm_pick<false>(s, (const bf16_t*)act, (const bf16_t*)wdown, mi, nullptr, y, R, d, F, k, E);
+    if (!fly && moe_gemm_tile_applies(R, k, E, F, d) && moe_gemm_tile_applies(R, k, E, d, F)) {
+      moe_gemm_tile_launch<true>(s, (const bf16_t*)a, (const bf16_t*)wgu, mi, (bf16_t*)act, nullptr, R, F, d, k, E);
+      moe_gemm_tile_launch<false>(s, (const bf16_t*)act, (const bf16_t*)wdown, mi, nullptr, y, R, d, F, k, E);
+    } else {
+      moe_gemm_pick<true>(s, (const bf16_t*)a, (const bf16_t*)wgu, mi, (bf16_t*)act, nullptr, R, F, d, k, E);
+      moe_gemm_pick<false>(s, (const bf16_t*)act, (const bf16_t*)wdown, mi, nullptr, y, R, d, F, k, E);
+    }
   } else {
     hipLaunchKernelGGL(k_moe_gu_f32, dim3(P, (F + 15) / 16), dim3(256), 0, s, a, wgu, mi.sel_e, mi.pair, act, F, d, k);
     hipLaunchKernelGGL(k_moe_down_f32, dim3(P, (d + 15) / 16), dim3(256), 0, s, act, wdown, mi.sel_e, mi.pair, mi.sel_p,
