@@ -127,19 +127,9 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __rest
 // broadcast with a lane read, and lane (e mod 64) keeps the running counter of expert e -- positions
 // follow from counts alone, so the result does not depend on any execution order.  The walk is a chain
 // of vector instructions per pair, so it is kept to a handful: EW = ceil(E / 64) counters per lane.
+// first walk of a wave's span [beg, end): c[j] (lane l) += number of pairs of expert l + 64 j
 template <int EW>
-__global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__ sel_e, int32_t* __restrict__ off,
-                                                     int32_t* __restrict__ pair, int P, int E) {
-  __shared__ int cnt[16][EW * 64];
-  __shared__ int offs[EW * 64 + 1];
-  __shared__ int wave_tot[EW];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const int per = (((P + 15) / 16) + 63) & ~63;
-  const int beg = wv * per < P ? wv * per : P;
-  const int end = beg + per < P ? beg + per : P;
-  int c[EW];                                     // lane holds the counters of experts lane + 64 j
-#pragma unroll
-  for (int j = 0; j < EW; ++j) c[j] = 0;
+__device__ inline void moe_walk_count(const int32_t* __restrict__ sel_e, int beg, int end, int lane, int (&c)[EW]) {
   for (int i0 = beg; i0 < end; i0 += 64) {
     const int v = i0 + lane < end ? sel_e[i0 + lane] : -1;
     const int nt = end - i0 < 64 ? end - i0 : 64;
@@ -152,35 +142,11 @@ __global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__
       }
     }
   }
-#pragma unroll
-  for (int j = 0; j < EW; ++j) cnt[wv][lane + 64 * j] = c[j];
-  __syncthreads();
-  // exclusive prefix sum of the per-expert totals over EW * 64 slots (EW waves, shuffle scan)
-  int tot = 0, incl = 0;
-  if (tid < EW * 64) {
-#pragma unroll
-    for (int w = 0; w < 16; ++w) tot += cnt[w][tid];
-    incl = tot;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
-    if (lane == 63) wave_tot[wv] = incl;
-  }
-  __syncthreads();
-  if (tid < EW * 64) {
-    int base = 0;
-    for (int w = 0; w < wv; ++w) base += wave_tot[w];
-    offs[tid] = base + incl - tot;
-    if (tid == EW * 64 - 1) offs[EW * 64] = base + incl;
-  }
-  __syncthreads();
-  if (tid <= E) off[tid] = offs[tid];          // experts >= E have no pairs: offs[E] is the total
-#pragma unroll
-  for (int j = 0; j < EW; ++j) {
-    const int e = lane + 64 * j;
-    int b = offs[e];
-    for (int w = 0; w < wv; ++w) b += cnt[w][e];
-    c[j] = b;
-  }
+}
+// second walk: c[j] (lane l) holds the next list position of expert l + 64 j; every pair is stored at its position
+template <int EW>
+__device__ inline void moe_walk_scatter(const int32_t* __restrict__ sel_e, int beg, int end, int lane, int (&c)[EW],
+                                        int32_t* __restrict__ pair) {
   for (int i0 = beg; i0 < end; i0 += 64) {
     const int v = i0 + lane < end ? sel_e[i0 + lane] : -1;
     const int nt = end - i0 < 64 ? end - i0 : 64;
@@ -201,6 +167,150 @@ __global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__
     }
     if (lane < nt) pair[mypos] = i0 + lane;      // one store per chunk, after the loop
   }
+}
+// exclusive prefix over the EW * 64 per-expert totals held by threads tid < EW * 64 (one per thread) -> offs[0 .. EW*64]
+template <int EW>
+__device__ inline void moe_expert_offsets(int tot, int tid, int* offs /* LDS [EW*64+1] */, int* wave_tot /* LDS [EW] */) {
+  const int lane = tid & 63, wv = tid >> 6;
+  int incl = 0;
+  if (tid < EW * 64) {
+    incl = tot;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) { const int up = __shfl_up(incl, o); if (lane >= o) incl += up; }
+    if (lane == 63) wave_tot[wv] = incl;
+  }
+  __syncthreads();
+  if (tid < EW * 64) {
+    int base = 0;
+    for (int w = 0; w < wv; ++w) base += wave_tot[w];
+    offs[tid] = base + incl - tot;
+    if (tid == EW * 64 - 1) offs[EW * 64] = base + incl;
+  }
+  __syncthreads();
+}
+
+template <int EW>
+__global__ __launch_bounds__(1024) void k_moe_bucket(const int32_t* __restrict__ sel_e, int32_t* __restrict__ off,
+                                                     int32_t* __restrict__ pair, int P, int E) {
+  __shared__ int cnt[16][EW * 64];
+  __shared__ int offs[EW * 64 + 1];
+  __shared__ int wave_tot[EW];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int per = (((P + 15) / 16) + 63) & ~63;
+  const int beg = wv * per < P ? wv * per : P;
+  const int end = beg + per < P ? beg + per : P;
+  int c[EW];                                     // lane holds the counters of experts lane + 64 j
+#pragma unroll
+  for (int j = 0; j < EW; ++j) c[j] = 0;
+  moe_walk_count<EW>(sel_e, beg, end, lane, c);
+#pragma unroll
+  for (int j = 0; j < EW; ++j) cnt[wv][lane + 64 * j] = c[j];
+  __syncthreads();
+  int tot = 0;
+  if (tid < EW * 64) {
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += cnt[w][tid];
+  }
+  moe_expert_offsets<EW>(tot, tid, offs, wave_tot);
+  if (tid <= E) off[tid] = offs[tid];          // experts >= E have no pairs: offs[E] is the total
+#pragma unroll
+  for (int j = 0; j < EW; ++j) {
+    const int e = lane + 64 * j;
+    int b = offs[e];
+    for (int w = 0; w < wv; ++w) b += cnt[w][e];
+    c[j] = b;
+  }
+  moe_walk_scatter<EW>(sel_e, beg, end, lane, c, pair);
+}
+
+// The same sort for prefill-sized batches (tens of thousands of pairs, where one workgroup's walk takes 0.6 ms):
+// spans of MOE_SPAN pairs, one per wave, over as many workgroups as it takes, in three launches -- count per span,
+// positions per (span, expert) by one workgroup, scatter per span.  Positions still follow from counts alone:
+// the lists are the ones k_moe_bucket produces.
+constexpr int MOE_SPAN = 256;
+template <int EW>
+__global__ __launch_bounds__(1024) void k_moe_span_count(const int32_t* __restrict__ sel_e, int32_t* __restrict__ span_cnt, int P) {
+  const int lane = threadIdx.x & 63, sp = blockIdx.x * 16 + (threadIdx.x >> 6);
+  const int beg = sp * MOE_SPAN;
+  if (beg >= P) return;
+  const int end = beg + MOE_SPAN < P ? beg + MOE_SPAN : P;
+  int c[EW];
+#pragma unroll
+  for (int j = 0; j < EW; ++j) c[j] = 0;
+  moe_walk_count<EW>(sel_e, beg, end, lane, c);
+#pragma unroll
+  for (int j = 0; j < EW; ++j) span_cnt[(size_t)sp * (EW * 64) + lane + 64 * j] = c[j];
+}
+// span_cnt [n_spans][EW*64]: in, the counts; out, the first list position of (span, expert)
+template <int EW>
+__global__ __launch_bounds__(1024) void k_moe_span_offsets(int32_t* __restrict__ span_cnt, int32_t* __restrict__ off, int n_spans, int E) {
+  __shared__ int cnt[16][EW * 64];
+  __shared__ int offs[EW * 64 + 1];
+  __shared__ int wave_tot[EW];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int per = (n_spans + 15) / 16;
+  const int s0 = wv * per < n_spans ? wv * per : n_spans, s1 = s0 + per < n_spans ? s0 + per : n_spans;
+  int c[EW];
+#pragma unroll
+  for (int j = 0; j < EW; ++j) c[j] = 0;
+  for (int sp = s0; sp < s1; ++sp)
+#pragma unroll
+    for (int j = 0; j < EW; ++j) c[j] += span_cnt[(size_t)sp * (EW * 64) + lane + 64 * j];
+#pragma unroll
+  for (int j = 0; j < EW; ++j) cnt[wv][lane + 64 * j] = c[j];
+  __syncthreads();
+  int tot = 0;
+  if (tid < EW * 64) {
+#pragma unroll
+    for (int w = 0; w < 16; ++w) tot += cnt[w][tid];
+  }
+  moe_expert_offsets<EW>(tot, tid, offs, wave_tot);
+  if (tid <= E) off[tid] = offs[tid];
+#pragma unroll
+  for (int j = 0; j < EW; ++j) {
+    const int e = lane + 64 * j;
+    int b = offs[e];
+    for (int w = 0; w < wv; ++w) b += cnt[w][e];
+    c[j] = b;
+  }
+  for (int sp = s0; sp < s1; ++sp)
+#pragma unroll
+    for (int j = 0; j < EW; ++j) {
+      const size_t idx = (size_t)sp * (EW * 64) + lane + 64 * j;
+      const int v = span_cnt[idx];
+      span_cnt[idx] = c[j];
+      c[j] += v;
+    }
+}
+template <int EW>
+__global__ __launch_bounds__(1024) void k_moe_span_scatter(const int32_t* __restrict__ sel_e, const int32_t* __restrict__ span_base,
+                                                           int32_t* __restrict__ pair, int P) {
+  const int lane = threadIdx.x & 63, sp = blockIdx.x * 16 + (threadIdx.x >> 6);
+  const int beg = sp * MOE_SPAN;
+  if (beg >= P) return;
+  const int end = beg + MOE_SPAN < P ? beg + MOE_SPAN : P;
+  int c[EW];
+#pragma unroll
+  for (int j = 0; j < EW; ++j) c[j] = span_base[(size_t)sp * (EW * 64) + lane + 64 * j];
+  moe_walk_scatter<EW>(sel_e, beg, end, lane, c, pair);
+}
+// the sort, whichever way: up to MOE_SORT_ONE pairs by the single workgroup
+constexpr int MOE_SORT_ONE = 4096;
+template <int EW>
+static void moe_sort_launch(hipStream_t s, const MoeIndex& mi, int P, int E) {
+  if (P <= MOE_SORT_ONE) {
+    hipLaunchKernelGGL(k_moe_bucket<EW>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+    return;
+  }
+  const int n_spans = (P + MOE_SPAN - 1) / MOE_SPAN, wgs = (n_spans + 15) / 16;
+  hipLaunchKernelGGL(k_moe_span_count<EW>, dim3(wgs), dim3(1024), 0, s, mi.sel_e, mi.span, P);
+  hipLaunchKernelGGL(k_moe_span_offsets<EW>, dim3(1), dim3(1024), 0, s, mi.span, mi.off, n_spans, E);
+  hipLaunchKernelGGL(k_moe_span_scatter<EW>, dim3(wgs), dim3(1024), 0, s, mi.sel_e, mi.span, mi.pair, P);
+}
+static void moe_sort(hipStream_t s, const MoeIndex& mi, int P, int E) {
+  if (E <= 64) moe_sort_launch<1>(s, mi, P, E);
+  else if (E <= 128) moe_sort_launch<2>(s, mi, P, E);
+  else moe_sort_launch<4>(s, mi, P, E);
 }
 
 // ---------------------------------------------------------------------------------------------- expert lists
@@ -429,9 +539,13 @@ __global__ __launch_bounds__(256) void k_moe_down_f32(const float* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------- launch
+// (span, expert) counters of the multi-workgroup sort: spans of 256 pairs x the expert count rounded up to 64
+static size_t moe_span_ints(int R, int k, int E) {
+  return (((size_t)R * k + 255) / 256) * (size_t)(((E + 63) / 64) * 64);
+}
 size_t moe_index_bytes(int R, int k, int E) {
   auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
-  return 3 * al((size_t)R * k * 4) + al((size_t)(E + 1) * 4);
+  return 3 * al((size_t)R * k * 4) + al((size_t)(E + 1) * 4) + al(moe_span_ints(R, k, E) * 4);
 }
 MoeIndex moe_index_carve(void* base, int R, int k, int E) {
   auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
@@ -440,7 +554,8 @@ MoeIndex moe_index_carve(void* base, int R, int k, int E) {
   mi.sel_e = (int32_t*)p; p += al((size_t)R * k * 4);
   mi.sel_p = (float*)p;   p += al((size_t)R * k * 4);
   mi.pair = (int32_t*)p;  p += al((size_t)R * k * 4);
-  mi.off = (int32_t*)p;
+  mi.off = (int32_t*)p;   p += al((size_t)(E + 1) * 4);
+  mi.span = (int32_t*)p;
   return mi;
 }
 
@@ -646,9 +761,7 @@ void launch_moe_ffn(hipStream_t s, const T* a, const T* router, const T* wgu, co
   // decode-sized batches of bf16 models: the grouped GEMMs find their lists themselves (mi.pair = null)
   const bool fly = sizeof(T) == 2 && R <= MOE_FLY_ROWS && P <= 65535;
   if (fly) mi.pair = nullptr;
-  else if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
-  else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
-  else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  else moe_sort(s, mi, P, E);
   if constexpr (sizeof(T) == 2) {
     if (!fly && moe_gemm_tile_applies(R, k, E, F, d) && moe_gemm_tile_applies(R, k, E, d, F)) {
       moe_gemm_tile_launch<true>(s, (const bf16_t*)a, (const bf16_t*)wgu, mi, (bf16_t*)act, nullptr, R, F, d, k, E);
@@ -879,9 +992,7 @@ void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, con
                      router, mi.sel_e, mi.sel_p, d, E, k);
   const bool fly = R <= MOE_FLY_ROWS && P <= 65535;
   if (fly) mi.pair = nullptr;
-  else if (E <= 64) hipLaunchKernelGGL(k_moe_bucket<1>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
-  else if (E <= 128) hipLaunchKernelGGL(k_moe_bucket<2>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
-  else hipLaunchKernelGGL(k_moe_bucket<4>, dim3(1), dim3(1024), 0, s, mi.sel_e, mi.off, mi.pair, P, E);
+  else moe_sort(s, mi, P, E);
   const long mean = ((long)P + E - 1) / E;
   if (mean <= 20) {
     moe_gemm_mx_launch<2, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);

@@ -232,7 +232,7 @@ void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const 
 
 // moe.hip : mixture-of-experts feed-forward.  Index arrays of one call (device): the selected experts and
 // their probabilities per row, the (row, slot) pairs sorted by expert and every expert's span in that list.
-struct MoeIndex { int32_t* sel_e; float* sel_p; int32_t* pair; int32_t* off; };
+struct MoeIndex { int32_t* sel_e; float* sel_p; int32_t* pair; int32_t* off; int32_t* span /* sort scratch */; };
 size_t moe_index_bytes(int R, int k, int E);
 MoeIndex moe_index_carve(void* base, int R, int k, int E);
 // a [R, d] normed rows; router [E, d]; wgu [E, 2F, d] (per expert: gate rows, then up rows); wdown [E, d, F]

@@ -41,8 +41,9 @@ CASES = [
     (B.PLT_BF16,  1,   2048, 1024, 64, 8, 0.02, 0.0),  # a single row
     (B.PLT_BF16,  70,  128,  64,  100, 4, 0.05, 0.0),  # more than 64 experts (two counters per lane in the sort)
     (B.PLT_F32,   33,  64,   32,  200, 3, 0.1,  0.0),  # more than 128 experts
-    (B.PLT_BF16,  2100, 128, 64,   8,  2, 0.05, 0.0),  # prefill-sized row count: several chunks per wave in the sort;
+    (B.PLT_BF16,  2100, 128, 64,   8,  2, 0.05, 0.0),  # prefill-sized row count: the sort spread over several workgroups;
                                                        # hundreds of rows per expert: the 256 x 256-tile grouped GEMM
+    (B.PLT_BF16,  1100, 128, 64,  100, 8, 0.05, 0.0),  # 8800 pairs, 100 experts: the multi-workgroup sort with two counters per lane
     (B.PLT_BF16,  1500, 256, 192,  12, 4, 0.05, 0.6),  # the tiled GEMM on crowded and empty experts, ragged row tiles,
                                                        # hidden width no multiple of its 128-column half tile
 ]
