@@ -11,7 +11,7 @@ CPU oracle timed on the host cores.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--only-main] [--no-cpu-baseline]
 
-Single-section runs for profiling (each prints its own JSON line): --attn-kernel-only, --prefill-only,
+Single-section runs for profiling (each prints its own JSON line): --attn-kernel-only, --prefill-only, --prefill-moe-only,
 --copy-reference; --kv-fp8 runs the main workload with e4m3 K/V caches (a labelled variant, not the
 headline).
 """
@@ -335,14 +335,19 @@ def bench_prefill(B, shape, blob, g, Bn=4, n=8192, L=3, w=64, reps=2):
         kv.prefill(prompt, want_logits=False)
     torch.cuda.synchronize()
     dt = (time.perf_counter() - t0) / reps
+    # feed-forward weights a row multiplies: the dense SwiGLU, or (mixture of experts) the router and top_k experts
+    ffn = 3 * shape.ffn_hidden * shape.d_model
+    if shape.n_experts:
+        ffn = shape.top_k * ffn + shape.n_experts * shape.d_model
     params = shape.n_layers * ((shape.n_heads + 2 * shape.n_kv_heads) * shape.head_dim * shape.d_model
-                               + shape.d_model * shape.n_heads * shape.head_dim + 3 * shape.ffn_hidden * shape.d_model)
+                               + shape.d_model * shape.n_heads * shape.head_dim + ffn)
     fl_gemm = 2.0 * params * Bn * n * L + 2.0 * shape.vocab * shape.d_model * Bn
     fl_attn = 4.0 * shape.head_dim * shape.n_heads * Bn * shape.n_layers * (L * n * n / 2 + (L - 1) * n * min(w, n))
     kv.close(); m.close(); del kv
     torch.cuda.empty_cache()
     tf = (fl_gemm + fl_attn) / dt / 1e12
-    return {"workload": f"CLP prefill, ~1.3B PLT, bf16, L={L}, window {w}, batch {Bn}, {n}-token prompts (configs[4])",
+    what = (f"{shape.top_k}-of-{shape.n_experts} mixture-of-experts shape" if shape.n_experts else "~1.3B PLT")
+    return {"workload": f"CLP prefill, {what}, bf16, L={L}, window {w}, batch {Bn}, {n}-token prompts" + ("" if shape.n_experts else " (configs[4])"),
             "ms": dt * 1e3, "tokens_per_s": Bn * n / dt, "flops_projections": fl_gemm, "flops_attention": fl_attn,
             "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
 
@@ -585,6 +590,7 @@ def main():
                     help="also time one GPU's share of the L=4, window 128, 8192-token configuration (batch 128 resident)")
     ap.add_argument("--attn-kernel-only", action="store_true", help="only the kernel-only fused attention configuration (bf16 and e4m3 caches)")
     ap.add_argument("--prefill-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3")
+    ap.add_argument("--prefill-moe-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3 on the 8-of-64 mixture-of-experts shape")
     ap.add_argument("--copy-reference", action="store_true", help="only the plain copy kernel (reference for HBM traffic counters)")
     ap.add_argument("--sweep-moe", action="store_true", help="only the mixture-of-experts serving sweep (batch 4..64, context 5000, 256 tokens, 5 runs)")
     ap.add_argument("--moe-only", action="store_true", help="only the mixture-of-experts shape (8 of 64 experts) at batch 64")
@@ -620,6 +626,12 @@ def main():
         return
     if args.lowbit_gemm_only:
         print(json.dumps({"lowbit_gemm": bench_lowbit_gemm(B, args.batch * args.loops)}), flush=True)
+        return
+    if args.prefill_moe_only:
+        mshape = synth.PLT_MOE_1B7B
+        cfg0 = B.make_config(mshape, dtype=B.PLT_BF16)
+        g0 = torch.Generator(device="cuda"); g0.manual_seed(SEED + 1)
+        print(json.dumps({"prefill_moe": bench_prefill(B, mshape, fill_weights_on_device(B, cfg0, SEED), g0)}), flush=True)
         return
     if args.prefill_only:
         cfg0 = B.make_config(shape, dtype=B.PLT_BF16)

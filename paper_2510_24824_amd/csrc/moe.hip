@@ -18,6 +18,8 @@
 //                     order (deterministic, no atomics)
 // Experts nobody selected cost no weight traffic (their workgroups leave at once).  Batches of up to 1024 rows
 // (decode steps) skip k_moe_bucket: the grouped GEMMs derive their expert's list from sel_e themselves.
+// Prefill-sized batches (hundreds of rows per expert) sort over many workgroups (k_moe_span_*) and run both
+// GEMMs as k_moe_gemm_tile (256 x 256 tiles, matrix-core-bound).
 #include "plt_internal.h"
 
 namespace plt {
