@@ -22,6 +22,7 @@
 // [4 bytes] (byte c = chunk 4*group + c).  Activation codes: row-major [M][K].  Activation scales:
 // [M][ceil(K/512)][g][c]: byte (g, c) of group q is the scale of k block 16 q + 4 c + g.
 #include "plt_internal.h"
+#include <type_traits>
 
 namespace plt {
 
@@ -254,7 +255,141 @@ __global__ __launch_bounds__(256) void k_gemm_mx(const uint8_t* __restrict__ a, 
   }
 }
 
-int gemm_mx_splits(int K) { return (K + MX_KR - 1) / MX_KR; }
+// ---------------------------------------------------------------------------------------------- prefill-sized row counts
+// The same product for thousands of rows (matrix-core-bound): workgroup tile 256 rows x 256 columns, whole K (no
+// split-K slabs), K in steps of one 128-wide chunk through two LDS stages filled HBM -> LDS directly; 8 waves as
+// 2 x 4, each 128 rows x 64 columns = 8 x 4 tiles of the block-scaled MFMA.  A stage holds the activation tile
+// (256 rows x 128 code bytes; the 16-byte pieces of a row XOR-swizzled with the row number so that the fragment
+// reads of 16 rows touch every bank once) and 16 weight strips x 1 KiB exactly as they lie in memory (that IS the
+// A-operand layout: lane l reads bytes 16 l ..).  The block scales go from memory straight into registers, one
+// dword per lane and 4 chunks (512 k) for either operand, fetched one group of 4 chunks ahead.
+__global__ __launch_bounds__(512) void k_gemm_mx_tile(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
+                                                      const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
+                                                      float* __restrict__ c, int M, int N, int K) {
+  constexpr int BM = 256, BN = 256, THREADS = 512, WN = 4, MI = 8, NT = 4;
+  constexpr int A_BYTES = BM * 128, W_BYTES = (BN / 16) * 1024, STAGE_BYTES = A_BYTES + W_BYTES;
+  extern __shared__ __attribute__((aligned(16))) char mxt_lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int wm = wv / WN, wn = wv % WN;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, n_strips = N >> 4, asb = mx_ascale_row_bytes(K);
+  // this thread's pieces of a stage: 4 of the activation tile (slot s = i*THREADS + tid -> row s/8, piece (s%8) ^ (row%8)),
+  // 2 of the weight strips (slot s -> strip s/64 of the tile, byte 16 (s%64) of its KiB)
+  const uint8_t* pa[4]; const uint8_t* pw[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int sl = i * THREADS + tid, row = sl >> 3, pc = (sl & 7) ^ (row & 7);
+    int gm = m0 + row; if (gm >= M) gm = M - 1;                 // rows beyond M: computed, never stored
+    pa[i] = a + (size_t)gm * K + pc * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int sl = i * THREADS + tid;
+    int strip = (n0 >> 4) + (sl >> 6); if (strip >= n_strips) strip = n_strips - 1;
+    pw[i] = w + (size_t)strip * n_chunks * 1024 + (sl & 63) * 16;
+  }
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mxt_lds;
+  auto dma16 = [](const uint8_t* src, unsigned lds_wave_base) {  // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
+    unsigned keep_m0;                                            // m0 is left as it was found
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
+  };
+  auto issue = [&](int ch) {                                     // chunk ch -> stage ch & 1
+    const unsigned stage = lds0 + (unsigned)(ch & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      dma16(pa[i] + (size_t)ch * 128, stage + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      dma16(pw[i] + (size_t)ch * 1024, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+  };
+  // scale dwords of chunk group q: weights: strip j of this wave, this lane; activations: row tile i, this lane's row, block g
+  const uint8_t* wsp[NT]; const uint8_t* asp[MI];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) {
+    int strip = (n0 >> 4) + wn * NT + j; if (strip >= n_strips) strip = n_strips - 1;
+    wsp[j] = w_sc + ((size_t)strip * n_cgrp * 64 + lane) * 4;
+  }
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    int gm = m0 + wm * 128 + i * 16 + m16; if (gm >= M) gm = M - 1;
+    asp[i] = a_sc + (size_t)gm * asb + g * 4;
+  }
+  unsigned wsc[NT], asc[MI], wsc_n[NT], asc_n[MI];
+  auto load_scales = [&](int q, unsigned (&ws)[NT], unsigned (&as)[MI]) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) ws[j] = *reinterpret_cast<const unsigned*>(wsp[j] + (size_t)q * 256);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) as[i] = *reinterpret_cast<const unsigned*>(asp[i] + q * 16);
+  };
+  f32x4 acc[MI][NT];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int sw0 = (g ^ (m16 & 7)) * 16;                  // byte offset of the lane's first piece inside its row
+  // one chunk: kk = its place in the group of 4 (selects the scale byte), compile-time
+  auto step = [&](int ch, auto kk_tag) {
+    constexpr int kk = decltype(kk_tag)::value;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of chunk ch has landed (and the next group's scales)
+    __syncthreads();                                   // ... and everyone's; chunk ch - 1 is no longer read
+    if (ch + 1 < n_chunks) issue(ch + 1);
+    const char* As = mxt_lds + (ch & 1) * STAGE_BYTES;
+    const char* Ws = As + A_BYTES;
+    uint4 fw[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) fw[j] = *reinterpret_cast<const uint4*>(Ws + (wn * NT + j) * 1024 + lane * 16);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const char* ap = As + (wm * 128 + i * 16 + m16) * 128;
+      const uint4 lo = *reinterpret_cast<const uint4*>(ap + sw0), hi = *reinterpret_cast<const uint4*>(ap + (sw0 ^ 64));
+      const i32x8 bv = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const i32x8 av = {(int)fw[j].x, (int)fw[j].y, (int)fw[j].z, (int)fw[j].w, 0, 0, 0, 0};
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[i][j], 4, 0, kk, (int)wsc[j], kk, (int)asc[i]);
+      }
+    }
+  };
+  load_scales(0, wsc, asc);
+  issue(0);
+  for (int q = 0; q < n_cgrp; ++q) {
+    const int ch0 = q * 4;
+    step(ch0, std::integral_constant<int, 0>{});
+    if (q + 1 < n_cgrp) load_scales(q + 1, wsc_n, asc_n);     // waited for at the top of the next step, a chunk of MFMAs later
+    if (ch0 + 1 < n_chunks) step(ch0 + 1, std::integral_constant<int, 1>{});
+    if (ch0 + 2 < n_chunks) step(ch0 + 2, std::integral_constant<int, 2>{});
+    if (ch0 + 3 < n_chunks) step(ch0 + 3, std::integral_constant<int, 3>{});
+    if (q + 1 < n_cgrp) {
+#pragma unroll
+      for (int j = 0; j < NT; ++j) wsc[j] = wsc_n[j];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) asc[i] = asc_n[i];
+    }
+  }
+  // acc[i][j][x]: row m0 + wm*128 + i*16 + m16, column n0 + (wn*NT + j)*16 + 4 g + x
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int gm = m0 + wm * 128 + i * 16 + m16;
+    if (gm >= M) continue;
+    float* o = c + (size_t)gm * N;
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int gn = n0 + (wn * NT + j) * 16 + 4 * g;
+      if (gn < N) *reinterpret_cast<f32x4*>(o + gn) = acc[i][j];          // N % 16 == 0: whole groups of 4 columns
+    }
+  }
+}
+
+// rows from which the tiled kernel takes over (its 256 x 256 tiles must fill the chip)
+static bool gemm_mx_tile_applies(int M, int N, int K) {
+  const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+  return M >= 512 && tiles >= 128 && (K % 128) == 0 && (N % 16) == 0;
+}
+
+// number of [M, N] float slabs the product leaves: one per K range of the streaming kernel, a single one from the
+// tiled kernel
+int gemm_mx_splits(int M, int N, int K) { return gemm_mx_tile_applies(M, N, K) ? 1 : (K + MX_KR - 1) / MX_KR; }
 
 template <int MT, int NB>
 static void mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
@@ -265,7 +400,7 @@ static void mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, cons
     (void)hipFuncSetAttribute((const void*)k_gemm_mx<MT, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  const int S = gemm_mx_splits(K), rbs = (M + MT * 16 - 1) / (MT * 16);
+  const int S = (K + MX_KR - 1) / MX_KR, rbs = (M + MT * 16 - 1) / (MT * 16);
   const int n_grp = ((N >> 4) + NB - 1) / NB;
   const int per_cu = MT == 8 ? 1 : 2;                         // workgroups that fit a compute unit (LDS)
   int n_groups = 256 * per_cu / (S * (rbs < 4 ? rbs : 4)); if (n_groups < 1) n_groups = 1;
@@ -273,11 +408,21 @@ static void mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, cons
   hipLaunchKernelGGL((k_gemm_mx<MT, NB>), dim3(n_groups, rbs, S), dim3(256), lds, s, a, a_sc, w, w_sc, c, M, N, K, n_groups);
 }
 
-// c: gemm_mx_splits(K) slabs of [M, N] floats.  N % 16 == 0, K % 128 == 0.  Strips per wave task (NB) grow
+// c: gemm_mx_splits(M, N, K) slabs of [M, N] floats.  N % 16 == 0, K % 128 == 0.  Strips per wave task (NB) grow
 // until the waves of one (K range, row block) cover the strips in one pass if possible.
 void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
                     int M, int N, int K) {
-  const int n_strips = N >> 4, S = gemm_mx_splits(K);
+  if (gemm_mx_tile_applies(M, N, K)) {
+    constexpr int LDS_BYTES = 2 * (256 * 128 + 16 * 1024);
+    static bool attr_done = false;
+    if (!attr_done) {
+      (void)hipFuncSetAttribute((const void*)k_gemm_mx_tile, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+      attr_done = true;
+    }
+    hipLaunchKernelGGL(k_gemm_mx_tile, dim3((N + 255) / 256, (M + 255) / 256), dim3(512), LDS_BYTES, s, a, a_sc, w, w_sc, c, M, N, K);
+    return;
+  }
+  const int n_strips = N >> 4, S = (K + MX_KR - 1) / MX_KR;
   const bool small = M <= 64;
   int slots = 256 * (small ? 2 : 1) / S * 4; if (slots < 4) slots = 4;
   const int nb = (n_strips + slots - 1) / slots;

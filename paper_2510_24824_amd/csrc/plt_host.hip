@@ -300,7 +300,7 @@ static int mx_max_k(const plt_config& c) {
   return k;
 }
 static size_t gemm_out_need(const plt_config& c, int M, int N, int K, bool head = false) {
-  if (c.w_dtype == PLT_MXFP4 && !head) return (size_t)gemm_mx_splits(K) * M * N;
+  if (c.w_dtype == PLT_MXFP4 && !head) return (size_t)gemm_mx_splits(M, N, K) * M * N;
   const int S = c.dtype == PLT_BF16 ? gemm_bf16_splits_any(M, N, K) : 1;
   return (size_t)S * M * N;
 }
@@ -438,7 +438,7 @@ static void norm_to_a(plt_model* m, const Work& wk, const float* partials, int S
 static int run_gemm_mx(plt_model* m, const Work& wk, const void* w, const uint8_t* w_sc, int M, int N, int K, bool decode) {
   ProfScope prof(m, PLT_PROF_GEMM, decode);
   launch_gemm_mx(m->stream, wk.a_codes, wk.a_scales, (const uint8_t*)w, w_sc, wk.gout, M, N, K);
-  return gemm_mx_splits(K);
+  return gemm_mx_splits(M, N, K);
 }
 
 template <typename T>
@@ -963,7 +963,7 @@ extern "C" int plt_mx_quantize_act(int32_t dtype, int32_t M, int32_t K, const vo
 }
 extern "C" size_t plt_gemm_mx_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || !mx_shape_ok(N, K)) { fail(PLT_EINVAL, "plt_gemm_mx_scratch_bytes: bad shape"); return 0; }
-  return align256((size_t)gemm_mx_splits(K) * M * N * 4);
+  return align256((size_t)gemm_mx_splits(M, N, K) * M * N * 4);
 }
 extern "C" int plt_gemm_mx(int32_t M, int32_t N, int32_t K, const void* a_codes, const void* a_scales, const void* w_codes,
                            const void* w_scales, float* c, void* scratch, size_t scratch_bytes, void* hip_stream) {
@@ -972,7 +972,7 @@ extern "C" int plt_gemm_mx(int32_t M, int32_t N, int32_t K, const void* a_codes,
   if ((((uintptr_t)a_codes) | ((uintptr_t)a_scales) | ((uintptr_t)w_codes) | ((uintptr_t)w_scales) | ((uintptr_t)c)) & 15)
     return fail(PLT_EINVAL, "plt_gemm_mx: pointers must be 16-byte aligned");
   hipStream_t s = (hipStream_t)hip_stream;
-  const int S = gemm_mx_splits(K);
+  const int S = gemm_mx_splits(M, N, K);
   if (S == 1) {
     launch_gemm_mx(s, (const uint8_t*)a_codes, (const uint8_t*)a_scales, (const uint8_t*)w_codes, (const uint8_t*)w_scales, c, M, N, K);
   } else {

@@ -226,7 +226,7 @@ constexpr int MX_KR = 1024, MX_LDA = MX_KR + 16, MX_SB = MX_KR / 32;
 void launch_mx_quant_w(hipStream_t s, const bf16_t* w, uint8_t* codes, uint8_t* scales, int N, int K);
 template <typename T>
 void launch_mx_quant_a(hipStream_t s, const T* a, uint8_t* codes, uint8_t* scales, int M, int K);
-int gemm_mx_splits(int K);
+int gemm_mx_splits(int M, int N, int K);
 void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
                     int M, int N, int K);
 

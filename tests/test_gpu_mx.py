@@ -96,7 +96,9 @@ GEMM_CASES = [(128, 6144, 2048),   # QKV projection of the 1.3B model at 64 sequ
               (256, 11264, 2048),  # gate/up at L = 4: two row blocks, four strips per wave task
               (37, 80, 384),       # nothing a multiple of a tile
               (130, 2048, 1024),   # second row block with two rows
-              (1, 16, 128)]
+              (1, 16, 128),
+              (2048, 4096, 640),   # prefill-sized: the 256 x 256-tile kernel, whole K (5 chunks: a partial scale group)
+              (1100, 6640, 256)]   # the tiled kernel with ragged last row and column tiles
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
