@@ -21,6 +21,7 @@
 // Prefill-sized batches (hundreds of rows per expert) sort over many workgroups (k_moe_span_*) and run both
 // GEMMs as k_moe_gemm_tile (256 x 256 tiles, matrix-core-bound).
 #include "plt_internal.h"
+#include <type_traits>
 
 namespace plt {
 
@@ -986,6 +987,207 @@ static void moe_gemm_mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a
                      mi.off, mi.pair, mi.sel_e, mi.sel_p, act, act_sc, y, R, N, K, k);
 }
 
+// Prefill-sized batches on low-bit operands: the grouping of k_moe_gemm_tile (row-tile slots over the experts' sorted
+// lists, rows gathered through the list) around the tile algebra of the dense low-bit prefill kernel (256 list rows
+// x 256 weight rows, one 128-wide chunk per LDS stage, weight strips as they lie in memory, scale dwords straight
+// into registers).  GU: 8 gate strips and the matching 8 up strips per tile; a wave owns 32 hidden columns = one
+// block, which it quantises to e4m3 in its epilogue.  DOWN: output scaled by p_e and scattered to the k slabs.
+template <bool GU>
+__global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
+                                                          const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
+                                                          const int32_t* __restrict__ off, const int32_t* __restrict__ pair,
+                                                          const float* __restrict__ sel_p, uint8_t* __restrict__ act_out,
+                                                          uint8_t* __restrict__ act_sc_out, float* __restrict__ y_out,
+                                                          int R, int N, int K, int topk, int E) {
+  constexpr int BM = 256, THREADS = 512, WN = 4, MI = 8, NT = 4;
+  constexpr int A_BYTES = BM * 128, W_BYTES = 16 * 1024, STAGE_BYTES = A_BYTES + W_BYTES;
+  extern __shared__ __attribute__((aligned(16))) char mxm_lds[];
+  __shared__ int s_where[3];
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  const int wm = wv / WN, wn = wv % WN;
+  if (wv == 0) {
+    const int slot = blockIdx.y;
+    int base = 0, found = -1;
+    for (int e0 = 0; e0 < E && found < 0; e0 += 64) {
+      const int e = e0 + lane;
+      const int n_e = e < E ? off[e + 1] - off[e] : 0;
+      const int nt = (n_e + BM - 1) / BM;
+      int incl = nt;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) { const int v = __shfl_up(incl, o, 64); if (lane >= o) incl += v; }
+      const bool mine = slot >= base + incl - nt && slot < base + incl;
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(mine);
+      if (bal) {
+        found = e0 + __builtin_ctzll(bal);
+        if (mine) { s_where[0] = e; s_where[1] = off[e] + (slot - (base + incl - nt)) * BM; s_where[2] = off[e + 1]; }
+      }
+      base += __shfl(incl, 63, 64);
+    }
+    if (found < 0 && lane == 0) s_where[0] = -1;
+  }
+  __syncthreads();
+  const int e = s_where[0];
+  if (e < 0) return;
+  const int p0 = s_where[1], p_end = s_where[2];
+  const int NR = GU ? 2 * N : N, out_strips = N >> 4;
+  const int n0 = blockIdx.x * (GU ? 128 : 256);
+  const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, asb = mx_ascale_row_bytes(K);
+  const uint8_t* we = w + (size_t)e * ((size_t)NR * K / 2);
+  const uint8_t* wse = w_sc + (size_t)e * mx_wscale_bytes(NR, K);
+  // strip (within the expert's matrix) behind slot t of the tile's 16 weight strips
+  auto strip_of = [&](int t) -> int {
+    int st = (n0 >> 4) + (GU ? (t & 7) : t);
+    if (st >= out_strips) st = out_strips - 1;                 // beyond N: a valid strip, results not stored
+    return (GU && t >= 8) ? out_strips + st : st;
+  };
+  auto src_row = [&](int pos) -> size_t {
+    if (pos >= p_end) pos = p_end - 1;
+    return GU ? (size_t)(pair[pos] / topk) : (size_t)pos;
+  };
+  const uint8_t* pa[4]; const uint8_t* pw[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int sl = i * THREADS + tid, row = sl >> 3, pc = (sl & 7) ^ (row & 7);
+    pa[i] = a + src_row(p0 + row) * K + pc * 16;
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int sl = i * THREADS + tid;
+    pw[i] = we + (size_t)strip_of(sl >> 6) * n_chunks * 1024 + (sl & 63) * 16;
+  }
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mxm_lds;
+  auto dma16 = [](const uint8_t* src, unsigned lds_wave_base) {
+    unsigned keep_m0;                                            // m0 is left as it was found
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
+  };
+  auto issue = [&](int ch) {
+    const unsigned stage = lds0 + (unsigned)(ch & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      dma16(pa[i] + (size_t)ch * 128, stage + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      dma16(pw[i] + (size_t)ch * 1024, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+  };
+  // the wave's four weight tiles: GU: slots 2 wn, 2 wn + 1 (gate) and 8 + 2 wn, 9 + 2 wn (up); DOWN: slots 4 wn ..
+  int wslot[NT];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) wslot[j] = GU ? (j < 2 ? wn * 2 + j : 8 + wn * 2 + (j - 2)) : wn * NT + j;
+  const uint8_t* wsp[NT]; const uint8_t* asp[MI];
+#pragma unroll
+  for (int j = 0; j < NT; ++j) wsp[j] = wse + ((size_t)strip_of(wslot[j]) * n_cgrp * 64 + lane) * 4;
+#pragma unroll
+  for (int i = 0; i < MI; ++i) asp[i] = a_sc + src_row(p0 + wm * 128 + i * 16 + m16) * asb + g * 4;
+  unsigned wsc[NT], asc[MI], wsc_n[NT], asc_n[MI];
+  auto load_scales = [&](int q, unsigned (&ws)[NT], unsigned (&as)[MI]) {
+#pragma unroll
+    for (int j = 0; j < NT; ++j) ws[j] = *reinterpret_cast<const unsigned*>(wsp[j] + (size_t)q * 256);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) as[i] = *reinterpret_cast<const unsigned*>(asp[i] + q * 16);
+  };
+  f32x4 acc[MI][NT];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int sw0 = (g ^ (m16 & 7)) * 16;
+  auto step = [&](int ch, auto kk_tag) {
+    constexpr int kk = decltype(kk_tag)::value;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (ch + 1 < n_chunks) issue(ch + 1);
+    const char* As = mxm_lds + (ch & 1) * STAGE_BYTES;
+    const char* Ws = As + A_BYTES;
+    uint4 fw[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) fw[j] = *reinterpret_cast<const uint4*>(Ws + wslot[j] * 1024 + lane * 16);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const char* ap = As + (wm * 128 + i * 16 + m16) * 128;
+      const uint4 lo = *reinterpret_cast<const uint4*>(ap + sw0), hi = *reinterpret_cast<const uint4*>(ap + (sw0 ^ 64));
+      const i32x8 bv = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const i32x8 av = {(int)fw[j].x, (int)fw[j].y, (int)fw[j].z, (int)fw[j].w, 0, 0, 0, 0};
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[i][j], 4, 0, kk, (int)wsc[j], kk, (int)asc[i]);
+      }
+    }
+  };
+  load_scales(0, wsc, asc);
+  issue(0);
+  for (int q = 0; q < n_cgrp; ++q) {
+    const int ch0 = q * 4;
+    step(ch0, std::integral_constant<int, 0>{});
+    if (q + 1 < n_cgrp) load_scales(q + 1, wsc_n, asc_n);
+    if (ch0 + 1 < n_chunks) step(ch0 + 1, std::integral_constant<int, 1>{});
+    if (ch0 + 2 < n_chunks) step(ch0 + 2, std::integral_constant<int, 2>{});
+    if (ch0 + 3 < n_chunks) step(ch0 + 3, std::integral_constant<int, 3>{});
+    if (q + 1 < n_cgrp) {
+#pragma unroll
+      for (int j = 0; j < NT; ++j) wsc[j] = wsc_n[j];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) asc[i] = asc_n[i];
+    }
+  }
+  const int nbp = mx_ascale_row_bytes(N);
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    const int pos = p0 + wm * 128 + i * 16 + m16;
+    if (GU) {
+      // hidden values of list row pos, columns n0 + 32 wn + 16 j + 4 g + x (j = 0, 1): one 32-wide block over the 4 lane groups
+      float h[2][4];
+      float amax = 0.f;
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const float gt = acc[i][j][x];
+          h[j][x] = gt / (1.0f + expf(-gt)) * acc[i][2 + j][x];
+          amax = fmaxf(amax, fabsf(h[j][x]));
+        }
+      amax = fmaxf(amax, __shfl_xor(amax, 16)); amax = fmaxf(amax, __shfl_xor(amax, 32));
+      const int ex = mx_block_exponent(amax, 8);
+      const int col = n0 + wn * 32;
+      if (pos < p_end && col < N) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          *reinterpret_cast<unsigned*>(act_out + (size_t)pos * N + col + j * 16 + 4 * g) = mx_pack4_e4m3(h[j][0], h[j][1], h[j][2], h[j][3], ex);
+        if (g == 0) act_sc_out[(size_t)pos * nbp + mx_ascale_index(col >> 5)] = (uint8_t)(ex + 127);
+      }
+    } else {
+      if (pos >= p_end) continue;
+      const int pr = pair[pos];
+      const int row = pr / topk, slot = pr - row * topk;
+      const float p = sel_p[pr];
+      float* o = y_out + ((size_t)slot * R + row) * N;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int gn = n0 + (wn * NT + j) * 16 + 4 * g;
+        if (gn >= N) continue;
+        f32x4 v = acc[i][j];
+        v[0] *= p; v[1] *= p; v[2] *= p; v[3] *= p;
+        *reinterpret_cast<f32x4*>(o + gn) = v;
+      }
+    }
+  }
+}
+template <bool GU>
+static void moe_gemm_mx_tile_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc,
+                                    const MoeIndex& mi, uint8_t* act, uint8_t* act_sc, float* y, int R, int N, int K, int k, int E) {
+  constexpr int LDS_BYTES = 2 * (256 * 128 + 16 * 1024);
+  static bool attr_done = false;
+  if (!attr_done) {
+    (void)hipFuncSetAttribute((const void*)k_moe_gemm_mx_tile<GU>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    attr_done = true;
+  }
+  const int ncols = GU ? 128 : 256;
+  const long P = (long)R * k;
+  dim3 grid((N + ncols - 1) / ncols, (unsigned)(P / 256 + E));
+  hipLaunchKernelGGL(k_moe_gemm_mx_tile<GU>, grid, dim3(512), LDS_BYTES, s, a, a_sc, w, w_sc, mi.off, mi.pair, mi.sel_p, act, act_sc, y,
+                     R, N, K, k, E);
+}
+
 void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const bf16_t* router, const uint8_t* wgu,
                        const uint8_t* wgu_sc, const uint8_t* wdown, const uint8_t* wdown_sc, uint8_t* act_codes,
                        uint8_t* act_scales, float* y, MoeIndex mi, int R, int d, int F, int E, int k) {
@@ -996,7 +1198,11 @@ void launch_moe_ffn_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, con
   if (fly) mi.pair = nullptr;
   else moe_sort(s, mi, P, E);
   const long mean = ((long)P + E - 1) / E;
-  if (mean <= 20) {
+  if (!fly && mean >= 192 && (d % 128) == 0 && (F % 128) == 0) {
+    // prefill-sized: matrix-core-bound tiles (F % 128: whole 32-wide hidden blocks per wave, whole chunks for the down product)
+    moe_gemm_mx_tile_launch<true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
+    moe_gemm_mx_tile_launch<false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
+  } else if (mean <= 20) {
     moe_gemm_mx_launch<2, true>(s, a, a_sc, wgu, wgu_sc, mi, act_codes, act_scales, nullptr, R, F, d, k, E);
     moe_gemm_mx_launch<2, false>(s, act_codes, act_scales, wdown, wdown_sc, mi, nullptr, nullptr, y, R, d, F, k, E);
   } else if (mean <= 48) {
