@@ -263,6 +263,40 @@ def test_moe_lowbit_full_width_single_position():
     kv.close(); model.close()
 
 
+def test_lowbit_prefill_sized_gate_up_projection_single_position():
+    """2048 rows through a layer with a 2048-wide SwiGLU: the gate/up projection (2048 x 4096 x 256) is large enough
+    for the 256 x 256-tile low-bit kernel inside the model (whole K, one float slab; the other projections of this
+    shape stay on the streaming kernel), followed by the SwiGLU + quantiser kernel.  2048 single-position L = 1
+    sequences, compared as in the full-width MoE test: most sequences to the bf16 level of the head, the worst
+    within 5 % of the largest logit."""
+    from tests.helpers import oshape
+    from tests.test_gpu_model import dev_tokens
+    shape = synth.ModelShape(n_layers=1, d_model=256, n_heads=2, n_kv_heads=2, head_dim=128, ffn_hidden=2048,
+                             vocab=300, n_loops=1, window=8)
+    weights = lively_weights(shape, 31, bf16=True, std=0.05)
+    n_seq = 2048
+    prompts = synth.token_ids((n_seq, 1), shape.vocab, 32)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, w_dtype=B.PLT_MXFP4)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    kv = B.KV(model, n_seq, 4)
+    _, lg = kv.prefill(dev_tokens(prompts))
+    got = lg.cpu().numpy()
+    orc = O.PLTOracle(oshape(shape), weights, kv_bf16=True, w_mx=True)
+    refs = {}
+    for b in range(n_seq):                               # 300 distinct tokens: one oracle run per token
+        t = int(prompts[b, 0])
+        if t not in refs:
+            refs[t] = orc.clp_prefill([t], 4)[1]
+    ref = np.stack([refs[int(prompts[b, 0])] for b in range(n_seq)])
+    top = float(np.max(np.abs(ref)))
+    worst = float(np.max(np.abs(got - ref)))
+    rel_rms = np.sqrt(np.mean((got - ref) ** 2, axis=1) / np.mean(ref ** 2, axis=1))
+    print(f"{len(refs)} distinct tokens; worst abs err {worst:.3e}; max |logit| {top:.3f}; relative rms error median "
+          f"{np.median(rel_rms):.3e} max {np.max(rel_rms):.3e}")
+    assert np.median(rel_rms) <= 1.5e-2 and worst <= 0.05 * top
+    kv.close(); model.close()
+
+
 @pytest.mark.parametrize("heads,D,kv_dtype", [((4, 2), 128, 0), ((8, 8), 64, B.PLT_FP8_E4M3)])
 def test_lowbit_model_with_attention_output_quantised_in_the_kernel(heads, D, kv_dtype):
     """n_heads * head_dim = 512: in decode steps the attention kernel itself writes its output as e4m3 blocks
