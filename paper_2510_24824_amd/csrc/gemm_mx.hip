@@ -269,24 +269,26 @@ __global__ __launch_bounds__(512) void k_gemm_mx_tile(const uint8_t* __restrict_
   constexpr int BM = 256, BN = 256, THREADS = 512, WN = 4, MI = 8, NT = 4;
   constexpr int A_BYTES = BM * 128, W_BYTES = (BN / 16) * 1024, STAGE_BYTES = A_BYTES + W_BYTES;
   extern __shared__ __attribute__((aligned(16))) char mxt_lds[];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  // The 128 accumulators and the 8-register operand tuples leave little room: what is the same for a whole wave
+  // is kept in scalar registers (hence the readfirstlane), and per-lane addresses as 32-bit offsets from them.
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), m16 = lane & 15, g = lane >> 4;
   const int wm = wv / WN, wn = wv % WN;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, n_strips = N >> 4, asb = mx_ascale_row_bytes(K);
   // this thread's pieces of a stage: 4 of the activation tile (slot s = i*THREADS + tid -> row s/8, piece (s%8) ^ (row%8)),
   // 2 of the weight strips (slot s -> strip s/64 of the tile, byte 16 (s%64) of its KiB)
-  const uint8_t* pa[4]; const uint8_t* pw[2];
+  unsigned pa[4];                       // byte offsets into a (M * K < 2^32)
+  const uint8_t* pw[2];                 // the two strips are the same for the whole wave: scalar base + 16 lane
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int sl = i * THREADS + tid, row = sl >> 3, pc = (sl & 7) ^ (row & 7);
     int gm = m0 + row; if (gm >= M) gm = M - 1;                 // rows beyond M: computed, never stored
-    pa[i] = a + (size_t)gm * K + pc * 16;
+    pa[i] = (unsigned)gm * (unsigned)K + pc * 16;
   }
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    const int sl = i * THREADS + tid;
-    int strip = (n0 >> 4) + (sl >> 6); if (strip >= n_strips) strip = n_strips - 1;
-    pw[i] = w + (size_t)strip * n_chunks * 1024 + (sl & 63) * 16;
+    int strip = (n0 >> 4) + i * 8 + wv; if (strip >= n_strips) strip = n_strips - 1;      // slot (i*512 + tid) / 64 = 8 i + wave
+    pw[i] = w + (size_t)strip * n_chunks * 1024;
   }
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mxt_lds;
   auto dma16 = [](const uint8_t* src, unsigned lds_wave_base) {  // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
@@ -298,29 +300,30 @@ __global__ __launch_bounds__(512) void k_gemm_mx_tile(const uint8_t* __restrict_
     const unsigned stage = lds0 + (unsigned)(ch & 1) * STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      dma16(pa[i] + (size_t)ch * 128, stage + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+      dma16(a + ((size_t)pa[i] + (size_t)ch * 128), stage + (unsigned)(i * THREADS + wv * 64) * 16);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-      dma16(pw[i] + (size_t)ch * 1024, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+      dma16(pw[i] + (size_t)ch * 1024 + lane * 16, stage + A_BYTES + (unsigned)(i * THREADS + wv * 64) * 16);
   };
   // scale dwords of chunk group q: weights: strip j of this wave, this lane; activations: row tile i, this lane's row, block g
-  const uint8_t* wsp[NT]; const uint8_t* asp[MI];
+  const uint8_t* wsp[NT];               // per wave (scalar); + 4 lane
+  unsigned asp[MI];                     // byte offsets into a_sc
 #pragma unroll
   for (int j = 0; j < NT; ++j) {
     int strip = (n0 >> 4) + wn * NT + j; if (strip >= n_strips) strip = n_strips - 1;
-    wsp[j] = w_sc + ((size_t)strip * n_cgrp * 64 + lane) * 4;
+    wsp[j] = w_sc + (size_t)strip * n_cgrp * 256;
   }
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     int gm = m0 + wm * 128 + i * 16 + m16; if (gm >= M) gm = M - 1;
-    asp[i] = a_sc + (size_t)gm * asb + g * 4;
+    asp[i] = (unsigned)gm * (unsigned)asb + g * 4;
   }
   unsigned wsc[NT], asc[MI], wsc_n[NT], asc_n[MI];
   auto load_scales = [&](int q, unsigned (&ws)[NT], unsigned (&as)[MI]) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j) ws[j] = *reinterpret_cast<const unsigned*>(wsp[j] + (size_t)q * 256);
+    for (int j = 0; j < NT; ++j) ws[j] = *reinterpret_cast<const unsigned*>(wsp[j] + (size_t)q * 256 + lane * 4);
 #pragma unroll
-    for (int i = 0; i < MI; ++i) as[i] = *reinterpret_cast<const unsigned*>(asp[i] + q * 16);
+    for (int i = 0; i < MI; ++i) as[i] = *reinterpret_cast<const unsigned*>(a_sc + ((size_t)asp[i] + q * 16));
   };
   f32x4 acc[MI][NT];
 #pragma unroll
