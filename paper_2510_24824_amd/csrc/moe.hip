@@ -1003,7 +1003,9 @@ __global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restr
   constexpr int A_BYTES = BM * 128, W_BYTES = 16 * 1024, STAGE_BYTES = A_BYTES + W_BYTES;
   extern __shared__ __attribute__((aligned(16))) char mxm_lds[];
   __shared__ int s_where[3];
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  // (wave-uniform values in scalar registers, per-lane addresses as 32-bit offsets: the accumulators and operand
+  // tuples leave few vector registers)
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), m16 = lane & 15, g = lane >> 4;
   const int wm = wv / WN, wn = wv % WN;
   if (wv == 0) {
     const int slot = blockIdx.y;
@@ -1026,9 +1028,9 @@ __global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restr
     if (found < 0 && lane == 0) s_where[0] = -1;
   }
   __syncthreads();
-  const int e = s_where[0];
+  const int e = __builtin_amdgcn_readfirstlane(s_where[0]);
   if (e < 0) return;
-  const int p0 = s_where[1], p_end = s_where[2];
+  const int p0 = __builtin_amdgcn_readfirstlane(s_where[1]), p_end = __builtin_amdgcn_readfirstlane(s_where[2]);
   const int NR = GU ? 2 * N : N, out_strips = N >> 4;
   const int n0 = blockIdx.x * (GU ? 128 : 256);
   const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, asb = mx_ascale_row_bytes(K);
@@ -1044,17 +1046,15 @@ __global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restr
     if (pos >= p_end) pos = p_end - 1;
     return GU ? (size_t)(pair[pos] / topk) : (size_t)pos;
   };
-  const uint8_t* pa[4]; const uint8_t* pw[2];
+  unsigned pa[4];                       // byte offsets into a (rows x K < 2^32)
+  const uint8_t* pw[2];                 // per wave: scalar base, + 16 lane
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int sl = i * THREADS + tid, row = sl >> 3, pc = (sl & 7) ^ (row & 7);
-    pa[i] = a + src_row(p0 + row) * K + pc * 16;
+    pa[i] = (unsigned)src_row(p0 + row) * (unsigned)K + pc * 16;
   }
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int sl = i * THREADS + tid;
-    pw[i] = we + (size_t)strip_of(sl >> 6) * n_chunks * 1024 + (sl & 63) * 16;
-  }
+  for (int i = 0; i < 2; ++i) pw[i] = we + (size_t)strip_of(i * 8 + wv) * n_chunks * 1024;     // slot (i*512 + tid) / 64 = 8 i + wave
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mxm_lds;
   auto dma16 = [](const uint8_t* src, unsigned lds_wave_base) {
     unsigned keep_m0;                                            // m0 is left as it was found
@@ -1065,26 +1065,27 @@ __global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restr
     const unsigned stage = lds0 + (unsigned)(ch & 1) * STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
-      dma16(pa[i] + (size_t)ch * 128, stage + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+      dma16(a + ((size_t)pa[i] + (size_t)ch * 128), stage + (unsigned)(i * THREADS + wv * 64) * 16);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-      dma16(pw[i] + (size_t)ch * 1024, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
+      dma16(pw[i] + (size_t)ch * 1024 + lane * 16, stage + A_BYTES + (unsigned)(i * THREADS + wv * 64) * 16);
   };
   // the wave's four weight tiles: GU: slots 2 wn, 2 wn + 1 (gate) and 8 + 2 wn, 9 + 2 wn (up); DOWN: slots 4 wn ..
   int wslot[NT];
 #pragma unroll
   for (int j = 0; j < NT; ++j) wslot[j] = GU ? (j < 2 ? wn * 2 + j : 8 + wn * 2 + (j - 2)) : wn * NT + j;
-  const uint8_t* wsp[NT]; const uint8_t* asp[MI];
+  const uint8_t* wsp[NT];               // per wave; + 4 lane
+  unsigned asp[MI];                     // byte offsets into a_sc
 #pragma unroll
-  for (int j = 0; j < NT; ++j) wsp[j] = wse + ((size_t)strip_of(wslot[j]) * n_cgrp * 64 + lane) * 4;
+  for (int j = 0; j < NT; ++j) wsp[j] = wse + (size_t)strip_of(wslot[j]) * n_cgrp * 256;
 #pragma unroll
-  for (int i = 0; i < MI; ++i) asp[i] = a_sc + src_row(p0 + wm * 128 + i * 16 + m16) * asb + g * 4;
+  for (int i = 0; i < MI; ++i) asp[i] = (unsigned)src_row(p0 + wm * 128 + i * 16 + m16) * (unsigned)asb + g * 4;
   unsigned wsc[NT], asc[MI], wsc_n[NT], asc_n[MI];
   auto load_scales = [&](int q, unsigned (&ws)[NT], unsigned (&as)[MI]) {
 #pragma unroll
-    for (int j = 0; j < NT; ++j) ws[j] = *reinterpret_cast<const unsigned*>(wsp[j] + (size_t)q * 256);
+    for (int j = 0; j < NT; ++j) ws[j] = *reinterpret_cast<const unsigned*>(wsp[j] + (size_t)q * 256 + lane * 4);
 #pragma unroll
-    for (int i = 0; i < MI; ++i) as[i] = *reinterpret_cast<const unsigned*>(asp[i] + q * 16);
+    for (int i = 0; i < MI; ++i) as[i] = *reinterpret_cast<const unsigned*>(a_sc + ((size_t)asp[i] + q * 16));
   };
   f32x4 acc[MI][NT];
 #pragma unroll
