@@ -805,7 +805,9 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
   uint8_t* As = lds_moe_mx;
   uint8_t* Ss = lds_moe_mx + MT * 16 * MX_LDA;
   constexpr int NS = 4;
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
+  // (the wave number in a scalar register: the strips' base addresses then are scalar too and a lane adds only
+  // its 16 lane / 4 lane bytes at the load, which saves the vector registers the accumulators need)
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), m16 = lane & 15, g = lane >> 4;
   const int e = blockIdx.y;
   const bool fly = pair == nullptr;              // no sorted lists: derive this expert's list from the selections
   int beg, n_e;
@@ -826,8 +828,8 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
     col0[sb] = strip * 16;
     if (strip >= out_strips) strip = out_strips - 1;             // beyond N: a valid strip, results not stored
     const int strip_abs = (GU && sb >= 2) ? out_strips + strip : strip;      // up rows follow the gate rows
-    wp[sb] = w + (size_t)e * ((size_t)NR * K / 2) + (size_t)strip_abs * n_chunks * 1024 + lane * 16;
-    sp[sb] = w_sc + (size_t)e * mx_wscale_bytes(NR, K) + ((size_t)strip_abs * n_cgrp * 64 + lane) * 4;
+    wp[sb] = w + (size_t)e * ((size_t)NR * K / 2) + (size_t)strip_abs * n_chunks * 1024;
+    sp[sb] = w_sc + (size_t)e * mx_wscale_bytes(NR, K) + (size_t)strip_abs * n_cgrp * 256;
   }
   struct WBuf { uint4 q[NS][4]; unsigned sc[NS]; };
   WBuf bufA, bufB;
@@ -839,9 +841,9 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         int ch = cg * 4 + kk; if (ch >= n_chunks) ch = 0;         // beyond K: an in-range chunk (meets zero codes)
-        f.q[sb][kk] = ldg16_stream(wp[sb] + (size_t)ch * 1024);
+        f.q[sb][kk] = ldg16_stream(wp[sb] + (size_t)ch * 1024 + lane * 16);
       }
-      f.sc[sb] = *reinterpret_cast<const unsigned*>(sp[sb] + (size_t)cgs * 256);
+      f.sc[sb] = *reinterpret_cast<const unsigned*>(sp[sb] + (size_t)cgs * 256 + lane * 4);
     }
   };
   const unsigned lds_as = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)As;
