@@ -46,6 +46,10 @@ CASES = [
     (B.PLT_BF16,  1100, 128, 64,  100, 8, 0.05, 0.0),  # 8800 pairs, 100 experts: the multi-workgroup sort with two counters per lane
     (B.PLT_BF16,  1500, 256, 192,  12, 4, 0.05, 0.6),  # the tiled GEMM on crowded and empty experts, ragged row tiles,
                                                        # hidden width no multiple of its 128-column half tile
+    (B.PLT_BF16,  530, 384,  64,  200, 3, 0.05, 0.0),  # matrix-core router: 200 experts (13 column blocks, the last ragged),
+                                                       # three chunks of the row over four waves
+    (B.PLT_BF16,  2085, 640, 64,   24, 3, 0.05, 0.0),  # matrix-core router at a prefill-sized row count: two row blocks per
+                                                       # wave, ragged last workgroup, five chunks over four waves
 ]
 
 

@@ -216,11 +216,12 @@ def test_moe_model_with_lowbit_experts(mode, kv_dtype, seed):
 MX_MOE_SEED = 0
 
 
-@pytest.mark.parametrize("rows,E,k", [(40, 4, 2), (70, 4, 2), (150, 4, 2), (1100, 4, 2)])
+@pytest.mark.parametrize("rows,E,k", [(40, 4, 2), (70, 4, 2), (150, 4, 2), (1100, 4, 2), (2100, 4, 2)])
 def test_moe_lowbit_tile_variants_single_position(rows, E, k):
     """20, 35 and 75 rows per expert on average: the 32-row, 64-row and 128-row tiles of the grouped low-bit
     GEMM (several tiles per expert); 550 rows per expert: the prefill-sized 256 x 256-tile kernel (sorted lists, ragged
-    row tiles); on single-position L = 1 sequences where the comparison is tight."""
+    row tiles); 2100 rows: the router's prefill-sized launch on e4m3 rows; on single-position L = 1 sequences where the
+    comparison is tight."""
     from tests.helpers import oshape, with_shape
     shape = with_shape(MX_MOE, n_loops=1, n_experts=E, top_k=k, n_layers=1)
     weights = lively_weights(shape, 3, bf16=True, std=0.05, router_std=0.2)
