@@ -14,7 +14,7 @@
 //                                              V layout (16-byte chunks of consecutive positions)
 // With this orientation a lane owns one query row in S^T, P^T and O^T alike, so the online
 // softmax needs no data movement between the two contractions; the row maximum is completed
-// with two wavefront shuffles (lanes r, r+16, r+32, r+48).  The four waves of a workgroup take
+// with a row swap and a half-wave swap (lanes r, r+16, r+32, r+48).  The four waves of a workgroup take
 // alternate tiles and merge their (m, l, O) states through LDS; workgroups that split one
 // stream leave (m, l, O) records in an HBM scratch that a small second kernel merges (a
 // device-scope fence per workgroup costs far more on this multi-die part than a launch).
@@ -34,6 +34,17 @@ typedef __attribute__((ext_vector_type(8))) float f32x8;
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ inline uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+// max over the four lanes r, r+16, r+32, r+48 (the lanes that share a query row), left in all four: gfx950's row
+// and half-wave swaps run on the vector ALU (given two copies of one value, the element-wise max of the two
+// registers after a swap is the pairwise max); a wavefront shuffle takes the much longer way through the LDS.
+// Written as asm: the compiler folds the builtin's two results into one.  The s_nop cover the read/write hazards.
+__device__ __forceinline__ float row4_max(float v) {
+  float a = v, b = v;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t"
+               "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1"
+               : "+v"(a), "+v"(b));
+  return a;
+}
 
 
 template <int D>
@@ -110,7 +121,7 @@ __device__ inline void tile_step(WaveState<D>& st, KvTile<D, false>& t, const ui
   mid();
   float sv[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) { sv[i] = s0[i] * scale_log2; sv[4 + i] = s1[i] * scale_log2; }
+  for (int i = 0; i < 4; ++i) { sv[i] = s0[i]; sv[4 + i] = s1[i]; }
   if (need_mask) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) if (!valid(j)) sv[j] = NEG_INF;
@@ -118,24 +129,26 @@ __device__ inline void tile_step(WaveState<D>& st, KvTile<D, false>& t, const ui
   float mx = sv[0];
 #pragma unroll
   for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(st.m, mx);
+  mx = row4_max(mx);
+  const float m_new = fmaxf(st.m, mx * scale_log2);      // the scale is positive: max and scaling commute
   const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
   f32x8 p;
   float ps = 0.f;
 #pragma unroll
-  for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(sv[j] - m_safe); ps += p[j]; }
+  for (int j = 0; j < 8; ++j) { p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[j], scale_log2, -m_safe)); ps += p[j]; }
   st.l = st.l * alpha + ps;
   st.m = m_new;
   const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+  // alpha == 1 in every lane (no row raised its maximum: the usual case after the first few tiles): the rescale
+  // of the accumulators is skipped for the whole wave
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-  for (int dt = 0; dt < D / 16; ++dt) {
-    f32x4 a = st.acc[dt];
-    a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
-    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.v[dt]), pb, a, 0, 0, 0);
+    for (int dt = 0; dt < D / 16; ++dt) { st.acc[dt][0] *= alpha; st.acc[dt][1] *= alpha; st.acc[dt][2] *= alpha; st.acc[dt][3] *= alpha; }
   }
+#pragma unroll
+  for (int dt = 0; dt < D / 16; ++dt)
+    st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(t.v[dt]), pb, st.acc[dt], 0, 0, 0);
   end();
 }
 
@@ -160,7 +173,7 @@ __device__ inline void tile_step(WaveState<D>& st, KvTile<D, true>& t, const uin
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sv[4 * a + i] = s[a][i] * scale_log2;
+    for (int i = 0; i < 4; ++i) sv[4 * a + i] = s[a][i];
   if (need_mask) {
 #pragma unroll
     for (int j = 0; j < 16; ++j) if (!valid(j)) sv[j] = NEG_INF;
@@ -168,25 +181,28 @@ __device__ inline void tile_step(WaveState<D>& st, KvTile<D, true>& t, const uin
   float mx = sv[0];
 #pragma unroll
   for (int j = 1; j < 16; ++j) mx = fmaxf(mx, sv[j]);
-  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(st.m, mx);
+  mx = row4_max(mx);
+  const float m_new = fmaxf(st.m, mx * scale_log2);      // the scale is positive: max and scaling commute
   const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
   f32x8 p0, p1;
   float ps = 0.f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    p0[j] = __builtin_amdgcn_exp2f(sv[j] - m_safe); p1[j] = __builtin_amdgcn_exp2f(sv[8 + j] - m_safe);
+    p0[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[j], scale_log2, -m_safe));
+    p1[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[8 + j], scale_log2, -m_safe));
     ps += p0[j] + p1[j];
   }
   st.l = st.l * alpha + ps;
   st.m = m_new;
   const bf16x8 pb0 = __builtin_convertvector(p0, bf16x8), pb1 = __builtin_convertvector(p1, bf16x8);
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {      // (as above)
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) { st.acc[dt][0] *= alpha; st.acc[dt][1] *= alpha; st.acc[dt][2] *= alpha; st.acc[dt][3] *= alpha; }
+  }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt) {
     f32x4 a = st.acc[dt];
-    a[0] *= alpha; a[1] *= alpha; a[2] *= alpha; a[3] *= alpha;
     const uint4 r = t.v[dt];
     a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.x, r.y), pb0, a, 0, 0, 0);
     st.acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(e4m3x8_to_bf16(r.z, r.w), pb1, a, 0, 0, 0);
