@@ -33,6 +33,45 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 // loads of all 8 weight rows issued together (the router matrix is small and cache-resident: what costs
 // here is load latency, not bytes).
 constexpr int ROUTE_WAVES = 8, ROUTE_EB = 8;
+// Exchange step S of an all-to-all reduction over the 16 lanes of a row (lanes that share lane / 16): pairs, then
+// pairs of pairs, then the two quads of a half row (mirrored: every lane of a quad already holds the quad's
+// result), then the two half rows.  After the four steps every lane has combined all 16.
+template <int S, typename V>
+__device__ inline V row16_xchg(V x) {
+  constexpr int ctrl = S == 0 ? 0xB1 : S == 1 ? 0x4E : S == 2 ? 0x141 : 0x140;   // quad_perm 1032, quad_perm 2301, row_half_mirror, row_mirror
+  const int u = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(V, __builtin_amdgcn_update_dpp(0, u, ctrl, 0xf, 0xf, true));   // (every lane has a source lane)
+}
+
+// The same over the four lanes r, r + 16, r + 32, r + 48 (one lane of each row): gfx950's row swap and half-wave
+// swap, which run on the vector ALU; given two copies of one value, combining the two registers after a swap
+// combines the pairs.  Written as asm: the compiler folds the builtin's two results into one.  The s_nop cover the
+// instructions' read/write hazards.
+#define PLT_ROW4_OP(NAME, T, CONSTRAINT, INSTR)                                                                         \
+  __device__ __forceinline__ T NAME(T v) {                                                                              \
+    T a = v, b = v;                                                                                                     \
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\t" INSTR " %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t" \
+                 "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\t" INSTR " %0, %0, %1"                                         \
+                 : "+" CONSTRAINT(a), "+" CONSTRAINT(b));                                                               \
+    return a;                                                                                                           \
+  }
+PLT_ROW4_OP(row4_max_f32, float, "v", "v_max_f32")
+PLT_ROW4_OP(row4_add_f32, float, "v", "v_add_f32")
+PLT_ROW4_OP(row4_min_i32, int, "v", "v_min_i32")
+#undef PLT_ROW4_OP
+__device__ __forceinline__ float wave_max_f32(float v) {
+  v = fmaxf(v, row16_xchg<0>(v)); v = fmaxf(v, row16_xchg<1>(v)); v = fmaxf(v, row16_xchg<2>(v)); v = fmaxf(v, row16_xchg<3>(v));
+  return row4_max_f32(v);
+}
+__device__ __forceinline__ float wave_add_f32(float v) {
+  v += row16_xchg<0>(v); v += row16_xchg<1>(v); v += row16_xchg<2>(v); v += row16_xchg<3>(v);
+  return row4_add_f32(v);
+}
+__device__ __forceinline__ int wave_min_i32(int v) {
+  v = min(v, row16_xchg<0>(v)); v = min(v, row16_xchg<1>(v)); v = min(v, row16_xchg<2>(v)); v = min(v, row16_xchg<3>(v));
+  return row4_min_i32(v);
+}
+
 // TA: type of the row (model dtype, or fp8_t: e4m3 codes with block scales a_sc of a low-bit model); T: router matrix
 template <typename TA, typename T>
 __global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __restrict__ a, const uint8_t* __restrict__ a_sc,
@@ -45,8 +84,24 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __rest
   const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   if constexpr (sizeof(TA) == 1) {
     const int nbp = mx_ascale_row_bytes(d);
-    for (int i = tid; i < d; i += ROUTE_WAVES * 64)
-      xr[i] = ldexpf(e4m3_to_f32(a[(size_t)r * d + i]), (int)a_sc[(size_t)r * nbp + mx_ascale_index(i >> 5)] - 127);
+    if ((d & 3) == 0) {                                     // four codes (of one block) per thread: one round trip
+      for (int i = tid * 4; i < d; i += ROUTE_WAVES * 64 * 4) {
+        const unsigned q = *reinterpret_cast<const unsigned*>(a + (size_t)r * d + i);
+        const int ex = (int)a_sc[(size_t)r * nbp + mx_ascale_index(i >> 5)] - 127;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) xr[i + c] = ldexpf(e4m3_to_f32((fp8_t)((q >> (8 * c)) & 0xffu)), ex);
+      }
+    } else {
+      for (int i = tid; i < d; i += ROUTE_WAVES * 64)
+        xr[i] = ldexpf(e4m3_to_f32(a[(size_t)r * d + i]), (int)a_sc[(size_t)r * nbp + mx_ascale_index(i >> 5)] - 127);
+    }
+  } else if (sizeof(TA) == 2 && (d & 7) == 0) {           // 16 bytes per thread: the whole row in one round trip
+    for (int i = tid * 8; i < d; i += ROUTE_WAVES * 64 * 8) {
+      const uint4 q = *reinterpret_cast<const uint4*>(reinterpret_cast<const bf16_t*>(a) + (size_t)r * d + i);
+      const unsigned u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+      for (int c = 0; c < 4; ++c) { xr[i + 2 * c] = bf16_to_f32((bf16_t)(u[c] & 0xffffu)); xr[i + 2 * c + 1] = bf16_to_f32((bf16_t)(u[c] >> 16)); }
+    }
   } else {
     for (int i = tid; i < d; i += ROUTE_WAVES * 64) xr[i] = ld<TA>(a + (size_t)r * d + i);
   }
@@ -88,9 +143,7 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __rest
     }
 #pragma unroll
     for (int j = 0; j < ROUTE_EB; ++j) {
-      float s = acc[j];
-#pragma unroll
-      for (int o = 32; o; o >>= 1) s += __shfl_xor(s, o);
+      const float s = wave_add_f32(acc[j]);
       const int e = e0 + j * ROUTE_WAVES;
       if (lane == 0 && e < E) lg[e] = s;
     }
@@ -98,43 +151,31 @@ __global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __rest
   __syncthreads();
   if (wv != 0) return;
   // softmax over all E (<= 256) logits and the k largest, one wave: lane holds logits lane + 64 j
+  // (the exchanges between lanes are data-parallel-primitive moves and row / half-wave swaps on the vector ALU;
+  // wavefront shuffles through the LDS crossbar made this tail as long as the logits before it)
   float v[4];
   float mx = -INFINITY;
 #pragma unroll
   for (int j = 0; j < 4; ++j) { const int idx = lane + 64 * j; v[j] = idx < E ? lg[idx] : -INFINITY; mx = fmaxf(mx, v[j]); }
-#pragma unroll
-  for (int o = 32; o; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  mx = wave_max_f32(mx);
   float sum = 0.f;
 #pragma unroll
   for (int j = 0; j < 4; ++j) if (lane + 64 * j < E) sum += expf(v[j] - mx);
-#pragma unroll
-  for (int o = 32; o; o >>= 1) sum += __shfl_xor(sum, o);
+  sum = wave_add_f32(sum);
+  const float inv = 1.0f / sum;
   for (int t = 0; t < k; ++t) {
-    float bv = v[0]; int bi = lane;            // lane's best: ascending j, strict >, so its lowest index wins ties
+    float lv = v[0]; int li = lane;            // lane's best: ascending j, strict >, so its lowest index wins ties
 #pragma unroll
-    for (int j = 1; j < 4; ++j) if (v[j] > bv) { bv = v[j]; bi = lane + 64 * j; }
-#pragma unroll
-    for (int o = 32; o; o >>= 1) {
-      const float ov = __shfl_xor(bv, o); const int oi = __shfl_xor(bi, o);
-      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-    }
-    if (lane == 0) { sel_e[(size_t)r * k + t] = bi; sel_p[(size_t)r * k + t] = expf(bv - mx) / sum; }
+    for (int j = 1; j < 4; ++j) if (v[j] > lv) { lv = v[j]; li = lane + 64 * j; }
+    const float bv = wave_max_f32(lv);                                    // the largest logit left,
+    const int bi = wave_min_i32(lv == bv ? li : 0x7fffffff);              // then the lowest index that has it
+    if (lane == 0) { sel_e[(size_t)r * k + t] = bi; sel_p[(size_t)r * k + t] = expf(bv - mx) * inv; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = (lane + 64 * j == bi) ? -INFINITY : v[j];     // taken: out of the running
   }
 }
 
 // ---------------------------------------------------------------------------------------------- router, matrix cores
-// Exchange step S of an all-to-all reduction over the 16 lanes of a row (lanes that share lane / 16): pairs, then
-// pairs of pairs, then the two quads of a half row (mirrored: every lane of a quad already holds the quad's
-// result), then the two half rows.  After the four steps every lane has combined all 16.
-template <int S, typename V>
-__device__ inline V row16_xchg(V x) {
-  constexpr int ctrl = S == 0 ? 0xB1 : S == 1 ? 0x4E : S == 2 ? 0x141 : 0x140;   // quad_perm 1032, quad_perm 2301, row_half_mirror, row_mirror
-  const int u = __builtin_bit_cast(int, x);
-  return __builtin_bit_cast(V, __builtin_amdgcn_update_dpp(0, u, ctrl, 0xf, 0xf, true));   // (every lane has a source lane)
-}
-
 // The same router for batches of 512 rows and more, 16-bit router matrices, row lengths that are a multiple of 128:
 // the logits of RB x 16 rows x all experts as 16x16x32 bf16 tiles (rows = A operand, router rows = B operand), so
 // the router matrix is read from the last-level cache once per RB x 16 rows instead of once per row.  The KS
