@@ -168,3 +168,64 @@ def test_decode_step_moe_8_of_64_batch64_ctx2048_sampled():
         clear += 1
     assert clear >= 2
     kv.close(); model.close()
+
+
+def _untile(t):
+    """Inverse of binding.moe_tile_weights for one matrix: blob strip order -> logical [N, K]."""
+    N, K = t.shape
+    return np.ascontiguousarray(t.reshape(N // 16, K // 32, 4, 16, 8).transpose(0, 3, 1, 2, 4)).reshape(N, K)
+
+
+def test_moe_ffn_one_prefill_chunk_16384_rows_sampled():
+    """The mixture-of-experts feed-forward alone at the size of one prefill chunk of the paper's 8-of-64 recipe
+    (16384 rows of 2048, 64 SwiGLU experts of hidden 1024, 8 per row): the router on the matrix cores, the stable
+    sort of 131072 (row, slot) pairs over many workgroups, both grouped GEMMs on 256 x 256 tiles.  The weights are
+    drawn on the device directly in the blob's strip order (a random matrix in any order is a random matrix) and
+    un-permuted on the host for the experts the sampled rows select; the oracle recomputes those rows."""
+    from tests.test_gpu_moe import _bf16_bound
+    R, d, F, E, k = 16384, 2048, 1024, 64, 8
+    g = torch.Generator(device="cuda"); g.manual_seed(bench.SEED + 21)
+    bf = torch.bfloat16
+    a = torch.randn(R, d, generator=g, device="cuda").to(bf)
+    router = (torch.randn(E, d, generator=g, device="cuda") * 0.05).to(bf)
+    gu = (torch.randn(E, 2 * F, d, generator=g, device="cuda") * 0.02).to(bf)      # strip order
+    dn = (torch.randn(E, d, F, generator=g, device="cuda") * 0.02).to(bf)          # strip order
+    y = torch.empty(R, d, dtype=torch.float32, device="cuda")
+    sel_e = torch.empty(R, k, dtype=torch.int32, device="cuda")
+    sel_p = torch.empty(R, k, dtype=torch.float32, device="cuda")
+    lib = B.lib()
+    nb = lib.plt_moe_scratch_bytes(B.PLT_BF16, R, d, F, E, k)
+    assert nb > 0, lib.plt_last_error().decode()
+    scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    rc = lib.plt_moe_ffn(B.PLT_BF16, R, d, F, E, k, a.data_ptr(), router.data_ptr(), gu.data_ptr(), dn.data_ptr(),
+                         y.data_ptr(), sel_e.data_ptr(), sel_p.data_ptr(), scratch.data_ptr(), nb,
+                         torch.cuda.current_stream().cuda_stream)
+    assert rc == 0, lib.plt_last_error().decode()
+    torch.cuda.synchronize()
+    se = sel_e.cpu().numpy(); sp = sel_p.cpu().numpy()
+    # every row: k distinct experts, probabilities in decreasing order; the lists cover all R * k pairs
+    assert np.all(np.sort(se, axis=1)[:, 1:] != np.sort(se, axis=1)[:, :-1]) and np.all(np.diff(sp, axis=1) <= 0)
+    counts = np.bincount(se.reshape(-1), minlength=E)
+    print(f"rows per expert min/mean/max {counts.min()}/{counts.mean():.0f}/{counts.max()}")
+    router_h = router.float().cpu().numpy()
+    compared = 0
+    for r in (0, 255, 256, 4099, 8191, 12345, 16382, 16383):    # first / last rows of row tiles and chunks, some inside
+        b = a[r].float().cpu().numpy()
+        ids, p, margin = O.moe_route(b, router_h, k)
+        if margin < 1e-4:                       # float and float64 logits may order the boundary pair differently
+            print(f"row {r}: routing gap {margin:.3e}: not compared")
+            continue
+        assert list(se[r]) == list(ids), (r, se[r], ids, margin)
+        assert np.max(np.abs(sp[r] - p)) <= 1e-5
+        W = {"w_gate": {}, "w_up": {}, "w_down": {}}
+        ref = np.zeros(d)
+        for e, pe in zip(ids, p):
+            gate_up = _untile(gu[e].float().cpu().numpy())
+            W["w_gate"][e], W["w_up"][e], W["w_down"][e] = gate_up[:F], gate_up[F:], _untile(dn[e].float().cpu().numpy())
+            ref += pe * O.swiglu_ffn(b, W["w_gate"][e], W["w_up"][e], W["w_down"][e], None)
+        err = np.abs(y[r].cpu().numpy() - ref)
+        tol = _bf16_bound(b, W, ids, p) + 1e-5 * max(float(np.max(np.abs(ref))), 1.0)    # as in tests/test_gpu_moe.py
+        print(f"row {r}: routing gap {margin:.3e}; max |y| {np.max(np.abs(ref)):.3e}; max err {err.max():.3e}")
+        assert np.all(err <= tol) and err.max() <= 2e-2, (r, float(err.max()))
+        compared += 1
+    assert compared >= 5
