@@ -229,3 +229,55 @@ def test_moe_ffn_one_prefill_chunk_16384_rows_sampled():
         assert np.all(err <= tol) and err.max() <= 2e-2, (r, float(err.max()))
         compared += 1
     assert compared >= 5
+
+
+def test_prefill_4x8192_L3_equals_shorter_prefill_plus_decode_steps():
+    """The prefill workload bench.py times (4 prompts of 8192 tokens, L = 3, window 64, the 1.3B widths; two layers
+    deep) cannot be walked by the position-by-position oracle in seconds, so it is checked through a property that
+    holds at any size [Alg. 1 l.1-3: the prompt is consumed by the same micro-batch rule as decoding]: the prefill
+    of all n tokens must leave the state that the prefill of the first n - 37 tokens followed by 37 teacher-forced
+    decode steps leaves -- and those decode steps are checked against the oracle at full size above.  Compared:
+    the last position's logits, the carry, and for sampled sequences both layers' shared K/V (positions both paths
+    took through the prefill kernels: identical; the last 37: equal to bf16 rounding) and rings."""
+    shape = bench.with_layers(synth.PLT_1P3B, 2)
+    Bn, n, m = 4, 8192, 37
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=3, window=64)
+    blob = bench.fill_weights_on_device(B, cfg, bench.SEED)
+    model = B.Model(cfg, blob)
+    g = torch.Generator(device="cuda"); g.manual_seed(bench.SEED + 31)
+    tokens = torch.randint(0, shape.vocab, (Bn, n), generator=g, device="cuda", dtype=torch.int32)
+    kv_a = B.KV(model, Bn, n + 1)
+    next_a, lg_a = kv_a.prefill(tokens)
+    next_a = next_a.cpu().numpy().copy(); lg_a = lg_a.float().cpu().numpy().copy()
+    kv_b = B.KV(model, Bn, n + 1)
+    kv_b.prefill(tokens[:, :n - m].contiguous(), want_logits=False)
+    for i in range(m):
+        next_b, lg_b = kv_b.decode_step(tokens[:, n - m + i].contiguous())
+    next_b = next_b.cpu().numpy(); lg_b = lg_b.float().cpu().numpy()
+    top = float(np.max(np.abs(lg_a)))
+    d_lg = float(np.max(np.abs(lg_a - lg_b)))
+    ca, cb = kv_a.get_carry(), kv_b.get_carry()
+    d_c = float(np.max(np.abs(ca - cb)) / np.max(np.abs(ca)))
+    print(f"logits: max |.| {top:.3f}, max difference {d_lg:.3e}; carry: max relative difference {d_c:.3e}")
+    # both paths round every stored activation to bf16 (2^-8 relative) and differ in accumulation order only; each
+    # is within 1 % of the largest logit of the exact result (the bar of the oracle comparisons), so the two are
+    # within 2 % of each other
+    assert d_lg <= 2e-2 * top and d_c <= 2e-2
+    margin = np.sort(lg_a, axis=1)
+    for b in range(Bn):
+        if margin[b, -1] - margin[b, -2] > 4e-2 * top:
+            assert next_a[b] == next_b[b], (b, next_a[b], next_b[b])
+    for b in (0, Bn - 1):
+        for layer in range(shape.n_layers):
+            ea, eb = kv_a.export(b, layer, n), kv_b.export(b, layer, n)
+            for name in ("k_share", "v_share"):
+                assert np.array_equal(ea[name][:, :n - m], eb[name][:, :n - m]), (b, layer, name)
+                scale = float(np.max(np.abs(ea[name][:, n - m:])))
+                diff = float(np.max(np.abs(ea[name][:, n - m:] - eb[name][:, n - m:])))
+                assert diff <= 2e-2 * scale, (b, layer, name, diff, scale)
+            for name in ("k_ring", "v_ring"):
+                scale = float(np.max(np.abs(ea[name])))
+                diff = float(np.max(np.abs(ea[name] - eb[name])))
+                assert diff <= 2e-2 * scale, (b, layer, name, diff, scale)
+            print(f"seq {b} layer {layer}: shared K/V identical below position {n - m}; last {m} and rings within 2 % of the largest entry")
+    kv_a.close(); kv_b.close(); model.close()
