@@ -34,18 +34,6 @@ typedef __attribute__((ext_vector_type(8))) float f32x8;
 
 __device__ inline bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 __device__ inline uint4 ldg16(const bf16_t* p) { return *reinterpret_cast<const uint4*>(p); }
-// max over the four lanes r, r+16, r+32, r+48 (the lanes that share a query row), left in all four: gfx950's row
-// and half-wave swaps run on the vector ALU (given two copies of one value, the element-wise max of the two
-// registers after a swap is the pairwise max); a wavefront shuffle takes the much longer way through the LDS.
-// Written as asm: the compiler folds the builtin's two results into one.  The s_nop cover the read/write hazards.
-__device__ __forceinline__ float row4_max(float v) {
-  float a = v, b = v;
-  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t"
-               "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1"
-               : "+v"(a), "+v"(b));
-  return a;
-}
-
 
 template <int D>
 struct WaveState {
@@ -129,7 +117,7 @@ __device__ inline void tile_step(WaveState<D>& st, KvTile<D, false>& t, const ui
   float mx = sv[0];
 #pragma unroll
   for (int j = 1; j < 8; ++j) mx = fmaxf(mx, sv[j]);
-  mx = row4_max(mx);
+  mx = row4_max_f32(mx);
   const float m_new = fmaxf(st.m, mx * scale_log2);      // the scale is positive: max and scaling commute
   const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
@@ -181,7 +169,7 @@ __device__ inline void tile_step(WaveState<D>& st, KvTile<D, true>& t, const uin
   float mx = sv[0];
 #pragma unroll
   for (int j = 1; j < 16; ++j) mx = fmaxf(mx, sv[j]);
-  mx = row4_max(mx);
+  mx = row4_max_f32(mx);
   const float m_new = fmaxf(st.m, mx * scale_log2);      // the scale is positive: max and scaling commute
   const float m_safe = (m_new == NEG_INF) ? 0.f : m_new;
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_safe);
@@ -222,8 +210,7 @@ struct WgMerge {
 template <int D>
 __device__ inline void wg_park(WgMerge<D>& sm, const WaveState<D>& st, int wv, int m16, int g) {
   float l = st.l;
-  l += __shfl_xor(l, 16, 64);
-  l += __shfl_xor(l, 32, 64);
+  l = row4_add_f32(l);
   if (g == 0) { sm.m[wv][m16] = st.m; sm.l[wv][m16] = l; }
 #pragma unroll
   for (int dt = 0; dt < D / 16; ++dt)
@@ -312,8 +299,8 @@ __device__ inline void finalize_row(const AttnDecArgs& A, int b, int kvh, int rt
   float amax = 0.f;
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) amax = fmaxf(amax, fabsf(out[i]));
-  amax = fmaxf(amax, __shfl_xor(amax, 1)); amax = fmaxf(amax, __shfl_xor(amax, 2));
-  if (D == 64) amax = fmaxf(amax, __shfl_xor(amax, 4));
+  amax = fmaxf(amax, row16_xchg<0>(amax)); amax = fmaxf(amax, row16_xchg<1>(amax));
+  if (D == 64) amax = fmaxf(amax, row16_xchg<2>(amax));
   const int e = mx_block_exponent(amax, 8);
   const int col = r_head * D + dc;
   unsigned* dst = reinterpret_cast<unsigned*>(A.y_codes + yrow * (size_t)(A.Hq * D) + col);

@@ -27,20 +27,6 @@ constexpr int PF_QROWS = 128;                 // query positions per workgroup
 
 __device__ inline bf16x8 pf_bf(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// max over the four lanes r, r+16, r+32, r+48 (the lanes that share a query row), left in all four: gfx950's row
-// and half-wave swaps run on the vector ALU, a wavefront shuffle would take the much longer way through the LDS
-__device__ __forceinline__ float pf_row_max(float v) {
-  // v_permlane16_swap exchanges the first register's odd rows with the second's even rows (rows of 16 lanes),
-  // v_permlane32_swap the first's upper half wave with the second's lower half; given two copies of one value,
-  // the element-wise max of the two registers afterwards is the pairwise max.  Written as asm: the compiler
-  // folds the builtin's two results into one.  The s_nop cover the instructions' read/write hazards.
-  float a = v, b = v;
-  asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t"
-               "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\tv_max_f32 %0, %0, %1"
-               : "+v"(a), "+v"(b));
-  return a;
-}
-
 template <int D>
 struct PfState {           // online softmax state of one 16-row query tile
   float m;                 // running maximum (log2 domain); starts at a large negative finite value, so that
@@ -90,7 +76,7 @@ __device__ __forceinline__ void pf_softmax(PfState<D>& st, const f32x4 (&s)[2][2
   float mx = sv[0];
 #pragma unroll
   for (int j = 1; j < 16; ++j) mx = fmaxf(mx, sv[j]);
-  mx = pf_row_max(mx);
+  mx = row4_max_f32(mx);
   const float m_new = fmaxf(st.m, mx * scale_log2);        // the scale is positive: max and scaling commute
   const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
   f32x8 p[2];

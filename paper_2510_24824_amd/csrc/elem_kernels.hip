@@ -7,9 +7,7 @@
 namespace plt {
 
 __device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  return wave_add_f32(v);
 }
 
 // block-wide sum for blockDim.x == 256 (4 waves)
@@ -184,7 +182,7 @@ __global__ __launch_bounds__(256) void k_resid_norm4_mx(float* __restrict__ x, c
     const float4 gn = reinterpret_cast<const float4*>(gain)[i];
     const float n0 = v[it].x * inv * gn.x, n1 = v[it].y * inv * gn.y, n2 = v[it].z * inv * gn.z, n3 = v[it].w * inv * gn.w;
     float amax = fmaxf(fmaxf(fabsf(n0), fabsf(n1)), fmaxf(fabsf(n2), fabsf(n3)));
-    amax = fmaxf(amax, __shfl_xor(amax, 1)); amax = fmaxf(amax, __shfl_xor(amax, 2)); amax = fmaxf(amax, __shfl_xor(amax, 4));
+    amax = fmaxf(amax, row16_xchg<0>(amax)); amax = fmaxf(amax, row16_xchg<1>(amax)); amax = fmaxf(amax, row16_xchg<2>(amax));   // 8 consecutive lanes
     const int e = mx_block_exponent(amax, 8);
     *reinterpret_cast<unsigned*>(codes + (size_t)r * d + 4 * i) = mx_pack4_e4m3(n0, n1, n2, n3, e);
     if ((i & 7) == 0) scales[(size_t)r * nbp + mx_ascale_index(i >> 3)] = (uint8_t)(e + 127);
@@ -215,7 +213,7 @@ __global__ __launch_bounds__(256) void k_silu_mul_mx(const float* __restrict__ g
   const float h0 = gt.x / (1.0f + expf(-gt.x)) * up.x, h1 = gt.y / (1.0f + expf(-gt.y)) * up.y,
               h2 = gt.z / (1.0f + expf(-gt.z)) * up.z, h3 = gt.w / (1.0f + expf(-gt.w)) * up.w;
   float amax = fmaxf(fmaxf(fabsf(h0), fabsf(h1)), fmaxf(fabsf(h2), fabsf(h3)));
-  amax = fmaxf(amax, __shfl_xor(amax, 1)); amax = fmaxf(amax, __shfl_xor(amax, 2)); amax = fmaxf(amax, __shfl_xor(amax, 4));
+  amax = fmaxf(amax, row16_xchg<0>(amax)); amax = fmaxf(amax, row16_xchg<1>(amax)); amax = fmaxf(amax, row16_xchg<2>(amax));   // 8 consecutive lanes
   if (!live) return;
   const int e = mx_block_exponent(amax, 8), nbp = mx_ascale_row_bytes(F);
   *reinterpret_cast<unsigned*>(codes + (size_t)r * F + 4 * j) = mx_pack4_e4m3(h0, h1, h2, h3, e);
@@ -405,7 +403,7 @@ __global__ __launch_bounds__(256) void k_rope_append_tile(const float* __restric
       float zp = 0.f;
 #pragma unroll
       for (int i = 0; i < PP; ++i) zp += lo[i] * gate_w[hs * D + jb + i] + hi[i] * gate_w[hs * D + half + jb + i];
-      zp += __shfl_xor(zp, 1, 64); zp += __shfl_xor(zp, 2, 64); zp += __shfl_xor(zp, 4, 64);
+      zp += row16_xchg<0>(zp); zp += row16_xchg<1>(zp); zp += row16_xchg<2>(zp);      // the 8 lanes of a position
       if (ok && (t & 7) == 0) z_out[row * Hq + hs] = zp + gate_b[hs];
     }
     if (ok) {

@@ -33,45 +33,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 // loads of all 8 weight rows issued together (the router matrix is small and cache-resident: what costs
 // here is load latency, not bytes).
 constexpr int ROUTE_WAVES = 8, ROUTE_EB = 8;
-// Exchange step S of an all-to-all reduction over the 16 lanes of a row (lanes that share lane / 16): pairs, then
-// pairs of pairs, then the two quads of a half row (mirrored: every lane of a quad already holds the quad's
-// result), then the two half rows.  After the four steps every lane has combined all 16.
-template <int S, typename V>
-__device__ inline V row16_xchg(V x) {
-  constexpr int ctrl = S == 0 ? 0xB1 : S == 1 ? 0x4E : S == 2 ? 0x141 : 0x140;   // quad_perm 1032, quad_perm 2301, row_half_mirror, row_mirror
-  const int u = __builtin_bit_cast(int, x);
-  return __builtin_bit_cast(V, __builtin_amdgcn_update_dpp(0, u, ctrl, 0xf, 0xf, true));   // (every lane has a source lane)
-}
-
-// The same over the four lanes r, r + 16, r + 32, r + 48 (one lane of each row): gfx950's row swap and half-wave
-// swap, which run on the vector ALU; given two copies of one value, combining the two registers after a swap
-// combines the pairs.  Written as asm: the compiler folds the builtin's two results into one.  The s_nop cover the
-// instructions' read/write hazards.
-#define PLT_ROW4_OP(NAME, T, CONSTRAINT, INSTR)                                                                         \
-  __device__ __forceinline__ T NAME(T v) {                                                                              \
-    T a = v, b = v;                                                                                                     \
-    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\t" INSTR " %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t" \
-                 "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\t" INSTR " %0, %0, %1"                                         \
-                 : "+" CONSTRAINT(a), "+" CONSTRAINT(b));                                                               \
-    return a;                                                                                                           \
-  }
-PLT_ROW4_OP(row4_max_f32, float, "v", "v_max_f32")
-PLT_ROW4_OP(row4_add_f32, float, "v", "v_add_f32")
-PLT_ROW4_OP(row4_min_i32, int, "v", "v_min_i32")
-#undef PLT_ROW4_OP
-__device__ __forceinline__ float wave_max_f32(float v) {
-  v = fmaxf(v, row16_xchg<0>(v)); v = fmaxf(v, row16_xchg<1>(v)); v = fmaxf(v, row16_xchg<2>(v)); v = fmaxf(v, row16_xchg<3>(v));
-  return row4_max_f32(v);
-}
-__device__ __forceinline__ float wave_add_f32(float v) {
-  v += row16_xchg<0>(v); v += row16_xchg<1>(v); v += row16_xchg<2>(v); v += row16_xchg<3>(v);
-  return row4_add_f32(v);
-}
-__device__ __forceinline__ int wave_min_i32(int v) {
-  v = min(v, row16_xchg<0>(v)); v = min(v, row16_xchg<1>(v)); v = min(v, row16_xchg<2>(v)); v = min(v, row16_xchg<3>(v));
-  return row4_min_i32(v);
-}
-
 // TA: type of the row (model dtype, or fp8_t: e4m3 codes with block scales a_sc of a low-bit model); T: router matrix
 template <typename TA, typename T>
 __global__ __launch_bounds__(ROUTE_WAVES * 64) void k_moe_route(const TA* __restrict__ a, const uint8_t* __restrict__ a_sc,
@@ -1151,7 +1112,7 @@ __global__ __launch_bounds__(256, MT <= 4 ? 2 : 1) void k_moe_gemm_mx(const uint
             h[j][x] = gt / (1.0f + expf(-gt)) * acc[2 + j][i][x];
             amax = fmaxf(amax, fabsf(h[j][x]));
           }
-        amax = fmaxf(amax, __shfl_xor(amax, 16)); amax = fmaxf(amax, __shfl_xor(amax, 32));
+        amax = row4_max_f32(amax);
         const int ex = mx_block_exponent(amax, 8);
         if (li < n_e && col0[0] < N) {
 #pragma unroll
@@ -1351,7 +1312,7 @@ __global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restr
           h[j][x] = gt / (1.0f + expf(-gt)) * acc[i][2 + j][x];
           amax = fmaxf(amax, fabsf(h[j][x]));
         }
-      amax = fmaxf(amax, __shfl_xor(amax, 16)); amax = fmaxf(amax, __shfl_xor(amax, 32));
+      amax = row4_max_f32(amax);
       const int ex = mx_block_exponent(amax, 8);
       const int col = n0 + wn * 32;
       if (pos < p_end && col < N) {

@@ -46,6 +46,46 @@ __device__ inline uint4 ldg16_stream(const void* p) {
   const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
   return make_uint4(v[0], v[1], v[2], v[3]);
 }
+// ---- reductions over lanes on the vector ALU (no trip through the LDS crossbar) ----
+// Exchange step S of an all-to-all reduction over the 16 lanes of a row (lanes that share lane / 16): pairs, then
+// pairs of pairs, then the two quads of a half row (mirrored: every lane of a quad already holds the quad's
+// result), then the two half rows.  After the four steps every lane has combined all 16.
+template <int S, typename V>
+__device__ inline V row16_xchg(V x) {
+  constexpr int ctrl = S == 0 ? 0xB1 : S == 1 ? 0x4E : S == 2 ? 0x141 : 0x140;   // quad_perm 1032, quad_perm 2301, row_half_mirror, row_mirror
+  const int u = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(V, __builtin_amdgcn_update_dpp(0, u, ctrl, 0xf, 0xf, true));   // (every lane has a source lane)
+}
+
+// The same over the four lanes r, r + 16, r + 32, r + 48 (one lane of each row): gfx950's row swap and half-wave
+// swap, which run on the vector ALU; given two copies of one value, combining the two registers after a swap
+// combines the pairs.  Written as asm: the compiler folds the builtin's two results into one.  The s_nop cover the
+// instructions' read/write hazards.
+#define PLT_ROW4_OP(NAME, T, CONSTRAINT, INSTR)                                                                         \
+  __device__ __forceinline__ T NAME(T v) {                                                                              \
+    T a = v, b = v;                                                                                                     \
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1\n\t" INSTR " %0, %0, %1\n\tv_mov_b32 %1, %0\n\ts_nop 1\n\t" \
+                 "v_permlane32_swap_b32 %0, %1\n\ts_nop 1\n\t" INSTR " %0, %0, %1"                                         \
+                 : "+" CONSTRAINT(a), "+" CONSTRAINT(b));                                                               \
+    return a;                                                                                                           \
+  }
+PLT_ROW4_OP(row4_max_f32, float, "v", "v_max_f32")
+PLT_ROW4_OP(row4_add_f32, float, "v", "v_add_f32")
+PLT_ROW4_OP(row4_min_i32, int, "v", "v_min_i32")
+#undef PLT_ROW4_OP
+__device__ __forceinline__ float wave_max_f32(float v) {
+  v = fmaxf(v, row16_xchg<0>(v)); v = fmaxf(v, row16_xchg<1>(v)); v = fmaxf(v, row16_xchg<2>(v)); v = fmaxf(v, row16_xchg<3>(v));
+  return row4_max_f32(v);
+}
+__device__ __forceinline__ float wave_add_f32(float v) {
+  v += row16_xchg<0>(v); v += row16_xchg<1>(v); v += row16_xchg<2>(v); v += row16_xchg<3>(v);
+  return row4_add_f32(v);
+}
+__device__ __forceinline__ int wave_min_i32(int v) {
+  v = min(v, row16_xchg<0>(v)); v = min(v, row16_xchg<1>(v)); v = min(v, row16_xchg<2>(v)); v = min(v, row16_xchg<3>(v));
+  return row4_min_i32(v);
+}
+
 template <typename T> __device__ inline float ld(const T* p);
 template <> __device__ inline float ld<float>(const float* p) { return *p; }
 template <> __device__ inline float ld<bf16_t>(const bf16_t* p) { return bf16_to_f32(*p); }
