@@ -837,6 +837,18 @@ __global__ __launch_bounds__(512) void k_moe_gemm_tile(const bf16_t* __restrict_
     for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   const int sw0 = (g ^ (m16 & 7)) * 16;
   issue(0);
+  // down projection: where this lane's 8 output rows go and their weights p_e, requested now and used after the
+  // K loop (two dependent loads that the epilogue would otherwise wait for with the matrix cores idle)
+  int out_pr[MI]; float out_p[MI];
+  if (!GU) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      int pos = p0 + wm * 128 + i * 16 + m16; if (pos >= p_end) pos = p_end - 1;
+      out_pr[i] = pair[pos];
+    }
+#pragma unroll
+    for (int i = 0; i < MI; ++i) out_p[i] = sel_p[out_pr[i]];
+  }
   for (int ks = 0; ks < ks_total; ++ks) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of slice ks has landed
     __syncthreads();                                   // ... and everyone's; slice ks - 1 is no longer read
@@ -881,9 +893,9 @@ __global__ __launch_bounds__(512) void k_moe_gemm_tile(const bf16_t* __restrict_
         *reinterpret_cast<ushort4*>(o + gn) = pk;
       }
     } else {
-      const int pr = pair[pos];
+      const int pr = out_pr[i];
       const int row = pr / topk, slot = pr - row * topk;
-      const float p = sel_p[pr];
+      const float p = out_p[i];
       float* o = y_out + ((size_t)slot * R + row) * N;
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
