@@ -138,10 +138,10 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
         const int gn = n0 + wn * (NT * 8) + j * 16 + 4 * g;
         float v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) { const float gt = acc[i][j][e]; v[e] = gt / (1.0f + __expf(-gt)) * acc[i][j + NT / 2][e]; }
+        for (int e = 0; e < 4; ++e) { const float gt = acc[i][j][e]; v[e] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * acc[i][j + NT / 2][e]; }   // 1-ulp reciprocal: the result is rounded to bf16
         if (gn + 3 < N && (N & 3) == 0) {
-          ushort4 p; p.x = f32_to_bf16(v[0]); p.y = f32_to_bf16(v[1]); p.z = f32_to_bf16(v[2]); p.w = f32_to_bf16(v[3]);
-          *reinterpret_cast<ushort4*>(o + gn) = p;
+          const f32x4 vv = {v[0], v[1], v[2], v[3]};               // hardware conversion (nearest even), two instructions
+          *reinterpret_cast<bf16x4*>(o + gn) = __builtin_convertvector(vv, bf16x4);
         } else {
           for (int e = 0; e < 4; ++e) if (gn + e < N) o[gn + e] = f32_to_bf16(v[e]);
         }

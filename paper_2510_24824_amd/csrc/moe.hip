@@ -888,9 +888,9 @@ __global__ __launch_bounds__(512) void k_moe_gemm_tile(const bf16_t* __restrict_
         if (gn >= N) continue;                       // N is a multiple of 16: whole groups of 4 columns
         float v[4];
 #pragma unroll
-        for (int x = 0; x < 4; ++x) { const float gt = acc[i][j][x]; v[x] = gt / (1.0f + expf(-gt)) * acc[i][j + NT / 2][x]; }
-        ushort4 pk; pk.x = f32_to_bf16(v[0]); pk.y = f32_to_bf16(v[1]); pk.z = f32_to_bf16(v[2]); pk.w = f32_to_bf16(v[3]);
-        *reinterpret_cast<ushort4*>(o + gn) = pk;
+        for (int x = 0; x < 4; ++x) { const float gt = acc[i][j][x]; v[x] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * acc[i][j + NT / 2][x]; }   // (as the dense tile kernel: the result is rounded to bf16)
+        const f32x4 vv = {v[0], v[1], v[2], v[3]};                 // hardware conversion (nearest even), two instructions
+        *reinterpret_cast<bf16x4*>(o + gn) = __builtin_convertvector(vv, bf16x4);
       }
     } else {
       const int pr = out_pr[i];
