@@ -1321,7 +1321,7 @@ __global__ __launch_bounds__(512) void k_moe_gemm_mx_tile(const uint8_t* __restr
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
           const float gt = acc[i][j][x];
-          h[j][x] = gt / (1.0f + expf(-gt)) * acc[i][2 + j][x];
+          h[j][x] = gt * __builtin_amdgcn_rcpf(1.0f + __expf(-gt)) * acc[i][2 + j][x];   // (fast forms: the value is rounded to e4m3)
           amax = fmaxf(amax, fabsf(h[j][x]));
         }
       amax = row4_max_f32(amax);
