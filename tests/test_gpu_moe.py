@@ -50,6 +50,8 @@ CASES = [
                                                        # three chunks of the row over four waves
     (B.PLT_BF16,  2085, 640, 64,   24, 3, 0.05, 0.0),  # matrix-core router at a prefill-sized row count: two row blocks per
                                                        # wave, ragged last workgroup, five chunks over four waves
+    (B.PLT_BF16,  512, 128,  64,   8,  8, 0.05, 0.0),  # the smallest batch that takes the matrix-core router; every expert
+                                                       # selected by every row (k = E: the top-k loop runs the logits dry)
 ]
 
 
