@@ -8,7 +8,10 @@
  *   - "dev" pointers are HIP device pointers owned by the caller (the library never frees
  *     them); "host" pointers are ordinary host memory.  The stream handed to plt_init is the
  *     caller's hipStream_t (NULL = default stream); all work is asynchronous on it except the
- *     export / import / debug hooks, which synchronise the stream.
+ *     export / import / debug hooks (the ones that take host pointers), which synchronise the stream.
+ *     plt_init and plt_kv_alloc are the only calls that allocate device memory (small tables and
+ *     the per-step activation scratch); plt_prefill and plt_decode_step allocate nothing, never
+ *     synchronise and clear memory with kernels only, so their launches may be captured in a HIP graph.
  *   - Matrices are row-major [out_features, in_features] (y = W x).  dtype PLT_F32 keeps
  *     weights, caches and GEMM inputs in float; PLT_BF16 keeps them in bfloat16 with float
  *     accumulation, a float residual stream and float softmax statistics.
@@ -29,8 +32,9 @@
  * With n_experts > 0 the feed-forward of every layer is a mixture of SwiGLU experts [appendix,
  * "MoE Models Recipe": k of E experts per token].  The paper does not print the router; the reading
  * taken is: logits r = W_r b on the normed row b, p = softmax(r) over all E experts, the k experts
- * with the largest logits are evaluated (equal logits: lowest index first) and their outputs are
- * summed with weights p_e as they are (not renormalised).
+ * with the largest p are evaluated (equal p: lowest index first; softmax is monotone, so the device
+ * takes the same decision on the float logits r) and their outputs are summed with weights p_e as
+ * they are (not renormalised).
  */
 #ifndef PLT_H_
 #define PLT_H_
@@ -141,8 +145,8 @@ size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ctx);
 size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_t n_ctx);
 
 /* Binds the cache layout to the caller's device buffer (>= plt_kv_bytes, 256-byte aligned),
- * clears it, and allocates the per-step activation scratch (the only hipMalloc besides
- * plt_prefill's temporary workspace).  [Sec. 2.2.2: one shared cache + (L-1) windows] */
+ * clears it, and allocates the per-step activation scratch (the library's only hipMalloc besides
+ * plt_init's small tables).  [Sec. 2.2.2: one shared cache + (L-1) windows] */
 int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* dev_buf, size_t nbytes,
                  plt_kv** out);
 void plt_kv_free(plt_kv* kv);
@@ -150,9 +154,16 @@ void plt_kv_free(plt_kv* kv);
 /* Prefill [Alg. 1 l.1-3 = Alg. 2 forward]: consumes dev_tokens [batch, n] (int32, row-major),
  * fills the shared cache for positions 0..n-1, the windows and the carried states, and
  * writes the greedy next token of every sequence to dev_next [batch] and, if not NULL, the
- * last position's logits to dev_logits [batch, vocab] (float).  Restarts the kv object. */
+ * last position's logits to dev_logits [batch, vocab] (float).  Restarts the kv object.
+ * Loop-major over the whole prompt, i.e. the sequential execution of the method (loop l of every
+ * position before loop l + 1 of any), in chunks of whole sequences (about 16384 rows at a time).
+ * dev_workspace: caller-owned device buffer (256-byte aligned) of at least
+ * plt_prefill_workspace_bytes(m, kv, n) bytes for one chunk's activations; its contents are
+ * undefined afterwards.  Asynchronous on the model's stream; PLT_ENOMEM if the workspace is too
+ * small, PLT_ECTXFULL if n > max_ctx (no state change in either case). */
+size_t plt_prefill_workspace_bytes(const plt_model* m, const plt_kv* kv, int32_t n);
 int plt_prefill(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t n,
-                int32_t* dev_next, float* dev_logits);
+                int32_t* dev_next, float* dev_logits, void* dev_workspace, size_t workspace_bytes);
 
 /* One decode step [Alg. 1 l.5-9]: consumes the newest token of every sequence
  * (dev_tokens [batch]), runs the L loop stages of this position as one pass, appends to the
@@ -189,6 +200,16 @@ int plt_set_carry(plt_kv* kv, const float* host_src, size_t host_nbytes);
 /* Residual-stream rows after the last layer of the most recent decode step: float
  * [batch, L, d] (row l = loop l+1's output H^(l+1)[p]). */
 int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes);
+/* One layer of block f on the decode micro-batch from a GIVEN residual stream [Alg. 3 l.1-6, then the
+ * feed-forward]: host_x_in float [batch, L, d] (row (b, l) = loop l+1 of sequence b) is taken as the input of
+ * layer `layer` at the position the next plt_decode_step would consume; the layer runs exactly as inside that
+ * step (its K/V for this position are appended to the shared cache / windows of that layer), and the layer's
+ * output rows are returned in host_x_out.  The position counter does not move; the carried states and the
+ * other layers' caches are untouched.  Lets a test feed every layer the reference's layer input (per-layer
+ * teacher forcing), so that a single layer is compared at the stated tolerance without the accumulation of
+ * roundings over depth.  CLP modes only; synchronises. */
+int plt_debug_layer(plt_model* m, plt_kv* kv, int32_t layer, const float* host_x_in, float* host_x_out,
+                    size_t host_nbytes);
 
 /* Kernel-only fused decode attention [Alg. 3 l.2-5, Eq. 2; first-loop row: global only].
  * All pointers are device pointers, element type `dtype`, in the cache's native layout:

@@ -379,6 +379,9 @@ class PLTOracle:
         self._store = bf16_round if kv_bf16 else e4m3_round if kv_fp8 else (lambda a: np.asarray(a, np.float64))
         self._head = weights["emb"] if shape.tie_embeddings else weights["head"]
         self.route_margins = []     # logit gap of every routing decision taken (MoE models)
+        # bookkeeping for per-layer comparisons: when set to a list, every layer evaluated by f() appends
+        # (loop l, layer m, position p, the layer's input row, the layer's output row); no arithmetic depends on it
+        self.layer_trace = None
         # low-bit linear layers: the four projections of every layer on microscaling operands
         self.w_mx = w_mx
         if w_mx:
@@ -409,6 +412,7 @@ class PLTOracle:
                 share_only = True
         for m in range(s.n_layers):
             W = self.w["layers"][m]
+            x_in = x
             a = rmsnorm(x, W["norm1"], s.norm_eps)
             act_in = (lambda t: t)
             if self.w_mx:                       # quantised projections: dequantised weights, e4m3-block inputs
@@ -443,6 +447,8 @@ class PLTOracle:
                 x = x + moe_ffn(b, W, s.top_k, self.route_margins, hid)
             else:
                 x = x + swiglu_ffn(b, W["w_gate"], W["w_up"], W["w_down"], hid)
+            if self.layer_trace is not None:
+                self.layer_trace.append((l, m, p, x_in.copy(), x.copy()))
         return x
 
     def embed(self, t):

@@ -47,7 +47,8 @@ _SIGS = {
     "plt_kv_logical_bytes": (_Z, [_P, _I, _I]),
     "plt_kv_alloc": (C.c_int, [_P, _I, _I, _P, _Z, C.POINTER(_P)]),
     "plt_kv_free": (None, [_P]),
-    "plt_prefill": (C.c_int, [_P, _P, _P, _I, _P, _P]),
+    "plt_prefill_workspace_bytes": (_Z, [_P, _P, _I]),
+    "plt_prefill": (C.c_int, [_P, _P, _P, _I, _P, _P, _P, _Z]),
     "plt_decode_step": (C.c_int, [_P, _P, _P, _P, _P]),
     "plt_kv_position": (_I, [_P]),
     "plt_last_error": (C.c_char_p, []),
@@ -58,6 +59,7 @@ _SIGS = {
     "plt_get_carry": (C.c_int, [_P, _P, _Z]),
     "plt_set_carry": (C.c_int, [_P, _P, _Z]),
     "plt_get_hidden": (C.c_int, [_P, _P, _Z]),
+    "plt_debug_layer": (C.c_int, [_P, _P, _I, _P, _P, _Z]),
     "plt_attn_pad32": (_I, [_I]),
     "plt_attn_pad": (_I, [_I, _I]),
     "plt_attn_scratch_bytes": (_Z, [_I, _I, _I, _I, _I]),
@@ -263,15 +265,31 @@ class KV:
         self.h = h
         self.next = torch.empty(batch, dtype=torch.int32, device="cuda")
         self.logits = torch.empty(batch, model.cfg.vocab, dtype=torch.float32, device="cuda")
+        self._ws = None
 
     def prefill(self, tokens, want_logits=True):
         """tokens: int32 device tensor [batch, n]; returns (next ids, logits) device tensors."""
         assert tokens.dtype.is_floating_point is False and tokens.is_cuda and tokens.dim() == 2
         assert tokens.shape[0] == self.batch
+        import torch
         tokens = tokens.contiguous()
-        _check(lib().plt_prefill(self.model.h, self.h, _ptr(tokens), tokens.shape[1], _ptr(self.next),
-                                 _ptr(self.logits) if want_logits else None))
+        n = tokens.shape[1]
+        nb = lib().plt_prefill_workspace_bytes(self.model.h, self.h, n)
+        if nb == 0:
+            raise PltError(-1, lib().plt_last_error().decode())
+        # the workspace is the caller's: a torch buffer, kept until the kv object goes (the call is asynchronous)
+        if self._ws is None or self._ws.numel() < nb:
+            self._ws = None
+            self._ws = torch.empty(nb, dtype=torch.uint8, device="cuda")
+        _check(lib().plt_prefill(self.model.h, self.h, _ptr(tokens), n, _ptr(self.next),
+                                 _ptr(self.logits) if want_logits else None, _ptr(self._ws), self._ws.numel()))
         return self.next, (self.logits if want_logits else None)
+
+    def drop_workspace(self):
+        """Frees the prefill workspace (after a synchronisation: the prefill that used it may still be running)."""
+        import torch
+        torch.cuda.synchronize()
+        self._ws = None
 
     def decode_step(self, tokens, want_logits=True):
         tokens = tokens.contiguous()
@@ -336,10 +354,21 @@ class KV:
         _check(lib().plt_get_hidden(self.h, out.ctypes.data_as(_P), out.nbytes))
         return out
 
+    def debug_layer(self, layer, x_in):
+        """One layer of block f on the decode micro-batch from a given residual stream x_in [batch, rows, d]
+        (float32 numpy) at the position the next decode step would consume; returns the layer's output rows."""
+        x_in = np.ascontiguousarray(x_in, np.float32)
+        out = np.zeros_like(x_in)
+        _check(lib().plt_debug_layer(self.model.h, self.h, layer, x_in.ctypes.data_as(_P), out.ctypes.data_as(_P), x_in.nbytes))
+        return out
+
     def close(self):
         if self.h:
+            import torch
+            torch.cuda.synchronize()       # the workspace and the buffer go back to torch's allocator below
             lib().plt_kv_free(self.h)
             self.h = None
+            self._ws = None
 
 
 # ---- kernel-only hooks -------------------------------------------------------------------

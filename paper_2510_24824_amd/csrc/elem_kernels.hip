@@ -603,6 +603,20 @@ void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n) {
   hipLaunchKernelGGL(k_copy_f32, dim3(g), dim3(256), 0, s, x, hprev, n);
 }
 
+__global__ void k_fill_zero(uint4* __restrict__ p, size_t n16, unsigned char* __restrict__ tail, int n_tail) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  if (i < (size_t)n_tail) tail[i] = 0;
+  for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+void launch_fill_zero(hipStream_t s, void* p, size_t nbytes) {
+  if (nbytes == 0) return;
+  const size_t n16 = nbytes >> 4;
+  size_t g = (n16 + 255) / 256; if (g < 1) g = 1; if (g > 8192) g = 8192;
+  hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)g), dim3(256), 0, s, (uint4*)p, n16, (unsigned char*)p + (n16 << 4),
+                     (int)(nbytes & 15));
+}
+
 // ---- layout packs: plain [S, n, D] <-> K [S, n_pad * D] (kblk_index order) / V [S, n_pad * D] (vblk_index order) ----
 template <typename T>
 __global__ void k_pack_k(const T* __restrict__ src, T* __restrict__ dst, int n, int n_pad, int D, int unpack) {

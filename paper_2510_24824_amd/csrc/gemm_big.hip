@@ -161,11 +161,9 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
 template <int EPI, int BM, int BN, int WM, int WN>
 void tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, void* out, int M, int N, int K) {
   constexpr int LDS_BYTES = 2 * (BM + BN) * GB_BK * 2;          // two stages x (A tile + W tile)
-  static bool attr_done = false;     // one flag per template instance: more than 64 KB of dynamic LDS needs the opt-in
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  (void)attr_once;
   const int ncols = EPI == EPI_SWIGLU ? BN / 2 : BN;             // output columns per tile
   dim3 grid((N + ncols - 1) / ncols, (M + BM - 1) / BM);
   hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K);

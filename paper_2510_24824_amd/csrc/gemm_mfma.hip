@@ -313,11 +313,9 @@ int gemm_bf16_splits_any(int M, int N, int K) {
 template <int MT, int NB, int NW>
 static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K, const WsPlan& p) {
   const size_t lds = (size_t)MT * 16 * WS_LDK * sizeof(bf16_t);
-  static bool attr_done = false;     // one flag per template instance
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_wstream<MT, NB, NW>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  (void)attr_once;
   hipLaunchKernelGGL((k_gemm_wstream<MT, NB, NW>), dim3(p.n_groups, p.rbs, p.S), dim3(NW * 64), lds, s, a, w, c, M, N, K,
                      p.n_groups);
 }

@@ -398,11 +398,9 @@ template <int MT, int NB>
 static void mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
                       int M, int N, int K) {
   const size_t lds = (size_t)MT * 16 * (MX_LDA + MX_SB);
-  static bool attr_done = false;     // one flag per template instance
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_gemm_mx<MT, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_mx<MT, NB>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  (void)attr_once;
   const int S = (K + MX_KR - 1) / MX_KR, rbs = (M + MT * 16 - 1) / (MT * 16);
   const int n_grp = ((N >> 4) + NB - 1) / NB;
   const int per_cu = MT == 8 ? 1 : 2;                         // workgroups that fit a compute unit (LDS)
@@ -417,11 +415,9 @@ void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const 
                     int M, int N, int K) {
   if (gemm_mx_tile_applies(M, N, K)) {
     constexpr int LDS_BYTES = 2 * (256 * 128 + 16 * 1024);
-    static bool attr_done = false;
-    if (!attr_done) {
-      (void)hipFuncSetAttribute((const void*)k_gemm_mx_tile, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-      attr_done = true;
-    }
+    // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+    static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_mx_tile, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+    (void)attr_once;
     hipLaunchKernelGGL(k_gemm_mx_tile, dim3((N + 255) / 256, (M + 255) / 256), dim3(512), LDS_BYTES, s, a, a_sc, w, w_sc, c, M, N, K);
     return;
   }

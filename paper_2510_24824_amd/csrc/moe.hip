@@ -727,11 +727,9 @@ template <int MT, int KR, bool GU, int NS, int KH>
 static void moe_gemm_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act,
                             float* y, int R, int N, int K, int k, int E) {
   const size_t lds = (size_t)MT * 16 * (KR + 8) * sizeof(bf16_t);
-  static bool attr_done = false;     // one flag per template instance
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_moe_gemm<MT, KR, GU, NS, KH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_moe_gemm<MT, KR, GU, NS, KH>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  (void)attr_once;
   const int cols_per_wg = 4 * 16 * (GU ? NS / 2 : NS);
   hipLaunchKernelGGL((k_moe_gemm<MT, KR, GU, NS, KH>), dim3((N + cols_per_wg - 1) / cols_per_wg, E), dim3(256), lds, s, a, w,
                      mi.off, mi.pair, mi.sel_e, mi.sel_p, act, y, R, N, K, k);
@@ -917,11 +915,9 @@ template <bool GU>
 static void moe_gemm_tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, const MoeIndex& mi, bf16_t* act, float* y,
                                  int R, int N, int K, int k, int E) {
   constexpr int LDS_BYTES = 2 * (256 + 256) * 64 * 2;
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_moe_gemm_tile<GU>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_moe_gemm_tile<GU>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  (void)attr_once;
   const int ncols = GU ? 128 : 256;
   const long P = (long)R * k;
   dim3 grid((N + ncols - 1) / ncols, (unsigned)(P / 256 + E));
@@ -1154,11 +1150,9 @@ template <int MT, bool GU>
 static void moe_gemm_mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc,
                                const MoeIndex& mi, uint8_t* act, uint8_t* act_sc, float* y, int R, int N, int K, int k, int E) {
   const size_t lds = (size_t)MT * 16 * (MX_LDA + MX_SB);
-  static bool attr_done = false;     // one flag per template instance
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_moe_gemm_mx<MT, GU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_moe_gemm_mx<MT, GU>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  (void)attr_once;
   const int cols_per_wg = GU ? 128 : 256;
   hipLaunchKernelGGL((k_moe_gemm_mx<MT, GU>), dim3((N + cols_per_wg - 1) / cols_per_wg, E), dim3(256), lds, s, a, a_sc, w, w_sc,
                      mi.off, mi.pair, mi.sel_e, mi.sel_p, act, act_sc, y, R, N, K, k);
@@ -1354,11 +1348,9 @@ template <bool GU>
 static void moe_gemm_mx_tile_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc,
                                     const MoeIndex& mi, uint8_t* act, uint8_t* act_sc, float* y, int R, int N, int K, int k, int E) {
   constexpr int LDS_BYTES = 2 * (256 * 128 + 16 * 1024);
-  static bool attr_done = false;
-  if (!attr_done) {
-    (void)hipFuncSetAttribute((const void*)k_moe_gemm_mx_tile<GU>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-    attr_done = true;
-  }
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_moe_gemm_mx_tile<GU>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  (void)attr_once;
   const int ncols = GU ? 128 : 256;
   const long P = (long)R * k;
   dim3 grid((N + ncols - 1) / ncols, (unsigned)(P / 256 + E));

@@ -444,14 +444,17 @@ static int run_gemm_mx(plt_model* m, const Work& wk, const void* w, const uint8_
 template <typename T>
 static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap rm, int cache, int variant,
                        KvView loc /*prefill local K/V + b0*/, int Bc, int n_prefill, int attn_L,
-                       const float* next_gain /*norm applied after the last layer, or null*/) {
-  // Runs all layers of block f on the R rows in wk.x (a = RMSNorm(x) is already in wk.a).
+                       const float* next_gain /*norm applied after the last layer, or null*/,
+                       int layer_beg = 0, int layer_end = -1 /* -1: all layers */) {
+  // Runs layers layer_beg .. layer_end - 1 of block f on the R rows in wk.x (a = RMSNorm(x) with the first of these
+  // layers' gain is already in wk.a).
   const plt_config& c = m->cfg;
   hipStream_t s = m->stream;
   const int d = c.d_model, Hq = c.n_heads, Hkv = c.n_kv_heads, D = c.head_dim, F = c.ffn_hidden;
   const int Nqkv = (Hq + 2 * Hkv) * D;
   Dims dm{rm.prefill ? Bc : kv->B, attn_L, Hq, Hkv, D, d, F, c.vocab};
-  for (int l = 0; l < c.n_layers; ++l) {
+  if (layer_end < 0) layer_end = c.n_layers;
+  for (int l = layer_beg; l < layer_end; ++l) {
     const LayerW& w = m->layers[l];
     KvView v = kv_view(kv, l, cache);
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
@@ -583,8 +586,13 @@ extern "C" int plt_decode_step(plt_model* m, plt_kv* kv, const int32_t* dev_toke
   if (kv->pos >= kv->max_ctx) return fail(PLT_ECTXFULL, "plt_decode_step: context full (%d positions)", kv->max_ctx);
   int rc = m->cfg.dtype == PLT_BF16 ? decode_step_t<bf16_t>(m, kv, dev_tokens, dev_next, dev_logits)
                                     : decode_step_t<float>(m, kv, dev_tokens, dev_next, dev_logits);
-  if (rc != PLT_OK) return rc;
-  HIP_TRY(hipGetLastError());
+  if (rc == PLT_OK && hipGetLastError() != hipSuccess) rc = fail(PLT_EHIP, "plt_decode_step: a kernel launch failed");
+  if (rc != PLT_OK) {
+    // some launches may have run (device-side position counter included): the host and device views of the
+    // position can no longer be trusted, so the object asks for plt_prefill / plt_kv_set_position again
+    kv->started = false;
+    return rc;
+  }
   kv->pos += 1;
   return PLT_OK;
 }
@@ -592,18 +600,22 @@ extern "C" int plt_decode_step(plt_model* m, plt_kv* kv, const int32_t* dev_toke
 // ------------------------------------------------------------------------------ prefill
 static const int PREFILL_ROWS = 16384;   // activation rows per chunk of whole sequences
 
-template <typename T>
-static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n, int32_t* dev_next,
-                     float* dev_logits) {
+// Layout of the prefill workspace: one chunk's activation buffers, carved from one caller buffer.
+struct PrefillPlan {
+  int Bc, Rc, n_pad_loc;
+  size_t o_x, o_h, o_a, o_g, o_q, o_z, o_y, o_act, o_ac, o_as, o_hs, o_moe, o_kl, o_vl, o_tmp, total;
+  size_t kv_loc_bytes, hs_bytes;
+};
+static PrefillPlan prefill_plan(const plt_model* m, const plt_kv* kv, int n) {
   const plt_config& c = m->cfg;
-  hipStream_t s = m->stream;
   const int B = kv->B, L = c.n_loops, d = c.d_model, Hq = c.n_heads, Hkv = c.n_kv_heads, D = c.head_dim,
             F = c.ffn_hidden, V = c.vocab, es = m->es, kes = m->kes;
   const int Nqkv = (Hq + 2 * Hkv) * D;
-  int Bc = PREFILL_ROWS / n; if (Bc < 1) Bc = 1; if (Bc > B) Bc = B;
-  const int Rc = Bc * n;
-  if (Rc > 60000) return fail(PLT_EINVAL, "plt_prefill: prompt too long (%d positions; limit 60000)", n);
-  const int n_pad_loc = pad_kv(n, m->kv8);
+  PrefillPlan p;
+  p.Bc = PREFILL_ROWS / n; if (p.Bc < 1) p.Bc = 1; if (p.Bc > B) p.Bc = B;
+  p.Rc = p.Bc * n;
+  p.n_pad_loc = pad_kv(n, m->kv8);
+  const int Rc = p.Rc, Bc = p.Bc;
   size_t go = gemm_out_need(c, Rc, Nqkv, d), t;
   if ((t = gemm_out_need(c, Rc, d, Hq * D)) > go) go = t;
   const int E = c.n_experts, topk = E > 0 ? c.top_k : 1;
@@ -614,31 +626,45 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
     if ((t = gemm_out_need(c, Rc, d, F)) > go) go = t;
   }
   if ((t = gemm_out_need(c, Bc, V, d, true)) > go) go = t;
-  // one temporary workspace, carved into the chunk's activation buffers
   size_t off = 0;
   auto carve = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   const size_t wes = m->mx ? 4 : es;      // low-bit models keep projection inputs as float until they are quantised
-  const size_t o_x = carve((size_t)Rc * d * 4), o_h = carve((size_t)Rc * d * 4), o_a = carve((size_t)Rc * d * wes),
-               o_g = carve(go * 4), o_q = carve((size_t)Rc * Hq * D * es), o_z = carve((size_t)Rc * Hq * 4),
-               o_y = carve((size_t)Rc * Hq * D * es), o_act = carve((size_t)Rc * topk * F * wes),
-               o_ac = carve(m->mx ? (size_t)Rc * mx_max_k(c) : 256), o_as = carve(m->mx ? (size_t)Rc * mx_ascale_row_bytes(mx_max_k(c)) : 256),
-               o_hs = carve(m->mx && E > 0 ? (size_t)Rc * topk * mx_ascale_row_bytes(F) : 256),
-               o_moe = carve(E > 0 ? moe_index_bytes(Rc, topk, E) : 256),
-               o_kl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes), o_vl = carve((size_t)Bc * Hkv * n_pad_loc * D * kes),
-               o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
-  char* ws = nullptr;
-  hipError_t e = hipMalloc((void**)&ws, off);
-  if (e != hipSuccess) return fail(PLT_ENOMEM, "plt_prefill: workspace of %zu bytes: %s", off, hipGetErrorString(e));
-  (void)hipMemsetAsync(ws + o_kl, 0, (size_t)2 * align256((size_t)Bc * Hkv * n_pad_loc * D * kes), s);
-  Work wk{(float*)(ws + o_x), ws + o_a, (float*)(ws + o_g), ws + o_q, (float*)(ws + o_z), ws + o_y, ws + o_act,
-          (float*)(ws + o_tmp), ws + o_moe, (uint8_t*)(ws + o_ac), (uint8_t*)(ws + o_as), (uint8_t*)(ws + o_hs)};
-  if (m->mx && E > 0) (void)hipMemsetAsync(ws + o_hs, 0, (size_t)Rc * topk * mx_ascale_row_bytes(F), s);
-  float* hprev = (float*)(ws + o_h);
+  p.kv_loc_bytes = (size_t)Bc * Hkv * p.n_pad_loc * D * kes;
+  p.hs_bytes = m->mx && E > 0 ? (size_t)Rc * topk * mx_ascale_row_bytes(F) : 0;
+  p.o_x = carve((size_t)Rc * d * 4); p.o_h = carve((size_t)Rc * d * 4); p.o_a = carve((size_t)Rc * d * wes);
+  p.o_g = carve(go * 4); p.o_q = carve((size_t)Rc * Hq * D * es); p.o_z = carve((size_t)Rc * Hq * 4);
+  p.o_y = carve((size_t)Rc * Hq * D * es); p.o_act = carve((size_t)Rc * topk * F * wes);
+  p.o_ac = carve(m->mx ? (size_t)Rc * mx_max_k(c) : 256);
+  p.o_as = carve(m->mx ? (size_t)Rc * mx_ascale_row_bytes(mx_max_k(c)) : 256);
+  p.o_hs = carve(p.hs_bytes ? p.hs_bytes : 256);
+  p.o_moe = carve(E > 0 ? moe_index_bytes(Rc, topk, E) : 256);
+  p.o_kl = carve(p.kv_loc_bytes); p.o_vl = carve(p.kv_loc_bytes);
+  p.o_tmp = carve((L > 1 && is_plt(c) && es == 2) ? (size_t)Rc * Hq * D * 4 : 256);
+  p.total = off;
+  return p;
+}
+
+template <typename T>
+static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n, int32_t* dev_next,
+                     float* dev_logits, char* ws) {
+  const plt_config& c = m->cfg;
+  hipStream_t s = m->stream;
+  const int B = kv->B, L = c.n_loops, d = c.d_model, V = c.vocab;
+  const PrefillPlan pl = prefill_plan(m, kv, n);
+  const int Bc = pl.Bc;
+  // the chunk's own-loop K/V (and, low-bit mixture-of-experts models, the pad bytes of the hidden rows' scales) start
+  // from zero; cleared by a fill kernel, not a memset node, so that the call may be captured in a HIP graph
+  launch_fill_zero(s, ws + pl.o_kl, pl.o_vl + pl.kv_loc_bytes - pl.o_kl);
+  if (pl.hs_bytes) launch_fill_zero(s, ws + pl.o_hs, pl.hs_bytes);
+  Work wk{(float*)(ws + pl.o_x), ws + pl.o_a, (float*)(ws + pl.o_g), ws + pl.o_q, (float*)(ws + pl.o_z), ws + pl.o_y,
+          ws + pl.o_act, (float*)(ws + pl.o_tmp), ws + pl.o_moe, (uint8_t*)(ws + pl.o_ac), (uint8_t*)(ws + pl.o_as),
+          (uint8_t*)(ws + pl.o_hs)};
+  float* hprev = (float*)(ws + pl.o_h);
   for (int b0 = 0; b0 < B; b0 += Bc) {
     const int bc = b0 + Bc <= B ? Bc : B - b0;
     const int R = bc * n;
     const int32_t* toks = dev_tokens + (size_t)b0 * n;
-    KvView loc{}; loc.k_loc = ws + o_kl; loc.v_loc = ws + o_vl; loc.n_pad_loc = n_pad_loc; loc.b0 = b0;
+    KvView loc{}; loc.k_loc = ws + pl.o_kl; loc.v_loc = ws + pl.o_vl; loc.n_pad_loc = pl.n_pad_loc; loc.b0 = b0;
     for (int l = 0; l < L; ++l) {
       RowMap rm{1, n, is_clp(c) ? l : 0, nullptr};
       if (is_clp(c)) {
@@ -663,19 +689,34 @@ static int prefill_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int n,
     head_and_argmax<T>(m, kv, wk, bc, n, n - 1, dev_next + b0, dev_logits ? dev_logits + (size_t)b0 * V : nullptr);
   }
   launch_pos_set(s, kv->pos_dev, B, n, 0);
-  e = hipStreamSynchronize(s);
-  (void)hipFree(ws);
-  if (e != hipSuccess) return fail(PLT_EHIP, "plt_prefill: %s", hipGetErrorString(e));
   return PLT_OK;
 }
 
+static int prefill_check(const plt_model* m, const plt_kv* kv, int32_t n, const char* who) {
+  if (!m || !kv || kv->m != m) return fail(PLT_EINVAL, "%s: bad model / kv object", who);
+  if (n < 1) return fail(PLT_EINVAL, "%s: empty prompt", who);
+  if (n > kv->max_ctx) return fail(PLT_ECTXFULL, "%s: prompt of %d exceeds max_ctx %d", who, n, kv->max_ctx);
+  int Bc = PREFILL_ROWS / n; if (Bc < 1) Bc = 1; if (Bc > kv->B) Bc = kv->B;
+  if ((long)Bc * n > 60000) return fail(PLT_EINVAL, "%s: prompt too long (%d positions; limit 60000)", who, n);
+  return PLT_OK;
+}
+
+extern "C" size_t plt_prefill_workspace_bytes(const plt_model* m, const plt_kv* kv, int32_t n) {
+  if (prefill_check(m, kv, n, "plt_prefill_workspace_bytes") != PLT_OK) return 0;
+  return prefill_plan(m, kv, n).total;
+}
+
 extern "C" int plt_prefill(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t n, int32_t* dev_next,
-                           float* dev_logits) {
-  if (!m || !kv || kv->m != m || !dev_tokens || !dev_next) return fail(PLT_EINVAL, "plt_prefill: bad argument");
-  if (n < 1) return fail(PLT_EINVAL, "plt_prefill: empty prompt");
-  if (n > kv->max_ctx) return fail(PLT_ECTXFULL, "plt_prefill: prompt of %d exceeds max_ctx %d", n, kv->max_ctx);
-  int rc = m->cfg.dtype == PLT_BF16 ? prefill_t<bf16_t>(m, kv, dev_tokens, n, dev_next, dev_logits)
-                                    : prefill_t<float>(m, kv, dev_tokens, n, dev_next, dev_logits);
+                           float* dev_logits, void* dev_workspace, size_t workspace_bytes) {
+  if (!dev_tokens || !dev_next) return fail(PLT_EINVAL, "plt_prefill: null tokens / next pointer");
+  int rc = prefill_check(m, kv, n, "plt_prefill");
+  if (rc != PLT_OK) return rc;
+  const size_t need = prefill_plan(m, kv, n).total;
+  if (!dev_workspace || (((uintptr_t)dev_workspace) & 255)) return fail(PLT_EINVAL, "plt_prefill: workspace must be a 256-byte aligned device buffer");
+  if (workspace_bytes < need) return fail(PLT_ENOMEM, "plt_prefill: workspace has %zu bytes, this prompt needs %zu", workspace_bytes, need);
+  kv->started = false;              // a failure below leaves the object in need of a new prefill
+  rc = m->cfg.dtype == PLT_BF16 ? prefill_t<bf16_t>(m, kv, dev_tokens, n, dev_next, dev_logits, (char*)dev_workspace)
+                                : prefill_t<float>(m, kv, dev_tokens, n, dev_next, dev_logits, (char*)dev_workspace);
   if (rc != PLT_OK) return rc;
   HIP_TRY(hipGetLastError());
   kv->pos = n; kv->started = true;
@@ -792,6 +833,36 @@ extern "C" int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes) {
   return copy_sync(kv, host_dst, kv->x, need, hipMemcpyDeviceToHost);
 }
 
+// One layer of block f on the decode micro-batch, from a given residual stream (test hook): what the decode step
+// does for layer `layer` at the position the next plt_decode_step would consume, cache append included.
+template <typename T>
+static void debug_layer_t(plt_model* m, plt_kv* kv, int layer) {
+  const plt_config& c = m->cfg;
+  const int B = kv->B, L = c.n_loops, R = B * L;
+  Work wk{kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, nullptr, kv->moe_idx, kv->a_codes, kv->a_scales, kv->act_sc};
+  KvView none{}; none.b0 = 0;
+  RowMap rm{0, L, 0, kv->pos_dev};
+  norm_to_a<T>(m, wk, nullptr, 0, 0, m->layers[layer].norm1, R);
+  const int variant = c.mode == PLT_MODE_CLP ? V_PLT : (c.mode == PLT_MODE_CLP_SHARE_ONLY ? V_SHARE_ONLY : V_OWN_KV);
+  stack_pass<T>(m, kv, wk, R, rm, 0, variant, none, 0, 0, L, nullptr, layer, layer + 1);
+}
+extern "C" int plt_debug_layer(plt_model* m, plt_kv* kv, int32_t layer, const float* host_x_in, float* host_x_out,
+                               size_t host_nbytes) {
+  if (!m || !kv || kv->m != m || !host_x_in || !host_x_out) return fail(PLT_EINVAL, "plt_debug_layer: bad argument");
+  const plt_config& c = m->cfg;
+  if (!is_clp(c)) return fail(PLT_EINVAL, "plt_debug_layer: not available in vanilla-loop mode");
+  if (layer < 0 || layer >= c.n_layers) return fail(PLT_EINVAL, "plt_debug_layer: layer out of range");
+  if (!kv->started) return fail(PLT_ESTATE, "plt_debug_layer: plt_prefill (or plt_kv_set_position) must come first");
+  if (kv->pos >= kv->max_ctx) return fail(PLT_ECTXFULL, "plt_debug_layer: context full (%d positions)", kv->max_ctx);
+  const size_t need = (size_t)kv->B * c.n_loops * c.d_model * 4;
+  if (host_nbytes != need) return fail(PLT_EINVAL, "plt_debug_layer: host buffers must have %zu bytes", need);
+  int rc = copy_sync(kv, kv->x, host_x_in, need, hipMemcpyHostToDevice);
+  if (rc != PLT_OK) return rc;
+  if (c.dtype == PLT_BF16) debug_layer_t<bf16_t>(m, kv, layer); else debug_layer_t<float>(m, kv, layer);
+  HIP_TRY(hipGetLastError());
+  return copy_sync(kv, host_x_out, kv->x, need, hipMemcpyDeviceToHost);
+}
+
 // ---- kernel-only hooks ----
 __global__ void k_sum_slabs(const float* __restrict__ p, float* __restrict__ c, int S, size_t n);
 extern "C" int32_t plt_attn_pad32(int32_t n) { return pad32(n); }
@@ -804,21 +875,21 @@ extern "C" size_t plt_attn_scratch_bytes(int32_t B, int32_t L, int32_t Hq, int32
   return s > p ? s : p;
 }
 
-extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
+// shared by plt_attn_decode and plt_attn_decode_static: argument checks, then the launches on `scratch`
+static int attn_decode_checked(const char* who, int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
                                int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring, const void* q,
                                const void* k_share, const void* v_share, const void* k_ring, const void* v_ring,
-                               const float* z, void* y, void* scratch, size_t scratch_bytes, int32_t n_splits,
-                               void* hip_stream) {
-  if (dtype != PLT_F32 && dtype != PLT_BF16 && dtype != PLT_FP8_E4M3) return fail(PLT_EINVAL, "plt_attn_decode: unknown dtype");
+                               const float* z, void* y, void* scratch, size_t scratch_bytes, bool exact_scratch,
+                               int32_t n_splits, void* hip_stream) {
+  if (dtype != PLT_F32 && dtype != PLT_BF16 && dtype != PLT_FP8_E4M3) return fail(PLT_EINVAL, "%s: unknown dtype", who);
   const bool kv8 = dtype == PLT_FP8_E4M3;
   if (B < 1 || L < 1 || L > 16 || Hq < 1 || Hkv < 1 || Hq % Hkv || (D != 64 && D != 128))
-    return fail(PLT_EINVAL, "plt_attn_decode: bad shape");
-  if (n_ctx < 1 || n_ctx > n_alloc) return fail(PLT_EINVAL, "plt_attn_decode: need 1 <= n_ctx <= n_alloc");
-  if (L > 1 && (w < 1 || n_ring < 1 || n_ring > w)) return fail(PLT_EINVAL, "plt_attn_decode: need 1 <= n_ring <= w");
+    return fail(PLT_EINVAL, "%s: bad shape", who);
+  if (n_ctx < 1 || n_ctx > n_alloc) return fail(PLT_EINVAL, "%s: need 1 <= n_ctx <= n_alloc", who);
+  if (L > 1 && (w < 1 || n_ring < 1 || n_ring > w)) return fail(PLT_EINVAL, "%s: need 1 <= n_ring <= w", who);
   if (!q || !k_share || !v_share || !y || !scratch || (L > 1 && (!k_ring || !v_ring || !z)))
-    return fail(PLT_EINVAL, "plt_attn_decode: null pointer");
-  if (scratch_bytes < plt_attn_scratch_bytes(B, L, Hq, Hkv, D)) return fail(PLT_ENOMEM, "plt_attn_decode: scratch too small");
-  if ((long)B * L > 60000) return fail(PLT_EINVAL, "plt_attn_decode: B * L too large");
+    return fail(PLT_EINVAL, "%s: null pointer", who);
+  if ((long)B * L > 60000) return fail(PLT_EINVAL, "%s: B * L too large", who);
   hipStream_t s = (hipStream_t)hip_stream;
   KvView v{};
   v.k_share = (void*)k_share; v.v_share = (void*)v_share; v.k_ring = (void*)k_ring; v.v_ring = (void*)v_ring;
@@ -826,17 +897,33 @@ extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, 
   Dims dm{B, L, Hq, Hkv, D, 0, 0, 0};
   if (dtype == PLT_BF16 || kv8) {
     if (n_splits <= 0) n_splits = attn_mfma_default_splits(B, Hkv, L, Hq / Hkv, n_ctx, kv8);
+    if (n_splits > 64) n_splits = 64;
+    // exact_scratch: the buffer is laid out for exactly the splits of this call (the library's own static buffer);
+    // otherwise for the 64 splits plt_attn_scratch_bytes sizes a caller's buffer for
+    const int layout_splits = exact_scratch ? n_splits : 64;
+    const size_t need = attn_mfma_scratch_bytes(B, L, Hq, Hkv, D, layout_splits);
+    if (scratch_bytes < need) return fail(PLT_ENOMEM, "%s: needs %zu bytes of scratch for %d splits, %zu available", who, need, n_splits, scratch_bytes);
     launch_attn_decode_mfma(s, (const bf16_t*)q, z, (bf16_t*)y, v, nullptr, n_ctx, L > 1 ? n_ring : 0, dm, 0,
-                            scratch, n_splits, 0, 0, kv8);
+                            scratch, n_splits, 0, 0, kv8, layout_splits);
   } else {
+    if (scratch_bytes < align256((size_t)B * 4)) return fail(PLT_ENOMEM, "%s: scratch too small", who);
     if (L > 1 && n_ring != (n_ctx < w ? n_ctx : w))
-      return fail(PLT_EINVAL, "plt_attn_decode: float path needs n_ring == min(n_ctx, w)");
+      return fail(PLT_EINVAL, "%s: float path needs n_ring == min(n_ctx, w)", who);
     launch_pos_set(s, (int32_t*)scratch, B, n_ctx - 1, 0);
     RowMap rm{0, L, 0, (const int32_t*)scratch};
     launch_attn_f32(s, (const float*)q, z, (float*)y, v, rm, B * L, dm, 0);
   }
   HIP_TRY(hipGetLastError());
   return PLT_OK;
+}
+
+extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
+                               int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring, const void* q,
+                               const void* k_share, const void* v_share, const void* k_ring, const void* v_ring,
+                               const float* z, void* y, void* scratch, size_t scratch_bytes, int32_t n_splits,
+                               void* hip_stream) {
+  return attn_decode_checked("plt_attn_decode", dtype, B, L, Hq, Hkv, D, n_alloc, n_ctx, w, n_ring, q, k_share, v_share,
+                             k_ring, v_ring, z, y, scratch, scratch_bytes, false, n_splits, hip_stream);
 }
 
 extern "C" int64_t plt_attn_k_index(int32_t dtype, int32_t pos, int32_t f, int32_t D) {

@@ -195,6 +195,8 @@ int argmax_scratch_elems(int B);   // elements of part_v and of part_i
 void launch_carry_update(hipStream_t s, const float* x, float* carry, int B, int L, int d);
 void launch_pos_set(hipStream_t s, int32_t* pos, int B, int value, int increment);
 void launch_shift_copy(hipStream_t s, const float* x, float* hprev, size_t n);
+// clears nbytes at p (16-byte aligned) with a kernel: unlike a memset node, safe inside a captured HIP graph
+void launch_fill_zero(hipStream_t s, void* p, size_t nbytes);
 template <typename T>
 void launch_pack_k(hipStream_t s, const T* src, T* dst, int S, int n, int n_pad, int D);
 template <typename T>

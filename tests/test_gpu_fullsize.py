@@ -1,5 +1,12 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times, on sampled
-sequences (sequences of a batch are independent, so the oracle checks one at a time)."""
+sequences (sequences of a batch are independent, so the oracle checks one at a time).
+
+Two comparisons per decode step.  End to end: the step's logits at the stated bf16 bar of 2e-2 max-abs.  Per layer,
+teacher-forced: every layer of the device is fed the ORACLE's input of that layer for the sampled sequences
+(plt_debug_layer) and its output rows are held to the same 2e-2 max-abs, so that a defect of a few 1e-2 in any
+single layer's residual, norm, attention or feed-forward path fails, which the end-to-end hidden state -- about
+0.2 off on values of magnitude 50 after 24 layers of bf16 roundings -- could not show.  The accumulated drift of the
+free-running hidden state is printed, labelled as accumulated, and only sanity-bounded."""
 import ctypes as C
 
 import numpy as np
@@ -9,6 +16,7 @@ import torch
 import bench
 from oracle import plt_oracle as O
 from paper_2510_24824_amd import binding as B, synth
+from tests.helpers import lively_weights, oshape
 
 pytestmark = pytest.mark.gpu
 
@@ -25,9 +33,51 @@ def oracle_step(shape, cfg, weights_host, exports, carry, token, pos):
         for l in range(cfg.n_loops - 1):
             orc.kv.kr[l, m] = e["k_ring"][l].transpose(1, 0, 2); orc.kv.vr[l, m] = e["v_ring"][l].transpose(1, 0, 2)
     orc.carry = carry.astype(np.float64).copy(); orc.pos = pos; orc.trace = []
+    orc.layer_trace = []
     nxt, lg = orc.clp_decode_step(int(token))
     oracle_step.route_margins = list(orc.route_margins)     # mixture-of-experts models: the step's routing gaps
+    # the step's layer inputs / outputs [L, layers, d] (the oracle walks loop by loop, layer by layer)
+    L, nl = cfg.n_loops, shape.n_layers
+    x_in = np.zeros((L, nl, shape.d_model)); x_out = np.zeros_like(x_in)
+    assert len(orc.layer_trace) == L * nl
+    for (l, m, p, a, b) in orc.layer_trace:
+        assert p == pos
+        x_in[l - 1, m] = a; x_out[l - 1, m] = b
+    oracle_step.layer_in, oracle_step.layer_out = x_in, x_out
     return nxt, lg, orc.trace[-1]
+
+
+ROUTING_NOISE = 4e-3        # bf16 storage of the normed row moves a router logit by about 2e-3
+ACCUMULATED_DRIFT_SANITY = 5e-2     # free-running hidden state after all layers, relative to its largest entry
+
+
+def per_layer_teacher_forced(kv, shape, cfg, pos, layer_io, tol=2e-2, skip=None):
+    """layer_io: {sequence: (x_in [L, layers, d], x_out [L, layers, d])} from the oracle.  Feeds every layer of the
+    device the oracle's layer input for those sequences (zeros for the others, whose rows are not looked at) at
+    position pos and returns the largest |device - oracle| over the sampled rows per layer; asserts each <= tol.
+    skip(seq, loop row, layer) -> True leaves that row of that layer out (used where an integer decision inside the
+    layer -- the experts chosen -- is within rounding reach and differs)."""
+    Bn, L = kv.batch, cfg.n_loops
+    worst = []
+    for m in range(shape.n_layers):
+        kv.set_position(pos)
+        xin = np.zeros((Bn, L, shape.d_model), np.float32)
+        for b, (x_in, _) in layer_io.items():
+            xin[b] = x_in[:, m]
+        out = kv.debug_layer(m, xin)
+        assert kv.position == pos
+        e = 0.0
+        for b, (x_in, x_out) in layer_io.items():
+            for l in range(L):
+                if skip is not None and skip(b, l, m):
+                    continue
+                # the float32 copy of the input is what both sides continue from
+                ref = x_out[l, m] - x_in[l, m] + xin[b, l].astype(np.float64)
+                e = max(e, float(np.max(np.abs(out[b, l] - ref))))
+        worst.append(e)
+    print("per-layer teacher-forced max-abs:", " ".join(f"{e:.1e}" for e in worst))
+    assert max(worst) <= tol, (int(np.argmax(worst)), max(worst))
+    return worst
 
 
 @pytest.mark.parametrize("kv_dtype,shape", [(0, synth.PLT_1P3B), (B.PLT_FP8_E4M3, synth.PLT_1P3B), (0, synth.PLT_DENSE_GQA)],
@@ -51,16 +101,21 @@ def test_decode_step_1p3b_L2_batch64_ctx2048_sampled(kv_dtype, shape):
     n1, lg1 = kv.decode_step(nxt.clone())
     hidden = kv.get_hidden()
     wh = bench.weights_to_host(B, cfg, blob)
+    layer_io = {}
     for b in sample:
         exports, carry, token = state[b]
         o_next, o_lg, o_hid = oracle_step(shape, cfg, wh, exports, carry, token, pos)
+        layer_io[b] = (oracle_step.layer_in, oracle_step.layer_out)
         err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
-        rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
-        print(f"seq {b}: logits max-abs {err:.3e}; hidden max rel {rel_h:.3e}; margin {np.sort(o_lg)[-1] - np.sort(o_lg)[-2]:.3e}")
+        abs_h = float(np.max(np.abs(hidden[b] - o_hid)))
+        rel_h = abs_h / float(np.max(np.abs(o_hid)))
+        print(f"seq {b}: logits max-abs {err:.3e}; accumulated hidden drift after {shape.n_layers} layers {abs_h:.3e} abs = {rel_h:.3e} of the "
+              f"largest entry (reported, not the parity bar); margin {np.sort(o_lg)[-1] - np.sort(o_lg)[-2]:.3e}")
         assert err <= 2e-2, err
-        assert rel_h <= 2e-2, rel_h            # 24 layers of bf16 roundings on a state of magnitude ~50
+        assert rel_h <= ACCUMULATED_DRIFT_SANITY, rel_h
         if np.sort(o_lg)[-1] - np.sort(o_lg)[-2] > 4e-2:
             assert int(n1[b].item()) == o_next
+    per_layer_teacher_forced(kv, shape, cfg, pos, layer_io)
     kv.close(); model.close()
 
 
@@ -88,9 +143,11 @@ def test_decode_step_L4_w128_ctx8192_sampled():
     err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
     rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
     per_row = [float(np.max(np.abs(hidden[b, l] - o_hid[l])) / np.max(np.abs(o_hid[l]))) for l in range(L)]
-    print(f"logits max-abs {err:.3e} (max |logit| {np.max(np.abs(o_lg)):.2f}); hidden max rel {rel_h:.3e}; per row {per_row}; "
-          f"max |hidden| {np.max(np.abs(o_hid)):.1f}")
-    assert err <= 2e-2 and rel_h <= 2e-2, (err, rel_h)
+    print(f"logits max-abs {err:.3e} (max |logit| {np.max(np.abs(o_lg)):.2f}); accumulated hidden drift {rel_h:.3e} of the largest "
+          f"entry (reported); per row {per_row}; max |hidden| {np.max(np.abs(o_hid)):.1f}")
+    assert err <= 2e-2 and rel_h <= ACCUMULATED_DRIFT_SANITY, (err, rel_h)
+    per_layer_teacher_forced(kv, shape, cfg, pos, {b: (oracle_step.layer_in, oracle_step.layer_out)})
+    kv.set_position(pos + 1)
     # batch independence: the same sequence alone in a batch of 1 gives the same logits (the split
     # count of the attention kernel differs, so agreement is to rounding, not bit for bit)
     kv1 = B.KV(model, 1, N)
@@ -126,8 +183,9 @@ def test_decode_step_160_rows_sampled():
     o_next, o_lg, o_hid = oracle_step(shape, cfg, wh, exports, carry[b], int(tok[b].item()), pos)
     err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
     rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
-    print(f"logits max-abs {err:.3e}; hidden max rel {rel_h:.3e}")
-    assert err <= 2e-2 and rel_h <= 2e-2, (err, rel_h)
+    print(f"logits max-abs {err:.3e}; accumulated hidden drift {rel_h:.3e} of the largest entry (reported)")
+    assert err <= 2e-2 and rel_h <= ACCUMULATED_DRIFT_SANITY, (err, rel_h)
+    per_layer_teacher_forced(kv, shape, cfg, pos, {b: (oracle_step.layer_in, oracle_step.layer_out)})
     kv.close(); model.close()
 
 
@@ -137,7 +195,8 @@ def test_decode_step_moe_8_of_64_batch64_ctx2048_sampled():
     batch 64 x L = 2 at a 2048-token context built by plt_prefill (which routes 16k rows per chunk through the
     same grouped kernels).  Sampled sequences are recomputed by the oracle from the exported state.  A
     sequence that disagrees while its smallest routing gap in this step is within reach of bf16 rounding is
-    reported and skipped; at least two of the three samples must agree."""
+    reported and its end-to-end comparison not asserted; at least two of the three samples must agree end to end, and
+    every (row, layer) pair with a routing gap above that noise must agree per layer."""
     shape = bench.with_layers(synth.PLT_MOE_1B7B, 2)
     Bn, N = 64, 2048
     pos = N - 1
@@ -154,19 +213,29 @@ def test_decode_step_moe_8_of_64_batch64_ctx2048_sampled():
     hidden = kv.get_hidden()
     wh = bench.weights_to_host(B, cfg, blob)
     clear = 0
+    layer_io, gaps = {}, {}
     for b in sample:
         exports, carry, token = state[b]
         o_next, o_lg, o_hid = oracle_step(shape, cfg, wh, exports, carry, token, pos)
-        gap = min(oracle_step.route_margins)
+        layer_io[b] = (oracle_step.layer_in, oracle_step.layer_out)
+        gaps[b] = np.array(oracle_step.route_margins).reshape(cfg.n_loops, shape.n_layers)    # the oracle walks loop by loop
+        gap = float(gaps[b].min())
         err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
         rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
-        print(f"seq {b}: smallest routing gap {gap:.3e}; logits max-abs {err:.3e}; hidden max rel {rel_h:.3e}")
-        ok = err <= 2e-2 and rel_h <= 2e-2
-        if not ok and gap < 4e-3:      # router logits are ~N(0, 0.9); bf16 activations move them by ~2e-3
+        print(f"seq {b}: smallest routing gap {gap:.3e}; logits max-abs {err:.3e}; accumulated hidden drift {rel_h:.3e} of the largest entry")
+        ok = err <= 2e-2 and rel_h <= ACCUMULATED_DRIFT_SANITY
+        if not ok and gap < ROUTING_NOISE:      # router logits are ~N(0, 0.9); bf16 activations move them by ~2e-3
+            print(f"seq {b}: a routing decision of this step is within rounding reach; the end-to-end comparison of this sequence is not asserted")
             continue
-        assert ok, (b, err, rel_h, gap)
+        assert ok, (b, err, rel_h, gap)        # a disagreement with every gap above the noise is a failure
         clear += 1
     assert clear >= 2
+    # per layer, from the oracle's layer input: every row of every layer whose routing gap is above the noise must
+    # match at the bf16 bar (a row within reach of the noise may legitimately evaluate a different expert)
+    n_skipped = sum(int(np.sum(g < ROUTING_NOISE)) for g in gaps.values())
+    per_layer_teacher_forced(kv, shape, cfg, pos, layer_io, skip=lambda b, l, m: gaps[b][l, m] < ROUTING_NOISE)
+    print(f"per-layer comparison left out {n_skipped} of {len(sample) * cfg.n_loops * shape.n_layers} (row, layer) pairs with a routing gap below {ROUTING_NOISE}")
+    assert n_skipped <= 2
     kv.close(); model.close()
 
 
@@ -284,3 +353,103 @@ def test_prefill_4x8192_L3_equals_shorter_prefill_plus_decode_steps(kv_dtype):
                 assert diff <= kv_tol * scale, (b, layer, name, diff, scale)
             print(f"seq {b} layer {layer}: shared K/V identical below position {n - m}; last {m} and rings within {kv_tol:.0%} of the largest entry")
     kv_a.close(); kv_b.close(); model.close()
+
+
+def test_decode_step_L4_w128_ctx8192_batch128_sampled():
+    """One GPU's share of the long-context configuration (L = 4, window 128, 8192-token shared KV, batch 128:
+    206 GB of shared K/V + 9.7 GB of windows resident), in the launch configuration bench.py times: one workgroup per
+    (sequence, kv head) stream, no split.  State built by plt_prefill of 128 x 8191 tokens; one sampled sequence's
+    decode step is recomputed by the oracle from the exported state: logits end to end, every layer teacher-forced."""
+    shape = synth.PLT_1P3B
+    Bn, N, L, w = 128, 8192, 4, 128
+    pos = N - 1
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, n_loops=L, window=w)
+    blob = bench.fill_weights_on_device(B, cfg, bench.SEED)
+    model = B.Model(cfg, blob)
+    free = torch.cuda.mem_get_info()[0]
+    need = model.kv_bytes(Bn, N)
+    if need > free - (12 << 30):
+        pytest.skip(f"needs {need / 2**30:.0f} GiB of KV, {free / 2**30:.0f} GiB free on this device")
+    kv = B.KV(model, Bn, N)
+    g = torch.Generator(device="cuda"); g.manual_seed(17)
+    prompt = torch.randint(0, shape.vocab, (Bn, pos), generator=g, device="cuda", dtype=torch.int32)
+    nxt, _ = kv.prefill(prompt, want_logits=False)
+    b = 77
+    exports = [kv.export(b, m, pos) for m in range(shape.n_layers)]
+    carry = kv.get_carry()
+    tok = nxt.clone()
+    n1, lg1 = kv.decode_step(tok)
+    hidden = kv.get_hidden()
+    wh = bench.weights_to_host(B, cfg, blob)
+    o_next, o_lg, o_hid = oracle_step(shape, cfg, wh, exports, carry[b], int(tok[b].item()), pos)
+    err = float(np.max(np.abs(lg1[b].float().cpu().numpy() - o_lg)))
+    rel_h = float(np.max(np.abs(hidden[b] - o_hid)) / np.max(np.abs(o_hid)))
+    print(f"seq {b} of {Bn}: logits max-abs {err:.3e}; accumulated hidden drift {rel_h:.3e} of the largest entry (reported)")
+    assert err <= 2e-2 and rel_h <= ACCUMULATED_DRIFT_SANITY, (err, rel_h)
+    if np.sort(o_lg)[-1] - np.sort(o_lg)[-2] > 4e-2:
+        assert int(n1[b].item()) == o_next
+    per_layer_teacher_forced(kv, shape, cfg, pos, {b: (oracle_step.layer_in, oracle_step.layer_out)})
+    kv.close(); model.close()
+
+
+def test_prefill_4x8192_L3_narrow_model_against_oracle():
+    """The long-prompt prefill path itself against the oracle: 4 prompts of 8192 tokens at L = 3, window 64 (the
+    prefill workload's batch, length, loops and window) on a narrow model (1 layer, d = 128, 2 query heads / 1 kv
+    head of 128) that the position-by-position oracle walks in seconds.  8192 positions per sequence make plt_prefill
+    run two chunks of two sequences (16384 rows each), 64 query tiles of 128 rows and up to 128 key steps of 64 per
+    sequence.  For one sequence of each chunk the oracle consumes the same prompt by Alg. 1's micro-batch rule (equal
+    to Alg. 2's loop-major pass: pinned at 1e-10 in the oracle's own tests) and is compared with the device's: shared
+    K/V at EVERY position (the keys of layer 0 depend on the embedding only, the point is the cache indexing of both
+    chunks), windows, carried states H^(1), H^(2) of the last position, last-position logits; and, for the sequence
+    of the last chunk, the residual rows H^(3)[p] and H^(2)[p] of every position p, which plt_prefill leaves in its
+    workspace (rows of the last chunk, at offset 0 and at the next multiple of 256 bytes after them)."""
+    shape = synth.ModelShape(n_layers=1, d_model=128, n_heads=2, n_kv_heads=1, head_dim=128, ffn_hidden=256,
+                             vocab=512, n_loops=3, window=64)
+    Bn, n, L = 4, 8192, 3
+    weights = lively_weights(shape, 21, bf16=True, std=0.05)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    kv = B.KV(model, Bn, n + 1)
+    prompts = synth.token_ids((Bn, n), shape.vocab, 22)
+    nxt, lg = kv.prefill(torch.from_numpy(np.ascontiguousarray(prompts, np.int32)).cuda())
+    torch.cuda.synchronize()
+    nxt = nxt.cpu().numpy(); lg = lg.float().cpu().numpy()
+    carry = kv.get_carry()
+    d = shape.d_model
+    Bc = max(1, min(Bn, 16384 // n)); rows = Bc * n
+    assert Bc == 2, "two chunks of two sequences are the point of this case"
+    ws = kv._ws
+    x_last = ws[:rows * d * 4].view(torch.float32).reshape(Bc, n, d).cpu().numpy()          # H^(L) of the last chunk
+    off = (rows * d * 4 + 255) // 256 * 256
+    x_prev = ws[off:off + rows * d * 4].view(torch.float32).reshape(Bc, n, d).cpu().numpy()  # H^(L-1) of the last chunk
+    wf = {k: np.asarray(v, np.float64) for k, v in weights.items() if k != "layers"}     # (conversion once, not per call)
+    wf["layers"] = [{k: np.asarray(v, np.float64) for k, v in lw.items()} for lw in weights["layers"]]
+    for b in (1, 3):             # last sequence of the first chunk, last sequence of the second
+        orc = O.PLTOracle(oshape(shape), wf, kv_bf16=True)
+        o_next, o_lg = orc.clp_prefill(list(prompts[b]), n + 1)
+        H = np.stack(orc.trace)                                   # [n, L, d]
+        e_lg = float(np.max(np.abs(lg[b] - o_lg)))
+        e_c = float(np.max(np.abs(carry[b] - H[n - 1, :L - 1])))
+        e = kv.export(b, 0, n)
+        e_ks = float(np.max(np.abs(e["k_share"] - orc.kv.ks[0, :n].transpose(1, 0, 2))))
+        e_vs = float(np.max(np.abs(e["v_share"] - orc.kv.vs[0, :n].transpose(1, 0, 2))))
+        e_kr = float(np.max(np.abs(e["k_ring"] - orc.kv.kr[:, 0].transpose(0, 2, 1, 3))))
+        e_vr = float(np.max(np.abs(e["v_ring"] - orc.kv.vr[:, 0].transpose(0, 2, 1, 3))))
+        print(f"seq {b}: logits {e_lg:.2e} (max |logit| {np.max(np.abs(o_lg)):.2f}); carry {e_c:.2e} (max |H| {np.max(np.abs(H)):.2f}); "
+              f"shared K {e_ks:.2e} V {e_vs:.2e}; window K {e_kr:.2e} V {e_vr:.2e}")
+        # K/V: both sides round the same float value to bf16 up to float32-vs-float64 noise: equal or one bf16 step apart
+        kmax = float(np.max(np.abs(orc.kv.ks[0, :n])))
+        assert max(e_ks, e_kr) <= 2.0 ** -7 * kmax and max(e_vs, e_vr) <= 2.0 ** -7 * float(np.max(np.abs(orc.kv.vs[0, :n])))
+        assert e_lg <= 2e-2 and e_c <= 2e-2, (b, e_lg, e_c)
+        if np.sort(o_lg)[-1] - np.sort(o_lg)[-2] > 4e-2:
+            assert int(nxt[b]) == o_next
+        if b >= Bn - Bc:
+            i = b - (Bn - Bc)
+            e3 = np.max(np.abs(x_last[i] - H[:, L - 1]), axis=1)          # per position
+            e2 = np.max(np.abs(x_prev[i] - H[:, L - 2]), axis=1)
+            worst3, worst2 = int(np.argmax(e3)), int(np.argmax(e2))
+            print(f"seq {b}: H^(3) over all {n} positions max-abs {e3.max():.2e} (at position {worst3}); H^(2) {e2.max():.2e} (at {worst2}); "
+                  f"tile and chunk borders 127/128: {e3[127]:.1e}/{e3[128]:.1e}, 63/64/65 (window): {e3[63]:.1e}/{e3[64]:.1e}/{e3[65]:.1e}, "
+                  f"8191: {e3[8191]:.1e}")
+            assert e3.max() <= 2e-2 and e2.max() <= 2e-2, (b, float(e3.max()), float(e2.max()))
+    kv.close(); model.close()
