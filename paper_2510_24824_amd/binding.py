@@ -275,8 +275,9 @@ class KV:
         tokens = tokens.contiguous()
         n = tokens.shape[1]
         nb = lib().plt_prefill_workspace_bytes(self.model.h, self.h, n)
-        if nb == 0:
-            raise PltError(-1, lib().plt_last_error().decode())
+        if nb == 0:       # an invalid prompt length: the call itself reports the precise status
+            _check(lib().plt_prefill(self.model.h, self.h, _ptr(tokens), n, _ptr(self.next), None, None, 0))
+            raise PltError(-1, "plt_prefill_workspace_bytes returned 0")
         # the workspace is the caller's: a torch buffer, kept until the kv object goes (the call is asynchronous)
         if self._ws is None or self._ws.numel() < nb:
             self._ws = None
