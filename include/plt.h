@@ -241,6 +241,23 @@ int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv
                     void* dev_y, void* dev_scratch, size_t scratch_bytes, int32_t n_splits,
                     void* hip_stream);
 
+/* plt_attn_decode for callers that cannot allocate device memory or pass a workspace of their own: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks,
+ * kernels and results as plt_attn_decode (identical bits for the same n_splits), but the split partials
+ * live in a device array the library itself holds (PLT_ATTN_STATIC_SCRATCH_BYTES per GPU, resident until the
+ * process ends); this call allocates and frees nothing and synchronises nothing.  A shape whose partials for
+ * the chosen number of splits (n_splits <= 0: the library's choice) do not fit the array is refused with
+ * PLT_ENOMEM and nothing is launched: B * Hkv * ceil(L * Hq / Hkv / 16) streams need
+ * (n_splits * (32 + 16 D) + 16 D) * 4 bytes each (kernel-only configuration B 32, 4 kv heads, D 128, 2 splits:
+ * 3.1 MiB).  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two threads) race on it and must be serialised by the caller; calls on different GPUs are independent. */
+enum { PLT_ATTN_STATIC_SCRATCH_BYTES = 8 << 20 };
+int plt_attn_decode_static(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
+                           int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring,
+                           const void* dev_q, const void* dev_k_share, const void* dev_v_share,
+                           const void* dev_k_ring, const void* dev_v_ring, const float* dev_z,
+                           void* dev_y, int32_t n_splits, void* hip_stream);
+
 /* Device-side layout conversion for the hook above: plain [S, n, D] (S independent streams,
  * e.g. B*Hkv) -> K layout [S, n_pad * D] (pad positions zeroed) and V layout [S, n_pad * D] (see v_share above).
  * K layout of the 2-byte and 1-byte types: a tile of T = 32 (64) positions is T*D elements stored as

@@ -64,6 +64,7 @@ _SIGS = {
     "plt_attn_pad": (_I, [_I, _I]),
     "plt_attn_scratch_bytes": (_Z, [_I, _I, _I, _I, _I]),
     "plt_attn_decode": (C.c_int, [_I] * 10 + [_P] * 8 + [_Z, _I, _P]),
+    "plt_attn_decode_static": (C.c_int, [_I] * 10 + [_P] * 7 + [_I, _P]),
     "plt_attn_k_index": (C.c_int64, [_I, _I, _I, _I]),
     "plt_attn_v_index": (C.c_int64, [_I, _I, _I, _I]),
     "plt_attn_pack_k": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
@@ -435,6 +436,22 @@ class AttnDecode:
                                      _ptr(self.vs), _ptr(self.kr), _ptr(self.vr), _ptr(self.z), _ptr(self.y),
                                      _ptr(self.scratch), self.scratch.numel(), n_splits, _stream()))
         return self.y
+
+    def run_static(self, n_ctx=None, n_ring=None, n_splits=0, y=None):
+        """The same call through the entry point that allocates nothing (split partials in the library's own
+        device array); writes into y (default: a second output tensor kept by this object)."""
+        import torch
+        B, L, Hq, Hkv, D, N, w = self.dims
+        n_ctx = N if n_ctx is None else n_ctx
+        n_ring = (w if n_ring is None else n_ring) if L > 1 else 0
+        if y is None:
+            if getattr(self, "y_static", None) is None:
+                self.y_static = torch.empty_like(self.q)
+            y = self.y_static
+        _check(lib().plt_attn_decode_static(self.dtype, B, L, Hq, Hkv, D, N, n_ctx, w, n_ring, _ptr(self.q), _ptr(self.ks),
+                                            _ptr(self.vs), _ptr(self.kr), _ptr(self.vr), _ptr(self.z), _ptr(y), n_splits,
+                                            _stream()))
+        return y
 
 
 def gemm(dtype, a, w):

@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 #include "plt_internal.h"
@@ -22,6 +23,31 @@ static int fail(int code, const char* fmt, ...) {
        if (e_ != hipSuccess) return fail(PLT_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); } while (0)
 
 extern "C" const char* plt_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------------ static scratch
+// Device memory the library itself holds, for the entry point that must not allocate
+// (plt_attn_decode_static): the split partials of the fused decode attention live here.  Every GPU the library
+// runs on holds its own copy of the array until the process ends.  In host code the array's NAME is only a
+// stand-in: the device address comes from hipGetSymbolAddress, once per device with that device current, and
+// only that pointer is ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[PLT_ATTN_STATIC_SCRATCH_BYTES];
+static const int MAX_DEVICES = 64;
+static void* g_scratch_ptr[MAX_DEVICES];     // per device: address of that device's copy of `scratch`, or null
+static std::mutex g_scratch_mu;
+static int static_scratch(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEVICES) return fail(PLT_EINVAL, "static scratch: device index %d not supported", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(PLT_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return PLT_OK;
+}
 
 // ------------------------------------------------------------------------------ objects
 struct LayerW {
@@ -170,6 +196,13 @@ extern "C" int plt_init(const plt_config* cfg, const void* dev_weights, size_t n
   if (((uintptr_t)dev_weights) & 255) return fail(PLT_EINVAL, "plt_init: weight blob must be 256-byte aligned");
   int ndev = 0;
   HIP_TRY(hipGetDeviceCount(&ndev));
+  {
+    // set-up time is when the current device's copy of the static scratch is looked up (plt_attn_decode_static
+    // does it on its first call on a device otherwise)
+    void* sp = nullptr;
+    const int rc = static_scratch(&sp);
+    if (rc != PLT_OK) return rc;
+  }
   plt_model* m = new (std::nothrow) plt_model();
   if (!m) return fail(PLT_ENOMEM, "plt_init: out of host memory");
   m->cfg = *cfg; m->stream = (hipStream_t)hip_stream; m->blob = (const char*)dev_weights;
@@ -924,6 +957,21 @@ extern "C" int plt_attn_decode(int32_t dtype, int32_t B, int32_t L, int32_t Hq, 
                                void* hip_stream) {
   return attn_decode_checked("plt_attn_decode", dtype, B, L, Hq, Hkv, D, n_alloc, n_ctx, w, n_ring, q, k_share, v_share,
                              k_ring, v_ring, z, y, scratch, scratch_bytes, false, n_splits, hip_stream);
+}
+
+extern "C" int plt_attn_decode_static(int32_t dtype, int32_t B, int32_t L, int32_t Hq, int32_t Hkv, int32_t D,
+                                      int32_t n_alloc, int32_t n_ctx, int32_t w, int32_t n_ring, const void* q,
+                                      const void* k_share, const void* v_share, const void* k_ring, const void* v_ring,
+                                      const float* z, void* y, int32_t n_splits, void* hip_stream) {
+  void* sp = nullptr;
+  const int rc = static_scratch(&sp);        // a table look-up after the first call on this device
+  if (rc != PLT_OK) return rc;
+  // same checks and launches as plt_attn_decode; the records are laid out for exactly this call's splits, every
+  // record a launch reads is written by the same launch first (nothing has to start at zero), and a shape whose
+  // records exceed the array is refused
+  return attn_decode_checked("plt_attn_decode_static", dtype, B, L, Hq, Hkv, D, n_alloc, n_ctx, w, n_ring, q, k_share,
+                             v_share, k_ring, v_ring, z, y, sp, (size_t)PLT_ATTN_STATIC_SCRATCH_BYTES, true, n_splits,
+                             hip_stream);
 }
 
 extern "C" int64_t plt_attn_k_index(int32_t dtype, int32_t pos, int32_t f, int32_t D) {
