@@ -194,9 +194,12 @@ def copy_reference(B):
             "bytes_written_per_launch": n, "GBps_read_plus_write": 2 * n / (e0.elapsed_time(e1) * 1e-3 / 3) / 1e9}
 
 
-def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_next):
+def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_next, kv=None):
     """One decode step of each sampled sequence through the CPU oracle, from the exported device
-    state.  state: {seq: (exports per layer, carry, token)}; gpu_*: {seq: array}."""
+    state.  state: {seq: (exports per layer, carry, token)}; gpu_*: {seq: array}.  With kv (the device object,
+    still alive): additionally every layer of the device is fed the oracle's input of that layer for the sampled
+    sequences (plt_debug_layer) and the largest |device - oracle| of any layer's output rows is reported: the
+    per-layer, teacher-forced parity, free of the accumulation of bf16 roundings over depth."""
     from oracle import plt_oracle as O
     try:
         from threadpoolctl import threadpool_info
@@ -208,6 +211,7 @@ def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_n
                         shape.ffn_hidden, shape.vocab, cfg.n_loops, cfg.window, shape.rope_theta, shape.norm_eps,
                         shape.tie_embeddings)
     total, err_l, err_h, rel_h, same = 0.0, 0.0, 0.0, 0.0, True
+    layer_io = {}
     for seq, (exports, carry0, token0) in state.items():
         fp8 = cfg.kv_dtype == B.PLT_FP8_E4M3
         orc = O.PLTOracle(osh, w, kv_bf16=not fp8, kv_fp8=fp8)
@@ -216,10 +220,14 @@ def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_n
             orc.kv.ks[m, :pos] = e["k_share"].transpose(1, 0, 2); orc.kv.vs[m, :pos] = e["v_share"].transpose(1, 0, 2)
             for l in range(cfg.n_loops - 1):
                 orc.kv.kr[l, m] = e["k_ring"][l].transpose(1, 0, 2); orc.kv.vr[l, m] = e["v_ring"][l].transpose(1, 0, 2)
-        orc.carry = carry0.astype(np.float64).copy(); orc.pos = pos; orc.trace = []
+        orc.carry = carry0.astype(np.float64).copy(); orc.pos = pos; orc.trace = []; orc.layer_trace = []
         t0 = time.perf_counter()
         nxt, lg = orc.clp_decode_step(int(token0))
         total += time.perf_counter() - t0
+        x_in = np.zeros((cfg.n_loops, shape.n_layers, shape.d_model)); x_out = np.zeros_like(x_in)
+        for (l, m, p, a, b) in orc.layer_trace:
+            x_in[l - 1, m] = a; x_out[l - 1, m] = b
+        layer_io[seq] = (x_in, x_out)
         err_l = max(err_l, float(np.max(np.abs(lg - gpu_logits[seq]))))
         err_h = max(err_h, float(np.max(np.abs(orc.trace[-1] - gpu_hidden[seq]))))
         rel_h = max(rel_h, float(np.max(np.abs(orc.trace[-1] - gpu_hidden[seq])) / np.max(np.abs(orc.trace[-1]))))
@@ -227,11 +235,27 @@ def oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_n
         if top2[1] - top2[0] > 2 * 2e-2:          # away from a near-tie the greedy id must agree
             same = same and (nxt == gpu_next[seq])
     n = len(state)
-    return {"value": n / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n} of the batch's {cfg_batch_note(state)} sequences, one decode step each (all {cfg.n_loops} loop rows, "
-                      f"{shape.n_layers} layers, context {pos + 1}) from the device's exported KV state; {total:.1f} s of CPU work",
-            "seconds": total, "parity_max_abs_logits": err_l, "parity_max_abs_hidden": err_h,
-            "parity_max_rel_hidden": rel_h, "greedy_ids_equal_where_margin_gt_0.04": bool(same)}
+    out = {"value": n / total, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+           "sample": f"{n} of the batch's {cfg_batch_note(state)} sequences, one decode step each (all {cfg.n_loops} loop rows, "
+                     f"{shape.n_layers} layers, context {pos + 1}) from the device's exported KV state; {total:.1f} s of CPU work",
+           "seconds": total, "parity_max_abs_logits": err_l,
+           "accumulated_hidden_drift_max_abs": err_h, "accumulated_hidden_drift_max_rel": rel_h,
+           "accumulated_hidden_drift_note": f"free-running residual stream after all {shape.n_layers} layers (bf16 roundings add up over depth); "
+                                            "the parity bar is held per layer, see parity_per_layer_teacher_forced_max_abs",
+           "greedy_ids_equal_where_margin_gt_0.04": bool(same)}
+    if kv is not None:
+        worst = 0.0
+        for m in range(shape.n_layers):
+            kv.set_position(pos)
+            xin = np.zeros((kv.batch, cfg.n_loops, shape.d_model), np.float32)
+            for seq, (x_in, _) in layer_io.items():
+                xin[seq] = x_in[:, m]
+            got = kv.debug_layer(m, xin)
+            for seq, (x_in, x_out) in layer_io.items():
+                ref = x_out[:, m] - x_in[:, m] + xin[seq].astype(np.float64)
+                worst = max(worst, float(np.max(np.abs(got[seq] - ref))))
+        out["parity_per_layer_teacher_forced_max_abs"] = worst
+    return out
 
 
 def cfg_batch_note(state):
@@ -281,39 +305,73 @@ def bench_attn_kernel(B, steps, warmup, fp8=False):
             "launches_timed": n}
 
 
-def bench_long_context(B, shape, blob, g, steps):
-    """L = 4, window 128, 8192-token shared KV (the KV-bandwidth-bound configuration).  Batch 256 needs
-    412 GB of shared KV and does not fit one GPU; batch 128 (206 GB + 9.7 GB of rings) is one GPU's
-    share and is resident here.  Caches hold N(0, 0.5) values drawn on the device (timing only; the
-    parity of this shape is covered by the GPU tests).  The vanilla sequential loop keeps 4 full caches,
-    so it is timed at batch 32 (the same 206 GB) and compared per sequence."""
+def bench_long_context(B, shape, blob, g, steps, parity=True):
+    """L = 4, window 128, 8192-token shared KV (the KV-bandwidth-bound configuration, configs[3]).  Batch 256 needs
+    412 GB of shared KV in bf16 and does not fit one GPU.  What one GPU shows:
+      * batch 128 (206 GB + 9.7 GB of windows), resident, PLT L = 4 against the non-looped model; the PLT state is built
+        by plt_prefill of 128 x 8191 tokens and one sampled sequence's step is checked against the oracle (logits end
+        to end, every layer teacher-forced);
+      * batch 256 at the real per-layer shape with the shared caches of 12 layers in memory, aliased to the 24 layers
+        (timing only: each layer still streams its full 17 GB, so the bytes moved are the real ones);
+      * the vanilla sequential loop keeps 4 full caches, so it is timed at batch 32 (the same 206 GB) per sequence;
+      * with e4m3 caches the whole batch-256 configuration is resident (206 GB + 4.8 GB of windows).
+    Caches of the timing-only rows hold N(0, 0.5) values drawn on the device."""
     import torch
     N, w = 8192, 128
     pos = N - 1
-    res = {"context": N, "window": w, "note": "batch 256 (412 GB of KV) exceeds 288 GB; one GPU's share (batch 128) timed"}
-    for name, mode, Lx, Bn, kvd in [("plt_L4_b128", B.PLT_MODE_CLP, 4, 128, 0), ("nonlooped_L1_b128", B.PLT_MODE_CLP, 1, 128, 0),
-                                    ("plt_L4_b32", B.PLT_MODE_CLP, 4, 32, 0), ("vanilla_loop_L4_b32", B.PLT_MODE_VANILLA_LOOP, 4, 32, 0),
-                                    # e4m3 caches: the whole batch-256 configuration is resident (206 GB + 4.8 GB of rings)
-                                    ("plt_L4_b256_fp8kv", B.PLT_MODE_CLP, 4, 256, B.PLT_FP8_E4M3),
-                                    ("nonlooped_L1_b256_fp8kv", B.PLT_MODE_CLP, 1, 256, B.PLT_FP8_E4M3)]:
+    res = {"context": N, "window": w, "workload": "~1.3B PLT, bf16, L=4, window 128, 8192-token shared KV (configs[3]); batch 256 = 412 GB of KV "
+                                                   "exceeds 288 GB: batch 128 resident (parity-checked), batch 256 with 12 of 24 layers of shared cache in "
+                                                   "memory (aliased, timing only), batch 256 resident with e4m3 caches"}
+    rows = [("plt_L4_b128", B.PLT_MODE_CLP, 4, 128, 0, 0), ("nonlooped_L1_b128", B.PLT_MODE_CLP, 1, 128, 0, 0),
+            ("plt_L4_b32", B.PLT_MODE_CLP, 4, 32, 0, 0), ("vanilla_loop_L4_b32", B.PLT_MODE_VANILLA_LOOP, 4, 32, 0, 0),
+            ("plt_L4_b256_aliased", B.PLT_MODE_CLP, 4, 256, 0, 12), ("nonlooped_L1_b256_aliased", B.PLT_MODE_CLP, 1, 256, 0, 12),
+            ("plt_L4_b256_fp8kv", B.PLT_MODE_CLP, 4, 256, B.PLT_FP8_E4M3, 0),
+            ("nonlooped_L1_b256_fp8kv", B.PLT_MODE_CLP, 1, 256, B.PLT_FP8_E4M3, 0)]
+    for name, mode, Lx, Bn, kvd, alias in rows:
         cfg = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=w, kv_dtype=kvd)
         m = B.Model(cfg, blob)
+        m.kv_alias_layers(alias)
         kv = B.KV(m, Bn, N)
-        fill_kv_random(B, kv, g)
         tok = torch.randint(0, shape.vocab, (Bn,), generator=g, device="cuda", dtype=torch.int32)
+        row = {}
+        if name == "plt_L4_b128" and parity:
+            # real state + the parity leg of this configuration
+            t0 = time.perf_counter()
+            prompt = torch.randint(0, shape.vocab, (Bn, pos), generator=g, device="cuda", dtype=torch.int32)
+            nxt, _ = kv.prefill(prompt, want_logits=False)
+            torch.cuda.synchronize()
+            row["kv_fill"] = f"plt_prefill of {Bn} x {pos} uniform token ids ({time.perf_counter() - t0:.1f} s)"
+            kv.drop_workspace(); del prompt
+            b = 77
+            carry_all = kv.get_carry()
+            state = {b: ([kv.export(b, l, pos) for l in range(shape.n_layers)], carry_all[b], int(nxt[b].item()))}
+            tok = nxt.clone()
+            n1, lg1 = kv.decode_step(tok)
+            hid1 = kv.get_hidden()
+            row["parity"] = oracle_sample(B, shape, cfg, blob, state, pos, {b: lg1[b].float().cpu().numpy().astype(np.float64)},
+                                          {b: hid1[b].astype(np.float64)}, {b: int(n1[b].item())}, kv=kv)
+            log(f"[bench] long context parity (batch 128, sequence {b}): logits {row['parity']['parity_max_abs_logits']:.2e}, "
+                f"per layer {row['parity']['parity_per_layer_teacher_forced_max_abs']:.2e}")
+        else:
+            fill_kv_random(B, kv, g)
+            row["kv_fill"] = "N(0, 0.5) drawn on the device (timing only)" + (f"; shared caches of {alias} layers aliased to {shape.n_layers}" if alias else "")
         m.profile_enable(1 << B.PLT_PROF_ATTN)
         ms = time_steps(kv, pos, tok, 1, steps)
         attn_ms, attn_n = m.profile_read(B.PLT_PROF_ATTN, reset=True)
         ab = attn_alg_bytes(Bn, Lx if mode == B.PLT_MODE_CLP else 1, shape.n_heads, shape.n_kv_heads, shape.head_dim, N, w,
                             2, 1 if kvd else 2)
         us = attn_ms * 1e3 / max(attn_n, 1)
-        res[name] = {"ms_per_step": ms, "tokens_per_s": Bn / (ms * 1e-3), "attn_us_per_launch": us,
-                     "attn_GBps": ab / (us * 1e-6) / 1e9, "kv_bytes": m.kv_logical_bytes(Bn, N)}
+        row.update({"ms_per_step": ms, "tokens_per_s": Bn / (ms * 1e-3), "attn_us_per_launch": us,
+                    "attn_GBps": ab / (us * 1e-6) / 1e9, "attn_frac_of_8TBps": ab / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                    "kv_bytes": m.kv_logical_bytes(Bn, N)})
+        res[name] = row
         log(f"[bench] long context {name}: {ms:.2f} ms/step, attention {us:.0f} us/launch = {ab / (us * 1e-6) / 1e12:.2f} TB/s")
         kv.close(); m.close(); del kv
         torch.cuda.empty_cache()
     res["latency_plt_L4_vs_nonlooped_b128"] = res["plt_L4_b128"]["ms_per_step"] / res["nonlooped_L1_b128"]["ms_per_step"]
     res["latency_vanilla_L4_vs_plt_L4_b32"] = res["vanilla_loop_L4_b32"]["ms_per_step"] / res["plt_L4_b32"]["ms_per_step"]
+    res["latency_plt_L4_vs_nonlooped_b256_aliased"] = (res["plt_L4_b256_aliased"]["ms_per_step"]
+                                                       / res["nonlooped_L1_b256_aliased"]["ms_per_step"])
     res["latency_plt_L4_vs_nonlooped_b256_fp8kv"] = (res["plt_L4_b256_fp8kv"]["ms_per_step"]
                                                       / res["nonlooped_L1_b256_fp8kv"]["ms_per_step"])
     return res
@@ -352,7 +410,7 @@ def bench_prefill(B, shape, blob, g, Bn=4, n=8192, L=3, w=64, reps=2):
             "roofline": {"bound": "mfma", "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0, "traffic": None}}
 
 
-def bench_sweep(B, shape, blob, g, n_new=256, runs=5):
+def bench_sweep(B, shape, blob, g, n_new=256, runs=5, contexts=(1024, 2048, 5000), batches=(1, 4, 16, 64, 256), graph=True):
     """The paper's serving recipe on synthetic inputs: prefill context {1024, 2048, 5000}, batch 1..256,
     n_new consecutive greedy decode steps (the context grows), mean per-token latency over `runs` runs,
     for the non-looped model, PLT-2 and the vanilla sequential loop-2 in the same library.  Caches are
@@ -360,12 +418,23 @@ def bench_sweep(B, shape, blob, g, n_new=256, runs=5):
     import torch
     free_bytes = torch.cuda.mem_get_info()[0]
     table = []
-    for ctx in (1024, 2048, 5000):
-        for bs in (1, 4, 16, 64, 256):
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()          # stream capture needs a stream of its own; default priority
+    with torch.cuda.stream(side):
+        _sweep_rows(B, shape, blob, g, n_new, runs, contexts, batches, graph, free_bytes, table)
+    torch.cuda.synchronize()
+    return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "step_replayed_as_hip_graph": bool(graph), "rows": table}
+
+
+def _sweep_rows(B, shape, blob, g, n_new, runs, contexts, batches, graph, free_bytes, table):
+    import torch
+    for ctx in contexts:
+        for bs in batches:
             row = {"context": ctx, "batch": bs}
             for name, mode, Lx in [("nonlooped", B.PLT_MODE_CLP, 1), ("plt2", B.PLT_MODE_CLP, 2), ("vanilla_loop2", B.PLT_MODE_VANILLA_LOOP, 2)]:
                 cfg = B.make_config(shape, dtype=B.PLT_BF16, mode=mode, n_loops=Lx, window=64)
                 m = B.Model(cfg, blob)
+                m.use_graph(graph)
                 need = m.kv_bytes(bs, ctx + n_new)
                 if need > free_bytes - (8 << 30):
                     row[name] = None
@@ -393,7 +462,6 @@ def bench_sweep(B, shape, blob, g, n_new=256, runs=5):
                 row["vanilla_loop2_vs_nonlooped"] = row["vanilla_loop2"] / row["nonlooped"] if row["vanilla_loop2"] else None
             log(f"[bench] sweep {row}")
             table.append(row)
-    return {"decoded_tokens": n_new, "runs": runs, "unit": "ms per token", "rows": table}
 
 
 def bench_sweep_moe(B, g, n_new=256, runs=5, ctx=5000):
@@ -584,10 +652,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--only-main", action="store_true", help="skip the baselines, the L sweep and the kernel-only run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--sweep", action="store_true", help="also run the batch x context serving sweep (several minutes)")
-    ap.add_argument("--prefill", action="store_true", help="also time the CLP prefill of 4 x 8192 tokens at L=3")
-    ap.add_argument("--long-context", action="store_true",
-                    help="also time one GPU's share of the L=4, window 128, 8192-token configuration (batch 128 resident)")
+    ap.add_argument("--sweep", action="store_true", help="the full batch x context serving sweep (batch 1..256 x context 1024/2048/5000, 256 tokens, 5 runs: several minutes) instead of the reduced one")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the reduced serving sweep")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the CLP prefill of 4 x 8192 tokens at L=3 (configs[4])")
+    ap.add_argument("--no-long-context", action="store_true",
+                    help="skip the L=4, window 128, 8192-token configuration (configs[3]: batch 128 resident + parity, batch 256 aliased / e4m3)")
+    ap.add_argument("--sweep-eager", action="store_true", help="serving sweep without the HIP-graph replay of the step")
     ap.add_argument("--attn-kernel-only", action="store_true", help="only the kernel-only fused attention configuration (bf16 and e4m3 caches)")
     ap.add_argument("--prefill-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3")
     ap.add_argument("--prefill-moe-only", action="store_true", help="only the CLP prefill of 4 x 8192 tokens at L=3 on the 8-of-64 mixture-of-experts shape")
@@ -721,6 +791,12 @@ def main():
     ceiling = measure_read_ceiling(B)
     out["roofline"]["measured_stream_read_GBps"] = ceiling          # context: what a plain read kernel reaches here
     out["roofline"]["frac_of_measured_stream_read"] = achieved / ceiling
+    if not args.no_cpu_baseline:
+        log(f"[bench] timing the CPU oracle on {len(sample)} sequences (10-15 s) ...")
+        out["cpu_baseline"] = oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_next, kv=kv)
+        log(f"[bench] parity: logits {out['cpu_baseline']['parity_max_abs_logits']:.2e}, per layer (teacher-forced) "
+            f"{out['cpu_baseline']['parity_per_layer_teacher_forced_max_abs']:.2e}")
+        state.clear()
 
     if not args.only_main and not kvd:
         # ---- same library, same weights: non-looped, the L sweep and the vanilla sequential loop.
@@ -821,17 +897,19 @@ def main():
         torch.cuda.empty_cache()
         out["lowbit_model"] = lb
 
-    if args.sweep:
-        out["serving_sweep"] = bench_sweep(B, shape, blob, g)
-    if args.prefill:
-        out["prefill"] = bench_prefill(B, shape, blob, g)
-        log(f"[bench] prefill 4 x 8192, L=3: {out['prefill']['ms']:.0f} ms, {out['prefill']['roofline']['achieved']:.0f} TFLOP/s")
-    if args.long_context:
-        out["long_context"] = bench_long_context(B, shape, blob, g, max(4, args.steps // 4))
-
-    if not args.no_cpu_baseline:
-        log(f"[bench] timing the CPU oracle on {len(sample)} sequences (10-15 s) ...")
-        out["cpu_baseline"] = oracle_sample(B, shape, cfg, blob, state, pos, gpu_logits, gpu_hidden, gpu_next)
+    if not args.only_main and not kvd:
+        if args.sweep:
+            out["serving_sweep"] = bench_sweep(B, shape, blob, g, graph=not args.sweep_eager)
+        elif not args.no_sweep:
+            # reduced form of the paper's serving protocol (256 tokens, mean of 5): 128 tokens, mean of 2, three batches x two contexts
+            out["serving_sweep"] = bench_sweep(B, shape, blob, g, n_new=128, runs=2, contexts=(1024, 5000), batches=(1, 16, 64),
+                                               graph=not args.sweep_eager)
+            out["serving_sweep"]["note"] = "reduced: 128 decoded tokens, mean of 2 runs; --sweep runs the full protocol"
+        if not args.no_prefill:
+            out["prefill"] = bench_prefill(B, shape, blob, g)
+            log(f"[bench] prefill 4 x 8192, L=3: {out['prefill']['ms']:.0f} ms, {out['prefill']['roofline']['achieved']:.0f} TFLOP/s")
+        if not args.no_long_context:
+            out["long_context"] = bench_long_context(B, shape, blob, g, max(4, args.steps // 4), parity=not args.no_cpu_baseline)
     print(json.dumps(out), flush=True)
 
 

@@ -171,6 +171,17 @@ int plt_prefill(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t n,
 int plt_decode_step(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t* dev_next,
                     float* dev_logits);
 
+/* Replay mode of plt_decode_step (off by default).  While on, a step is issued as ONE HIP graph launch: the
+ * launch sequence of the step (about 220 dependent kernels for 24 layers) is recorded by stream capture the first
+ * time and whenever dev_tokens / dev_next / dev_logits or the attention's split count change (the split count
+ * depends on the context length only for batches that leave compute units idle), and replayed otherwise -- the
+ * position is a device-side counter, so the same recorded launches serve every position [Alg. 1 l.5-9 is the same
+ * work at every step].  The graph holds kernel nodes only (the step clears no memory).  Results are those of the
+ * eager step bit for bit.  If capture or instantiation fails, nothing has been launched, the state is unchanged and
+ * the step returns PLT_EHIP.  The stream handed to plt_init must not be the legacy NULL stream while this is on
+ * (stream capture does not work on it).  Ignored while plt_profile_enable is on (events are recorded eagerly). */
+int plt_use_graph(plt_model* m, int32_t on);
+
 /* Number of positions consumed so far (prompt + decode steps), or a negative status. */
 int32_t plt_kv_position(const plt_kv* kv);
 
@@ -193,6 +204,14 @@ int plt_kv_export(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t
                   void* host_dst, size_t host_nbytes);
 int plt_kv_import(plt_kv* kv, int32_t seq, int32_t layer, int32_t cache, int32_t n,
                   const void* host_src, size_t host_nbytes);
+
+/* Timing-only aliasing of the shared caches (bench hook; results are meaningless while it is on): kv objects
+ * created AFTER this call keep the shared K/V of only phys_layers layers in memory, and layer m streams and
+ * appends to the memory of layer m mod phys_layers (windows stay per layer).  A batch whose shared cache exceeds
+ * the device (256 sequences x 8192 positions x 24 layers = 412 GB in bf16) can then be timed at its real
+ * per-layer shape: every layer still streams its full 17 GB, far more than any cache on the die holds, so
+ * the bytes moved per step are the real ones.  phys_layers = 0 switches it off. */
+int plt_kv_alias_layers(plt_model* m, int32_t phys_layers);
 
 /* Carried states H^l[p-1], l = 1..L-1, of every sequence: float [batch, L-1, d]. */
 int plt_get_carry(plt_kv* kv, float* host_dst, size_t host_nbytes);

@@ -50,6 +50,8 @@ _SIGS = {
     "plt_prefill_workspace_bytes": (_Z, [_P, _P, _I]),
     "plt_prefill": (C.c_int, [_P, _P, _P, _I, _P, _P, _P, _Z]),
     "plt_decode_step": (C.c_int, [_P, _P, _P, _P, _P]),
+    "plt_kv_alias_layers": (C.c_int, [_P, _I]),
+    "plt_use_graph": (C.c_int, [_P, _I]),
     "plt_kv_position": (_I, [_P]),
     "plt_last_error": (C.c_char_p, []),
     "plt_kv_set_position": (C.c_int, [_P, _I]),
@@ -234,6 +236,14 @@ class Model:
 
     def kv_logical_bytes(self, batch, n_ctx):
         return lib().plt_kv_logical_bytes(self.h, batch, n_ctx)
+
+    def kv_alias_layers(self, phys_layers):
+        """Timing only: kv objects created afterwards keep `phys_layers` layers of shared cache (0: all)."""
+        _check(lib().plt_kv_alias_layers(self.h, int(phys_layers)))
+
+    def use_graph(self, on=True):
+        """plt_decode_step replays its launch sequence as one HIP graph (captured on first use)."""
+        _check(lib().plt_use_graph(self.h, 1 if on else 0))
 
     def profile_enable(self, mask):
         """mask: OR of (1 << PLT_PROF_ATTN), (1 << PLT_PROF_GEMM); 0 switches the instrumentation off."""

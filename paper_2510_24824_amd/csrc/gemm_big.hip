@@ -32,7 +32,7 @@ enum { EPI_F32 = 0, EPI_SWIGLU = 1 };
 //   256 x 64, 4 x 2 waves of 64 x 32 : the gate/up projection of decode steps with 129..256 rows, SwiGLU fused
 //       (all rows of the step in one tile, whole K: no split-K slabs, no separate activation kernel).  The same
 //       tile for the plain QKV projection measured slower than the weight-streaming kernel and is not used.
-template <int EPI, int BM, int BN, int WM, int WN>
+template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                           void* __restrict__ out, int M, int N, int K) {
   // N: EPI_F32: output columns (= rows of w); EPI_SWIGLU: F (w has 2F rows, the output F columns)
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
                  : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
   };
   auto issue = [&](int ks) {
-    const unsigned stage = lds0 + (unsigned)(ks & 1) * STAGE_BYTES;
+    const unsigned stage = lds0 + (unsigned)(ks % STAGES) * STAGE_BYTES;
     const int k0 = ks * GB_BK;
 #pragma unroll
     for (int i = 0; i < DMA_A; ++i)
@@ -97,13 +97,22 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
 
   // fragment addressing: row r = (multiple of 16) + m16, chunk kc = k32*4 + g -> slot r*8 + (kc ^ (m16 & 7))
   const int sw0 = (g ^ (m16 & 7)) * 16;                 // byte offset of the lane's chunk inside its row, k32 = 0
-  issue(0);
+  // STAGES - 1 slices are requested ahead: with two stages a slice has one K step to arrive (enough when the matrix
+  // cores are the limit, as in prefill); the decode-row tile is latency-bound with that (a slice of 40 KB per round
+  // trip), so it runs three stages and waits only for the OLDEST slice in flight (loads return in order)
+#pragma unroll
+  for (int st = 0; st < STAGES - 1; ++st) if (st < ks_total) issue(st);
   for (int ks = 0; ks < ks_total; ++ks) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's part of slice ks has landed
-    __syncthreads();                   // ... and everyone's; every wave is done with slice ks - 1, whose
-                                       // stage is refilled next
-    if (ks + 1 < ks_total) issue(ks + 1);
-    const char* As = gb_lds + (ks & 1) * STAGE_BYTES;
+    // this wave's part of slice ks has landed: everything but the (STAGES - 2) younger slices still in flight
+    if (STAGES == 2 || ks + STAGES - 2 >= ks_total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" :: "n"((STAGES - 2) * (DMA_A + DMA_W)) : "memory");
+    // ... and everyone's; every wave is done with slice ks - 1, whose stage is refilled next.  With more than two
+    // stages the bare barrier instruction: __syncthreads() would drain the younger slices too (its fence waits for
+    // every load in flight); the asm statements on both sides keep the LDS reads where they are
+    if (STAGES == 2) __syncthreads(); else __builtin_amdgcn_s_barrier();
+    if (ks + STAGES - 1 < ks_total) issue(ks + STAGES - 1);
+    else asm volatile("" ::: "memory");
+    const char* As = gb_lds + (ks % STAGES) * STAGE_BYTES;
     const char* Ws = As + A_BYTES;
 #pragma unroll
     for (int k32 = 0; k32 < GB_BK / 32; ++k32) {
@@ -158,15 +167,15 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
   }
 }
 
-template <int EPI, int BM, int BN, int WM, int WN>
+template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2>
 void tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, void* out, int M, int N, int K) {
-  constexpr int LDS_BYTES = 2 * (BM + BN) * GB_BK * 2;          // two stages x (A tile + W tile)
+  constexpr int LDS_BYTES = STAGES * (BM + BN) * GB_BK * 2;     // stages x (A tile + W tile)
   // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
-  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN, STAGES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   (void)attr_once;
   const int ncols = EPI == EPI_SWIGLU ? BN / 2 : BN;             // output columns per tile
   dim3 grid((N + ncols - 1) / ncols, (M + BM - 1) / BM);
-  hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K);
+  hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN, STAGES>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K);
 }
 
 }  // namespace
@@ -194,8 +203,13 @@ bool gemm_swiglu_rows_applies(int M, int F, int K) {
   return M > 128 && M <= 256 && (K % GB_BK) == 0 && (F + 31) / 32 >= 128;   // enough 32-column tiles to occupy the chip
 }
 
+// the same tile with the plain float epilogue: wide projections at 129..256 rows, whole K, no slabs
+void launch_gemm_rows_tile(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
+  tile_launch<EPI_F32, 256, 64, 4, 2, 3>(s, a, w, (void*)c, M, N, K);
+}
+
 void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
-  tile_launch<EPI_SWIGLU, 256, 64, 4, 2>(s, a, wgu, (void*)act, M, F, K);
+  tile_launch<EPI_SWIGLU, 256, 64, 4, 2, 3>(s, a, wgu, (void*)act, M, F, K);
 }
 
 }  // namespace plt

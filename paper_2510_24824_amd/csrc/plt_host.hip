@@ -70,10 +70,13 @@ struct plt_model {
   bool kv8; // caches hold e4m3 bytes
   bool mx;  // the four per-layer projections run on MXFP4 weights and MXFP8 activations
   double* inv_freq = nullptr;   // device [D/2]: rotary frequencies theta^(-2j/D), computed in double
+  bool use_graph = false;       // plt_decode_step replays its launch sequence as a HIP graph (see plt_use_graph)
+  int phys_layers = 0;          // timing-only aliasing of the shared caches: layer m uses the memory of layer m % phys_layers (0: off)
 };
 struct plt_kv {
   plt_model* m;
   int B, max_ctx, n_pad, w_pad, n_caches, n_rings;
+  int share_layers;    // layers of shared cache physically present (= n_layers unless aliased for timing)
   char* buf;
   size_t share_elems;  // elements of one layer's K_share (= V_share): B*Hkv*n_pad*D
   size_t ring_elems;   // elements of one layer's ring K (= ring V): B*(L-1)*Hkv*w_pad*D
@@ -86,6 +89,9 @@ struct plt_kv {
   uint8_t *a_codes, *a_scales;   // low-bit models: the quantised input of the next projection
   uint8_t* act_sc;               // low-bit mixture-of-experts models: block scales of the experts' hidden rows
   float* arg_v; int* arg_i;   // argmax chunk winners
+  // the decode step's launch sequence as an instantiated HIP graph, valid for these arguments / this split count
+  hipGraphExec_t graph_exec = nullptr;
+  const int32_t* g_tokens = nullptr; int32_t* g_next = nullptr; float* g_logits = nullptr; int g_splits = -1;
 };
 
 static bool cfg_valid(const plt_config* c, const char** why) {
@@ -307,7 +313,8 @@ extern "C" size_t plt_kv_bytes(const plt_model* m, int32_t batch, int32_t max_ct
   const plt_config& c = m->cfg;
   const size_t share = (size_t)batch * c.n_kv_heads * pad_kv(max_ctx, m->kv8) * c.head_dim;
   const size_t ring = (size_t)batch * n_rings_of(c) * c.n_kv_heads * pad_kv(c.window > 0 ? c.window : 1, m->kv8) * c.head_dim;
-  return align256(2 * share * c.n_layers * n_caches_of(c) * m->kes) + align256(2 * ring * c.n_layers * m->kes);
+  const size_t sl = m->phys_layers > 0 && m->phys_layers < c.n_layers ? m->phys_layers : c.n_layers;
+  return align256(2 * share * sl * n_caches_of(c) * m->kes) + align256(2 * ring * c.n_layers * m->kes);
 }
 
 extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_t n_ctx) {
@@ -320,6 +327,7 @@ extern "C" size_t plt_kv_logical_bytes(const plt_model* m, int32_t batch, int32_
 
 static void kv_release(plt_kv* kv) {
   if (!kv) return;
+  if (kv->graph_exec) (void)hipGraphExecDestroy(kv->graph_exec);
   void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch,
                   kv->arg_v, kv->arg_i, kv->moe_idx, kv->a_codes, kv->a_scales, kv->act_sc};
   for (void* p : ptrs) if (p) (void)hipFree(p);
@@ -356,7 +364,8 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   kv->buf = (char*)dev_buf;
   kv->share_elems = (size_t)batch * c.n_kv_heads * kv->n_pad * c.head_dim;
   kv->ring_elems = (size_t)batch * kv->n_rings * c.n_kv_heads * kv->w_pad * c.head_dim;
-  kv->ring_base = align256(2 * kv->share_elems * c.n_layers * kv->n_caches * m->kes);
+  kv->share_layers = m->phys_layers > 0 && m->phys_layers < c.n_layers ? m->phys_layers : c.n_layers;
+  kv->ring_base = align256(2 * kv->share_elems * kv->share_layers * kv->n_caches * m->kes);
   kv->pos = 0; kv->started = false;
   // cleared so that padded / not-yet-written slots hold finite values (masked keys multiply
   // their value rows by zero weights, which must not meet NaN bit patterns)
@@ -411,6 +420,12 @@ extern "C" int plt_kv_alloc(plt_model* m, int32_t batch, int32_t max_ctx, void* 
   return PLT_OK;
 }
 
+extern "C" int plt_kv_alias_layers(plt_model* m, int32_t phys_layers) {
+  if (!m || phys_layers < 0) return fail(PLT_EINVAL, "plt_kv_alias_layers: bad argument");
+  m->phys_layers = phys_layers;
+  return PLT_OK;
+}
+
 extern "C" int32_t plt_kv_position(const plt_kv* kv) {
   if (!kv) return fail(PLT_EINVAL, "plt_kv_position: null kv");
   return kv->pos;
@@ -421,7 +436,7 @@ static KvView kv_view(const plt_kv* kv, int layer, int cache) {
   const plt_config& c = m->cfg;
   KvView v;
   const size_t es = m->kes;
-  char* sb = kv->buf + ((size_t)cache * c.n_layers + layer) * 2 * kv->share_elems * es;
+  char* sb = kv->buf + ((size_t)cache * kv->share_layers + layer % kv->share_layers) * 2 * kv->share_elems * es;
   v.k_share = sb; v.v_share = sb + kv->share_elems * es;
   if (kv->n_rings > 0) {
     char* rb = kv->buf + kv->ring_base + (size_t)layer * 2 * kv->ring_elems * es;
@@ -430,7 +445,7 @@ static KvView kv_view(const plt_kv* kv, int layer, int cache) {
   v.k_loc = nullptr; v.v_loc = nullptr;
   v.n_pad = kv->n_pad; v.w_pad = kv->w_pad; v.n_pad_loc = 0;
   v.w = c.window > 0 ? c.window : 1; v.n_rings = kv->n_rings; v.b0 = 0;
-  v.cache_stride = (size_t)c.n_layers * 2 * kv->share_elems;   // elements between cache c and c + 1 of one layer
+  v.cache_stride = (size_t)kv->share_layers * 2 * kv->share_elems;   // elements between cache c and c + 1 of one layer
   return v;
 }
 
@@ -612,11 +627,61 @@ static int decode_step_t(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, in
   return PLT_OK;
 }
 
+// The one launch parameter of a decode step that the HOST derives from the position (everything else the kernels
+// read from the device-side position counter): the number of workgroups a stream of the attention is split over.
+static int step_splits(const plt_model* m, const plt_kv* kv) {
+  const plt_config& c = m->cfg;
+  if (c.dtype != PLT_BF16) return 0;
+  const int G = c.n_heads / c.n_kv_heads;
+  const int L = (is_clp(c) && c.mode != PLT_MODE_CLP_OWN_KV) ? c.n_loops : 1;
+  return attn_mfma_default_splits(kv->B, c.n_kv_heads, L, G, kv->pos + 1, m->kv8);
+}
+
+// Replays the step as a HIP graph: captured (stream capture of the very launch sequence the eager step issues) the
+// first time and whenever the arguments or the attention split count change, replayed otherwise.  No memset nodes:
+// the step clears nothing.  A failed capture or instantiation launches nothing and is reported.
+static int decode_step_graph(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t* dev_next, float* dev_logits) {
+  const int splits = step_splits(m, kv);
+  if (!kv->graph_exec || kv->g_tokens != dev_tokens || kv->g_next != dev_next || kv->g_logits != dev_logits || kv->g_splits != splits) {
+    if (kv->graph_exec) { (void)hipGraphExecDestroy(kv->graph_exec); kv->graph_exec = nullptr; }
+    hipGraph_t graph = nullptr;
+    if (m->stream == nullptr) return fail(PLT_EHIP, "plt_decode_step: graph replay needs a stream of its own (the model was created on the NULL stream)");
+    hipError_t e = hipStreamBeginCapture(m->stream, hipStreamCaptureModeThreadLocal);
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(PLT_EHIP, "plt_decode_step: hipStreamBeginCapture: %s", hipGetErrorString(e)); }
+    const int rc = m->cfg.dtype == PLT_BF16 ? decode_step_t<bf16_t>(m, kv, dev_tokens, dev_next, dev_logits)
+                                            : decode_step_t<float>(m, kv, dev_tokens, dev_next, dev_logits);
+    e = hipStreamEndCapture(m->stream, &graph);            // always ends the capture, also after a failed launch
+    if (rc != PLT_OK || e != hipSuccess || !graph) {
+      if (graph) (void)hipGraphDestroy(graph);
+      (void)hipGetLastError();
+      return fail(PLT_EHIP, "plt_decode_step: stream capture failed: %s", hipGetErrorString(e));
+    }
+    e = hipGraphInstantiate(&kv->graph_exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) { kv->graph_exec = nullptr; return fail(PLT_EHIP, "plt_decode_step: hipGraphInstantiate: %s", hipGetErrorString(e)); }
+    kv->g_tokens = dev_tokens; kv->g_next = dev_next; kv->g_logits = dev_logits; kv->g_splits = splits;
+  }
+  HIP_TRY(hipGraphLaunch(kv->graph_exec, m->stream));
+  return PLT_OK;
+}
+
+extern "C" int plt_use_graph(plt_model* m, int32_t on) {
+  if (!m) return fail(PLT_EINVAL, "plt_use_graph: null model");
+  m->use_graph = on != 0;
+  return PLT_OK;
+}
+
 extern "C" int plt_decode_step(plt_model* m, plt_kv* kv, const int32_t* dev_tokens, int32_t* dev_next,
                                float* dev_logits) {
   if (!m || !kv || kv->m != m || !dev_tokens || !dev_next) return fail(PLT_EINVAL, "plt_decode_step: bad argument");
   if (!kv->started) return fail(PLT_ESTATE, "plt_decode_step: plt_prefill (or plt_kv_set_position) must come first");
   if (kv->pos >= kv->max_ctx) return fail(PLT_ECTXFULL, "plt_decode_step: context full (%d positions)", kv->max_ctx);
+  if (m->use_graph && m->profile == 0) {       // (the event instrumentation records events: eager only)
+    // a capture or instantiation that fails has launched nothing: the error is reported and the state is unchanged
+    const int rc = decode_step_graph(m, kv, dev_tokens, dev_next, dev_logits);
+    if (rc == PLT_OK) kv->pos += 1;
+    return rc;
+  }
   int rc = m->cfg.dtype == PLT_BF16 ? decode_step_t<bf16_t>(m, kv, dev_tokens, dev_next, dev_logits)
                                     : decode_step_t<float>(m, kv, dev_tokens, dev_next, dev_logits);
   if (rc == PLT_OK && hipGetLastError() != hipSuccess) rc = fail(PLT_EHIP, "plt_decode_step: a kernel launch failed");
