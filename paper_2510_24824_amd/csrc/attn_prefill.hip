@@ -45,10 +45,14 @@ struct PfState {           // online softmax state of one 16-row query tile
 // into eight different bank groups.
 template <int D>
 struct PfLds {
-  bf16_t k[32][D];         // [key][feature]; chunk c of row r at chunk c ^ ((r & 3) | ((r >> 3) & 1) << 2)
+  bf16_t k[32][D];         // [key][feature]; chunk c of row r at chunk c ^ kx(r)
   bf16_t v[D][32];         // [feature][position]; chunk c of row d at chunk c ^ ((d >> 1) & 3)
-  __device__ bf16_t* kp(int r, int c) { return &k[r][(c ^ ((r & 3) | (((r >> 3) & 1) << 2))) * 8]; }
-  __device__ const bf16_t* kp(int r, int c) const { return &k[r][(c ^ ((r & 3) | (((r >> 3) & 1) << 2))) * 8]; }
+  // kx: distinct over the eight rows a fragment read serves together (r, r+1, r+2, r+3, r+8 .. r+11) AND with bit 2
+  // differing between the two consecutive rows whose chunks 0..3 one group of eight lanes writes when a tile is
+  // stored (with r % 4 in the low bits those two rows' chunks fell into the same four bank groups: two-way conflicts)
+  __device__ static int kx(int r) { return ((r & 1) << 2) | ((r >> 1) & 1) | (((r >> 3) & 1) << 1); }
+  __device__ bf16_t* kp(int r, int c) { return &k[r][(c ^ kx(r)) * 8]; }
+  __device__ const bf16_t* kp(int r, int c) const { return &k[r][(c ^ kx(r)) * 8]; }
   __device__ bf16_t* vp(int d, int c) { return &v[d][(c ^ ((d >> 1) & 3)) * 8]; }
   __device__ const bf16_t* vp(int d, int c) const { return &v[d][(c ^ ((d >> 1) & 3)) * 8]; }
 };
