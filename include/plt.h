@@ -229,6 +229,18 @@ int plt_get_hidden(plt_kv* kv, float* host_dst, size_t host_nbytes);
  * roundings over depth.  CLP modes only; synchronises. */
 int plt_debug_layer(plt_model* m, plt_kv* kv, int32_t layer, const float* host_x_in, float* host_x_out,
                     size_t host_nbytes);
+/* Low-bit dense models (w_dtype = PLT_MXFP4, n_experts = 0): the quantised activations that entered the four
+ * projections of the layer the LAST plt_debug_layer call ran [inference efficiency evaluation recipe; formats under
+ * "Low-bit projections" below].  which = 0: input of the QKV projection (normed rows, K = d_model), 1: input of the
+ * output projection (attention output, K = n_heads * head_dim), 2: input of the gate/up projection (normed rows,
+ * K = d_model), 3: input of the down projection (SwiGLU product, K = ffn_hidden).  host_codes: e4m3 bytes
+ * [batch * L, K] row-major; host_scales: [batch * L, 16 * ceil(K / 512)] scale bytes in the order of
+ * plt_mx_act_scale_index.  A quantiser decides integers from floats, so two correct implementations may round
+ * an element that sits on a rounding boundary to neighbouring codes; with the device's own codes in hand a test can
+ * give the reference exactly the operands the device multiplied and compare the layer without that ambiguity.
+ * PLT_ESTATE before the first plt_debug_layer call; synchronises. */
+int plt_debug_act_codes(plt_kv* kv, int32_t which, uint8_t* host_codes, size_t codes_nbytes,
+                        uint8_t* host_scales, size_t scales_nbytes);
 
 /* Kernel-only fused decode attention [Alg. 3 l.2-5, Eq. 2; first-loop row: global only].
  * All pointers are device pointers, element type `dtype`, in the cache's native layout:

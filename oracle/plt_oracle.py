@@ -382,6 +382,13 @@ class PLTOracle:
         # bookkeeping for per-layer comparisons: when set to a list, every layer evaluated by f() appends
         # (loop l, layer m, position p, the layer's input row, the layer's output row); no arithmetic depends on it
         self.layer_trace = None
+        # low-bit models, for tests that must not depend on which way a value on a rounding boundary falls: when
+        # act_trace is a list, every value about to be block-quantised is appended as (loop l, layer m, stage, value)
+        # with stage 0 = QKV input, 1 = output-projection input, 2 = gate/up input, 3 = down-projection input; and when
+        # act_override maps (l, m, stage) to a vector, that vector is used IN PLACE of this oracle's own quantised
+        # value (e.g. the dequantised codes another implementation chose).  Neither changes any arithmetic by itself.
+        self.act_trace = None
+        self.act_override = None
         # low-bit linear layers: the four projections of every layer on microscaling operands
         self.w_mx = w_mx
         if w_mx:
@@ -391,13 +398,14 @@ class PLTOracle:
                                    for name in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down")})
 
     # -- block f: one pass of the whole layer stack for one row at position p in loop l (1-based)
-    def f(self, x, p, l, kv, global_cache_id=1, plain=False):
+    def f(self, x, p, l, kv, global_cache_id=1, plain=False, layers=None):
         """Transformer stack applied to one hidden row.
 
         l == 1 (or plain=True): ordinary causal attention; its rotated K and its V are
         appended to global cache `global_cache_id` (the first loop's cache is the shared one).
         l >= 2: Alg. 3 -- global attention over the shared cache (0..p inclusive), sliding
         window attention over this loop's own last w entries, Eq. (2) gate merge.
+        layers: the layers to apply (default: all, in order); tests apply one layer to a given row.
         """
         s = self.s
         Hq, Hkv, D = s.n_heads, s.n_kv_heads, s.head_dim
@@ -410,15 +418,21 @@ class PLTOracle:
                 first, global_cache_id = True, l
             elif self.variant == "clp_share_only":    # Table 1 row 4: global branch only
                 share_only = True
-        for m in range(s.n_layers):
+        for m in (range(s.n_layers) if layers is None else layers):
             W = self.w["layers"][m]
             x_in = x
             a = rmsnorm(x, W["norm1"], s.norm_eps)
-            act_in = (lambda t: t)
+            act_in = (lambda t, stage: t)
             if self.w_mx:                       # quantised projections: dequantised weights, e4m3-block inputs
                 W = {**W, **self.wq_mx[m]}
-                act_in = lambda t: mx_dequantize(*mx_quantize(t, "e4m3"))
-            a = act_in(a)
+
+                def act_in(t, stage, m=m):
+                    if self.act_trace is not None:
+                        self.act_trace.append((l, m, stage, np.array(t, np.float64)))
+                    if self.act_override is not None and (l, m, stage) in self.act_override:
+                        return np.asarray(self.act_override[(l, m, stage)], np.float64)
+                    return mx_dequantize(*mx_quantize(t, "e4m3"))
+            a = act_in(a, 0)
             q = (np.asarray(W["wq"], np.float64) @ a).reshape(Hq, D)          # Alg. 3 l.1
             k = (np.asarray(W["wk"], np.float64) @ a).reshape(Hkv, D)
             v = (np.asarray(W["wv"], np.float64) @ a).reshape(Hkv, D)
@@ -440,9 +454,9 @@ class PLTOracle:
                 for h in range(Hq):
                     y[h] = gated_attention_row(qr[h], Kg[:, h // G], Vg[:, h // G],
                                                Kl[:, h // G], Vl[:, h // G], z[h])  # Alg. 3 l.2-5
-            x = x + np.asarray(W["wo"], np.float64) @ act_in(y.reshape(Hq * D))         # Alg. 3 l.6
-            b = act_in(rmsnorm(x, W["norm2"], s.norm_eps))
-            hid = act_in if self.w_mx else None
+            x = x + np.asarray(W["wo"], np.float64) @ act_in(y.reshape(Hq * D), 1)      # Alg. 3 l.6
+            b = act_in(rmsnorm(x, W["norm2"], s.norm_eps), 2)
+            hid = (lambda t: act_in(t, 3)) if self.w_mx else None
             if s.n_experts > 0:
                 x = x + moe_ffn(b, W, s.top_k, self.route_margins, hid)
             else:

@@ -62,6 +62,7 @@ _SIGS = {
     "plt_set_carry": (C.c_int, [_P, _P, _Z]),
     "plt_get_hidden": (C.c_int, [_P, _P, _Z]),
     "plt_debug_layer": (C.c_int, [_P, _P, _I, _P, _P, _Z]),
+    "plt_debug_act_codes": (C.c_int, [_P, _I, _P, _Z, _P, _Z]),
     "plt_attn_pad32": (_I, [_I]),
     "plt_attn_pad": (_I, [_I, _I]),
     "plt_attn_scratch_bytes": (_Z, [_I, _I, _I, _I, _I]),
@@ -373,6 +374,17 @@ class KV:
         out = np.zeros_like(x_in)
         _check(lib().plt_debug_layer(self.model.h, self.h, layer, x_in.ctypes.data_as(_P), out.ctypes.data_as(_P), x_in.nbytes))
         return out
+
+    def debug_act_codes(self, which):
+        """Low-bit dense models: (e4m3 code bytes [rows, K], scale bytes [rows, 16 * ceil(K / 512)]) of the input of
+        projection `which` (0 QKV, 1 output, 2 gate/up, 3 down) of the layer the last debug_layer call ran."""
+        c = self.model.cfg
+        K = c.n_heads * c.head_dim if which == 1 else (c.ffn_hidden if which == 3 else c.d_model)
+        rows = self.batch * c.n_loops
+        codes = np.zeros((rows, K), np.uint8)
+        scales = np.zeros((rows, 16 * ((K + 511) // 512)), np.uint8)
+        _check(lib().plt_debug_act_codes(self.h, which, codes.ctypes.data_as(_P), codes.nbytes, scales.ctypes.data_as(_P), scales.nbytes))
+        return codes, scales
 
     def close(self):
         if self.h:

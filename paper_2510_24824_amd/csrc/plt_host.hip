@@ -89,6 +89,9 @@ struct plt_kv {
   uint8_t *a_codes, *a_scales;   // low-bit models: the quantised input of the next projection
   uint8_t* act_sc;               // low-bit mixture-of-experts models: block scales of the experts' hidden rows
   float* arg_v; int* arg_i;   // argmax chunk winners
+  // test hook (plt_debug_layer on a low-bit model): copies of the e4m3 codes / block scales that entered the layer's
+  // four projections, one slot per projection (allocated on first use)
+  uint8_t* dbg_codes = nullptr; uint8_t* dbg_scales = nullptr; size_t dbg_codes_slot = 0, dbg_scales_slot = 0; bool dbg_on = false;
   // the decode step's launch sequence as an instantiated HIP graph, valid for these arguments / this split count
   hipGraphExec_t graph_exec = nullptr;
   const int32_t* g_tokens = nullptr; int32_t* g_next = nullptr; float* g_logits = nullptr; int g_splits = -1;
@@ -329,7 +332,7 @@ static void kv_release(plt_kv* kv) {
   if (!kv) return;
   if (kv->graph_exec) (void)hipGraphExecDestroy(kv->graph_exec);
   void* ptrs[] = {kv->x, kv->a, kv->gout, kv->q, kv->z, kv->y, kv->act, kv->carry, kv->pos_dev, kv->attn_scratch,
-                  kv->arg_v, kv->arg_i, kv->moe_idx, kv->a_codes, kv->a_scales, kv->act_sc};
+                  kv->arg_v, kv->arg_i, kv->moe_idx, kv->a_codes, kv->a_scales, kv->act_sc, kv->dbg_codes, kv->dbg_scales};
   for (void* p : ptrs) if (p) (void)hipFree(p);
   delete kv;
 }
@@ -489,6 +492,14 @@ static int run_gemm_mx(plt_model* m, const Work& wk, const void* w, const uint8_
   return gemm_mx_splits(M, N, K);
 }
 
+// test hook: keeps a copy of the quantised input of projection `slot` (0 QKV, 1 output, 2 gate/up, 3 down)
+static void dbg_capture(plt_model* m, plt_kv* kv, const Work& wk, int slot, int R, int K) {
+  if (!kv->dbg_on) return;
+  (void)hipMemcpyAsync(kv->dbg_codes + slot * kv->dbg_codes_slot, wk.a_codes, (size_t)R * K, hipMemcpyDeviceToDevice, m->stream);
+  (void)hipMemcpyAsync(kv->dbg_scales + slot * kv->dbg_scales_slot, wk.a_scales, (size_t)R * mx_ascale_row_bytes(K),
+                       hipMemcpyDeviceToDevice, m->stream);
+}
+
 template <typename T>
 static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap rm, int cache, int variant,
                        KvView loc /*prefill local K/V + b0*/, int Bc, int n_prefill, int attn_L,
@@ -506,6 +517,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     const LayerW& w = m->layers[l];
     KvView v = kv_view(kv, l, cache);
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
+    if (m->mx) dbg_capture(m, kv, wk, 0, R, d);
     int S = m->mx ? run_gemm_mx(m, wk, w.wqkv, w.wqkv_sc, R, Nqkv, d, !rm.prefill)
                   : run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                       // Alg. 3 l.1
     if (m->kv8)
@@ -551,11 +563,13 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     }
     if (m->mx) {                                                                                 // Alg. 3 l.6
       if (!y_mx) launch_mx_quant_a<bf16_t>(s, (const bf16_t*)wk.y, wk.a_codes, wk.a_scales, R, Hq * D);
+      dbg_capture(m, kv, wk, 1, R, Hq * D);
       S = run_gemm_mx(m, wk, w.wo, w.wo_sc, R, d, Hq * D, dec);
     } else {
       S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);
     }
     norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, w.norm2, R);
+    if (m->mx) dbg_capture(m, kv, wk, 2, R, d);
     if (m->mx && c.n_experts > 0) {                          // mixture of experts on low-bit operands
       ProfScope prof(m, PLT_PROF_GEMM, dec);
       launch_moe_ffn_mx(s, wk.a_codes, wk.a_scales, (const bf16_t*)w.router, (const uint8_t*)w.wgu, w.wgu_sc,
@@ -565,6 +579,7 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
     } else if (m->mx) {                                      // low-bit gate/up and down projections
       S = run_gemm_mx(m, wk, w.wgu, w.wgu_sc, R, 2 * F, d, dec);
       launch_silu_mul_mx(s, wk.gout, S, (size_t)R * 2 * F, wk.a_codes, wk.a_scales, R, F);      // SwiGLU + e4m3 blocks
+      dbg_capture(m, kv, wk, 3, R, F);
       S = run_gemm_mx(m, wk, w.wdown, w.wdown_sc, R, d, F, dec);
     } else if (c.n_experts > 0) {                                   // mixture of experts: k slabs, one per selected expert
       ProfScope prof(m, PLT_PROF_GEMM, dec);
@@ -956,9 +971,30 @@ extern "C" int plt_debug_layer(plt_model* m, plt_kv* kv, int32_t layer, const fl
   if (host_nbytes != need) return fail(PLT_EINVAL, "plt_debug_layer: host buffers must have %zu bytes", need);
   int rc = copy_sync(kv, kv->x, host_x_in, need, hipMemcpyHostToDevice);
   if (rc != PLT_OK) return rc;
+  if (m->mx && c.n_experts == 0 && !kv->dbg_codes) {        // capture slots of the four quantised projection inputs
+    const int maxK = mx_max_k(c), R = kv->B * c.n_loops;
+    kv->dbg_codes_slot = align256((size_t)R * maxK); kv->dbg_scales_slot = align256((size_t)R * mx_ascale_row_bytes(maxK));
+    HIP_TRY(hipMalloc((void**)&kv->dbg_codes, 4 * kv->dbg_codes_slot));
+    HIP_TRY(hipMalloc((void**)&kv->dbg_scales, 4 * kv->dbg_scales_slot));
+  }
+  kv->dbg_on = kv->dbg_codes != nullptr;
   if (c.dtype == PLT_BF16) debug_layer_t<bf16_t>(m, kv, layer); else debug_layer_t<float>(m, kv, layer);
+  kv->dbg_on = false;
   HIP_TRY(hipGetLastError());
   return copy_sync(kv, host_x_out, kv->x, need, hipMemcpyDeviceToHost);
+}
+
+extern "C" int plt_debug_act_codes(plt_kv* kv, int32_t which, uint8_t* host_codes, size_t codes_nbytes,
+                                   uint8_t* host_scales, size_t scales_nbytes) {
+  if (!kv || !host_codes || !host_scales || which < 0 || which > 3) return fail(PLT_EINVAL, "plt_debug_act_codes: bad argument");
+  const plt_config& c = kv->m->cfg;
+  if (!kv->dbg_codes) return fail(PLT_ESTATE, "plt_debug_act_codes: needs a dense low-bit model and a plt_debug_layer call first");
+  const int K = which == 1 ? c.n_heads * c.head_dim : (which == 3 ? c.ffn_hidden : c.d_model), R = kv->B * c.n_loops;
+  const size_t nc = (size_t)R * K, ns = (size_t)R * mx_ascale_row_bytes(K);
+  if (codes_nbytes != nc || scales_nbytes != ns) return fail(PLT_EINVAL, "plt_debug_act_codes: buffers must have %zu and %zu bytes", nc, ns);
+  int rc = copy_sync(kv, host_codes, kv->dbg_codes + which * kv->dbg_codes_slot, nc, hipMemcpyDeviceToHost);
+  if (rc != PLT_OK) return rc;
+  return copy_sync(kv, host_scales, kv->dbg_scales + which * kv->dbg_scales_slot, ns, hipMemcpyDeviceToHost);
 }
 
 // ---- kernel-only hooks ----

@@ -309,3 +309,95 @@ def test_lowbit_model_with_attention_output_quantised_in_the_kernel(heads, D, kv
     weights = lively_weights(shape, 13, bf16=True, std=0.05)
     prompts = synth.token_ids((3, 7), shape.vocab, 14)
     run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 6, 0.08 * 9.0, kv_dtype=kv_dtype, w_dtype=B.PLT_MXFP4)
+
+
+def test_lowbit_layers_from_the_devices_own_activation_codes():
+    """A low-bit layer compared WITHOUT the rounding-boundary ambiguity of the quantisers.  A quantiser decides an
+    integer from a float; device (float32, bf16 attention internals) and oracle (float64) inputs differ in the last
+    bits, so a few per cent of the codes legitimately differ by one step and a free-running comparison needs a wide
+    bar (MX_MODEL_TOL).  Here every layer of the device gets the oracle's layer input (plt_debug_layer), the e4m3 codes
+    and scales that entered its four projections are read back (plt_debug_act_codes), and the oracle evaluates the
+    same layer with exactly those operands in place of its own quantised values.  Then
+      * the layer's output must agree to float accumulation level (bar 2e-3 on states of magnitude 3), so a wrong
+        scale, layout, operand order or epilogue anywhere between two quantisers fails;
+      * every device code must be a valid rounding of the value the oracle computed from the same upstream operands:
+        equal to the oracle's own code or its neighbour on the e4m3 grid (saturation at 448 included: both follow the
+        same rule; small elements of the attention output, whose bf16 softmax weights give it an absolute error of 2^-8
+        of the row maximum, may be further off in steps, not in value), at most 15 % of them different (measured 8 % for the attention output, which passes through a bf16
+        rounding on the device, a fraction of a per cent elsewhere), and without bias: the mean signed relative
+        difference between the device's and the oracle's dequantised rows stays below 1 % (a 5 % error in the SwiGLU
+        or norm arithmetic moves most elements to the neighbouring code in ONE direction and shifts that mean by 5 %)."""
+    from tests.helpers import oshape
+    shape = MX_SMALL
+    L, nl, d = shape.n_loops, shape.n_layers, shape.d_model
+    weights = lively_weights(shape, 9, bf16=True, std=0.05)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, w_dtype=B.PLT_MXFP4)
+    model = B.Model(cfg, B.pack_weights(cfg, weights))
+    Bn, n = 2, 9
+    kv = B.KV(model, Bn, 20)
+    prompts = synth.token_ids((Bn, n), shape.vocab, 10)
+    nxt, _ = kv.prefill(torch.from_numpy(np.ascontiguousarray(prompts, np.int32)).cuda())
+    nxt = nxt.cpu().numpy()
+    pos = n
+    carry = kv.get_carry()
+    orcs = []
+    for b in range(Bn):
+        orc = O.PLTOracle(oshape(shape), weights, kv_bf16=True, w_mx=True)
+        orc.kv = O.RingKV(orc._store, oshape(shape), pos + 1)
+        for m in range(nl):
+            e = kv.export(b, m, pos)
+            orc.kv.ks[m, :pos] = e["k_share"].transpose(1, 0, 2); orc.kv.vs[m, :pos] = e["v_share"].transpose(1, 0, 2)
+            for l in range(L - 1):
+                orc.kv.kr[l, m] = e["k_ring"][l].transpose(1, 0, 2); orc.kv.vr[l, m] = e["v_ring"][l].transpose(1, 0, 2)
+        orc.carry = carry[b].astype(np.float64).copy(); orc.pos = pos; orc.trace = []
+        orc.layer_trace = []
+        orc.clp_decode_step(int(nxt[b]))                      # free run: the layer inputs to teacher-force with
+        orc.x_in = {(l, m): a for (l, m, p, a, _) in orc.layer_trace}
+        orcs.append(orc)
+
+    def dequant(codes, scales, K):
+        blk = np.arange(K // 32)
+        sidx = (blk >> 4) * 16 + (blk & 3) * 4 + ((blk >> 2) & 3)                  # plt_mx_act_scale_index
+        ex = scales[:, sidx].astype(np.int64) - 127                                # [rows, K/32]
+        return synth.e4m3_from_bits(codes).astype(np.float64) * np.repeat(np.ldexp(1.0, ex), 32, axis=1), ex
+
+    worst_out, worst_bias, n_elem, n_diff = 0.0, 0.0, 0, 0
+    for m in range(nl):
+        kv.set_position(pos)
+        xin = np.zeros((Bn, L, d), np.float32)
+        for b in range(Bn):
+            for l in range(1, L + 1):
+                xin[b, l - 1] = orcs[b].x_in[(l, m)]
+        out = kv.debug_layer(m, xin)
+        stages = []
+        for st in range(4):
+            codes, scales = kv.debug_act_codes(st)
+            stages.append(dequant(codes, scales, codes.shape[1]))
+        for b in range(Bn):
+            orc = orcs[b]
+            orc.act_override = {(l, m, st): stages[st][0][b * L + l - 1] for l in range(1, L + 1) for st in range(4)}
+            orc.act_trace = []
+            for l in range(1, L + 1):
+                ref = orc.f(xin[b, l - 1].astype(np.float64), pos, l, orc.kv, layers=[m])
+                worst_out = max(worst_out, float(np.max(np.abs(out[b, l - 1] - ref))))
+            for (l, mm, st, t) in orc.act_trace:
+                dev, ex = stages[st][0][b * L + l - 1], stages[st][1][b * L + l - 1]
+                q_own, e_own = O.mx_quantize(t, "e4m3")
+                own = O.mx_dequantize(q_own, e_own)
+                same_scale = np.repeat(e_own == ex, 32)
+                # one grid step at the element's magnitude (2^-3 of its binade; 2^-9 of the block scale for subnormals)
+                mag = np.maximum(np.abs(own), np.abs(dev)) / np.repeat(np.ldexp(1.0, e_own), 32)
+                step = np.ldexp(1.0, np.maximum(np.floor(np.log2(np.maximum(mag, 2.0 ** -20))), -6).astype(np.int64) - 3) * np.repeat(np.ldexp(1.0, e_own), 32)
+                # the attention output reaches its quantiser through bf16 softmax weights and a bf16 store: an ABSOLUTE
+                # error of 2^-8 of the row's largest entry, which moves small elements by more than one of their steps
+                slack = (2.0 ** -8 if st == 1 else 2.0 ** -12) * float(np.max(np.abs(t)))
+                ok = np.where(same_scale, np.abs(dev - own) <= step * (1 + 1e-9) + slack, np.abs(dev - t) <= 2.0 ** -3 * np.abs(t) + step + slack)
+                assert np.all(ok), (m, b, l, st, np.where(~ok)[0][:8], dev[~ok][:8], own[~ok][:8], t[~ok][:8])
+                n_elem += dev.size; n_diff += int(np.sum(dev != own))
+                big = np.abs(own) > 0.05 * np.max(np.abs(own))
+                worst_bias = max(worst_bias, abs(float(np.mean((dev[big] - own[big]) / own[big]))))
+            orc.act_override = None
+    print(f"layer outputs from the device's own codes: max-abs {worst_out:.2e}; codes that are the oracle's neighbour: {n_diff} of {n_elem}; "
+          f"largest mean signed deviation of a quantised row {worst_bias:.2e}")
+    assert worst_out <= 2e-3 and worst_bias <= 1e-2 and n_diff <= 0.15 * n_elem, (worst_out, worst_bias, n_diff, n_elem)
+    kv.close(); model.close()

@@ -261,3 +261,42 @@ def test_unquantised_expert_hidden_is_caught(monkeypatch):
     orig = O.swiglu_ffn
     monkeypatch.setattr(O, "swiglu_ffn", lambda b, wg, wu, wd, hidden_in=None: orig(b, wg, wu, wd, None))
     assert some_pin_fails()
+
+
+def test_activation_trace_and_override_hooks_change_no_arithmetic():
+    """The bookkeeping hooks of the low-bit model (act_trace records every value about to be block-quantised;
+    act_override substitutes given vectors for the oracle's own quantised ones; layers= applies a subset of the stack)
+    are inert: tracing changes nothing, overriding every stage with the oracle's OWN quantised value reproduces the
+    plain run bit for bit, walking the layers one at a time equals walking them together, and overriding one stage with
+    a different vector does change the result (the hook is really consulted)."""
+    s = synth.ModelShape(**{**SMALL.__dict__, "ffn_hidden": 64})      # every K a multiple of 32
+    w = small_weights(shape=s)
+    toks = synth.token_ids((1, 6), s.vocab, 5)[0]
+    plain = O.PLTOracle(oshape(s), w, kv_bf16=True, w_mx=True)
+    plain.clp_prefill(list(toks), 8)
+    ref = np.stack(plain.trace)
+
+    traced = O.PLTOracle(oshape(s), w, kv_bf16=True, w_mx=True)
+    traced.act_trace = []; traced.layer_trace = []
+    traced.clp_prefill(list(toks), 8)
+    assert np.array_equal(np.stack(traced.trace), ref)
+    assert len(traced.act_trace) == len(toks) * s.n_loops * s.n_layers * 4
+    assert sorted({st for (_, _, st, _) in traced.act_trace}) == [0, 1, 2, 3]
+
+    # the last position again, layer by layer, every stage overridden with the oracle's own quantised value
+    p = len(toks) - 1
+    mine = {}
+    for (l, m, st, t) in traced.act_trace[-s.n_loops * s.n_layers * 4:]:
+        mine[(l, m, st)] = O.mx_dequantize(*O.mx_quantize(t, "e4m3"))
+    x_in = {(l, m): a for (l, m, pp, a, b) in traced.layer_trace if pp == p}
+    x_out = {(l, m): b for (l, m, pp, a, b) in traced.layer_trace if pp == p}
+    traced.act_override = mine
+    for l in range(1, s.n_loops + 1):
+        x = x_in[(l, 0)]
+        for m in range(s.n_layers):
+            x = traced.f(x, p, l, traced.kv, layers=[m])
+            assert np.array_equal(x, x_out[(l, m)]), (l, m)
+    # a different vector at one stage moves the output
+    moved = dict(mine); moved[(1, 0, 3)] = mine[(1, 0, 3)] * 1.25
+    traced.act_override = moved
+    assert not np.array_equal(traced.f(x_in[(1, 0)], p, 1, traced.kv, layers=[0]), x_out[(1, 0)])
