@@ -319,6 +319,13 @@ int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* dev_a,
              const void* dev_w, float* dev_c, void* dev_scratch, size_t scratch_bytes,
              void* hip_stream);
 size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K);
+/* Kernel-only form of the prefill's output / down projection, whose epilogue adds the product to the residual
+ * stream [block f's two residual connections around Alg. 3 l.6 and the feed-forward]: x [M, N] (float, device,
+ * updated in place) += a [M, K] * w [N, K]^T with bf16 a and w (device), float accumulation.  Only for the row counts
+ * that take the 256 x 256 tile kernel (M >= 512, at least 200 tiles, K a multiple of 64); any other shape returns
+ * PLT_EINVAL and leaves x untouched (the model adds those products in its residual + norm kernel instead). */
+int plt_gemm_residual(int32_t M, int32_t N, int32_t K, const void* dev_a, const void* dev_w, float* dev_x,
+                      void* hip_stream);
 
 /* Kernel-only mixture-of-experts feed-forward [appendix, "MoE Models Recipe"; router reading in the
  * header comment]: for R rows a [R, d] (already normed), router [E, d], wgu [E, 2F, d], wdown [E, d, F]

@@ -74,6 +74,7 @@ _SIGS = {
     "plt_attn_pack_v": (C.c_int, [_I, _I, _I, _I, _P, _P, _P]),
     "plt_gemm": (C.c_int, [_I, _I, _I, _I, _P, _P, _P, _P, _Z, _P]),
     "plt_gemm_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_gemm_residual": (C.c_int, [_I, _I, _I, _P, _P, _P, _P]),
     "plt_moe_weight_index": (C.c_int64, [_I, _I, _I]),
     "plt_moe_scratch_bytes": (_Z, [_I] * 6),
     "plt_moe_ffn": (C.c_int, [_I] * 6 + [_P] * 8 + [_Z, _P]),
@@ -486,6 +487,13 @@ def gemm(dtype, a, w):
     scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
     _check(lib().plt_gemm(dtype, M, N, K, _ptr(a.contiguous()), _ptr(w.contiguous()), _ptr(c), _ptr(scratch), nb, _stream()))
     return c
+
+
+def gemm_residual(a, w, x):
+    """x [M,N] float32 (device, updated in place) += a [M,K] w [N,K]^T, bf16 device tensors, through the prefill tile kernel."""
+    M, K = a.shape
+    _check(lib().plt_gemm_residual(M, w.shape[0], K, _ptr(a.contiguous()), _ptr(w.contiguous()), _ptr(x), _stream()))
+    return x
 
 
 def moe_ffn(dtype, a, router, w_gate, w_up, w_down, top_k):

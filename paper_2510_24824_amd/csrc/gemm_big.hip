@@ -8,6 +8,10 @@
 //   EPI_F32    : float c[M,N]                                        (QKV, output, down projections)
 //   EPI_SWIGLU : w = [W_gate; W_up] ([2F,K]); the tile holds 128 gate columns and the matching 128 up
 //                columns and writes silu(gate) * up as bf16 act[M,F]              (SwiGLU, fused)
+//   EPI_RESID  : float c[M,N] += product (the residual stream updated in place by the output / down projection)
+//   EPI_ROPE   : w = W_qkv of a prefill chunk; waves as 4 x 2 so that a wave holds whole heads (64 rows x 128
+//                columns): rotary embedding, gate logit and the cache appends straight from the accumulators
+//                [Alg. 3 l.1, l.4; Sec. 2.2.2] - the float QKV matrix is never written
 #include "plt_internal.h"
 
 namespace plt {
@@ -17,7 +21,141 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 namespace {
 
 constexpr int GB_BK = 64;
-enum { EPI_F32 = 0, EPI_SWIGLU = 1 };
+#ifndef GB_PFD_VALUE
+#define GB_PFD_VALUE 0
+#endif
+constexpr int GB_PFD = GB_PFD_VALUE;      // prefill tiles: slices of last-level-cache prefetch beyond the slice being loaded
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_RESID = 3 };
+
+// What the EPI_ROPE epilogue needs beyond the product: row gm of the chunk is position gm % n of chunk sequence gm / n
+struct RopeEpi {
+  const float* gate_w; const float* gate_b; const double* inv_freq;
+  bf16_t* q_out; float* z_out;
+  KvView kv;
+  int n, loop, Hq, Hkv, mode;
+};
+
+// four consecutive cache elements from four floats (destination aligned to the four)
+__device__ inline void store4(bf16_t* dst, const f32x4 v) { *reinterpret_cast<bf16x4*>(dst) = __builtin_convertvector(v, bf16x4); }
+__device__ inline void store4(fp8_t* dst, const f32x4 v) {
+  float c[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) c[e] = fminf(fmaxf(v[e], -448.f), 448.f);
+  const int pk = __builtin_amdgcn_cvt_pk_fp8_f32(c[0], c[1], 0, false);
+  *reinterpret_cast<unsigned*>(dst) = (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(c[2], c[3], pk, true);
+}
+
+// S3 of the layer on a wave's accumulators: acc[i][j][e] = row row0 + 16 i + m16, column col0 + 16 j + 4 g + e of
+// the QKV product; the wave's NT*16 columns are whole heads of D.  Same arithmetic as k_rope_append_tile: angle in
+// turns reduced in double, hardware sine / cosine, pairs (f, f + D/2); the gate logit from the un-rotated query;
+// first-loop K/V into the shared cache, later loops' into the chunk's own K/V and (last w positions) the rings.
+template <int D, typename KT, int MI, int NT>
+__device__ inline void rope_epilogue(f32x4 (&acc)[MI][NT], const RopeEpi& ep, int row0, int col0, int M, int N, int m16, int g) {
+  constexpr int HT = D / 16, PT = HT / 2, half = D / 2;     // 16-column tiles per head, per rotation half
+  static_assert((NT * 16) % D == 0, "a wave holds whole heads");
+  const int Hq = ep.Hq, Hkv = ep.Hkv, n = ep.n, mode = ep.mode, loop = ep.loop;
+  const KvView& kv = ep.kv;
+#pragma unroll
+  for (int hh = 0; hh < NT / HT; ++hh) {
+    const int c0 = col0 + hh * D;
+    if (c0 >= N) break;                                      // (the same for the whole wave)
+    const int hs = c0 / D;
+    const bool is_q = hs < Hq, is_k = !is_q && hs < Hq + Hkv;
+    const bool want_z = is_q && mode == 0 && loop > 0;
+    double fr[PT][4];
+    float gw_lo[PT][4], gw_hi[PT][4];
+    if (is_q || is_k) {
+#pragma unroll
+      for (int t = 0; t < PT; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) fr[t][e] = ep.inv_freq[16 * t + 4 * g + e] * 0.15915494309189535;
+    }
+    if (want_z) {
+#pragma unroll
+      for (int t = 0; t < PT; ++t) {
+        const float4 a = *reinterpret_cast<const float4*>(ep.gate_w + hs * D + 16 * t + 4 * g);
+        const float4 b = *reinterpret_cast<const float4*>(ep.gate_w + hs * D + half + 16 * t + 4 * g);
+        gw_lo[t][0] = a.x; gw_lo[t][1] = a.y; gw_lo[t][2] = a.z; gw_lo[t][3] = a.w;
+        gw_hi[t][0] = b.x; gw_hi[t][1] = b.y; gw_hi[t][2] = b.z; gw_hi[t][3] = b.w;
+      }
+    }
+    const int kh = is_k ? hs - Hq : hs - Hq - Hkv;
+    const bool own = mode == 0 && loop > 0;                  // non-first loop of the method: own K/V (+ ring tail)
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int gm = row0 + i * 16 + m16;
+      const bool ok = gm < M;
+      const int b = ok ? gm / n : 0, p = ok ? gm - b * n : 0;
+      f32x4* lo = &acc[i][hh * HT];
+      f32x4* hi = &acc[i][hh * HT + PT];
+      if (want_z) {                                          // gate logit on the un-rotated query [Alg. 3 l.4]
+        float zp = 0.f;
+#pragma unroll
+        for (int t = 0; t < PT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) zp += lo[t][e] * gw_lo[t][e] + hi[t][e] * gw_hi[t][e];
+        zp = row4_add_f32(zp);                               // the four lanes that share the row
+        if (ok && g == 0) ep.z_out[(size_t)gm * Hq + hs] = zp + ep.gate_b[hs];
+      }
+      if (is_q || is_k) {
+#pragma unroll
+        for (int t = 0; t < PT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            double a = (double)p * fr[t][e];
+            a -= rint(a);
+            const float sn = __builtin_amdgcn_sinf((float)a), c = __builtin_amdgcn_cosf((float)a);
+            const float l0 = lo[t][e], h0 = hi[t][e];
+            lo[t][e] = l0 * c - h0 * sn; hi[t][e] = h0 * c + l0 * sn;
+          }
+      }
+      if (!ok) continue;
+      if (is_q) {
+        bf16_t* dst = ep.q_out + (size_t)gm * Hq * D + (size_t)hs * D + 4 * g;
+#pragma unroll
+        for (int t = 0; t < PT; ++t) { store4(dst + 16 * t, lo[t]); store4(dst + half + 16 * t, hi[t]); }
+        continue;
+      }
+      if (mode == 2 && loop > 0) continue;                   // KV-share ablation: non-first loops keep no K/V
+      const size_t stream = own ? (size_t)b * Hkv + kh : (size_t)(kv.b0 + b) * Hkv + kh;
+      const size_t stream_elems = (size_t)(own ? kv.n_pad_loc : kv.n_pad) * D;
+      const bool ring = own && p >= n - kv.w;                // the w most recent entries also enter the ring
+      const int slot = p % kv.w;
+      const size_t rstream = (((size_t)(kv.b0 + b) * kv.n_rings + (loop - 1)) * Hkv + kh) * (size_t)kv.w_pad * D;
+      if (is_k) {
+        KT* dst = (KT*)(own ? kv.k_loc : kv.k_share) + stream * stream_elems;
+#pragma unroll
+        for (int t = 0; t < PT; ++t) {
+          store4(dst + kblk_index<KT>(p, 16 * t + 4 * g, D), lo[t]);
+          store4(dst + kblk_index<KT>(p, half + 16 * t + 4 * g, D), hi[t]);
+        }
+        if (ring) {
+          KT* rd = (KT*)kv.k_ring + rstream;
+#pragma unroll
+          for (int t = 0; t < PT; ++t) {
+            store4(rd + kblk_index<KT>(slot, 16 * t + 4 * g, D), lo[t]);
+            store4(rd + kblk_index<KT>(slot, half + 16 * t + 4 * g, D), hi[t]);
+          }
+        }
+      } else {
+        // V is stored position-fastest: a lane's four features of one position are four separate elements; the 16
+        // lanes of a row group write 16 consecutive positions of a feature, i.e. whole 16-byte chunks per instruction
+        KT* dst = (KT*)(own ? kv.v_loc : kv.v_share) + stream * stream_elems;
+#pragma unroll
+        for (int t = 0; t < HT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) st<KT>(dst + vblk_index<KT>(p, 16 * t + 4 * g + e, D), lo[t][e]);
+        if (ring) {
+          KT* rd = (KT*)kv.v_ring + rstream;
+#pragma unroll
+          for (int t = 0; t < HT; ++t)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) st<KT>(rd + vblk_index<KT>(slot, 16 * t + 4 * g + e, D), lo[t][e]);
+        }
+      }
+    }
+  }
+}
 
 // Operand tiles go HBM -> LDS directly (global_load_lds, 16 bytes per lane, no register staging), two
 // stages deep, one barrier per K slice.  A tile row holds 64 K-values = 8 chunks of 16 bytes; chunk kc of
@@ -32,9 +170,9 @@ enum { EPI_F32 = 0, EPI_SWIGLU = 1 };
 //   256 x 64, 4 x 2 waves of 64 x 32 : the gate/up projection of decode steps with 129..256 rows, SwiGLU fused
 //       (all rows of the step in one tile, whole K: no split-K slabs, no separate activation kernel).  The same
 //       tile for the plain QKV projection measured slower than the weight-streaming kernel and is not used.
-template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2>
+template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t, int PFD = 0>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
-                                                          void* __restrict__ out, int M, int N, int K) {
+                                                          void* __restrict__ out, int M, int N, int K, const RopeEpi ep) {
   // N: EPI_F32: output columns (= rows of w); EPI_SWIGLU: F (w has 2F rows, the output F columns)
   constexpr int THREADS = WM * WN * 64;
   constexpr int MI = BM / WM / 16, NT = BN / WN / 16;       // 16 x 16 tiles per wave: rows, columns
@@ -45,8 +183,22 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
   extern __shared__ __attribute__((aligned(16))) char gb_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, m16 = lane & 15, g = lane >> 4;
   const int wm = wv / WN, wn = wv % WN;
-  const int m0 = blockIdx.y * BM;
-  const int n0 = blockIdx.x * (EPI == EPI_SWIGLU ? HALF : BN);
+  int tile_m = blockIdx.y, tile_n = blockIdx.x;
+  if constexpr (BM == 256 && BN == 256) {
+    // Prefill tiles: which tile a workgroup takes follows the dies.  Workgroups go to the 8 dies round-robin in launch
+    // order, and a die's cache (4 MB) only helps tiles that run on it AT THE SAME TIME (a tile streams 2 MB of
+    // operands per 2048 of K): so die x takes a contiguous run of the tile sequence in which 32 consecutive tiles are
+    // 8 row tiles x 4 column tiles (12 operand panels for 32 tiles instead of ~17 in launch order).
+    constexpr int NXCD = 8, PR = 8;
+    const int TM = gridDim.y, TN = gridDim.x, total = TM * TN;
+    const int bid = blockIdx.y * TN + blockIdx.x, x = bid % NXCD, q = bid / NXCD;
+    const int v = x * (total / NXCD) + min(x, total % NXCD) + q;         // position in the die-major sequence
+    const int panel = v / (PR * TN), within = v - panel * (PR * TN);
+    const int rows = min(PR, TM - panel * PR);                            // (the last panel may be shorter)
+    tile_n = within / rows; tile_m = panel * PR + within - tile_n * rows;
+  }
+  const int m0 = tile_m * BM;
+  const int n0 = tile_n * (EPI == EPI_SWIGLU ? HALF : BN);
   const int w_rows = EPI == EPI_SWIGLU ? 2 * N : N;
   // global row of w behind local tile row r (rows beyond the matrix: clamped, their outputs are never stored)
   auto wrow = [&](int r) -> int {
@@ -88,6 +240,25 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
       dma16(pw[i] + k0, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
   };
   const int ks_total = K / GB_BK;
+  // PFD > 0: the slice PFD steps beyond the one being loaded is pulled into the last-level cache - every thread
+  // requests one 128-byte line of it (a tile row's 64 K-values) with a 4-byte direct load into a spare LDS word
+  // (no register is written, nothing reads the word).  All workgroups of a die work on the same few row and column
+  // tiles at about the same K, so a slice's first request otherwise meets the memory latency (1-2 us) with one
+  // slice time of slack; this way it meets it PFD slices early.
+  static_assert(PFD == 0 || (BM + BN == THREADS && STAGES == 2), "one line per thread");
+  const bf16_t* pf_row = nullptr;
+  if constexpr (PFD > 0) {
+    if (tid < BM) { int gm = m0 + tid; if (gm >= M) gm = M - 1; pf_row = a + (size_t)gm * K; }
+    else pf_row = w + (size_t)wrow(tid - BM) * K;
+  }
+  auto prefetch = [&](int ks) {
+    if (ks >= ks_total) ks = ks_total - 1;
+    const unsigned dst = lds0 + (unsigned)(STAGES * STAGE_BYTES) + __builtin_amdgcn_readfirstlane((unsigned)wv * 256);
+    const bf16_t* src = pf_row + (size_t)ks * GB_BK;
+    unsigned keep_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(dst), "v"(src) : "memory");
+  };
 
   f32x4 acc[MI][NT];
 #pragma unroll
@@ -102,40 +273,69 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
   // trip), so it runs three stages and waits only for the OLDEST slice in flight (loads return in order)
 #pragma unroll
   for (int st = 0; st < STAGES - 1; ++st) if (st < ks_total) issue(st);
+  if constexpr (PFD > 0) prefetch(PFD);
   for (int ks = 0; ks < ks_total; ++ks) {
-    // this wave's part of slice ks has landed: everything but the (STAGES - 2) younger slices still in flight
-    if (STAGES == 2 || ks + STAGES - 2 >= ks_total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // this wave's part of slice ks has landed: everything but the (STAGES - 2) younger slices still in flight (and
+    // the one prefetch request issued after it: loads return in order)
+    if constexpr (PFD > 0) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+    else if (STAGES == 2 || ks + STAGES - 2 >= ks_total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(%0)" :: "n"((STAGES - 2) * (DMA_A + DMA_W)) : "memory");
-    // ... and everyone's; every wave is done with slice ks - 1, whose stage is refilled next.  With more than two
-    // stages the bare barrier instruction: __syncthreads() would drain the younger slices too (its fence waits for
+    // ... and everyone's; every wave is done with slice ks - 1, whose stage is refilled next.  With loads that must
+    // stay in flight across it the bare barrier instruction: __syncthreads() would drain them (its fence waits for
     // every load in flight); the asm statements on both sides keep the LDS reads where they are
-    if (STAGES == 2) __syncthreads(); else __builtin_amdgcn_s_barrier();
+    if (STAGES == 2 && PFD == 0) __syncthreads(); else __builtin_amdgcn_s_barrier();
     if (ks + STAGES - 1 < ks_total) issue(ks + STAGES - 1);
     else asm volatile("" ::: "memory");
+    if constexpr (PFD > 0) prefetch(ks + STAGES - 1 + PFD);      // (always one request per step: the wait above counts on it)
     const char* As = gb_lds + (ks % STAGES) * STAGE_BYTES;
     const char* Ws = As + A_BYTES;
+    // Fragment reads run ahead of the matrix cores inside the slice: the (k32, row tile) steps are one sequence, the
+    // activation fragment of step t + PF is requested before the MFMAs of step t, the weight fragments of the next
+    // k32 at the start of the current one - a wave then waits for an LDS round trip only at the head of a slice
+    constexpr int KS32 = GB_BK / 32, STEPS = KS32 * MI, PF = STEPS > 3 ? 3 : STEPS - 1;
+    constexpr int FWS = (NT + MI - 1) / MI;             // weight fragments of the next k32 requested per step
+    auto ld_fw = [&](int k32, int j) -> uint4 {
+      // EPI_SWIGLU: the first half of the tiles = this wave's gate columns, the second half = the matching up columns
+      const int r = EPI == EPI_SWIGLU ? (j < NT / 2 ? wn * (NT * 8) + j * 16 : HALF + wn * (NT * 8) + (j - NT / 2) * 16)
+                                      : wn * (NT * 16) + j * 16;
+      return *reinterpret_cast<const uint4*>(Ws + (r + m16) * 128 + (sw0 ^ (k32 * 64)));   // chunk index ^ 4 per k32
+    };
+    auto ld_fa = [&](int t) -> uint4 {
+      const int k32 = t / MI, i = t % MI;
+      return *reinterpret_cast<const uint4*>(As + (wm * (MI * 16) + i * 16 + m16) * 128 + (sw0 ^ (k32 * 64)));
+    };
+    uint4 fw[2][NT], fa[PF + 1];
 #pragma unroll
-    for (int k32 = 0; k32 < GB_BK / 32; ++k32) {
-      const int sw = sw0 ^ (k32 * 64);                  // chunk index ^ 4
-      uint4 fw[NT];
+    for (int j = 0; j < NT; ++j) fw[0][j] = ld_fw(0, j);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-        // EPI_SWIGLU: the first half of the tiles = this wave's gate columns, the second half = the matching up columns
-        const int r = EPI == EPI_SWIGLU ? (j < NT / 2 ? wn * (NT * 8) + j * 16 : HALF + wn * (NT * 8) + (j - NT / 2) * 16)
-                                        : wn * (NT * 16) + j * 16;
-        fw[j] = *reinterpret_cast<const uint4*>(Ws + (r + m16) * 128 + sw);
-      }
+    for (int t = 0; t < PF; ++t) fa[t] = ld_fa(t);
+    __builtin_amdgcn_sched_group_barrier(0x100, NT + PF, 0);          // the slice's first fragments, all requested at once
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const uint4 fa = *reinterpret_cast<const uint4*>(As + (wm * (MI * 16) + i * 16 + m16) * 128 + sw);
+    for (int t = 0; t < STEPS; ++t) {
+      const int k32 = t / MI, i = t % MI;
+      int reads = 0;
+      if (k32 + 1 < KS32)
 #pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[j]),
-                                                             __builtin_bit_cast(bf16x8, fa), acc[i][j], 0, 0, 0);
-      }
+        for (int f = 0; f < FWS; ++f) if (i * FWS + f < NT) { fw[(k32 + 1) & 1][i * FWS + f] = ld_fw(k32 + 1, i * FWS + f); ++reads; }
+      if (t + PF < STEPS) { fa[(t + PF) % (PF + 1)] = ld_fa(t + PF); ++reads; }
+#pragma unroll
+      for (int j = 0; j < NT; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fw[k32 & 1][j]),
+                                                           __builtin_bit_cast(bf16x8, fa[t % (PF + 1)]), acc[i][j], 0, 0, 0);
+      // keep this order in the instruction stream: the step's LDS reads, then its MFMAs (the scheduler otherwise
+      // sinks every read to just before its first use, and the wave waits out each round trip)
+      if (reads == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      else if (reads == 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+      else if (reads == 3) __builtin_amdgcn_sched_group_barrier(0x100, 3, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);
     }
   }
+  if constexpr (PFD > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the last prefetch words have landed in this workgroup's LDS
   // acc[i][j][e]: row m0 + wm*MI*16 + i*16 + m16, column (tile j) + 4*g + e
+  if constexpr (EPI == EPI_ROPE) {
+    rope_epilogue<D, KT, MI, NT>(acc, ep, m0 + wm * (MI * 16), n0 + wn * (NT * 16), M, N, m16, g);
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int gm = m0 + wm * (MI * 16) + i * 16 + m16;
@@ -160,22 +360,27 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int gn = n0 + wn * (NT * 16) + j * 16 + 4 * g;
-        if (gn + 3 < N && (N & 3) == 0) *reinterpret_cast<f32x4*>(o + gn) = acc[i][j];
-        else for (int e = 0; e < 4; ++e) if (gn + e < N) o[gn + e] = acc[i][j][e];
+        if (EPI == EPI_RESID) {                        // every element belongs to one lane of one workgroup: plain read-add-write
+          if (gn + 3 < N && (N & 3) == 0) *reinterpret_cast<f32x4*>(o + gn) = *reinterpret_cast<const f32x4*>(o + gn) + acc[i][j];
+          else for (int e = 0; e < 4; ++e) if (gn + e < N) o[gn + e] += acc[i][j][e];
+        } else {
+          if (gn + 3 < N && (N & 3) == 0) *reinterpret_cast<f32x4*>(o + gn) = acc[i][j];
+          else for (int e = 0; e < 4; ++e) if (gn + e < N) o[gn + e] = acc[i][j][e];
+        }
       }
     }
   }
 }
 
-template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2>
-void tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, void* out, int M, int N, int K) {
-  constexpr int LDS_BYTES = STAGES * (BM + BN) * GB_BK * 2;     // stages x (A tile + W tile)
+template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t, int PFD = 0>
+void tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, void* out, int M, int N, int K, const RopeEpi& ep = RopeEpi{}) {
+  constexpr int LDS_BYTES = STAGES * (BM + BN) * GB_BK * 2 + (PFD > 0 ? WM * WN * 64 * 4 : 0);     // stages x (A tile + W tile) (+ the prefetch's landing area)
   // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
-  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN, STAGES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN, STAGES, D, KT, PFD>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   (void)attr_once;
   const int ncols = EPI == EPI_SWIGLU ? BN / 2 : BN;             // output columns per tile
   dim3 grid((N + ncols - 1) / ncols, (M + BM - 1) / BM);
-  hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN, STAGES>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K);
+  hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN, STAGES, D, KT, PFD>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K, ep);
 }
 
 }  // namespace
@@ -188,11 +393,35 @@ bool gemm_big_applies(int M, int N, int K) {
 }
 
 void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
-  tile_launch<EPI_F32, 256, 256, 2, 4>(s, a, w, (void*)c, M, N, K);
+  tile_launch<EPI_F32, 256, 256, 2, 4, 2, 128, bf16_t, GB_PFD>(s, a, w, (void*)c, M, N, K);
+}
+
+void launch_gemm_big_resid(hipStream_t s, const bf16_t* a, const bf16_t* w, float* x, int M, int N, int K) {
+  tile_launch<EPI_RESID, 256, 256, 2, 4, 2, 128, bf16_t, GB_PFD>(s, a, w, (void*)x, M, N, K);
 }
 
 void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
-  tile_launch<EPI_SWIGLU, 256, 256, 2, 4>(s, a, wgu, (void*)act, M, F, K);
+  tile_launch<EPI_SWIGLU, 256, 256, 2, 4, 2, 128, bf16_t, GB_PFD>(s, a, wgu, (void*)act, M, F, K);
+}
+
+// QKV projection of a prefill chunk with S3 (rotary embedding, gate logit, cache appends) as its epilogue: for bf16
+// models with heads of 64 or 128 whose chunk rows are whole sequences of n positions; not for the per-loop-cache modes.
+bool gemm_rope_applies(int M, int N, int K, int D) {
+  const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
+  return M >= 512 && tiles >= 128 && (K % GB_BK) == 0 && (D == 64 || D == 128) && N % D == 0;
+}
+
+void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
+                          const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, int n, int loop, const Dims& dm,
+                          const double* inv_freq, int mode, bool kv8) {
+  const RopeEpi ep{gate_w, gate_b, inv_freq, q_out, z_out, kv, n, loop, dm.Hq, dm.Hkv, mode};
+  if (dm.D == 128) {
+    if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, fp8_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
+    else tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, bf16_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
+  } else {
+    if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 64, fp8_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
+    else tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 64, bf16_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
+  }
 }
 
 // Decode step: act[M, F] = silu(a Wg^T) * (a Wu^T) for up to 256 rows in one launch, no slabs.

@@ -513,19 +513,29 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
   const int Nqkv = (Hq + 2 * Hkv) * D;
   Dims dm{rm.prefill ? Bc : kv->B, attn_L, Hq, Hkv, D, d, F, c.vocab};
   if (layer_end < 0) layer_end = c.n_layers;
+  const bool big_resid = c.dtype == PLT_BF16 && !m->mx;
   for (int l = layer_beg; l < layer_end; ++l) {
     const LayerW& w = m->layers[l];
     KvView v = kv_view(kv, l, cache);
     v.k_loc = loc.k_loc; v.v_loc = loc.v_loc; v.n_pad_loc = loc.n_pad_loc; v.b0 = loc.b0;
     if (m->mx) dbg_capture(m, kv, wk, 0, R, d);
-    int S = m->mx ? run_gemm_mx(m, wk, w.wqkv, w.wqkv_sc, R, Nqkv, d, !rm.prefill)
-                  : run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                       // Alg. 3 l.1
-    if (m->kv8)
-      launch_rope_append<bf16_t, fp8_t>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (bf16_t*)wk.q, wk.z, v, rm,
-                                        R, dm, m->inv_freq, variant);
-    else
-      launch_rope_append<T, T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
-                               dm, m->inv_freq, variant);
+    int S = 1;
+    if (!m->mx && c.dtype == PLT_BF16 && rm.prefill && variant != V_OWN_KV && R % rm.rows_per_seq == 0 &&
+        gemm_rope_applies(R, Nqkv, d, D)) {
+      // prefill chunk: S3 runs as the projection's epilogue (no float QKV matrix)                  // Alg. 3 l.1, l.4
+      ProfScope prof(m, PLT_PROF_GEMM, false);
+      launch_gemm_big_rope(s, (const bf16_t*)wk.a, (const bf16_t*)w.wqkv, R, Nqkv, d, w.gate_w, w.gate_b, (bf16_t*)wk.q,
+                           wk.z, v, rm.rows_per_seq, rm.loop_fixed, dm, m->inv_freq, variant, m->kv8);
+    } else {
+      S = m->mx ? run_gemm_mx(m, wk, w.wqkv, w.wqkv_sc, R, Nqkv, d, !rm.prefill)
+                : run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                         // Alg. 3 l.1
+      if (m->kv8)
+        launch_rope_append<bf16_t, fp8_t>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (bf16_t*)wk.q, wk.z, v, rm,
+                                          R, dm, m->inv_freq, variant);
+      else
+        launch_rope_append<T, T>(s, wk.gout, S, (size_t)R * Nqkv, w.gate_w, w.gate_b, (T*)wk.q, wk.z, v, rm, R,
+                                 dm, m->inv_freq, variant);
+    }
     const bool dec = !rm.prefill;
     const int plain = variant != V_PLT;
     // low-bit models, decode: the attention kernel writes y as e4m3 blocks itself (no scale padding needed)
@@ -565,6 +575,10 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       if (!y_mx) launch_mx_quant_a<bf16_t>(s, (const bf16_t*)wk.y, wk.a_codes, wk.a_scales, R, Hq * D);
       dbg_capture(m, kv, wk, 1, R, Hq * D);
       S = run_gemm_mx(m, wk, w.wo, w.wo_sc, R, d, Hq * D, dec);
+    } else if (big_resid && gemm_big_applies(R, d, Hq * D)) {      // many rows: the residual add is the projection's epilogue
+      ProfScope prof(m, PLT_PROF_GEMM, dec);
+      launch_gemm_big_resid(s, (const bf16_t*)wk.y, (const bf16_t*)w.wo, wk.x, R, d, Hq * D);
+      S = 0;
     } else {
       S = run_gemm(m, wk.y, w.wo, wk.gout, R, d, Hq * D, dec);
     }
@@ -595,9 +609,17 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       S = run_gemm(m, wk.a, w.wgu, wk.gout, R, 2 * F, d, dec);
       launch_silu_mul<T>(s, wk.gout, S, (size_t)R * 2 * F, (T*)wk.act, R, F);
     }
-    if (c.n_experts == 0 && !m->mx) S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
+    if (c.n_experts == 0 && !m->mx) {
+      if (big_resid && gemm_big_applies(R, d, F)) {
+        ProfScope prof(m, PLT_PROF_GEMM, dec);
+        launch_gemm_big_resid(s, (const bf16_t*)wk.act, (const bf16_t*)w.wdown, wk.x, R, d, F);
+        S = 0;
+      } else {
+        S = run_gemm(m, wk.act, w.wdown, wk.gout, R, d, F, dec);
+      }
+    }
     const float* gain = l + 1 < c.n_layers ? m->layers[l + 1].norm1 : next_gain;
-    norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, gain, R);
+    if (S > 0 || gain) norm_to_a<T>(m, wk, wk.gout, S, (size_t)R * d, gain, R);      // (nothing left to do otherwise)
   }
 }
 
@@ -1283,6 +1305,15 @@ __global__ void k_sum_slabs(const float* __restrict__ p, float* __restrict__ c, 
 extern "C" size_t plt_gemm_scratch_bytes(int32_t M, int32_t N, int32_t K) {
   if (M < 1 || N < 1 || K < 1) { fail(PLT_EINVAL, "plt_gemm_scratch_bytes: bad shape"); return 0; }
   return align256((size_t)gemm_bf16_splits_any(M, N, K) * M * N * 4);
+}
+
+extern "C" int plt_gemm_residual(int32_t M, int32_t N, int32_t K, const void* a, const void* w, float* x, void* hip_stream) {
+  if (M < 1 || N < 1 || K < 1 || !a || !w || !x) return fail(PLT_EINVAL, "plt_gemm_residual: bad argument");
+  if ((long)M > 256L * 65535 || !gemm_big_applies(M, N, K))
+    return fail(PLT_EINVAL, "plt_gemm_residual: only shapes that take the 256 x 256 tile kernel (M >= 512, >= 200 tiles, K %% 64 == 0)");
+  launch_gemm_big_resid((hipStream_t)hip_stream, (const bf16_t*)a, (const bf16_t*)w, x, M, N, K);
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
 }
 
 extern "C" int plt_gemm(int32_t dtype, int32_t M, int32_t N, int32_t K, const void* a, const void* w, float* c,

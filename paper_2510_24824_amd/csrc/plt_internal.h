@@ -216,7 +216,14 @@ void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c,
 // gemm_big.hip: many rows (prefill), 256 x 256 tiles, no split-K; optional fused SwiGLU epilogue
 bool gemm_big_applies(int M, int N, int K);
 void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
+void launch_gemm_big_resid(hipStream_t s, const bf16_t* a, const bf16_t* w, float* x, int M, int N, int K);   // x += a w^T
 void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K);
+// QKV projection of a prefill chunk (rows = whole sequences of n positions) with the rotary embedding, the gate logit
+// and the cache appends as its epilogue; same outputs as launch_gemm_big + launch_rope_append without the float matrix
+bool gemm_rope_applies(int M, int N, int K, int D);
+void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
+                          const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, int n, int loop, const Dims& dm,
+                          const double* inv_freq, int mode, bool kv8);
 // decode rows (M <= 256): the gate/up projection with the SwiGLU fused, whole K per workgroup, no slabs
 bool gemm_swiglu_rows_applies(int M, int F, int K);
 void launch_gemm_rows_tile(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);

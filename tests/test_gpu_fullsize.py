@@ -396,7 +396,9 @@ def test_decode_step_L4_w128_ctx8192_batch128_sampled():
     kv.close(); model.close()
 
 
-def test_prefill_4x8192_L3_narrow_model_against_oracle():
+@pytest.mark.parametrize("heads,kv_dtype", [((2, 1, 128), 0), ((2, 1, 128), B.PLT_FP8_E4M3), ((4, 2, 64), 0)],
+                         ids=["heads128-bf16kv", "heads128-e4m3kv", "heads64-bf16kv"])
+def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype):
     """The long-prompt prefill path itself against the oracle: 4 prompts of 8192 tokens at L = 3, window 64 (the
     prefill workload's batch, length, loops and window) on a narrow model (1 layer, d = 128, 2 query heads / 1 kv
     head of 128) that the position-by-position oracle walks in seconds.  8192 positions per sequence make plt_prefill
@@ -406,12 +408,18 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle():
     K/V at EVERY position (the keys of layer 0 depend on the embedding only, the point is the cache indexing of both
     chunks), windows, carried states H^(1), H^(2) of the last position, last-position logits; and, for the sequence
     of the last chunk, the residual rows H^(3)[p] and H^(2)[p] of every position p, which plt_prefill leaves in its
-    workspace (rows of the last chunk, at offset 0 and at the next multiple of 256 bytes after them)."""
-    shape = synth.ModelShape(n_layers=1, d_model=128, n_heads=2, n_kv_heads=1, head_dim=128, ffn_hidden=256,
+    workspace (rows of the last chunk, at offset 0 and at the next multiple of 256 bytes after them).
+    The QKV projection of such a chunk (16384 rows x 512 columns: 128 tiles) carries RoPE, the gate logit and the cache
+    appends as its epilogue, so the every-position cache comparison is that epilogue's check; also with heads of 64
+    (two heads per wave) and with e4m3 caches (stored values: the oracle's code or its neighbour, i.e. within one step
+    = 2^-3 of the value, plus the bf16 bar on the pre-rounding values)."""
+    Hq, Hkv, D = heads
+    fp8 = kv_dtype == B.PLT_FP8_E4M3
+    shape = synth.ModelShape(n_layers=1, d_model=128, n_heads=Hq, n_kv_heads=Hkv, head_dim=D, ffn_hidden=256,
                              vocab=512, n_loops=3, window=64)
     Bn, n, L = 4, 8192, 3
     weights = lively_weights(shape, 21, bf16=True, std=0.05)
-    cfg = B.make_config(shape, dtype=B.PLT_BF16)
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, kv_dtype=kv_dtype)
     model = B.Model(cfg, B.pack_weights(cfg, weights))
     kv = B.KV(model, Bn, n + 1)
     prompts = synth.token_ids((Bn, n), shape.vocab, 22)
@@ -429,7 +437,7 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle():
     wf = {k: np.asarray(v, np.float64) for k, v in weights.items() if k != "layers"}     # (conversion once, not per call)
     wf["layers"] = [{k: np.asarray(v, np.float64) for k, v in lw.items()} for lw in weights["layers"]]
     for b in (1, 3):             # last sequence of the first chunk, last sequence of the second
-        orc = O.PLTOracle(oshape(shape), wf, kv_bf16=True)
+        orc = O.PLTOracle(oshape(shape), wf, kv_bf16=not fp8, kv_fp8=fp8)
         o_next, o_lg = orc.clp_prefill(list(prompts[b]), n + 1)
         H = np.stack(orc.trace)                                   # [n, L, d]
         e_lg = float(np.max(np.abs(lg[b] - o_lg)))
@@ -443,8 +451,14 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle():
               f"shared K {e_ks:.2e} V {e_vs:.2e}; window K {e_kr:.2e} V {e_vr:.2e}")
         # K/V: both sides round the same float value to bf16 up to float32-vs-float64 noise: equal or one bf16 step apart
         kmax = float(np.max(np.abs(orc.kv.ks[0, :n])))
-        assert max(e_ks, e_kr) <= 2.0 ** -7 * kmax and max(e_vs, e_vr) <= 2.0 ** -7 * float(np.max(np.abs(orc.kv.vs[0, :n])))
-        assert e_lg <= 2e-2 and e_c <= 2e-2, (b, e_lg, e_c)
+        step = 2.0 ** -3 if fp8 else 2.0 ** -7        # e4m3: neighbouring codes are up to 2^-3 of the value apart
+        assert max(e_ks, e_kr) <= step * kmax and max(e_vs, e_vr) <= step * float(np.max(np.abs(orc.kv.vs[0, :n])))
+        if fp8:                                       # ... and all but a few per cent of the codes are the oracle's own
+            same = np.mean(e["k_share"] == orc.kv.ks[0, :n].transpose(1, 0, 2).astype(np.float32))
+            same_v = np.mean(e["v_share"] == orc.kv.vs[0, :n].transpose(1, 0, 2).astype(np.float32))
+            print(f"seq {b}: e4m3 codes equal to the oracle's: K {same:.4f}, V {same_v:.4f}")
+            assert same >= 0.94 and same_v >= 0.94
+        assert e_lg <= (4e-2 if fp8 else 2e-2) and e_c <= (4e-2 if fp8 else 2e-2), (b, e_lg, e_c)
         if np.sort(o_lg)[-1] - np.sort(o_lg)[-2] > 4e-2:
             assert int(nxt[b]) == o_next
         if b >= Bn - Bc:
@@ -455,5 +469,16 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle():
             print(f"seq {b}: H^(3) over all {n} positions max-abs {e3.max():.2e} (at position {worst3}); H^(2) {e2.max():.2e} (at {worst2}); "
                   f"tile and chunk borders 127/128: {e3[127]:.1e}/{e3[128]:.1e}, 63/64/65 (window): {e3[63]:.1e}/{e3[64]:.1e}/{e3[65]:.1e}, "
                   f"8191: {e3[8191]:.1e}")
-            assert e3.max() <= 2e-2 and e2.max() <= 2e-2, (b, float(e3.max()), float(e2.max()))
+            if fp8:
+                # e4m3 caches: about 5 % of the stored codes are the oracle's NEIGHBOUR (the two sides' pre-rounding values
+                # straddle a boundary), each such element off by a whole step = up to 2^-3 of its value.  Where few keys
+                # share the softmax weight (early positions, the window border) one such V element reaches the output
+                # undiluted, so over 8192 positions x 128 features the largest deviation is a flipped code's, not the
+                # arithmetic's: the bar of the e4m3 model tests (4e-2, tests/test_gpu_fp8.py) must hold at all but
+                # 0.2 % of the positions, and a flipped code's reach (one step of the largest V entry, ~0.125) everywhere
+                frac3, frac2 = float(np.mean(e3 > 4e-2)), float(np.mean(e2 > 4e-2))
+                print(f"seq {b}: positions beyond 4e-2: H^(3) {frac3:.4%}, H^(2) {frac2:.4%}")
+                assert frac3 <= 2e-3 and frac2 <= 2e-3 and e3.max() <= 0.125 and e2.max() <= 0.125, (b, frac3, frac2, float(e3.max()), float(e2.max()))
+            else:
+                assert e3.max() <= 2e-2 and e2.max() <= 2e-2, (b, float(e3.max()), float(e2.max()))
     kv.close(); model.close()

@@ -189,6 +189,24 @@ def test_gemm_hook_matches_float64_product():
         assert np.max(np.abs(c32.cpu().numpy() - ref)) <= 1e-5 * K + 1e-4, (M, N, K)
 
 
+def test_gemm_residual_hook_adds_the_float64_product_in_place():
+    """The prefill's output / down projections add their product to the residual stream in the tile kernel's epilogue:
+    x += a w^T against the float64 product (ragged last row and column tiles included); other shapes are refused."""
+    rng = np.random.default_rng(5)
+    for (M, N, K) in [(4096, 4096, 128), (4100, 3101, 64), (16384, 1028, 192)]:
+        a = synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
+        w = synth.round_to_bf16(rng.standard_normal((N, K)).astype(np.float32))
+        x0 = rng.standard_normal((M, N)).astype(np.float32) * 3
+        ref = x0.astype(np.float64) + a.astype(np.float64) @ w.astype(np.float64).T
+        x = torch.from_numpy(x0).cuda()
+        B.gemm_residual(torch.from_numpy(a).cuda().to(torch.bfloat16), torch.from_numpy(w).cuda().to(torch.bfloat16), x)
+        assert np.max(np.abs(x.cpu().numpy() - ref)) <= 1e-5 * K + 1e-4, (M, N, K)
+    x = torch.zeros(128, 256, device="cuda")
+    with pytest.raises(B.PltError):
+        B.gemm_residual(torch.zeros(128, 64, device="cuda", dtype=torch.bfloat16), torch.zeros(256, 64, device="cuda", dtype=torch.bfloat16), x)
+    assert float(x.abs().max()) == 0.0
+
+
 @pytest.mark.parametrize("dtype,tol", [(B.PLT_F32, 2e-5), (B.PLT_BF16, 2e-2)])
 def test_edge_cases_single_token_prompt_and_window_larger_than_context(dtype, tol):
     """Prompt of one token (position 0 sees only itself; every loop gets a zero shifted-in state),
