@@ -260,6 +260,9 @@ int plt_debug_act_codes(plt_kv* kv, int32_t which, uint8_t* host_codes, size_t c
  * n_ctx shared entries and n_ring (<= w) ring slots are valid for every sequence.
  * scratch: device buffer of plt_attn_scratch_bytes(...) bytes (split partials).
  * n_splits <= 0 lets the library choose.  Rows of loop 0 get the global branch only.
+ * The L * (Hq / Hkv) query rows that share one (sequence, kv head) stream are served by ONE pass over its cache
+ * bytes while they number at most 16 (the matrix-core tile's width: every named configuration: 2..16 rows); from 17
+ * rows on each further group of 16 is a workgroup of its own that streams the same cache bytes again.
  * plt_attn_pad: positions are padded to a multiple of 32 (64 for PLT_FP8_E4M3);
  * plt_attn_pad32(n) = plt_attn_pad(PLT_BF16, n). */
 int32_t plt_attn_pad32(int32_t n);
