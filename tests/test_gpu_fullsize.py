@@ -396,9 +396,10 @@ def test_decode_step_L4_w128_ctx8192_batch128_sampled():
     kv.close(); model.close()
 
 
-@pytest.mark.parametrize("heads,kv_dtype", [((2, 1, 128), 0), ((2, 1, 128), B.PLT_FP8_E4M3), ((4, 2, 64), 0)],
-                         ids=["heads128-bf16kv", "heads128-e4m3kv", "heads64-bf16kv"])
-def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype):
+@pytest.mark.parametrize("heads,kv_dtype,mode", [((2, 1, 128), 0, B.PLT_MODE_CLP), ((2, 1, 128), B.PLT_FP8_E4M3, B.PLT_MODE_CLP),
+                                                 ((4, 2, 64), 0, B.PLT_MODE_CLP), ((2, 1, 128), 0, B.PLT_MODE_CLP_SHARE_ONLY)],
+                         ids=["heads128-bf16kv", "heads128-e4m3kv", "heads64-bf16kv", "heads128-bf16kv-share-only"])
+def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype, mode):
     """The long-prompt prefill path itself against the oracle: 4 prompts of 8192 tokens at L = 3, window 64 (the
     prefill workload's batch, length, loops and window) on a narrow model (1 layer, d = 128, 2 query heads / 1 kv
     head of 128) that the position-by-position oracle walks in seconds.  8192 positions per sequence make plt_prefill
@@ -411,7 +412,8 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype):
     workspace (rows of the last chunk, at offset 0 and at the next multiple of 256 bytes after them).
     The QKV projection of such a chunk (16384 rows x 512 columns: 128 tiles) carries RoPE, the gate logit and the cache
     appends as its epilogue, so the every-position cache comparison is that epilogue's check; also with heads of 64
-    (two heads per wave) and with e4m3 caches (stored values: the oracle's code or its neighbour, i.e. within one step
+    (two heads per wave), in the KV-share-only ablation mode (non-first loops append nothing and have no gate) and with
+    e4m3 caches (stored values: the oracle's code or its neighbour, i.e. within one step
     = 2^-3 of the value, plus the bf16 bar on the pre-rounding values)."""
     Hq, Hkv, D = heads
     fp8 = kv_dtype == B.PLT_FP8_E4M3
@@ -419,7 +421,8 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype):
                              vocab=512, n_loops=3, window=64)
     Bn, n, L = 4, 8192, 3
     weights = lively_weights(shape, 21, bf16=True, std=0.05)
-    cfg = B.make_config(shape, dtype=B.PLT_BF16, kv_dtype=kv_dtype)
+    share_only = mode == B.PLT_MODE_CLP_SHARE_ONLY
+    cfg = B.make_config(shape, dtype=B.PLT_BF16, kv_dtype=kv_dtype, mode=mode)
     model = B.Model(cfg, B.pack_weights(cfg, weights))
     kv = B.KV(model, Bn, n + 1)
     prompts = synth.token_ids((Bn, n), shape.vocab, 22)
@@ -437,7 +440,7 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype):
     wf = {k: np.asarray(v, np.float64) for k, v in weights.items() if k != "layers"}     # (conversion once, not per call)
     wf["layers"] = [{k: np.asarray(v, np.float64) for k, v in lw.items()} for lw in weights["layers"]]
     for b in (1, 3):             # last sequence of the first chunk, last sequence of the second
-        orc = O.PLTOracle(oshape(shape), wf, kv_bf16=not fp8, kv_fp8=fp8)
+        orc = O.PLTOracle(oshape(shape), wf, kv_bf16=not fp8, kv_fp8=fp8, variant="clp_share_only" if share_only else "plt")
         o_next, o_lg = orc.clp_prefill(list(prompts[b]), n + 1)
         H = np.stack(orc.trace)                                   # [n, L, d]
         e_lg = float(np.max(np.abs(lg[b] - o_lg)))
@@ -445,8 +448,10 @@ def test_prefill_4x8192_L3_narrow_model_against_oracle(heads, kv_dtype):
         e = kv.export(b, 0, n)
         e_ks = float(np.max(np.abs(e["k_share"] - orc.kv.ks[0, :n].transpose(1, 0, 2))))
         e_vs = float(np.max(np.abs(e["v_share"] - orc.kv.vs[0, :n].transpose(1, 0, 2))))
-        e_kr = float(np.max(np.abs(e["k_ring"] - orc.kv.kr[:, 0].transpose(0, 2, 1, 3))))
-        e_vr = float(np.max(np.abs(e["v_ring"] - orc.kv.vr[:, 0].transpose(0, 2, 1, 3))))
+        e_kr = e_vr = 0.0
+        if not share_only:                                       # (that mode keeps no windows)
+            e_kr = float(np.max(np.abs(e["k_ring"] - orc.kv.kr[:, 0].transpose(0, 2, 1, 3))))
+            e_vr = float(np.max(np.abs(e["v_ring"] - orc.kv.vr[:, 0].transpose(0, 2, 1, 3))))
         print(f"seq {b}: logits {e_lg:.2e} (max |logit| {np.max(np.abs(o_lg)):.2f}); carry {e_c:.2e} (max |H| {np.max(np.abs(H)):.2f}); "
               f"shared K {e_ks:.2e} V {e_vs:.2e}; window K {e_kr:.2e} V {e_vr:.2e}")
         # K/V: both sides round the same float value to bf16 up to float32-vs-float64 noise: equal or one bf16 step apart
