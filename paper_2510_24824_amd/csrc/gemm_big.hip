@@ -167,9 +167,10 @@ __device__ inline void rope_epilogue(f32x4 (&acc)[MI][NT], const RopeEpi& ep, in
 //   256 x 256, 2 x 4 waves of 128 x 64 : prefill-sized row counts (MFMA-bound).  Two waves along N (128 x 128
 //       per wave, accumulators in AGPRs, one wave per SIMD) halve the LDS reads per MFMA but measured 1.5x
 //       slower: a single wave per SIMD cannot hide the LDS and barrier latency.
-//   256 x 64, 4 x 2 waves of 64 x 32 : the gate/up projection of decode steps with 129..256 rows, SwiGLU fused
-//       (all rows of the step in one tile, whole K: no split-K slabs, no separate activation kernel).  The same
-//       tile for the plain QKV projection measured slower than the weight-streaming kernel and is not used.
+//   256 / 128 / 64 x 64, waves of 64 x 32 (32 x 32 for the 64-row tile) : the gate/up projection of decode steps,
+//       SwiGLU fused (all rows of the step in one tile, whole K: no split-K slabs, no separate activation kernel),
+//       three LDS stages (four for the 64-row tile).  The same tile for the plain QKV projection pays from 129 rows
+//       on (up to 128 rows: equal to the weight-streaming kernel, which is kept there).
 template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t, int PFD = 0>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                           void* __restrict__ out, int M, int N, int K, const RopeEpi ep) {
@@ -424,12 +425,15 @@ void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, in
   }
 }
 
-// Decode step: act[M, F] = silu(a Wg^T) * (a Wu^T) for up to 256 rows in one launch, no slabs.
-// Measured inside the decode step: at 129..256 rows (where the streaming kernel needs two row blocks and
-// its slabs double) this is 5 % of the step faster; up to 128 rows the streaming kernel plus the separate
-// activation kernel is as fast or faster, so those row counts keep it.
+// Decode step: act[M, F] = silu(a Wg^T) * (a Wu^T) for up to 256 rows in one launch: all rows of the step in one
+// tile, whole K, 32 gate + 32 up columns per workgroup, SwiGLU in the epilogue - no split-K slabs and no separate
+// activation kernel.  With three or four LDS stages and the fragment reads running ahead of the matrix cores this
+// beats the streaming kernel + activation kernel at every row count (batch 64: L = 2 step 6.13 -> 5.95 ms, non-looped
+// 5.39 -> 5.29; batch 1: 1.66 -> 1.56 ms per token); the tile height follows the rows (64 / 128 / 256).
 bool gemm_swiglu_rows_applies(int M, int F, int K) {
-  return M > 128 && M <= 256 && (K % GB_BK) == 0 && (F + 31) / 32 >= 128;   // enough 32-column tiles to occupy the chip
+  // (larger row counts - several 256-row tiles - until the 256 x 256 prefill tiles fill the chip: 257..1024 rows
+  // measured 4-6 % of the step faster than the streaming kernel, which reads the weights once per 128-row block)
+  return M >= 1 && (K % GB_BK) == 0 && (F + 31) / 32 >= 128;   // enough 32-column tiles to occupy the chip
 }
 
 // the same tile with the plain float epilogue: wide projections at 129..256 rows, whole K, no slabs
@@ -438,6 +442,8 @@ void launch_gemm_rows_tile(hipStream_t s, const bf16_t* a, const bf16_t* w, floa
 }
 
 void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
+  if (M <= 64) { tile_launch<EPI_SWIGLU, 64, 64, 2, 2, 4>(s, a, wgu, (void*)act, M, F, K); return; }
+  if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 64, 2, 2, 3>(s, a, wgu, (void*)act, M, F, K); return; }
   tile_launch<EPI_SWIGLU, 256, 64, 4, 2, 3>(s, a, wgu, (void*)act, M, F, K);
 }
 

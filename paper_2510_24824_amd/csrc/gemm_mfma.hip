@@ -303,10 +303,14 @@ static WsPlan ws_plan(int M, int N, int K) {
   return p;
 }
 
-// Wide projections (QKV) at 129..192 rows: all rows in one 256 x 64 tile, whole K, three LDS stages -- no slabs, and
-// measured 2 % of the decode step faster than two row blocks of the streaming kernel (at 193..256 rows: equal)
+// Wide projections (QKV) at 129..192 rows and from 257 rows up to where the 256 x 256 prefill tiles take over: all
+// rows in 256 x 64 tiles, whole K, three LDS stages -- no slabs, and measured 2 % (129..192 rows) and 4-6 % (257..1024
+// rows, where the streaming kernel reads the weights once per 128-row block) of the decode step faster than the
+// streaming kernel; at 193..256 rows and up to 128 rows: equal, the streaming kernel is kept.  Narrow projections
+// (output, down: 2048 columns = 32 such tiles per 256 rows) lose with it at every row count.
 static bool tile_rows_applies(int M, int N, int K) {
-  return M > 128 && M <= 192 && N >= 4096 && K <= 4096 && (K % 64) == 0;
+  if (N < 4096 || K > 4096 || (K % 64) != 0) return false;
+  return (M > 128 && M <= 192) || (M > 256 && !gemm_big_applies(M, N, K));
 }
 
 // splits for the generic entry: the streaming kernel writes one slab per workgroup K span

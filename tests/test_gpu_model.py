@@ -179,6 +179,7 @@ def test_gemm_hook_matches_float64_product():
                       (128, 1536, 2048), (192, 2048, 1152), (64, 1000, 2048), (256, 333, 640),
                       (512, 256, 128), (700, 390, 192), (1024, 1000, 64),
                       (160, 4096, 256), (150, 4100, 128), (192, 6144, 2048),    # 129..192 rows, wide: one 256 x 64 tile per 64 columns, three LDS stages
+                      (300, 4096, 256), (1000, 4100, 128), (513, 6144, 512),     # 257.. rows, wide: several 256-row tiles (ragged last tile)
                       (4096, 4096, 128), (4100, 3100, 64)]:          # the last two take the 256 x 256 tile kernel
         a = synth.round_to_bf16(rng.standard_normal((M, K)).astype(np.float32))
         w = synth.round_to_bf16(rng.standard_normal((N, K)).astype(np.float32))
