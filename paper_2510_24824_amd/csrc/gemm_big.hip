@@ -9,6 +9,8 @@
 //   EPI_SWIGLU : w = [W_gate; W_up] ([2F,K]); the tile holds 128 gate columns and the matching 128 up
 //                columns and writes silu(gate) * up as bf16 act[M,F]              (SwiGLU, fused)
 //   EPI_RESID  : float c[M,N] += product (the residual stream updated in place by the output / down projection)
+//   EPI_ROPE_DEC : the same for the rows of a decode step (64 rows x 128 columns per workgroup, a wave = 16 rows x one
+//                or two whole heads); row (b, l) appends to the shared cache (l = 0) or to ring l - 1 [Alg. 1 l.5-7]
 //   EPI_ROPE   : w = W_qkv of a prefill chunk; waves as 4 x 2 so that a wave holds whole heads (64 rows x 128
 //                columns): rotary embedding, gate logit and the cache appends straight from the accumulators
 //                [Alg. 3 l.1, l.4; Sec. 2.2.2] - the float QKV matrix is never written
@@ -21,11 +23,19 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 namespace {
 
 constexpr int GB_BK = 64;
+#ifndef GB_ROPE_ROWS_MIN
+#define GB_ROPE_ROWS_MIN 128
+#endif
+#ifndef GB_ST64
+#define GB_ST64 4
+#define GB_ST128 3
+#define GB_ST256 3
+#endif
 #ifndef GB_PFD_VALUE
 #define GB_PFD_VALUE 0
 #endif
 constexpr int GB_PFD = GB_PFD_VALUE;      // prefill tiles: slices of last-level-cache prefetch beyond the slice being loaded
-enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_RESID = 3 };
+enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_RESID = 3, EPI_ROPE_DEC = 4 };
 
 // What the EPI_ROPE epilogue needs beyond the product: row gm of the chunk is position gm % n of chunk sequence gm / n
 struct RopeEpi {
@@ -33,6 +43,7 @@ struct RopeEpi {
   bf16_t* q_out; float* z_out;
   KvView kv;
   int n, loop, Hq, Hkv, mode;
+  const int32_t* pos; int L;      // EPI_ROPE_DEC: row gm is loop stage gm % L of sequence gm / L at position pos[gm / L]
 };
 
 // four consecutive cache elements from four floats (destination aligned to the four)
@@ -171,6 +182,101 @@ __device__ inline void rope_epilogue(f32x4 (&acc)[MI][NT], const RopeEpi& ep, in
 //       SwiGLU fused (all rows of the step in one tile, whole K: no split-K slabs, no separate activation kernel),
 //       three LDS stages (four for the 64-row tile).  The same tile for the plain QKV projection pays from 129 rows
 //       on (up to 128 rows: equal to the weight-streaming kernel, which is kept there).
+// S3 for the rows of a decode step: as rope_epilogue, but every row carries its own loop stage and position (row gm =
+// stage gm % L of sequence gm / L at position pos[gm / L]), the first stage appends to the shared cache (the cache of
+// its stage in the per-loop-cache mode), later stages to their ring slot p mod w.  Same arithmetic as k_rope_append.
+template <int D, typename KT, int MI, int NT>
+__device__ inline void rope_epilogue_decode(f32x4 (&acc)[MI][NT], const RopeEpi& ep, int row0, int col0, int M, int N, int m16, int g) {
+  constexpr int HT = D / 16, PT = HT / 2, half = D / 2;
+  static_assert((NT * 16) % D == 0, "a wave holds whole heads");
+  const int Hq = ep.Hq, Hkv = ep.Hkv, L = ep.L, mode = ep.mode;
+  const KvView& kv = ep.kv;
+#pragma unroll
+  for (int hh = 0; hh < NT / HT; ++hh) {
+    const int c0 = col0 + hh * D;
+    if (c0 >= N) break;                                      // (the same for the whole wave)
+    const int hs = c0 / D;
+    const bool is_q = hs < Hq, is_k = !is_q && hs < Hq + Hkv;
+    const bool want_z = is_q && mode == 0 && L > 1;
+    double fr[PT][4];
+    float gw_lo[PT][4], gw_hi[PT][4];
+    if (is_q || is_k) {
+#pragma unroll
+      for (int t = 0; t < PT; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) fr[t][e] = ep.inv_freq[16 * t + 4 * g + e] * 0.15915494309189535;
+    }
+    if (want_z) {
+#pragma unroll
+      for (int t = 0; t < PT; ++t) {
+        const float4 a = *reinterpret_cast<const float4*>(ep.gate_w + hs * D + 16 * t + 4 * g);
+        const float4 b = *reinterpret_cast<const float4*>(ep.gate_w + hs * D + half + 16 * t + 4 * g);
+        gw_lo[t][0] = a.x; gw_lo[t][1] = a.y; gw_lo[t][2] = a.z; gw_lo[t][3] = a.w;
+        gw_hi[t][0] = b.x; gw_hi[t][1] = b.y; gw_hi[t][2] = b.z; gw_hi[t][3] = b.w;
+      }
+    }
+    const int kh = is_k ? hs - Hq : hs - Hq - Hkv;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int gm = row0 + i * 16 + m16;
+      const bool ok = gm < M;
+      const int b = ok ? gm / L : 0, l = ok ? gm - b * L : 0, p = ok ? ep.pos[b] : 0;
+      f32x4* lo = &acc[i][hh * HT];
+      f32x4* hi = &acc[i][hh * HT + PT];
+      if (want_z) {                                          // gate logit on the un-rotated query [Alg. 3 l.4]
+        float zp = 0.f;
+#pragma unroll
+        for (int t = 0; t < PT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) zp += lo[t][e] * gw_lo[t][e] + hi[t][e] * gw_hi[t][e];
+        zp = row4_add_f32(zp);                               // the four lanes that share the row
+        if (ok && l > 0 && g == 0) ep.z_out[((size_t)b * (L - 1) + (l - 1)) * Hq + hs] = zp + ep.gate_b[hs];
+      }
+      if (is_q || is_k) {
+#pragma unroll
+        for (int t = 0; t < PT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            double a = (double)p * fr[t][e];
+            a -= rint(a);
+            const float sn = __builtin_amdgcn_sinf((float)a), c = __builtin_amdgcn_cosf((float)a);
+            const float l0 = lo[t][e], h0 = hi[t][e];
+            lo[t][e] = l0 * c - h0 * sn; hi[t][e] = h0 * c + l0 * sn;
+          }
+      }
+      if (!ok) continue;
+      if (is_q) {
+        bf16_t* dst = ep.q_out + (size_t)gm * Hq * D + (size_t)hs * D + 4 * g;
+#pragma unroll
+        for (int t = 0; t < PT; ++t) { store4(dst + 16 * t, lo[t]); store4(dst + half + 16 * t, hi[t]); }
+        continue;
+      }
+      if (mode == 2 && l > 0) continue;                      // KV-share ablation: non-first loops keep no K/V
+      const int bg = kv.b0 + b;
+      KT *kd, *vd; int at;
+      if (mode != 0 || l == 0) {                             // first loop: the shared cache [Sec. 2.2.2]
+        const size_t off = (mode == 3 ? (size_t)l * kv.cache_stride : 0) + ((size_t)bg * Hkv + kh) * (size_t)kv.n_pad * D;
+        kd = (KT*)kv.k_share + off; vd = (KT*)kv.v_share + off; at = p;
+      } else {                                               // later loops: only the w most recent entries survive
+        const size_t off = (((size_t)bg * kv.n_rings + (l - 1)) * Hkv + kh) * (size_t)kv.w_pad * D;
+        kd = (KT*)kv.k_ring + off; vd = (KT*)kv.v_ring + off; at = p % kv.w;
+      }
+      if (is_k) {
+#pragma unroll
+        for (int t = 0; t < PT; ++t) {
+          store4(kd + kblk_index<KT>(at, 16 * t + 4 * g, D), lo[t]);
+          store4(kd + kblk_index<KT>(at, half + 16 * t + 4 * g, D), hi[t]);
+        }
+      } else {
+#pragma unroll
+        for (int t = 0; t < HT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) st<KT>(vd + vblk_index<KT>(at, 16 * t + 4 * g + e, D), lo[t][e]);
+      }
+    }
+  }
+}
+
 template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t, int PFD = 0>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                           void* __restrict__ out, int M, int N, int K, const RopeEpi ep) {
@@ -337,6 +443,10 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
     rope_epilogue<D, KT, MI, NT>(acc, ep, m0 + wm * (MI * 16), n0 + wn * (NT * 16), M, N, m16, g);
     return;
   }
+  if constexpr (EPI == EPI_ROPE_DEC) {
+    rope_epilogue_decode<D, KT, MI, NT>(acc, ep, m0 + wm * (MI * 16), n0 + wn * (NT * 16), M, N, m16, g);
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     const int gm = m0 + wm * (MI * 16) + i * 16 + m16;
@@ -412,10 +522,30 @@ bool gemm_rope_applies(int M, int N, int K, int D) {
   return M >= 512 && tiles >= 128 && (K % GB_BK) == 0 && (D == 64 || D == 128) && N % D == 0;
 }
 
+// QKV projection of a decode step with S3 as its epilogue: 64-row x 128-column tiles (a wave = 16 rows x 128 columns),
+// whole K, four LDS stages; one launch instead of the streaming kernel's K-range slabs + k_rope_append.  Measured in
+// the decode step at batch 64: 192 rows (L = 3) 6.59 -> 6.42 ms, 256 rows (L = 4) 6.84 -> 6.71 ms, 128 rows equal, so
+// it is used from 129 rows on.
+bool gemm_rope_rows_applies(int M, int N, int K, int D) {
+  return M > GB_ROPE_ROWS_MIN && (K % GB_BK) == 0 && (D == 64 || D == 128) && N % 128 == 0;
+}
+void launch_gemm_rope_rows(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
+                           const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, const int32_t* pos, int L,
+                           const Dims& dm, const double* inv_freq, int mode, bool kv8) {
+  RopeEpi ep{gate_w, gate_b, inv_freq, q_out, z_out, kv, 0, 0, dm.Hq, dm.Hkv, mode, pos, L};
+  if (dm.D == 128) {
+    if (kv8) tile_launch<EPI_ROPE_DEC, 64, 128, 4, 1, 4, 128, fp8_t>(s, a, wqkv, nullptr, M, N, K, ep);
+    else tile_launch<EPI_ROPE_DEC, 64, 128, 4, 1, 4, 128, bf16_t>(s, a, wqkv, nullptr, M, N, K, ep);
+  } else {
+    if (kv8) tile_launch<EPI_ROPE_DEC, 64, 128, 4, 1, 4, 64, fp8_t>(s, a, wqkv, nullptr, M, N, K, ep);
+    else tile_launch<EPI_ROPE_DEC, 64, 128, 4, 1, 4, 64, bf16_t>(s, a, wqkv, nullptr, M, N, K, ep);
+  }
+}
+
 void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
                           const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, int n, int loop, const Dims& dm,
                           const double* inv_freq, int mode, bool kv8) {
-  const RopeEpi ep{gate_w, gate_b, inv_freq, q_out, z_out, kv, n, loop, dm.Hq, dm.Hkv, mode};
+  const RopeEpi ep{gate_w, gate_b, inv_freq, q_out, z_out, kv, n, loop, dm.Hq, dm.Hkv, mode, nullptr, 1};
   if (dm.D == 128) {
     if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, fp8_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
     else tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, bf16_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
@@ -442,9 +572,9 @@ void launch_gemm_rows_tile(hipStream_t s, const bf16_t* a, const bf16_t* w, floa
 }
 
 void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
-  if (M <= 64) { tile_launch<EPI_SWIGLU, 64, 64, 2, 2, 4>(s, a, wgu, (void*)act, M, F, K); return; }
-  if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 64, 2, 2, 3>(s, a, wgu, (void*)act, M, F, K); return; }
-  tile_launch<EPI_SWIGLU, 256, 64, 4, 2, 3>(s, a, wgu, (void*)act, M, F, K);
+  if (M <= 64) { tile_launch<EPI_SWIGLU, 64, 64, 2, 2, GB_ST64>(s, a, wgu, (void*)act, M, F, K); return; }
+  if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 64, 2, 2, GB_ST128>(s, a, wgu, (void*)act, M, F, K); return; }
+  tile_launch<EPI_SWIGLU, 256, 64, 4, 2, GB_ST256>(s, a, wgu, (void*)act, M, F, K);
 }
 
 }  // namespace plt

@@ -526,6 +526,11 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       ProfScope prof(m, PLT_PROF_GEMM, false);
       launch_gemm_big_rope(s, (const bf16_t*)wk.a, (const bf16_t*)w.wqkv, R, Nqkv, d, w.gate_w, w.gate_b, (bf16_t*)wk.q,
                            wk.z, v, rm.rows_per_seq, rm.loop_fixed, dm, m->inv_freq, variant, m->kv8);
+    } else if (!m->mx && c.dtype == PLT_BF16 && !rm.prefill && gemm_rope_rows_applies(R, Nqkv, d, D)) {
+      // decode rows: likewise (row (b, l) at position pos[b])                                      // Alg. 1 l.5-7
+      ProfScope prof(m, PLT_PROF_GEMM, true);
+      launch_gemm_rope_rows(s, (const bf16_t*)wk.a, (const bf16_t*)w.wqkv, R, Nqkv, d, w.gate_w, w.gate_b, (bf16_t*)wk.q,
+                            wk.z, v, rm.pos, rm.rows_per_seq, dm, m->inv_freq, variant, m->kv8);
     } else {
       S = m->mx ? run_gemm_mx(m, wk, w.wqkv, w.wqkv_sc, R, Nqkv, d, !rm.prefill)
                 : run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                         // Alg. 3 l.1

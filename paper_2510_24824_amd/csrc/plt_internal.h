@@ -220,6 +220,10 @@ void launch_gemm_big_resid(hipStream_t s, const bf16_t* a, const bf16_t* w, floa
 void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K);
 // QKV projection of a prefill chunk (rows = whole sequences of n positions) with the rotary embedding, the gate logit
 // and the cache appends as its epilogue; same outputs as launch_gemm_big + launch_rope_append without the float matrix
+bool gemm_rope_rows_applies(int M, int N, int K, int D);        // the decode-row form: row (b, l) at position pos[b]
+void launch_gemm_rope_rows(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
+                           const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, const int32_t* pos, int L,
+                           const Dims& dm, const double* inv_freq, int mode, bool kv8);
 bool gemm_rope_applies(int M, int N, int K, int D);
 void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
                           const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, int n, int loop, const Dims& dm,

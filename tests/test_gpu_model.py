@@ -219,6 +219,22 @@ def test_edge_cases_single_token_prompt_and_window_larger_than_context(dtype, to
     run_teacher_forced(shape, dtype, B.PLT_MODE_CLP, weights, prompts, 6, tol)
 
 
+@pytest.mark.parametrize("mode", [B.PLT_MODE_CLP, B.PLT_MODE_CLP_SHARE_ONLY, B.PLT_MODE_CLP_OWN_KV, B.PLT_MODE_VANILLA_LOOP])
+@pytest.mark.parametrize("kv_dtype", [0, B.PLT_FP8_E4M3], ids=["bf16kv", "e4m3kv"])
+def test_decode_steps_of_more_than_128_rows_all_modes(mode, kv_dtype):
+    """From 129 rows on the QKV projection of a decode step carries RoPE, the gate logit and the cache appends as its
+    epilogue (64-row x 128-column tiles; row (b, l) at its sequence's own position): 48 sequences x 3 loops = 144 rows
+    (three row tiles, the last ragged; 144 sequences in the sequential-loop mode), every mode's append rule, both cache
+    types, against the oracle's teacher-forced steps."""
+    shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64,
+                             ffn_hidden=192, vocab=300, n_loops=3, window=8)
+    weights = lively_weights(shape, 51, bf16=True, std=0.02)
+    Bn = 144 if mode == B.PLT_MODE_VANILLA_LOOP else 48
+    n, steps = (9, 2) if mode == B.PLT_MODE_VANILLA_LOOP else (19, 3)
+    prompts = synth.token_ids((Bn, n), shape.vocab, 52)
+    run_teacher_forced(shape, B.PLT_BF16, mode, weights, prompts, steps, 4e-2 if kv_dtype else 2e-2, kv_dtype=kv_dtype)
+
+
 def test_window_one_and_many_loops():
     """w = 1: the window holds only the current position, so the local branch returns its own value row."""
     shape = synth.ModelShape(n_layers=1, d_model=64, n_heads=2, n_kv_heads=1, head_dim=64,
