@@ -23,18 +23,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 namespace {
 
 constexpr int GB_BK = 64;
-#ifndef GB_ROPE_ROWS_MIN
-#define GB_ROPE_ROWS_MIN 128
-#endif
-#ifndef GB_ST64
-#define GB_ST64 4
-#define GB_ST128 3
-#define GB_ST256 3
-#endif
-#ifndef GB_PFD_VALUE
-#define GB_PFD_VALUE 0
-#endif
-constexpr int GB_PFD = GB_PFD_VALUE;      // prefill tiles: slices of last-level-cache prefetch beyond the slice being loaded
 enum { EPI_F32 = 0, EPI_SWIGLU = 1, EPI_ROPE = 2, EPI_RESID = 3, EPI_ROPE_DEC = 4 };
 
 // What the EPI_ROPE epilogue needs beyond the product: row gm of the chunk is position gm % n of chunk sequence gm / n
@@ -277,7 +265,7 @@ __device__ inline void rope_epilogue_decode(f32x4 (&acc)[MI][NT], const RopeEpi&
   }
 }
 
-template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t, int PFD = 0>
+template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t>
 __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __restrict__ a, const bf16_t* __restrict__ w,
                                                           void* __restrict__ out, int M, int N, int K, const RopeEpi ep) {
   // N: EPI_F32: output columns (= rows of w); EPI_SWIGLU: F (w has 2F rows, the output F columns)
@@ -320,12 +308,12 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
   for (int i = 0; i < DMA_A; ++i) {
     const int sl = i * THREADS + tid, row = sl >> 3, kc = (sl & 7) ^ (row & 7);
     int gm = m0 + row; if (gm >= M) gm = M - 1;
-    pa[i] = a + (size_t)gm * K + kc * 8;
+    pa[i] = a + (size_t)gm * K + kc * 8 + (size_t)blockIdx.z * ((K / GB_BK + gridDim.z - 1) / gridDim.z) * GB_BK;
   }
 #pragma unroll
   for (int i = 0; i < DMA_W; ++i) {
     const int sl = i * THREADS + tid, row = sl >> 3, kc = (sl & 7) ^ (row & 7);
-    pw[i] = w + (size_t)wrow(row) * K + kc * 8;
+    pw[i] = w + (size_t)wrow(row) * K + kc * 8 + (size_t)blockIdx.z * ((K / GB_BK + gridDim.z - 1) / gridDim.z) * GB_BK;
   }
   // Direct load issued as an instruction of its own (not through the compiler's builtin): the compiler
   // orders every later LDS read after a builtin direct load (it cannot tell the two stages apart), which
@@ -346,27 +334,11 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
     for (int i = 0; i < DMA_W; ++i)
       dma16(pw[i] + k0, stage + A_BYTES + __builtin_amdgcn_readfirstlane((unsigned)(i * THREADS + wv * 64) * 16));
   };
-  const int ks_total = K / GB_BK;
-  // PFD > 0: the slice PFD steps beyond the one being loaded is pulled into the last-level cache - every thread
-  // requests one 128-byte line of it (a tile row's 64 K-values) with a 4-byte direct load into a spare LDS word
-  // (no register is written, nothing reads the word).  All workgroups of a die work on the same few row and column
-  // tiles at about the same K, so a slice's first request otherwise meets the memory latency (1-2 us) with one
-  // slice time of slack; this way it meets it PFD slices early.
-  static_assert(PFD == 0 || (BM + BN == THREADS && STAGES == 2), "one line per thread");
-  const bf16_t* pf_row = nullptr;
-  if constexpr (PFD > 0) {
-    if (tid < BM) { int gm = m0 + tid; if (gm >= M) gm = M - 1; pf_row = a + (size_t)gm * K; }
-    else pf_row = w + (size_t)wrow(tid - BM) * K;
-  }
-  auto prefetch = [&](int ks) {
-    if (ks >= ks_total) ks = ks_total - 1;
-    const unsigned dst = lds0 + (unsigned)(STAGES * STAGE_BYTES) + __builtin_amdgcn_readfirstlane((unsigned)wv * 256);
-    const bf16_t* src = pf_row + (size_t)ks * GB_BK;
-    unsigned keep_m0;
-    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, off\n\ts_mov_b32 m0, %0"
-                 : "=&s"(keep_m0) : "s"(dst), "v"(src) : "memory");
-  };
-
+  // gridDim.z > 1 (EPI_F32 only): workgroup z takes the z-th run of K slices and writes float slab z (consumers add the
+  // slabs in order)
+  const int ks_all = K / GB_BK, ks_per = (ks_all + (int)gridDim.z - 1) / (int)gridDim.z;
+  const int ks_first = (int)blockIdx.z * ks_per;
+  const int ks_total = ks_all - ks_first < ks_per ? ks_all - ks_first : ks_per;
   f32x4 acc[MI][NT];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -380,20 +352,16 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
   // trip), so it runs three stages and waits only for the OLDEST slice in flight (loads return in order)
 #pragma unroll
   for (int st = 0; st < STAGES - 1; ++st) if (st < ks_total) issue(st);
-  if constexpr (PFD > 0) prefetch(PFD);
   for (int ks = 0; ks < ks_total; ++ks) {
-    // this wave's part of slice ks has landed: everything but the (STAGES - 2) younger slices still in flight (and
-    // the one prefetch request issued after it: loads return in order)
-    if constexpr (PFD > 0) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-    else if (STAGES == 2 || ks + STAGES - 2 >= ks_total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // this wave's part of slice ks has landed: everything but the (STAGES - 2) younger slices still in flight
+    if (STAGES == 2 || ks + STAGES - 2 >= ks_total) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(%0)" :: "n"((STAGES - 2) * (DMA_A + DMA_W)) : "memory");
     // ... and everyone's; every wave is done with slice ks - 1, whose stage is refilled next.  With loads that must
     // stay in flight across it the bare barrier instruction: __syncthreads() would drain them (its fence waits for
     // every load in flight); the asm statements on both sides keep the LDS reads where they are
-    if (STAGES == 2 && PFD == 0) __syncthreads(); else __builtin_amdgcn_s_barrier();
+    if (STAGES == 2) __syncthreads(); else __builtin_amdgcn_s_barrier();
     if (ks + STAGES - 1 < ks_total) issue(ks + STAGES - 1);
     else asm volatile("" ::: "memory");
-    if constexpr (PFD > 0) prefetch(ks + STAGES - 1 + PFD);      // (always one request per step: the wait above counts on it)
     const char* As = gb_lds + (ks % STAGES) * STAGE_BYTES;
     const char* Ws = As + A_BYTES;
     // Fragment reads run ahead of the matrix cores inside the slice: the (k32, row tile) steps are one sequence, the
@@ -437,7 +405,6 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
       __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);
     }
   }
-  if constexpr (PFD > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the last prefetch words have landed in this workgroup's LDS
   // acc[i][j][e]: row m0 + wm*MI*16 + i*16 + m16, column (tile j) + 4*g + e
   if constexpr (EPI == EPI_ROPE) {
     rope_epilogue<D, KT, MI, NT>(acc, ep, m0 + wm * (MI * 16), n0 + wn * (NT * 16), M, N, m16, g);
@@ -467,7 +434,7 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
         }
       }
     } else {
-      float* o = (float*)out + (size_t)gm * N;
+      float* o = (float*)out + (size_t)blockIdx.z * M * N + (size_t)gm * N;
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int gn = n0 + wn * (NT * 16) + j * 16 + 4 * g;
@@ -483,15 +450,15 @@ __global__ __launch_bounds__(WM * WN * 64) void k_gemm_tile(const bf16_t* __rest
   }
 }
 
-template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t, int PFD = 0>
+template <int EPI, int BM, int BN, int WM, int WN, int STAGES = 2, int D = 128, typename KT = bf16_t>
 void tile_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, void* out, int M, int N, int K, const RopeEpi& ep = RopeEpi{}) {
-  constexpr int LDS_BYTES = STAGES * (BM + BN) * GB_BK * 2 + (PFD > 0 ? WM * WN * 64 * 4 : 0);     // stages x (A tile + W tile) (+ the prefetch's landing area)
+  constexpr int LDS_BYTES = STAGES * (BM + BN) * GB_BK * 2;     // stages x (A tile + W tile)
   // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
-  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN, STAGES, D, KT, PFD>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_tile<EPI, BM, BN, WM, WN, STAGES, D, KT>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   (void)attr_once;
   const int ncols = EPI == EPI_SWIGLU ? BN / 2 : BN;             // output columns per tile
   dim3 grid((N + ncols - 1) / ncols, (M + BM - 1) / BM);
-  hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN, STAGES, D, KT, PFD>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K, ep);
+  hipLaunchKernelGGL((k_gemm_tile<EPI, BM, BN, WM, WN, STAGES, D, KT>), grid, dim3(WM * WN * 64), LDS_BYTES, s, a, w, out, M, N, K, ep);
 }
 
 }  // namespace
@@ -504,15 +471,15 @@ bool gemm_big_applies(int M, int N, int K) {
 }
 
 void launch_gemm_big(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
-  tile_launch<EPI_F32, 256, 256, 2, 4, 2, 128, bf16_t, GB_PFD>(s, a, w, (void*)c, M, N, K);
+  tile_launch<EPI_F32, 256, 256, 2, 4>(s, a, w, (void*)c, M, N, K);
 }
 
 void launch_gemm_big_resid(hipStream_t s, const bf16_t* a, const bf16_t* w, float* x, int M, int N, int K) {
-  tile_launch<EPI_RESID, 256, 256, 2, 4, 2, 128, bf16_t, GB_PFD>(s, a, w, (void*)x, M, N, K);
+  tile_launch<EPI_RESID, 256, 256, 2, 4>(s, a, w, (void*)x, M, N, K);
 }
 
 void launch_gemm_big_swiglu(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
-  tile_launch<EPI_SWIGLU, 256, 256, 2, 4, 2, 128, bf16_t, GB_PFD>(s, a, wgu, (void*)act, M, F, K);
+  tile_launch<EPI_SWIGLU, 256, 256, 2, 4>(s, a, wgu, (void*)act, M, F, K);
 }
 
 // QKV projection of a prefill chunk with S3 (rotary embedding, gate logit, cache appends) as its epilogue: for bf16
@@ -527,7 +494,7 @@ bool gemm_rope_applies(int M, int N, int K, int D) {
 // the decode step at batch 64: 192 rows (L = 3) 6.59 -> 6.42 ms, 256 rows (L = 4) 6.84 -> 6.71 ms, 128 rows equal, so
 // it is used from 129 rows on.
 bool gemm_rope_rows_applies(int M, int N, int K, int D) {
-  return M > GB_ROPE_ROWS_MIN && (K % GB_BK) == 0 && (D == 64 || D == 128) && N % 128 == 0;
+  return M > 128 && (K % GB_BK) == 0 && (D == 64 || D == 128) && N % 128 == 0;
 }
 void launch_gemm_rope_rows(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, int M, int N, int K, const float* gate_w,
                            const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv, const int32_t* pos, int L,
@@ -547,18 +514,18 @@ void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, in
                           const double* inv_freq, int mode, bool kv8) {
   const RopeEpi ep{gate_w, gate_b, inv_freq, q_out, z_out, kv, n, loop, dm.Hq, dm.Hkv, mode, nullptr, 1};
   if (dm.D == 128) {
-    if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, fp8_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
-    else tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, bf16_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
+    if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 128, fp8_t>(s, a, wqkv, nullptr, M, N, K, ep);
+    else tile_launch<EPI_ROPE, 256, 256, 4, 2>(s, a, wqkv, nullptr, M, N, K, ep);
   } else {
-    if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 64, fp8_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
-    else tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 64, bf16_t, GB_PFD>(s, a, wqkv, nullptr, M, N, K, ep);
+    if (kv8) tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 64, fp8_t>(s, a, wqkv, nullptr, M, N, K, ep);
+    else tile_launch<EPI_ROPE, 256, 256, 4, 2, 2, 64, bf16_t>(s, a, wqkv, nullptr, M, N, K, ep);
   }
 }
 
 // Decode step: act[M, F] = silu(a Wg^T) * (a Wu^T) for up to 256 rows in one launch: all rows of the step in one
 // tile, whole K, 32 gate + 32 up columns per workgroup, SwiGLU in the epilogue - no split-K slabs and no separate
-// activation kernel.  With three or four LDS stages and the fragment reads running ahead of the matrix cores this
-// beats the streaming kernel + activation kernel at every row count (batch 64: L = 2 step 6.13 -> 5.95 ms, non-looped
+// activation kernel.  With three or four LDS stages (deeper rings: equal) and the fragment reads running ahead of the
+// matrix cores this beats the streaming kernel + activation kernel at every row count (batch 64: L = 2 step 6.13 -> 5.95 ms, non-looped
 // 5.39 -> 5.29; batch 1: 1.66 -> 1.56 ms per token); the tile height follows the rows (64 / 128 / 256).
 bool gemm_swiglu_rows_applies(int M, int F, int K) {
   // (larger row counts - several 256-row tiles - until the 256 x 256 prefill tiles fill the chip: 257..1024 rows
@@ -566,15 +533,35 @@ bool gemm_swiglu_rows_applies(int M, int F, int K) {
   return M >= 1 && (K % GB_BK) == 0 && (F + 31) / 32 >= 128;   // enough 32-column tiles to occupy the chip
 }
 
-// the same tile with the plain float epilogue: wide projections at 129..256 rows, whole K, no slabs
-void launch_gemm_rows_tile(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
-  tile_launch<EPI_F32, 256, 64, 4, 2, 3>(s, a, w, (void*)c, M, N, K);
+// Decode-sized projections with the plain float epilogue: 64-column row tiles x S runs of K slices (one float slab per
+// run; consumers add them in order), S chosen so that about 256 workgroups share the work
+int gemm_rows_split_slabs(int M, int N, int K) {
+  const int tiles = ((N + 63) / 64) * ((M + 255) / 256);
+  int S = 256 / tiles; if (S < 1) S = 1;      // (128 and 512 workgroups measured slower)
+  const int ks = K / GB_BK; if (S > ks / 4) S = ks / 4 > 0 ? ks / 4 : 1;
+  return S;
+}
+void launch_gemm_rows_split(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
+  const int S = gemm_rows_split_slabs(M, N, K);
+  constexpr int LDS256 = 3 * (256 + 64) * GB_BK * 2, LDS128 = 3 * (128 + 64) * GB_BK * 2, LDS64 = 4 * (64 + 64) * GB_BK * 2;
+  RopeEpi ep{};
+  if (M <= 64) {
+    static const hipError_t a1 = hipFuncSetAttribute((const void*)k_gemm_tile<EPI_F32, 64, 64, 2, 2, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS64); (void)a1;
+    hipLaunchKernelGGL((k_gemm_tile<EPI_F32, 64, 64, 2, 2, 4>), dim3((N + 63) / 64, 1, S), dim3(256), LDS64, s, a, w, (void*)c, M, N, K, ep);
+  } else if (M <= 128) {
+    static const hipError_t a2 = hipFuncSetAttribute((const void*)k_gemm_tile<EPI_F32, 128, 64, 2, 2, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS128); (void)a2;
+    hipLaunchKernelGGL((k_gemm_tile<EPI_F32, 128, 64, 2, 2, 3>), dim3((N + 63) / 64, 1, S), dim3(256), LDS128, s, a, w, (void*)c, M, N, K, ep);
+  } else {
+    static const hipError_t a3 = hipFuncSetAttribute((const void*)k_gemm_tile<EPI_F32, 256, 64, 4, 2, 3>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS256); (void)a3;
+    hipLaunchKernelGGL((k_gemm_tile<EPI_F32, 256, 64, 4, 2, 3>), dim3((N + 63) / 64, (M + 255) / 256, S), dim3(512), LDS256, s, a, w, (void*)c, M, N, K, ep);
+  }
 }
 
+
 void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
-  if (M <= 64) { tile_launch<EPI_SWIGLU, 64, 64, 2, 2, GB_ST64>(s, a, wgu, (void*)act, M, F, K); return; }
-  if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 64, 2, 2, GB_ST128>(s, a, wgu, (void*)act, M, F, K); return; }
-  tile_launch<EPI_SWIGLU, 256, 64, 4, 2, GB_ST256>(s, a, wgu, (void*)act, M, F, K);
+  if (M <= 64) { tile_launch<EPI_SWIGLU, 64, 64, 2, 2, 4>(s, a, wgu, (void*)act, M, F, K); return; }
+  if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 64, 2, 2, 3>(s, a, wgu, (void*)act, M, F, K); return; }
+  tile_launch<EPI_SWIGLU, 256, 64, 4, 2, 3>(s, a, wgu, (void*)act, M, F, K);
 }
 
 }  // namespace plt

@@ -303,19 +303,18 @@ static WsPlan ws_plan(int M, int N, int K) {
   return p;
 }
 
-// Wide projections (QKV) at 129..192 rows and from 257 rows up to where the 256 x 256 prefill tiles take over: all
-// rows in 256 x 64 tiles, whole K, three LDS stages -- no slabs, and measured 2 % (129..192 rows) and 4-6 % (257..1024
-// rows, where the streaming kernel reads the weights once per 128-row block) of the decode step faster than the
-// streaming kernel; at 193..256 rows and up to 128 rows: equal, the streaming kernel is kept.  Narrow projections
-// (output, down: 2048 columns = 32 such tiles per 256 rows) lose with it at every row count.
-static bool tile_rows_applies(int M, int N, int K) {
-  if (N < 4096 || K > 4096 || (K % 64) != 0) return false;
-  return (M > 128 && M <= 192) || (M > 256 && !gemm_big_applies(M, N, K));
+// Decode-sized projections (up to 1024 rows, K from 1024 on) run as row tiles of the tile kernel with K split over
+// about 256 workgroups: 64 / 128 / 256 rows x 64 columns x a run of K slices, three or four LDS stages, one float slab
+// per K run (one slab, i.e. whole K, when the tiles alone fill the chip: wide projections from 257 rows on).  Measured
+// in the decode step against the streaming kernel above: batch 64 L = 1 / 2 / 3 / 4 -1.8 / -3.0 / -3.2 / -2.3 %, batch 1
+// -7.9 %, batch 16 -5.6 % (fewer and smaller slabs: 8 runs of K for the down projection instead of 11 ranges, and what
+// a kernel leaves dirty in eight L2s is drained at its boundary).  The streaming kernel keeps short K and tiny N.
+static bool rows_split_applies(int M, int N, int K) {
+  return M >= 1 && M <= 1024 && N >= 256 && K >= 1024 && (K % 64) == 0 && !gemm_big_applies(M, N, K);
 }
-
 // splits for the generic entry: the streaming kernel writes one slab per workgroup K span
 int gemm_bf16_splits_any(int M, int N, int K) {
-  if (tile_rows_applies(M, N, K)) return 1;
+  if (rows_split_applies(M, N, K)) return gemm_rows_split_slabs(M, N, K);
   if (gemm_use_wstream(M, N, K)) return ws_plan(M, N, K).S;
   if (gemm_big_applies(M, N, K)) return 1;
   return gemm_bf16_splits(M, N, K);
@@ -332,7 +331,7 @@ static void ws_launch(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c,
 }
 
 void launch_gemm_bf16_any(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
-  if (tile_rows_applies(M, N, K)) { launch_gemm_rows_tile(s, a, w, c, M, N, K); return; }
+  if (rows_split_applies(M, N, K)) { launch_gemm_rows_split(s, a, w, c, M, N, K); return; }
   if (!gemm_use_wstream(M, N, K)) {
     if (gemm_big_applies(M, N, K)) launch_gemm_big(s, a, w, c, M, N, K);
     else launch_gemm_bf16(s, a, w, c, M, N, K, gemm_bf16_splits(M, N, K));

@@ -230,7 +230,8 @@ void launch_gemm_big_rope(hipStream_t s, const bf16_t* a, const bf16_t* wqkv, in
                           const double* inv_freq, int mode, bool kv8);
 // decode rows (M <= 256): the gate/up projection with the SwiGLU fused, whole K per workgroup, no slabs
 bool gemm_swiglu_rows_applies(int M, int F, int K);
-void launch_gemm_rows_tile(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
+int gemm_rows_split_slabs(int M, int N, int K);
+void launch_gemm_rows_split(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K);
 void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K);
 // picks the weight-streaming kernel for few rows, the big-tile one for many, the small-tile one between
 int gemm_bf16_splits_any(int M, int N, int K);
