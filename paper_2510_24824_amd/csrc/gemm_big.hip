@@ -538,7 +538,7 @@ bool gemm_swiglu_rows_applies(int M, int F, int K) {
 int gemm_rows_split_slabs(int M, int N, int K) {
   const int tiles = ((N + 63) / 64) * ((M + 255) / 256);
   int S = 256 / tiles; if (S < 1) S = 1;      // (128 and 512 workgroups measured slower)
-  const int ks = K / GB_BK; if (S > ks / 4) S = ks / 4 > 0 ? ks / 4 : 1;
+  const int ks = K / GB_BK; if (S > ks / 8) S = ks / 8 > 0 ? ks / 8 : 1;      // at least 8 slices per run (4: equal at batch 64, slower at batch 1; 16: slower)
   return S;
 }
 void launch_gemm_rows_split(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c, int M, int N, int K) {
