@@ -134,7 +134,9 @@ void launch_gemm_bf16(hipStream_t s, const bf16_t* a, const bf16_t* w, float* c,
 }  // namespace plt
 
 // ----------------------------------------------------------------------------------------------
-// Decode-time variant ("weight streaming"): few rows (M <= 128 per row block), weights read once.
+// Weight-streaming variant for few rows (M <= 128 per row block), weights read once.  It served every decode
+// projection until the row tiles of gemm_big.hip overtook it (rows_split_applies below); it remains the kernel for
+// few-row products with K below 1024, K no multiple of 64, or fewer than 256 columns.
 //
 // A workgroup owns one K range of KR = 512 and keeps the matching slice of the activations
 // (up to 128 rows x 512, bf16) resident in LDS.  Its 4 waves (one per SIMD, so each may use the
