@@ -380,6 +380,18 @@ size_t plt_gemm_mx_scratch_bytes(int32_t M, int32_t N, int32_t K);
 int plt_gemm_mx(int32_t M, int32_t N, int32_t K, const void* dev_a_codes, const void* dev_a_scales,
                 const void* dev_w_codes, const void* dev_w_scales, float* dev_c, void* dev_scratch,
                 size_t scratch_bytes, void* hip_stream);
+/* The gate/up projection of the low-bit feed-forward block with its activation and the quantiser of the
+ * down projection's operand [inference efficiency evaluation recipe; SwiGLU feed-forward of the backbone]:
+ * h[M, F] = silu(a Wg^T) * (a Wu^T) from the low-bit operands above, w = [gate rows; up rows] = [2F, K]
+ * (F % 32 == 0, K % 128 == 0), written as e4m3 codes [M][F] and block scales [M][16 * ceil(F/512)] in the
+ * activation layout (bytes of blocks beyond F are 0).  For decode-sized M and F >= 4096 one kernel (the
+ * activation and the quantiser are the product's epilogue); otherwise the product's K-range slabs go through
+ * dev_scratch (plt_gemm_mx_swiglu_scratch_bytes) and a second kernel.  The result must not alias the operand.
+ * All pointers device memory, 16-byte aligned; PLT_EINVAL / PLT_ENOMEM as for plt_gemm_mx. */
+size_t plt_gemm_mx_swiglu_scratch_bytes(int32_t M, int32_t F, int32_t K);
+int plt_gemm_mx_swiglu(int32_t M, int32_t F, int32_t K, const void* dev_a_codes, const void* dev_a_scales,
+                       const void* dev_w_codes, const void* dev_w_scales, void* dev_h_codes, void* dev_h_scales,
+                       void* dev_scratch, size_t scratch_bytes, void* hip_stream);
 
 /* Plain device-to-device copy kernel (16 bytes per lane): the known-size reference for HBM
  * traffic counters and a practical bandwidth ceiling.  nbytes and both pointers must be

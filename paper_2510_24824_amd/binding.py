@@ -88,6 +88,8 @@ _SIGS = {
     "plt_mx_quantize_act": (C.c_int, [_I, _I, _I, _P, _P, _P, _P]),
     "plt_gemm_mx_scratch_bytes": (_Z, [_I, _I, _I]),
     "plt_gemm_mx": (C.c_int, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _Z, _P]),
+    "plt_gemm_mx_swiglu_scratch_bytes": (_Z, [_I, _I, _I]),
+    "plt_gemm_mx_swiglu": (C.c_int, [_I, _I, _I, _P, _P, _P, _P, _P, _P, _P, _Z, _P]),
     "plt_stream_copy": (C.c_int, [_P, _P, _Z, _P]),
     "plt_stream_read": (C.c_int, [_P, _Z, _P, _Z, _P]),
     "plt_profile_enable": (C.c_int, [_P, _I]),
@@ -559,3 +561,18 @@ def gemm_mx(a_codes, a_scales, w_codes, w_scales, M, N, K):
     _check(lib().plt_gemm_mx(M, N, K, _ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), _ptr(c), _ptr(scratch), nb,
                              _stream()))
     return c
+
+
+def gemm_mx_swiglu(a_codes, a_scales, w_codes, w_scales, M, F, K):
+    """Low-bit gate/up projection + SwiGLU + block quantiser: (e4m3 codes [M, F], e8m0 scales [M, 16 * ceil(F / 512)])."""
+    import torch
+    nb = lib().plt_gemm_mx_swiglu_scratch_bytes(M, F, K)
+    ns = lib().plt_mx_act_scale_bytes(M, F)
+    if nb == 0 or ns == 0:
+        raise PltError(-1, lib().plt_last_error().decode())
+    codes = torch.empty(M, F, dtype=torch.uint8, device="cuda")
+    scales = torch.empty(M, ns // M, dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(nb, dtype=torch.uint8, device="cuda")
+    _check(lib().plt_gemm_mx_swiglu(M, F, K, _ptr(a_codes), _ptr(a_scales), _ptr(w_codes), _ptr(w_scales), _ptr(codes), _ptr(scales),
+                                    _ptr(scratch), nb, _stream()))
+    return codes, scales

@@ -384,6 +384,223 @@ __global__ __launch_bounds__(512) void k_gemm_mx_tile(const uint8_t* __restrict_
   }
 }
 
+// ---------------------------------------------------------------------------------------------- decode-sized row counts
+// The same product for the few hundred rows of a decode step, organised like the bf16 row tiles: a workgroup takes
+// BM rows x 64 columns (4 weight strips) x one run of K (blockIdx.z; runs are whole
+// groups of 4 chunks, so that a scale dword never straddles two runs) and writes one float slab per run.  Chunks of
+// 128 k go HBM -> LDS directly through a ring of STAGES stages: the activation rows (BM x 128 code bytes, 16-byte
+// pieces XOR-swizzled with the row number) and the 4 strips' KiB as they lie in memory; only the oldest chunk in
+// flight is waited for (loads return in order), one bare barrier per chunk.  4 waves, each BM / 4 rows x all 64
+// columns.  The block scales (one dword per lane and group of 4 chunks) come the same way, a group ahead.
+// EPI 1 (gate/up): the tile is 32 gate + the matching 32 up columns over the whole K, and its epilogue applies SwiGLU
+// and quantises the 32 hidden values of a row - exactly one block - to e4m3 with their scale byte: no slabs and no
+// separate activation kernel.
+enum { MXR_F32 = 0, MXR_SWIGLU = 1 };
+template <int EPI, int BM, int STAGES>
+__global__ __launch_bounds__(256) void k_gemm_mx_rows(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
+                                                      const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
+                                                      void* __restrict__ out, uint8_t* __restrict__ out_sc, int M, int N, int K) {
+  // N: MXR_F32: output columns (= rows of w); MXR_SWIGLU: F (w has 2F rows: gate rows, then up rows; the output F columns)
+  constexpr int THREADS = 256, MI = BM / 64, NT = 4, DMA_A = BM * 8 / THREADS, DMA_N = DMA_A + 1;
+  constexpr int A_BYTES = BM * 128, STAGE_BYTES = A_BYTES + NT * 1024;
+  static_assert(BM == 64 || BM == 128 || BM == 256, "rows per tile");
+  extern __shared__ __attribute__((aligned(16))) char mxr_lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), m16 = lane & 15, g = lane >> 4;
+  const int m0 = blockIdx.y * BM, tile_n = blockIdx.x;
+  const int n_chunks = K >> 7, n_cgrp = (n_chunks + 3) >> 2, asb = mx_ascale_row_bytes(K);
+  const int w_rows = EPI == MXR_SWIGLU ? 2 * N : N, n_strips = w_rows >> 4;
+  // weight strip behind tile strip j (beyond the matrix: clamped, never stored)
+  auto strip_of = [&](int j) -> int {
+    int st = EPI == MXR_SWIGLU ? (j < 2 ? tile_n * 2 + j : (N >> 4) + tile_n * 2 + (j - 2)) : tile_n * NT + j;
+    return st < n_strips ? st : n_strips - 1;
+  };
+  // this workgroup's run of chunk groups
+  const int gpz = (n_cgrp + (int)gridDim.z - 1) / (int)gridDim.z;
+  const int q0 = (int)blockIdx.z * gpz, q1 = q0 + gpz < n_cgrp ? q0 + gpz : n_cgrp;
+  const int ch0 = q0 * 4, ch1 = q1 * 4 < n_chunks ? q1 * 4 : n_chunks;              // (an empty run writes a slab of zeros)
+  // this thread's pieces of a stage: slot s = i*THREADS + tid -> row s/8, piece (s%8) ^ (row%8); one weight strip per wave
+  unsigned pa[DMA_A];
+#pragma unroll
+  for (int i = 0; i < DMA_A; ++i) {
+    const int sl = i * THREADS + tid, row = sl >> 3, pc = (sl & 7) ^ (row & 7);
+    int gm = m0 + row; if (gm >= M) gm = M - 1;                 // rows beyond M: computed, never stored
+    pa[i] = (unsigned)gm * (unsigned)K + pc * 16;
+  }
+  const uint8_t* pw = w + (size_t)strip_of(wv) * n_chunks * 1024 + lane * 16;
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mxr_lds;
+  auto dma16 = [](const uint8_t* src, unsigned lds_wave_base) {  // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
+    unsigned keep_m0;                                            // m0 is left as it was found
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
+  };
+  auto issue = [&](int ch) {                                     // chunk ch -> stage (ch - ch0) % STAGES
+    const unsigned stage = lds0 + (unsigned)((ch - ch0) % STAGES) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < DMA_A; ++i)
+      dma16(a + ((size_t)pa[i] + (size_t)ch * 128), stage + (unsigned)(i * THREADS + wv * 64) * 16);
+    dma16(pw + (size_t)ch * 1024, stage + A_BYTES + (unsigned)wv * 1024);
+  };
+  // Scale dwords of chunk group q (one per lane covers the group's 4 chunks) take the same road, 4 bytes per lane: wave
+  // j fetches strip j's (lane (m, g): weight row m, block g), every wave those of its own row tiles (row m16, block
+  // g), into one of two scale areas behind the stages; the registers are filled from there at the group's first chunk
+  constexpr int SC_OFF = STAGES * STAGE_BYTES, SC_BYTES = NT * 256 + 4 * MI * 256, DMA_S = 1 + MI;
+  const uint8_t* wsp = w_sc + (size_t)strip_of(wv) * n_cgrp * 256 + lane * 4;
+  unsigned asp[MI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i) {
+    int gm = m0 + wv * (MI * 16) + i * 16 + m16; if (gm >= M) gm = M - 1;
+    asp[i] = (unsigned)gm * (unsigned)asb + g * 4;
+  }
+  auto dma4 = [](const uint8_t* src, unsigned lds_wave_base) {   // lane l: 4 bytes -> LDS[lds_wave_base + 4 l]
+    unsigned keep_m0;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %2, off\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep_m0) : "s"(lds_wave_base), "v"(src) : "memory");
+  };
+  auto issue_scales = [&](int q) {
+    const unsigned area = lds0 + SC_OFF + (unsigned)((q - q0) & 1) * SC_BYTES;
+    dma4(wsp + (size_t)q * 256, area + (unsigned)wv * 256);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) dma4(a_sc + ((size_t)asp[i] + q * 16), area + NT * 256 + (unsigned)(wv * MI + i) * 256);
+  };
+  unsigned wsc[NT], asc[MI];
+  f32x4 acc[MI][NT];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int sw0 = (g ^ (m16 & 7)) * 16;                  // byte offset of the lane's first piece inside its row
+  // one chunk: kk = its place in the group of 4 (selects the scale byte), compile-time
+  auto step = [&](int ch, auto kk_tag) {
+    constexpr int kk = decltype(kk_tag)::value;
+    // this wave's part of chunk ch has landed: everything but the STAGES - 2 younger chunks (the scale dwords of a
+    // group are requested a group ahead, between two chunks: they are older than what may stay in flight at the
+    // group's first chunk)
+    if (ch + STAGES - 2 >= ch1) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(%0)" :: "n"((STAGES - 2) * DMA_N) : "memory");
+    __builtin_amdgcn_s_barrier();                      // ... and everyone's; every wave is done with chunk ch - 1 (bare: the loads in flight stay in flight)
+    if (ch + STAGES - 1 < ch1) issue(ch + STAGES - 1);
+    else asm volatile("" ::: "memory");
+    if constexpr (kk == 0) {
+      const int q = ch >> 2;
+      if (q + 1 < q1) issue_scales(q + 1);
+      const char* sc = mxr_lds + SC_OFF + ((q - q0) & 1) * SC_BYTES;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) wsc[j] = *reinterpret_cast<const unsigned*>(sc + j * 256 + lane * 4);
+#pragma unroll
+      for (int i = 0; i < MI; ++i) asc[i] = *reinterpret_cast<const unsigned*>(sc + NT * 256 + (wv * MI + i) * 256 + lane * 4);
+    }
+    const char* As = mxr_lds + ((ch - ch0) % STAGES) * STAGE_BYTES;
+    const char* Ws = As + A_BYTES;
+    uint4 fw[NT];
+#pragma unroll
+    for (int j = 0; j < NT; ++j) fw[j] = *reinterpret_cast<const uint4*>(Ws + j * 1024 + lane * 16);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const char* ap = As + (wv * (MI * 16) + i * 16 + m16) * 128;
+      const uint4 lo = *reinterpret_cast<const uint4*>(ap + sw0), hi = *reinterpret_cast<const uint4*>(ap + (sw0 ^ 64));
+      const i32x8 bv = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const i32x8 av = {(int)fw[j].x, (int)fw[j].y, (int)fw[j].z, (int)fw[j].w, 0, 0, 0, 0};
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(av, bv, acc[i][j], 4, 0, kk, (int)wsc[j], kk, (int)asc[i]);
+      }
+    }
+  };
+  if (q0 < q1) issue_scales(q0);
+#pragma unroll
+  for (int st = 0; st < STAGES - 1; ++st) if (ch0 + st < ch1) issue(ch0 + st);
+  for (int q = q0; q < q1; ++q) {
+    const int c4 = q * 4;
+    step(c4, std::integral_constant<int, 0>{});
+    if (c4 + 1 < ch1) step(c4 + 1, std::integral_constant<int, 1>{});
+    if (c4 + 2 < ch1) step(c4 + 2, std::integral_constant<int, 2>{});
+    if (c4 + 3 < ch1) step(c4 + 3, std::integral_constant<int, 3>{});
+  }
+  // acc[i][j][x]: row m0 + wv*MI*16 + i*16 + m16, column 4 g + x of tile strip j
+  if constexpr (EPI == MXR_SWIGLU) {
+    const int nbp = mx_ascale_row_bytes(N);
+    uint8_t* codes = (uint8_t*)out;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int gm = m0 + wv * (MI * 16) + i * 16 + m16;
+      float h[2][4];
+      float amax = 0.f;
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+          const float gt = acc[i][jj][x];
+          h[jj][x] = gt / (1.0f + expf(-gt)) * acc[i][jj + 2][x];
+          amax = fmaxf(amax, fabsf(h[jj][x]));
+        }
+      amax = fmaxf(amax, __shfl_xor(amax, 16));        // the row's 32 hidden values sit in the 4 lanes m16 + 16 g
+      amax = fmaxf(amax, __shfl_xor(amax, 32));
+      if (gm >= M || tile_n * 32 >= N) continue;
+      const int e = mx_block_exponent(amax, 8);
+#pragma unroll
+      for (int jj = 0; jj < 2; ++jj)
+        *reinterpret_cast<unsigned*>(codes + (size_t)gm * N + tile_n * 32 + jj * 16 + 4 * g) = mx_pack4_e4m3(h[jj][0], h[jj][1], h[jj][2], h[jj][3], e);
+      if (g == 0) {
+        out_sc[(size_t)gm * nbp + mx_ascale_index(tile_n)] = (uint8_t)(e + 127);
+        if (tile_n == 0) for (int b = N >> 5; b < nbp; ++b) out_sc[(size_t)gm * nbp + mx_ascale_index(b)] = 0;   // scale bytes beyond F
+      }
+    }
+  } else {
+    float* cs = (float*)out + (size_t)blockIdx.z * M * N;
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      const int gm = m0 + wv * (MI * 16) + i * 16 + m16;
+      if (gm >= M) continue;
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int gn = (tile_n * NT + j) * 16 + 4 * g;
+        if (gn < N) *reinterpret_cast<f32x4*>(cs + (size_t)gm * N + gn) = acc[i][j];       // N % 16 == 0: whole groups of 4 columns
+      }
+    }
+  }
+}
+
+// Row tiles serve the decode-sized row counts below the tiled kernel's.  Tiles are 64 rows high at every row count
+// (with the 4-bit weights a tile's traffic is mostly its activation rows, so taking the weights once per 64 rows costs
+// little, and three such workgroups fit a compute unit: measured at 192 / 256 rows against 128- and 256-row tiles:
+// decode step -5 %); K runs: about 256 workgroups (128, 384, 512: slower), whole groups of 4 chunks.
+constexpr int MXR_BM = 64, MXR_STAGES = 4;
+static bool gemm_mx_tile_applies(int M, int N, int K);
+static bool gemm_mx_rows_applies(int M, int N, int K) {
+  return M >= 1 && M <= 1024 && N >= 256 && (N % 16) == 0 && K >= 512 && (K % 128) == 0 && !gemm_mx_tile_applies(M, N, K);
+}
+static int gemm_mx_rows_slabs(int M, int N, int K) {
+  const int tiles = ((N + 63) / 64) * ((M + MXR_BM - 1) / MXR_BM), n_cgrp = ((K >> 7) + 3) >> 2;
+  int S = 256 / tiles; if (S < 1) S = 1;
+  if (S > n_cgrp) S = n_cgrp;
+  const int gpz = (n_cgrp + S - 1) / S;
+  return (n_cgrp + gpz - 1) / gpz;              // no empty run
+}
+template <int EPI>
+static void mx_rows_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, void* out,
+                           uint8_t* out_sc, int M, int N, int K, int col_tiles, int S) {
+  constexpr int LDS_BYTES = MXR_STAGES * (MXR_BM * 128 + 4096) + 2 * (4 * 256 + 4 * (MXR_BM / 64) * 256);     // stages + two scale areas
+  // opt-in to more than 64 KB of dynamic LDS: once per template instance, thread-safe (initialisation of a local static)
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_mx_rows<EPI, MXR_BM, MXR_STAGES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  (void)attr_once;
+  hipLaunchKernelGGL((k_gemm_mx_rows<EPI, MXR_BM, MXR_STAGES>), dim3(col_tiles, (M + MXR_BM - 1) / MXR_BM, S), dim3(256), LDS_BYTES, s,
+                     a, a_sc, w, w_sc, out, out_sc, M, N, K);
+}
+static void launch_gemm_mx_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
+                                int M, int N, int K) {
+  mx_rows_launch<MXR_F32>(s, a, a_sc, w, w_sc, (void*)c, nullptr, M, N, K, (N + 63) / 64, gemm_mx_rows_slabs(M, N, K));
+}
+
+// Gate/up projection of a decode step with SwiGLU and the e4m3 block quantiser as its epilogue: codes[M, F] and their
+// scale bytes (the down projection's operand) straight from the product
+bool gemm_mx_swiglu_rows_applies(int M, int F, int K) {
+  return M >= 1 && M <= 1024 && (F % 32) == 0 && F / 32 >= 128 && K >= 512 && (K % 128) == 0 && !gemm_mx_tile_applies(M, 2 * F, K);
+}
+void launch_gemm_mx_swiglu_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* wgu, const uint8_t* wgu_sc,
+                                uint8_t* codes, uint8_t* scales, int M, int F, int K) {
+  mx_rows_launch<MXR_SWIGLU>(s, a, a_sc, wgu, wgu_sc, (void*)codes, scales, M, F, K, F / 32, 1);
+}
+
 // rows from which the tiled kernel takes over (its 256 x 256 tiles must fill the chip)
 static bool gemm_mx_tile_applies(int M, int N, int K) {
   const long tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
@@ -392,7 +609,11 @@ static bool gemm_mx_tile_applies(int M, int N, int K) {
 
 // number of [M, N] float slabs the product leaves: one per K range of the streaming kernel, a single one from the
 // tiled kernel
-int gemm_mx_splits(int M, int N, int K) { return gemm_mx_tile_applies(M, N, K) ? 1 : (K + MX_KR - 1) / MX_KR; }
+int gemm_mx_splits(int M, int N, int K) {
+  if (gemm_mx_tile_applies(M, N, K)) return 1;
+  if (gemm_mx_rows_applies(M, N, K)) return gemm_mx_rows_slabs(M, N, K);
+  return (K + MX_KR - 1) / MX_KR;
+}
 
 template <int MT, int NB>
 static void mx_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
@@ -421,6 +642,7 @@ void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const 
     hipLaunchKernelGGL(k_gemm_mx_tile, dim3((N + 255) / 256, (M + 255) / 256), dim3(512), LDS_BYTES, s, a, a_sc, w, w_sc, c, M, N, K);
     return;
   }
+  if (gemm_mx_rows_applies(M, N, K)) { launch_gemm_mx_rows(s, a, a_sc, w, w_sc, c, M, N, K); return; }
   const int n_strips = N >> 4, S = (K + MX_KR - 1) / MX_KR;
   const bool small = M <= 64;
   int slots = 256 * (small ? 2 : 1) / S * 4; if (slots < 4) slots = 4;

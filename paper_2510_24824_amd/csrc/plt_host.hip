@@ -596,10 +596,23 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
                         moe_index_carve(wk.moe_idx, R, c.top_k, c.n_experts), R, d, F, c.n_experts, c.top_k);
       S = c.top_k;
     } else if (m->mx) {                                      // low-bit gate/up and down projections
-      S = run_gemm_mx(m, wk, w.wgu, w.wgu_sc, R, 2 * F, d, dec);
-      launch_silu_mul_mx(s, wk.gout, S, (size_t)R * 2 * F, wk.a_codes, wk.a_scales, R, F);      // SwiGLU + e4m3 blocks
-      dbg_capture(m, kv, wk, 3, R, F);
-      S = run_gemm_mx(m, wk, w.wdown, w.wdown_sc, R, d, F, dec);
+      if (gemm_mx_swiglu_rows_applies(R, F, d)) {
+        // decode rows: SwiGLU + e4m3 blocks in the product's epilogue.  The hidden codes and their scale bytes go to
+        // the (otherwise unused, 4 bytes per element) hidden-row buffer: the product's own operand stays intact
+        Work wh = wk;
+        wh.a_codes = (uint8_t*)wk.act; wh.a_scales = (uint8_t*)wk.act + align256((size_t)R * F);
+        {
+          ProfScope prof(m, PLT_PROF_GEMM, dec);
+          launch_gemm_mx_swiglu_rows(s, wk.a_codes, wk.a_scales, (const uint8_t*)w.wgu, w.wgu_sc, wh.a_codes, wh.a_scales, R, F, d);
+        }
+        dbg_capture(m, kv, wh, 3, R, F);
+        S = run_gemm_mx(m, wh, w.wdown, w.wdown_sc, R, d, F, dec);
+      } else {
+        S = run_gemm_mx(m, wk, w.wgu, w.wgu_sc, R, 2 * F, d, dec);
+        launch_silu_mul_mx(s, wk.gout, S, (size_t)R * 2 * F, wk.a_codes, wk.a_scales, R, F);      // SwiGLU + e4m3 blocks
+        dbg_capture(m, kv, wk, 3, R, F);
+        S = run_gemm_mx(m, wk, w.wdown, w.wdown_sc, R, d, F, dec);
+      }
     } else if (c.n_experts > 0) {                                   // mixture of experts: k slabs, one per selected expert
       ProfScope prof(m, PLT_PROF_GEMM, dec);
       launch_moe_ffn<T>(s, (const T*)wk.a, (const T*)w.router, (const T*)w.wgu, (const T*)w.wdown, (T*)wk.act, wk.gout,
@@ -1244,6 +1257,34 @@ extern "C" int plt_gemm_mx(int32_t M, int32_t N, int32_t K, const void* a_codes,
                    (float*)scratch, M, N, K);
     const size_t n = (size_t)M * N;
     hipLaunchKernelGGL(k_sum_slabs, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)scratch, c, S, n);
+  }
+  HIP_TRY(hipGetLastError());
+  return PLT_OK;
+}
+
+extern "C" size_t plt_gemm_mx_swiglu_scratch_bytes(int32_t M, int32_t F, int32_t K) {
+  if (M < 1 || F < 32 || (F % 32) || !mx_shape_ok(2 * F, K)) { fail(PLT_EINVAL, "plt_gemm_mx_swiglu_scratch_bytes: bad shape"); return 0; }
+  return gemm_mx_swiglu_rows_applies(M, F, K) ? 256 : align256((size_t)gemm_mx_splits(M, 2 * F, K) * M * 2 * F * 4);
+}
+extern "C" int plt_gemm_mx_swiglu(int32_t M, int32_t F, int32_t K, const void* a_codes, const void* a_scales, const void* w_codes,
+                                  const void* w_scales, void* h_codes, void* h_scales, void* scratch, size_t scratch_bytes,
+                                  void* hip_stream) {
+  if (M < 1 || M > 128 * 65535 || F < 32 || (F % 32) || !mx_shape_ok(2 * F, K) || !a_codes || !a_scales || !w_codes || !w_scales ||
+      !h_codes || !h_scales)
+    return fail(PLT_EINVAL, "plt_gemm_mx_swiglu: bad argument (F %% 32, K %% 128)");
+  if ((((uintptr_t)a_codes) | ((uintptr_t)a_scales) | ((uintptr_t)w_codes) | ((uintptr_t)w_scales) | ((uintptr_t)h_codes) |
+       ((uintptr_t)h_scales)) & 15)
+    return fail(PLT_EINVAL, "plt_gemm_mx_swiglu: pointers must be 16-byte aligned");
+  if (h_codes == a_codes || h_scales == a_scales) return fail(PLT_EINVAL, "plt_gemm_mx_swiglu: the result must not overwrite the operand");
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (gemm_mx_swiglu_rows_applies(M, F, K)) {
+    launch_gemm_mx_swiglu_rows(s, (const uint8_t*)a_codes, (const uint8_t*)a_scales, (const uint8_t*)w_codes, (const uint8_t*)w_scales,
+                               (uint8_t*)h_codes, (uint8_t*)h_scales, M, F, K);
+  } else {
+    if (!scratch || scratch_bytes < plt_gemm_mx_swiglu_scratch_bytes(M, F, K)) return fail(PLT_ENOMEM, "plt_gemm_mx_swiglu: scratch too small");
+    launch_gemm_mx(s, (const uint8_t*)a_codes, (const uint8_t*)a_scales, (const uint8_t*)w_codes, (const uint8_t*)w_scales,
+                   (float*)scratch, M, 2 * F, K);
+    launch_silu_mul_mx(s, (const float*)scratch, gemm_mx_splits(M, 2 * F, K), (size_t)M * 2 * F, (uint8_t*)h_codes, (uint8_t*)h_scales, M, F);
   }
   HIP_TRY(hipGetLastError());
   return PLT_OK;

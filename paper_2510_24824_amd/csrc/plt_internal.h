@@ -284,6 +284,10 @@ void launch_mx_quant_a(hipStream_t s, const T* a, uint8_t* codes, uint8_t* scale
 int gemm_mx_splits(int M, int N, int K);
 void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
                     int M, int N, int K);
+// decode rows: gate/up projection with SwiGLU and the e4m3 block quantiser as its epilogue (codes[M, F] + scale bytes)
+bool gemm_mx_swiglu_rows_applies(int M, int F, int K);
+void launch_gemm_mx_swiglu_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* wgu, const uint8_t* wgu_sc,
+                                uint8_t* codes, uint8_t* scales, int M, int F, int K);
 
 // moe.hip : mixture-of-experts feed-forward.  Index arrays of one call (device): the selected experts and
 // their probabilities per row, the (row, slot) pairs sorted by expert and every expert's span in that list.

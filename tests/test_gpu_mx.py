@@ -98,7 +98,10 @@ GEMM_CASES = [(128, 6144, 2048),   # QKV projection of the 1.3B model at 64 sequ
               (130, 2048, 1024),   # second row block with two rows
               (1, 16, 128),
               (2048, 4096, 640),   # prefill-sized: the 256 x 256-tile kernel, whole K (5 chunks: a partial scale group)
-              (1100, 6640, 256)]   # the tiled kernel with ragged last row and column tiles
+              (1100, 6640, 256),   # the tiled kernel with ragged last row and column tiles
+              (200, 2048, 640),    # row tiles: four 64-row tiles, the last with a ragged tail, 5 chunks (a partial scale group)
+              (384, 1040, 1536),   # row tiles: six row tiles, a ragged last column tile, three K runs
+              (16, 256, 512)]      # row tiles: the smallest shape they take (one scale group, four column tiles)
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_CASES)
@@ -123,6 +126,61 @@ def test_gemm_mx_matches_oracle(M, N, K):
     # and the quantised product is close to the unquantised one (sanity of the whole chain)
     exact = x.astype(np.float64) @ w.astype(np.float64).T
     assert np.abs(ref - exact).max() <= 0.25 * np.abs(exact).max()
+
+
+SWIGLU_CASES = [(128, 5632, 2048),   # gate/up of the 1.3B model at 64 sequences x 2 loops: one kernel, SwiGLU + quantiser in its epilogue
+                (64, 4096, 512),     # one scale group
+                (200, 4096, 640),    # four row tiles, the last with a ragged tail, a partial scale group
+                (300, 4128, 1024),   # five row tiles, F / 32 = 129 column tiles
+                (1, 4096, 512),
+                (40, 1024, 384)]     # too narrow for the fused kernel: product slabs + the activation kernel
+
+
+@pytest.mark.parametrize("M,F,K", SWIGLU_CASES)
+def test_gemm_mx_swiglu_matches_oracle(M, F, K):
+    """h = silu(a Wg^T) * (a Wu^T) quantised to e4m3 blocks by the device against the oracle's float64 evaluation of
+    the same chain from the same quantised operands.  The quantiser decides integers from floats that differ in
+    their last bits (float32 accumulation on the device), so: the scale byte of a block equals the oracle's unless
+    the block maximum lies within float accumulation error of a power of two; with the same scale every code is
+    the oracle's or its neighbour on the e4m3 grid (plus the accumulation error for elements far below the row's
+    largest); at most 2 % of the codes differ, and without bias (a wrong
+    activation formula, operand order, gate/up swap or block assignment fails all of these at once)."""
+    w = synth.normal((2 * F, K), 11, 82, 0.05, True)
+    x = synth.normal((M, K), 11, 83, 1.0, False)
+    x[:, : K // 2] *= np.exp(synth.normal((M, 1), 11, 84, 1.0, False))
+    wc, ws = B.mx_quantize_weights(torch.from_numpy(w).cuda().to(torch.bfloat16))
+    ac, asc = B.mx_quantize_act(torch.from_numpy(x).cuda())
+    hc, hs = B.gemm_mx_swiglu(ac, asc, wc, ws, M, F, K)
+    dev_q, dev_e = decode_acts(hc, hs, M, F)
+    pad = np.setdiff1d(np.arange(hs.shape[1]), [(b >> 4) * 16 + (b & 3) * 4 + ((b >> 2) & 3) for b in range(F // 32)])
+    assert np.all(hs.cpu().numpy()[:, pad] == 0)
+    wq, we = O.mx_quantize(w, "e2m1")
+    aq, ae = O.mx_quantize(x, "e4m3")
+    gu = O.mx_dequantize(aq, ae) @ O.mx_dequantize(wq, we).T
+    g, u = gu[:, :F], gu[:, F:]
+    h = g / (1.0 + np.exp(-g)) * u
+    own_q, own_e = O.mx_quantize(h, "e4m3")
+    own = O.mx_dequantize(own_q, own_e)
+    dev = dev_q * np.repeat(np.ldexp(1.0, dev_e), 32, axis=1)
+    same = own_e == dev_e
+    amax = np.abs(h).reshape(M, F // 32, 32).max(axis=2)
+    mant = amax / np.exp2(np.floor(np.log2(np.maximum(amax, 1e-300))))                          # in [1, 2)
+    near_pow2 = np.minimum(mant - 1.0, 2.0 - mant) <= 1e-4                                      # block maximum next to a power of two
+    assert np.all(same | near_pow2), np.argwhere(~(same | near_pow2))[:8]
+    s32 = np.repeat(same, 32, axis=1)
+    mag = np.maximum(np.abs(own), np.abs(dev)) / np.repeat(np.ldexp(1.0, own_e), 32, axis=1)
+    step = np.ldexp(1.0, np.maximum(np.floor(np.log2(np.maximum(mag, 2.0 ** -20))), -6).astype(np.int64) - 3) * np.repeat(np.ldexp(1.0, own_e), 32, axis=1)
+    # the products carry the float accumulation error of 2048 terms (an ABSOLUTE error, 2^-16 of the sum of |terms|):
+    # elements far below their row's largest may move by more than one of their own (finer) steps
+    slack = 2.0 ** -12 * np.max(np.abs(h), axis=1, keepdims=True)
+    ok = np.where(s32, np.abs(dev - own) <= step * (1 + 1e-9) + slack, np.abs(dev - h) <= 2.0 ** -3 * np.abs(h) + step + slack)
+    assert np.all(ok), (np.argwhere(~ok)[:8], dev[~ok][:8], own[~ok][:8])
+    n_diff = int(np.sum(dev != own))
+    big = np.abs(own) > 0.05 * np.max(np.abs(own), axis=1, keepdims=True)
+    bias = abs(float(np.mean((dev[big] - own[big]) / own[big])))
+    print(f"codes that are the oracle's neighbour: {n_diff} of {dev.size}; blocks with another scale byte: {int(np.sum(~same))}; "
+          f"mean signed deviation {bias:.2e}")
+    assert n_diff <= 0.02 * dev.size and bias <= 2e-3
 
 
 def test_gemm_mx_rejects_bad_shapes():
@@ -311,7 +369,12 @@ def test_lowbit_model_with_attention_output_quantised_in_the_kernel(heads, D, kv
     run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 6, 0.08 * 9.0, kv_dtype=kv_dtype, w_dtype=B.PLT_MXFP4)
 
 
-def test_lowbit_layers_from_the_devices_own_activation_codes():
+MX_WIDE = synth.ModelShape(n_layers=2, d_model=512, n_heads=4, n_kv_heads=2, head_dim=128, ffn_hidden=4096,
+                           vocab=300, n_loops=3, window=5)
+
+
+@pytest.mark.parametrize("shape", [MX_SMALL, MX_WIDE], ids=["small", "wide-ffn"])
+def test_lowbit_layers_from_the_devices_own_activation_codes(shape):
     """A low-bit layer compared WITHOUT the rounding-boundary ambiguity of the quantisers.  A quantiser decides an
     integer from a float; device (float32, bf16 attention internals) and oracle (float64) inputs differ in the last
     bits, so a few per cent of the codes legitimately differ by one step and a free-running comparison needs a wide
@@ -326,9 +389,12 @@ def test_lowbit_layers_from_the_devices_own_activation_codes():
         of the row maximum, may be further off in steps, not in value), at most 15 % of them different (measured 8 % for the attention output, which passes through a bf16
         rounding on the device, a fraction of a per cent elsewhere), and without bias: the mean signed relative
         difference between the device's and the oracle's dequantised rows stays below 1 % (a 5 % error in the SwiGLU
-        or norm arithmetic moves most elements to the neighbouring code in ONE direction and shifts that mean by 5 %)."""
+        or norm arithmetic moves most elements to the neighbouring code in ONE direction and shifts that mean by 5 %).
+    The wide shape (ffn_hidden 4096, heads x head_dim = 512) takes the decode-row kernels of full-size models: every
+    projection as K-split row tiles, SwiGLU and the quantiser of the down projection's operand in the gate/up
+    product's epilogue, the attention output quantised by the attention kernel; its states are larger, and the
+    output bar scales with them."""
     from tests.helpers import oshape
-    shape = MX_SMALL
     L, nl, d = shape.n_loops, shape.n_layers, shape.d_model
     weights = lively_weights(shape, 9, bf16=True, std=0.05)
     cfg = B.make_config(shape, dtype=B.PLT_BF16, w_dtype=B.PLT_MXFP4)
@@ -361,7 +427,7 @@ def test_lowbit_layers_from_the_devices_own_activation_codes():
         ex = scales[:, sidx].astype(np.int64) - 127                                # [rows, K/32]
         return synth.e4m3_from_bits(codes).astype(np.float64) * np.repeat(np.ldexp(1.0, ex), 32, axis=1), ex
 
-    worst_out, worst_bias, n_elem, n_diff = 0.0, 0.0, 0, 0
+    worst_out, worst_bias, n_elem, n_diff, top_out = 0.0, 0.0, 0, 0, 0.0
     for m in range(nl):
         kv.set_position(pos)
         xin = np.zeros((Bn, L, d), np.float32)
@@ -380,6 +446,7 @@ def test_lowbit_layers_from_the_devices_own_activation_codes():
             for l in range(1, L + 1):
                 ref = orc.f(xin[b, l - 1].astype(np.float64), pos, l, orc.kv, layers=[m])
                 worst_out = max(worst_out, float(np.max(np.abs(out[b, l - 1] - ref))))
+                top_out = max(top_out, float(np.max(np.abs(ref))))
             for (l, mm, st, t) in orc.act_trace:
                 dev, ex = stages[st][0][b * L + l - 1], stages[st][1][b * L + l - 1]
                 q_own, e_own = O.mx_quantize(t, "e4m3")
@@ -397,7 +464,7 @@ def test_lowbit_layers_from_the_devices_own_activation_codes():
                 big = np.abs(own) > 0.05 * np.max(np.abs(own))
                 worst_bias = max(worst_bias, abs(float(np.mean((dev[big] - own[big]) / own[big]))))
             orc.act_override = None
-    print(f"layer outputs from the device's own codes: max-abs {worst_out:.2e}; codes that are the oracle's neighbour: {n_diff} of {n_elem}; "
+    print(f"layer outputs from the device's own codes: max-abs {worst_out:.2e} (largest |output| {top_out:.2f}); codes that are the oracle's neighbour: {n_diff} of {n_elem}; "
           f"largest mean signed deviation of a quantised row {worst_bias:.2e}")
-    assert worst_out <= 2e-3 and worst_bias <= 1e-2 and n_diff <= 0.15 * n_elem, (worst_out, worst_bias, n_diff, n_elem)
+    assert worst_out <= 2e-3 * max(1.0, top_out / 3.0) and worst_bias <= 1e-2 and n_diff <= 0.15 * n_elem, (worst_out, top_out, worst_bias, n_diff, n_elem)
     kv.close(); model.close()
