@@ -22,11 +22,11 @@
 // [4 bytes] (byte c = chunk 4*group + c).  Activation codes: row-major [M][K].  Activation scales:
 // [M][ceil(K/512)][g][c]: byte (g, c) of group q is the scale of k block 16 q + 4 c + g.
 #include "plt_internal.h"
+#include "rope_epilogue.h"
 #include <type_traits>
 
 namespace plt {
 
-typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
 // ---------------------------------------------------------------------------------------------- quantisers
@@ -395,15 +395,17 @@ __global__ __launch_bounds__(512) void k_gemm_mx_tile(const uint8_t* __restrict_
 // EPI 1 (gate/up): the tile is 32 gate + the matching 32 up columns over the whole K, and its epilogue applies SwiGLU
 // and quantises the 32 hidden values of a row - exactly one block - to e4m3 with their scale byte: no slabs and no
 // separate activation kernel.
-enum { MXR_F32 = 0, MXR_SWIGLU = 1 };
-template <int EPI, int BM, int STAGES>
+enum { MXR_F32 = 0, MXR_SWIGLU = 1, MXR_ROPE = 2 };
+template <int EPI, int BM, int STAGES, int NT = 4, int D = 128, typename KT = bf16_t>
 __global__ __launch_bounds__(256) void k_gemm_mx_rows(const uint8_t* __restrict__ a, const uint8_t* __restrict__ a_sc,
                                                       const uint8_t* __restrict__ w, const uint8_t* __restrict__ w_sc,
-                                                      void* __restrict__ out, uint8_t* __restrict__ out_sc, int M, int N, int K) {
-  // N: MXR_F32: output columns (= rows of w); MXR_SWIGLU: F (w has 2F rows: gate rows, then up rows; the output F columns)
-  constexpr int THREADS = 256, MI = BM / 64, NT = 4, DMA_A = BM * 8 / THREADS, DMA_N = DMA_A + 1;
+                                                      void* __restrict__ out, uint8_t* __restrict__ out_sc, int M, int N, int K,
+                                                      const RopeEpi ep) {
+  // N: MXR_F32 / MXR_ROPE: output columns (= rows of w); MXR_SWIGLU: F (w has 2F rows: gate rows, then up rows; the output F columns)
+  // NT: 16-column weight strips per tile (4; 8 for MXR_ROPE, whose waves must hold whole heads)
+  constexpr int THREADS = 256, MI = BM / 64, DMA_A = BM * 8 / THREADS, DMA_W = NT / 4, DMA_N = DMA_A + DMA_W;
   constexpr int A_BYTES = BM * 128, STAGE_BYTES = A_BYTES + NT * 1024;
-  static_assert(BM == 64 || BM == 128 || BM == 256, "rows per tile");
+  static_assert((BM == 64 || BM == 128 || BM == 256) && (NT == 4 || NT == 8) && (EPI != MXR_SWIGLU || NT == 4), "tile shape");
   extern __shared__ __attribute__((aligned(16))) char mxr_lds[];
   const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), m16 = lane & 15, g = lane >> 4;
   const int m0 = blockIdx.y * BM, tile_n = blockIdx.x;
@@ -426,7 +428,9 @@ __global__ __launch_bounds__(256) void k_gemm_mx_rows(const uint8_t* __restrict_
     int gm = m0 + row; if (gm >= M) gm = M - 1;                 // rows beyond M: computed, never stored
     pa[i] = (unsigned)gm * (unsigned)K + pc * 16;
   }
-  const uint8_t* pw = w + (size_t)strip_of(wv) * n_chunks * 1024 + lane * 16;
+  const uint8_t* pw[DMA_W];                                     // wave wv fetches tile strips wv, wv + 4
+#pragma unroll
+  for (int t = 0; t < DMA_W; ++t) pw[t] = w + (size_t)strip_of(wv + 4 * t) * n_chunks * 1024 + lane * 16;
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)mxr_lds;
   auto dma16 = [](const uint8_t* src, unsigned lds_wave_base) {  // lane l: 16 bytes -> LDS[lds_wave_base + 16 l]
     unsigned keep_m0;                                            // m0 is left as it was found
@@ -438,13 +442,16 @@ __global__ __launch_bounds__(256) void k_gemm_mx_rows(const uint8_t* __restrict_
 #pragma unroll
     for (int i = 0; i < DMA_A; ++i)
       dma16(a + ((size_t)pa[i] + (size_t)ch * 128), stage + (unsigned)(i * THREADS + wv * 64) * 16);
-    dma16(pw + (size_t)ch * 1024, stage + A_BYTES + (unsigned)wv * 1024);
+#pragma unroll
+    for (int t = 0; t < DMA_W; ++t) dma16(pw[t] + (size_t)ch * 1024, stage + A_BYTES + (unsigned)(wv + 4 * t) * 1024);
   };
   // Scale dwords of chunk group q (one per lane covers the group's 4 chunks) take the same road, 4 bytes per lane: wave
   // j fetches strip j's (lane (m, g): weight row m, block g), every wave those of its own row tiles (row m16, block
   // g), into one of two scale areas behind the stages; the registers are filled from there at the group's first chunk
-  constexpr int SC_OFF = STAGES * STAGE_BYTES, SC_BYTES = NT * 256 + 4 * MI * 256, DMA_S = 1 + MI;
-  const uint8_t* wsp = w_sc + (size_t)strip_of(wv) * n_cgrp * 256 + lane * 4;
+  constexpr int SC_OFF = STAGES * STAGE_BYTES, SC_BYTES = NT * 256 + 4 * MI * 256;
+  const uint8_t* wsp[DMA_W];
+#pragma unroll
+  for (int t = 0; t < DMA_W; ++t) wsp[t] = w_sc + (size_t)strip_of(wv + 4 * t) * n_cgrp * 256 + lane * 4;
   unsigned asp[MI];
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
@@ -458,7 +465,8 @@ __global__ __launch_bounds__(256) void k_gemm_mx_rows(const uint8_t* __restrict_
   };
   auto issue_scales = [&](int q) {
     const unsigned area = lds0 + SC_OFF + (unsigned)((q - q0) & 1) * SC_BYTES;
-    dma4(wsp + (size_t)q * 256, area + (unsigned)wv * 256);
+#pragma unroll
+    for (int t = 0; t < DMA_W; ++t) dma4(wsp[t] + (size_t)q * 256, area + (unsigned)(wv + 4 * t) * 256);
 #pragma unroll
     for (int i = 0; i < MI; ++i) dma4(a_sc + ((size_t)asp[i] + q * 16), area + NT * 256 + (unsigned)(wv * MI + i) * 256);
   };
@@ -517,7 +525,9 @@ __global__ __launch_bounds__(256) void k_gemm_mx_rows(const uint8_t* __restrict_
     if (c4 + 3 < ch1) step(c4 + 3, std::integral_constant<int, 3>{});
   }
   // acc[i][j][x]: row m0 + wv*MI*16 + i*16 + m16, column 4 g + x of tile strip j
-  if constexpr (EPI == MXR_SWIGLU) {
+  if constexpr (EPI == MXR_ROPE) {
+    rope_epilogue_decode<D, KT, MI, NT>(acc, ep, m0 + wv * (MI * 16), tile_n * (NT * 16), M, N, m16, g);
+  } else if constexpr (EPI == MXR_SWIGLU) {
     const int nbp = mx_ascale_row_bytes(N);
     uint8_t* codes = (uint8_t*)out;
 #pragma unroll
@@ -584,7 +594,36 @@ static void mx_rows_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc,
   static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_mx_rows<EPI, MXR_BM, MXR_STAGES>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
   (void)attr_once;
   hipLaunchKernelGGL((k_gemm_mx_rows<EPI, MXR_BM, MXR_STAGES>), dim3(col_tiles, (M + MXR_BM - 1) / MXR_BM, S), dim3(256), LDS_BYTES, s,
-                     a, a_sc, w, w_sc, out, out_sc, M, N, K);
+                     a, a_sc, w, w_sc, out, out_sc, M, N, K, RopeEpi{});
+}
+
+// QKV projection of a decode step with S3 (rotary embedding, gate logit, cache appends) as its epilogue: 64 rows x 128
+// columns per workgroup (a wave = 16 rows x one or two whole heads), whole K; no float QKV matrix, no append kernel.
+// From 65 rows on (two row tiles: with fewer the whole-K tiles are too few workgroups; measured at batch 64, 2048-token
+// context: L = 2 / 3 / 4 step -2 / -1 / -2 %, 64 rows equal, 32 rows and fewer +2-3 %)
+bool gemm_mx_rope_rows_applies(int M, int N, int K, int D) {
+  return M > 64 && M <= 1024 && (N % 128) == 0 && K >= 128 && (K % 128) == 0 && (D == 64 || D == 128);
+}
+template <int D, typename KT>
+static void mx_rope_launch(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, int M, int N, int K,
+                           const RopeEpi& ep) {
+  constexpr int LDS_BYTES = MXR_STAGES * (MXR_BM * 128 + 8192) + 2 * (8 * 256 + 4 * (MXR_BM / 64) * 256);
+  static const hipError_t attr_once = hipFuncSetAttribute((const void*)k_gemm_mx_rows<MXR_ROPE, MXR_BM, MXR_STAGES, 8, D, KT>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+  (void)attr_once;
+  hipLaunchKernelGGL((k_gemm_mx_rows<MXR_ROPE, MXR_BM, MXR_STAGES, 8, D, KT>), dim3(N / 128, (M + MXR_BM - 1) / MXR_BM, 1), dim3(256), LDS_BYTES, s,
+                     a, a_sc, w, w_sc, nullptr, nullptr, M, N, K, ep);
+}
+void launch_gemm_mx_rope_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* wqkv, const uint8_t* wqkv_sc, int M, int N,
+                              int K, const float* gate_w, const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv,
+                              const int32_t* pos, int L, const Dims& dm, const double* inv_freq, int mode, bool kv8) {
+  const RopeEpi ep{gate_w, gate_b, inv_freq, q_out, z_out, kv, 0, 0, dm.Hq, dm.Hkv, mode, pos, L};
+  if (dm.D == 128) {
+    if (kv8) mx_rope_launch<128, fp8_t>(s, a, a_sc, wqkv, wqkv_sc, M, N, K, ep);
+    else mx_rope_launch<128, bf16_t>(s, a, a_sc, wqkv, wqkv_sc, M, N, K, ep);
+  } else {
+    if (kv8) mx_rope_launch<64, fp8_t>(s, a, a_sc, wqkv, wqkv_sc, M, N, K, ep);
+    else mx_rope_launch<64, bf16_t>(s, a, a_sc, wqkv, wqkv_sc, M, N, K, ep);
+  }
 }
 static void launch_gemm_mx_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
                                 int M, int N, int K) {

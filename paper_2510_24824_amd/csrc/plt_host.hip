@@ -531,6 +531,11 @@ static void stack_pass(plt_model* m, plt_kv* kv, const Work& wk, int R, RowMap r
       ProfScope prof(m, PLT_PROF_GEMM, true);
       launch_gemm_rope_rows(s, (const bf16_t*)wk.a, (const bf16_t*)w.wqkv, R, Nqkv, d, w.gate_w, w.gate_b, (bf16_t*)wk.q,
                             wk.z, v, rm.pos, rm.rows_per_seq, dm, m->inv_freq, variant, m->kv8);
+    } else if (m->mx && c.dtype == PLT_BF16 && !rm.prefill && gemm_mx_rope_rows_applies(R, Nqkv, d, D)) {
+      // low-bit decode rows: likewise
+      ProfScope prof(m, PLT_PROF_GEMM, true);
+      launch_gemm_mx_rope_rows(s, wk.a_codes, wk.a_scales, (const uint8_t*)w.wqkv, w.wqkv_sc, R, Nqkv, d, w.gate_w, w.gate_b,
+                               (bf16_t*)wk.q, wk.z, v, rm.pos, rm.rows_per_seq, dm, m->inv_freq, variant, m->kv8);
     } else {
       S = m->mx ? run_gemm_mx(m, wk, w.wqkv, w.wqkv_sc, R, Nqkv, d, !rm.prefill)
                 : run_gemm(m, wk.a, w.wqkv, wk.gout, R, Nqkv, d, !rm.prefill);                         // Alg. 3 l.1

@@ -284,6 +284,11 @@ void launch_mx_quant_a(hipStream_t s, const T* a, uint8_t* codes, uint8_t* scale
 int gemm_mx_splits(int M, int N, int K);
 void launch_gemm_mx(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* w, const uint8_t* w_sc, float* c,
                     int M, int N, int K);
+// decode rows: QKV projection with S3 (rotary embedding, gate logit, cache appends) as its epilogue
+bool gemm_mx_rope_rows_applies(int M, int N, int K, int D);
+void launch_gemm_mx_rope_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* wqkv, const uint8_t* wqkv_sc, int M, int N,
+                              int K, const float* gate_w, const float* gate_b, bf16_t* q_out, float* z_out, const KvView& kv,
+                              const int32_t* pos, int L, const Dims& dm, const double* inv_freq, int mode, bool kv8);
 // decode rows: gate/up projection with SwiGLU and the e4m3 block quantiser as its epilogue (codes[M, F] + scale bytes)
 bool gemm_mx_swiglu_rows_applies(int M, int F, int K);
 void launch_gemm_mx_swiglu_rows(hipStream_t s, const uint8_t* a, const uint8_t* a_sc, const uint8_t* wgu, const uint8_t* wgu_sc,

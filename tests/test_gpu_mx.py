@@ -203,6 +203,33 @@ def test_model_with_lowbit_projections(mode, kv_dtype):
     run_teacher_forced(MX_SMALL, B.PLT_BF16, mode, weights, prompts, 6, MX_MODEL_TOL, kv_dtype=kv_dtype, w_dtype=B.PLT_MXFP4)
 
 
+@pytest.mark.parametrize("mode", [B.PLT_MODE_CLP, B.PLT_MODE_CLP_SHARE_ONLY, B.PLT_MODE_CLP_OWN_KV, B.PLT_MODE_VANILLA_LOOP])
+@pytest.mark.parametrize("kv_dtype", [0, B.PLT_FP8_E4M3], ids=["bf16kv", "e4m3kv"])
+def test_lowbit_decode_steps_of_more_than_64_rows_all_modes(mode, kv_dtype):
+    """From 65 rows on the low-bit QKV projection of a decode step carries RoPE, the gate logit and the cache appends as
+    its epilogue (64-row x 128-column tiles, two heads of 64 per wave; row (b, l) at its sequence's own position):
+    24 sequences x 3 loops = 72 rows (two row tiles, the second ragged; 72 sequences in the sequential-loop mode),
+    every mode's append rule, both cache types.  Free-running low-bit bar, 8 % of the state's magnitude (4.2 with
+    these prompts; measured up to 0.25 with e4m3 caches over 24 sequences); a wrong ring slot, cache or position is off
+    by the state's full size."""
+    weights = lively_weights(MX_SMALL, 9, bf16=True, std=0.05)
+    Bn = 72 if mode == B.PLT_MODE_VANILLA_LOOP else 24
+    n, steps = (6, 2) if mode == B.PLT_MODE_VANILLA_LOOP else (9, 3)
+    prompts = synth.token_ids((Bn, n), MX_SMALL.vocab, 53)
+    run_teacher_forced(MX_SMALL, B.PLT_BF16, mode, weights, prompts, steps, 0.08 * 4.2, kv_dtype=kv_dtype, w_dtype=B.PLT_MXFP4)
+
+
+@pytest.mark.parametrize("kv_dtype", [0, B.PLT_FP8_E4M3], ids=["bf16kv", "e4m3kv"])
+def test_lowbit_decode_steps_of_more_than_64_rows_heads_of_128(kv_dtype):
+    """The same epilogue with heads of 128 (one head per wave), 512 hidden rows per head group so that the attention
+    kernel also writes its output as e4m3 blocks: 22 sequences x 3 loops = 66 rows."""
+    shape = synth.ModelShape(n_layers=2, d_model=256, n_heads=4, n_kv_heads=2, head_dim=128, ffn_hidden=256,
+                             vocab=300, n_loops=3, window=5)
+    weights = lively_weights(shape, 13, bf16=True, std=0.05)
+    prompts = synth.token_ids((22, 7), shape.vocab, 54)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 3, 0.08 * 9.0, kv_dtype=kv_dtype, w_dtype=B.PLT_MXFP4)
+
+
 def test_lowbit_model_single_position():
     """One position, L = 1: softmax over a single key returns the (bf16-stored) value row on both sides, so the
     values entering a quantiser differ only by float-level arithmetic -- dominated by the matrix-core
