@@ -552,6 +552,21 @@ def bench_lowbit_gemm(B, Mrows=128, reps=30):
         out["projections"][name] = {"N": N, "K": K, "mxfp4_us": t_mx, "bf16_us": t_bf, "act_quant_us": t_q,
                                     "mx_weight_bytes": N * K // 2 + N * K // 32, "bf16_weight_bytes": N * K * 2}
         log(f"[bench] low-bit GEMM {name} {Mrows}x{N}x{K}: MXFP4 {t_mx:.1f} us, bf16 {t_bf:.1f} us, activation quantiser {t_q:.1f} us")
+        if name == "gate_up":
+            # as the model runs it: SwiGLU and the quantiser of the down projection's operand in the product's epilogue
+            F = N // 2
+            hc = torch.empty(Mrows, F, dtype=torch.uint8, device="cuda")
+            hs = torch.empty(l.plt_mx_act_scale_bytes(Mrows, F), dtype=torch.uint8, device="cuda")
+            nb3 = l.plt_gemm_mx_swiglu_scratch_bytes(Mrows, F, K); s3 = torch.empty(nb3, dtype=torch.uint8, device="cuda")
+
+            def run_fused():
+                wc, wsc = q[i[0] % 8]; i[0] += 1
+                B._check(l.plt_gemm_mx_swiglu(Mrows, F, K, B._ptr(ac), B._ptr(asc), B._ptr(wc), B._ptr(wsc), B._ptr(hc), B._ptr(hs),
+                                              B._ptr(s3), nb3, st))
+
+            t_f = timed(run_fused)
+            out["projections"][name]["mxfp4_swiglu_quantiser_fused_us"] = t_f
+            log(f"[bench] low-bit gate/up with SwiGLU + quantiser fused {Mrows}x{F}x{K}: {t_f:.1f} us")
         del ws, q
     pr = out["projections"]
     out["per_layer_us"] = {"mxfp4": sum(v["mxfp4_us"] for v in pr.values()), "bf16": sum(v["bf16_us"] for v in pr.values())}
