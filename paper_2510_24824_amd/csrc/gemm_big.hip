@@ -332,6 +332,14 @@ void launch_gemm_rows_split(hipStream_t s, const bf16_t* a, const bf16_t* w, flo
 
 
 void launch_gemm_swiglu_rows(hipStream_t s, const bf16_t* a, const bf16_t* wgu, bf16_t* act, int M, int F, int K) {
+  // Wide feed-forward blocks (at least 200 tiles of 64 hidden columns), more than 64 rows: 64 gate + 64 up columns per
+  // tile - half as many workgroups, each taking the step's rows once for twice the columns (F = 16384, batch 64:
+  // L = 2 / 3 / 4 step -2 / -5 / -5 %; 64 rows and fewer: +1-2 %, so those keep the narrow tile)
+  if (M > 64 && (F + 63) / 64 >= 200) {
+    if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 128, 2, 2, 3>(s, a, wgu, (void*)act, M, F, K); return; }
+    tile_launch<EPI_SWIGLU, 256, 128, 4, 2, 3>(s, a, wgu, (void*)act, M, F, K);
+    return;
+  }
   if (M <= 64) { tile_launch<EPI_SWIGLU, 64, 64, 2, 2, 4>(s, a, wgu, (void*)act, M, F, K); return; }
   if (M <= 128) { tile_launch<EPI_SWIGLU, 128, 64, 2, 2, 3>(s, a, wgu, (void*)act, M, F, K); return; }
   tile_launch<EPI_SWIGLU, 256, 64, 4, 2, 3>(s, a, wgu, (void*)act, M, F, K);

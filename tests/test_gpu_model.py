@@ -235,6 +235,17 @@ def test_decode_steps_of_more_than_128_rows_all_modes(mode, kv_dtype):
     run_teacher_forced(shape, B.PLT_BF16, mode, weights, prompts, steps, 4e-2 if kv_dtype else 2e-2, kv_dtype=kv_dtype)
 
 
+@pytest.mark.parametrize("n_seq", [24, 48], ids=["72rows", "144rows"])
+def test_decode_steps_with_a_wide_feed_forward_block(n_seq):
+    """ffn_hidden = 12800 (200 tiles of 64 hidden columns): from 65 rows on the gate/up projection of a decode step
+    takes tiles of 64 gate + 64 up columns (128 x 128 at up to 128 rows, 256 x 128 beyond), SwiGLU in the epilogue."""
+    shape = synth.ModelShape(n_layers=1, d_model=128, n_heads=2, n_kv_heads=1, head_dim=64,
+                             ffn_hidden=12800, vocab=300, n_loops=3, window=8)
+    weights = lively_weights(shape, 61, bf16=True, std=0.02)
+    prompts = synth.token_ids((n_seq, 9), shape.vocab, 62)
+    run_teacher_forced(shape, B.PLT_BF16, B.PLT_MODE_CLP, weights, prompts, 2, 2e-2)
+
+
 def test_window_one_and_many_loops():
     """w = 1: the window holds only the current position, so the local branch returns its own value row."""
     shape = synth.ModelShape(n_layers=1, d_model=64, n_heads=2, n_kv_heads=1, head_dim=64,
