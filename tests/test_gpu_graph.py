@@ -10,8 +10,13 @@ from tests.helpers import lively_weights
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("dtype,L,moe", [(B.PLT_BF16, 3, False), (B.PLT_F32, 2, False), (B.PLT_BF16, 2, True)], ids=["bf16-L3", "f32-L2", "bf16-moe"])
-def test_graph_replay_equals_eager_steps(dtype, L, moe):
+@pytest.mark.parametrize("dtype,L,moe,n_seq,n_prompt",
+                         [(B.PLT_BF16, 3, False, 3, 70), (B.PLT_F32, 2, False, 3, 70), (B.PLT_BF16, 2, True, 3, 70),
+                          # one sequence, 600 tokens: the attention splits every stream over two workgroups, whose records
+                          # the last one to finish merges (a device counter that must be back at zero for every replay)
+                          (B.PLT_BF16, 2, False, 1, 600)],
+                         ids=["bf16-L3", "f32-L2", "bf16-moe", "bf16-L2-split-streams"])
+def test_graph_replay_equals_eager_steps(dtype, L, moe, n_seq, n_prompt):
     if moe:
         shape = synth.ModelShape(n_layers=2, d_model=128, n_heads=4, n_kv_heads=2, head_dim=64, ffn_hidden=64,
                                  vocab=300, n_loops=L, window=5, n_experts=8, top_k=2)
@@ -20,7 +25,7 @@ def test_graph_replay_equals_eager_steps(dtype, L, moe):
                                  vocab=300, n_loops=L, window=5)
     weights = lively_weights(shape, 3, bf16=dtype == B.PLT_BF16, std=0.05, router_std=0.5 if moe else None)
     cfg = B.make_config(shape, dtype=dtype)
-    prompts = torch.from_numpy(np.ascontiguousarray(synth.token_ids((3, 70), shape.vocab, 4), np.int32))
+    prompts = torch.from_numpy(np.ascontiguousarray(synth.token_ids((n_seq, n_prompt), shape.vocab, 4), np.int32))
     side = torch.cuda.Stream()                       # stream capture needs a stream of its own (not the NULL stream)
     with torch.cuda.stream(side):
         blob = B.pack_weights(cfg, weights)
@@ -29,7 +34,7 @@ def test_graph_replay_equals_eager_steps(dtype, L, moe):
 
         def run(graph):
             model.use_graph(graph)
-            kv = B.KV(model, 3, 100)
+            kv = B.KV(model, n_seq, n_prompt + 30)
             nxt, _ = kv.prefill(prompts.cuda())
             out = []
             tok = nxt.clone()
@@ -40,7 +45,7 @@ def test_graph_replay_equals_eager_steps(dtype, L, moe):
                 out.append((n1.cpu().numpy().copy(), lg.cpu().numpy().copy(), kv.get_hidden().copy(), junk))
                 torch.cuda.synchronize()
                 tok.copy_(n1)                         # same token buffer every step: the graph is captured once
-            assert kv.position == 70 + steps
+            assert kv.position == n_prompt + steps
             kv.close()
             return out
 
